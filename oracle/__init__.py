@@ -1,0 +1,180 @@
+"""ctypes front end of the fp64 CPU oracle (oracle/symb_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Importable from tests/, the smoke check and the bench's
+cpu_baseline leg; the GPU library and its Python binding never import this package,
+and this package never imports them.  It adds no arithmetic of its own: it builds
+the C file with gcc, marshals numpy arrays of bf16 bit patterns, and returns fp64.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "symb_oracle.c")
+_LIB = os.path.join(_HERE, "libsymb_oracle.so")
+
+NONE, LORA, IA3, IA3_IN = 0, 1, 2, 3
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP over independent rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+                               "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _Adapter(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("rank", C.c_int32), ("scale", C.c_double),
+                ("A", C.c_void_p), ("B", C.c_void_p)]
+
+
+@dataclass
+class Adapter:
+    """Host adapter of one segment: bit patterns (uint16 bf16) in storage layout."""
+    kind: int = NONE
+    rank: int = 0
+    scale: float = 0.0
+    A: Optional[np.ndarray] = None  # LoRA [rank, d_in]; IA3 l [d_out]; IA3_IN l [d_in]
+    B: Optional[np.ndarray] = None  # LoRA [d_out, rank]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.orc_num_threads.restype = C.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
+
+
+def _u16(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    assert a.dtype == np.uint16 and a.flags["C_CONTIGUOUS"], "bf16 bit patterns, contiguous"
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _pack(adapters: Sequence[Adapter], d_in: int, d_out: int):
+    arr = (_Adapter * max(1, len(adapters)))()
+    for i, a in enumerate(adapters):
+        arr[i].kind, arr[i].rank, arr[i].scale = int(a.kind), int(a.rank), float(a.scale)
+        if a.kind == LORA:
+            assert a.A.shape == (a.rank, d_in) and a.B.shape == (d_out, a.rank)
+        elif a.kind == IA3:
+            assert a.A.shape == (d_out,)
+        elif a.kind == IA3_IN:
+            assert a.A.shape == (d_in,)
+        arr[i].A = _u16(a.A).value if a.A is not None else None
+        arr[i].B = _u16(a.B).value if a.B is not None else None
+    return arr
+
+
+def row_segment_map(off) -> np.ndarray:
+    off = _i32(off)
+    S = len(off) - 1
+    out = np.empty(max(int(off[-1]), 0), dtype=np.int32)
+    rc = lib().orc_row_segment_map(C.c_int32(S), off.ctypes.data_as(C.c_void_p),
+                                   out.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise ValueError("invalid segment offsets")
+    return out
+
+
+def forward(off, adapters: Sequence[Adapter], X: np.ndarray, W: np.ndarray,
+            bias: Optional[np.ndarray] = None, rows=None):
+    """Returns (Y0, Y) as fp64 [nrows, d_out] for the listed rows (default: all)."""
+    off = _i32(off)
+    S = len(off) - 1
+    d_out, d_in = W.shape
+    assert X.shape[1] == d_in and X.shape[0] >= off[-1]
+    rows_a = None if rows is None else _i32(rows)
+    n = int(off[-1]) if rows is None else len(rows_a)
+    Y0 = np.empty((n, d_out), dtype=np.float64)
+    Y = np.empty((n, d_out), dtype=np.float64)
+    ad = _pack(adapters, d_in, d_out)
+    rc = lib().orc_forward_rows(C.c_int32(d_in), C.c_int32(d_out), C.c_int32(S),
+                                off.ctypes.data_as(C.c_void_p), ad, _u16(X), _u16(W), _u16(bias),
+                                C.c_int32(n), None if rows_a is None else rows_a.ctypes.data_as(C.c_void_p),
+                                Y0.ctypes.data_as(C.c_void_p), Y.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise ValueError("oracle forward: bad offsets or row index")
+    return Y0, Y
+
+
+def backward_input(off, adapters: Sequence[Adapter], dY: np.ndarray, W: np.ndarray,
+                   rows=None, base_only: bool = False) -> np.ndarray:
+    off = _i32(off)
+    S = len(off) - 1
+    d_out, d_in = W.shape
+    assert dY.shape[1] == d_out and dY.shape[0] >= off[-1]
+    rows_a = None if rows is None else _i32(rows)
+    n = int(off[-1]) if rows is None else len(rows_a)
+    dX = np.empty((n, d_in), dtype=np.float64)
+    ad = _pack(adapters, d_in, d_out)
+    rc = lib().orc_backward_input_rows(C.c_int32(d_in), C.c_int32(d_out), C.c_int32(S),
+                                       off.ctypes.data_as(C.c_void_p), ad, _u16(dY), _u16(W),
+                                       C.c_int32(n),
+                                       None if rows_a is None else rows_a.ctypes.data_as(C.c_void_p),
+                                       C.c_int32(1 if base_only else 0), dX.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise ValueError("oracle backward: bad offsets or row index")
+    return dX
+
+
+def lora_grad(off, adapters: Sequence[Adapter], X: np.ndarray, dY: np.ndarray, i: int,
+              want_dA: bool = True, want_dB: bool = True):
+    """Returns (dA [r, d_in], dB [d_out, r]) in fp64 for LoRA segment i."""
+    off = _i32(off)
+    S = len(off) - 1
+    d_in, d_out = X.shape[1], dY.shape[1]
+    r = adapters[i].rank
+    dA = np.empty((r, d_in), dtype=np.float64) if want_dA else None
+    dB = np.empty((d_out, r), dtype=np.float64) if want_dB else None
+    ad = _pack(adapters, d_in, d_out)
+    rc = lib().orc_lora_grad_segment(C.c_int32(d_in), C.c_int32(d_out), C.c_int32(S),
+                                     off.ctypes.data_as(C.c_void_p), ad, _u16(X), _u16(dY), C.c_int32(i),
+                                     None if dA is None else dA.ctypes.data_as(C.c_void_p),
+                                     None if dB is None else dB.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise ValueError("oracle lora_grad: bad arguments")
+    return dA, dB
+
+
+def ia3_grad(off, adapters: Sequence[Adapter], X: np.ndarray, dY: np.ndarray, W: np.ndarray,
+             bias: Optional[np.ndarray], i: int, cols=None) -> np.ndarray:
+    """Returns dl (fp64) of IA3 / IA3_IN segment i for the listed channels (default: all)."""
+    off = _i32(off)
+    S = len(off) - 1
+    d_out, d_in = W.shape
+    full = d_out if adapters[i].kind == IA3 else d_in
+    cols_a = None if cols is None else _i32(cols)
+    n = full if cols is None else len(cols_a)
+    dl = np.empty(n, dtype=np.float64)
+    ad = _pack(adapters, d_in, d_out)
+    rc = lib().orc_ia3_grad_segment(C.c_int32(d_in), C.c_int32(d_out), C.c_int32(S),
+                                    off.ctypes.data_as(C.c_void_p), ad, _u16(X), _u16(dY), _u16(W),
+                                    _u16(bias), C.c_int32(i), C.c_int32(n),
+                                    None if cols_a is None else cols_a.ctypes.data_as(C.c_void_p),
+                                    dl.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise ValueError("oracle ia3_grad: bad arguments")
+    return dl

@@ -1,0 +1,290 @@
+/*
+ * CPU oracle for the segmented base+adapter linear layer.  TEST INFRASTRUCTURE ONLY:
+ * it exists to check the GPU library and to be timed beside it; no product path may
+ * call it.  It shares no code with the GPU path.
+ *
+ * What it is: the plain definition, written as nested loops in fp64 over inputs that
+ * are bf16 bit patterns (widened exactly), with no blocking, fusion or reordering.
+ * Outputs stay in fp64.  Rows are independent, so the outer row (or column) loop is
+ * spread over host threads with OpenMP; each output element is still one sequential
+ * fp64 sum.
+ *
+ * What it follows (Symbiosis, arXiv 2507.03220):
+ *   - Sec. 3.2 "Base Executor": requests of many clients for one frozen layer are
+ *     batched, executed once, and the output is split per client.
+ *   - Sec. 3.7: for nn.Linear / Conv1D the token position is irrelevant, so all
+ *     clients' tokens are flattened into one padding-free token sequence; client i
+ *     owns rows off[i] .. off[i+1]-1.
+ *   - Sec. 3.6: the layer is frozen, so backward is the output gradient times the
+ *     parameters (no weight gradient, nothing saved from forward), and the backward
+ *     batch is any batch of its own.
+ *   - Sec. 3.8 eqs. (1)-(3): y = Linear(x, W) + b, with a bias-free variant.
+ *   - Sec. 1 / Sec. 3.2 "Client": each client picks its own PEFT method and
+ *     parameters (LoRA rank/alpha, IA3).  The paper does not restate LoRA or IA3; the
+ *     standard definitions are used: LoRA adds s*(x A)B to the base output, IA3
+ *     rescales the layer output (or, for IA3_IN, the layer input) elementwise by a
+ *     learned vector.
+ *
+ * Storage layouts (row-major):  X [T][d_in], W [d_out][d_in], bias [d_out],
+ *   LoRA A [r][d_in] (so mathematically A_i[k][p] = A[p][k]), LoRA B [d_out][r]
+ *   (B_i[p][j] = B[j][p]), IA3 l [d_out], IA3_IN l [d_in].  Gradients use the layout
+ *   of the tensor they belong to.
+ *
+ * Parity pins (tests/test_oracle_*.py): brute-force Python loops on tiny shapes,
+ * merged-weight closed forms via a library fp64 matmul, B=0 / l=1 reductions,
+ * segment-permutation and batched-vs-alone invariance, exact central finite
+ * differences of <dY,Y>, noise linearity, and an exact integer-valued index probe.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORC_NONE = 0, ORC_LORA = 1, ORC_IA3 = 2, ORC_IA3_IN = 3 };
+
+typedef struct {
+    int32_t kind;
+    int32_t rank;
+    double scale;
+    const uint16_t* A; /* LoRA A, or the IA3 vector */
+    const uint16_t* B; /* LoRA B */
+} orc_adapter;
+
+static inline double bf(uint16_t b) {
+    union { uint32_t u; float f; } v;
+    v.u = ((uint32_t)b) << 16;
+    return (double)v.f;
+}
+
+int orc_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Offsets are valid when off[0] = 0 and they never decrease. */
+int orc_check_offsets(int32_t S, const int32_t* off) {
+    if (S < 0 || !off || off[0] != 0) return 1;
+    for (int32_t i = 0; i < S; ++i)
+        if (off[i + 1] < off[i]) return 1;
+    return 0;
+}
+
+/* seg(t) = i  <=>  off[i] <= t < off[i+1]  (Sec. 3.7 flattening; Sec. 3.2 split). */
+static int32_t seg_of(int32_t S, const int32_t* off, int32_t t) {
+    for (int32_t i = 0; i < S; ++i)
+        if (off[i] <= t && t < off[i + 1]) return i;
+    return -1;
+}
+
+int orc_row_segment_map(int32_t S, const int32_t* off, int32_t* out) {
+    if (orc_check_offsets(S, off)) return 1;
+    int32_t T = off[S];
+    for (int32_t t = 0; t < T; ++t) out[t] = seg_of(S, off, t);
+    return 0;
+}
+
+/*
+ * Forward for the listed rows (rows == NULL: rows 0..nrows-1).
+ *   Y0[t][j] = sum_k X[t][k] W[j][k] (+ b[j])
+ *   NONE:   Y = Y0
+ *   LORA:   H[t][p] = sum_k X[t][k] A[p][k];  Y[t][j] = Y0[t][j] + s * sum_p H[t][p] B[j][p]
+ *   IA3:    Y[t][j] = l[j] * Y0[t][j]
+ *   IA3_IN: Y[t][j] = sum_k (l[k] X[t][k]) W[j][k] (+ b[j]);  Y0 stays the unscaled base output
+ * Y0_out / Y_out: [nrows][d_out] fp64, either may be NULL.
+ */
+int orc_forward_rows(int32_t d_in, int32_t d_out, int32_t S, const int32_t* off,
+                     const orc_adapter* ad, const uint16_t* X, const uint16_t* W,
+                     const uint16_t* bias, int32_t nrows, const int32_t* rows,
+                     double* Y0_out, double* Y_out) {
+    if (orc_check_offsets(S, off)) return 1;
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t q = 0; q < nrows; ++q) {
+        int32_t t = rows ? rows[q] : q;
+        int32_t i = seg_of(S, off, t);
+        if (i < 0) { bad = 1; continue; }
+        const orc_adapter* a = &ad[i];
+        const uint16_t* x = X + (size_t)t * d_in;
+        double* H = NULL;
+        if (a->kind == ORC_LORA) {
+            H = (double*)malloc(sizeof(double) * (size_t)a->rank);
+            for (int32_t p = 0; p < a->rank; ++p) {
+                double h = 0.0;
+                for (int32_t k = 0; k < d_in; ++k) h += bf(x[k]) * bf(a->A[(size_t)p * d_in + k]);
+                H[p] = h;
+            }
+        }
+        for (int32_t j = 0; j < d_out; ++j) {
+            const uint16_t* w = W + (size_t)j * d_in;
+            double y0 = 0.0;
+            for (int32_t k = 0; k < d_in; ++k) y0 += bf(x[k]) * bf(w[k]);
+            if (bias) y0 += bf(bias[j]);
+            double y = y0;
+            if (a->kind == ORC_LORA) {
+                double u = 0.0;
+                for (int32_t p = 0; p < a->rank; ++p) u += H[p] * bf(a->B[(size_t)j * a->rank + p]);
+                y = y0 + a->scale * u;
+            } else if (a->kind == ORC_IA3) {
+                y = bf(a->A[j]) * y0;
+            } else if (a->kind == ORC_IA3_IN) {
+                double v = 0.0;
+                for (int32_t k = 0; k < d_in; ++k) v += bf(a->A[k]) * bf(x[k]) * bf(w[k]);
+                if (bias) v += bf(bias[j]);
+                y = v;
+            }
+            if (Y0_out) Y0_out[(size_t)q * d_out + j] = y0;
+            if (Y_out) Y_out[(size_t)q * d_out + j] = y;
+        }
+        free(H);
+    }
+    return bad;
+}
+
+/*
+ * Input gradient for the listed rows of a backward batch (its own offsets/adapters).
+ *   NONE:   dX[t][k] = sum_j dY[t][j] W[j][k]
+ *   LORA:   dH[t][p] = s * sum_j dY[t][j] B[j][p]
+ *           dX[t][k] = sum_j dY[t][j] W[j][k] + sum_p dH[t][p] A[p][k]   (base_only drops the 2nd sum)
+ *   IA3:    dX[t][k] = sum_j dY[t][j] l[j] W[j][k]
+ *   IA3_IN: dX[t][k] = l[k] * sum_j dY[t][j] W[j][k]
+ * base_only != 0 gives what the paper's executor returns (Sec. 3.6): dY times W only.
+ */
+int orc_backward_input_rows(int32_t d_in, int32_t d_out, int32_t S, const int32_t* off,
+                            const orc_adapter* ad, const uint16_t* dY, const uint16_t* W,
+                            int32_t nrows, const int32_t* rows, int32_t base_only,
+                            double* dX_out) {
+    if (orc_check_offsets(S, off)) return 1;
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t q = 0; q < nrows; ++q) {
+        int32_t t = rows ? rows[q] : q;
+        int32_t i = seg_of(S, off, t);
+        if (i < 0) { bad = 1; continue; }
+        const orc_adapter* a = &ad[i];
+        int kind = base_only ? ORC_NONE : a->kind;
+        const uint16_t* g = dY + (size_t)t * d_out;
+        double* dH = NULL;
+        if (kind == ORC_LORA) {
+            dH = (double*)malloc(sizeof(double) * (size_t)a->rank);
+            for (int32_t p = 0; p < a->rank; ++p) {
+                double h = 0.0;
+                for (int32_t j = 0; j < d_out; ++j) h += bf(g[j]) * bf(a->B[(size_t)j * a->rank + p]);
+                dH[p] = a->scale * h;
+            }
+        }
+        /* Base term, accumulated j-outermost so W is read along its rows; every dX[t][k]
+         * is still the sum over j = 0..d_out-1 taken in that order. */
+        double* o = dX_out + (size_t)q * d_in;
+        for (int32_t k = 0; k < d_in; ++k) o[k] = 0.0;
+        for (int32_t j = 0; j < d_out; ++j) {
+            double gj = bf(g[j]);
+            if (kind == ORC_IA3) gj *= bf(a->A[j]);
+            const uint16_t* w = W + (size_t)j * d_in;
+            for (int32_t k = 0; k < d_in; ++k) o[k] += gj * bf(w[k]);
+        }
+        if (kind == ORC_LORA) {
+            for (int32_t k = 0; k < d_in; ++k) {
+                double u = 0.0;
+                for (int32_t p = 0; p < a->rank; ++p) u += dH[p] * bf(a->A[(size_t)p * d_in + k]);
+                o[k] += u;
+            }
+        } else if (kind == ORC_IA3_IN) {
+            for (int32_t k = 0; k < d_in; ++k) o[k] = bf(a->A[k]) * o[k];
+        }
+        free(dH);
+    }
+    return bad;
+}
+
+/*
+ * LoRA parameter gradients of segment i (sum over the segment's own tokens only):
+ *   dA[p][k] = sum_t X[t][k] dH[t][p],  dH[t][p] = s * sum_j dY[t][j] B[j][p]
+ *   dB[j][p] = s * sum_t H[t][p] dY[t][j],  H[t][p] = sum_k X[t][k] A[p][k]
+ * dA_out [r][d_in], dB_out [d_out][r]; either may be NULL.  An empty segment gives zeros.
+ */
+int orc_lora_grad_segment(int32_t d_in, int32_t d_out, int32_t S, const int32_t* off,
+                          const orc_adapter* ad, const uint16_t* X, const uint16_t* dY,
+                          int32_t i, double* dA_out, double* dB_out) {
+    if (orc_check_offsets(S, off) || i < 0 || i >= S || ad[i].kind != ORC_LORA) return 1;
+    const orc_adapter* a = &ad[i];
+    const int32_t r = a->rank, lo = off[i], n = off[i + 1] - off[i];
+    double* H = (double*)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * r);
+    double* dH = (double*)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * r);
+#pragma omp parallel for schedule(static)
+    for (int32_t u = 0; u < n; ++u) {
+        const uint16_t* x = X + (size_t)(lo + u) * d_in;
+        const uint16_t* g = dY + (size_t)(lo + u) * d_out;
+        for (int32_t p = 0; p < r; ++p) {
+            double h = 0.0;
+            for (int32_t k = 0; k < d_in; ++k) h += bf(x[k]) * bf(a->A[(size_t)p * d_in + k]);
+            H[(size_t)u * r + p] = h;
+            double e = 0.0;
+            for (int32_t j = 0; j < d_out; ++j) e += bf(g[j]) * bf(a->B[(size_t)j * r + p]);
+            dH[(size_t)u * r + p] = a->scale * e;
+        }
+    }
+    if (dA_out) {
+#pragma omp parallel for schedule(static)
+        for (int32_t k = 0; k < d_in; ++k)
+            for (int32_t p = 0; p < r; ++p) {
+                double v = 0.0;
+                for (int32_t u = 0; u < n; ++u)
+                    v += bf(X[(size_t)(lo + u) * d_in + k]) * dH[(size_t)u * r + p];
+                dA_out[(size_t)p * d_in + k] = v;
+            }
+    }
+    if (dB_out) {
+#pragma omp parallel for schedule(static)
+        for (int32_t j = 0; j < d_out; ++j)
+            for (int32_t p = 0; p < r; ++p) {
+                double v = 0.0;
+                for (int32_t u = 0; u < n; ++u)
+                    v += H[(size_t)u * r + p] * bf(dY[(size_t)(lo + u) * d_out + j]);
+                dB_out[(size_t)j * r + p] = a->scale * v;
+            }
+    }
+    free(H);
+    free(dH);
+    return 0;
+}
+
+/*
+ * IA3 vector gradient of segment i for the listed channels (cols == NULL: 0..ncols-1).
+ *   IA3:    dl[j] = sum_t dY[t][j] * Y0[t][j],   Y0[t][j] = sum_k X[t][k] W[j][k] (+ b[j])
+ *   IA3_IN: dl[k] = sum_t X[t][k] * G[t][k],     G[t][k]  = sum_j dY[t][j] W[j][k]
+ */
+int orc_ia3_grad_segment(int32_t d_in, int32_t d_out, int32_t S, const int32_t* off,
+                         const orc_adapter* ad, const uint16_t* X, const uint16_t* dY,
+                         const uint16_t* W, const uint16_t* bias, int32_t i,
+                         int32_t ncols, const int32_t* cols, double* dl_out) {
+    if (orc_check_offsets(S, off) || i < 0 || i >= S) return 1;
+    const int kind = ad[i].kind;
+    if (kind != ORC_IA3 && kind != ORC_IA3_IN) return 1;
+    const int32_t lo = off[i], n = off[i + 1] - off[i];
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t q = 0; q < ncols; ++q) {
+        int32_t c = cols ? cols[q] : q;
+        double v = 0.0;
+        for (int32_t u = 0; u < n; ++u) {
+            const uint16_t* x = X + (size_t)(lo + u) * d_in;
+            const uint16_t* g = dY + (size_t)(lo + u) * d_out;
+            if (kind == ORC_IA3) {
+                double y0 = 0.0;
+                for (int32_t k = 0; k < d_in; ++k) y0 += bf(x[k]) * bf(W[(size_t)c * d_in + k]);
+                if (bias) y0 += bf(bias[c]);
+                v += bf(g[c]) * y0;
+            } else {
+                double G = 0.0;
+                for (int32_t j = 0; j < d_out; ++j) G += bf(g[j]) * bf(W[(size_t)j * d_in + c]);
+                v += bf(x[c]) * G;
+            }
+        }
+        dl_out[q] = v;
+    }
+    return 0;
+}

@@ -1,0 +1,78 @@
+"""Shared test helpers: tiny exactly-representable inputs and error metrics."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+import synth
+
+
+def grid_bits(rng: np.random.Generator, shape, lo=-12, hi=12, denom=8.0) -> np.ndarray:
+    """bf16 bit patterns of small multiples of 1/denom: sums of products are exact in fp64."""
+    v = rng.integers(lo, hi + 1, size=shape).astype(np.float32) / np.float32(denom)
+    b = synth.f32_to_bf16_bits(v)
+    assert np.array_equal(synth.bf16_bits_to_f32(b), v)
+    return b
+
+
+def f64(bits: np.ndarray) -> np.ndarray:
+    return synth.bf16_bits_to_f64(bits)
+
+
+def bits_of(v) -> np.ndarray:
+    v = np.asarray(v, dtype=np.float32)
+    b = synth.f32_to_bf16_bits(v)
+    assert np.array_equal(synth.bf16_bits_to_f32(b), v), "value not representable in bf16"
+    return b
+
+
+def tiny_problem(seed=0, d_in=5, d_out=3, lens=(3, 0, 2, 2, 4), kinds=None, ranks=None, bias=True):
+    """A mixed tiny batch (one empty segment) on the exact grid."""
+    rng = np.random.default_rng(seed)
+    S = len(lens)
+    kinds = kinds or [oracle.LORA, oracle.LORA, oracle.IA3, oracle.NONE, oracle.IA3_IN][:S]
+    ranks = ranks or [2, 3, 0, 0, 0][:S]
+    off = np.zeros(S + 1, dtype=np.int32)
+    off[1:] = np.cumsum(lens)
+    T = int(off[-1])
+    X = grid_bits(rng, (T, d_in))
+    W = grid_bits(rng, (d_out, d_in))
+    dY = grid_bits(rng, (T, d_out))
+    b = grid_bits(rng, (d_out,)) if bias else None
+    ads = []
+    for i in range(S):
+        if kinds[i] == oracle.LORA:
+            ads.append(oracle.Adapter(oracle.LORA, ranks[i], [2.0, 0.5, 1.0, 4.0, 0.25][i % 5],
+                                      grid_bits(rng, (ranks[i], d_in)), grid_bits(rng, (d_out, ranks[i]))))
+        elif kinds[i] == oracle.IA3:
+            ads.append(oracle.Adapter(oracle.IA3, 0, 0.0, grid_bits(rng, (d_out,))))
+        elif kinds[i] == oracle.IA3_IN:
+            ads.append(oracle.Adapter(oracle.IA3_IN, 0, 0.0, grid_bits(rng, (d_in,))))
+        else:
+            ads.append(oracle.Adapter())
+    return dict(off=off, X=X, W=W, dY=dY, bias=b, ads=ads, d_in=d_in, d_out=d_out, T=T, S=S)
+
+
+def rel_fro(got: np.ndarray, ref: np.ndarray) -> float:
+    den = float(np.linalg.norm(ref.astype(np.float64)))
+    num = float(np.linalg.norm(got.astype(np.float64) - ref.astype(np.float64)))
+    return num / den if den > 0 else num
+
+
+def max_abs_over_rms(got: np.ndarray, ref: np.ndarray) -> float:
+    ref = ref.astype(np.float64)
+    rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
+    err = float(np.max(np.abs(got.astype(np.float64) - ref))) if ref.size else 0.0
+    return err / rms if rms > 0 else err
+
+
+# Parity bar (relative Frobenius error, max-abs error on outputs scaled to unit RMS).
+REL_FRO_TOL = 4e-3
+MAX_ABS_TOL = 2e-2
+
+
+def assert_close(got, ref, what=""):
+    rf, ma = rel_fro(got, ref), max_abs_over_rms(got, ref)
+    assert rf <= REL_FRO_TOL, f"{what}: relative Frobenius error {rf:.3e} > {REL_FRO_TOL}"
+    assert ma <= MAX_ABS_TOL, f"{what}: max-abs/RMS error {ma:.3e} > {MAX_ABS_TOL}"
+    return rf, ma
