@@ -1,0 +1,172 @@
+/*
+ * symb.h -- C ABI of the MI355X (gfx950) base-executor layer with per-client adapters.
+ *
+ * One call runs ONE frozen linear layer over the flattened, padding-free token batch
+ * of many clients and applies each client's own adapter to that client's token
+ * segment.  Method: Symbiosis (arXiv 2507.03220):
+ *   - Sec. 3.2 "Base Executor": requests of many clients for one layer are batched,
+ *     the layer is executed once, the result is split per client.
+ *   - Sec. 3.7: token position is irrelevant for nn.Linear, so all clients' tokens
+ *     are concatenated along one token axis with no padding.
+ *   - Sec. 3.6: the layer is frozen; backward multiplies the output gradient by the
+ *     parameters, saves nothing from forward, and may run on a different batch.
+ *   - Sec. 3.8 eqs. (1)-(3): optional bias; a bias-free pass exists.
+ *   - Sec. 1 and Sec. 3.2 "Client": every client chooses its own PEFT method and
+ *     parameters (LoRA rank and alpha, IA3).  The paper keeps the adapter at the
+ *     client; here client and executor share one GPU (its "local" placement, Sec. 3.3)
+ *     and the adapter term is fused into the same call.  kind NONE for every segment
+ *     gives exactly the paper's executor.
+ *
+ * Notation.  S segments; segment i owns rows off[i] .. off[i+1]-1 of every [T][*]
+ * tensor, T = off[S].  For a row t of segment i:
+ *     Y0[t][j] = sum_k X[t][k] W[j][k] (+ bias[j])
+ *     NONE : Y = Y0
+ *     LORA : H[t][p] = sum_k X[t][k] A_i[p][k];   Y[t][j] = Y0[t][j] + s_i sum_p H[t][p] B_i[j][p]
+ *     IA3  : Y[t][j] = l_i[j] Y0[t][j]
+ *   backward (on the backward batch's own segments):
+ *     NONE : dX[t][k] = sum_j dY[t][j] W[j][k]
+ *     LORA : dH[t][p] = s_i sum_j dY[t][j] B_i[j][p];  dX[t][k] = sum_j dY[t][j] W[j][k] + sum_p dH[t][p] A_i[p][k]
+ *            dA_i[p][k] = sum_{t in i} dH[t][p] X[t][k];   dB_i[j][p] = s_i sum_{t in i} dY[t][j] H[t][p]
+ *     IA3  : dX[t][k] = sum_j dY[t][j] l_i[j] W[j][k];     dl_i[j] = sum_{t in i} dY[t][j] Y0[t][j]
+ *
+ * Types and layouts.  All matrices are dense row-major with no row stride argument.
+ * Activations, weights, bias and adapter tensors are bf16; accumulation is fp32;
+ * base and adapter terms are summed in fp32 and rounded once (nearest-even) to bf16
+ * at the store (H and dH travel between kernels as a bf16 value plus a bf16 rounding
+ * residual, i.e. with about 16 significand bits).  Adapter gradients
+ * are fp32 in the layout of the tensor they belong to.  Device pointers must be
+ * 16-byte aligned; d_in and d_out must be multiples of 8.
+ *
+ * Ownership.  The caller owns every device buffer and the workspace.  Host arrays
+ * (offsets, descriptors) are copied during the call and may be freed on return.
+ * The library allocates device memory only inside symb_create.
+ *
+ * Ordering.  All GPU work is enqueued on the given stream (a hipStream_t passed as
+ * void*; NULL = the default stream); calls return without synchronising.  Calls on
+ * one handle from several host threads must be serialised by the caller.
+ *
+ * Errors.  Every entry point returns a symb_status; nothing throws or aborts.  All
+ * argument checks happen before the first launch: a failing call enqueues nothing,
+ * leaves outputs untouched and the handle usable.  The library is stateless across
+ * calls (Sec. 3.6): no call depends on an earlier one.
+ */
+#ifndef SYMB_H
+#define SYMB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SYMB_OK = 0,
+    SYMB_ERR_INVALID_ARG = 1,         /* null pointer, bad dimension, bad flag, misaligned pointer */
+    SYMB_ERR_BAD_SEGMENTS = 2,        /* off[0] != 0 or offsets decrease */
+    SYMB_ERR_UNSUPPORTED = 3,         /* valid request this build cannot run (e.g. IA3_IN, rank > SYMB_MAX_RANK) */
+    SYMB_ERR_WORKSPACE_TOO_SMALL = 4,
+    SYMB_ERR_DEVICE = 5               /* a HIP call failed; see symb_last_error */
+} symb_status;
+
+typedef enum {
+    SYMB_ADAPTER_NONE = 0,
+    SYMB_ADAPTER_LORA = 1,
+    SYMB_ADAPTER_IA3 = 2,             /* output scaling, l[d_out] */
+    SYMB_ADAPTER_IA3_IN = 3           /* input scaling, l[d_in]: defined, not built on the GPU -> UNSUPPORTED */
+} symb_adapter_kind;
+
+enum { SYMB_MAX_RANK = 128 };
+
+typedef enum { SYMB_OP_FWD = 0, SYMB_OP_BWD_INPUT = 1, SYMB_OP_ADAPTER_GRAD = 2 } symb_op;
+
+/* flags of symb_base_linear_bwd_input */
+enum { SYMB_BWD_FULL = 0,             /* dX includes each segment's adapter branch */
+       SYMB_BWD_BASE_ONLY = 1 };      /* dX = dY W only: what the paper's executor returns (Sec. 3.6) */
+/* flags of symb_adapter_grad */
+enum { SYMB_GRAD_OVERWRITE = 0, SYMB_GRAD_ACCUMULATE = 1 };
+
+/* One segment's adapter (Sec. 3.2 "Client": method and parameters are per client). */
+typedef struct {
+    int32_t kind;      /* symb_adapter_kind */
+    int32_t rank;      /* LoRA: r >= 1 (any integer up to SYMB_MAX_RANK); otherwise ignored */
+    float scale;       /* LoRA: s = alpha / r, passed explicitly; otherwise ignored */
+    const void* A;     /* DEVICE. LoRA: bf16 [rank][d_in].  IA3: bf16 l[d_out] */
+    const void* B;     /* DEVICE. LoRA: bf16 [d_out][rank].  otherwise NULL */
+    void* dA;          /* DEVICE fp32, layout of A (IA3: dl[d_out]); NULL = no gradient wanted */
+    void* dB;          /* DEVICE fp32, layout of B; NULL = no gradient wanted */
+} symb_adapter;
+
+/* A flattened batch (Sec. 3.7): segment offsets plus one adapter per segment. */
+typedef struct {
+    int32_t d_in, d_out, num_segments;
+    const int32_t* seg_offsets;    /* HOST, num_segments+1 entries, off[0]=0, non-decreasing; T = off[S] */
+    const symb_adapter* adapters;  /* HOST, num_segments entries */
+} symb_batch;
+
+typedef struct symb_context* symb_handle;
+
+/* Creates a context on HIP device `device`: descriptor staging (pinned host ring +
+ * device ring).  The only call that allocates.  SYMB_ERR_DEVICE if HIP fails. */
+symb_status symb_create(symb_handle* out, int device);
+symb_status symb_destroy(symb_handle h);
+
+/* Host-only checks shared by every entry point (no GPU needed): dimensions, offsets
+ * (Sec. 3.7), per-segment descriptors.  Empty segments, S = 1, T = 0 are legal. */
+symb_status symb_validate_batch(const symb_batch* b);
+
+/* seg(t) = i <=> off[i] <= t < off[i+1], written to host_out[0..T-1] (Sec. 3.2: the
+ * split of the flattened batch back into clients).  Host-only. */
+symb_status symb_debug_row_segment_map(const symb_batch* b, int32_t* host_out);
+
+/* Host-only planner: for row tiles of `tile_m` rows, tile u covers rows
+ * [u*tile_m, min(T,(u+1)*tile_m)) and meets the non-empty segments seg_lo[u]..seg_hi[u]
+ * (inclusive).  Writes ceil(T/tile_m) entries to each array; *num_tiles gets the count. */
+symb_status symb_plan_row_tiles(const symb_batch* b, int32_t tile_m, int32_t* seg_lo,
+                                int32_t* seg_hi, int32_t* num_tiles);
+
+/* Bytes of caller-owned device workspace an operation needs for this batch (may be 0).
+ * Host-only. */
+symb_status symb_workspace_bytes(const symb_batch* b, int32_t op, size_t* out);
+
+/*
+ * Forward (Sec. 3.2, 3.7; eqs. of Sec. 3.8 for the bias):  Y = adapter_i(X W^T + bias).
+ *   X [T][d_in] bf16 DEVICE, W [d_out][d_in] bf16 DEVICE (nn.Linear layout),
+ *   bias [d_out] bf16 DEVICE or NULL, Y [T][d_out] bf16 DEVICE (written),
+ *   Ybase [T][d_out] bf16 DEVICE or NULL: if given, receives Y0 (the pre-adapter
+ *   output the paper's executor would have returned; needed later for IA3 dl).
+ *   ws: DEVICE workspace of at least symb_workspace_bytes(.., SYMB_OP_FWD, ..) bytes.
+ */
+symb_status symb_base_linear_fwd(symb_handle h, const symb_batch* b, const void* X, const void* W,
+                                 const void* bias, void* Y, void* Ybase, void* ws, size_t ws_bytes,
+                                 void* stream);
+
+/*
+ * Input gradient (Sec. 3.6):  dX = dY W (+ adapter branch unless SYMB_BWD_BASE_ONLY).
+ *   dY [T'][d_out] bf16 DEVICE, W as above, dX [T'][d_in] bf16 DEVICE (written).
+ *   The batch is the backward batch's own (any subset / regrouping of clients).
+ */
+symb_status symb_base_linear_bwd_input(symb_handle h, const symb_batch* b, const void* dY,
+                                       const void* W, void* dX, uint32_t flags, void* ws,
+                                       size_t ws_bytes, void* stream);
+
+/*
+ * Adapter gradients per segment (the client-side autograd of Sec. 3.2, fused here):
+ * for every segment whose descriptor has dA / dB non-NULL, writes (OVERWRITE) or adds
+ * to (ACCUMULATE) dA_i, dB_i (LoRA) or dl_i (IA3, through dA).  An empty segment
+ * writes zeros (OVERWRITE) or leaves the buffers alone (ACCUMULATE).
+ *   X [T'][d_in], dY [T'][d_out] bf16 DEVICE; Ybase [T'][d_out] bf16 DEVICE, required
+ *   iff some IA3 segment wants dl (else may be NULL -> SYMB_ERR_INVALID_ARG if needed).
+ */
+symb_status symb_adapter_grad(symb_handle h, const symb_batch* b, const void* X, const void* dY,
+                              const void* Ybase, uint32_t flags, void* ws, size_t ws_bytes,
+                              void* stream);
+
+const char* symb_status_string(symb_status s);
+/* Text of the last error on this handle (h == NULL: of handle-free calls on this thread). */
+const char* symb_last_error(symb_handle h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SYMB_H */

@@ -160,8 +160,9 @@ def lora_grad(off, adapters: Sequence[Adapter], X: np.ndarray, dY: np.ndarray, i
 
 
 def ia3_grad(off, adapters: Sequence[Adapter], X: np.ndarray, dY: np.ndarray, W: np.ndarray,
-             bias: Optional[np.ndarray], i: int, cols=None) -> np.ndarray:
-    """Returns dl (fp64) of IA3 / IA3_IN segment i for the listed channels (default: all)."""
+             bias: Optional[np.ndarray], i: int, cols=None, Y0_saved: Optional[np.ndarray] = None) -> np.ndarray:
+    """Returns dl (fp64) of IA3 / IA3_IN segment i for the listed channels (default: all).
+    Y0_saved: optional bf16 bits [T, d_out] of the base output the client kept from forward."""
     off = _i32(off)
     S = len(off) - 1
     d_out, d_in = W.shape
@@ -172,7 +173,7 @@ def ia3_grad(off, adapters: Sequence[Adapter], X: np.ndarray, dY: np.ndarray, W:
     ad = _pack(adapters, d_in, d_out)
     rc = lib().orc_ia3_grad_segment(C.c_int32(d_in), C.c_int32(d_out), C.c_int32(S),
                                     off.ctypes.data_as(C.c_void_p), ad, _u16(X), _u16(dY), _u16(W),
-                                    _u16(bias), C.c_int32(i), C.c_int32(n),
+                                    _u16(bias), _u16(Y0_saved), C.c_int32(i), C.c_int32(n),
                                     None if cols_a is None else cols_a.ctypes.data_as(C.c_void_p),
                                     dl.ctypes.data_as(C.c_void_p))
     if rc:

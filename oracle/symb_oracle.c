@@ -257,11 +257,15 @@ int orc_lora_grad_segment(int32_t d_in, int32_t d_out, int32_t S, const int32_t*
  * IA3 vector gradient of segment i for the listed channels (cols == NULL: 0..ncols-1).
  *   IA3:    dl[j] = sum_t dY[t][j] * Y0[t][j],   Y0[t][j] = sum_k X[t][k] W[j][k] (+ b[j])
  *   IA3_IN: dl[k] = sum_t X[t][k] * G[t][k],     G[t][k]  = sum_j dY[t][j] W[j][k]
+ * Y0_saved (IA3 only, may be NULL): the [T][d_out] bf16 base output the client kept from
+ * its forward pass (Sec. 3.2: a fine-tuning client saves the layer's input and output
+ * tensors for the backward pass; Sec. 4: they are 16-bit).  When given, it stands for
+ * Y0[t][j] in the sum above instead of the value recomputed from X and W.
  */
 int orc_ia3_grad_segment(int32_t d_in, int32_t d_out, int32_t S, const int32_t* off,
                          const orc_adapter* ad, const uint16_t* X, const uint16_t* dY,
-                         const uint16_t* W, const uint16_t* bias, int32_t i,
-                         int32_t ncols, const int32_t* cols, double* dl_out) {
+                         const uint16_t* W, const uint16_t* bias, const uint16_t* Y0_saved,
+                         int32_t i, int32_t ncols, const int32_t* cols, double* dl_out) {
     if (orc_check_offsets(S, off) || i < 0 || i >= S) return 1;
     const int kind = ad[i].kind;
     if (kind != ORC_IA3 && kind != ORC_IA3_IN) return 1;
@@ -273,7 +277,9 @@ int orc_ia3_grad_segment(int32_t d_in, int32_t d_out, int32_t S, const int32_t* 
         for (int32_t u = 0; u < n; ++u) {
             const uint16_t* x = X + (size_t)(lo + u) * d_in;
             const uint16_t* g = dY + (size_t)(lo + u) * d_out;
-            if (kind == ORC_IA3) {
+            if (kind == ORC_IA3 && Y0_saved) {
+                v += bf(g[c]) * bf(Y0_saved[(size_t)(lo + u) * d_out + c]);
+            } else if (kind == ORC_IA3) {
                 double y0 = 0.0;
                 for (int32_t k = 0; k < d_in; ++k) y0 += bf(x[k]) * bf(W[(size_t)c * d_in + k]);
                 if (bias) y0 += bf(bias[c]);

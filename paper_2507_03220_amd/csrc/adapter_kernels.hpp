@@ -1,0 +1,334 @@
+// HBM-bound kernels around the base GEMM: LoRA shrink (Hs = s X A^T), its backward twin
+// (dH = s dY B), the per-segment parameter gradients (dA, dB, dl) and the IA3 row scale
+// of dY.  All of them walk segment-aligned row chunks from a host-built work list, so a
+// chunk never mixes two clients.
+#pragma once
+#include "symb_device.hpp"
+
+namespace symb {
+
+// One unit of row work: rows [row0, row0 + nrows) of segment `seg` (nrows <= chunk size).
+struct RowChunk {
+    int32_t seg, row0, nrows, pad;
+};
+
+// -------------------------------------------------------------------------------------------
+// Skinny projection:  out[t][p] = s_i * sum_k L[t][k] * R_i[p][k],  p < rpad_i, stored as a bf16
+// value plus a bf16 residual (out[t][rpad_i + p])
+//   forward shrink : L = X  [T][K=d_in],  R_i = A_i  [r][d_in]
+//   backward dH    : L = dY [T][K=d_out], R_i = B_i^T packed [rpad][d_out] (see pack kernel)
+// A workgroup owns 16 rows; its 4 wavefronts split K in interleaved 64-element steps, read
+// MFMA fragments straight from global memory (each row is read as whole 128-byte lines, the
+// adapter rows come from L2), and meet in LDS for the final sum.  RB = max rank blocks of 16.
+// -------------------------------------------------------------------------------------------
+struct SkinnyParams {
+    const bf16* L;            // [T][K]
+    bf16* out;                // [T][out_pitch], out_pitch >= 2 * rpad_i
+    int K, out_pitch;
+    const RowChunk* chunks;   // device
+    const SegDesc* seg;       // device
+    const bf16* packed;       // backward: base of packed B^T area, else null
+    const int64_t* packed_off;// backward: element offset of segment i's [rpad][K] block
+    int use_packed;
+};
+
+template <int RB>
+__global__ void __launch_bounds__(256)
+symb_skinny_kernel(const SkinnyParams p) {
+    __shared__ float red[4][16][RB * 16 + 4];
+    const RowChunk ch = p.chunks[blockIdx.x];
+    const SegDesc sd = p.seg[ch.seg];
+    const int nb = sd.rpad >> 4;                         // rank blocks in use (uniform)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int trow = lane & 15, kq = lane >> 4;
+    const bool row_ok = trow < ch.nrows;
+    const bf16* lrow = p.L + (size_t)(ch.row0 + (row_ok ? trow : 0)) * p.K;
+    const bf16* rbase = p.use_packed ? (p.packed + p.packed_off[ch.seg]) : sd.A;
+    const int rrows = p.use_packed ? sd.rpad : sd.rank;  // valid adapter rows
+
+    floatx4 acc[RB];
+#pragma unroll
+    for (int j = 0; j < RB; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    for (int k0 = wave * 64; k0 < p.K; k0 += 256) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int k = k0 + h * 32 + kq * 8;
+            const bool kok = k < p.K;
+            uint4 lv = make_uint4(0u, 0u, 0u, 0u);
+            if (row_ok && kok) lv = *reinterpret_cast<const uint4*>(lrow + k);
+            const bf16x8 lf = __builtin_bit_cast(bf16x8, lv);
+#pragma unroll
+            for (int j = 0; j < RB; ++j) {
+                if (j < nb) {
+                    const int pr = j * 16 + trow;
+                    uint4 rv = make_uint4(0u, 0u, 0u, 0u);
+                    if (pr < rrows && kok) rv = *reinterpret_cast<const uint4*>(rbase + (size_t)pr * p.K + k);
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rv), lf, acc[j], 0, 0, 0);
+                }
+            }
+        }
+    }
+    // lane holds out[t = trow][p = j*16 + 4*kq + q]
+#pragma unroll
+    for (int j = 0; j < RB; ++j)
+        if (j < nb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) red[wave][trow][j * 16 + kq * 4 + q] = acc[j][q];
+    __syncthreads();
+    // One row of `out` holds, for its own segment, rpad values rounded to bf16 followed by the
+    // rpad rounding residuals (also bf16): hi + lo carries ~16 significand bits into the GEMM.
+    const int npairs = 16 * (sd.rpad >> 1);
+    for (int e = tid; e < npairs; e += 256) {
+        const int t = e / (sd.rpad >> 1), pp = (e % (sd.rpad >> 1)) * 2;
+        if (t < ch.nrows) {
+            const float v0 = sd.scale * (red[0][t][pp] + red[1][t][pp] + red[2][t][pp] + red[3][t][pp]);
+            const float v1 = sd.scale * (red[0][t][pp + 1] + red[1][t][pp + 1] + red[2][t][pp + 1] + red[3][t][pp + 1]);
+            const unsigned short h0 = f32_to_bf16_bits(v0), h1 = f32_to_bf16_bits(v1);
+            bf16* row = p.out + (size_t)(ch.row0 + t) * p.out_pitch;
+            *reinterpret_cast<unsigned int*>(row + pp) = (unsigned int)h0 | ((unsigned int)h1 << 16);
+            *reinterpret_cast<unsigned int*>(row + sd.rpad + pp) =
+                pack2_bf16(v0 - bf16_bits_to_f32(h0), v1 - bf16_bits_to_f32(h1));
+        }
+    }
+}
+
+// Packs B_i [d_out][r] into B_i^T [rpad][d_out] (zero rows beyond r) so the backward
+// projection reads K-contiguous adapter rows.  grid.y = segment, grid.x covers d_out.
+struct PackParams {
+    const SegDesc* seg;
+    bf16* packed;
+    const int64_t* packed_off;
+    int d_out;
+};
+__global__ void __launch_bounds__(256) symb_pack_bt_kernel(const PackParams p) {
+    const SegDesc sd = p.seg[blockIdx.y];
+    if (sd.kind != KIND_LORA) return;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= p.d_out) return;
+    unsigned short* dst = reinterpret_cast<unsigned short*>(p.packed + p.packed_off[blockIdx.y]);
+    const unsigned short* src = reinterpret_cast<const unsigned short*>(sd.B) + (size_t)j * sd.rank;
+    for (int q = 0; q < sd.rpad; ++q) dst[(size_t)q * p.d_out + j] = (q < sd.rank) ? src[q] : (unsigned short)0;
+}
+
+// -------------------------------------------------------------------------------------------
+// LoRA parameter gradients of one segment, contraction over its tokens:
+//   G[c][pp] = sum_t R[t][c] * L[t][pp]
+//   dB_i (CMAJOR = true ): R = dY, L = Hs -> out[c * rank + pp]      ([d_out][r])
+//   dA_i (CMAJOR = false): R = X,  L = dH -> out[pp * ncols + c]     ([r][d_in])
+// A workgroup owns 128 columns of one segment and walks its tokens 32 at a time through
+// LDS; both MFMA operands are token-strided in memory and are read with the transposing
+// LDS load.  Fixed summation order: results do not depend on the launch.
+// -------------------------------------------------------------------------------------------
+struct GradParams {
+    const bf16* R;            // [T][ncols]
+    const bf16* L;            // [T][l_pitch]: per row rpad_i values then rpad_i residuals (see skinny kernel)
+    int ncols, l_pitch;
+    const int32_t* off;
+    const SegDesc* seg;
+    const int32_t* seg_list;  // device: segments that want this gradient (grid.y indexes it)
+    int accumulate;
+};
+
+constexpr int GRAD_CT = 128;       // columns per workgroup
+constexpr int GRAD_TT = 32;        // tokens per step
+constexpr int GRAD_RPITCH = GRAD_CT * 2 + 16;   // LDS row pitch of the R tile in bytes
+
+__device__ __forceinline__ bf16x8 lds_read_tr_16x32(const unsigned char* base, int pitch_bytes, int col0, int lane) {
+    // tile [32 t][cols] (column-contiguous); returns for lane l: column col0 + (l & 15), t = 8*(l >> 4) + 0..7
+    const int g = lane >> 4, jj = lane & 15;
+    const unsigned char* p0 = base + (g * 8 + (jj >> 2)) * pitch_bytes + (col0 + ((jj & 3) << 2)) * 2;
+    typedef __attribute__((address_space(3))) shortx4 lds_s4;
+    shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(p0));
+    shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(p0 + 4 * pitch_bytes));
+    typedef __attribute__((__vector_size__(8 * sizeof(short)))) short shortx8;
+    shortx8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+template <int RB, bool CMAJOR>
+__global__ void __launch_bounds__(256)
+symb_lora_grad_kernel(const GradParams p) {
+    constexpr int LP = 2 * RB * 16 * 2 + 16;           // LDS row pitch of the L tile (value | residual) in bytes
+    __shared__ __attribute__((aligned(16))) unsigned char sR[GRAD_TT * GRAD_RPITCH];
+    __shared__ __attribute__((aligned(16))) unsigned char sL[GRAD_TT * LP];
+    const int s = p.seg_list[blockIdx.y];
+    const SegDesc sd = p.seg[s];
+    const int t_lo = p.off[s], t_hi = p.off[s + 1];
+    const int c0 = blockIdx.x * GRAD_CT;
+    const int nb = sd.rpad >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    floatx4 acc[2][RB];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < RB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // R tile: 32 rows x 16 chunks of 8 columns = 512 chunks, 2 per thread.  L tile: 32 x (rpad/8) chunks.
+    const int lw = sd.rpad >> 2;                       // 16-byte chunks per L row: 2 * rpad bf16
+    const int l_chunks = GRAD_TT * lw;
+    for (int t0 = t_lo; t0 < t_hi; t0 += GRAD_TT) {
+        uint4 rr[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int c = tid + i * 256, tr = c >> 4, cc = c & 15;
+            const bool ok = (t0 + tr) < t_hi && (c0 + cc * 8) < p.ncols;
+            rr[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (ok) rr[i] = *reinterpret_cast<const uint4*>(p.R + (size_t)(t0 + tr) * p.ncols + c0 + cc * 8);
+        }
+        __syncthreads();     // previous step's LDS reads are done
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int c = tid + i * 256, tr = c >> 4, cc = c & 15;
+            *reinterpret_cast<uint4*>(sR + tr * GRAD_RPITCH + cc * 16) = rr[i];
+        }
+        for (int c = tid; c < l_chunks; c += 256) {
+            const int tr = c / lw, pc = c % lw;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if ((t0 + tr) < t_hi) v = *reinterpret_cast<const uint4*>(p.L + (size_t)(t0 + tr) * p.l_pitch + pc * 8);
+            *reinterpret_cast<uint4*>(sL + tr * LP + pc * 16) = v;
+        }
+        __syncthreads();
+        bf16x8 rf[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) rf[i] = lds_read_tr_16x32(sR, GRAD_RPITCH, wave * 32 + i * 16, lane);
+#pragma unroll
+        for (int j = 0; j < RB; ++j) {
+            if (j < nb) {
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {      // bf16 value, then its rounding residual
+                    const bf16x8 lf = lds_read_tr_16x32(sL, LP, half * sd.rpad + j * 16, lane);
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        if constexpr (CMAJOR) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lf, rf[i], acc[i][j], 0, 0, 0);
+                        else acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rf[i], lf, acc[i][j], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+    float* out = CMAJOR ? sd.dB : sd.dA;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < RB; ++j) {
+            if (j < nb) {
+                if constexpr (CMAJOR) {
+                    // lane: column c = .. + (lane & 15); registers: pp = j*16 + 4*(lane >> 4) + q
+                    const int c = c0 + wave * 32 + i * 16 + (lane & 15);
+                    if (c < p.ncols) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int pp = j * 16 + ((lane >> 4) << 2) + q;
+                            if (pp < sd.rank) {
+                                float* dst = out + (size_t)c * sd.rank + pp;
+                                *dst = p.accumulate ? (*dst + acc[i][j][q]) : acc[i][j][q];
+                            }
+                        }
+                    }
+                } else {
+                    // lane: pp = j*16 + (lane & 15); registers: column c = .. + 4*(lane >> 4) + q
+                    const int pp = j * 16 + (lane & 15);
+                    const int c = c0 + wave * 32 + i * 16 + ((lane >> 4) << 2);
+                    if (pp < sd.rank && c < p.ncols) {
+                        float4* dst = reinterpret_cast<float4*>(out + (size_t)pp * p.ncols + c);
+                        float4 v = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+                        if (p.accumulate) { const float4 o = *dst; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
+                        *dst = v;
+                    }
+                }
+            }
+        }
+}
+
+// -------------------------------------------------------------------------------------------
+// IA3 vector gradient:  dl_i[j] = sum_{t in segment i} dY[t][j] * Y0[t][j]
+// grid.x covers d_out in blocks of 256 columns, grid.y indexes the IA3 segments that want it.
+// A thread owns 8 columns (16-byte loads) and every 8th token; partial sums meet in LDS.
+// -------------------------------------------------------------------------------------------
+struct Ia3GradParams {
+    const bf16* dY;
+    const bf16* Y0;
+    int d_out;
+    const int32_t* off;
+    const SegDesc* seg;
+    const int32_t* seg_list;
+    int accumulate;
+};
+__global__ void __launch_bounds__(256) symb_ia3_grad_kernel(const Ia3GradParams p) {
+    __shared__ float red[8][32][8];
+    const int s = p.seg_list[blockIdx.y];
+    const int t_lo = p.off[s], t_hi = p.off[s + 1];
+    const int cc = threadIdx.x & 31, tl = threadIdx.x >> 5;
+    const int c = blockIdx.x * 256 + cc * 8;
+    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (c < p.d_out) {
+        for (int t = t_lo + tl; t < t_hi; t += 8) {
+            const uint4 g = *reinterpret_cast<const uint4*>(p.dY + (size_t)t * p.d_out + c);
+            const uint4 y = *reinterpret_cast<const uint4*>(p.Y0 + (size_t)t * p.d_out + c);
+            const unsigned int gw[4] = {g.x, g.y, g.z, g.w}, yw[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                a[2 * q] += bf16_bits_to_f32((unsigned short)(gw[q] & 0xffffu)) * bf16_bits_to_f32((unsigned short)(yw[q] & 0xffffu));
+                a[2 * q + 1] += bf16_bits_to_f32((unsigned short)(gw[q] >> 16)) * bf16_bits_to_f32((unsigned short)(yw[q] >> 16));
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) red[tl][cc][q] = a[q];
+    __syncthreads();
+    if (tl == 0 && c < p.d_out) {
+        float* out = p.seg[s].dA + c;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < 8; ++w) v += red[w][cc][q];
+            out[q] = p.accumulate ? (out[q] + v) : v;
+        }
+    }
+}
+
+// -------------------------------------------------------------------------------------------
+// Row scale for the IA3 backward:  out[t][j] = bf16( dY[t][j] * l_seg(t)[j] ) for IA3 rows,
+// a plain copy for the others.  One workgroup per row chunk from the work list.
+// -------------------------------------------------------------------------------------------
+struct ScaleParams {
+    const bf16* dY;
+    bf16* out;
+    int d_out;
+    const RowChunk* chunks;
+    const SegDesc* seg;
+};
+__global__ void __launch_bounds__(256) symb_ia3_scale_rows_kernel(const ScaleParams p) {
+    const RowChunk ch = p.chunks[blockIdx.x];
+    const SegDesc sd = p.seg[ch.seg];
+    const bool ia3 = sd.kind == KIND_IA3;
+    const int nchunk = p.d_out >> 3;
+    for (int t = 0; t < ch.nrows; ++t) {
+        const size_t base = (size_t)(ch.row0 + t) * p.d_out;
+        for (int c = threadIdx.x; c < nchunk; c += 256) {
+            uint4 g = *reinterpret_cast<const uint4*>(p.dY + base + c * 8);
+            if (ia3) {
+                const uint4 l = *reinterpret_cast<const uint4*>(sd.A + c * 8);
+                unsigned int gw[4] = {g.x, g.y, g.z, g.w};
+                const unsigned int lw[4] = {l.x, l.y, l.z, l.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float lo = bf16_bits_to_f32((unsigned short)(gw[q] & 0xffffu)) * bf16_bits_to_f32((unsigned short)(lw[q] & 0xffffu));
+                    const float hi = bf16_bits_to_f32((unsigned short)(gw[q] >> 16)) * bf16_bits_to_f32((unsigned short)(lw[q] >> 16));
+                    gw[q] = pack2_bf16(lo, hi);
+                }
+                g = make_uint4(gw[0], gw[1], gw[2], gw[3]);
+            }
+            *reinterpret_cast<uint4*>(p.out + base + c * 8) = g;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256) symb_fill_zero_kernel(float* dst, size_t n) {
+    for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = 0.f;
+}
+
+}  // namespace symb

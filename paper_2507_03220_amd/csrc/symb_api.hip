@@ -1,0 +1,698 @@
+// Host side of the C ABI declared in include/symb.h: argument checks, the segment
+// planner, descriptor staging and the kernel launches.  Nothing here computes any part
+// of the layer on the CPU; without a GPU every compute entry point fails with
+// SYMB_ERR_DEVICE.
+#include "../../include/symb.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "adapter_kernels.hpp"
+#include "gemm_kernel.hpp"
+
+using namespace symb;
+
+namespace {
+
+thread_local std::string g_tls_error;
+
+constexpr int kSlots = 4;                       // descriptor ring depth
+constexpr size_t kSlotBytes = (size_t)2 << 20;  // capacity of one descriptor blob
+constexpr int kSkinnyRows = 16;                 // rows per skinny / scale work item
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int rpad_of(int r) { return (r + 15) / 16 * 16; }
+
+}  // namespace
+
+struct symb_context {
+    int device = 0;
+    unsigned char* host_ring = nullptr;   // pinned, kSlots * kSlotBytes
+    unsigned char* dev_ring = nullptr;    // device, kSlots * kSlotBytes
+    hipEvent_t slot_done[kSlots] = {};
+    bool slot_used[kSlots] = {};
+    int next_slot = 0;
+    std::string error;
+};
+
+namespace {
+
+symb_status fail(symb_handle h, symb_status st, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (h) h->error = buf;
+    g_tls_error = buf;
+    return st;
+}
+
+#define SYMB_HIP(h, call)                                                                      \
+    do {                                                                                       \
+        hipError_t e_ = (call);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return fail(h, SYMB_ERR_DEVICE, "%s failed: %s", #call, hipGetErrorString(e_));    \
+    } while (0)
+
+symb_status validate(symb_handle h, const symb_batch* b) {
+    if (!b) return fail(h, SYMB_ERR_INVALID_ARG, "batch is null");
+    if (b->d_in <= 0 || b->d_out <= 0) return fail(h, SYMB_ERR_INVALID_ARG, "d_in and d_out must be positive");
+    if ((b->d_in % 8) || (b->d_out % 8)) return fail(h, SYMB_ERR_INVALID_ARG, "d_in and d_out must be multiples of 8");
+    if (b->num_segments < 0) return fail(h, SYMB_ERR_INVALID_ARG, "num_segments is negative");
+    if (!b->seg_offsets) return fail(h, SYMB_ERR_INVALID_ARG, "seg_offsets is null");
+    if (b->num_segments > 0 && !b->adapters) return fail(h, SYMB_ERR_INVALID_ARG, "adapters is null");
+    if (b->seg_offsets[0] != 0) return fail(h, SYMB_ERR_BAD_SEGMENTS, "seg_offsets[0] must be 0");
+    for (int i = 0; i < b->num_segments; ++i)
+        if (b->seg_offsets[i + 1] < b->seg_offsets[i])
+            return fail(h, SYMB_ERR_BAD_SEGMENTS, "seg_offsets decrease at segment %d", i);
+    for (int i = 0; i < b->num_segments; ++i) {
+        const symb_adapter& a = b->adapters[i];
+        switch (a.kind) {
+            case SYMB_ADAPTER_NONE: break;
+            case SYMB_ADAPTER_LORA:
+                if (a.rank < 1) return fail(h, SYMB_ERR_INVALID_ARG, "segment %d: LoRA rank must be >= 1", i);
+                if (a.rank > SYMB_MAX_RANK)
+                    return fail(h, SYMB_ERR_UNSUPPORTED, "segment %d: LoRA rank %d exceeds SYMB_MAX_RANK", i, a.rank);
+                if (!a.A || !a.B) return fail(h, SYMB_ERR_INVALID_ARG, "segment %d: LoRA needs A and B", i);
+                if (((uintptr_t)a.A & 15) || ((uintptr_t)a.dA & 15) || ((uintptr_t)a.dB & 3) || ((uintptr_t)a.B & 1))
+                    return fail(h, SYMB_ERR_INVALID_ARG, "segment %d: adapter pointer misaligned", i);
+                if ((a.rank % 8) == 0 && ((uintptr_t)a.B & 15))
+                    return fail(h, SYMB_ERR_INVALID_ARG, "segment %d: B must be 16-byte aligned", i);
+                break;
+            case SYMB_ADAPTER_IA3:
+                if (!a.A) return fail(h, SYMB_ERR_INVALID_ARG, "segment %d: IA3 needs its vector in A", i);
+                if (((uintptr_t)a.A & 15) || ((uintptr_t)a.dA & 15))
+                    return fail(h, SYMB_ERR_INVALID_ARG, "segment %d: adapter pointer misaligned", i);
+                break;
+            case SYMB_ADAPTER_IA3_IN:
+                return fail(h, SYMB_ERR_UNSUPPORTED, "segment %d: IA3 input scaling is not built on the GPU", i);
+            default: return fail(h, SYMB_ERR_INVALID_ARG, "segment %d: unknown adapter kind %d", i, a.kind);
+        }
+    }
+    return SYMB_OK;
+}
+
+bool misaligned16(const void* p) { return ((uintptr_t)p & 15) != 0; }
+
+// ---- planner (pure integer host work) ------------------------------------------------------
+void plan_row_tiles(const symb_batch* b, int tile_m, std::vector<int32_t>& lo, std::vector<int32_t>& hi) {
+    const int S = b->num_segments;
+    const int32_t* off = b->seg_offsets;
+    const int T = off[S];
+    const int nt = (T + tile_m - 1) / tile_m;
+    lo.assign(nt, 0);
+    hi.assign(nt, -1);
+    int s = 0;
+    for (int u = 0; u < nt; ++u) {
+        const int r0 = u * tile_m, r1 = std::min(T, r0 + tile_m);
+        while (off[s + 1] <= r0) ++s;            // first segment that owns row r0 (non-empty by construction)
+        int e = s;
+        while (off[e + 1] < r1) ++e;             // segment that owns row r1 - 1
+        lo[u] = s;
+        hi[u] = e;
+    }
+}
+
+void plan_chunks(const symb_batch* b, int rows, bool lora_only, std::vector<RowChunk>& out) {
+    out.clear();
+    for (int i = 0; i < b->num_segments; ++i) {
+        if (lora_only && b->adapters[i].kind != SYMB_ADAPTER_LORA) continue;
+        for (int r = b->seg_offsets[i]; r < b->seg_offsets[i + 1]; r += rows)
+            out.push_back(RowChunk{i, r, std::min(rows, b->seg_offsets[i + 1] - r), 0});
+    }
+}
+
+struct BatchInfo {
+    int S = 0, T = 0;
+    int n_lora = 0, n_ia3 = 0;
+    int max_rpad = 0;
+    size_t packed_elems = 0;   // sum rpad_i * d_out over LoRA segments
+};
+
+BatchInfo inspect(const symb_batch* b) {
+    BatchInfo bi;
+    bi.S = b->num_segments;
+    bi.T = b->seg_offsets[bi.S];
+    for (int i = 0; i < bi.S; ++i) {
+        const symb_adapter& a = b->adapters[i];
+        if (a.kind == SYMB_ADAPTER_LORA) {
+            ++bi.n_lora;
+            bi.max_rpad = std::max(bi.max_rpad, rpad_of(a.rank));
+            bi.packed_elems += (size_t)rpad_of(a.rank) * b->d_out;
+        } else if (a.kind == SYMB_ADAPTER_IA3) {
+            ++bi.n_ia3;
+        }
+    }
+    return bi;
+}
+
+// Workspace layout (all regions 256-byte aligned, in this order; absent regions have size 0).
+struct WsLayout {
+    size_t h_off = 0, h_bytes = 0;        // Hs  [T][2*max_rpad] bf16
+    size_t dh_off = 0, dh_bytes = 0;      // dH  [T][2*max_rpad] bf16
+    size_t pk_off = 0, pk_bytes = 0;      // packed B^T
+    size_t sc_off = 0, sc_bytes = 0;      // IA3-scaled copy of dY [T][d_out] bf16
+    size_t total = 0;
+};
+
+WsLayout ws_layout(const symb_batch* b, const BatchInfo& bi, int op, bool full_bwd, bool any_lora_grad) {
+    WsLayout w;
+    size_t cur = 0;
+    auto take = [&](size_t& off, size_t& bytes, size_t n) {
+        off = cur;
+        bytes = n;
+        cur += align_up(n, 256);
+    };
+    const size_t hb = (size_t)bi.T * (2 * bi.max_rpad) * 2;   // value + residual halves
+    if (op == SYMB_OP_FWD) {
+        if (bi.n_lora) take(w.h_off, w.h_bytes, hb);
+    } else if (op == SYMB_OP_BWD_INPUT) {
+        if (full_bwd && bi.n_lora) {
+            take(w.dh_off, w.dh_bytes, hb);
+            take(w.pk_off, w.pk_bytes, bi.packed_elems * 2);
+        }
+        if (full_bwd && bi.n_ia3) take(w.sc_off, w.sc_bytes, (size_t)bi.T * b->d_out * 2);
+    } else {
+        if (any_lora_grad) {
+            take(w.h_off, w.h_bytes, hb);
+            take(w.dh_off, w.dh_bytes, hb);
+            take(w.pk_off, w.pk_bytes, bi.packed_elems * 2);
+        }
+    }
+    w.total = cur;
+    return w;
+}
+
+// ---- descriptor blob -------------------------------------------------------------------------
+struct Blob {
+    std::vector<unsigned char> bytes;
+    template <class T>
+    size_t add(const T* p, size_t n) {
+        const size_t off = align_up(bytes.size(), 16);
+        bytes.resize(off + std::max<size_t>(n, 1) * sizeof(T));
+        if (n) memcpy(bytes.data() + off, p, n * sizeof(T));
+        return off;
+    }
+};
+
+symb_status upload(symb_handle h, const Blob& blob, hipStream_t st, unsigned char** dev_base) {
+    if (blob.bytes.size() > kSlotBytes)
+        return fail(h, SYMB_ERR_UNSUPPORTED, "batch descriptors need %zu bytes, capacity is %zu", blob.bytes.size(), kSlotBytes);
+    const int slot = h->next_slot;
+    if (h->slot_used[slot]) SYMB_HIP(h, hipEventSynchronize(h->slot_done[slot]));
+    unsigned char* hp = h->host_ring + (size_t)slot * kSlotBytes;
+    unsigned char* dp = h->dev_ring + (size_t)slot * kSlotBytes;
+    memcpy(hp, blob.bytes.data(), blob.bytes.size());
+    SYMB_HIP(h, hipMemcpyAsync(dp, hp, blob.bytes.size(), hipMemcpyHostToDevice, st));
+    *dev_base = dp;
+    return SYMB_OK;
+}
+
+// Marks the slot busy until everything enqueued so far on `st` has run (kernels read it).
+symb_status seal_slot(symb_handle h, hipStream_t st) {
+    const int slot = h->next_slot;
+    SYMB_HIP(h, hipEventRecord(h->slot_done[slot], st));
+    h->slot_used[slot] = true;
+    h->next_slot = (slot + 1) % kSlots;
+    return SYMB_OK;
+}
+
+std::vector<SegDesc> make_segdesc(const symb_batch* b) {
+    std::vector<SegDesc> v(b->num_segments);
+    for (int i = 0; i < b->num_segments; ++i) {
+        const symb_adapter& a = b->adapters[i];
+        SegDesc d{};
+        d.kind = a.kind;
+        d.rank = a.kind == SYMB_ADAPTER_LORA ? a.rank : 0;
+        d.rpad = rpad_of(d.rank);
+        d.scale = a.kind == SYMB_ADAPTER_LORA ? a.scale : 0.f;
+        d.A = (const bf16*)a.A;
+        d.B = (const bf16*)a.B;
+        d.dA = (float*)a.dA;
+        d.dB = (float*)a.dB;
+        v[i] = d;
+    }
+    return v;
+}
+
+// ---- GEMM launch -----------------------------------------------------------------------------
+struct GemmChoice {
+    int bm;
+};
+
+template <int BM, int BN, int WGM, int WGN, bool NN>
+symb_status launch_gemm_t(symb_handle h, GemmParams gp, hipStream_t st) {
+    using TT = GemmTile<BM, BN, WGM, WGN, NN>;
+    auto kfn = symb_gemm_kernel<BM, BN, WGM, WGN, NN>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        SYMB_HIP(h, hipFuncSetAttribute(reinterpret_cast<const void*>(kfn), hipFuncAttributeMaxDynamicSharedMemorySize, TT::SMEM));
+        attr_set = true;
+    }
+    gp.num_m_tiles = (gp.M + BM - 1) / BM;
+    gp.num_n_tiles = (gp.N + BN - 1) / BN;
+    gp.group_m = 8;
+    const int total = gp.num_m_tiles * gp.num_n_tiles;
+    const int grid = ((total + 7) / 8) * 8;
+    hipLaunchKernelGGL(kfn, dim3(grid), dim3(TT::NT), TT::SMEM, st, gp);
+    SYMB_HIP(h, hipGetLastError());
+    return SYMB_OK;
+}
+
+// Row-tile height of the GEMM variant used for an M x N problem.
+int gemm_tile_m(int M, int N) {
+    const long big = (long)((M + 255) / 256) * ((N + 255) / 256);
+    return big >= 128 ? 256 : 128;
+}
+
+template <bool NN>
+symb_status launch_gemm(symb_handle h, const GemmParams& gp, hipStream_t st) {
+    if (gemm_tile_m(gp.M, gp.N) == 256) return launch_gemm_t<256, 256, 2, 4, NN>(h, gp, st);
+    return launch_gemm_t<128, 128, 2, 2, NN>(h, gp, st);
+}
+
+template <int RB>
+void launch_skinny_rb(const SkinnyParams& sp, int nchunks, hipStream_t st) {
+    hipLaunchKernelGGL(symb_skinny_kernel<RB>, dim3(nchunks), dim3(256), 0, st, sp);
+}
+symb_status launch_skinny(symb_handle h, const SkinnyParams& sp, int nchunks, int max_rpad, hipStream_t st) {
+    if (nchunks == 0) return SYMB_OK;
+    if (max_rpad <= 16) launch_skinny_rb<1>(sp, nchunks, st);
+    else if (max_rpad <= 32) launch_skinny_rb<2>(sp, nchunks, st);
+    else if (max_rpad <= 64) launch_skinny_rb<4>(sp, nchunks, st);
+    else launch_skinny_rb<8>(sp, nchunks, st);
+    SYMB_HIP(h, hipGetLastError());
+    return SYMB_OK;
+}
+
+template <int RB, bool CM>
+void launch_grad_rb(const GradParams& gp, int nseg, hipStream_t st) {
+    hipLaunchKernelGGL((symb_lora_grad_kernel<RB, CM>), dim3((gp.ncols + GRAD_CT - 1) / GRAD_CT, nseg), dim3(256), 0, st, gp);
+}
+template <bool CM>
+symb_status launch_grad(symb_handle h, const GradParams& gp, int nseg, int max_rpad, hipStream_t st) {
+    if (nseg == 0) return SYMB_OK;
+    if (max_rpad <= 16) launch_grad_rb<1, CM>(gp, nseg, st);
+    else if (max_rpad <= 32) launch_grad_rb<2, CM>(gp, nseg, st);
+    else if (max_rpad <= 64) launch_grad_rb<4, CM>(gp, nseg, st);
+    else launch_grad_rb<8, CM>(gp, nseg, st);
+    SYMB_HIP(h, hipGetLastError());
+    return SYMB_OK;
+}
+
+symb_status check_handle(symb_handle h) {
+    if (!h) return fail(nullptr, SYMB_ERR_INVALID_ARG, "handle is null");
+    if (hipSetDevice(h->device) != hipSuccess) return fail(h, SYMB_ERR_DEVICE, "hipSetDevice(%d) failed", h->device);
+    return SYMB_OK;
+}
+
+}  // namespace
+
+// =============================================================================================
+extern "C" {
+
+const char* symb_status_string(symb_status s) {
+    switch (s) {
+        case SYMB_OK: return "SYMB_OK";
+        case SYMB_ERR_INVALID_ARG: return "SYMB_ERR_INVALID_ARG";
+        case SYMB_ERR_BAD_SEGMENTS: return "SYMB_ERR_BAD_SEGMENTS";
+        case SYMB_ERR_UNSUPPORTED: return "SYMB_ERR_UNSUPPORTED";
+        case SYMB_ERR_WORKSPACE_TOO_SMALL: return "SYMB_ERR_WORKSPACE_TOO_SMALL";
+        case SYMB_ERR_DEVICE: return "SYMB_ERR_DEVICE";
+    }
+    return "SYMB_ERR_UNKNOWN";
+}
+
+const char* symb_last_error(symb_handle h) { return h ? h->error.c_str() : g_tls_error.c_str(); }
+
+symb_status symb_create(symb_handle* out, int device) {
+    if (!out) return fail(nullptr, SYMB_ERR_INVALID_ARG, "out is null");
+    *out = nullptr;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return fail(nullptr, SYMB_ERR_DEVICE, "no HIP device available");
+    if (device < 0 || device >= ndev) return fail(nullptr, SYMB_ERR_INVALID_ARG, "device %d out of range (%d devices)", device, ndev);
+    SYMB_HIP(nullptr, hipSetDevice(device));
+    symb_context* c = new symb_context();
+    c->device = device;
+    if (hipHostMalloc((void**)&c->host_ring, kSlots * kSlotBytes, hipHostMallocDefault) != hipSuccess ||
+        hipMalloc((void**)&c->dev_ring, kSlots * kSlotBytes) != hipSuccess) {
+        if (c->host_ring) (void)hipHostFree(c->host_ring);
+        delete c;
+        return fail(nullptr, SYMB_ERR_DEVICE, "descriptor staging allocation failed");
+    }
+    for (int i = 0; i < kSlots; ++i) {
+        if (hipEventCreateWithFlags(&c->slot_done[i], hipEventDisableTiming) != hipSuccess) {
+            delete c;
+            return fail(nullptr, SYMB_ERR_DEVICE, "hipEventCreate failed");
+        }
+    }
+    *out = c;
+    return SYMB_OK;
+}
+
+symb_status symb_destroy(symb_handle h) {
+    if (!h) return SYMB_OK;
+    (void)hipSetDevice(h->device);
+    for (int i = 0; i < kSlots; ++i) {
+        if (h->slot_used[i]) (void)hipEventSynchronize(h->slot_done[i]);
+        if (h->slot_done[i]) (void)hipEventDestroy(h->slot_done[i]);
+    }
+    if (h->dev_ring) (void)hipFree(h->dev_ring);
+    if (h->host_ring) (void)hipHostFree(h->host_ring);
+    delete h;
+    return SYMB_OK;
+}
+
+symb_status symb_validate_batch(const symb_batch* b) { return validate(nullptr, b); }
+
+symb_status symb_debug_row_segment_map(const symb_batch* b, int32_t* host_out) {
+    symb_status st = validate(nullptr, b);
+    if (st != SYMB_OK) return st;
+    if (!host_out && b->seg_offsets[b->num_segments] > 0) return fail(nullptr, SYMB_ERR_INVALID_ARG, "host_out is null");
+    for (int i = 0; i < b->num_segments; ++i)
+        for (int t = b->seg_offsets[i]; t < b->seg_offsets[i + 1]; ++t) host_out[t] = i;
+    return SYMB_OK;
+}
+
+symb_status symb_plan_row_tiles(const symb_batch* b, int32_t tile_m, int32_t* seg_lo, int32_t* seg_hi, int32_t* num_tiles) {
+    symb_status st = validate(nullptr, b);
+    if (st != SYMB_OK) return st;
+    if (tile_m <= 0 || !num_tiles) return fail(nullptr, SYMB_ERR_INVALID_ARG, "tile_m must be positive and num_tiles non-null");
+    std::vector<int32_t> lo, hi;
+    plan_row_tiles(b, tile_m, lo, hi);
+    *num_tiles = (int32_t)lo.size();
+    if (!lo.empty() && (!seg_lo || !seg_hi)) return fail(nullptr, SYMB_ERR_INVALID_ARG, "seg_lo / seg_hi is null");
+    for (size_t u = 0; u < lo.size(); ++u) {
+        seg_lo[u] = lo[u];
+        seg_hi[u] = hi[u];
+    }
+    return SYMB_OK;
+}
+
+static bool wants_lora_grad(const symb_batch* b) {
+    for (int i = 0; i < b->num_segments; ++i)
+        if (b->adapters[i].kind == SYMB_ADAPTER_LORA && (b->adapters[i].dA || b->adapters[i].dB) &&
+            b->seg_offsets[i + 1] > b->seg_offsets[i])
+            return true;
+    return false;
+}
+
+symb_status symb_workspace_bytes(const symb_batch* b, int32_t op, size_t* out) {
+    symb_status st = validate(nullptr, b);
+    if (st != SYMB_OK) return st;
+    if (!out) return fail(nullptr, SYMB_ERR_INVALID_ARG, "out is null");
+    if (op < SYMB_OP_FWD || op > SYMB_OP_ADAPTER_GRAD) return fail(nullptr, SYMB_ERR_INVALID_ARG, "unknown op %d", op);
+    const BatchInfo bi = inspect(b);
+    *out = ws_layout(b, bi, op, true, wants_lora_grad(b)).total;
+    return SYMB_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+symb_status symb_base_linear_fwd(symb_handle h, const symb_batch* b, const void* X, const void* W, const void* bias,
+                                 void* Y, void* Ybase, void* ws, size_t ws_bytes, void* stream) {
+    symb_status st = check_handle(h);
+    if (st != SYMB_OK) return st;
+    if ((st = validate(h, b)) != SYMB_OK) return st;
+    const BatchInfo bi = inspect(b);
+    if (bi.T == 0) return SYMB_OK;
+    if (!X || !W || !Y) return fail(h, SYMB_ERR_INVALID_ARG, "X, W and Y are required");
+    if (misaligned16(X) || misaligned16(W) || misaligned16(Y) || misaligned16(Ybase) || misaligned16(bias) || misaligned16(ws))
+        return fail(h, SYMB_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
+    const WsLayout wl = ws_layout(b, bi, SYMB_OP_FWD, true, false);
+    if (wl.total > ws_bytes || (wl.total && !ws))
+        return fail(h, SYMB_ERR_WORKSPACE_TOO_SMALL, "forward needs %zu workspace bytes, got %zu", wl.total, ws_bytes);
+    hipStream_t s = (hipStream_t)stream;
+
+    const int bm = gemm_tile_m(bi.T, b->d_out);
+    std::vector<int32_t> lo, hi;
+    plan_row_tiles(b, bm, lo, hi);
+    std::vector<RowChunk> chunks;
+    plan_chunks(b, kSkinnyRows, true, chunks);
+    const std::vector<SegDesc> sd = make_segdesc(b);
+    Blob blob;
+    const size_t o_seg = blob.add(sd.data(), sd.size());
+    const size_t o_off = blob.add(b->seg_offsets, (size_t)bi.S + 1);
+    const size_t o_lo = blob.add(lo.data(), lo.size());
+    const size_t o_hi = blob.add(hi.data(), hi.size());
+    const size_t o_ch = blob.add(chunks.data(), chunks.size());
+    unsigned char* dev = nullptr;
+    if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
+
+    unsigned char* wsb = (unsigned char*)ws;
+    bf16* Hs = bi.n_lora ? (bf16*)(wsb + wl.h_off) : nullptr;
+    if (bi.n_lora) {
+        SkinnyParams sp{};
+        sp.L = (const bf16*)X;
+        sp.out = Hs;
+        sp.K = b->d_in;
+        sp.out_pitch = 2 * bi.max_rpad;
+        sp.chunks = (const RowChunk*)(dev + o_ch);
+        sp.seg = (const SegDesc*)(dev + o_seg);
+        sp.use_packed = 0;
+        if ((st = launch_skinny(h, sp, (int)chunks.size(), bi.max_rpad, s)) != SYMB_OK) return st;
+    }
+    GemmParams gp{};
+    gp.Aop = (const bf16*)X;
+    gp.Bop = (const bf16*)W;
+    gp.C = (bf16*)Y;
+    gp.Cbase = (bf16*)Ybase;
+    gp.bias = (const bf16*)bias;
+    gp.M = bi.T;
+    gp.N = b->d_out;
+    gp.K = b->d_in;
+    gp.off = (const int32_t*)(dev + o_off);
+    gp.seg = (const SegDesc*)(dev + o_seg);
+    gp.tile_seg_lo = (const int32_t*)(dev + o_lo);
+    gp.tile_seg_hi = (const int32_t*)(dev + o_hi);
+    gp.ext = Hs;
+    gp.ext_pitch = 2 * bi.max_rpad;
+    gp.epi_ia3 = bi.n_ia3 > 0;
+    if ((st = launch_gemm<false>(h, gp, s)) != SYMB_OK) return st;
+    return seal_slot(h, s);
+}
+
+// ---------------------------------------------------------------------------------------------
+symb_status symb_base_linear_bwd_input(symb_handle h, const symb_batch* b, const void* dY, const void* W, void* dX,
+                                       uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
+    symb_status st = check_handle(h);
+    if (st != SYMB_OK) return st;
+    if ((st = validate(h, b)) != SYMB_OK) return st;
+    if (flags != SYMB_BWD_FULL && flags != SYMB_BWD_BASE_ONLY) return fail(h, SYMB_ERR_INVALID_ARG, "unknown backward flag %u", flags);
+    const BatchInfo bi = inspect(b);
+    if (bi.T == 0) return SYMB_OK;
+    if (!dY || !W || !dX) return fail(h, SYMB_ERR_INVALID_ARG, "dY, W and dX are required");
+    if (misaligned16(dY) || misaligned16(W) || misaligned16(dX) || misaligned16(ws))
+        return fail(h, SYMB_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
+    const bool full = flags == SYMB_BWD_FULL;
+    const WsLayout wl = ws_layout(b, bi, SYMB_OP_BWD_INPUT, full, false);
+    if (wl.total > ws_bytes || (wl.total && !ws))
+        return fail(h, SYMB_ERR_WORKSPACE_TOO_SMALL, "backward needs %zu workspace bytes, got %zu", wl.total, ws_bytes);
+    hipStream_t s = (hipStream_t)stream;
+    const bool lora = full && bi.n_lora > 0, ia3 = full && bi.n_ia3 > 0;
+
+    const int bm = gemm_tile_m(bi.T, b->d_in);
+    std::vector<int32_t> lo, hi;
+    plan_row_tiles(b, bm, lo, hi);
+    std::vector<RowChunk> chunks, all_chunks;
+    if (lora) plan_chunks(b, kSkinnyRows, true, chunks);
+    if (ia3) plan_chunks(b, kSkinnyRows, false, all_chunks);
+    const std::vector<SegDesc> sd = make_segdesc(b);
+    std::vector<int64_t> pk_off(bi.S, 0);
+    {
+        int64_t cur = 0;
+        for (int i = 0; i < bi.S; ++i)
+            if (sd[i].kind == KIND_LORA) {
+                pk_off[i] = cur;
+                cur += (int64_t)sd[i].rpad * b->d_out;
+            }
+    }
+    Blob blob;
+    const size_t o_seg = blob.add(sd.data(), sd.size());
+    const size_t o_off = blob.add(b->seg_offsets, (size_t)bi.S + 1);
+    const size_t o_lo = blob.add(lo.data(), lo.size());
+    const size_t o_hi = blob.add(hi.data(), hi.size());
+    const size_t o_ch = blob.add(chunks.data(), chunks.size());
+    const size_t o_all = blob.add(all_chunks.data(), all_chunks.size());
+    const size_t o_pk = blob.add(pk_off.data(), pk_off.size());
+    unsigned char* dev = nullptr;
+    if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
+
+    unsigned char* wsb = (unsigned char*)ws;
+    const bf16* a_op = (const bf16*)dY;
+    bf16* dH = nullptr;
+    if (lora) {
+        dH = (bf16*)(wsb + wl.dh_off);
+        PackParams pp{(const SegDesc*)(dev + o_seg), (bf16*)(wsb + wl.pk_off), (const int64_t*)(dev + o_pk), b->d_out};
+        hipLaunchKernelGGL(symb_pack_bt_kernel, dim3((b->d_out + 255) / 256, bi.S), dim3(256), 0, s, pp);
+        SYMB_HIP(h, hipGetLastError());
+        SkinnyParams sp{};
+        sp.L = (const bf16*)dY;
+        sp.out = dH;
+        sp.K = b->d_out;
+        sp.out_pitch = 2 * bi.max_rpad;
+        sp.chunks = (const RowChunk*)(dev + o_ch);
+        sp.seg = (const SegDesc*)(dev + o_seg);
+        sp.packed = (const bf16*)(wsb + wl.pk_off);
+        sp.packed_off = (const int64_t*)(dev + o_pk);
+        sp.use_packed = 1;
+        if ((st = launch_skinny(h, sp, (int)chunks.size(), bi.max_rpad, s)) != SYMB_OK) return st;
+    }
+    if (ia3) {
+        ScaleParams sc{(const bf16*)dY, (bf16*)(wsb + wl.sc_off), b->d_out, (const RowChunk*)(dev + o_all), (const SegDesc*)(dev + o_seg)};
+        hipLaunchKernelGGL(symb_ia3_scale_rows_kernel, dim3((unsigned)all_chunks.size()), dim3(256), 0, s, sc);
+        SYMB_HIP(h, hipGetLastError());
+        a_op = (const bf16*)(wsb + wl.sc_off);
+    }
+    GemmParams gp{};
+    gp.Aop = a_op;
+    gp.Bop = (const bf16*)W;
+    gp.C = (bf16*)dX;
+    gp.M = bi.T;
+    gp.N = b->d_in;
+    gp.K = b->d_out;
+    gp.off = (const int32_t*)(dev + o_off);
+    gp.seg = (const SegDesc*)(dev + o_seg);
+    gp.tile_seg_lo = (const int32_t*)(dev + o_lo);
+    gp.tile_seg_hi = (const int32_t*)(dev + o_hi);
+    gp.ext = dH;
+    gp.ext_pitch = 2 * bi.max_rpad;
+    gp.epi_ia3 = 0;
+    if ((st = launch_gemm<true>(h, gp, s)) != SYMB_OK) return st;
+    return seal_slot(h, s);
+}
+
+// ---------------------------------------------------------------------------------------------
+symb_status symb_adapter_grad(symb_handle h, const symb_batch* b, const void* X, const void* dY, const void* Ybase,
+                              uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
+    symb_status st = check_handle(h);
+    if (st != SYMB_OK) return st;
+    if ((st = validate(h, b)) != SYMB_OK) return st;
+    if (flags != SYMB_GRAD_OVERWRITE && flags != SYMB_GRAD_ACCUMULATE) return fail(h, SYMB_ERR_INVALID_ARG, "unknown gradient flag %u", flags);
+    const BatchInfo bi = inspect(b);
+    if (!X || !dY) {
+        if (bi.T > 0) return fail(h, SYMB_ERR_INVALID_ARG, "X and dY are required");
+    }
+    if (misaligned16(X) || misaligned16(dY) || misaligned16(Ybase) || misaligned16(ws))
+        return fail(h, SYMB_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
+    const bool acc = flags == SYMB_GRAD_ACCUMULATE;
+    hipStream_t s = (hipStream_t)stream;
+
+    // Which segments want which gradient.  Empty segments: zeros when overwriting, nothing otherwise.
+    std::vector<int32_t> want_a, want_b, want_l;
+    std::vector<std::pair<float*, size_t>> zero_fill;
+    int grad_max_rpad = 0;
+    for (int i = 0; i < bi.S; ++i) {
+        const symb_adapter& a = b->adapters[i];
+        const bool empty = b->seg_offsets[i + 1] == b->seg_offsets[i];
+        if (a.kind == SYMB_ADAPTER_LORA) {
+            if (empty) {
+                if (!acc && a.dA) zero_fill.emplace_back((float*)a.dA, (size_t)a.rank * b->d_in);
+                if (!acc && a.dB) zero_fill.emplace_back((float*)a.dB, (size_t)a.rank * b->d_out);
+                continue;
+            }
+            if (a.dA) want_a.push_back(i);
+            if (a.dB) want_b.push_back(i);
+            if (a.dA || a.dB) grad_max_rpad = std::max(grad_max_rpad, rpad_of(a.rank));
+        } else if (a.kind == SYMB_ADAPTER_IA3 && a.dA) {
+            if (empty) {
+                if (!acc) zero_fill.emplace_back((float*)a.dA, (size_t)b->d_out);
+                continue;
+            }
+            want_l.push_back(i);
+        }
+    }
+    if (!want_l.empty() && !Ybase)
+        return fail(h, SYMB_ERR_INVALID_ARG, "an IA3 segment wants dl but Ybase (the pre-adapter output) is null");
+    const bool any_lora = !want_a.empty() || !want_b.empty();
+    const WsLayout wl = ws_layout(b, bi, SYMB_OP_ADAPTER_GRAD, true, any_lora);
+    if (wl.total > ws_bytes || (wl.total && !ws))
+        return fail(h, SYMB_ERR_WORKSPACE_TOO_SMALL, "adapter_grad needs %zu workspace bytes, got %zu", wl.total, ws_bytes);
+    for (const auto& z : zero_fill) {       // a fill kernel, not a memset node: safe under graph capture
+        hipLaunchKernelGGL(symb_fill_zero_kernel, dim3((unsigned)std::min<size_t>((z.second + 255) / 256, 1024)), dim3(256), 0, s, z.first, z.second);
+        SYMB_HIP(h, hipGetLastError());
+    }
+    if (!any_lora && want_l.empty()) return SYMB_OK;
+
+    // Row chunks of the LoRA segments that want a gradient (Hs for dB, dH for dA).
+    std::vector<RowChunk> ch_h, ch_dh;
+    for (int i : want_b)
+        for (int r = b->seg_offsets[i]; r < b->seg_offsets[i + 1]; r += kSkinnyRows)
+            ch_h.push_back(RowChunk{i, r, std::min(kSkinnyRows, b->seg_offsets[i + 1] - r), 0});
+    for (int i : want_a)
+        for (int r = b->seg_offsets[i]; r < b->seg_offsets[i + 1]; r += kSkinnyRows)
+            ch_dh.push_back(RowChunk{i, r, std::min(kSkinnyRows, b->seg_offsets[i + 1] - r), 0});
+    const std::vector<SegDesc> sd = make_segdesc(b);
+    std::vector<int64_t> pk_off(bi.S, 0);
+    {
+        int64_t cur = 0;
+        for (int i = 0; i < bi.S; ++i)
+            if (sd[i].kind == KIND_LORA) {
+                pk_off[i] = cur;
+                cur += (int64_t)sd[i].rpad * b->d_out;
+            }
+    }
+    Blob blob;
+    const size_t o_seg = blob.add(sd.data(), sd.size());
+    const size_t o_off = blob.add(b->seg_offsets, (size_t)bi.S + 1);
+    const size_t o_chh = blob.add(ch_h.data(), ch_h.size());
+    const size_t o_chd = blob.add(ch_dh.data(), ch_dh.size());
+    const size_t o_pk = blob.add(pk_off.data(), pk_off.size());
+    const size_t o_wa = blob.add(want_a.data(), want_a.size());
+    const size_t o_wb = blob.add(want_b.data(), want_b.size());
+    const size_t o_wl = blob.add(want_l.data(), want_l.size());
+    unsigned char* dev = nullptr;
+    if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
+    unsigned char* wsb = (unsigned char*)ws;
+    const SegDesc* dseg = (const SegDesc*)(dev + o_seg);
+    const int32_t* doff = (const int32_t*)(dev + o_off);
+
+    if (!want_b.empty()) {       // dB_i = s_i * dY_i^T H_i  ==  dY_i^T Hs_i
+        SkinnyParams sp{};
+        sp.L = (const bf16*)X;
+        sp.out = (bf16*)(wsb + wl.h_off);
+        sp.K = b->d_in;
+        sp.out_pitch = 2 * bi.max_rpad;
+        sp.chunks = (const RowChunk*)(dev + o_chh);
+        sp.seg = dseg;
+        sp.use_packed = 0;
+        if ((st = launch_skinny(h, sp, (int)ch_h.size(), grad_max_rpad, s)) != SYMB_OK) return st;
+        GradParams gp{(const bf16*)dY, (const bf16*)(wsb + wl.h_off), b->d_out, 2 * bi.max_rpad, doff, dseg,
+                      (const int32_t*)(dev + o_wb), acc ? 1 : 0};
+        if ((st = launch_grad<true>(h, gp, (int)want_b.size(), grad_max_rpad, s)) != SYMB_OK) return st;
+    }
+    if (!want_a.empty()) {       // dA_i = dH_i^T X_i
+        PackParams pp{dseg, (bf16*)(wsb + wl.pk_off), (const int64_t*)(dev + o_pk), b->d_out};
+        hipLaunchKernelGGL(symb_pack_bt_kernel, dim3((b->d_out + 255) / 256, bi.S), dim3(256), 0, s, pp);
+        SYMB_HIP(h, hipGetLastError());
+        SkinnyParams sp{};
+        sp.L = (const bf16*)dY;
+        sp.out = (bf16*)(wsb + wl.dh_off);
+        sp.K = b->d_out;
+        sp.out_pitch = 2 * bi.max_rpad;
+        sp.chunks = (const RowChunk*)(dev + o_chd);
+        sp.seg = dseg;
+        sp.packed = (const bf16*)(wsb + wl.pk_off);
+        sp.packed_off = (const int64_t*)(dev + o_pk);
+        sp.use_packed = 1;
+        if ((st = launch_skinny(h, sp, (int)ch_dh.size(), grad_max_rpad, s)) != SYMB_OK) return st;
+        GradParams gp{(const bf16*)X, (const bf16*)(wsb + wl.dh_off), b->d_in, 2 * bi.max_rpad, doff, dseg,
+                      (const int32_t*)(dev + o_wa), acc ? 1 : 0};
+        if ((st = launch_grad<false>(h, gp, (int)want_a.size(), grad_max_rpad, s)) != SYMB_OK) return st;
+    }
+    if (!want_l.empty()) {
+        Ia3GradParams ip{(const bf16*)dY, (const bf16*)Ybase, b->d_out, doff, dseg, (const int32_t*)(dev + o_wl), acc ? 1 : 0};
+        hipLaunchKernelGGL(symb_ia3_grad_kernel, dim3((b->d_out + 255) / 256, (unsigned)want_l.size()), dim3(256), 0, s, ip);
+        SYMB_HIP(h, hipGetLastError());
+    }
+    return seal_slot(h, s);
+}
+
+}  // extern "C"

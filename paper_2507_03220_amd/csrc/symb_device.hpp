@@ -1,0 +1,50 @@
+// Device-side types shared by the HIP kernels of the segmented base+adapter layer.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace symb {
+
+typedef __bf16 bf16;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short shortx4;
+
+enum : int32_t { KIND_NONE = 0, KIND_LORA = 1, KIND_IA3 = 2, KIND_IA3_IN = 3 };
+
+// Per-segment descriptor as the kernels see it (device memory, one per segment).
+struct SegDesc {
+    int32_t kind;
+    int32_t rank;      // LoRA rank r_i (0 otherwise)
+    int32_t rpad;      // r_i rounded up to a multiple of 16 (MFMA K granularity)
+    float scale;       // s_i
+    const bf16* A;     // LoRA A [r][d_in] / IA3 l[d_out]
+    const bf16* B;     // LoRA B [d_out][r]
+    float* dA;         // fp32 grads (may be null)
+    float* dB;
+};
+
+// Round-to-nearest-even fp32 -> bf16 (finite inputs; NaN stays NaN).
+__device__ __forceinline__ unsigned short f32_to_bf16_bits(float f) {
+    unsigned int u = __builtin_bit_cast(unsigned int, f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+__device__ __forceinline__ float bf16_bits_to_f32(unsigned short b) {
+    return __builtin_bit_cast(float, ((unsigned int)b) << 16);
+}
+__device__ __forceinline__ unsigned int pack2_bf16(float lo, float hi) {
+    return (unsigned int)f32_to_bf16_bits(lo) | ((unsigned int)f32_to_bf16_bits(hi) << 16);
+}
+
+// Segment of row t among segments [lo, hi]: off[i] <= t < off[i+1].  Empty segments never match.
+__device__ __forceinline__ int seg_of_row(const int32_t* __restrict__ off, int lo, int hi, int t) {
+    int s = lo;
+    while (s < hi && t >= off[s + 1]) ++s;
+    return s;
+}
+
+}  // namespace symb

@@ -66,13 +66,32 @@ def max_abs_over_rms(got: np.ndarray, ref: np.ndarray) -> float:
     return err / rms if rms > 0 else err
 
 
-# Parity bar (relative Frobenius error, max-abs error on outputs scaled to unit RMS).
+# Parity bar: relative Frobenius error per tensor, and max-abs error measured on the
+# tensor scaled to unit RMS.  A bf16 OUTPUT cannot be closer to the exact value than half
+# an ulp of its own format, which is up to 2^-8 of the element's magnitude, so for tensors
+# the library must deliver in bf16 that unavoidable quantisation term is added per element;
+# fp32 outputs (parameter gradients) get the bare bound.
 REL_FRO_TOL = 4e-3
 MAX_ABS_TOL = 2e-2
+BF16_HALF_ULP = 2.0 ** -8
 
 
-def assert_close(got, ref, what=""):
-    rf, ma = rel_fro(got, ref), max_abs_over_rms(got, ref)
+def max_abs_excess(got: np.ndarray, ref: np.ndarray, out_bf16: bool) -> float:
+    """max over elements of |err| / allowed, allowed = MAX_ABS_TOL*RMS (+ 2^-8 |ref| for bf16 outputs)."""
+    ref = ref.astype(np.float64)
+    if ref.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    allowed = MAX_ABS_TOL * rms + (BF16_HALF_ULP * np.abs(ref) if out_bf16 else 0.0)
+    err = np.abs(got.astype(np.float64) - ref)
+    if rms == 0.0:
+        return 0.0 if not err.any() else float("inf")
+    return float(np.max(err / allowed))
+
+
+def assert_close(got, ref, what="", out_bf16=False):
+    rf, ex = rel_fro(got, ref), max_abs_excess(got, ref, out_bf16)
     assert rf <= REL_FRO_TOL, f"{what}: relative Frobenius error {rf:.3e} > {REL_FRO_TOL}"
-    assert ma <= MAX_ABS_TOL, f"{what}: max-abs/RMS error {ma:.3e} > {MAX_ABS_TOL}"
-    return rf, ma
+    assert ex <= 1.0, f"{what}: max-abs error is {ex:.3f} x the allowed {MAX_ABS_TOL} * RMS" + \
+        (" + bf16 half-ulp" if out_bf16 else "")
+    return rf, ex * MAX_ABS_TOL

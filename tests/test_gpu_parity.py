@@ -1,0 +1,253 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the
+same seeded bf16 bit patterns.  Sizes here let the oracle compute every element in
+seconds while still spanning several tiles, ragged tails, segment-straddling tiles,
+empty and one-token segments, odd ranks and every adapter kind.
+
+Bar: relative Frobenius error <= 4e-3 and max-abs error <= 2e-2 after scaling the
+oracle tensor to unit RMS (plus, for tensors delivered in bf16, the half-ulp of bf16 at
+the element's magnitude), per tensor (per segment for parameter gradients); integer
+work (row->segment map, adapter selection) bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from helpers import assert_close, bits_of
+
+pytestmark = pytest.mark.gpu
+
+gh = None
+sb = None
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    global gh, sb
+    import gpu_harness
+    from paper_2507_03220_amd import binding
+    gh, sb = gpu_harness, binding
+    binding.lib()          # fail loudly if the HIP library is not built
+    yield
+    torch.cuda.synchronize()
+
+
+def make_problem(seed, d_in, d_out, lens, kinds, ranks, bias=True, scales=None):
+    rng = np.random.default_rng(seed)
+    S = len(lens)
+    off = np.zeros(S + 1, dtype=np.int32)
+    off[1:] = np.cumsum(lens)
+    T = int(off[-1])
+    nb = lambda shape, std, mean=0.0: synth.f32_to_bf16_bits(
+        (mean + std * rng.standard_normal(shape)).astype(np.float32))
+    ads = []
+    for i in range(S):
+        k = kinds[i % len(kinds)]
+        if k == oracle.LORA:
+            r = ranks[i % len(ranks)]
+            s = scales[i % len(scales)] if scales else 16.0 / r
+            ads.append(gh.HostAdapter(k, r, s, nb((r, d_in), d_in ** -0.5), nb((d_out, r), r ** -0.5)))
+        elif k == oracle.IA3:
+            ads.append(gh.HostAdapter(k, 0, 0.0, nb((d_out,), 0.1, 1.0)))
+        else:
+            ads.append(gh.HostAdapter())
+    return dict(off=off, T=T, d_in=d_in, d_out=d_out, ads=ads,
+                X=nb((T, d_in), 1.0), W=nb((d_out, d_in), d_in ** -0.5), dY=nb((T, d_out), 1.0),
+                bias=nb((d_out,), 0.5) if bias else None)
+
+
+def oracle_ads(ads):
+    return [oracle.Adapter(a.kind, a.rank, a.scale, a.A, a.B) for a in ads]
+
+
+def check_all(p, tag):
+    oads = oracle_ads(p["ads"])
+    off = p["off"]
+    # forward
+    Y, Yb = gh.forward(off, p["ads"], p["X"], p["W"], p["bias"], want_base=True)
+    Y0r, Yr = oracle.forward(off, oads, p["X"], p["W"], p["bias"])
+    if p["T"]:
+        assert_close(gh.bf16_to_f64(Y), Yr, f"{tag} Y", out_bf16=True)
+        assert_close(gh.bf16_to_f64(Yb), Y0r, f"{tag} Ybase", out_bf16=True)
+    # backward, both flavours
+    for base_only in (False, True):
+        dX = gh.backward_input(off, p["ads"], p["dY"], p["W"], base_only=base_only)
+        dXr = oracle.backward_input(off, oads, p["dY"], p["W"], base_only=base_only)
+        if p["T"]:
+            assert_close(gh.bf16_to_f64(dX), dXr, f"{tag} dX base_only={base_only}", out_bf16=True)
+    # adapter gradients.  The saved base output a client feeds back is a bf16 tensor: both sides
+    # get the same one, the oracle's Y0 rounded to bf16 here (never the GPU's own output).
+    Y0_saved = synth.f32_to_bf16_bits(Y0r.astype(np.float32))
+    dev = gh.adapter_grad(off, p["ads"], p["X"], p["dY"], Y0_saved, p["d_in"], p["d_out"])
+    for i, a in enumerate(p["ads"]):
+        d = dev.descs[i]
+        empty = off[i + 1] == off[i]
+        if a.kind == oracle.LORA:
+            dAr, dBr = oracle.lora_grad(off, oads, p["X"], p["dY"], i)
+            dA, dB = d.dA.cpu().numpy(), d.dB.cpu().numpy()
+            if empty:
+                assert not dA.any() and not dB.any(), f"{tag} empty segment {i} must give zero grads"
+            else:
+                assert_close(dA, dAr, f"{tag} dA[{i}]")
+                assert_close(dB, dBr, f"{tag} dB[{i}]")
+        elif a.kind == oracle.IA3:
+            dlr = oracle.ia3_grad(off, oads, p["X"], p["dY"], p["W"], p["bias"], i, Y0_saved=Y0_saved)
+            dl = d.dA.cpu().numpy()
+            if empty:
+                assert not dl.any()
+            else:
+                assert_close(dl, dlr, f"{tag} dl[{i}]")
+    return Y, Yb
+
+
+L, I, N = oracle.LORA, oracle.IA3, oracle.NONE
+
+
+def test_cfg1_tiny_full():
+    wl = synth.cfg1_tiny()
+    pr = wl.projections[0]
+    ads = []
+    for c in wl.clients:
+        t = synth.make_adapter(wl, pr, c)
+        ads.append(gh.HostAdapter(t.kind, t.rank, t.scale, t.A, t.B))
+    p = dict(off=wl.offsets, T=wl.T, d_in=pr.d_in, d_out=pr.d_out, ads=ads, X=synth.make_X(wl, pr),
+             W=synth.make_W(wl, pr), dY=synth.make_dY(wl, pr, wl.T), bias=None)
+    check_all(p, "cfg1")
+
+
+@pytest.mark.parametrize("case", [
+    # several 128-row tiles, ragged tail, tiles that straddle segments, an empty and two 1-token segments
+    dict(seed=1, d_in=320, d_out=264, lens=[130, 1, 0, 77, 1, 300, 64], kinds=[L, I, L, N, L, L, I], ranks=[8, 16, 5, 24, 33]),
+    # wide enough for the 256x256 variant (>= 128 big tiles): M 1500 (ragged), N 6200/K 136
+    dict(seed=2, d_in=136, d_out=6208, lens=[700, 5, 795], kinds=[L, I, L], ranks=[16, 8]),
+    dict(seed=3, d_in=6208, d_out=136, lens=[700, 5, 795], kinds=[L, I, L], ranks=[16, 8]),
+    # all kinds NONE: the paper's plain executor
+    dict(seed=4, d_in=256, d_out=512, lens=[100, 156], kinds=[N], ranks=[1]),
+    # rank 1, rank 128 (max), rank 100, K tail (d_in not a multiple of 64)
+    dict(seed=5, d_in=200, d_out=392, lens=[40, 90, 33], kinds=[L], ranks=[1, 128, 100], bias=False),
+    # single segment, single token
+    dict(seed=6, d_in=64, d_out=64, lens=[1], kinds=[L], ranks=[8]),
+    dict(seed=7, d_in=72, d_out=40, lens=[1], kinds=[I], ranks=[1]),
+    # many decode rows interleaved with long segments
+    dict(seed=8, d_in=512, d_out=384, lens=[1, 1, 200, 1, 1, 1, 90, 1, 257, 1, 1], kinds=[L, I, L, L, I, N, I, L, L, I, L], ranks=[4, 64, 16, 8, 32, 128]),
+])
+def test_mixed_batches_full(case):
+    c = dict(case)
+    p = make_problem(c.pop("seed"), c.pop("d_in"), c.pop("d_out"), c.pop("lens"), c.pop("kinds"), c.pop("ranks"), **c)
+    check_all(p, f"case{case['seed']}")
+
+
+def test_empty_batch_and_all_empty_segments():
+    p = make_problem(9, 64, 64, [0, 0], [L, I], [8])
+    check_all(p, "all-empty")
+
+
+def test_index_probe_bit_exact():
+    """Adapter selection per row, read back through exactly representable values."""
+    lens = [3, 0, 1, 130, 1, 1, 0, 260, 2, 129]
+    S = len(lens)
+    off = np.zeros(S + 1, dtype=np.int32)
+    off[1:] = np.cumsum(lens)
+    T, d_in, d_out = int(off[-1]), 64, 256
+    Xf = np.zeros((T, d_in), np.float32); Xf[:, 0] = 1
+    W = bits_of(np.zeros((d_out, d_in)))
+    ads, oads = [], []
+    for i in range(S):
+        Af = np.zeros((2, d_in), np.float32); Af[0, 0] = 1
+        Bf = np.zeros((d_out, 2), np.float32); Bf[:, 0] = i + 1
+        ads.append(gh.HostAdapter(L, 2, 1.0, bits_of(Af), bits_of(Bf)))
+    Y, _ = gh.forward(off, ads, bits_of(Xf), W, None, want_base=False)
+    _, Yr = oracle.forward(off, oracle_ads(ads), bits_of(Xf), W)
+    got = gh.bf16_to_f64(Y)
+    np.testing.assert_array_equal(got, Yr)
+    np.testing.assert_array_equal(got[:, 0].astype(np.int32) - 1, oracle.row_segment_map(off))
+    batch = sb.Batch(d_in, d_out, off, [sb.Adapter() for _ in range(S)])
+    np.testing.assert_array_equal(sb.symb_debug_row_segment_map(batch), oracle.row_segment_map(off))
+
+
+def test_stateless_and_deterministic():
+    p = make_problem(10, 320, 264, [130, 77, 300], [L, I, L], [8, 16])
+    a = [gh.bf16_bits(t) for t in gh.forward(p["off"], p["ads"], p["X"], p["W"], p["bias"])]
+    gh.backward_input(p["off"], p["ads"], p["dY"], p["W"])          # unrelated call in between
+    q = make_problem(11, 64, 72, [5], [L], [4])
+    gh.forward(q["off"], q["ads"], q["X"], q["W"], q["bias"])
+    b = [gh.bf16_bits(t) for t in gh.forward(p["off"], p["ads"], p["X"], p["W"], p["bias"])]
+    np.testing.assert_array_equal(a[0], b[0])
+    np.testing.assert_array_equal(a[1], b[1])
+    g1 = gh.adapter_grad(p["off"], p["ads"], p["X"], p["dY"], torch.from_numpy(a[1].view(np.int16)).view(torch.bfloat16).cuda())
+    g2 = gh.adapter_grad(p["off"], p["ads"], p["X"], p["dY"], torch.from_numpy(a[1].view(np.int16)).view(torch.bfloat16).cuda())
+    for d1, d2 in zip(g1.descs, g2.descs):
+        if d1.dA is not None:
+            assert torch.equal(d1.dA, d2.dA)
+        if d1.dB is not None:
+            assert torch.equal(d1.dB, d2.dB)
+
+
+def test_backward_batch_is_independent_of_forward_batch():
+    """Backward on a regrouped subset of the forward clients gives the same rows (bitwise)."""
+    p = make_problem(12, 264, 320, [130, 1, 77, 300], [L, I, L, N], [8, 16])
+    off = p["off"]
+    dX = gh.bf16_bits(gh.backward_input(off, p["ads"], p["dY"], p["W"]))
+    order = [2, 0]
+    idx = np.concatenate([np.arange(off[i], off[i + 1]) for i in order])
+    noff = np.zeros(len(order) + 1, dtype=np.int32)
+    noff[1:] = np.cumsum([off[i + 1] - off[i] for i in order])
+    sub = gh.bf16_bits(gh.backward_input(noff, [p["ads"][i] for i in order], np.ascontiguousarray(p["dY"][idx]), p["W"]))
+    np.testing.assert_array_equal(sub, dX[idx])
+
+
+def test_gradient_accumulate_adds():
+    p = make_problem(13, 136, 264, [90, 33], [L, I], [8])
+    _, Yb = gh.forward(p["off"], p["ads"], p["X"], p["W"], p["bias"])
+    g = gh.adapter_grad(p["off"], p["ads"], p["X"], p["dY"], Yb)
+    once = [(d.dA.clone() if d.dA is not None else None, d.dB.clone() if d.dB is not None else None) for d in g.descs]
+    gh.adapter_grad(p["off"], p["ads"], p["X"], p["dY"], Yb, accumulate_into=g)
+    for (a1, b1), d in zip(once, g.descs):
+        if a1 is not None:
+            assert torch.equal(d.dA, a1 + a1)
+        if b1 is not None:
+            assert torch.equal(d.dB, b1 + b1)
+
+
+def test_inference_segments_get_no_gradient_work():
+    p = make_problem(14, 136, 264, [50, 3, 40], [L, L, I], [8])
+    p["ads"][1].want_grad = False
+    _, Yb = gh.forward(p["off"], p["ads"], p["X"], p["W"], p["bias"])
+    g = gh.adapter_grad(p["off"], p["ads"], p["X"], p["dY"], Yb)
+    assert g.descs[1].dA is None and g.descs[1].dB is None
+    dAr, dBr = oracle.lora_grad(p["off"], oracle_ads(p["ads"]), p["X"], p["dY"], 0)
+    assert_close(g.descs[0].dA.cpu().numpy(), dAr, "dA[0]")
+    assert_close(g.descs[0].dB.cpu().numpy(), dBr, "dB[0]")
+
+
+def test_errors_enqueue_nothing_and_leave_handle_usable():
+    p = make_problem(15, 64, 72, [5, 6], [L, I], [4])
+    dev = gh.upload_adapters(p["ads"], 64, 72, grads=True)
+    X, W, dYd = gh.to_dev(p["X"]), gh.to_dev(p["W"]), gh.to_dev(p["dY"])
+    Y = torch.full((11, 72), 7.0, device="cuda", dtype=torch.bfloat16)
+    h = gh.handle()
+    good = sb.Batch(64, 72, p["off"], dev.descs)
+    ws = gh.workspace(good, sb.SYMB_OP_FWD)
+
+    def expect(status, fn):
+        with pytest.raises(sb.SymbError) as e:
+            fn()
+        assert e.value.status == status, str(e.value)
+        torch.cuda.synchronize()
+        assert bool((Y == 7.0).all()), "a failing call must leave the output untouched"
+
+    bad_off = sb.Batch(64, 72, [0, 6, 5], dev.descs)
+    expect(sb.SYMB_ERR_BAD_SEGMENTS, lambda: sb.symb_base_linear_fwd(h, bad_off, X, W, None, Y, None, ws))
+    expect(sb.SYMB_ERR_INVALID_ARG, lambda: sb.symb_base_linear_fwd(h, good, None, W, None, Y, None, ws))
+    expect(sb.SYMB_ERR_WORKSPACE_TOO_SMALL, lambda: sb.symb_base_linear_fwd(h, good, X, W, None, Y, None, None))
+    expect(sb.SYMB_ERR_INVALID_ARG, lambda: sb.symb_base_linear_bwd_input(h, good, dYd, W, Y, 5, None))
+    expect(sb.SYMB_ERR_INVALID_ARG,            # IA3 segment wants dl but no Ybase given
+           lambda: sb.symb_adapter_grad(h, good, X, dYd, None, sb.SYMB_GRAD_OVERWRITE, gh.workspace(good, sb.SYMB_OP_ADAPTER_GRAD)))
+    ia3_in = sb.Batch(64, 72, [0, 11], [sb.Adapter(sb.SYMB_ADAPTER_IA3_IN, 0, 0.0, dev.descs[1].A)])
+    expect(sb.SYMB_ERR_UNSUPPORTED, lambda: sb.symb_base_linear_fwd(h, ia3_in, X, W, None, Y, None, None))
+    # the handle still works
+    sb.symb_base_linear_fwd(h, good, X, W, None, Y, None, ws)
+    torch.cuda.synchronize()
+    _, Yr = oracle.forward(p["off"], oracle_ads(p["ads"]), p["X"], p["W"])
+    assert_close(gh.bf16_to_f64(Y), Yr, "Y after failed calls", out_bf16=True)

@@ -1,0 +1,129 @@
+"""Host-side checks of libsymb.so that need no GPU: every declared symbol is exported,
+argument validation, the segment planner and the row->segment map (bit-exact against
+the oracle's map).  No compute entry point is called here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2507_03220_amd import binding as sb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    from paper_2507_03220_amd import build
+    build.build(force=False)
+
+
+def _declared_symbols():
+    text = ""
+    inc = os.path.join(ROOT, "include")
+    for f in sorted(os.listdir(inc)):
+        if f.endswith(".h"):
+            text += open(os.path.join(inc, f)).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(symb_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_symbols()
+    assert set(names) == set(sb.EXPORTS), names
+    l = sb.lib()
+    for n in names:
+        assert getattr(l, n) is not None
+
+
+def test_status_strings():
+    l = sb.lib()
+    assert l.symb_status_string(0) == b"SYMB_OK"
+    assert l.symb_status_string(2) == b"SYMB_ERR_BAD_SEGMENTS"
+
+
+def _batch(off, ads=None, d_in=64, d_out=64):
+    ads = ads if ads is not None else [sb.Adapter() for _ in range(len(off) - 1)]
+    return sb.Batch(d_in, d_out, off, ads)
+
+
+def test_validation_rejects_bad_batches():
+    assert sb.symb_validate_batch(_batch([0, 4, 9])) == sb.SYMB_OK
+    assert sb.symb_validate_batch(_batch([0, 0, 0])) == sb.SYMB_OK          # empty segments are legal
+    assert sb.symb_validate_batch(_batch([0])) == sb.SYMB_OK                # no segments at all
+    assert sb.symb_validate_batch(_batch([1, 4])) == sb.SYMB_ERR_BAD_SEGMENTS
+    assert sb.symb_validate_batch(_batch([0, 5, 3])) == sb.SYMB_ERR_BAD_SEGMENTS
+    assert sb.symb_validate_batch(_batch([0, 4], d_in=0)) == sb.SYMB_ERR_INVALID_ARG
+    assert sb.symb_validate_batch(_batch([0, 4], d_out=12)) == sb.SYMB_ERR_INVALID_ARG   # not a multiple of 8
+    fake = 0x1000  # an aligned, never dereferenced address: validation is host-only
+    lora = lambda **kw: sb.Adapter(**{**dict(kind=sb.SYMB_ADAPTER_LORA, rank=8, scale=2.0, A=fake, B=fake), **kw})
+    assert sb.symb_validate_batch(_batch([0, 4], [lora()])) == sb.SYMB_OK
+    assert sb.symb_validate_batch(_batch([0, 4], [lora(rank=0)])) == sb.SYMB_ERR_INVALID_ARG
+    assert sb.symb_validate_batch(_batch([0, 4], [lora(A=None)])) == sb.SYMB_ERR_INVALID_ARG
+    assert sb.symb_validate_batch(_batch([0, 4], [lora(B=None)])) == sb.SYMB_ERR_INVALID_ARG
+    assert sb.symb_validate_batch(_batch([0, 4], [lora(A=fake + 2)])) == sb.SYMB_ERR_INVALID_ARG
+    assert sb.symb_validate_batch(_batch([0, 4], [lora(rank=sb.SYMB_MAX_RANK + 1)])) == sb.SYMB_ERR_UNSUPPORTED
+    assert sb.symb_validate_batch(_batch([0, 4], [lora(rank=5, B=fake + 2)])) == sb.SYMB_OK   # odd rank: 2-byte B
+    assert sb.symb_validate_batch(_batch([0, 4], [sb.Adapter(kind=7)])) == sb.SYMB_ERR_INVALID_ARG
+    assert sb.symb_validate_batch(_batch([0, 4], [sb.Adapter(kind=sb.SYMB_ADAPTER_IA3)])) == sb.SYMB_ERR_INVALID_ARG
+    assert sb.symb_validate_batch(_batch([0, 4], [sb.Adapter(kind=sb.SYMB_ADAPTER_IA3, A=fake)])) == sb.SYMB_OK
+    assert sb.symb_validate_batch(_batch([0, 4], [sb.Adapter(kind=sb.SYMB_ADAPTER_IA3_IN, A=fake)])) == sb.SYMB_ERR_UNSUPPORTED
+    assert b"IA3 input scaling" in sb.lib().symb_last_error(None)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_row_segment_map_is_bit_exact_vs_oracle(seed):
+    rng = np.random.default_rng(seed)
+    S = int(rng.integers(1, 70))
+    lens = rng.choice([0, 1, 1, 2, 3, 17, 64, 255, 256, 257, 1000], size=S)
+    off = np.zeros(S + 1, dtype=np.int32)
+    off[1:] = np.cumsum(lens)
+    got = sb.symb_debug_row_segment_map(_batch(off))
+    np.testing.assert_array_equal(got, oracle.row_segment_map(off))
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("tile_m", [16, 128, 256])
+def test_row_tile_plan_matches_oracle_map(seed, tile_m):
+    rng = np.random.default_rng(100 + seed)
+    S = int(rng.integers(1, 70))
+    lens = rng.choice([0, 0, 1, 1, 2, 3, 17, 64, 255, 256, 257, 1000], size=S)
+    off = np.zeros(S + 1, dtype=np.int32)
+    off[1:] = np.cumsum(lens)
+    lo, hi = sb.symb_plan_row_tiles(_batch(off), tile_m)
+    seg = oracle.row_segment_map(off)
+    T = int(off[-1])
+    assert len(lo) == (T + tile_m - 1) // tile_m
+    for u in range(len(lo)):
+        rows = seg[u * tile_m:min(T, (u + 1) * tile_m)]
+        assert lo[u] == rows.min() and hi[u] == rows.max()
+
+
+def test_workspace_bytes_formula():
+    fake = 0x1000
+    ads = [sb.Adapter(sb.SYMB_ADAPTER_LORA, 5, 1.0, fake, fake, fake, fake), sb.Adapter(),
+           sb.Adapter(sb.SYMB_ADAPTER_IA3, 0, 0.0, fake), sb.Adapter(sb.SYMB_ADAPTER_LORA, 40, 1.0, fake, fake)]
+    b = sb.Batch(64, 128, [0, 10, 20, 30, 100], ads)
+    T, rp = 100, 2 * 48                               # pitch = 2 * (max rank rounded up to 16)
+    up = lambda n: (n + 255) // 256 * 256
+    packed = (16 + 48) * 128 * 2
+    assert sb.symb_workspace_bytes(b, sb.SYMB_OP_FWD) == up(T * rp * 2)
+    assert sb.symb_workspace_bytes(b, sb.SYMB_OP_BWD_INPUT) == up(T * rp * 2) + up(packed) + up(T * 128 * 2)
+    assert sb.symb_workspace_bytes(b, sb.SYMB_OP_ADAPTER_GRAD) == 2 * up(T * rp * 2) + up(packed)
+    none = sb.Batch(64, 128, [0, 100], [sb.Adapter()])
+    for op in (sb.SYMB_OP_FWD, sb.SYMB_OP_BWD_INPUT, sb.SYMB_OP_ADAPTER_GRAD):
+        assert sb.symb_workspace_bytes(none, op) == 0
+
+
+def test_compute_entry_points_fail_cleanly_without_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(sb.SymbError) as e:
+        sb.symb_create(0)
+    assert e.value.status == sb.SYMB_ERR_DEVICE
+    with pytest.raises(sb.SymbError) as e:
+        sb.symb_base_linear_fwd(None, _batch([0, 4]), 0x1000, 0x1000, None, 0x1000)
+    assert e.value.status == sb.SYMB_ERR_INVALID_ARG      # null handle, nothing launched

@@ -378,3 +378,28 @@ def test_cfg1_moments():
     dY = synth.make_dY(wl, pr, wl.T)
     dXb = oracle.backward_input(wl.offsets, ads, dY, W, base_only=True)
     assert abs(np.var(dXb) - pr.d_out / pr.d_in) < 0.05
+
+
+# ---------------------------------------------------------------------------
+# IA3 gradient from the client's saved bf16 base output (Sec. 3.2: fine-tuning clients
+# save the layer output for backward; Sec. 4: 16-bit).
+# ---------------------------------------------------------------------------
+def test_ia3_grad_from_saved_output():
+    rng = np.random.default_rng(33)
+    d_in, d_out = 3, 4
+    off = np.array([0, 2, 7], dtype=np.int32)
+    pick = lambda shape: bits_of(rng.choice([-1.0, -0.5, 0.0, 0.5, 1.0], size=shape))
+    X, W, b, dY = pick((7, d_in)), pick((d_out, d_in)), pick((d_out,)), grid_bits(rng, (7, d_out))
+    ads = [oracle.Adapter(oracle.LORA, 1, 1.0, pick((1, d_in)), pick((d_out, 1))),
+           oracle.Adapter(oracle.IA3, 0, 0.0, grid_bits(rng, (d_out,)))]
+    Y0, _ = oracle.forward(off, ads, X, W, b)
+    # here every Y0 is a small multiple of 1/4, hence exact in bf16: both routes must agree exactly
+    saved = bits_of(Y0)
+    np.testing.assert_array_equal(oracle.ia3_grad(off, ads, X, dY, W, b, 1, Y0_saved=saved),
+                                  oracle.ia3_grad(off, ads, X, dY, W, b, 1))
+    # and with an arbitrary saved tensor the sum is over exactly that tensor (exact rationals)
+    other = grid_bits(rng, (7, d_out))
+    got = oracle.ia3_grad(off, ads, X, dY, W, b, 1, cols=[3, 1], Y0_saved=other)
+    for q, j in enumerate([3, 1]):
+        ref = sum(Fraction(float(f64(dY)[t, j])) * Fraction(float(f64(other)[t, j])) for t in range(2, 7))
+        assert got[q] == float(ref)
