@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the segmented base+adapter layer on one MI355X.
+
+A step = one pass of the whole hot path over one synthetic batch: for every projection
+of the layer shape, forward (shrink + fused GEMM), input gradient (dH + fused GEMM) and
+adapter gradients (dA, dB, dl), all through the C ABI.  Inputs are resident in HBM before
+the timed region.  Default workload: the Gemma2-27B-shaped layer with 20 LoRA clients x
+1024 tokens (T = 20480), ranks from {8, 16}.
+
+Prints ONE JSON line (see README/DESIGN for the fields).  Run with --gpus 1 only.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak (256 CU x 4096 flop/clk x 2.4 GHz)
+HBM_PEAK_GBS = 8000.0
+
+
+def build_layer(cfg: str, handle):
+    import numpy as np
+    import synth
+    from paper_2507_03220_amd import binding as sb
+    from paper_2507_03220_amd.layer import ProjectionRun, SegmentSpec
+
+    wl = synth.CONFIGS[cfg]()
+    runs = []
+    t0 = time.time()
+    for pr in wl.projections:
+        segs = []
+        for c in wl.clients:
+            a = synth.make_adapter(wl, pr, c)
+            segs.append(SegmentSpec(c.n_tokens, a.kind, a.rank, a.scale, a.A, a.B, c.finetune))
+        Tb = sum(c.n_tokens for c in wl.clients if c.finetune)
+        run = ProjectionRun(handle, pr.name, pr.d_in, pr.d_out, segs, synth.make_W(wl, pr), synth.make_X(wl, pr),
+                            synth.make_dY(wl, pr, Tb))
+        runs.append(run)
+    return wl, runs, time.time() - t0
+
+
+def step(runs, stream):
+    for r in runs:
+        r.fwd(stream)
+    for r in runs:
+        r.bwd_input(stream)
+        r.adapter_grad(stream)
+
+
+def cpu_baseline(cfg: str, budget_s: float = 20.0) -> dict:
+    """Times the fp64 oracle, as it stands, on a bounded sample of the same workload:
+    forward and input-gradient rows of the widest projection plus full LoRA gradients of
+    one client on the narrowest one; reports algorithmic TFLOP/s of that sample."""
+    import numpy as np
+    import oracle
+    import synth
+
+    wl = synth.CONFIGS[cfg]()
+    pr = max(wl.projections, key=lambda p: p.d_in * p.d_out)
+    clients = wl.clients
+    off = wl.offsets
+    # sample: rows of the first two non-empty segments only, so only those rows are generated
+    keep = [i for i, c in enumerate(clients) if c.n_tokens > 0][:2]
+    sub_clients = [clients[i] for i in keep]
+    sub_off = synth.offsets_of(sub_clients)
+    Ts = int(sub_off[-1])
+    ads = []
+    for c in sub_clients:
+        a = synth.make_adapter(wl, pr, c)
+        ads.append(oracle.Adapter(a.kind, a.rank, a.scale, a.A, a.B))
+    W = synth.make_W(wl, pr)
+    X = synth.normal_bf16((Ts, pr.d_in), 1.0, "cpu_baseline/X")
+    dY = synth.normal_bf16((Ts, pr.d_out), 1.0, "cpu_baseline/dY")
+    per_row = 2.0 * pr.d_in * pr.d_out
+    nthreads = oracle.num_threads()
+    # calibrate with one row per thread, then size the sample to the budget
+    rows = np.arange(min(nthreads, Ts), dtype=np.int32)
+    t0 = time.time(); oracle.forward(sub_off, ads, X, W, None, rows=rows); t_cal = time.time() - t0
+    n = int(max(nthreads, min(Ts, (budget_s / 2.2) / max(t_cal, 1e-3) * len(rows))))
+    n = (n // nthreads) * nthreads or nthreads
+    rows = np.linspace(0, Ts - 1, n).astype(np.int32)
+    t0 = time.time(); oracle.forward(sub_off, ads, X, W, None, rows=rows); t_f = time.time() - t0
+    t0 = time.time(); oracle.backward_input(sub_off, ads, dY, W, rows=rows); t_b = time.time() - t0
+    flops = 2 * n * per_row
+    t_g, g_flops = 0.0, 0.0
+    if ads[0].kind == oracle.LORA:
+        # LoRA gradients of one client on a bounded token count
+        ng = min(int(sub_off[1]), 256)
+        goff = np.array([0, ng], dtype=np.int32)
+        t0 = time.time(); oracle.lora_grad(goff, ads[:1], X[:ng], dY[:ng], 0); t_g = time.time() - t0
+        g_flops = 4.0 * ng * ads[0].rank * (pr.d_in + pr.d_out) * 1.5   # dA, dB plus recomputed H and dH
+    total_t = t_f + t_b + t_g
+    return {"value": (flops + g_flops) / total_t / 1e12, "unit": "TFLOP/s", "cores": nthreads, "kind": "oracle",
+            "sample": f"{cfg} projection {pr.name} ({pr.d_in}->{pr.d_out}): {n} rows forward ({t_f:.1f}s) + {n} rows "
+                      f"input gradient ({t_b:.1f}s)" + (f" + LoRA gradients of one client over {ng} tokens ({t_g:.1f}s)" if t_g else ""),
+            "seconds": total_t}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=20.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2507_03220_amd import binding as sb
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    sb.lib()
+    torch.cuda.set_device(0)
+    h = sb.symb_create(0)
+    wl, runs, t_gen = build_layer(args.config, h)
+    stream_obj = torch.cuda.current_stream()
+    stream = stream_obj.cuda_stream
+    print(f"[bench] {wl.name}: T={wl.T} S={len(wl.clients)} projections={[r.name for r in runs]} "
+          f"inputs generated+uploaded in {t_gen:.1f}s", file=sys.stderr, flush=True)
+
+    for r in runs:          # one untimed pass materialises saved outputs where IA3 gradients need them
+        r.fwd(stream)
+        r.sync_saved_output()
+    for _ in range(args.warmup):
+        step(runs, stream)
+    torch.cuda.synchronize()
+
+    sb.symb_debug_gemm_timing_enable(h, True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record(stream_obj)
+    for _ in range(args.steps):
+        step(runs, stream)
+    e1.record(stream_obj)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = wall_ms / args.steps
+
+    fl = {k: sum(r.flops()[k] for r in runs) for k in runs[0].flops()}
+    tflops = fl["total"] / (ms_per_step * 1e-3) / 1e12
+    tokens = wl.T
+    timing = [sb.symb_debug_gemm_timing_read(h, v) for v in (0, 1)]
+    sb.symb_debug_gemm_timing_enable(h, False)
+    dom = 0 if timing[0][0] >= timing[1][0] else 1
+    ms_tot, n_launch, fl_tot = timing[dom]
+    avg_ms = ms_tot / max(n_launch, 1)
+    achieved = (fl_tot / max(n_launch, 1)) / (avg_ms * 1e-3) / 1e12 if n_launch else 0.0
+    gemm_ms_per_step = (timing[0][0] + timing[1][0]) / args.steps
+    out = {
+        "metric": "fwd+bwd base+adapter layer TFLOP/s",
+        "value": round(tflops, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {len(wl.clients)} clients, T={wl.T} tokens, "
+                               f"projections {','.join(f'{r.name}:{r.d_in}->{r.d_out}' for r in runs)}; "
+                               "fwd + dX + adapter grads per projection",
+                   "tokens": tokens, "clients": len(wl.clients)},
+        "mfma_util": round(tflops / BF16_MFMA_PEAK_TFLOPS, 4),
+        "token_layers_per_s": round(tokens / (ms_per_step * 1e-3), 1),
+        "model_equiv_tokens_per_s": round(tokens / (ms_per_step * 1e-3) / 46.0, 1) if args.config == "cfg4" else None,
+        "event_ms_per_step": round(ev_ms / args.steps, 4),
+        "gemm_ms_per_step": round(gemm_ms_per_step, 4),
+        "algorithmic_tflop_per_step": round(fl["total"] / 1e12, 4),
+        "roofline": {
+            "bound": "mfma",
+            "kernel": "symb_gemm_kernel<256,256,2,4,%s>" % ("true" if dom else "false"),
+            "achieved": round(achieved, 2),
+            "peak": BF16_MFMA_PEAK_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4),
+            "avg_launch_ms": round(avg_ms, 4),
+            "launches": n_launch,
+            "traffic": None,
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config, args.cpu_budget)
+        out["cpu_baseline"]["value"] = float("%.3g" % out["cpu_baseline"]["value"])
+        out["cpu_baseline"]["seconds"] = round(out["cpu_baseline"]["seconds"], 1)
+    print(json.dumps(out), flush=True)
+    sb.symb_destroy(h)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

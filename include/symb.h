@@ -162,6 +162,20 @@ symb_status symb_adapter_grad(symb_handle h, const symb_batch* b, const void* X,
                               const void* Ybase, uint32_t flags, void* ws, size_t ws_bytes,
                               void* stream);
 
+/*
+ * Measurement hook (not part of the method): while enabled, every launch of the base
+ * GEMM kernel is bracketed by a pair of HIP events on the caller's stream, so a bench
+ * can read that kernel's own duration inside its timed region.  `variant` 0 = forward
+ * kernel (W read K-contiguous), 1 = input-gradient kernel (W read N-contiguous).
+ * read synchronises on the recorded events and returns the totals since the last
+ * enable call (which clears them).  At most 4096 launches are recorded after an
+ * enable; later ones are not timed.  `flops_total` is the algorithmic work of those launches
+ * (2*M*N*K plus the fused LoRA term 2*n_i*r_i*N per segment).
+ */
+symb_status symb_debug_gemm_timing_enable(symb_handle h, int32_t on);
+symb_status symb_debug_gemm_timing_read(symb_handle h, int32_t variant, double* ms_total,
+                                        int64_t* launches, double* flops_total);
+
 const char* symb_status_string(symb_status s);
 /* Text of the last error on this handle (h == NULL: of handle-free calls on this thread). */
 const char* symb_last_error(symb_handle h);

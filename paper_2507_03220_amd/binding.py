@@ -25,7 +25,8 @@ SYMB_MAX_RANK = 128
 
 EXPORTS = ("symb_create", "symb_destroy", "symb_validate_batch", "symb_debug_row_segment_map",
            "symb_plan_row_tiles", "symb_workspace_bytes", "symb_base_linear_fwd",
-           "symb_base_linear_bwd_input", "symb_adapter_grad", "symb_status_string", "symb_last_error")
+           "symb_base_linear_bwd_input", "symb_adapter_grad", "symb_status_string", "symb_last_error",
+           "symb_debug_gemm_timing_enable", "symb_debug_gemm_timing_read")
 
 
 class symb_adapter(C.Structure):
@@ -66,6 +67,9 @@ def lib() -> C.CDLL:
         l.symb_base_linear_fwd.argtypes = [vp, bp, vp, vp, vp, vp, vp, vp, sz, vp]
         l.symb_base_linear_bwd_input.argtypes = [vp, bp, vp, vp, vp, u32, vp, sz, vp]
         l.symb_adapter_grad.argtypes = [vp, bp, vp, vp, vp, u32, vp, sz, vp]
+        l.symb_debug_gemm_timing_enable.argtypes = [vp, i32]
+        l.symb_debug_gemm_timing_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64),
+                                                  C.POINTER(C.c_double)]
         l.symb_status_string.argtypes = [C.c_int]
         l.symb_status_string.restype = C.c_char_p
         l.symb_last_error.argtypes = [vp]
@@ -190,3 +194,14 @@ def symb_adapter_grad(handle, batch: Batch, X, dY, Ybase=None, flags: int = SYMB
     wp, wb = _ws_args(ws)
     _check(lib().symb_adapter_grad(handle, batch.ref(), _ptr(X), _ptr(dY), _ptr(Ybase), int(flags),
                                    wp, wb, stream or None), handle)
+
+
+def symb_debug_gemm_timing_enable(handle, on: bool) -> None:
+    _check(lib().symb_debug_gemm_timing_enable(handle, 1 if on else 0), handle)
+
+
+def symb_debug_gemm_timing_read(handle, variant: int):
+    """Returns (ms_total, launches, flops_total) of the GEMM launches of `variant` since enable."""
+    ms, n, fl = C.c_double(0), C.c_int64(0), C.c_double(0)
+    _check(lib().symb_debug_gemm_timing_read(handle, int(variant), C.byref(ms), C.byref(n), C.byref(fl)), handle)
+    return ms.value, n.value, fl.value

@@ -38,6 +38,7 @@ struct GemmParams {
                                 // then rpad residuals of the row's own segment; null = no LoRA term
     int ext_pitch;
     int epi_ia3;                // forward: scale rows of IA3 segments by l_i[n]
+    double timing_flops;        // host bookkeeping for the measurement hook; unused on the device
 };
 
 constexpr int GEMM_BK = 64;

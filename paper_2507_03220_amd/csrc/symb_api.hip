@@ -26,6 +26,7 @@ thread_local std::string g_tls_error;
 constexpr int kSlots = 4;                       // descriptor ring depth
 constexpr size_t kSlotBytes = (size_t)2 << 20;  // capacity of one descriptor blob
 constexpr int kSkinnyRows = 16;                 // rows per skinny / scale work item
+constexpr int kMaxTimed = 4096;                 // GEMM launches recorded between two timing reads
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int rpad_of(int r) { return (r + 15) / 16 * 16; }
@@ -40,6 +41,11 @@ struct symb_context {
     bool slot_used[kSlots] = {};
     int next_slot = 0;
     std::string error;
+    // measurement hook: event pairs around GEMM launches
+    bool timing = false;
+    std::vector<hipEvent_t> tev;                 // 2 * kMaxTimed events, created on first enable
+    struct Timed { int variant; double flops; };
+    std::vector<Timed> timed;
 };
 
 namespace {
@@ -262,9 +268,27 @@ symb_status launch_gemm_t(symb_handle h, GemmParams gp, hipStream_t st) {
     gp.group_m = 8;
     const int total = gp.num_m_tiles * gp.num_n_tiles;
     const int grid = ((total + 7) / 8) * 8;
+    const bool timed = h->timing && (int)h->timed.size() < kMaxTimed;
+    const size_t slot = h->timed.size();
+    if (timed) SYMB_HIP(h, hipEventRecord(h->tev[2 * slot], st));
     hipLaunchKernelGGL(kfn, dim3(grid), dim3(TT::NT), TT::SMEM, st, gp);
     SYMB_HIP(h, hipGetLastError());
+    if (timed) {
+        SYMB_HIP(h, hipEventRecord(h->tev[2 * slot + 1], st));
+        h->timed.push_back({NN ? 1 : 0, gp.timing_flops});
+    }
     return SYMB_OK;
+}
+
+// Algorithmic work of one GEMM launch: 2 M N K plus the fused LoRA term.
+double gemm_flops(const symb_batch* b, int N, int K, bool lora) {
+    const int S = b->num_segments;
+    double f = 2.0 * b->seg_offsets[S] * (double)N * K;
+    if (lora)
+        for (int i = 0; i < S; ++i)
+            if (b->adapters[i].kind == SYMB_ADAPTER_LORA)
+                f += 2.0 * (b->seg_offsets[i + 1] - b->seg_offsets[i]) * (double)b->adapters[i].rank * N;
+    return f;
 }
 
 // Row-tile height of the GEMM variant used for an M x N problem.
@@ -358,9 +382,43 @@ symb_status symb_create(symb_handle* out, int device) {
     return SYMB_OK;
 }
 
+symb_status symb_debug_gemm_timing_enable(symb_handle h, int32_t on) {
+    symb_status st = check_handle(h);
+    if (st != SYMB_OK) return st;
+    if (on && h->tev.empty()) {
+        h->tev.resize(2 * kMaxTimed);
+        for (auto& e : h->tev) SYMB_HIP(h, hipEventCreate(&e));
+        h->timed.reserve(kMaxTimed);
+    }
+    h->timing = on != 0;
+    h->timed.clear();
+    return SYMB_OK;
+}
+
+symb_status symb_debug_gemm_timing_read(symb_handle h, int32_t variant, double* ms_total, int64_t* launches,
+                                        double* flops_total) {
+    symb_status st = check_handle(h);
+    if (st != SYMB_OK) return st;
+    if (!ms_total || !launches || !flops_total) return fail(h, SYMB_ERR_INVALID_ARG, "null output pointer");
+    *ms_total = 0.0;
+    *launches = 0;
+    *flops_total = 0.0;
+    for (size_t i = 0; i < h->timed.size(); ++i) {
+        if (h->timed[i].variant != variant) continue;
+        SYMB_HIP(h, hipEventSynchronize(h->tev[2 * i + 1]));
+        float ms = 0.f;
+        SYMB_HIP(h, hipEventElapsedTime(&ms, h->tev[2 * i], h->tev[2 * i + 1]));
+        *ms_total += ms;
+        *launches += 1;
+        *flops_total += h->timed[i].flops;
+    }
+    return SYMB_OK;
+}
+
 symb_status symb_destroy(symb_handle h) {
     if (!h) return SYMB_OK;
     (void)hipSetDevice(h->device);
+    for (auto& e : h->tev) (void)hipEventDestroy(e);
     for (int i = 0; i < kSlots; ++i) {
         if (h->slot_used[i]) (void)hipEventSynchronize(h->slot_done[i]);
         if (h->slot_done[i]) (void)hipEventDestroy(h->slot_done[i]);
@@ -475,6 +533,7 @@ symb_status symb_base_linear_fwd(symb_handle h, const symb_batch* b, const void*
     gp.ext = Hs;
     gp.ext_pitch = 2 * bi.max_rpad;
     gp.epi_ia3 = bi.n_ia3 > 0;
+    gp.timing_flops = gemm_flops(b, b->d_out, b->d_in, bi.n_lora > 0);
     if ((st = launch_gemm<false>(h, gp, s)) != SYMB_OK) return st;
     return seal_slot(h, s);
 }
@@ -565,6 +624,7 @@ symb_status symb_base_linear_bwd_input(symb_handle h, const symb_batch* b, const
     gp.ext = dH;
     gp.ext_pitch = 2 * bi.max_rpad;
     gp.epi_ia3 = 0;
+    gp.timing_flops = gemm_flops(b, b->d_in, b->d_out, lora);
     if ((st = launch_gemm<true>(h, gp, s)) != SYMB_OK) return st;
     return seal_slot(h, s);
 }
