@@ -18,6 +18,7 @@
 // one row m, runs of 4 consecutive n: rows keep their own segment in the epilogue and
 // the store is 8 bytes per lane.
 #pragma once
+#include "gemm_mainloop_asm.hpp"
 #include "symb_device.hpp"
 
 namespace symb {
@@ -38,10 +39,23 @@ struct GemmParams {
                                 // then rpad residuals of the row's own segment; null = no LoRA term
     int ext_pitch;
     int epi_ia3;                // forward: scale rows of IA3 segments by l_i[n]
+    int stagger;                // start delay unit (s_sleep 127 each) between the 8 phase groups of the first wave of tiles
     double timing_flops;        // host bookkeeping for the measurement hook; unused on the device
+#ifdef SYMB_GEMM_TRACE
+    unsigned long long* trace;  // tuning builds only: 4 timestamps per tile
+#endif
+#ifdef SYMB_GEMM_PROBE
+    int probe;                  // tuning builds only: 1 = no in-loop global loads, 2 = nor LDS reads
+#endif
 };
 
-constexpr int GEMM_BK = 64;
+constexpr int GEMM_BK = 64;       // k per register-staged tile (K remainder, LoRA term)
+constexpr int GEMM_SK = 32;       // k per main-loop stage (direct global -> LDS)
+constexpr int GEMM_NSTAGE = 4;    // main-loop LDS ring depth
+
+// s_waitcnt immediates (gfx9 encoding: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8]).
+__device__ __host__ constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0F70; }
+__device__ __host__ constexpr int lgkmcnt0_mask() { return ~0x0F00; }
 
 // 16-byte chunk swizzle of a K-contiguous tile row (8 chunks of 8 bf16 per row).
 __device__ __forceinline__ int swz_row(int row) { return (row & 7) ^ ((row >> 3) & 1); }
@@ -53,8 +67,13 @@ struct GemmTile {
     static constexpr int WTM = BM / WGM, WTN = BN / WGN;
     static constexpr int MB = WTM / 32, NB = WTN / 32;
     static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
-    static constexpr int SMEM = 2 * (A_BYTES + B_BYTES);
+    static constexpr int A_STAGE = BM * GEMM_SK * 2, B_STAGE = BN * GEMM_SK * 2, STAGE_BYTES = A_STAGE + B_STAGE;
+    static constexpr int C_PITCH = BN * 2 + 16, C_BYTES = BM * C_PITCH;     // epilogue staging of the bf16 tile
+    static constexpr int SMEM_IN = (2 * (A_BYTES + B_BYTES) > GEMM_NSTAGE * STAGE_BYTES) ? 2 * (A_BYTES + B_BYTES) : GEMM_NSTAGE * STAGE_BYTES;
+    static constexpr int SMEM = SMEM_IN > C_BYTES ? SMEM_IN : C_BYTES;
     static constexpr int CA = BM * 8 / NT, CB = BN * 8 / NT;   // 16-byte chunks per thread per K-step
+    // 256x256 with 4 wavefronts: the hand-scheduled assembly main loop (gemm_mainloop_asm.hpp)
+    static constexpr bool ASM_LOOP = (BM == 256 && BN == 256 && WGM == 2 && WGN == 2);
     static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tile must be made of 32x32 blocks");
     static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0, "tile chunks must divide over the threads");
 };
@@ -68,6 +87,11 @@ __device__ __forceinline__ int lds_off_nmajor(int k, int nc) { return k * (BN * 
 
 __device__ __forceinline__ bf16x8 lds_read_frag_kmajor(const unsigned char* buf, int row, int kc) {
     return *reinterpret_cast<const bf16x8*>(buf + lds_off_kmajor(row, kc));
+}
+// K-contiguous main-loop stage: [rows][32] bf16, 64 B per row, chunk kc (0..3) stored at kc ^ ((row >> 2) & 3):
+// 16 consecutive rows at one kc then hit 16 different 16-byte bank groups.
+__device__ __forceinline__ bf16x8 lds_read_frag_k32(const unsigned char* buf, int row, int kc) {
+    return *reinterpret_cast<const bf16x8*>(buf + row * 64 + ((kc ^ ((row >> 2) & 3)) << 4));
 }
 
 // Fragment of a 32(n) x 16(k) block out of an N-contiguous tile via the transposing LDS read:
@@ -115,6 +139,16 @@ symb_gemm_kernel(const GemmParams p) {
     const int tn = (lin % width) / gsz;
     const int m0 = tm * BM, n0 = tn * BN;
 
+    // Tiles all take the same time, so workgroups that start together also reach their epilogue
+    // together and the whole chip stops multiplying while one burst of stores drains.  Delaying
+    // the first resident workgroup of each CU by a phase (8 phases) keeps the bursts apart.
+    if (p.stagger > 0 && blockIdx.x < 8 * 32) {
+        const int phase = (blockIdx.x >> 3) & 7;
+        for (int i = 0; i < phase * p.stagger; ++i) __builtin_amdgcn_s_sleep(127);
+    }
+#ifdef SYMB_GEMM_TRACE
+    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 4 + 0] = __builtin_amdgcn_s_memrealtime();
+#endif
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave / WGN) * TT::WTM, wn0 = (wave % WGN) * TT::WTN;
 
@@ -126,42 +160,19 @@ symb_gemm_kernel(const GemmParams p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // ---- per-thread global load slots.  Chunk i of a thread sits NT/8 rows (K-contiguous tiles)
-    // or NT/(BN/8) k-rows (N-contiguous weight tile) below chunk 0, in the same 16-byte column, so
-    // one pointer and one LDS offset per operand are enough (the swizzles repeat every 16 rows).
+    // ---- per-thread staging slots.  Chunk i of a thread sits NT/8 rows (K-contiguous tiles) or
+    // NT/(BN/8) k-rows (N-contiguous weight tile) below chunk 0, in the same 16-byte column, so one
+    // LDS offset per operand is enough (the swizzles repeat every 16 rows / 4 k-rows).
     constexpr int RSTEP = NT / 8;                 // row step between a thread's chunks, K-contiguous tile
     constexpr int KSTEP = NT / (BN / 8);          // k-row step, N-contiguous tile
     static_assert(RSTEP % 16 == 0 && (!NN || KSTEP % 4 == 0), "chunk stride must preserve the LDS swizzle");
     const int lrow = tid >> 3, lkc = (tid & 7) * 8;
-    const bf16* a_base = p.Aop + (size_t)(m0 + lrow) * p.K + lkc;
-    const int a_lds0 = lds_off_kmajor(lrow, tid & 7);
-    const bf16* b_base;
-    int b_lds0;
     const int nn_k = tid / (BN / 8), nn_nc = tid % (BN / 8);
-    const bool nn_ok = (n0 + nn_nc * 8) < p.N;
-    if constexpr (!NN) {
-        b_base = p.Bop + (size_t)(n0 + lrow) * p.K + lkc;
-        b_lds0 = a_lds0;
-    } else {
-        b_base = p.Bop + (size_t)nn_k * p.N + (nn_ok ? (n0 + nn_nc * 8) : 0);
-        b_lds0 = lds_off_nmajor<BN>(nn_k, nn_nc);
-    }
+    const int a_lds0 = lds_off_kmajor(lrow, tid & 7);
+    const int b_lds0 = NN ? lds_off_nmajor<BN>(nn_k, nn_nc) : a_lds0;
 
     uint4 ra[CA], rb[CB];
-    auto gload = [&](int k0) {
-        const bool kok = (k0 + lkc) < p.K;
-#pragma unroll
-        for (int i = 0; i < CA; ++i)
-            ra[i] = ld_global_16(a_base + (size_t)i * RSTEP * p.K + k0, kok && (m0 + lrow + i * RSTEP) < p.M);
-#pragma unroll
-        for (int i = 0; i < CB; ++i) {
-            if constexpr (!NN)
-                rb[i] = ld_global_16(b_base + (size_t)i * RSTEP * p.K + k0, kok && (n0 + lrow + i * RSTEP) < p.N);
-            else
-                rb[i] = ld_global_16(b_base + (size_t)(k0 + i * KSTEP) * p.N, nn_ok && (k0 + nn_k + i * KSTEP) < p.K);
-        }
-    };
-    auto lds_store = [&](int buf) {
+    auto lds_store = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < CA; ++i) *reinterpret_cast<uint4*>(sA + buf * TT::A_BYTES + a_lds0 + i * RSTEP * 128) = ra[i];
 #pragma unroll
@@ -170,46 +181,224 @@ symb_gemm_kernel(const GemmParams p) {
             else *reinterpret_cast<uint4*>(sB + buf * TT::B_BYTES + b_lds0 + i * KSTEP * (BN * 2)) = rb[i];
         }
     };
-    auto compute = [&](int buf, int nks) {
-        const unsigned char* bufA = sA + buf * TT::A_BYTES;
-        const unsigned char* bufB = sB + buf * TT::B_BYTES;
+
+    // ---- main-loop staging: global memory -> LDS directly (no registers), NSTAGE stages of SK = 32
+    // k each.  One such load instruction moves 16 bytes per lane into 1 KiB of consecutive LDS, so
+    // the lane -> global chunk map below is the inverse of the LDS swizzle.  No predicates: a row
+    // (column chunk) outside the problem is clamped onto the last valid one and never stored.
+    // Offsets are 32-bit element offsets from a wave-uniform tile pointer that advances per stage.
+    constexpr int NW = NT / 64;
+    constexpr int AI = BM / 16 / NW, BI = BN / 16 / NW;       // load instructions per wave per stage
+    static_assert(AI >= 1 && BI >= 1, "tile too small for this many wavefronts");
+    unsigned a_off[AI], b_off[BI];
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            if (ks < nks) {
-                bf16x8 xa[MB], wb[NB];
+    for (int j = 0; j < AI; ++j) {
+        const int row = (wave * AI + j) * 16 + (lane >> 2), kc = (lane & 3) ^ ((row >> 2) & 3);
+        a_off[j] = (unsigned)(min(m0 + row, p.M - 1) - m0) * (unsigned)p.K + kc * 8;
+    }
 #pragma unroll
-                for (int i = 0; i < MB; ++i)
-                    xa[i] = lds_read_frag_kmajor(bufA, wm0 + i * 32 + (lane & 31), ks * 2 + (lane >> 5));
+    for (int j = 0; j < BI; ++j) {
+        if constexpr (!NN) {
+            const int row = (wave * BI + j) * 16 + (lane >> 2), kc = (lane & 3) ^ ((row >> 2) & 3);
+            b_off[j] = (unsigned)(min(n0 + row, p.N - 1) - n0) * (unsigned)p.K + kc * 8;
+        } else {
+            constexpr int CPR = BN / 8;                        // 16-byte chunks per k-row
+            const int krow = (wave * BI + j) * (64 / CPR) + lane / CPR, nc = (lane % CPR) ^ ((krow & 3) << 2);
+            b_off[j] = (unsigned)krow * (unsigned)p.N + (unsigned)min(nc * 8, p.N - 8 - n0);
+        }
+    }
+    const bf16* const a_tile = p.Aop + (size_t)m0 * p.K;
+    const bf16* const b_tile = NN ? (p.Bop + n0) : (p.Bop + (size_t)n0 * p.K);
+    typedef __attribute__((address_space(3))) void lds_void_t;
+    typedef __attribute__((address_space(1))) const void glb_void_t;
+    auto stage_issue = [&](int stage, int ks32) __attribute__((always_inline)) {
+        unsigned char* sa = smem + stage * TT::STAGE_BYTES;
+        unsigned char* sb = sa + TT::A_STAGE;
+        const bf16* at = a_tile + (size_t)ks32 * GEMM_SK;
+        const bf16* bt = NN ? (b_tile + (size_t)ks32 * GEMM_SK * p.N) : (b_tile + (size_t)ks32 * GEMM_SK);
 #pragma unroll
-                for (int j = 0; j < NB; ++j) {
-                    if constexpr (!NN) wb[j] = lds_read_frag_kmajor(bufB, wn0 + j * 32 + (lane & 31), ks * 2 + (lane >> 5));
-                    else wb[j] = lds_read_frag_nmajor<BN>(bufB, wn0 + j * 32, ks * 16, lane);
-                }
+        for (int j = 0; j < AI; ++j)
+            __builtin_amdgcn_global_load_lds((glb_void_t*)(at + a_off[j]), (lds_void_t*)(sa + (wave * AI + j) * 1024), 16, 0, 0);
 #pragma unroll
-                for (int i = 0; i < MB; ++i)
+        for (int j = 0; j < BI; ++j)
+            __builtin_amdgcn_global_load_lds((glb_void_t*)(bt + b_off[j]), (lds_void_t*)(sb + (wave * BI + j) * 1024), 16, 0, 0);
+    };
+    // Predicated, zero-filling variant for the K remainder (K % 64 != 0).
+    auto gload_tail = [&](int k0) __attribute__((always_inline)) {
+        const bool kok = (k0 + lkc) < p.K;
 #pragma unroll
-                    for (int j = 0; j < NB; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[j], xa[i], acc[i][j], 0, 0, 0);
+        for (int i = 0; i < CA; ++i)
+            ra[i] = ld_global_16(p.Aop + (size_t)min(m0 + lrow + i * RSTEP, p.M - 1) * p.K + k0 + lkc, kok);
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+            if constexpr (!NN)
+                rb[i] = ld_global_16(p.Bop + (size_t)min(n0 + lrow + i * RSTEP, p.N - 1) * p.K + k0 + lkc, kok);
+            else {
+                const int kr = k0 + nn_k + i * KSTEP;
+                rb[i] = ld_global_16(p.Bop + (size_t)min(kr, p.K - 1) * p.N + n0 + min(nn_nc * 8, p.N - 8 - n0), kr < p.K);
             }
         }
     };
 
-    // ---- main loop over K: global -> registers -> LDS, double buffered
-    const int KT = (p.K + BK - 1) / BK;
-    gload(0);
-    lds_store(0);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < KT) gload((kt + 1) * BK);
-        compute(cur, BK / 16);
-        if (kt + 1 < KT) lds_store(cur ^ 1);
+    // MFMA fragments, double buffered in registers across the 16-wide k-steps.
+    bf16x8 xa[2][MB], wb[2][NB];
+    // from a 64-k tile staged through registers (K remainder, LoRA term)
+    auto load_frags = [&](int buf, int ks, int set) __attribute__((always_inline)) {
+        const unsigned char* bufA = sA + buf * TT::A_BYTES;
+        const unsigned char* bufB = sB + buf * TT::B_BYTES;
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+            xa[set][i] = lds_read_frag_kmajor(bufA, wm0 + i * 32 + (lane & 31), ks * 2 + (lane >> 5));
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            if constexpr (!NN) wb[set][j] = lds_read_frag_kmajor(bufB, wn0 + j * 32 + (lane & 31), ks * 2 + (lane >> 5));
+            else wb[set][j] = lds_read_frag_nmajor<BN>(bufB, wn0 + j * 32, ks * 16, lane);
+        }
+    };
+    // from a 32-k main-loop stage
+    auto load_frags32 = [&](int stage, int ks, int set) __attribute__((always_inline)) {
+        const unsigned char* bufA = smem + stage * TT::STAGE_BYTES;
+        const unsigned char* bufB = bufA + TT::A_STAGE;
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+            xa[set][i] = lds_read_frag_k32(bufA, wm0 + i * 32 + (lane & 31), ks * 2 + (lane >> 5));
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            if constexpr (!NN) wb[set][j] = lds_read_frag_k32(bufB, wn0 + j * 32 + (lane & 31), ks * 2 + (lane >> 5));
+            else wb[set][j] = lds_read_frag_nmajor<BN>(bufB, wn0 + j * 32, ks * 16, lane);
+        }
+    };
+    auto mfma_set = [&](int set) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[set][j], xa[set][i], acc[i][j], 0, 0, 0);
+    };
+    // Asks the scheduler to issue one LDS fragment read after each MFMA instead of sinking the
+    // reads to just before their first use (which would leave the matrix pipe idle for the
+    // whole LDS latency once per k-step).
+    auto interleave_hint = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < MB + NB; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, NN ? 2 : 1, 0);   // then LDS reads
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, MB * NB - (MB + NB), 0);
+    };
+    // Plain (not pipelined) pass over one register-staged tile; K remainder and LoRA term.
+    auto compute = [&](int buf, int nks) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            if (ks < nks) {
+                load_frags(buf, ks, 0);
+                mfma_set(0);
+            }
+        }
+    };
+
+    // ---- main loop over the full 32-k stages.  NSTAGE LDS buffers form a ring; the loads of
+    // stage t + NSTAGE are issued as soon as every wavefront is done with stage t, i.e. NSTAGE - 1
+    // iterations before they are needed.  Per iteration: MFMAs of k-step 0 run while the fragments
+    // of k-step 1 are read; then this wavefront's loads of the next stage are awaited, one barrier
+    // makes that stage complete for everybody (and frees this one), the refill of this buffer is
+    // issued, and the MFMAs of k-step 1 run while the next stage's first fragments are read.
+    // Every iteration issues the same number of loads (past the end they refetch the last stage
+    // into a buffer nobody reads again), so the vmcnt immediates below stay exact.
+    constexpr int NS = GEMM_NSTAGE, LPS = AI + BI;             // loads per wavefront per stage
+    constexpr int VM_STEADY = LPS * (NS - 2);                  // younger stages that may stay in flight
+    static_assert(LPS * (NS - 1) < 64, "vmcnt is a 6-bit counter");
+    const int KF = p.K / GEMM_SK;                              // full stages
+    if constexpr (TT::ASM_LOOP) {
+        if (KF > 0) {
+            // lane byte offsets of the MFMA fragments inside one stage (see lds_read_frag_k32 /
+            // lds_read_frag_nmajor for the layouts they mirror)
+            const int r31 = lane & 31, hi = lane >> 5, sw = (r31 >> 2) & 3;
+            const unsigned vA0 = (unsigned)((wm0 + r31) * 64 + ((hi ^ sw) << 4));
+            const unsigned vA1 = (unsigned)((wm0 + r31) * 64 + (((2 + hi) ^ sw) << 4));
+            unsigned vB[4];
+            if constexpr (!NN) {
+                vB[0] = (unsigned)(TT::A_STAGE + (wn0 + r31) * 64 + ((hi ^ sw) << 4));
+                vB[1] = (unsigned)(TT::A_STAGE + (wn0 + r31) * 64 + (((2 + hi) ^ sw) << 4));
+                vB[2] = vB[3] = 0u;
+            } else {
+                const int g = lane >> 4, jj = lane & 15, kk = (jj >> 2) & 3;
+                const int krow = ((g >> 1) << 3) + (jj >> 2), c2 = ((g & 1) << 1) + ((jj & 3) >> 1);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    vB[j] = (unsigned)(TT::A_STAGE + krow * (BN * 2) + (((wn0 >> 3) + ((j ^ kk) << 2) + c2) << 4) + ((jj & 1) << 3));
+            }
+            const unsigned ab0 = a_off[0] * 2u, ab1 = a_off[1] * 2u, ab2 = a_off[2] * 2u, ab3 = a_off[3] * 2u;
+            const unsigned bb0 = b_off[0] * 2u, bb1 = b_off[1] * 2u, bb2 = b_off[2] * 2u, bb3 = b_off[3] * 2u;
+#ifdef SYMB_GEMM_PROBE
+            const unsigned long long ga = (unsigned long long)(p.probe == 3 ? p.Aop : a_tile), gb = (unsigned long long)(p.probe == 3 ? p.Bop : b_tile);
+#else
+            const unsigned long long ga = (unsigned long long)a_tile, gb = (unsigned long long)b_tile;
+#endif
+            const unsigned stride_b = NN ? 64u * (unsigned)p.N : 64u;
+            const unsigned swa = (unsigned)__builtin_amdgcn_readfirstlane(wave) * 4096u;
+#define SYMB_GEMM_LOOP_OPERANDS                                                                                     \
+    : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]), "+a"(acc[1][0]), "+a"(acc[1][1]),       \
+      "+a"(acc[1][2]), "+a"(acc[1][3]), "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),       \
+      "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3])                                           \
+    : "v"(vA0), "v"(vA1), "v"(vB[0]), "v"(vB[1]), "v"(vB[2]), "v"(vB[3]), "v"(ab0), "v"(ab1), "v"(ab2), "v"(ab3),  \
+      "v"(bb0), "v"(bb1), "v"(bb2), "v"(bb3), "s"(ga), "s"(gb), "s"(stride_b), "s"(KF), "s"(swa)                   \
+    : SYMB_GEMM_LOOP_CLOBBERS
+#ifdef SYMB_GEMM_TRACE
+            if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 4 + 1] = __builtin_amdgcn_s_memrealtime();
+#endif
+            if constexpr (NN) asm volatile(SYMB_GEMM_LOOP_NN SYMB_GEMM_LOOP_OPERANDS);
+#ifdef SYMB_GEMM_PROBE
+            else if (p.probe == 1) asm volatile(SYMB_GEMM_LOOP_NT_NOLOAD SYMB_GEMM_LOOP_OPERANDS);
+            else if (p.probe == 2) asm volatile(SYMB_GEMM_LOOP_NT_NOREAD SYMB_GEMM_LOOP_OPERANDS);
+#endif
+            else asm volatile(SYMB_GEMM_LOOP_NT SYMB_GEMM_LOOP_OPERANDS);
+#undef SYMB_GEMM_LOOP_OPERANDS
+            __builtin_amdgcn_s_barrier();                      // everything landed and read before LDS is reused
+#ifdef SYMB_GEMM_TRACE
+            if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 4 + 2] = __builtin_amdgcn_s_memrealtime();
+#endif
+        }
+    } else if (KF > 0) {
+#pragma unroll
+        for (int t = 0; t < NS; ++t) stage_issue(t, min(t, KF - 1));
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(LPS * (NS - 1)));
+        __builtin_amdgcn_s_barrier();
+        load_frags32(0, 0, 0);
+#ifdef SYMB_GEMM_TRACE
+        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 4 + 1] = __builtin_amdgcn_s_memrealtime();
+#endif
+        int stage = 0;
+        for (int kt = 0; kt < KF; ++kt) {
+            const int nxt = (stage + 1 == NS) ? 0 : stage + 1;
+            load_frags32(stage, 1, 1);
+            mfma_set(0);
+            interleave_hint();
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(VM_STEADY) & lgkmcnt0_mask());
+            __builtin_amdgcn_s_barrier();
+            stage_issue(stage, min(kt + NS, KF - 1));
+            load_frags32(nxt, 0, 0);
+            mfma_set(1);
+            interleave_hint();
+            stage = nxt;
+        }
+        __builtin_amdgcn_s_waitcnt(0);                         // everything landed before LDS is reused
+        __builtin_amdgcn_s_barrier();
+#ifdef SYMB_GEMM_TRACE
+        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 4 + 2] = __builtin_amdgcn_s_memrealtime();
+#endif
+    }
+    if (KF * GEMM_SK < p.K) {
+        gload_tail(KF * GEMM_SK);
+        lds_store(0);
+        __syncthreads();
+        compute(0, (p.K - KF * GEMM_SK + 15) >> 4);
         __syncthreads();
     }
 
     // ---- bias, optional store of the pre-adapter output
     const int seg_lo = p.tile_seg_lo[tm], seg_hi = p.tile_seg_hi[tm];
-    auto for_each_quad = [&](auto&& fn) {
+    auto for_each_quad = [&](auto&& fn) __attribute__((always_inline)) {
         // fn(i, j, rg, m, n): this lane holds acc[i][j][rg*4 .. rg*4+3] = C[m][n .. n+3]
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
@@ -224,7 +413,7 @@ symb_gemm_kernel(const GemmParams p) {
         }
     };
     if (p.bias) {
-        for_each_quad([&](int i, int j, int rg, int, int n) {
+        for_each_quad([&](int i, int j, int rg, int, int n) __attribute__((always_inline)) {
             if (n < p.N) {
                 const uint2 bv = *reinterpret_cast<const uint2*>(p.bias + n);
                 acc[i][j][rg * 4 + 0] += bf16_bits_to_f32((unsigned short)(bv.x & 0xffffu));
@@ -235,7 +424,7 @@ symb_gemm_kernel(const GemmParams p) {
         });
     }
     if (p.Cbase) {
-        for_each_quad([&](int i, int j, int rg, int m, int n) {
+        for_each_quad([&](int i, int j, int rg, int m, int n) __attribute__((always_inline)) {
             if (m < p.M && n < p.N) {
                 uint2 o;
                 o.x = pack2_bf16(acc[i][j][rg * 4 + 0], acc[i][j][rg * 4 + 1]);
@@ -297,27 +486,46 @@ symb_gemm_kernel(const GemmParams p) {
         }
     }
 
-    // ---- epilogue: IA3 scale of each row's own segment, one rounding to bf16, 8-byte stores
-    for_each_quad([&](int i, int j, int rg, int m, int n) {
-        if (m < p.M && n < p.N) {
-            float v0 = acc[i][j][rg * 4 + 0], v1 = acc[i][j][rg * 4 + 1];
-            float v2 = acc[i][j][rg * 4 + 2], v3 = acc[i][j][rg * 4 + 3];
-            if (p.epi_ia3) {
-                const int s = seg_of_row(p.off, seg_lo, seg_hi, m);
-                if (p.seg[s].kind == KIND_IA3) {
-                    const uint2 lv = *reinterpret_cast<const uint2*>(p.seg[s].A + n);
-                    v0 *= bf16_bits_to_f32((unsigned short)(lv.x & 0xffffu));
-                    v1 *= bf16_bits_to_f32((unsigned short)(lv.x >> 16));
-                    v2 *= bf16_bits_to_f32((unsigned short)(lv.y & 0xffffu));
-                    v3 *= bf16_bits_to_f32((unsigned short)(lv.y >> 16));
-                }
+    // ---- epilogue: IA3 scale of each row's own segment and one rounding to bf16 in registers,
+    // then the tile goes through LDS so that every store instruction writes whole rows: a lane
+    // owns 4 consecutive columns of 32 different rows, which as direct stores is 32 partial
+    // lines per instruction; after the transpose it is two full 512-byte rows.
+    constexpr int CP = TT::C_PITCH;                  // bytes per staged row (BN * 2 + 16: bank spread)
+    for_each_quad([&](int i, int j, int rg, int m, int n) __attribute__((always_inline)) {
+        float v0 = acc[i][j][rg * 4 + 0], v1 = acc[i][j][rg * 4 + 1];
+        float v2 = acc[i][j][rg * 4 + 2], v3 = acc[i][j][rg * 4 + 3];
+        if (p.epi_ia3 && m < p.M && n < p.N) {
+            const int s = seg_of_row(p.off, seg_lo, seg_hi, m);
+            if (p.seg[s].kind == KIND_IA3) {
+                const uint2 lv = *reinterpret_cast<const uint2*>(p.seg[s].A + n);
+                v0 *= bf16_bits_to_f32((unsigned short)(lv.x & 0xffffu));
+                v1 *= bf16_bits_to_f32((unsigned short)(lv.x >> 16));
+                v2 *= bf16_bits_to_f32((unsigned short)(lv.y & 0xffffu));
+                v3 *= bf16_bits_to_f32((unsigned short)(lv.y >> 16));
             }
-            uint2 o;
-            o.x = pack2_bf16(v0, v1);
-            o.y = pack2_bf16(v2, v3);
-            *reinterpret_cast<uint2*>(p.C + (size_t)m * p.N + n) = o;
         }
+        uint2 o;
+        o.x = pack2_bf16(v0, v1);
+        o.y = pack2_bf16(v2, v3);
+        *reinterpret_cast<uint2*>(smem + (m - m0) * CP + (n - n0) * 2) = o;
     });
+    __syncthreads();
+    {
+        constexpr int LPR = BN / 8;                  // lanes per row (16 bytes each)
+        constexpr int RPI = 64 / LPR;                // rows per store instruction
+        constexpr int NW = NT / 64;
+        const int col = (lane % LPR) * 8;
+#pragma unroll 4
+        for (int r = wave * RPI + lane / LPR; r < BM; r += NW * RPI) {
+            const int m = m0 + r, n = n0 + col;
+            if (m < p.M && n < p.N)
+                *reinterpret_cast<uint4*>(p.C + (size_t)m * p.N + n) = *reinterpret_cast<const uint4*>(smem + r * CP + col * 2);
+        }
+    }
+#ifdef SYMB_GEMM_TRACE
+    __builtin_amdgcn_s_waitcnt(0);
+    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 4 + 3] = __builtin_amdgcn_s_memrealtime();
+#endif
 }
 
 }  // namespace symb

@@ -9,6 +9,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <utility>
@@ -266,6 +267,16 @@ symb_status launch_gemm_t(symb_handle h, GemmParams gp, hipStream_t st) {
     gp.num_m_tiles = (gp.M + BM - 1) / BM;
     gp.num_n_tiles = (gp.N + BN - 1) / BN;
     gp.group_m = 8;
+    {
+        static const int stagger = [] { const char* e = getenv("SYMB_GEMM_STAGGER"); return e ? atoi(e) : 0; }();
+        gp.stagger = stagger;
+    }
+#ifdef SYMB_GEMM_PROBE
+    { const char* e = getenv("SYMB_GEMM_PROBE"); gp.probe = e ? atoi(e) : 0; }
+#endif
+#ifdef SYMB_GEMM_TRACE
+    { const char* e = getenv("SYMB_TRACE_PTR"); gp.trace = e ? (unsigned long long*)strtoull(e, nullptr, 0) : nullptr; }
+#endif
     const int total = gp.num_m_tiles * gp.num_n_tiles;
     const int grid = ((total + 7) / 8) * 8;
     const bool timed = h->timing && (int)h->timed.size() < kMaxTimed;
@@ -291,16 +302,28 @@ double gemm_flops(const symb_batch* b, int N, int K, bool lora) {
     return f;
 }
 
-// Row-tile height of the GEMM variant used for an M x N problem.
-int gemm_tile_m(int M, int N) {
+// Tile variants: 0 = 256x256 tile, 8 wavefronts (2x4), compiler-scheduled main loop;
+// 1 = 128x128 tile, 4 wavefronts (2x2), compiler-scheduled; 2 = 256x256 tile, 4 wavefronts (2x2),
+// hand-scheduled assembly main loop (the default for large problems).
+// SYMB_GEMM_VARIANT overrides the choice (tuning aid).
+int gemm_variant(int M, int N) {
+    static const int forced = [] {
+        const char* e = getenv("SYMB_GEMM_VARIANT");
+        return e ? atoi(e) : -1;
+    }();
+    if (forced >= 0 && forced <= 2) return forced;
     const long big = (long)((M + 255) / 256) * ((N + 255) / 256);
-    return big >= 128 ? 256 : 128;
+    return big >= 128 ? 2 : 1;
 }
+int gemm_tile_m(int M, int N) { return gemm_variant(M, N) == 1 ? 128 : 256; }
 
 template <bool NN>
 symb_status launch_gemm(symb_handle h, const GemmParams& gp, hipStream_t st) {
-    if (gemm_tile_m(gp.M, gp.N) == 256) return launch_gemm_t<256, 256, 2, 4, NN>(h, gp, st);
-    return launch_gemm_t<128, 128, 2, 2, NN>(h, gp, st);
+    switch (gemm_variant(gp.M, gp.N)) {
+        case 0: return launch_gemm_t<256, 256, 2, 4, NN>(h, gp, st);
+        case 2: return launch_gemm_t<256, 256, 2, 2, NN>(h, gp, st);
+        default: return launch_gemm_t<128, 128, 2, 2, NN>(h, gp, st);
+    }
 }
 
 template <int RB>

@@ -36,8 +36,12 @@ __device__ __forceinline__ unsigned short f32_to_bf16_bits(float f) {
 __device__ __forceinline__ float bf16_bits_to_f32(unsigned short b) {
     return __builtin_bit_cast(float, ((unsigned int)b) << 16);
 }
+// Two fp32 -> packed bf16 pair, round-to-nearest-even in hardware (v_cvt_pk_bf16_f32).
 __device__ __forceinline__ unsigned int pack2_bf16(float lo, float hi) {
-    return (unsigned int)f32_to_bf16_bits(lo) | ((unsigned int)f32_to_bf16_bits(hi) << 16);
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, bf16x2_t));
 }
 
 // Segment of row t among segments [lo, hi]: off[i] <= t < off[i+1].  Empty segments never match.
