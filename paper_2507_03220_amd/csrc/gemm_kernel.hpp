@@ -132,6 +132,9 @@ symb_gemm_kernel(const GemmParams p) {
     const int per_xcd = (total + 7) >> 3;
     const int lin = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (lin >= total || (int)(blockIdx.x >> 3) >= per_xcd) return;
+#ifdef SYMB_GEMM_PROBE
+    if (p.probe == 4 && (blockIdx.x & 7) != 0) return;     // tuning: only one XCD works
+#endif
     const int width = p.group_m * p.num_n_tiles;
     const int first_m = (lin / width) * p.group_m;
     const int gsz = min(p.num_m_tiles - first_m, p.group_m);
@@ -147,7 +150,7 @@ symb_gemm_kernel(const GemmParams p) {
         for (int i = 0; i < phase * p.stagger; ++i) __builtin_amdgcn_s_sleep(127);
     }
 #ifdef SYMB_GEMM_TRACE
-    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 4 + 0] = __builtin_amdgcn_s_memrealtime();
+    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 8 + 0] = __builtin_amdgcn_s_memrealtime();
 #endif
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave / WGN) * TT::WTM, wn0 = (wave % WGN) * TT::WTN;
@@ -286,13 +289,43 @@ symb_gemm_kernel(const GemmParams p) {
         }
         __builtin_amdgcn_sched_group_barrier(0x008, MB * NB - (MB + NB), 0);
     };
-    // Plain (not pipelined) pass over one register-staged tile; K remainder and LoRA term.
-    auto compute = [&](int buf, int nks) __attribute__((always_inline)) {
+    // Plain (not pipelined) pass over the register-staged tile in buffer 0; K remainder and LoRA
+    // term.  The 4-wavefront variant keeps its accumulators pinned in the accumulation registers,
+    // so its k-steps are assembly here too (nothing outside assembly ever writes an accumulator).
+    const unsigned lds0 = (unsigned)(size_t)smem;          // LDS byte address of the dynamic segment
+    auto compute = [&](int nks) __attribute__((always_inline)) {
+        if constexpr (TT::ASM_LOOP) {
+            const int r31 = lane & 31, hi = lane >> 5;
+            for (int ks = 0; ks < nks; ++ks) {
+                const unsigned va = lds0 + (unsigned)lds_off_kmajor(wm0 + r31, ks * 2 + hi);
+#define SYMB_ACC16                                                                                                 \
+    "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]), "+a"(acc[1][0]), "+a"(acc[1][1]),          \
+    "+a"(acc[1][2]), "+a"(acc[1][3]), "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),          \
+    "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3])
+                if constexpr (!NN) {
+                    const unsigned vb = lds0 + 2 * TT::A_BYTES + (unsigned)lds_off_kmajor(wn0 + r31, ks * 2 + hi);
+                    asm volatile(SYMB_GEMM_KSTEP64_NT : SYMB_ACC16 : "v"(va), "v"(vb) : SYMB_GEMM_LOOP_CLOBBERS);
+                } else {
+                    const int g = lane >> 4, jj = lane & 15;
+                    const int k = ks * 16 + ((g >> 1) << 3) + (jj >> 2);
+                    unsigned vb[4];
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            if (ks < nks) {
-                load_frags(buf, ks, 0);
-                mfma_set(0);
+                    for (int j = 0; j < 4; ++j) {
+                        const int n = wn0 + j * 32 + ((g & 1) << 4) + ((jj & 3) << 2);
+                        vb[j] = lds0 + 2 * TT::A_BYTES + (unsigned)lds_off_nmajor<BN>(k, n >> 3) + ((n & 7) << 1);
+                    }
+                    asm volatile(SYMB_GEMM_KSTEP64_NN : SYMB_ACC16 : "v"(va), "v"(vb[0]), "v"(vb[1]), "v"(vb[2]), "v"(vb[3])
+                                 : SYMB_GEMM_LOOP_CLOBBERS);
+                }
+#undef SYMB_ACC16
+            }
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < BK / 16; ++ks) {
+                if (ks < nks) {
+                    load_frags(0, ks, 0);
+                    mfma_set(0);
+                }
             }
         }
     };
@@ -314,19 +347,19 @@ symb_gemm_kernel(const GemmParams p) {
             // lane byte offsets of the MFMA fragments inside one stage (see lds_read_frag_k32 /
             // lds_read_frag_nmajor for the layouts they mirror)
             const int r31 = lane & 31, hi = lane >> 5, sw = (r31 >> 2) & 3;
-            const unsigned vA0 = (unsigned)((wm0 + r31) * 64 + ((hi ^ sw) << 4));
-            const unsigned vA1 = (unsigned)((wm0 + r31) * 64 + (((2 + hi) ^ sw) << 4));
+            const unsigned vA0 = lds0 + (unsigned)((wm0 + r31) * 64 + ((hi ^ sw) << 4));
+            const unsigned vA1 = lds0 + (unsigned)((wm0 + r31) * 64 + (((2 + hi) ^ sw) << 4));
             unsigned vB[4];
             if constexpr (!NN) {
-                vB[0] = (unsigned)(TT::A_STAGE + (wn0 + r31) * 64 + ((hi ^ sw) << 4));
-                vB[1] = (unsigned)(TT::A_STAGE + (wn0 + r31) * 64 + (((2 + hi) ^ sw) << 4));
+                vB[0] = lds0 + (unsigned)(TT::A_STAGE + (wn0 + r31) * 64 + ((hi ^ sw) << 4));
+                vB[1] = lds0 + (unsigned)(TT::A_STAGE + (wn0 + r31) * 64 + (((2 + hi) ^ sw) << 4));
                 vB[2] = vB[3] = 0u;
             } else {
                 const int g = lane >> 4, jj = lane & 15, kk = (jj >> 2) & 3;
                 const int krow = ((g >> 1) << 3) + (jj >> 2), c2 = ((g & 1) << 1) + ((jj & 3) >> 1);
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    vB[j] = (unsigned)(TT::A_STAGE + krow * (BN * 2) + (((wn0 >> 3) + ((j ^ kk) << 2) + c2) << 4) + ((jj & 1) << 3));
+                    vB[j] = lds0 + (unsigned)(TT::A_STAGE + krow * (BN * 2) + (((wn0 >> 3) + ((j ^ kk) << 2) + c2) << 4) + ((jj & 1) << 3));
             }
             const unsigned ab0 = a_off[0] * 2u, ab1 = a_off[1] * 2u, ab2 = a_off[2] * 2u, ab3 = a_off[3] * 2u;
             const unsigned bb0 = b_off[0] * 2u, bb1 = b_off[1] * 2u, bb2 = b_off[2] * 2u, bb3 = b_off[3] * 2u;
@@ -336,7 +369,7 @@ symb_gemm_kernel(const GemmParams p) {
             const unsigned long long ga = (unsigned long long)a_tile, gb = (unsigned long long)b_tile;
 #endif
             const unsigned stride_b = NN ? 64u * (unsigned)p.N : 64u;
-            const unsigned swa = (unsigned)__builtin_amdgcn_readfirstlane(wave) * 4096u;
+            const unsigned swa = (unsigned)__builtin_amdgcn_readfirstlane((int)lds0 + wave * 4096);
 #define SYMB_GEMM_LOOP_OPERANDS                                                                                     \
     : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]), "+a"(acc[1][0]), "+a"(acc[1][1]),       \
       "+a"(acc[1][2]), "+a"(acc[1][3]), "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),       \
@@ -345,7 +378,7 @@ symb_gemm_kernel(const GemmParams p) {
       "v"(bb0), "v"(bb1), "v"(bb2), "v"(bb3), "s"(ga), "s"(gb), "s"(stride_b), "s"(KF), "s"(swa)                   \
     : SYMB_GEMM_LOOP_CLOBBERS
 #ifdef SYMB_GEMM_TRACE
-            if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 4 + 1] = __builtin_amdgcn_s_memrealtime();
+            if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 8 + 1] = __builtin_amdgcn_s_memrealtime();
 #endif
             if constexpr (NN) asm volatile(SYMB_GEMM_LOOP_NN SYMB_GEMM_LOOP_OPERANDS);
 #ifdef SYMB_GEMM_PROBE
@@ -356,7 +389,7 @@ symb_gemm_kernel(const GemmParams p) {
 #undef SYMB_GEMM_LOOP_OPERANDS
             __builtin_amdgcn_s_barrier();                      // everything landed and read before LDS is reused
 #ifdef SYMB_GEMM_TRACE
-            if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 4 + 2] = __builtin_amdgcn_s_memrealtime();
+            if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 8 + 2] = __builtin_amdgcn_s_memrealtime();
 #endif
         }
     } else if (KF > 0) {
@@ -366,7 +399,7 @@ symb_gemm_kernel(const GemmParams p) {
         __builtin_amdgcn_s_barrier();
         load_frags32(0, 0, 0);
 #ifdef SYMB_GEMM_TRACE
-        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 4 + 1] = __builtin_amdgcn_s_memrealtime();
+        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 8 + 1] = __builtin_amdgcn_s_memrealtime();
 #endif
         int stage = 0;
         for (int kt = 0; kt < KF; ++kt) {
@@ -385,18 +418,21 @@ symb_gemm_kernel(const GemmParams p) {
         __builtin_amdgcn_s_waitcnt(0);                         // everything landed before LDS is reused
         __builtin_amdgcn_s_barrier();
 #ifdef SYMB_GEMM_TRACE
-        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 4 + 2] = __builtin_amdgcn_s_memrealtime();
+        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 8 + 2] = __builtin_amdgcn_s_memrealtime();
 #endif
     }
     if (KF * GEMM_SK < p.K) {
         gload_tail(KF * GEMM_SK);
         lds_store(0);
         __syncthreads();
-        compute(0, (p.K - KF * GEMM_SK + 15) >> 4);
+        compute((p.K - KF * GEMM_SK + 15) >> 4);
         __syncthreads();
     }
 
-    // ---- bias, optional store of the pre-adapter output
+    // ---- output staging.  A lane owns 4 consecutive columns of 32 different rows; stored directly
+    // that is 32 partial lines per instruction, so the bf16 tile goes through LDS and leaves as
+    // whole 512-byte rows.  The accumulators are only read here: bias and the IA3 scale of each
+    // row's own segment are applied on the way out, then one rounding to bf16.
     const int seg_lo = p.tile_seg_lo[tm], seg_hi = p.tile_seg_hi[tm];
     auto for_each_quad = [&](auto&& fn) __attribute__((always_inline)) {
         // fn(i, j, rg, m, n): this lane holds acc[i][j][rg*4 .. rg*4+3] = C[m][n .. n+3]
@@ -412,26 +448,60 @@ symb_gemm_kernel(const GemmParams p) {
                 }
         }
     };
-    if (p.bias) {
-        for_each_quad([&](int i, int j, int rg, int, int n) __attribute__((always_inline)) {
-            if (n < p.N) {
-                const uint2 bv = *reinterpret_cast<const uint2*>(p.bias + n);
-                acc[i][j][rg * 4 + 0] += bf16_bits_to_f32((unsigned short)(bv.x & 0xffffu));
-                acc[i][j][rg * 4 + 1] += bf16_bits_to_f32((unsigned short)(bv.x >> 16));
-                acc[i][j][rg * 4 + 2] += bf16_bits_to_f32((unsigned short)(bv.y & 0xffffu));
-                acc[i][j][rg * 4 + 3] += bf16_bits_to_f32((unsigned short)(bv.y >> 16));
-            }
-        });
-    }
-    if (p.Cbase) {
-        for_each_quad([&](int i, int j, int rg, int m, int n) __attribute__((always_inline)) {
-            if (m < p.M && n < p.N) {
+    constexpr int CP = TT::C_PITCH;                  // bytes per staged row (BN * 2 + 16: bank spread)
+    auto stage_out = [&](bf16* __restrict__ dst, bool scale_ia3) __attribute__((always_inline)) {
+        if (!p.bias && !scale_ia3) {
+            for_each_quad([&](int i, int j, int rg, int m, int n) __attribute__((always_inline)) {
                 uint2 o;
                 o.x = pack2_bf16(acc[i][j][rg * 4 + 0], acc[i][j][rg * 4 + 1]);
                 o.y = pack2_bf16(acc[i][j][rg * 4 + 2], acc[i][j][rg * 4 + 3]);
-                *reinterpret_cast<uint2*>(p.Cbase + (size_t)m * p.N + n) = o;
-            }
-        });
+                *reinterpret_cast<uint2*>(smem + (m - m0) * CP + (n - n0) * 2) = o;
+            });
+        } else {
+            for_each_quad([&](int i, int j, int rg, int m, int n) __attribute__((always_inline)) {
+                float v0 = acc[i][j][rg * 4 + 0], v1 = acc[i][j][rg * 4 + 1];
+                float v2 = acc[i][j][rg * 4 + 2], v3 = acc[i][j][rg * 4 + 3];
+                if (m < p.M && n < p.N) {
+                    if (p.bias) {
+                        const uint2 bv = *reinterpret_cast<const uint2*>(p.bias + n);
+                        v0 += bf16_bits_to_f32((unsigned short)(bv.x & 0xffffu));
+                        v1 += bf16_bits_to_f32((unsigned short)(bv.x >> 16));
+                        v2 += bf16_bits_to_f32((unsigned short)(bv.y & 0xffffu));
+                        v3 += bf16_bits_to_f32((unsigned short)(bv.y >> 16));
+                    }
+                    if (scale_ia3) {
+                        const int s = seg_of_row(p.off, seg_lo, seg_hi, m);
+                        if (p.seg[s].kind == KIND_IA3) {
+                            const uint2 lv = *reinterpret_cast<const uint2*>(p.seg[s].A + n);
+                            v0 *= bf16_bits_to_f32((unsigned short)(lv.x & 0xffffu));
+                            v1 *= bf16_bits_to_f32((unsigned short)(lv.x >> 16));
+                            v2 *= bf16_bits_to_f32((unsigned short)(lv.y & 0xffffu));
+                            v3 *= bf16_bits_to_f32((unsigned short)(lv.y >> 16));
+                        }
+                    }
+                }
+                uint2 o;
+                o.x = pack2_bf16(v0, v1);
+                o.y = pack2_bf16(v2, v3);
+                *reinterpret_cast<uint2*>(smem + (m - m0) * CP + (n - n0) * 2) = o;
+            });
+        }
+        __syncthreads();
+        constexpr int LPR = BN / 8;                  // lanes per row (16 bytes each)
+        constexpr int RPI = 64 / LPR;                // rows per store instruction
+        const int col = (lane % LPR) * 8;
+#pragma unroll 4
+        for (int r = wave * RPI + lane / LPR; r < BM; r += (NT / 64) * RPI) {
+            const int m = m0 + r, n = n0 + col;
+            if (m < p.M && n < p.N)
+                *reinterpret_cast<uint4*>(dst + (size_t)m * p.N + n) = *reinterpret_cast<const uint4*>(smem + r * CP + col * 2);
+        }
+    };
+
+    // ---- optional store of the pre-adapter output (accumulator + bias, before the LoRA term)
+    if (p.Cbase) {
+        stage_out(p.Cbase, false);
+        __syncthreads();                             // LDS is reused by the LoRA tiles below
     }
 
     // ---- LoRA term: extra K-steps per LoRA segment that meets this row tile
@@ -480,51 +550,21 @@ symb_gemm_kernel(const GemmParams p) {
                 }
                 lds_store(0);
                 __syncthreads();
-                compute(0, min(BK, kext - kc0) >> 4);
+                compute(min(BK, kext - kc0) >> 4);
                 __syncthreads();
             }
         }
     }
 
-    // ---- epilogue: IA3 scale of each row's own segment and one rounding to bf16 in registers,
-    // then the tile goes through LDS so that every store instruction writes whole rows: a lane
-    // owns 4 consecutive columns of 32 different rows, which as direct stores is 32 partial
-    // lines per instruction; after the transpose it is two full 512-byte rows.
-    constexpr int CP = TT::C_PITCH;                  // bytes per staged row (BN * 2 + 16: bank spread)
-    for_each_quad([&](int i, int j, int rg, int m, int n) __attribute__((always_inline)) {
-        float v0 = acc[i][j][rg * 4 + 0], v1 = acc[i][j][rg * 4 + 1];
-        float v2 = acc[i][j][rg * 4 + 2], v3 = acc[i][j][rg * 4 + 3];
-        if (p.epi_ia3 && m < p.M && n < p.N) {
-            const int s = seg_of_row(p.off, seg_lo, seg_hi, m);
-            if (p.seg[s].kind == KIND_IA3) {
-                const uint2 lv = *reinterpret_cast<const uint2*>(p.seg[s].A + n);
-                v0 *= bf16_bits_to_f32((unsigned short)(lv.x & 0xffffu));
-                v1 *= bf16_bits_to_f32((unsigned short)(lv.x >> 16));
-                v2 *= bf16_bits_to_f32((unsigned short)(lv.y & 0xffffu));
-                v3 *= bf16_bits_to_f32((unsigned short)(lv.y >> 16));
-            }
-        }
-        uint2 o;
-        o.x = pack2_bf16(v0, v1);
-        o.y = pack2_bf16(v2, v3);
-        *reinterpret_cast<uint2*>(smem + (m - m0) * CP + (n - n0) * 2) = o;
-    });
-    __syncthreads();
-    {
-        constexpr int LPR = BN / 8;                  // lanes per row (16 bytes each)
-        constexpr int RPI = 64 / LPR;                // rows per store instruction
-        constexpr int NW = NT / 64;
-        const int col = (lane % LPR) * 8;
-#pragma unroll 4
-        for (int r = wave * RPI + lane / LPR; r < BM; r += NW * RPI) {
-            const int m = m0 + r, n = n0 + col;
-            if (m < p.M && n < p.N)
-                *reinterpret_cast<uint4*>(p.C + (size_t)m * p.N + n) = *reinterpret_cast<const uint4*>(smem + r * CP + col * 2);
-        }
-    }
 #ifdef SYMB_GEMM_TRACE
+    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 8 + 4] = __builtin_amdgcn_s_memrealtime();
+#endif
+    // ---- final output: bias, IA3 scale, one rounding, whole-row stores
+    stage_out(p.C, p.epi_ia3 != 0);
+#ifdef SYMB_GEMM_TRACE
+    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 8 + 7] = __builtin_amdgcn_s_memrealtime();
     __builtin_amdgcn_s_waitcnt(0);
-    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 4 + 3] = __builtin_amdgcn_s_memrealtime();
+    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 8 + 3] = __builtin_amdgcn_s_memrealtime();
 #endif
 }
 

@@ -186,6 +186,25 @@ def build(nn, no_loads=False, no_reads=False):
     return L
 
 
+def build_kstep64(nn):
+    """One 16-wide k-step on a register-staged 64-k tile (K remainder, LoRA term): read the
+    eight fragments, wait, 16 MFMAs.  Operands: %0-%15 accumulators, %16 A fragment address,
+    %17 (K-contiguous W) or %17-%20 (N-contiguous W, one per 32-column block) B addresses."""
+    L = []
+    for i in range(4):
+        L.append(f"ds_read_b128 {fa(0, i)}, %16 offset:{4096 * i}")
+    if not nn:
+        for j in range(4):
+            L.append(f"ds_read_b128 {fb(0, j)}, %17 offset:{4096 * j}")
+    else:
+        for j in range(4):
+            for h in range(2):
+                L.append(f"ds_read_b64_tr_b16 {fb_half(0, j, h)}, %{17 + j} offset:{2048 * h}")
+    L.append("s_waitcnt lgkmcnt(0)")
+    L += [mfma(0, i, j) for i in range(4) for j in range(4)]
+    return L
+
+
 def emit(name, lines):
     out = [f"#define {name} \\"]
     for l in lines:
@@ -210,6 +229,10 @@ def main():
 {emit("SYMB_GEMM_LOOP_NT", build(False))}
 
 {emit("SYMB_GEMM_LOOP_NN", build(True))}
+
+{emit("SYMB_GEMM_KSTEP64_NT", build_kstep64(False))}
+
+{emit("SYMB_GEMM_KSTEP64_NN", build_kstep64(True))}
 
 #ifdef SYMB_GEMM_PROBE   // tuning builds only: the same loop without its in-loop global loads / LDS reads
 {emit("SYMB_GEMM_LOOP_NT_NOLOAD", build(False, no_loads=True))}
