@@ -50,7 +50,7 @@ def step(runs, stream):
         r.fwd(stream)
     for r in runs:
         r.bwd_input(stream)
-        r.adapter_grad(stream)
+        r.adapter_grad(stream, reuse_dh=True)     # same batch, same dY: dH is still in the workspace
 
 
 def cpu_baseline(cfg: str, budget_s: float = 20.0) -> dict:

@@ -17,7 +17,7 @@ struct RowChunk {
 // value plus a bf16 residual (out[t][rpad_i + p])
 //   forward shrink : L = X  [T][K=d_in],  R_i = A_i  [r][d_in]
 //   backward dH    : L = dY [T][K=d_out], R_i = B_i^T packed [rpad][d_out] (see pack kernel)
-// A workgroup owns 16 rows; its 4 wavefronts split K in interleaved 64-element steps, read
+// A workgroup owns 32 rows; its 4 wavefronts split K in interleaved 128-element steps, read
 // MFMA fragments straight from global memory (each row is read as whole 128-byte lines, the
 // adapter rows come from L2), and meet in LDS for the final sum.  RB = max rank blocks of 16.
 // -------------------------------------------------------------------------------------------
@@ -32,63 +32,116 @@ struct SkinnyParams {
     int use_packed;
 };
 
+constexpr int SKINNY_ROWS = 32;     // rows per workgroup (two 16-row MFMA blocks per wavefront)
+
 template <int RB>
 __global__ void __launch_bounds__(256)
 symb_skinny_kernel(const SkinnyParams p) {
-    __shared__ float red[4][16][RB * 16 + 4];
+    __shared__ float red[3][SKINNY_ROWS][RB * 16 + 4];   // partial sums of wavefronts 1..3
     const RowChunk ch = p.chunks[blockIdx.x];
     const SegDesc sd = p.seg[ch.seg];
     const int nb = sd.rpad >> 4;                         // rank blocks in use (uniform)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int trow = lane & 15, kq = lane >> 4;
-    const bool row_ok = trow < ch.nrows;
-    const bf16* lrow = p.L + (size_t)(ch.row0 + (row_ok ? trow : 0)) * p.K;
+    // rows past the chunk are clamped onto its last row; their results are never stored
+    const bf16* lrow[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) lrow[b] = p.L + (size_t)(ch.row0 + min(b * 16 + trow, ch.nrows - 1)) * p.K + kq * 8;
     const bf16* rbase = p.use_packed ? (p.packed + p.packed_off[ch.seg]) : sd.A;
-    const int rrows = p.use_packed ? sd.rpad : sd.rank;  // valid adapter rows
+    const int rrows = p.use_packed ? sd.rpad : sd.rank;  // valid adapter rows; the rest count as zero
+    const bf16* rrow[RB];
+    bool r_ok[RB];
+#pragma unroll
+    for (int j = 0; j < RB; ++j) {
+        r_ok[j] = (j * 16 + trow) < rrows;
+        rrow[j] = rbase + (size_t)(r_ok[j] ? (j * 16 + trow) : 0) * p.K + kq * 8;
+    }
 
-    floatx4 acc[RB];
+    floatx4 acc[2][RB];
 #pragma unroll
-    for (int j = 0; j < RB; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int j = 0; j < RB; ++j) acc[b][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    for (int k0 = wave * 64; k0 < p.K; k0 += 256) {
+    // Each wavefront takes every 4th 128-element slice of K (256 bytes per row per step); all
+    // loads of a step are issued before its MFMAs so several KiB per wavefront are in flight.
+    const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
+    int k0 = wave * 128;
+    for (; k0 + 128 <= p.K; k0 += 512) {
+        uint4 lv[2][4], rv[RB][4];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int k = k0 + h * 32 + kq * 8;
-            const bool kok = k < p.K;
-            uint4 lv = make_uint4(0u, 0u, 0u, 0u);
-            if (row_ok && kok) lv = *reinterpret_cast<const uint4*>(lrow + k);
-            const bf16x8 lf = __builtin_bit_cast(bf16x8, lv);
+        for (int h = 0; h < 4; ++h) {
 #pragma unroll
-            for (int j = 0; j < RB; ++j) {
+            for (int b = 0; b < 2; ++b) lv[b][h] = *reinterpret_cast<const uint4*>(lrow[b] + k0 + h * 32);
+#pragma unroll
+            for (int j = 0; j < RB; ++j)
+                if (j < nb) rv[j][h] = *reinterpret_cast<const uint4*>(rrow[j] + k0 + h * 32);
+        }
+#pragma unroll
+        for (int h = 0; h < 4; ++h)
+#pragma unroll
+            for (int j = 0; j < RB; ++j)
                 if (j < nb) {
-                    const int pr = j * 16 + trow;
-                    uint4 rv = make_uint4(0u, 0u, 0u, 0u);
-                    if (pr < rrows && kok) rv = *reinterpret_cast<const uint4*>(rbase + (size_t)pr * p.K + k);
-                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rv), lf, acc[j], 0, 0, 0);
+                    const bf16x8 rf = __builtin_bit_cast(bf16x8, r_ok[j] ? rv[j][h] : zero4);
+#pragma unroll
+                    for (int b = 0; b < 2; ++b)
+                        acc[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rf, __builtin_bit_cast(bf16x8, lv[b][h]), acc[b][j], 0, 0, 0);
                 }
-            }
+    }
+    for (; k0 < p.K; k0 += 512) {                        // the slice that crosses the end of K
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            const bool kok = (k0 + h * 32 + kq * 8) < p.K;
+            uint4 lv[2];
+#pragma unroll
+            for (int b = 0; b < 2; ++b) lv[b] = kok ? *reinterpret_cast<const uint4*>(lrow[b] + k0 + h * 32) : zero4;
+#pragma unroll
+            for (int j = 0; j < RB; ++j)
+                if (j < nb) {
+                    const uint4 rv = (kok && r_ok[j]) ? *reinterpret_cast<const uint4*>(rrow[j] + k0 + h * 32) : zero4;
+#pragma unroll
+                    for (int b = 0; b < 2; ++b)
+                        acc[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rv), __builtin_bit_cast(bf16x8, lv[b]), acc[b][j], 0, 0, 0);
+                }
         }
     }
-    // lane holds out[t = trow][p = j*16 + 4*kq + q]
+    // lane holds out[t = b*16 + trow][p = j*16 + 4*kq + q]
+    if (wave > 0) {
 #pragma unroll
-    for (int j = 0; j < RB; ++j)
-        if (j < nb)
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) red[wave][trow][j * 16 + kq * 4 + q] = acc[j][q];
+            for (int j = 0; j < RB; ++j)
+                if (j < nb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) red[wave - 1][b * 16 + trow][j * 16 + kq * 4 + q] = acc[b][j][q];
+    }
     __syncthreads();
     // One row of `out` holds, for its own segment, rpad values rounded to bf16 followed by the
-    // rpad rounding residuals (also bf16): hi + lo carries ~16 significand bits into the GEMM.
-    const int npairs = 16 * (sd.rpad >> 1);
-    for (int e = tid; e < npairs; e += 256) {
-        const int t = e / (sd.rpad >> 1), pp = (e % (sd.rpad >> 1)) * 2;
-        if (t < ch.nrows) {
-            const float v0 = sd.scale * (red[0][t][pp] + red[1][t][pp] + red[2][t][pp] + red[3][t][pp]);
-            const float v1 = sd.scale * (red[0][t][pp + 1] + red[1][t][pp + 1] + red[2][t][pp + 1] + red[3][t][pp + 1]);
-            const unsigned short h0 = f32_to_bf16_bits(v0), h1 = f32_to_bf16_bits(v1);
-            bf16* row = p.out + (size_t)(ch.row0 + t) * p.out_pitch;
-            *reinterpret_cast<unsigned int*>(row + pp) = (unsigned int)h0 | ((unsigned int)h1 << 16);
-            *reinterpret_cast<unsigned int*>(row + sd.rpad + pp) =
-                pack2_bf16(v0 - bf16_bits_to_f32(h0), v1 - bf16_bits_to_f32(h1));
+    // rpad rounding residuals (also bf16): value + residual carries ~16 significand bits on.
+    if (wave == 0) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int t = b * 16 + trow;
+            if (t < ch.nrows) {
+                bf16* row = p.out + (size_t)(ch.row0 + t) * p.out_pitch;
+#pragma unroll
+                for (int j = 0; j < RB; ++j)
+                    if (j < nb) {
+                        const int pp = j * 16 + kq * 4;
+                        float v[4];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            v[q] = sd.scale * (acc[b][j][q] + red[0][t][pp + q] + red[1][t][pp + q] + red[2][t][pp + q]);
+                        const unsigned h01 = pack2_bf16(v[0], v[1]), h23 = pack2_bf16(v[2], v[3]);
+                        uint2 hi2, lo2;
+                        hi2.x = h01;
+                        hi2.y = h23;
+                        lo2.x = pack2_bf16(v[0] - bf16_bits_to_f32((unsigned short)(h01 & 0xffffu)), v[1] - bf16_bits_to_f32((unsigned short)(h01 >> 16)));
+                        lo2.y = pack2_bf16(v[2] - bf16_bits_to_f32((unsigned short)(h23 & 0xffffu)), v[3] - bf16_bits_to_f32((unsigned short)(h23 >> 16)));
+                        *reinterpret_cast<uint2*>(row + pp) = hi2;
+                        *reinterpret_cast<uint2*>(row + sd.rpad + pp) = lo2;
+                    }
+            }
         }
     }
 }

@@ -26,7 +26,7 @@ thread_local std::string g_tls_error;
 
 constexpr int kSlots = 4;                       // descriptor ring depth
 constexpr size_t kSlotBytes = (size_t)2 << 20;  // capacity of one descriptor blob
-constexpr int kSkinnyRows = 16;                 // rows per skinny / scale work item
+constexpr int kSkinnyRows = SKINNY_ROWS;        // rows per skinny / scale work item
 constexpr int kMaxTimed = 4096;                 // GEMM launches recorded between two timing reads
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -188,10 +188,10 @@ WsLayout ws_layout(const symb_batch* b, const BatchInfo& bi, int op, bool full_b
         }
         if (full_bwd && bi.n_ia3) take(w.sc_off, w.sc_bytes, (size_t)bi.T * b->d_out * 2);
     } else {
-        if (any_lora_grad) {
-            take(w.h_off, w.h_bytes, hb);
+        if (any_lora_grad) {      // dH first, at the offset the input-gradient call leaves it (SYMB_GRAD_REUSE_DH)
             take(w.dh_off, w.dh_bytes, hb);
             take(w.pk_off, w.pk_bytes, bi.packed_elems * 2);
+            take(w.h_off, w.h_bytes, hb);
         }
     }
     w.total = cur;
@@ -658,14 +658,15 @@ symb_status symb_adapter_grad(symb_handle h, const symb_batch* b, const void* X,
     symb_status st = check_handle(h);
     if (st != SYMB_OK) return st;
     if ((st = validate(h, b)) != SYMB_OK) return st;
-    if (flags != SYMB_GRAD_OVERWRITE && flags != SYMB_GRAD_ACCUMULATE) return fail(h, SYMB_ERR_INVALID_ARG, "unknown gradient flag %u", flags);
+    if (flags & ~(uint32_t)(SYMB_GRAD_ACCUMULATE | SYMB_GRAD_REUSE_DH)) return fail(h, SYMB_ERR_INVALID_ARG, "unknown gradient flag %u", flags);
+    const bool reuse_dh = (flags & SYMB_GRAD_REUSE_DH) != 0;
     const BatchInfo bi = inspect(b);
     if (!X || !dY) {
         if (bi.T > 0) return fail(h, SYMB_ERR_INVALID_ARG, "X and dY are required");
     }
     if (misaligned16(X) || misaligned16(dY) || misaligned16(Ybase) || misaligned16(ws))
         return fail(h, SYMB_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
-    const bool acc = flags == SYMB_GRAD_ACCUMULATE;
+    const bool acc = (flags & SYMB_GRAD_ACCUMULATE) != 0;
     hipStream_t s = (hipStream_t)stream;
 
     // Which segments want which gradient.  Empty segments: zeros when overwriting, nothing otherwise.
@@ -752,20 +753,22 @@ symb_status symb_adapter_grad(symb_handle h, const symb_batch* b, const void* X,
         if ((st = launch_grad<true>(h, gp, (int)want_b.size(), grad_max_rpad, s)) != SYMB_OK) return st;
     }
     if (!want_a.empty()) {       // dA_i = dH_i^T X_i
-        PackParams pp{dseg, (bf16*)(wsb + wl.pk_off), (const int64_t*)(dev + o_pk), b->d_out};
-        hipLaunchKernelGGL(symb_pack_bt_kernel, dim3((b->d_out + 255) / 256, bi.S), dim3(256), 0, s, pp);
-        SYMB_HIP(h, hipGetLastError());
-        SkinnyParams sp{};
-        sp.L = (const bf16*)dY;
-        sp.out = (bf16*)(wsb + wl.dh_off);
-        sp.K = b->d_out;
-        sp.out_pitch = 2 * bi.max_rpad;
-        sp.chunks = (const RowChunk*)(dev + o_chd);
-        sp.seg = dseg;
-        sp.packed = (const bf16*)(wsb + wl.pk_off);
-        sp.packed_off = (const int64_t*)(dev + o_pk);
-        sp.use_packed = 1;
-        if ((st = launch_skinny(h, sp, (int)ch_dh.size(), grad_max_rpad, s)) != SYMB_OK) return st;
+        if (!reuse_dh) {
+            PackParams pp{dseg, (bf16*)(wsb + wl.pk_off), (const int64_t*)(dev + o_pk), b->d_out};
+            hipLaunchKernelGGL(symb_pack_bt_kernel, dim3((b->d_out + 255) / 256, bi.S), dim3(256), 0, s, pp);
+            SYMB_HIP(h, hipGetLastError());
+            SkinnyParams sp{};
+            sp.L = (const bf16*)dY;
+            sp.out = (bf16*)(wsb + wl.dh_off);
+            sp.K = b->d_out;
+            sp.out_pitch = 2 * bi.max_rpad;
+            sp.chunks = (const RowChunk*)(dev + o_chd);
+            sp.seg = dseg;
+            sp.packed = (const bf16*)(wsb + wl.pk_off);
+            sp.packed_off = (const int64_t*)(dev + o_pk);
+            sp.use_packed = 1;
+            if ((st = launch_skinny(h, sp, (int)ch_dh.size(), grad_max_rpad, s)) != SYMB_OK) return st;
+        }
         GradParams gp{(const bf16*)X, (const bf16*)(wsb + wl.dh_off), b->d_in, 2 * bi.max_rpad, doff, dseg,
                       (const int32_t*)(dev + o_wa), acc ? 1 : 0};
         if ((st = launch_grad<false>(h, gp, (int)want_a.size(), grad_max_rpad, s)) != SYMB_OK) return st;

@@ -102,6 +102,7 @@ class ProjectionRun:
     # -- the three calls -----------------------------------------------------------------------
     def fwd(self, stream: int = 0) -> None:
         sb.symb_base_linear_fwd(self.h, self.fwd_batch, self.X, self.W, self.bias, self.Y, self.Ybase, self.ws, stream)
+        self._dh_in_ws = False
 
     def sync_saved_output(self) -> None:
         """What a client does between forward and backward: keep its rows of the base output."""
@@ -110,9 +111,14 @@ class ProjectionRun:
 
     def bwd_input(self, stream: int = 0, flags: int = sb.SYMB_BWD_FULL) -> None:
         sb.symb_base_linear_bwd_input(self.h, self.bwd_batch, self.dY, self.W, self.dX, flags, self.ws, stream)
+        self._dh_in_ws = flags == sb.SYMB_BWD_FULL
 
-    def adapter_grad(self, stream: int = 0, flags: int = sb.SYMB_GRAD_OVERWRITE) -> None:
+    def adapter_grad(self, stream: int = 0, flags: int = sb.SYMB_GRAD_OVERWRITE, reuse_dh: bool = False) -> None:
+        """reuse_dh: the workspace still holds dH from the bwd_input call just before (same batch, same dY)."""
+        if reuse_dh and getattr(self, "_dh_in_ws", False):
+            flags |= sb.SYMB_GRAD_REUSE_DH
         sb.symb_adapter_grad(self.h, self.bwd_batch, self.Xb, self.dY, self.Ybase_b, flags, self.ws, stream)
+        self._dh_in_ws = False
 
     # -- algorithmic work (flops) ----------------------------------------------------------------
     def flops(self) -> dict:

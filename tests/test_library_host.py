@@ -111,7 +111,7 @@ def test_workspace_bytes_formula():
     packed = (16 + 48) * 128 * 2
     assert sb.symb_workspace_bytes(b, sb.SYMB_OP_FWD) == up(T * rp * 2)
     assert sb.symb_workspace_bytes(b, sb.SYMB_OP_BWD_INPUT) == up(T * rp * 2) + up(packed) + up(T * 128 * 2)
-    assert sb.symb_workspace_bytes(b, sb.SYMB_OP_ADAPTER_GRAD) == 2 * up(T * rp * 2) + up(packed)
+    assert sb.symb_workspace_bytes(b, sb.SYMB_OP_ADAPTER_GRAD) == 2 * up(T * rp * 2) + up(packed)   # dH, packed B^T, Hs
     none = sb.Batch(64, 128, [0, 100], [sb.Adapter()])
     for op in (sb.SYMB_OP_FWD, sb.SYMB_OP_BWD_INPUT, sb.SYMB_OP_ADAPTER_GRAD):
         assert sb.symb_workspace_bytes(none, op) == 0
