@@ -102,6 +102,20 @@ def cpu_baseline(cfg: str, budget_s: float = 20.0) -> dict:
             "seconds": total_t}
 
 
+def measured_traffic(variant: int):
+    """HBM bytes per launch of the dominant GEMM kernel, from the rocprofv3 --pmc summary
+    committed under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy); None if absent."""
+    path = os.path.join(ROOT, "profiles", "cfg4_gemm_hbm_traffic.txt")
+    key = "traffic_bytes_per_launch_nn:" if variant else "traffic_bytes_per_launch_nt:"
+    try:
+        for line in open(path):
+            if line.startswith(key):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,6 +124,8 @@ def main() -> int:
     ap.add_argument("--config", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -128,6 +144,13 @@ def main() -> int:
     print(f"[bench] {wl.name}: T={wl.T} S={len(wl.clients)} projections={[r.name for r in runs]} "
           f"inputs generated+uploaded in {t_gen:.1f}s", file=sys.stderr, flush=True)
 
+    if args.copy_probe:     # a plain copy of known size: 1 GiB read + 1 GiB written per launch
+        src = torch.empty(1 << 29, device="cuda", dtype=torch.bfloat16).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for r in runs:          # one untimed pass materialises saved outputs where IA3 gradients need them
         r.fwd(stream)
         r.sync_saved_output()
@@ -190,7 +213,7 @@ def main() -> int:
             "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4),
             "avg_launch_ms": round(avg_ms, 4),
             "launches": n_launch,
-            "traffic": None,
+            "traffic": measured_traffic(dom),
         },
     }
     if not args.no_cpu_baseline:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "libsymb.so")
 SOURCES = [os.path.join(HERE, "csrc", "symb_api.hip")]
 DEPS = SOURCES + [os.path.join(HERE, "csrc", f) for f in
-                  ("gemm_kernel.hpp", "adapter_kernels.hpp", "symb_device.hpp")] + \
+                  ("gemm_kernel.hpp", "gemm_mainloop_asm.hpp", "adapter_kernels.hpp", "symb_device.hpp")] + \
     [os.path.join(os.path.dirname(HERE), "include", "symb.h")]
 
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-shared", "-fPIC",
@@ -42,5 +42,18 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+def build_ceiling() -> str:
+    """Compiles the stand-alone MFMA ceiling measurement (csrc/mfma_ceiling.hip)."""
+    out = os.path.join(HERE, "mfma_ceiling")
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    subprocess.check_call([hipcc, "-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+                           "-packed-fp32-ops", "-o", out, os.path.join(HERE, "csrc", "mfma_ceiling.hip")],
+                          stderr=subprocess.DEVNULL)
+    return out
+
+
 if __name__ == "__main__":
-    print(build(force=True, verbose=True))
+    if "--ceiling" in sys.argv:
+        print(build_ceiling())
+    else:
+        print(build(force=True, verbose=True))
