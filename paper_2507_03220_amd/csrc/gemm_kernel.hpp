@@ -42,7 +42,7 @@ struct GemmParams {
     int stagger;                // start delay unit (s_sleep 127 each) between the 8 phase groups of the first wave of tiles
     double timing_flops;        // host bookkeeping for the measurement hook; unused on the device
 #ifdef SYMB_GEMM_TRACE
-    unsigned long long* trace;  // tuning builds only: 4 timestamps per tile
+    unsigned long long* trace;  // tuning builds only: 16 timestamp slots per tile
 #endif
 #ifdef SYMB_GEMM_PROBE
     int probe;                  // tuning builds only: 1 = no in-loop global loads, 2 = nor LDS reads
@@ -69,11 +69,15 @@ struct GemmTile {
     static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
     static constexpr int A_STAGE = BM * GEMM_SK * 2, B_STAGE = BN * GEMM_SK * 2, STAGE_BYTES = A_STAGE + B_STAGE;
     static constexpr int C_PITCH = BN * 2 + 16, C_BYTES = BM * C_PITCH;     // epilogue staging of the bf16 tile
-    static constexpr int SMEM_IN = (2 * (A_BYTES + B_BYTES) > GEMM_NSTAGE * STAGE_BYTES) ? 2 * (A_BYTES + B_BYTES) : GEMM_NSTAGE * STAGE_BYTES;
-    static constexpr int SMEM = SMEM_IN > C_BYTES ? SMEM_IN : C_BYTES;
     static constexpr int CA = BM * 8 / NT, CB = BN * 8 / NT;   // 16-byte chunks per thread per K-step
-    // 256x256 with 4 wavefronts: the hand-scheduled assembly main loop (gemm_mainloop_asm.hpp)
+    // 256x256 with 4 wavefronts: the hand-scheduled assembly main loop (gemm_mainloop_asm.hpp),
+    // 64-k stages of 32 KiB per operand, three A units and two B units = all 160 KiB of LDS
     static constexpr bool ASM_LOOP = (BM == 256 && BN == 256 && WGM == 2 && WGN == 2);
+    static constexpr int SK = ASM_LOOP ? 64 : GEMM_SK;         // k per main-loop stage
+    static constexpr int UNIT = 32768, B_UNIT0 = 3 * UNIT;      // assembly loop: unit size, first B unit
+    static constexpr int SMEM_RING = ASM_LOOP ? 5 * UNIT : GEMM_NSTAGE * STAGE_BYTES;
+    static constexpr int SMEM_IN = (2 * (A_BYTES + B_BYTES) > SMEM_RING) ? 2 * (A_BYTES + B_BYTES) : SMEM_RING;
+    static constexpr int SMEM = SMEM_IN > C_BYTES ? SMEM_IN : C_BYTES;
     static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tile must be made of 32x32 blocks");
     static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0, "tile chunks must divide over the threads");
 };
@@ -150,10 +154,12 @@ symb_gemm_kernel(const GemmParams p) {
         for (int i = 0; i < phase * p.stagger; ++i) __builtin_amdgcn_s_sleep(127);
     }
 #ifdef SYMB_GEMM_TRACE
-    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 8 + 0] = __builtin_amdgcn_s_memrealtime();
+    if (p.trace && threadIdx.x == 0) { p.trace[(size_t)lin * 16 + 0] = __builtin_amdgcn_s_memrealtime(); p.trace[(size_t)lin * 16 + 5] = __builtin_readcyclecounter(); }
 #endif
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave / WGN) * TT::WTM, wn0 = (wave % WGN) * TT::WTN;
+    // segment range of this row tile, fetched now so that its latency hides under the main loop
+    const int seg_lo = p.tile_seg_lo[tm], seg_hi = p.tile_seg_hi[tm];
 
     floatx16 acc[MB][NB];
 #pragma unroll
@@ -341,44 +347,61 @@ symb_gemm_kernel(const GemmParams p) {
     constexpr int NS = GEMM_NSTAGE, LPS = AI + BI;             // loads per wavefront per stage
     constexpr int VM_STEADY = LPS * (NS - 2);                  // younger stages that may stay in flight
     static_assert(LPS * (NS - 1) < 64, "vmcnt is a 6-bit counter");
-    const int KF = p.K / GEMM_SK;                              // full stages
+    const int KF = p.K / TT::SK;                               // full stages
     if constexpr (TT::ASM_LOOP) {
         if (KF > 0) {
-            // lane byte offsets of the MFMA fragments inside one stage (see lds_read_frag_k32 /
-            // lds_read_frag_nmajor for the layouts they mirror)
-            const int r31 = lane & 31, hi = lane >> 5, sw = (r31 >> 2) & 3;
-            const unsigned vA0 = lds0 + (unsigned)((wm0 + r31) * 64 + ((hi ^ sw) << 4));
-            const unsigned vA1 = lds0 + (unsigned)((wm0 + r31) * 64 + (((2 + hi) ^ sw) << 4));
-            unsigned vB[4];
+            // Lane byte offsets of the MFMA fragments inside an operand's 64-k unit.  K-contiguous
+            // units use the layout of lds_off_kmajor, the N-contiguous weight unit that of
+            // lds_off_nmajor (read through the transposing LDS load, see lds_read_frag_nmajor).
+            const int r31 = lane & 31, hi = lane >> 5;
+            unsigned vA[4], vB[4];
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) vA[ks] = lds0 + (unsigned)lds_off_kmajor(wm0 + r31, ks * 2 + hi);
             if constexpr (!NN) {
-                vB[0] = lds0 + (unsigned)(TT::A_STAGE + (wn0 + r31) * 64 + ((hi ^ sw) << 4));
-                vB[1] = lds0 + (unsigned)(TT::A_STAGE + (wn0 + r31) * 64 + (((2 + hi) ^ sw) << 4));
-                vB[2] = vB[3] = 0u;
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) vB[ks] = lds0 + (unsigned)lds_off_kmajor(wn0 + r31, ks * 2 + hi);
             } else {
                 const int g = lane >> 4, jj = lane & 15, kk = (jj >> 2) & 3;
                 const int krow = ((g >> 1) << 3) + (jj >> 2), c2 = ((g & 1) << 1) + ((jj & 3) >> 1);
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    vB[j] = lds0 + (unsigned)(TT::A_STAGE + krow * (BN * 2) + (((wn0 >> 3) + ((j ^ kk) << 2) + c2) << 4) + ((jj & 1) << 3));
+                    vB[j] = lds0 + (unsigned)(krow * (BN * 2) + (((wn0 >> 3) + ((j ^ kk) << 2) + c2) << 4) + ((jj & 1) << 3));
             }
-            const unsigned ab0 = a_off[0] * 2u, ab1 = a_off[1] * 2u, ab2 = a_off[2] * 2u, ab3 = a_off[3] * 2u;
-            const unsigned bb0 = b_off[0] * 2u, bb1 = b_off[1] * 2u, bb2 = b_off[2] * 2u, bb3 = b_off[3] * 2u;
+            // Global byte offsets of this lane's eight loads per operand and stage.  One load
+            // instruction fills 1 KiB of consecutive LDS: 8 rows of a K-contiguous unit (8 lanes
+            // cover one whole 128-byte line) or 2 k-rows of the N-contiguous unit; the lane ->
+            // chunk map is the inverse of the LDS swizzle.  Rows / columns outside the problem
+            // are clamped onto the last valid one and never stored.
+            unsigned ab[8], bb[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int row = (wave * 8 + j) * 8 + (lane >> 3), kc = (lane & 7) ^ swz_row(row);
+                ab[j] = ((unsigned)(min(m0 + row, p.M - 1) - m0) * (unsigned)p.K + kc * 8) * 2u;
+                if constexpr (!NN) {
+                    bb[j] = ((unsigned)(min(n0 + row, p.N - 1) - n0) * (unsigned)p.K + kc * 8) * 2u;
+                } else {
+                    const int krow = (wave * 8 + j) * 2 + (lane >> 5), nc = (lane & 31) ^ ((krow & 3) << 2);
+                    bb[j] = ((unsigned)krow * (unsigned)p.N + (unsigned)min(nc * 8, p.N - 8 - n0)) * 2u;
+                }
+            }
 #ifdef SYMB_GEMM_PROBE
             const unsigned long long ga = (unsigned long long)(p.probe == 3 ? p.Aop : a_tile), gb = (unsigned long long)(p.probe == 3 ? p.Bop : b_tile);
 #else
             const unsigned long long ga = (unsigned long long)a_tile, gb = (unsigned long long)b_tile;
 #endif
-            const unsigned stride_b = NN ? 64u * (unsigned)p.N : 64u;
-            const unsigned swa = (unsigned)__builtin_amdgcn_readfirstlane((int)lds0 + wave * 4096);
+            const unsigned stride_b = NN ? 128u * (unsigned)p.N : 128u;
+            const unsigned swa = (unsigned)__builtin_amdgcn_readfirstlane((int)lds0 + wave * 8192);
 #define SYMB_GEMM_LOOP_OPERANDS                                                                                     \
     : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]), "+a"(acc[1][0]), "+a"(acc[1][1]),       \
       "+a"(acc[1][2]), "+a"(acc[1][3]), "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),       \
       "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3])                                           \
-    : "v"(vA0), "v"(vA1), "v"(vB[0]), "v"(vB[1]), "v"(vB[2]), "v"(vB[3]), "v"(ab0), "v"(ab1), "v"(ab2), "v"(ab3),  \
-      "v"(bb0), "v"(bb1), "v"(bb2), "v"(bb3), "s"(ga), "s"(gb), "s"(stride_b), "s"(KF), "s"(swa)                   \
+    : "v"(vA[0]), "v"(vA[1]), "v"(vA[2]), "v"(vA[3]), "v"(vB[0]), "v"(vB[1]), "v"(vB[2]), "v"(vB[3]),              \
+      "v"(ab[0]), "v"(ab[1]), "v"(ab[2]), "v"(ab[3]), "v"(ab[4]), "v"(ab[5]), "v"(ab[6]), "v"(ab[7]),              \
+      "v"(bb[0]), "v"(bb[1]), "v"(bb[2]), "v"(bb[3]), "v"(bb[4]), "v"(bb[5]), "v"(bb[6]), "v"(bb[7]),              \
+      "s"(ga), "s"(gb), "s"(stride_b), "s"(KF), "s"(swa)                                                           \
     : SYMB_GEMM_LOOP_CLOBBERS
 #ifdef SYMB_GEMM_TRACE
-            if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 8 + 1] = __builtin_amdgcn_s_memrealtime();
+            if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 1] = __builtin_amdgcn_s_memrealtime();
 #endif
             if constexpr (NN) asm volatile(SYMB_GEMM_LOOP_NN SYMB_GEMM_LOOP_OPERANDS);
 #ifdef SYMB_GEMM_PROBE
@@ -389,7 +412,7 @@ symb_gemm_kernel(const GemmParams p) {
 #undef SYMB_GEMM_LOOP_OPERANDS
             __builtin_amdgcn_s_barrier();                      // everything landed and read before LDS is reused
 #ifdef SYMB_GEMM_TRACE
-            if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 8 + 2] = __builtin_amdgcn_s_memrealtime();
+            if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 2] = __builtin_amdgcn_s_memrealtime();
 #endif
         }
     } else if (KF > 0) {
@@ -399,7 +422,7 @@ symb_gemm_kernel(const GemmParams p) {
         __builtin_amdgcn_s_barrier();
         load_frags32(0, 0, 0);
 #ifdef SYMB_GEMM_TRACE
-        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 8 + 1] = __builtin_amdgcn_s_memrealtime();
+        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 1] = __builtin_amdgcn_s_memrealtime();
 #endif
         int stage = 0;
         for (int kt = 0; kt < KF; ++kt) {
@@ -418,14 +441,14 @@ symb_gemm_kernel(const GemmParams p) {
         __builtin_amdgcn_s_waitcnt(0);                         // everything landed before LDS is reused
         __builtin_amdgcn_s_barrier();
 #ifdef SYMB_GEMM_TRACE
-        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 8 + 2] = __builtin_amdgcn_s_memrealtime();
+        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 2] = __builtin_amdgcn_s_memrealtime();
 #endif
     }
-    if (KF * GEMM_SK < p.K) {
-        gload_tail(KF * GEMM_SK);
+    if (KF * TT::SK < p.K) {
+        gload_tail(KF * TT::SK);
         lds_store(0);
         __syncthreads();
-        compute((p.K - KF * GEMM_SK + 15) >> 4);
+        compute((p.K - KF * TT::SK + 15) >> 4);
         __syncthreads();
     }
 
@@ -433,7 +456,6 @@ symb_gemm_kernel(const GemmParams p) {
     // that is 32 partial lines per instruction, so the bf16 tile goes through LDS and leaves as
     // whole 512-byte rows.  The accumulators are only read here: bias and the IA3 scale of each
     // row's own segment are applied on the way out, then one rounding to bf16.
-    const int seg_lo = p.tile_seg_lo[tm], seg_hi = p.tile_seg_hi[tm];
     auto for_each_quad = [&](auto&& fn) __attribute__((always_inline)) {
         // fn(i, j, rg, m, n): this lane holds acc[i][j][rg*4 .. rg*4+3] = C[m][n .. n+3]
 #pragma unroll
@@ -486,7 +508,13 @@ symb_gemm_kernel(const GemmParams p) {
                 *reinterpret_cast<uint2*>(smem + (m - m0) * CP + (n - n0) * 2) = o;
             });
         }
+#ifdef SYMB_GEMM_TRACE
+        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 8] = __builtin_amdgcn_s_memrealtime();
+#endif
         __syncthreads();
+#ifdef SYMB_GEMM_TRACE
+        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 9] = __builtin_amdgcn_s_memrealtime();
+#endif
         constexpr int LPR = BN / 8;                  // lanes per row (16 bytes each)
         constexpr int RPI = 64 / LPR;                // rows per store instruction
         const int col = (lane % LPR) * 8;
@@ -557,14 +585,14 @@ symb_gemm_kernel(const GemmParams p) {
     }
 
 #ifdef SYMB_GEMM_TRACE
-    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 8 + 4] = __builtin_amdgcn_s_memrealtime();
+    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 4] = __builtin_amdgcn_s_memrealtime();
 #endif
     // ---- final output: bias, IA3 scale, one rounding, whole-row stores
     stage_out(p.C, p.epi_ia3 != 0);
 #ifdef SYMB_GEMM_TRACE
-    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 8 + 7] = __builtin_amdgcn_s_memrealtime();
+    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 7] = __builtin_amdgcn_s_memrealtime();
     __builtin_amdgcn_s_waitcnt(0);
-    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 8 + 3] = __builtin_amdgcn_s_memrealtime();
+    if (p.trace && threadIdx.x == 0) { p.trace[(size_t)lin * 16 + 3] = __builtin_amdgcn_s_memrealtime(); p.trace[(size_t)lin * 16 + 6] = __builtin_readcyclecounter(); }
 #endif
 }
 

@@ -11,30 +11,38 @@ configuration shuffles accumulators between register files inside the loop.  Her
 accumulators are pinned ("+a" operands), the two fragment sets live in fixed registers,
 and every LDS read and global->LDS load is placed by hand between the MFMAs.
 
-Per iteration (one 32-k stage of a 4-deep LDS ring):
-  k-step 0: 16 MFMAs on fragment set F0 while the k-step-1 fragments of this stage
-            are read into F1;
-  wait for this wavefront's loads of the next stage, barrier (next stage complete for
-            everybody, this stage free);
-  k-step 1: 16 MFMAs on F1 while the next stage's k-step-0 fragments are read into F0
-            and the loads that refill this stage's buffer are issued.
+Why 64-k stages: the L2 serves one request per channel and clock whatever its size, so a
+K-contiguous operand loaded as 64-byte row pieces (32 k) costs twice the L2 cycles of
+whole 128-byte lines (64 k); with 256 CUs loading, half-line requests alone saturate the
+L2 at about the rate the matrix pipes consume.  A 64-k stage of one operand is a 32 KiB
+unit; 160 KiB of LDS hold a ring of three A units and two B units.
+
+Per iteration (one 64-k stage P, four 16-k steps, fragment sets F0/F1 alternating):
+  k-step 0,1: MFMAs while the next k-step's fragments are read; the eight loads of
+              A(P+2) go out, one per four MFMAs, into the unit freed by the previous barrier;
+  k-step 2:   MFMAs while the k-step-3 fragments are read (last reads of stage P); then wait
+              for this wavefront's loads of stage P+1, barrier (stage P+1 complete for
+              everybody, both units of stage P free);
+  k-step 3:   MFMAs while the first fragments of stage P+1 are read; the eight loads of
+              B(P+2) go out, one per two MFMAs, into B(P)'s unit.
 """
 import os
 
 F = {0: 192, 1: 224}          # first VGPR of fragment set 0 / 1 (A: 4x4 regs, then B: 4x4 regs)
 VT = 180                      # address temporaries v180..v187
-S_GA, S_GB, S_CNT, S_CUR, S_NXT, S_ADVA, S_T0, S_T1, S_T2, S_ADVB, S_WB, S_PRV = 80, 82, 84, 85, 86, 87, 88, 89, 90, 91, 92, 93
-STAGE_BYTES = 32768
-RING_MASK = 4 * STAGE_BYTES - 1
-A_STAGE = 16384
+S_GA, S_GB = 80, 82
+S_CNT, S_ACUR, S_ANXT, S_ANN, S_BCUR, S_BNXT, S_ADVA, S_ADVB, S_T0, S_T1, S_T2 = range(84, 95)
+UNIT = 32768                  # one operand's 64-k stage
+A_BASES = (0, UNIT, 2 * UNIT)
+B_BASES = (3 * UNIT, 4 * UNIT)
 
 # operand numbers
 ACC0 = 0
-VA = (16, 17)                 # A fragment lane offsets for k-step 0 / 1
-VB = (18, 19, 20, 21)         # NT: B lane offsets k-step 0 / 1 (20, 21 unused); NN: per n-block offsets
-AV = (22, 23, 24, 25)         # global byte offsets of this lane's 4 A loads
-BV = (26, 27, 28, 29)         # global byte offsets of this lane's 4 B loads
-GA, GB, STRIDE_B, KF, SWA = 30, 31, 32, 33, 34
+VA = (16, 17, 18, 19)         # A fragment lane offsets, k-step 0..3
+VB = (20, 21, 22, 23)         # NT: B lane offsets, k-step 0..3; NN: per 32-column block
+AV = tuple(range(24, 32))     # global byte offsets of this lane's 8 A loads
+BV = tuple(range(32, 40))     # global byte offsets of this lane's 8 B loads
+GA, GB, STRIDE_B, KF, SWA = 40, 41, 42, 43, 44
 
 
 def fa(s, i):
@@ -56,53 +64,51 @@ def mfma(s, i, j):
     return f"v_mfma_f32_32x32x16_bf16 %{ACC0 + 4 * i + j}, {fb(s, j)}, {fa(s, i)}, %{ACC0 + 4 * i + j}"
 
 
-def frag_reads(nn, dst, sbase, ks):
-    """Address setup + the LDS reads that fill fragment set `dst` from the stage at SGPR `sbase`."""
+def frag_reads(nn, dst, sa, sb, ks):
+    """Address setup + the LDS reads that fill fragment set `dst` with k-step `ks` of the stage
+    whose A / B units start at SGPR `sa` / `sb`."""
     setup, reads = [], []
-    setup.append(f"v_add_u32 v{VT}, s{sbase}, %{VA[ks]}")
+    setup.append(f"v_add_u32 v{VT}, s{sa}, %{VA[ks]}")
     for i in range(4):
-        reads.append(f"ds_read_b128 {fa(dst, i)}, v{VT} offset:{2048 * i}")
+        reads.append(f"ds_read_b128 {fa(dst, i)}, v{VT} offset:{4096 * i}")
     if not nn:
-        setup.append(f"v_add_u32 v{VT + 1}, s{sbase}, %{VB[ks]}")
+        setup.append(f"v_add_u32 v{VT + 1}, s{sb}, %{VB[ks]}")
         for j in range(4):
-            reads.append(f"ds_read_b128 {fb(dst, j)}, v{VT + 1} offset:{2048 * j}")
+            reads.append(f"ds_read_b128 {fb(dst, j)}, v{VT + 1} offset:{4096 * j}")
     else:
         for j in range(4):
-            setup.append(f"v_add_u32 v{VT + 1 + j}, s{sbase}, %{VB[j]}")
+            setup.append(f"v_add_u32 v{VT + 1 + j}, s{sb}, %{VB[j]}")
         for j in range(4):
             for h in range(2):
                 reads.append(f"ds_read_b64_tr_b16 {fb_half(dst, j, h)}, v{VT + 1 + j} offset:{8192 * ks + 2048 * h}")
     return setup, reads
 
 
-def half_issue(sdst, which):
-    """Four global->LDS loads (the A or the B half of one stage) into the buffer at SGPR `sdst`,
-    then the clamped advance of that operand's global base pointer."""
-    loads = []
+def unit_loads(sdst, which, js):
+    """global->LDS loads number `js` (of 8) of one operand's 64-k unit into the unit at SGPR `sdst`."""
+    V, G = (AV, S_GA) if which == "A" else (BV, S_GB)
+    return [[f"s_add_u32 s{S_T0}, s{sdst}, %{SWA}", f"s_add_u32 m0, s{S_T0}, {1024 * j}", "s_nop 0",
+             f"global_load_lds_dwordx4 %{V[j]}, s[{G}:{G + 1}]"] for j in js]
+
+
+def advance(which):
+    """Clamped advance of an operand's global base pointer to its next 64-k stage."""
     if which == "A":
-        for j in range(4):
-            pre = f"s_add_u32 m0, s{sdst}, %{SWA}" if j == 0 else "s_add_u32 m0, m0, 0x400"
-            loads.append([pre, "s_nop 0", f"global_load_lds_dwordx4 %{AV[j]}, s[{S_GA}:{S_GA + 1}]"])
-        adv = [f"s_cmp_lg_u32 s{S_ADVA}, 0",
-               f"s_cselect_b32 s{S_T0}, 64, 0",
-               f"s_cselect_b32 s{S_T2}, 1, 0",
-               f"s_add_u32 s{S_GA}, s{S_GA}, s{S_T0}", f"s_addc_u32 s{S_GA + 1}, s{S_GA + 1}, 0",
-               f"s_sub_u32 s{S_ADVA}, s{S_ADVA}, s{S_T2}"]
-    else:
-        for j in range(4):
-            pre = f"s_add_u32 m0, s{sdst}, s{S_WB}" if j == 0 else "s_add_u32 m0, m0, 0x400"
-            loads.append([pre, "s_nop 0", f"global_load_lds_dwordx4 %{BV[j]}, s[{S_GB}:{S_GB + 1}]"])
-        adv = [f"s_cmp_lg_u32 s{S_ADVB}, 0",
-               f"s_cselect_b32 s{S_T1}, %{STRIDE_B}, 0",
-               f"s_cselect_b32 s{S_T2}, 1, 0",
-               f"s_add_u32 s{S_GB}, s{S_GB}, s{S_T1}", f"s_addc_u32 s{S_GB + 1}, s{S_GB + 1}, 0",
-               f"s_sub_u32 s{S_ADVB}, s{S_ADVB}, s{S_T2}"]
-    return loads, adv
+        return [f"s_cmp_lg_u32 s{S_ADVA}, 0",
+                f"s_cselect_b32 s{S_T0}, 128, 0",
+                f"s_cselect_b32 s{S_T2}, 1, 0",
+                f"s_add_u32 s{S_GA}, s{S_GA}, s{S_T0}", f"s_addc_u32 s{S_GA + 1}, s{S_GA + 1}, 0",
+                f"s_sub_u32 s{S_ADVA}, s{S_ADVA}, s{S_T2}"]
+    return [f"s_cmp_lg_u32 s{S_ADVB}, 0",
+            f"s_cselect_b32 s{S_T1}, %{STRIDE_B}, 0",
+            f"s_cselect_b32 s{S_T2}, 1, 0",
+            f"s_add_u32 s{S_GB}, s{S_GB}, s{S_T1}", f"s_addc_u32 s{S_GB + 1}, s{S_GB + 1}, 0",
+            f"s_sub_u32 s{S_ADVB}, s{S_ADVB}, s{S_T2}"]
 
 
-def spread(mf, reads, loads):
-    """Reads go one (or two) per MFMA from the start; loads go one per 4 MFMAs so the vector
-    memory queue never backs up into the MFMA stream."""
+def spread(mf, reads, loads, every):
+    """Reads go one (or two) per MFMA from the start; loads go one per `every` MFMAs so the
+    vector memory queue never backs up into the MFMA stream."""
     out = []
     per = 2 if len(reads) > 8 else 1
     r = list(reads)
@@ -112,73 +118,54 @@ def spread(mf, reads, loads):
         for _ in range(per):
             if r:
                 out.append(r.pop(0))
-        if ld and k % 4 == 3:
+        if ld and k % every == every - 1:
             out.extend(ld.pop(0))
     assert not r and not ld
     return out
 
 
-def interleave(mf, others):
-    """One `other` group after each MFMA until they run out, then the remaining MFMAs."""
-    out = []
-    for k, m in enumerate(mf):
-        out.append(m)
-        if k < len(others):
-            o = others[k]
-            out.extend(o if isinstance(o, list) else [o])
-    for o in others[len(mf):]:
-        out.extend(o if isinstance(o, list) else [o])
-    return out
-
-
 def build(nn, no_loads=False, no_reads=False):
-    """Load issue order: A(0) B(0) A(1) B(1) A(2) B(2) A(3) in the prologue; iteration t issues
-    B(t+3) during k-step 0 (buffer freed by the previous barrier) and A(t+4) during k-step 1
-    (buffer freed by this iteration's barrier).  At iteration t's wait, stage t+1 must have
-    landed; four younger half-stages (16 loads) may still be in flight."""
+    """Load issue order: A(0) B(0) A(1) B(1) in the prologue; iteration P issues A(P+2) during
+    k-steps 0-1 and B(P+2) during k-step 3.  At iteration P's wait, stage P+1 must have landed;
+    the eight loads of A(P+2) may still be in flight."""
     L = []
     L += [f"s_mov_b64 s[{S_GA}:{S_GA + 1}], %{GA}", f"s_mov_b64 s[{S_GB}:{S_GB + 1}], %{GB}",
           f"s_mov_b32 s{S_CNT}, %{KF}", f"s_sub_u32 s{S_ADVA}, %{KF}, 1", f"s_sub_u32 s{S_ADVB}, %{KF}, 1",
-          f"s_add_u32 s{S_WB}, %{SWA}, {A_STAGE}", f"s_mov_b32 s{S_CUR}, 0"]
-    for t in range(4):
-        L.append(f"s_mov_b32 s{S_NXT}, {t * STAGE_BYTES}")
-        for which in ("A", "B") if t < 3 else ("A",):
-            loads, adv = half_issue(S_NXT, which)
-            for g in loads:
+          f"s_mov_b32 s{S_ACUR}, {A_BASES[0]}", f"s_mov_b32 s{S_ANXT}, {A_BASES[1]}", f"s_mov_b32 s{S_ANN}, {A_BASES[2]}",
+          f"s_mov_b32 s{S_BCUR}, {B_BASES[0]}", f"s_mov_b32 s{S_BNXT}, {B_BASES[1]}"]
+    for sa, sb in ((S_ACUR, S_BCUR), (S_ANXT, S_BNXT)):
+        for which, sd in (("A", sa), ("B", sb)):
+            for g in unit_loads(sd, which, range(8)):
                 L += g
-            L += adv
-    # s_prv: the buffer freed by the previous barrier (stage t+3 goes there); starts at stage 3's buffer
-    L += [f"s_mov_b32 s{S_NXT}, {STAGE_BYTES}", f"s_mov_b32 s{S_PRV}, {3 * STAGE_BYTES}", "s_waitcnt vmcnt(20)", "s_barrier"]
-    setup, reads = frag_reads(nn, 0, S_CUR, 0)
+            L += advance(which)
+    L += ["s_waitcnt vmcnt(16)", "s_barrier"]
+    setup, reads = frag_reads(nn, 0, S_ACUR, S_BCUR, 0)
     L += setup + reads + ["s_waitcnt lgkmcnt(0)"]
     # ---- loop
     L.append("1:")
-    setup, reads = frag_reads(nn, 1, S_CUR, 1)
-    loads, adv = half_issue(S_PRV, "B")
-    if no_reads:
-        reads = []
-    if no_loads:
-        loads = []
-    L += setup
-    mf = [mfma(0, i, j) for i in range(4) for j in range(4)]
-    L += spread(mf, reads, loads)
-    L += adv
-    L += ["s_waitcnt vmcnt(16) lgkmcnt(0)", "s_barrier"]
-    setup, reads = frag_reads(nn, 0, S_NXT, 0)
-    loads, adv = half_issue(S_CUR, "A")
-    if no_reads:
-        reads = []
-    if no_loads:
-        loads = []
-    L += setup
-    mf = [mfma(1, i, j) for i in range(4) for j in range(4)]
-    L += spread(mf, reads, loads)
-    L += adv
-    L += ["s_waitcnt lgkmcnt(0)",
-          f"s_mov_b32 s{S_PRV}, s{S_CUR}",
-          f"s_mov_b32 s{S_CUR}, s{S_NXT}",
-          f"s_add_u32 s{S_NXT}, s{S_NXT}, {STAGE_BYTES}",
-          f"s_and_b32 s{S_NXT}, s{S_NXT}, {RING_MASK}",
+    plan = [  # (MFMA set, fragments to read: (set, A unit, B unit, k-step), loads, one load per .. MFMAs, advance)
+        (0, (1, S_ACUR, S_BCUR, 1), unit_loads(S_ANN, "A", range(0, 4)), 4, None),
+        (1, (0, S_ACUR, S_BCUR, 2), unit_loads(S_ANN, "A", range(4, 8)), 4, "A"),
+        (0, (1, S_ACUR, S_BCUR, 3), [], 4, None),
+        (1, (0, S_ANXT, S_BNXT, 0), unit_loads(S_BCUR, "B", range(8)), 2, "B"),
+    ]
+    for ks, (mset, (dst, sa, sb, rks), loads, every, adv) in enumerate(plan):
+        setup, reads = frag_reads(nn, dst, sa, sb, rks)
+        if no_reads:
+            reads = []
+        if no_loads:
+            loads = []
+        L += setup
+        L += spread([mfma(mset, i, j) for i in range(4) for j in range(4)], reads, loads, every)
+        if adv:
+            L += advance(adv)
+        if ks == 2:
+            L += ["s_waitcnt vmcnt(8) lgkmcnt(0)", "s_barrier"]
+        else:
+            L += ["s_waitcnt lgkmcnt(0)"]
+    L += [f"s_mov_b32 s{S_T0}, s{S_ACUR}", f"s_mov_b32 s{S_ACUR}, s{S_ANXT}", f"s_mov_b32 s{S_ANXT}, s{S_ANN}",
+          f"s_mov_b32 s{S_ANN}, s{S_T0}",
+          f"s_mov_b32 s{S_T0}, s{S_BCUR}", f"s_mov_b32 s{S_BCUR}, s{S_BNXT}", f"s_mov_b32 s{S_BNXT}, s{S_T0}",
           f"s_sub_u32 s{S_CNT}, s{S_CNT}, 1",
           f"s_cmp_lg_u32 s{S_CNT}, 0",
           "s_cbranch_scc1 1b",
@@ -215,16 +202,17 @@ def emit(name, lines):
 
 def main():
     here = os.path.dirname(os.path.abspath(__file__))
-    clob = ['"memory"', '"scc"'] + [f'"s{r}"' for r in range(80, 94)] + [f'"v{r}"' for r in range(VT, 256)]
+    clob = ['"memory"', '"scc"'] + [f'"s{r}"' for r in range(80, 95)] + [f'"v{r}"' for r in range(VT, 256)]
     text = f"""// GENERATED by gen_gemm_mainloop.py -- do not edit by hand.
 // Main loop of the 256x256 / 4-wavefront base GEMM for gfx950 as inline-assembly templates.
-// Operands: %0-%15 accumulators (AGPR, i-major: block (i, j) is %(4i+j)); %16,%17 A fragment
-// lane offsets for k-step 0/1; %18-%21 B fragment lane offsets (K-contiguous W: k-step 0/1 in
-// %18,%19; N-contiguous W: one per 32-column block); %22-%25 / %26-%29 global byte offsets of
-// this lane's four A / four B loads per stage; %30,%31 global base of the A / B stage (64-bit
-// SGPR); %32 byte stride of B between stages; %33 number of 32-k stages (>= 1); %34 byte
-// offset of this wavefront's first A load inside a stage (wave * 4096).
-// Fixed registers: s80-s93, v{VT}-v255 (fragment sets at v{F[0]} and v{F[1]}).
+// Operands: %0-%15 accumulators (AGPR, i-major: block (i, j) is %(4i+j)); %16-%19 A fragment
+// lane offsets for k-step 0..3 inside an A unit; %20-%23 B fragment lane offsets inside a B unit
+// (K-contiguous W: k-step 0..3; N-contiguous W: one per 32-column block); %24-%31 / %32-%39
+// global byte offsets of this lane's eight A / eight B loads per stage; %40,%41 global base of
+// the A / B stage (64-bit SGPR); %42 byte stride of B between stages; %43 number of 64-k stages
+// (>= 1); %44 LDS byte address of the dynamic segment + this wavefront's first load inside a
+// unit (wave * 8192).  LDS: A units at 0/32/64 KiB, B units at 96/128 KiB of the segment.
+// Fixed registers: s80-s94, v{VT}-v255 (fragment sets at v{F[0]} and v{F[1]}).
 #pragma once
 {emit("SYMB_GEMM_LOOP_NT", build(False))}
 
