@@ -39,6 +39,7 @@ struct GemmParams {
                                 // then rpad residuals of the row's own segment; null = no LoRA term
     int ext_pitch;
     int epi_ia3;                // forward: scale rows of IA3 segments by l_i[n]
+    int walk;                   // 0: each XCD walks one contiguous run of tiles; 1: rounds of 32 tiles dealt to the XCDs in turn
     int stagger;                // start delay unit (s_sleep 127 each) between the 8 phase groups of the first wave of tiles
     double timing_flops;        // host bookkeeping for the measurement hook; unused on the device
 #ifdef SYMB_GEMM_TRACE
@@ -133,9 +134,18 @@ symb_gemm_kernel(const GemmParams p) {
     // ---- tile of this workgroup: consecutive workgroup ids go to different XCDs, so give every
     // XCD one contiguous run of tiles, walked in groups of group_m row tiles per column tile.
     const int total = p.num_m_tiles * p.num_n_tiles;
-    const int per_xcd = (total + 7) >> 3;
-    const int lin = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (lin >= total || (int)(blockIdx.x >> 3) >= per_xcd) return;
+    int lin;
+    if (p.walk == 1) {
+        // rounds of 32 tiles (one per CU of an XCD) dealt to the XCDs in turn: the eight XCDs work
+        // on neighbouring 8x4 blocks of the same row-tile group at the same time
+        const int k = blockIdx.x >> 3;
+        lin = (((k >> 5) << 3) + (blockIdx.x & 7)) * 32 + (k & 31);
+        if (lin >= total) return;
+    } else {
+        const int per_xcd = (total + 7) >> 3;
+        lin = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+        if (lin >= total || (int)(blockIdx.x >> 3) >= per_xcd) return;
+    }
 #ifdef SYMB_GEMM_PROBE
     if (p.probe == 4 && (blockIdx.x & 7) != 0) return;     // tuning: only one XCD works
 #endif

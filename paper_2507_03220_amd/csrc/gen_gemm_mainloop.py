@@ -32,6 +32,7 @@ F = {0: 192, 1: 224}          # first VGPR of fragment set 0 / 1 (A: 4x4 regs, t
 VT = 180                      # address temporaries v180..v187
 S_GA, S_GB = 80, 82
 S_CNT, S_ACUR, S_ANXT, S_ANN, S_BCUR, S_BNXT, S_ADVA, S_ADVB, S_T0, S_T1, S_T2 = range(84, 95)
+LOAD_MOD = (" " + os.environ["SYMB_GEN_LOAD_MOD"]) if os.environ.get("SYMB_GEN_LOAD_MOD") else ""   # tuning: cache policy bits
 UNIT = 32768                  # one operand's 64-k stage
 A_BASES = (0, UNIT, 2 * UNIT)
 B_BASES = (3 * UNIT, 4 * UNIT)
@@ -88,7 +89,7 @@ def unit_loads(sdst, which, js):
     """global->LDS loads number `js` (of 8) of one operand's 64-k unit into the unit at SGPR `sdst`."""
     V, G = (AV, S_GA) if which == "A" else (BV, S_GB)
     return [[f"s_add_u32 s{S_T0}, s{sdst}, %{SWA}", f"s_add_u32 m0, s{S_T0}, {1024 * j}", "s_nop 0",
-             f"global_load_lds_dwordx4 %{V[j]}, s[{G}:{G + 1}]"] for j in js]
+             f"global_load_lds_dwordx4 %{V[j]}, s[{G}:{G + 1}]" + LOAD_MOD] for j in js]
 
 
 def advance(which):

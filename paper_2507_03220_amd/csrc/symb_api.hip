@@ -277,8 +277,12 @@ symb_status launch_gemm_t(symb_handle h, GemmParams gp, hipStream_t st) {
 #ifdef SYMB_GEMM_TRACE
     { const char* e = getenv("SYMB_TRACE_PTR"); gp.trace = e ? (unsigned long long*)strtoull(e, nullptr, 0) : nullptr; }
 #endif
+    {
+        static const int walk = [] { const char* e = getenv("SYMB_GEMM_WALK"); return e ? atoi(e) : 0; }();
+        gp.walk = walk;
+    }
     const int total = gp.num_m_tiles * gp.num_n_tiles;
-    const int grid = ((total + 7) / 8) * 8;
+    const int grid = gp.walk == 1 ? ((total + 255) / 256) * 256 : ((total + 7) / 8) * 8;
     const bool timed = h->timing && (int)h->timed.size() < kMaxTimed;
     const size_t slot = h->timed.size();
     if (timed) SYMB_HIP(h, hipEventRecord(h->tev[2 * slot], st));
