@@ -122,7 +122,16 @@ __device__ __forceinline__ uint4 ld_global_16(const bf16* p, bool ok) {
     return v;
 }
 
-template <int BM, int BN, int WGM, int WGN, bool NN>
+// Accumulator operands of the assembly templates (4-wavefront 256x256 tile), i-major.
+#define SYMB_ACC16(P)                                                                                              \
+    P "a"(acc[0][0]), P "a"(acc[0][1]), P "a"(acc[0][2]), P "a"(acc[0][3]), P "a"(acc[1][0]), P "a"(acc[1][1]),      \
+    P "a"(acc[1][2]), P "a"(acc[1][3]), P "a"(acc[2][0]), P "a"(acc[2][1]), P "a"(acc[2][2]), P "a"(acc[2][3]),      \
+    P "a"(acc[3][0]), P "a"(acc[3][1]), P "a"(acc[3][2]), P "a"(acc[3][3])
+
+// PLAIN: no bias, no IA3 scale, no pre-adapter output (checked by the host).  The plain
+// instantiation contains no arithmetic on the accumulators outside the matrix instructions, so
+// they never leave the accumulation registers before the staging loop reads them one by one.
+template <int BM, int BN, int WGM, int WGN, bool NN, bool PLAIN = false>
 __global__ void __launch_bounds__(WGM * WGN * 64)
 symb_gemm_kernel(const GemmParams p) {
     using TT = GemmTile<BM, BN, WGM, WGN, NN>;
@@ -191,14 +200,20 @@ symb_gemm_kernel(const GemmParams p) {
     const int b_lds0 = NN ? lds_off_nmajor<BN>(nn_k, nn_nc) : a_lds0;
 
     uint4 ra[CA], rb[CB];
-    auto lds_store = [&](int buf) __attribute__((always_inline)) {
+    auto lds_store_a = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < CA; ++i) *reinterpret_cast<uint4*>(sA + buf * TT::A_BYTES + a_lds0 + i * RSTEP * 128) = ra[i];
+    };
+    auto lds_store_b = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < CB; ++i) {
             if constexpr (!NN) *reinterpret_cast<uint4*>(sB + buf * TT::B_BYTES + b_lds0 + i * RSTEP * 128) = rb[i];
             else *reinterpret_cast<uint4*>(sB + buf * TT::B_BYTES + b_lds0 + i * KSTEP * (BN * 2)) = rb[i];
         }
+    };
+    auto lds_store = [&](int buf) __attribute__((always_inline)) {
+        lds_store_a(buf);
+        lds_store_b(buf);
     };
 
     // ---- main-loop staging: global memory -> LDS directly (no registers), NSTAGE stages of SK = 32
@@ -314,13 +329,9 @@ symb_gemm_kernel(const GemmParams p) {
             const int r31 = lane & 31, hi = lane >> 5;
             for (int ks = 0; ks < nks; ++ks) {
                 const unsigned va = lds0 + (unsigned)lds_off_kmajor(wm0 + r31, ks * 2 + hi);
-#define SYMB_ACC16                                                                                                 \
-    "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]), "+a"(acc[1][0]), "+a"(acc[1][1]),          \
-    "+a"(acc[1][2]), "+a"(acc[1][3]), "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),          \
-    "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3])
                 if constexpr (!NN) {
                     const unsigned vb = lds0 + 2 * TT::A_BYTES + (unsigned)lds_off_kmajor(wn0 + r31, ks * 2 + hi);
-                    asm volatile(SYMB_GEMM_KSTEP64_NT : SYMB_ACC16 : "v"(va), "v"(vb) : SYMB_GEMM_LOOP_CLOBBERS);
+                    asm volatile(SYMB_GEMM_KSTEP64_NT : SYMB_ACC16("+") : "v"(va), "v"(vb) : SYMB_GEMM_LOOP_CLOBBERS);
                 } else {
                     const int g = lane >> 4, jj = lane & 15;
                     const int k = ks * 16 + ((g >> 1) << 3) + (jj >> 2);
@@ -330,10 +341,9 @@ symb_gemm_kernel(const GemmParams p) {
                         const int n = wn0 + j * 32 + ((g & 1) << 4) + ((jj & 3) << 2);
                         vb[j] = lds0 + 2 * TT::A_BYTES + (unsigned)lds_off_nmajor<BN>(k, n >> 3) + ((n & 7) << 1);
                     }
-                    asm volatile(SYMB_GEMM_KSTEP64_NN : SYMB_ACC16 : "v"(va), "v"(vb[0]), "v"(vb[1]), "v"(vb[2]), "v"(vb[3])
+                    asm volatile(SYMB_GEMM_KSTEP64_NN : SYMB_ACC16("+") : "v"(va), "v"(vb[0]), "v"(vb[1]), "v"(vb[2]), "v"(vb[3])
                                  : SYMB_GEMM_LOOP_CLOBBERS);
                 }
-#undef SYMB_ACC16
             }
         } else {
 #pragma unroll
@@ -402,9 +412,7 @@ symb_gemm_kernel(const GemmParams p) {
             const unsigned stride_b = NN ? 128u * (unsigned)p.N : 128u;
             const unsigned swa = (unsigned)__builtin_amdgcn_readfirstlane((int)lds0 + wave * 8192);
 #define SYMB_GEMM_LOOP_OPERANDS                                                                                     \
-    : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]), "+a"(acc[1][0]), "+a"(acc[1][1]),       \
-      "+a"(acc[1][2]), "+a"(acc[1][3]), "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),       \
-      "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3])                                           \
+    : SYMB_ACC16("+")                                                                                              \
     : "v"(vA[0]), "v"(vA[1]), "v"(vA[2]), "v"(vA[3]), "v"(vB[0]), "v"(vB[1]), "v"(vB[2]), "v"(vB[3]),              \
       "v"(ab[0]), "v"(ab[1]), "v"(ab[2]), "v"(ab[3]), "v"(ab[4]), "v"(ab[5]), "v"(ab[6]), "v"(ab[7]),              \
       "v"(bb[0]), "v"(bb[1]), "v"(bb[2]), "v"(bb[3]), "v"(bb[4]), "v"(bb[5]), "v"(bb[6]), "v"(bb[7]),              \
@@ -482,14 +490,27 @@ symb_gemm_kernel(const GemmParams p) {
     };
     constexpr int CP = TT::C_PITCH;                  // bytes per staged row (BN * 2 + 16: bank spread)
     auto stage_out = [&](bf16* __restrict__ dst, bool scale_ia3) __attribute__((always_inline)) {
-        if (!p.bias && !scale_ia3) {
+        if (PLAIN || (!p.bias && !scale_ia3)) {
             for_each_quad([&](int i, int j, int rg, int m, int n) __attribute__((always_inline)) {
+                float v0, v1, v2, v3;
+                if constexpr (TT::ASM_LOOP) {
+                    // read the four accumulation registers here and now: left to the compiler, all 256
+                    // are copied out ahead of the loop, which needs more registers than there are
+                    asm volatile("v_accvgpr_read_b32 %0, %4\n\tv_accvgpr_read_b32 %1, %5\n\t"
+                                 "v_accvgpr_read_b32 %2, %6\n\tv_accvgpr_read_b32 %3, %7"
+                                 : "=v"(v0), "=v"(v1), "=v"(v2), "=v"(v3)
+                                 : "a"(acc[i][j][rg * 4 + 0]), "a"(acc[i][j][rg * 4 + 1]), "a"(acc[i][j][rg * 4 + 2]),
+                                   "a"(acc[i][j][rg * 4 + 3]));
+                } else {
+                    v0 = acc[i][j][rg * 4 + 0]; v1 = acc[i][j][rg * 4 + 1];
+                    v2 = acc[i][j][rg * 4 + 2]; v3 = acc[i][j][rg * 4 + 3];
+                }
                 uint2 o;
-                o.x = pack2_bf16(acc[i][j][rg * 4 + 0], acc[i][j][rg * 4 + 1]);
-                o.y = pack2_bf16(acc[i][j][rg * 4 + 2], acc[i][j][rg * 4 + 3]);
+                o.x = pack2_bf16(v0, v1);
+                o.y = pack2_bf16(v2, v3);
                 *reinterpret_cast<uint2*>(smem + (m - m0) * CP + (n - n0) * 2) = o;
             });
-        } else {
+        } else if constexpr (!PLAIN) {
             for_each_quad([&](int i, int j, int rg, int m, int n) __attribute__((always_inline)) {
                 float v0 = acc[i][j][rg * 4 + 0], v1 = acc[i][j][rg * 4 + 1];
                 float v2 = acc[i][j][rg * 4 + 2], v3 = acc[i][j][rg * 4 + 3];
@@ -537,9 +558,11 @@ symb_gemm_kernel(const GemmParams p) {
     };
 
     // ---- optional store of the pre-adapter output (accumulator + bias, before the LoRA term)
-    if (p.Cbase) {
-        stage_out(p.Cbase, false);
-        __syncthreads();                             // LDS is reused by the LoRA tiles below
+    if constexpr (!PLAIN) {
+        if (p.Cbase) {
+            stage_out(p.Cbase, false);
+            __syncthreads();                         // LDS is reused by the LoRA tiles below
+        }
     }
 
     // ---- LoRA term: extra K-steps per LoRA segment that meets this row tile
@@ -557,6 +580,7 @@ symb_gemm_kernel(const GemmParams p) {
                     const bool ok = m >= r_lo && m < r_hi && (kc0 + kc * 8) < kext;
                     ra[i] = ld_global_16(p.ext + (size_t)(ok ? m : 0) * p.ext_pitch + kc0 + kc * 8, ok);
                 }
+                if constexpr (TT::ASM_LOOP) lds_store_a(0);    // one operand at a time: fewer registers live at once
                 // adapter-side tile
 #pragma unroll
                 for (int i = 0; i < CB; ++i) {
@@ -586,7 +610,8 @@ symb_gemm_kernel(const GemmParams p) {
                         rb[i] = ld_global_16(sd.A + (size_t)(ok ? pp : 0) * p.N + (ok ? n : 0), ok);
                     }
                 }
-                lds_store(0);
+                if constexpr (TT::ASM_LOOP) lds_store_b(0);
+                else lds_store(0);
                 __syncthreads();
                 compute(min(BK, kext - kc0) >> 4);
                 __syncthreads();

@@ -31,7 +31,7 @@ import os
 F = {0: 192, 1: 224}          # first VGPR of fragment set 0 / 1 (A: 4x4 regs, then B: 4x4 regs)
 VT = 180                      # address temporaries v180..v187
 S_GA, S_GB = 80, 82
-S_CNT, S_ACUR, S_ANXT, S_ANN, S_BCUR, S_BNXT, S_ADVA, S_ADVB, S_T0, S_T1, S_T2 = range(84, 95)
+S_CNT, S_ACUR, S_ANXT, S_ANN, S_BCUR, S_BNXT, S_T0, S_T1 = range(84, 92)
 LOAD_MOD = (" " + os.environ["SYMB_GEN_LOAD_MOD"]) if os.environ.get("SYMB_GEN_LOAD_MOD") else ""   # tuning: cache policy bits
 UNIT = 32768                  # one operand's 64-k stage
 A_BASES = (0, UNIT, 2 * UNIT)
@@ -44,6 +44,13 @@ VB = (20, 21, 22, 23)         # NT: B lane offsets, k-step 0..3; NN: per 32-colu
 AV = tuple(range(24, 32))     # global byte offsets of this lane's 8 A loads
 BV = tuple(range(32, 40))     # global byte offsets of this lane's 8 B loads
 GA, GB, STRIDE_B, KF, SWA = 40, 41, 42, 43, 44
+
+
+# The compiler does not look inside an assembly statement: whatever it places right after one
+# (a copy out of an accumulation register, say) must not meet a matrix instruction that is still
+# writing its result.  Every template therefore ends with more wait states than the longest
+# matrix-result hazard needs.
+MFMA_DRAIN = ["s_nop 15", "s_nop 7"]
 
 
 def fa(s, i):
@@ -92,19 +99,17 @@ def unit_loads(sdst, which, js):
              f"global_load_lds_dwordx4 %{V[j]}, s[{G}:{G + 1}]" + LOAD_MOD] for j in js]
 
 
-def advance(which):
-    """Clamped advance of an operand's global base pointer to its next 64-k stage."""
-    if which == "A":
-        return [f"s_cmp_lg_u32 s{S_ADVA}, 0",
-                f"s_cselect_b32 s{S_T0}, 128, 0",
-                f"s_cselect_b32 s{S_T2}, 1, 0",
-                f"s_add_u32 s{S_GA}, s{S_GA}, s{S_T0}", f"s_addc_u32 s{S_GA + 1}, s{S_GA + 1}, 0",
-                f"s_sub_u32 s{S_ADVA}, s{S_ADVA}, s{S_T2}"]
-    return [f"s_cmp_lg_u32 s{S_ADVB}, 0",
-            f"s_cselect_b32 s{S_T1}, %{STRIDE_B}, 0",
-            f"s_cselect_b32 s{S_T2}, 1, 0",
-            f"s_add_u32 s{S_GB}, s{S_GB}, s{S_T1}", f"s_addc_u32 s{S_GB + 1}, s{S_GB + 1}, 0",
-            f"s_sub_u32 s{S_ADVB}, s{S_ADVB}, s{S_T2}"]
+def advance(which, cond=None):
+    """Moves an operand's global base pointer to its next 64-k stage; with `cond` only if
+    KF > cond (the prologue must not run past a one-stage problem)."""
+    G, step = (S_GA, "128") if which == "A" else (S_GB, f"%{STRIDE_B}")
+    if cond is None:
+        pre = [f"s_mov_b32 s{S_T1}, {step}"] if which == "B" else []
+        src = f"s{S_T1}" if which == "B" else step
+        return pre + [f"s_add_u32 s{G}, s{G}, {src}", f"s_addc_u32 s{G + 1}, s{G + 1}, 0"]
+    return [f"s_cmp_gt_u32 %{KF}, {cond}",
+            f"s_cselect_b32 s{S_T1}, {step}, 0",
+            f"s_add_u32 s{G}, s{G}, s{S_T1}", f"s_addc_u32 s{G + 1}, s{G + 1}, 0"]
 
 
 def spread(mf, reads, loads, every):
@@ -125,25 +130,17 @@ def spread(mf, reads, loads, every):
     return out
 
 
-def build(nn, no_loads=False, no_reads=False):
-    """Load issue order: A(0) B(0) A(1) B(1) in the prologue; iteration P issues A(P+2) during
-    k-steps 0-1 and B(P+2) during k-step 3.  At iteration P's wait, stage P+1 must have landed;
-    the eight loads of A(P+2) may still be in flight."""
+def rotate():
+    return [f"s_mov_b32 s{S_T0}, s{S_ACUR}", f"s_mov_b32 s{S_ACUR}, s{S_ANXT}", f"s_mov_b32 s{S_ANXT}, s{S_ANN}",
+            f"s_mov_b32 s{S_ANN}, s{S_T0}",
+            f"s_mov_b32 s{S_T0}, s{S_BCUR}", f"s_mov_b32 s{S_BCUR}, s{S_BNXT}", f"s_mov_b32 s{S_BNXT}, s{S_T0}"]
+
+
+def body(nn, loads_on, last, no_reads=False):
+    """One 64-k stage P.  loads_on: issue A(P+2) and B(P+2) (steady state; the stage exists);
+    otherwise nothing younger than stage P+1 is in flight at the wait.  last: no next stage,
+    so no wait, no barrier and no fragment reads in k-step 3."""
     L = []
-    L += [f"s_mov_b64 s[{S_GA}:{S_GA + 1}], %{GA}", f"s_mov_b64 s[{S_GB}:{S_GB + 1}], %{GB}",
-          f"s_mov_b32 s{S_CNT}, %{KF}", f"s_sub_u32 s{S_ADVA}, %{KF}, 1", f"s_sub_u32 s{S_ADVB}, %{KF}, 1",
-          f"s_mov_b32 s{S_ACUR}, {A_BASES[0]}", f"s_mov_b32 s{S_ANXT}, {A_BASES[1]}", f"s_mov_b32 s{S_ANN}, {A_BASES[2]}",
-          f"s_mov_b32 s{S_BCUR}, {B_BASES[0]}", f"s_mov_b32 s{S_BNXT}, {B_BASES[1]}"]
-    for sa, sb in ((S_ACUR, S_BCUR), (S_ANXT, S_BNXT)):
-        for which, sd in (("A", sa), ("B", sb)):
-            for g in unit_loads(sd, which, range(8)):
-                L += g
-            L += advance(which)
-    L += ["s_waitcnt vmcnt(16)", "s_barrier"]
-    setup, reads = frag_reads(nn, 0, S_ACUR, S_BCUR, 0)
-    L += setup + reads + ["s_waitcnt lgkmcnt(0)"]
-    # ---- loop
-    L.append("1:")
     plan = [  # (MFMA set, fragments to read: (set, A unit, B unit, k-step), loads, one load per .. MFMAs, advance)
         (0, (1, S_ACUR, S_BCUR, 1), unit_loads(S_ANN, "A", range(0, 4)), 4, None),
         (1, (0, S_ACUR, S_BCUR, 2), unit_loads(S_ANN, "A", range(4, 8)), 4, "A"),
@@ -152,25 +149,56 @@ def build(nn, no_loads=False, no_reads=False):
     ]
     for ks, (mset, (dst, sa, sb, rks), loads, every, adv) in enumerate(plan):
         setup, reads = frag_reads(nn, dst, sa, sb, rks)
-        if no_reads:
-            reads = []
-        if no_loads:
-            loads = []
+        if no_reads or (last and ks == 3):
+            setup, reads = [], []
+        if not loads_on:
+            loads, adv = [], None
         L += setup
         L += spread([mfma(mset, i, j) for i in range(4) for j in range(4)], reads, loads, every)
         if adv:
             L += advance(adv)
-        if ks == 2:
-            L += ["s_waitcnt vmcnt(8) lgkmcnt(0)", "s_barrier"]
-        else:
+        if ks == 2 and not last:
+            L += [f"s_waitcnt vmcnt({8 if loads_on else 0}) lgkmcnt(0)", "s_barrier"]
+        elif not (last and ks == 3):
             L += ["s_waitcnt lgkmcnt(0)"]
-    L += [f"s_mov_b32 s{S_T0}, s{S_ACUR}", f"s_mov_b32 s{S_ACUR}, s{S_ANXT}", f"s_mov_b32 s{S_ANXT}, s{S_ANN}",
-          f"s_mov_b32 s{S_ANN}, s{S_T0}",
-          f"s_mov_b32 s{S_T0}, s{S_BCUR}", f"s_mov_b32 s{S_BCUR}, s{S_BNXT}", f"s_mov_b32 s{S_BNXT}, s{S_T0}",
-          f"s_sub_u32 s{S_CNT}, s{S_CNT}, 1",
-          f"s_cmp_lg_u32 s{S_CNT}, 0",
-          "s_cbranch_scc1 1b",
-          "s_waitcnt vmcnt(0)"]
+    return L
+
+
+def build(nn, no_loads=False, no_reads=False):
+    """Load issue order: A(0) B(0) A(1) B(1) in the prologue; steady iteration P (P <= KF-3)
+    issues A(P+2) during k-steps 0-1 and B(P+2) during k-step 3, and at its wait stage P+1 must
+    have landed while the eight loads of A(P+2) may still be in flight.  The last two stages run
+    a copy of the body without loads, so nothing is fetched twice and nothing is in flight when
+    the loop ends."""
+    L = []
+    L += [f"s_mov_b64 s[{S_GA}:{S_GA + 1}], %{GA}", f"s_mov_b64 s[{S_GB}:{S_GB + 1}], %{GB}",
+          f"s_sub_u32 s{S_CNT}, %{KF}, 2",
+          f"s_mov_b32 s{S_ACUR}, {A_BASES[0]}", f"s_mov_b32 s{S_ANXT}, {A_BASES[1]}", f"s_mov_b32 s{S_ANN}, {A_BASES[2]}",
+          f"s_mov_b32 s{S_BCUR}, {B_BASES[0]}", f"s_mov_b32 s{S_BNXT}, {B_BASES[1]}"]
+    # stage 0, then stage 1 (a one-stage problem fetches stage 0 twice; nobody reads the copy)
+    for n, (sa, sb) in enumerate(((S_ACUR, S_BCUR), (S_ANXT, S_BNXT))):
+        for which, sd in (("A", sa), ("B", sb)):
+            for g in unit_loads(sd, which, range(8)):
+                L += g
+            L += advance(which, cond=1) if n == 0 else advance(which)
+    L += ["s_waitcnt vmcnt(16)", "s_barrier"]
+    setup, reads = frag_reads(nn, 0, S_ACUR, S_BCUR, 0)
+    L += setup + reads + ["s_waitcnt lgkmcnt(0)"]
+    L += [f"s_cmp_lt_u32 %{KF}, 3", "s_cbranch_scc1 2f"]
+    # ---- steady loop: stages 0 .. KF-3
+    L.append("1:")
+    L += body(nn, not no_loads, False, no_reads)
+    L += rotate()
+    L += [f"s_sub_u32 s{S_CNT}, s{S_CNT}, 1", f"s_cmp_lg_u32 s{S_CNT}, 0", "s_cbranch_scc1 1b"]
+    # ---- stage KF-2 (if there is one), then stage KF-1
+    L.append("2:")
+    L += [f"s_cmp_lt_u32 %{KF}, 2", "s_cbranch_scc1 3f"]
+    L += body(nn, False, False, no_reads)
+    L += rotate()
+    L.append("3:")
+    L += body(nn, False, True, no_reads)
+    L.append("s_waitcnt vmcnt(0)")
+    L += MFMA_DRAIN
     return L
 
 
@@ -190,6 +218,7 @@ def build_kstep64(nn):
                 L.append(f"ds_read_b64_tr_b16 {fb_half(0, j, h)}, %{17 + j} offset:{2048 * h}")
     L.append("s_waitcnt lgkmcnt(0)")
     L += [mfma(0, i, j) for i in range(4) for j in range(4)]
+    L += MFMA_DRAIN
     return L
 
 
@@ -203,7 +232,7 @@ def emit(name, lines):
 
 def main():
     here = os.path.dirname(os.path.abspath(__file__))
-    clob = ['"memory"', '"scc"'] + [f'"s{r}"' for r in range(80, 95)] + [f'"v{r}"' for r in range(VT, 256)]
+    clob = ['"memory"', '"scc"'] + [f'"s{r}"' for r in range(80, 92)] + [f'"v{r}"' for r in range(VT, 256)]
     text = f"""// GENERATED by gen_gemm_mainloop.py -- do not edit by hand.
 // Main loop of the 256x256 / 4-wavefront base GEMM for gfx950 as inline-assembly templates.
 // Operands: %0-%15 accumulators (AGPR, i-major: block (i, j) is %(4i+j)); %16-%19 A fragment
@@ -213,7 +242,7 @@ def main():
 // the A / B stage (64-bit SGPR); %42 byte stride of B between stages; %43 number of 64-k stages
 // (>= 1); %44 LDS byte address of the dynamic segment + this wavefront's first load inside a
 // unit (wave * 8192).  LDS: A units at 0/32/64 KiB, B units at 96/128 KiB of the segment.
-// Fixed registers: s80-s94, v{VT}-v255 (fragment sets at v{F[0]} and v{F[1]}).
+// Fixed registers: s80-s91, v{VT}-v255 (fragment sets at v{F[0]} and v{F[1]}).
 #pragma once
 {emit("SYMB_GEMM_LOOP_NT", build(False))}
 

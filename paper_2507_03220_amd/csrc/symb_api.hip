@@ -255,10 +255,10 @@ struct GemmChoice {
     int bm;
 };
 
-template <int BM, int BN, int WGM, int WGN, bool NN>
+template <int BM, int BN, int WGM, int WGN, bool NN, bool PLAIN = false>
 symb_status launch_gemm_t(symb_handle h, GemmParams gp, hipStream_t st) {
     using TT = GemmTile<BM, BN, WGM, WGN, NN>;
-    auto kfn = symb_gemm_kernel<BM, BN, WGM, WGN, NN>;
+    auto kfn = symb_gemm_kernel<BM, BN, WGM, WGN, NN, PLAIN>;
     static bool attr_set = false;
     if (!attr_set) {
         SYMB_HIP(h, hipFuncSetAttribute(reinterpret_cast<const void*>(kfn), hipFuncAttributeMaxDynamicSharedMemorySize, TT::SMEM));
@@ -325,7 +325,9 @@ template <bool NN>
 symb_status launch_gemm(symb_handle h, const GemmParams& gp, hipStream_t st) {
     switch (gemm_variant(gp.M, gp.N)) {
         case 0: return launch_gemm_t<256, 256, 2, 4, NN>(h, gp, st);
-        case 2: return launch_gemm_t<256, 256, 2, 2, NN>(h, gp, st);
+        case 2:
+            if (!gp.bias && !gp.epi_ia3 && !gp.Cbase) return launch_gemm_t<256, 256, 2, 2, NN, true>(h, gp, st);
+            return launch_gemm_t<256, 256, 2, 2, NN>(h, gp, st);
         default: return launch_gemm_t<128, 128, 2, 2, NN>(h, gp, st);
     }
 }
