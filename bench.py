@@ -50,7 +50,8 @@ def step(runs, stream):
         r.fwd(stream)
     for r in runs:
         r.bwd_input(stream)
-        r.adapter_grad(stream, reuse_dh=True)     # same batch, same dY: dH is still in the workspace
+        # same batch, same X, same dY: Hs (forward) and dH (input gradient) are still in the workspace
+        r.adapter_grad(stream, reuse_dh=True, reuse_hs=True)
 
 
 def cpu_baseline(cfg: str, budget_s: float = 20.0) -> dict:

@@ -88,7 +88,11 @@ enum { SYMB_GRAD_OVERWRITE = 0, SYMB_GRAD_ACCUMULATE = 1,
        /* dH is taken from `ws` instead of being recomputed: `ws` must be the very workspace a
         * preceding symb_base_linear_bwd_input(SYMB_BWD_FULL) call used for this same batch and dY,
         * untouched since (the caller, not the library, carries it over: the library stays stateless) */
-       SYMB_GRAD_REUSE_DH = 2 };
+       SYMB_GRAD_REUSE_DH = 2,
+       /* Hs = s (X A^T) is taken from `ws` instead of being recomputed: `ws` must be the very
+        * workspace a preceding symb_base_linear_fwd call used for this same batch and X, and any
+        * call in between must have been on this same batch too (their regions do not overlap Hs) */
+       SYMB_GRAD_REUSE_HS = 4 };
 
 /* One segment's adapter (Sec. 3.2 "Client": method and parameters are per client). */
 typedef struct {
@@ -157,7 +161,7 @@ symb_status symb_base_linear_bwd_input(symb_handle h, const symb_batch* b, const
 /*
  * Adapter gradients per segment (the client-side autograd of Sec. 3.2, fused here):
  * for every segment whose descriptor has dA / dB non-NULL, writes (OVERWRITE) or adds
- * to (ACCUMULATE; flags may be OR-ed with SYMB_GRAD_REUSE_DH) dA_i, dB_i (LoRA) or dl_i (IA3, through dA).  An empty segment
+ * to (ACCUMULATE; flags may be OR-ed with SYMB_GRAD_REUSE_DH / SYMB_GRAD_REUSE_HS) dA_i, dB_i (LoRA) or dl_i (IA3, through dA).  An empty segment
  * writes zeros (OVERWRITE) or leaves the buffers alone (ACCUMULATE).
  *   X [T'][d_in], dY [T'][d_out] bf16 DEVICE; Ybase [T'][d_out] bf16 DEVICE, required
  *   iff some IA3 segment wants dl (else may be NULL -> SYMB_ERR_INVALID_ARG if needed).

@@ -20,7 +20,7 @@ SYMB_OK, SYMB_ERR_INVALID_ARG, SYMB_ERR_BAD_SEGMENTS, SYMB_ERR_UNSUPPORTED, \
 SYMB_ADAPTER_NONE, SYMB_ADAPTER_LORA, SYMB_ADAPTER_IA3, SYMB_ADAPTER_IA3_IN = range(4)
 SYMB_OP_FWD, SYMB_OP_BWD_INPUT, SYMB_OP_ADAPTER_GRAD = range(3)
 SYMB_BWD_FULL, SYMB_BWD_BASE_ONLY = 0, 1
-SYMB_GRAD_OVERWRITE, SYMB_GRAD_ACCUMULATE, SYMB_GRAD_REUSE_DH = 0, 1, 2
+SYMB_GRAD_OVERWRITE, SYMB_GRAD_ACCUMULATE, SYMB_GRAD_REUSE_DH, SYMB_GRAD_REUSE_HS = 0, 1, 2, 4
 SYMB_MAX_RANK = 128
 
 EXPORTS = ("symb_create", "symb_destroy", "symb_validate_batch", "symb_debug_row_segment_map",

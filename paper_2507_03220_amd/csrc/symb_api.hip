@@ -162,6 +162,9 @@ BatchInfo inspect(const symb_batch* b) {
 }
 
 // Workspace layout (all regions 256-byte aligned, in this order; absent regions have size 0).
+// Hs, dH and packed B^T sit at the same offsets for all three operations of one batch, so that a
+// gradient call on the same workspace can take over what the forward call (Hs) and the
+// input-gradient call (dH) left there (SYMB_GRAD_REUSE_HS / SYMB_GRAD_REUSE_DH).
 struct WsLayout {
     size_t h_off = 0, h_bytes = 0;        // Hs  [T][2*max_rpad] bf16
     size_t dh_off = 0, dh_bytes = 0;      // dH  [T][2*max_rpad] bf16
@@ -183,15 +186,16 @@ WsLayout ws_layout(const symb_batch* b, const BatchInfo& bi, int op, bool full_b
         if (bi.n_lora) take(w.h_off, w.h_bytes, hb);
     } else if (op == SYMB_OP_BWD_INPUT) {
         if (full_bwd && bi.n_lora) {
+            take(w.h_off, w.h_bytes, hb);     // not touched here: keeps the forward call's Hs intact
             take(w.dh_off, w.dh_bytes, hb);
             take(w.pk_off, w.pk_bytes, bi.packed_elems * 2);
         }
         if (full_bwd && bi.n_ia3) take(w.sc_off, w.sc_bytes, (size_t)bi.T * b->d_out * 2);
     } else {
-        if (any_lora_grad) {      // dH first, at the offset the input-gradient call leaves it (SYMB_GRAD_REUSE_DH)
+        if (any_lora_grad) {
+            take(w.h_off, w.h_bytes, hb);
             take(w.dh_off, w.dh_bytes, hb);
             take(w.pk_off, w.pk_bytes, bi.packed_elems * 2);
-            take(w.h_off, w.h_bytes, hb);
         }
     }
     w.total = cur;
@@ -664,8 +668,9 @@ symb_status symb_adapter_grad(symb_handle h, const symb_batch* b, const void* X,
     symb_status st = check_handle(h);
     if (st != SYMB_OK) return st;
     if ((st = validate(h, b)) != SYMB_OK) return st;
-    if (flags & ~(uint32_t)(SYMB_GRAD_ACCUMULATE | SYMB_GRAD_REUSE_DH)) return fail(h, SYMB_ERR_INVALID_ARG, "unknown gradient flag %u", flags);
-    const bool reuse_dh = (flags & SYMB_GRAD_REUSE_DH) != 0;
+    if (flags & ~(uint32_t)(SYMB_GRAD_ACCUMULATE | SYMB_GRAD_REUSE_DH | SYMB_GRAD_REUSE_HS))
+        return fail(h, SYMB_ERR_INVALID_ARG, "unknown gradient flag %u", flags);
+    const bool reuse_dh = (flags & SYMB_GRAD_REUSE_DH) != 0, reuse_hs = (flags & SYMB_GRAD_REUSE_HS) != 0;
     const BatchInfo bi = inspect(b);
     if (!X || !dY) {
         if (bi.T > 0) return fail(h, SYMB_ERR_INVALID_ARG, "X and dY are required");
@@ -745,15 +750,17 @@ symb_status symb_adapter_grad(symb_handle h, const symb_batch* b, const void* X,
     const int32_t* doff = (const int32_t*)(dev + o_off);
 
     if (!want_b.empty()) {       // dB_i = s_i * dY_i^T H_i  ==  dY_i^T Hs_i
-        SkinnyParams sp{};
-        sp.L = (const bf16*)X;
-        sp.out = (bf16*)(wsb + wl.h_off);
-        sp.K = b->d_in;
-        sp.out_pitch = 2 * bi.max_rpad;
-        sp.chunks = (const RowChunk*)(dev + o_chh);
-        sp.seg = dseg;
-        sp.use_packed = 0;
-        if ((st = launch_skinny(h, sp, (int)ch_h.size(), grad_max_rpad, s)) != SYMB_OK) return st;
+        if (!reuse_hs) {
+            SkinnyParams sp{};
+            sp.L = (const bf16*)X;
+            sp.out = (bf16*)(wsb + wl.h_off);
+            sp.K = b->d_in;
+            sp.out_pitch = 2 * bi.max_rpad;
+            sp.chunks = (const RowChunk*)(dev + o_chh);
+            sp.seg = dseg;
+            sp.use_packed = 0;
+            if ((st = launch_skinny(h, sp, (int)ch_h.size(), grad_max_rpad, s)) != SYMB_OK) return st;
+        }
         GradParams gp{(const bf16*)dY, (const bf16*)(wsb + wl.h_off), b->d_out, 2 * bi.max_rpad, doff, dseg,
                       (const int32_t*)(dev + o_wb), acc ? 1 : 0};
         if ((st = launch_grad<true>(h, gp, (int)want_b.size(), grad_max_rpad, s)) != SYMB_OK) return st;

@@ -103,6 +103,7 @@ class ProjectionRun:
     def fwd(self, stream: int = 0) -> None:
         sb.symb_base_linear_fwd(self.h, self.fwd_batch, self.X, self.W, self.bias, self.Y, self.Ybase, self.ws, stream)
         self._dh_in_ws = False
+        self._hs_in_ws = self._gather is None      # backward batch == forward batch: Hs stays valid for it
 
     def sync_saved_output(self) -> None:
         """What a client does between forward and backward: keep its rows of the base output."""
@@ -113,10 +114,14 @@ class ProjectionRun:
         sb.symb_base_linear_bwd_input(self.h, self.bwd_batch, self.dY, self.W, self.dX, flags, self.ws, stream)
         self._dh_in_ws = flags == sb.SYMB_BWD_FULL
 
-    def adapter_grad(self, stream: int = 0, flags: int = sb.SYMB_GRAD_OVERWRITE, reuse_dh: bool = False) -> None:
-        """reuse_dh: the workspace still holds dH from the bwd_input call just before (same batch, same dY)."""
+    def adapter_grad(self, stream: int = 0, flags: int = sb.SYMB_GRAD_OVERWRITE, reuse_dh: bool = False,
+                     reuse_hs: bool = False) -> None:
+        """reuse_dh: the workspace still holds dH from the bwd_input call just before (same batch, same dY).
+        reuse_hs: it still holds Hs from this run's forward call (only when the backward batch is the forward batch)."""
         if reuse_dh and getattr(self, "_dh_in_ws", False):
             flags |= sb.SYMB_GRAD_REUSE_DH
+        if reuse_hs and getattr(self, "_hs_in_ws", False):
+            flags |= sb.SYMB_GRAD_REUSE_HS
         sb.symb_adapter_grad(self.h, self.bwd_batch, self.Xb, self.dY, self.Ybase_b, flags, self.ws, stream)
         self._dh_in_ws = False
 

@@ -254,7 +254,7 @@ def test_errors_enqueue_nothing_and_leave_handle_usable():
 
 
 def test_adapter_grad_can_reuse_dh_from_the_input_gradient_call():
-    """SYMB_GRAD_REUSE_DH: same batch, same dY, same workspace -> bit-identical gradients."""
+    """SYMB_GRAD_REUSE_DH / SYMB_GRAD_REUSE_HS: same batch, same X and dY, same workspace -> bit-identical gradients."""
     p = make_problem(16, 264, 392, [150, 1, 70, 33], [L, I, L, L], [8, 24, 5])
     d_in, d_out, off = p["d_in"], p["d_out"], p["off"]
     Xd, dYd, Wd = gh.to_dev(p["X"]), gh.to_dev(p["dY"]), gh.to_dev(p["W"])
@@ -266,14 +266,27 @@ def test_adapter_grad_can_reuse_dh_from_the_input_gradient_call():
     sb.symb_adapter_grad(h, b1, Xd, dYd, Yb, sb.SYMB_GRAD_OVERWRITE, gh.workspace(b1, sb.SYMB_OP_ADAPTER_GRAD))
     reuse = gh.upload_adapters(p["ads"], d_in, d_out, grads=True)
     b2 = sb.Batch(d_in, d_out, off, reuse.descs)
-    n = max(sb.symb_workspace_bytes(b2, sb.SYMB_OP_BWD_INPUT), sb.symb_workspace_bytes(b2, sb.SYMB_OP_ADAPTER_GRAD))
+    n = max(sb.symb_workspace_bytes(b2, op) for op in (sb.SYMB_OP_FWD, sb.SYMB_OP_BWD_INPUT, sb.SYMB_OP_ADAPTER_GRAD))
     ws = torch.empty(n, device="cuda", dtype=torch.uint8)
     dX = torch.empty((p["T"], d_in), device="cuda", dtype=torch.bfloat16)
     sb.symb_base_linear_bwd_input(h, b2, dYd, Wd, dX, sb.SYMB_BWD_FULL, ws)
     sb.symb_adapter_grad(h, b2, Xd, dYd, Yb, sb.SYMB_GRAD_OVERWRITE | sb.SYMB_GRAD_REUSE_DH, ws)
     torch.cuda.synchronize()
-    for d1, d2 in zip(plain.descs, reuse.descs):
-        if d1.dA is not None:
-            assert torch.equal(d1.dA, d2.dA)
-        if d1.dB is not None:
-            assert torch.equal(d1.dB, d2.dB)
+
+    def same(x, y):
+        for d1, d2 in zip(x.descs, y.descs):
+            if d1.dA is not None:
+                assert torch.equal(d1.dA, d2.dA)
+            if d1.dB is not None:
+                assert torch.equal(d1.dB, d2.dB)
+    same(plain, reuse)
+    # forward, input gradient, then gradients taking both Hs and dH from the workspace
+    both = gh.upload_adapters(p["ads"], d_in, d_out, grads=True)
+    b3 = sb.Batch(d_in, d_out, off, both.descs)
+    ws.fill_(0x7f)
+    Y = torch.empty((p["T"], d_out), device="cuda", dtype=torch.bfloat16)
+    sb.symb_base_linear_fwd(h, b3, Xd, Wd, None, Y, None, ws)
+    sb.symb_base_linear_bwd_input(h, b3, dYd, Wd, dX, sb.SYMB_BWD_FULL, ws)
+    sb.symb_adapter_grad(h, b3, Xd, dYd, Yb, sb.SYMB_GRAD_OVERWRITE | sb.SYMB_GRAD_REUSE_DH | sb.SYMB_GRAD_REUSE_HS, ws)
+    torch.cuda.synchronize()
+    same(plain, both)

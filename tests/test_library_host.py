@@ -110,8 +110,9 @@ def test_workspace_bytes_formula():
     up = lambda n: (n + 255) // 256 * 256
     packed = (16 + 48) * 128 * 2
     assert sb.symb_workspace_bytes(b, sb.SYMB_OP_FWD) == up(T * rp * 2)
-    assert sb.symb_workspace_bytes(b, sb.SYMB_OP_BWD_INPUT) == up(T * rp * 2) + up(packed) + up(T * 128 * 2)
-    assert sb.symb_workspace_bytes(b, sb.SYMB_OP_ADAPTER_GRAD) == 2 * up(T * rp * 2) + up(packed)   # dH, packed B^T, Hs
+    # Hs (left alone by the input-gradient call), dH, packed B^T, IA3-scaled dY
+    assert sb.symb_workspace_bytes(b, sb.SYMB_OP_BWD_INPUT) == 2 * up(T * rp * 2) + up(packed) + up(T * 128 * 2)
+    assert sb.symb_workspace_bytes(b, sb.SYMB_OP_ADAPTER_GRAD) == 2 * up(T * rp * 2) + up(packed)   # Hs, dH, packed B^T
     none = sb.Batch(64, 128, [0, 100], [sb.Adapter()])
     for op in (sb.SYMB_OP_FWD, sb.SYMB_OP_BWD_INPUT, sb.SYMB_OP_ADAPTER_GRAD):
         assert sb.symb_workspace_bytes(none, op) == 0
