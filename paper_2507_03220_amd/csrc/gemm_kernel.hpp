@@ -489,55 +489,84 @@ symb_gemm_kernel(const GemmParams p) {
         }
     };
     constexpr int CP = TT::C_PITCH;                  // bytes per staged row (BN * 2 + 16: bank spread)
+    // The four accumulators of one quad.  In the assembly variant they are read by instructions
+    // placed here and now: left to the compiler, all 256 accumulation registers are copied out
+    // ahead of the loops, which needs more registers than there are.
+    auto read_quad = [&](int i, int j, int rg, float& v0, float& v1, float& v2, float& v3) __attribute__((always_inline)) {
+        if constexpr (TT::ASM_LOOP) {
+            asm volatile("v_accvgpr_read_b32 %0, %4\n\tv_accvgpr_read_b32 %1, %5\n\t"
+                         "v_accvgpr_read_b32 %2, %6\n\tv_accvgpr_read_b32 %3, %7"
+                         : "=v"(v0), "=v"(v1), "=v"(v2), "=v"(v3)
+                         : "a"(acc[i][j][rg * 4 + 0]), "a"(acc[i][j][rg * 4 + 1]), "a"(acc[i][j][rg * 4 + 2]),
+                           "a"(acc[i][j][rg * 4 + 3]));
+        } else {
+            v0 = acc[i][j][rg * 4 + 0]; v1 = acc[i][j][rg * 4 + 1];
+            v2 = acc[i][j][rg * 4 + 2]; v3 = acc[i][j][rg * 4 + 3];
+        }
+    };
     auto stage_out = [&](bf16* __restrict__ dst, bool scale_ia3) __attribute__((always_inline)) {
         if (PLAIN || (!p.bias && !scale_ia3)) {
             for_each_quad([&](int i, int j, int rg, int m, int n) __attribute__((always_inline)) {
                 float v0, v1, v2, v3;
-                if constexpr (TT::ASM_LOOP) {
-                    // read the four accumulation registers here and now: left to the compiler, all 256
-                    // are copied out ahead of the loop, which needs more registers than there are
-                    asm volatile("v_accvgpr_read_b32 %0, %4\n\tv_accvgpr_read_b32 %1, %5\n\t"
-                                 "v_accvgpr_read_b32 %2, %6\n\tv_accvgpr_read_b32 %3, %7"
-                                 : "=v"(v0), "=v"(v1), "=v"(v2), "=v"(v3)
-                                 : "a"(acc[i][j][rg * 4 + 0]), "a"(acc[i][j][rg * 4 + 1]), "a"(acc[i][j][rg * 4 + 2]),
-                                   "a"(acc[i][j][rg * 4 + 3]));
-                } else {
-                    v0 = acc[i][j][rg * 4 + 0]; v1 = acc[i][j][rg * 4 + 1];
-                    v2 = acc[i][j][rg * 4 + 2]; v3 = acc[i][j][rg * 4 + 3];
-                }
+                read_quad(i, j, rg, v0, v1, v2, v3);
                 uint2 o;
                 o.x = pack2_bf16(v0, v1);
                 o.y = pack2_bf16(v2, v3);
                 *reinterpret_cast<uint2*>(smem + (m - m0) * CP + (n - n0) * 2) = o;
             });
         } else if constexpr (!PLAIN) {
-            for_each_quad([&](int i, int j, int rg, int m, int n) __attribute__((always_inline)) {
-                float v0 = acc[i][j][rg * 4 + 0], v1 = acc[i][j][rg * 4 + 1];
-                float v2 = acc[i][j][rg * 4 + 2], v3 = acc[i][j][rg * 4 + 3];
-                if (m < p.M && n < p.N) {
-                    if (p.bias) {
-                        const uint2 bv = *reinterpret_cast<const uint2*>(p.bias + n);
-                        v0 += bf16_bits_to_f32((unsigned short)(bv.x & 0xffffu));
-                        v1 += bf16_bits_to_f32((unsigned short)(bv.x >> 16));
-                        v2 += bf16_bits_to_f32((unsigned short)(bv.y & 0xffffu));
-                        v3 += bf16_bits_to_f32((unsigned short)(bv.y >> 16));
-                    }
-                    if (scale_ia3) {
-                        const int s = seg_of_row(p.off, seg_lo, seg_hi, m);
-                        if (p.seg[s].kind == KIND_IA3) {
-                            const uint2 lv = *reinterpret_cast<const uint2*>(p.seg[s].A + n);
-                            v0 *= bf16_bits_to_f32((unsigned short)(lv.x & 0xffffu));
-                            v1 *= bf16_bits_to_f32((unsigned short)(lv.x >> 16));
-                            v2 *= bf16_bits_to_f32((unsigned short)(lv.y & 0xffffu));
-                            v3 *= bf16_bits_to_f32((unsigned short)(lv.y >> 16));
-                        }
-                    }
+            // bias of this lane's 16 column quads, once; IA3 vector of each row's own segment per row block
+            const uint2 zero2 = make_uint2(0u, 0u);
+            const int nq0 = n0 + wn0 + ((lane >> 5) << 2);
+            uint2 bv[NB][4];
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {
+                    const int n = nq0 + j * 32 + rg * 8;
+                    bv[j][rg] = (p.bias && n < p.N) ? *reinterpret_cast<const uint2*>(p.bias + n) : zero2;
                 }
-                uint2 o;
-                o.x = pack2_bf16(v0, v1);
-                o.y = pack2_bf16(v2, v3);
-                *reinterpret_cast<uint2*>(smem + (m - m0) * CP + (n - n0) * 2) = o;
-            });
+#pragma unroll
+            for (int i = 0; i < MB; ++i) {
+                const int m = m0 + wm0 + i * 32 + (lane & 31);
+                const bf16* lrow = nullptr;
+                if (scale_ia3 && m < p.M) {
+                    const int s = seg_of_row(p.off, seg_lo, seg_hi, m);
+                    if (p.seg[s].kind == KIND_IA3) lrow = p.seg[s].A;
+                }
+                uint2 lv[NB][4];
+#pragma unroll
+                for (int j = 0; j < NB; ++j)
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const int n = nq0 + j * 32 + rg * 8;
+                        lv[j][rg] = (lrow && n < p.N) ? *reinterpret_cast<const uint2*>(lrow + n) : make_uint2(0x3f803f80u, 0x3f803f80u);
+                    }
+#pragma unroll
+                for (int j = 0; j < NB; ++j)
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const int n = nq0 + j * 32 + rg * 8;
+                        float v0, v1, v2, v3;
+                        read_quad(i, j, rg, v0, v1, v2, v3);
+                        if (p.bias) {
+                            v0 += bf16_bits_to_f32((unsigned short)(bv[j][rg].x & 0xffffu));
+                            v1 += bf16_bits_to_f32((unsigned short)(bv[j][rg].x >> 16));
+                            v2 += bf16_bits_to_f32((unsigned short)(bv[j][rg].y & 0xffffu));
+                            v3 += bf16_bits_to_f32((unsigned short)(bv[j][rg].y >> 16));
+                        }
+                        if (scale_ia3) {           // rows of other kinds carry ones (exact)
+                            v0 *= bf16_bits_to_f32((unsigned short)(lv[j][rg].x & 0xffffu));
+                            v1 *= bf16_bits_to_f32((unsigned short)(lv[j][rg].x >> 16));
+                            v2 *= bf16_bits_to_f32((unsigned short)(lv[j][rg].y & 0xffffu));
+                            v3 *= bf16_bits_to_f32((unsigned short)(lv[j][rg].y >> 16));
+                        }
+                        uint2 o;
+                        o.x = pack2_bf16(v0, v1);
+                        o.y = pack2_bf16(v2, v3);
+                        *reinterpret_cast<uint2*>(smem + (m - m0) * CP + (n - n0) * 2) = o;
+                    }
+            }
         }
 #ifdef SYMB_GEMM_TRACE
         if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 8] = __builtin_amdgcn_s_memrealtime();
