@@ -63,20 +63,23 @@ symb_skinny_kernel(const SkinnyParams p) {
 #pragma unroll
         for (int j = 0; j < RB; ++j) acc[b][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    // Each wavefront takes every 4th 128-element slice of K (256 bytes per row per step); all
-    // loads of a step are issued before its MFMAs so several KiB per wavefront are in flight.
+    // Each wavefront takes every 4th 128-element slice of K (256 bytes per row per step).  The
+    // row data (the HBM stream) of the next slice is requested before the current slice is
+    // multiplied, so a wavefront always has 8 KiB of it in flight; the adapter rows come from L2.
     const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
-    int k0 = wave * 128;
-    for (; k0 + 128 <= p.K; k0 += 512) {
-        uint4 lv[2][4], rv[RB][4];
+    auto load_l = [&](uint4 (&lv)[2][4], int k) __attribute__((always_inline)) {
 #pragma unroll
-        for (int h = 0; h < 4; ++h) {
+        for (int h = 0; h < 4; ++h)
 #pragma unroll
-            for (int b = 0; b < 2; ++b) lv[b][h] = *reinterpret_cast<const uint4*>(lrow[b] + k0 + h * 32);
+            for (int b = 0; b < 2; ++b) lv[b][h] = *reinterpret_cast<const uint4*>(lrow[b] + k + h * 32);
+    };
+    auto step = [&](const uint4 (&lv)[2][4], int k) __attribute__((always_inline)) {
+        uint4 rv[RB][4];
+#pragma unroll
+        for (int h = 0; h < 4; ++h)
 #pragma unroll
             for (int j = 0; j < RB; ++j)
-                if (j < nb) rv[j][h] = *reinterpret_cast<const uint4*>(rrow[j] + k0 + h * 32);
-        }
+                if (j < nb) rv[j][h] = *reinterpret_cast<const uint4*>(rrow[j] + k + h * 32);
 #pragma unroll
         for (int h = 0; h < 4; ++h)
 #pragma unroll
@@ -87,6 +90,25 @@ symb_skinny_kernel(const SkinnyParams p) {
                     for (int b = 0; b < 2; ++b)
                         acc[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rf, __builtin_bit_cast(bf16x8, lv[b][h]), acc[b][j], 0, 0, 0);
                 }
+    };
+    int k0 = wave * 128;
+    if (k0 + 128 <= p.K) {
+        uint4 la[2][4], lb[2][4];
+        load_l(la, k0);
+        while (true) {
+            const int k1 = k0 + 512;
+            const bool more1 = k1 + 128 <= p.K;
+            if (more1) load_l(lb, k1);
+            step(la, k0);
+            k0 = k1;
+            if (!more1) break;
+            const int k2 = k1 + 512;
+            const bool more2 = k2 + 128 <= p.K;
+            if (more2) load_l(la, k2);
+            step(lb, k1);
+            k0 = k2;
+            if (!more2) break;
+        }
     }
     for (; k0 < p.K; k0 += 512) {                        // the slice that crosses the end of K
 #pragma unroll
@@ -297,8 +319,9 @@ symb_lora_grad_kernel(const GradParams p) {
 
 // -------------------------------------------------------------------------------------------
 // IA3 vector gradient:  dl_i[j] = sum_{t in segment i} dY[t][j] * Y0[t][j]
-// grid.x covers d_out in blocks of 256 columns, grid.y indexes the IA3 segments that want it.
-// A thread owns 8 columns (16-byte loads) and every 8th token; partial sums meet in LDS.
+// grid.x covers d_out in blocks of 128 columns, grid.y indexes the IA3 segments that want it.
+// A thread owns 8 columns (16-byte loads) and every 16th token, four tokens per step in flight;
+// partial sums meet in LDS in a fixed order.
 // -------------------------------------------------------------------------------------------
 struct Ia3GradParams {
     const bf16* dY;
@@ -309,23 +332,38 @@ struct Ia3GradParams {
     const int32_t* seg_list;
     int accumulate;
 };
+constexpr int IA3_GRAD_COLS = 128;
 __global__ void __launch_bounds__(256) symb_ia3_grad_kernel(const Ia3GradParams p) {
-    __shared__ float red[8][32][8];
+    __shared__ float red[16][16][9];
     const int s = p.seg_list[blockIdx.y];
     const int t_lo = p.off[s], t_hi = p.off[s + 1];
-    const int cc = threadIdx.x & 31, tl = threadIdx.x >> 5;
-    const int c = blockIdx.x * 256 + cc * 8;
+    const int cc = threadIdx.x & 15, tl = threadIdx.x >> 4;
+    const int c = blockIdx.x * IA3_GRAD_COLS + cc * 8;
     float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    auto fma8 = [&](const uint4& g, const uint4& y) __attribute__((always_inline)) {
+        const unsigned int gw[4] = {g.x, g.y, g.z, g.w}, yw[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            a[2 * q] += bf16_bits_to_f32((unsigned short)(gw[q] & 0xffffu)) * bf16_bits_to_f32((unsigned short)(yw[q] & 0xffffu));
+            a[2 * q + 1] += bf16_bits_to_f32((unsigned short)(gw[q] >> 16)) * bf16_bits_to_f32((unsigned short)(yw[q] >> 16));
+        }
+    };
     if (c < p.d_out) {
-        for (int t = t_lo + tl; t < t_hi; t += 8) {
+        int t = t_lo + tl;
+        for (; t + 48 < t_hi; t += 64) {
+            uint4 g[4], y[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                g[u] = *reinterpret_cast<const uint4*>(p.dY + (size_t)(t + 16 * u) * p.d_out + c);
+                y[u] = *reinterpret_cast<const uint4*>(p.Y0 + (size_t)(t + 16 * u) * p.d_out + c);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) fma8(g[u], y[u]);
+        }
+        for (; t < t_hi; t += 16) {
             const uint4 g = *reinterpret_cast<const uint4*>(p.dY + (size_t)t * p.d_out + c);
             const uint4 y = *reinterpret_cast<const uint4*>(p.Y0 + (size_t)t * p.d_out + c);
-            const unsigned int gw[4] = {g.x, g.y, g.z, g.w}, yw[4] = {y.x, y.y, y.z, y.w};
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                a[2 * q] += bf16_bits_to_f32((unsigned short)(gw[q] & 0xffffu)) * bf16_bits_to_f32((unsigned short)(yw[q] & 0xffffu));
-                a[2 * q + 1] += bf16_bits_to_f32((unsigned short)(gw[q] >> 16)) * bf16_bits_to_f32((unsigned short)(yw[q] >> 16));
-            }
+            fma8(g, y);
         }
     }
 #pragma unroll
@@ -337,7 +375,7 @@ __global__ void __launch_bounds__(256) symb_ia3_grad_kernel(const Ia3GradParams 
         for (int q = 0; q < 8; ++q) {
             float v = 0.f;
 #pragma unroll
-            for (int w = 0; w < 8; ++w) v += red[w][cc][q];
+            for (int w = 0; w < 16; ++w) v += red[w][cc][q];
             out[q] = p.accumulate ? (out[q] + v) : v;
         }
     }
@@ -359,14 +397,14 @@ __global__ void __launch_bounds__(256) symb_ia3_scale_rows_kernel(const ScalePar
     const SegDesc sd = p.seg[ch.seg];
     const bool ia3 = sd.kind == KIND_IA3;
     const int nchunk = p.d_out >> 3;
-    for (int t = 0; t < ch.nrows; ++t) {
-        const size_t base = (size_t)(ch.row0 + t) * p.d_out;
-        for (int c = threadIdx.x; c < nchunk; c += 256) {
-            uint4 g = *reinterpret_cast<const uint4*>(p.dY + base + c * 8);
+    // a thread keeps its 8 columns and walks the chunk's rows, four rows in flight
+    for (int c = threadIdx.x; c < nchunk; c += 256) {
+        uint4 l = make_uint4(0u, 0u, 0u, 0u);
+        if (ia3) l = *reinterpret_cast<const uint4*>(sd.A + c * 8);
+        const unsigned int lw[4] = {l.x, l.y, l.z, l.w};
+        auto scaled = [&](uint4 g) __attribute__((always_inline)) {
             if (ia3) {
-                const uint4 l = *reinterpret_cast<const uint4*>(sd.A + c * 8);
                 unsigned int gw[4] = {g.x, g.y, g.z, g.w};
-                const unsigned int lw[4] = {l.x, l.y, l.z, l.w};
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const float lo = bf16_bits_to_f32((unsigned short)(gw[q] & 0xffffu)) * bf16_bits_to_f32((unsigned short)(lw[q] & 0xffffu));
@@ -375,7 +413,20 @@ __global__ void __launch_bounds__(256) symb_ia3_scale_rows_kernel(const ScalePar
                 }
                 g = make_uint4(gw[0], gw[1], gw[2], gw[3]);
             }
-            *reinterpret_cast<uint4*>(p.out + base + c * 8) = g;
+            return g;
+        };
+        const size_t col = (size_t)c * 8;
+        int t = 0;
+        for (; t + 4 <= ch.nrows; t += 4) {
+            uint4 g[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) g[u] = *reinterpret_cast<const uint4*>(p.dY + (size_t)(ch.row0 + t + u) * p.d_out + col);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) *reinterpret_cast<uint4*>(p.out + (size_t)(ch.row0 + t + u) * p.d_out + col) = scaled(g[u]);
+        }
+        for (; t < ch.nrows; ++t) {
+            const uint4 g = *reinterpret_cast<const uint4*>(p.dY + (size_t)(ch.row0 + t) * p.d_out + col);
+            *reinterpret_cast<uint4*>(p.out + (size_t)(ch.row0 + t) * p.d_out + col) = scaled(g);
         }
     }
 }

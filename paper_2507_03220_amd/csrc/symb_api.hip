@@ -788,7 +788,7 @@ symb_status symb_adapter_grad(symb_handle h, const symb_batch* b, const void* X,
     }
     if (!want_l.empty()) {
         Ia3GradParams ip{(const bf16*)dY, (const bf16*)Ybase, b->d_out, doff, dseg, (const int32_t*)(dev + o_wl), acc ? 1 : 0};
-        hipLaunchKernelGGL(symb_ia3_grad_kernel, dim3((b->d_out + 255) / 256, (unsigned)want_l.size()), dim3(256), 0, s, ip);
+        hipLaunchKernelGGL(symb_ia3_grad_kernel, dim3((b->d_out + IA3_GRAD_COLS - 1) / IA3_GRAD_COLS, (unsigned)want_l.size()), dim3(256), 0, s, ip);
         SYMB_HIP(h, hipGetLastError());
     }
     return seal_slot(h, s);
