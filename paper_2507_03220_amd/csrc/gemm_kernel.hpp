@@ -596,7 +596,13 @@ symb_gemm_kernel(const GemmParams p) {
 
     // ---- LoRA term: extra K-steps per LoRA segment that meets this row tile
     if (p.ext) {
+        // Empty statements that name every accumulator as an accumulation-register operand, here and
+        // at the top of each segment's pass: without these anchors the register allocator moves most
+        // of the accumulators to scratch memory around this loop nest (about 190 registers per lane
+        // written out and read back per tile, more HBM traffic than the output itself).
+        if constexpr (TT::ASM_LOOP) asm volatile("" : SYMB_ACC16("+"));
         for (int s = seg_lo; s <= seg_hi; ++s) {
+            if constexpr (TT::ASM_LOOP) asm volatile("" : SYMB_ACC16("+"));
             const SegDesc sd = p.seg[s];
             const int r_lo = max(p.off[s], m0), r_hi = min(min(p.off[s + 1], m0 + BM), p.M);
             if (sd.kind != KIND_LORA || r_hi <= r_lo) continue;      // uniform over the workgroup
