@@ -42,18 +42,25 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
-def build_ceiling() -> str:
-    """Compiles the stand-alone MFMA ceiling measurement (csrc/mfma_ceiling.hip)."""
-    out = os.path.join(HERE, "mfma_ceiling")
+def build_tool(name: str) -> str:
+    """Compiles a stand-alone measurement (csrc/<name>.hip) into paper_2507_03220_amd/<name>."""
+    out = os.path.join(HERE, name)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     subprocess.check_call([hipcc, "-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
-                           "-packed-fp32-ops", "-o", out, os.path.join(HERE, "csrc", "mfma_ceiling.hip")],
+                           "-packed-fp32-ops", "-o", out, os.path.join(HERE, "csrc", name + ".hip")],
                           stderr=subprocess.DEVNULL)
     return out
+
+
+def build_ceiling() -> str:
+    """The MFMA ceiling measurement (csrc/mfma_ceiling.hip)."""
+    return build_tool("mfma_ceiling")
 
 
 if __name__ == "__main__":
     if "--ceiling" in sys.argv:
         print(build_ceiling())
+    elif "--l2-probe" in sys.argv:
+        print(build_tool("l2_lds_probe"))
     else:
         print(build(force=True, verbose=True))
