@@ -150,6 +150,36 @@ symb_status symb_base_linear_fwd(symb_handle h, const symb_batch* b, const void*
                                  void* stream);
 
 /*
+ * Activation privacy (Sec. 3.8, eqs. (1)-(3)).  A client hides its activations by adding noise n
+ * before the layer and removing the noise effect n_eff afterwards; because the layer (and a LoRA
+ * or IA3 adapter on it) is linear, the result is the one the plain call would have given.
+ *   (1) n_eff = layer(n) without bias: symb_base_linear_fwd on a batch whose segments hold the
+ *       noise rows, with bias == NULL (the bias-nullifying flow), the clients' own adapters.
+ *   (2) y_noisy = layer(x + n) + b, (3) y = y_noisy - n_eff: symb_noise_add, then
+ *       symb_base_linear_fwd_denoise, which subtracts n_eff in the epilogue, in fp32, before the
+ *       single rounding to bf16.
+ * A segment's noise tensor: rows == 1 broadcasts one row over the segment, rows == n_i gives
+ * every token its own row; ptr NULL = nothing for this segment.  Rows are dense bf16 DEVICE
+ * memory, 16-byte aligned, of width d_in (noise) or d_out (noise effect).
+ */
+typedef struct {
+    const void* ptr;
+    int32_t rows;
+    int32_t reserved;
+} symb_noise;
+
+/* Xn[t][k] = bf16(X[t][k] + n_seg(t)[.][k]) over the flattened batch (width b->d_in); the sum is
+ * formed in fp32 and rounded once.  noise: HOST array of b->num_segments entries. */
+symb_status symb_noise_add(symb_handle h, const symb_batch* b, const void* X, const symb_noise* noise,
+                           void* Xn, void* stream);
+
+/* symb_base_linear_fwd with  Y = (adapter-applied output, bias included) - n_eff  per segment.
+ * noise_effect: HOST array of b->num_segments entries (rows of width d_out).  No Ybase output. */
+symb_status symb_base_linear_fwd_denoise(symb_handle h, const symb_batch* b, const void* Xn, const void* W,
+                                         const void* bias, const symb_noise* noise_effect, void* Y,
+                                         void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Input gradient (Sec. 3.6):  dX = dY W (+ adapter branch unless SYMB_BWD_BASE_ONLY).
  *   dY [T'][d_out] bf16 DEVICE, W as above, dX [T'][d_in] bf16 DEVICE (written).
  *   The batch is the backward batch's own (any subset / regrouping of clients).

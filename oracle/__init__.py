@@ -120,6 +120,53 @@ def forward(off, adapters: Sequence[Adapter], X: np.ndarray, W: np.ndarray,
     return Y0, Y
 
 
+def _noise_args(off, noise: Sequence[Optional[np.ndarray]], width: int):
+    """noise[i]: None or bf16 bits [rows][width] (rows 1 = broadcast over the segment)."""
+    S = len(off) - 1
+    assert len(noise) == S
+    keep = [None if n is None else np.ascontiguousarray(np.asarray(n, dtype=np.uint16).reshape(-1, width)) for n in noise]
+    ptrs = (C.c_void_p * max(S, 1))(*[None if n is None else n.ctypes.data for n in keep])
+    rows = np.array([0 if n is None else n.shape[0] for n in keep] or [0], dtype=np.int32)
+    return keep, ptrs, rows
+
+
+def noise_add(off, X: np.ndarray, noise: Sequence[Optional[np.ndarray]]) -> np.ndarray:
+    """Client prepass of the privacy flow (Sec. 3.8): bf16 bits of x + n per segment."""
+    off = _i32(off)
+    S = len(off) - 1
+    width = X.shape[1]
+    keep, ptrs, rows = _noise_args(off, noise, width)
+    Xc = np.ascontiguousarray(X, dtype=np.uint16)
+    out = np.empty_like(Xc)
+    rc = lib().orc_noise_add(C.c_int32(width), C.c_int32(S), off.ctypes.data_as(C.c_void_p), _u16(Xc), ptrs,
+                             rows.ctypes.data_as(C.c_void_p), out.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise ValueError("oracle noise_add: bad offsets or noise rows")
+    return out
+
+
+def forward_private(off, adapters: Sequence[Adapter], Xn: np.ndarray, W: np.ndarray, bias: Optional[np.ndarray],
+                    noise: Sequence[Optional[np.ndarray]], rows=None) -> np.ndarray:
+    """y = (layer(xn) + b) - layer_without_bias(n), eqs. (1)-(3) of Sec. 3.8, fp64 [nrows, d_out]."""
+    off = _i32(off)
+    S = len(off) - 1
+    d_out, d_in = W.shape
+    assert Xn.shape[1] == d_in and Xn.shape[0] >= off[-1]
+    rows_a = None if rows is None else _i32(rows)
+    n = int(off[-1]) if rows is None else len(rows_a)
+    keep, ptrs, nrows = _noise_args(off, noise, d_in)
+    Y = np.empty((n, d_out), dtype=np.float64)
+    ad = _pack(adapters, d_in, d_out)
+    rc = lib().orc_forward_private_rows(C.c_int32(d_in), C.c_int32(d_out), C.c_int32(S),
+                                        off.ctypes.data_as(C.c_void_p), ad, _u16(Xn), _u16(W), _u16(bias), ptrs,
+                                        nrows.ctypes.data_as(C.c_void_p), C.c_int32(n),
+                                        None if rows_a is None else rows_a.ctypes.data_as(C.c_void_p),
+                                        Y.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise ValueError("oracle forward_private: bad offsets, noise rows or row index")
+    return Y
+
+
 def backward_input(off, adapters: Sequence[Adapter], dY: np.ndarray, W: np.ndarray,
                    rows=None, base_only: bool = False) -> np.ndarray:
     off = _i32(off)

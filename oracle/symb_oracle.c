@@ -146,6 +146,77 @@ int orc_forward_rows(int32_t d_in, int32_t d_out, int32_t S, const int32_t* off,
 }
 
 /*
+ * Activation privacy (Sec. 3.8, eqs. (1)-(3)).  A segment's noise: noise[i] NULL = none, else
+ * rows[i] rows of bf16, one broadcast row (rows[i] == 1) or one per token of the segment.
+ *
+ * orc_noise_add: the client's prepass  xn = x + n.  Activations are 16-bit (Sec. 4), so the sum
+ * is rounded to bf16, nearest-even (reading: formed in fp32, rounded once).
+ */
+static uint16_t to_bf16_rne(float f) {
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);   /* NaN */
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+int orc_noise_add(int32_t width, int32_t S, const int32_t* off, const uint16_t* X,
+                  const uint16_t* const* noise, const int32_t* rows, uint16_t* out) {
+    if (orc_check_offsets(S, off)) return 1;
+    for (int32_t i = 0; i < S; ++i) {
+        if (noise[i] && rows[i] != 1 && rows[i] != off[i + 1] - off[i]) return 1;
+        for (int32_t t = off[i]; t < off[i + 1]; ++t)
+            for (int32_t k = 0; k < width; ++k) {
+                uint16_t x = X[(size_t)t * width + k];
+                if (noise[i]) {
+                    const uint16_t n = noise[i][(size_t)(rows[i] == 1 ? 0 : t - off[i]) * width + k];
+                    uint32_t xu = (uint32_t)x << 16, nu = (uint32_t)n << 16;
+                    float xf, nf;
+                    memcpy(&xf, &xu, 4);
+                    memcpy(&nf, &nu, 4);
+                    x = to_bf16_rne(xf + nf);
+                }
+                out[(size_t)t * width + k] = x;
+            }
+    }
+    return 0;
+}
+
+/*
+ * orc_forward_private_rows: for the listed rows,
+ *   (1) n_eff   = layer(n), bias nullified, the row's own adapter applied;
+ *   (2) y_noisy = layer(xn) + b, the same adapter applied;
+ *   (3) y       = y_noisy - n_eff.
+ * Xn is what the executor receives (the output of orc_noise_add).  Both layer evaluations are
+ * orc_forward_rows; nothing is rounded.
+ */
+int orc_forward_private_rows(int32_t d_in, int32_t d_out, int32_t S, const int32_t* off,
+                             const orc_adapter* ad, const uint16_t* Xn, const uint16_t* W,
+                             const uint16_t* bias, const uint16_t* const* noise, const int32_t* rows_of,
+                             int32_t nrows, const int32_t* rows, double* Y_out) {
+    if (orc_check_offsets(S, off)) return 1;
+    const int32_t T = off[S];
+    /* the noise as a flattened batch of its own: broadcast rows written out per token */
+    uint16_t* Nfull = (uint16_t*)calloc((size_t)(T > 0 ? T : 1) * d_in, sizeof(uint16_t));
+    double* neff = (double*)malloc(sizeof(double) * (size_t)(nrows > 0 ? nrows : 1) * d_out);
+    if (!Nfull || !neff) { free(Nfull); free(neff); return 2; }
+    for (int32_t i = 0; i < S; ++i) {
+        if (!noise[i]) continue;
+        if (rows_of[i] != 1 && rows_of[i] != off[i + 1] - off[i]) { free(Nfull); free(neff); return 1; }
+        for (int32_t t = off[i]; t < off[i + 1]; ++t)
+            memcpy(Nfull + (size_t)t * d_in, noise[i] + (size_t)(rows_of[i] == 1 ? 0 : t - off[i]) * d_in,
+                   sizeof(uint16_t) * (size_t)d_in);
+    }
+    int rc = orc_forward_rows(d_in, d_out, S, off, ad, Nfull, W, NULL, nrows, rows, NULL, neff);      /* (1) */
+    if (!rc) rc = orc_forward_rows(d_in, d_out, S, off, ad, Xn, W, bias, nrows, rows, NULL, Y_out);   /* (2) */
+    if (!rc)
+        for (size_t e = 0; e < (size_t)nrows * d_out; ++e) Y_out[e] -= neff[e];                       /* (3) */
+    free(Nfull);
+    free(neff);
+    return rc;
+}
+
+/*
  * Input gradient for the listed rows of a backward batch (its own offsets/adapters).
  *   NONE:   dX[t][k] = sum_j dY[t][j] W[j][k]
  *   LORA:   dH[t][p] = s * sum_j dY[t][j] B[j][p]

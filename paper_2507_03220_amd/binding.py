@@ -25,13 +25,18 @@ SYMB_MAX_RANK = 128
 
 EXPORTS = ("symb_create", "symb_destroy", "symb_validate_batch", "symb_debug_row_segment_map",
            "symb_plan_row_tiles", "symb_workspace_bytes", "symb_base_linear_fwd",
-           "symb_base_linear_bwd_input", "symb_adapter_grad", "symb_status_string", "symb_last_error",
+           "symb_base_linear_bwd_input", "symb_adapter_grad", "symb_noise_add", "symb_base_linear_fwd_denoise",
+           "symb_status_string", "symb_last_error",
            "symb_debug_gemm_timing_enable", "symb_debug_gemm_timing_read")
 
 
 class symb_adapter(C.Structure):
     _fields_ = [("kind", C.c_int32), ("rank", C.c_int32), ("scale", C.c_float),
                 ("A", C.c_void_p), ("B", C.c_void_p), ("dA", C.c_void_p), ("dB", C.c_void_p)]
+
+
+class symb_noise(C.Structure):
+    _fields_ = [("ptr", C.c_void_p), ("rows", C.c_int32), ("reserved", C.c_int32)]
 
 
 class symb_batch(C.Structure):
@@ -67,6 +72,8 @@ def lib() -> C.CDLL:
         l.symb_base_linear_fwd.argtypes = [vp, bp, vp, vp, vp, vp, vp, vp, sz, vp]
         l.symb_base_linear_bwd_input.argtypes = [vp, bp, vp, vp, vp, u32, vp, sz, vp]
         l.symb_adapter_grad.argtypes = [vp, bp, vp, vp, vp, u32, vp, sz, vp]
+        l.symb_noise_add.argtypes = [vp, bp, vp, C.POINTER(symb_noise), vp, vp]
+        l.symb_base_linear_fwd_denoise.argtypes = [vp, bp, vp, vp, vp, C.POINTER(symb_noise), vp, vp, sz, vp]
         l.symb_debug_gemm_timing_enable.argtypes = [vp, i32]
         l.symb_debug_gemm_timing_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64),
                                                   C.POINTER(C.c_double)]
@@ -180,6 +187,34 @@ def symb_base_linear_fwd(handle, batch: Batch, X, W, bias, Y, Ybase=None, ws=Non
     wp, wb = _ws_args(ws)
     _check(lib().symb_base_linear_fwd(handle, batch.ref(), _ptr(X), _ptr(W), _ptr(bias), _ptr(Y), _ptr(Ybase),
                                       wp, wb, stream or None), handle)
+
+
+def _noise_array(batch: Batch, noise: Sequence):
+    """noise: per segment None or a tensor [rows][width] (rows 1 = broadcast) or a (ptr, rows) pair."""
+    if len(noise) != batch.S:
+        raise ValueError("one noise entry per segment")
+    arr = (symb_noise * max(batch.S, 1))()
+    for i, n in enumerate(noise):
+        if n is None:
+            continue
+        if isinstance(n, tuple):
+            arr[i].ptr, arr[i].rows = _ptr(n[0]), int(n[1])
+        else:
+            arr[i].ptr, arr[i].rows = _ptr(n), int(n.shape[0]) if n.dim() > 1 else 1
+    return arr
+
+
+def symb_noise_add(handle, batch: Batch, X, noise: Sequence, Xn, stream: int = 0) -> None:
+    arr = _noise_array(batch, noise)
+    _check(lib().symb_noise_add(handle, batch.ref(), _ptr(X), arr, _ptr(Xn), stream or None), handle)
+
+
+def symb_base_linear_fwd_denoise(handle, batch: Batch, Xn, W, bias, noise_effect: Sequence, Y, ws=None,
+                                 stream: int = 0) -> None:
+    wp, wb = _ws_args(ws)
+    arr = _noise_array(batch, noise_effect)
+    _check(lib().symb_base_linear_fwd_denoise(handle, batch.ref(), _ptr(Xn), _ptr(W), _ptr(bias), arr, _ptr(Y),
+                                              wp, wb, stream or None), handle)
 
 
 def symb_base_linear_bwd_input(handle, batch: Batch, dY, W, dX, flags: int = SYMB_BWD_FULL, ws=None,

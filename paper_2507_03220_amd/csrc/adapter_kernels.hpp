@@ -431,6 +431,45 @@ __global__ void __launch_bounds__(256) symb_ia3_scale_rows_kernel(const ScalePar
     }
 }
 
+// -------------------------------------------------------------------------------------------
+// Noise prepass of the privacy flow:  out[t][k] = bf16( X[t][k] + n_seg(t)[r][k] ), r = 0 for a
+// broadcast row, else the token's index inside its segment; rows of segments without noise are
+// copied.  One workgroup per row chunk from the work list; fp32 sum, one rounding.
+// -------------------------------------------------------------------------------------------
+struct NoiseAddParams {
+    const bf16* X;
+    bf16* out;
+    int width;
+    const RowChunk* chunks;
+    const int32_t* off;
+    const NoiseDesc* noise;
+};
+__global__ void __launch_bounds__(256) symb_noise_add_kernel(const NoiseAddParams p) {
+    const RowChunk ch = p.chunks[blockIdx.x];
+    const NoiseDesc nd = p.noise[ch.seg];
+    const int nchunk = p.width >> 3, seg0 = p.off[ch.seg];
+    for (int c = threadIdx.x; c < nchunk; c += 256) {
+        const size_t col = (size_t)c * 8;
+        for (int t = 0; t < ch.nrows; ++t) {
+            const int row = ch.row0 + t;
+            uint4 x = *reinterpret_cast<const uint4*>(p.X + (size_t)row * p.width + col);
+            if (nd.ptr) {
+                const uint4 n = *reinterpret_cast<const uint4*>(nd.ptr + (size_t)(nd.rows == 1 ? 0 : row - seg0) * p.width + col);
+                unsigned int xw[4] = {x.x, x.y, x.z, x.w};
+                const unsigned int nw[4] = {n.x, n.y, n.z, n.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float lo = bf16_bits_to_f32((unsigned short)(xw[q] & 0xffffu)) + bf16_bits_to_f32((unsigned short)(nw[q] & 0xffffu));
+                    const float hi = bf16_bits_to_f32((unsigned short)(xw[q] >> 16)) + bf16_bits_to_f32((unsigned short)(nw[q] >> 16));
+                    xw[q] = pack2_bf16(lo, hi);
+                }
+                x = make_uint4(xw[0], xw[1], xw[2], xw[3]);
+            }
+            *reinterpret_cast<uint4*>(p.out + (size_t)row * p.width + col) = x;
+        }
+    }
+}
+
 __global__ void __launch_bounds__(256) symb_fill_zero_kernel(float* dst, size_t n) {
     for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = 0.f;
 }

@@ -39,6 +39,7 @@ struct GemmParams {
                                 // then rpad residuals of the row's own segment; null = no LoRA term
     int ext_pitch;
     int epi_ia3;                // forward: scale rows of IA3 segments by l_i[n]
+    const NoiseDesc* neff;      // device [S] or null: per-segment noise effect subtracted last (privacy flow)
     int walk;                   // 0: each XCD walks one contiguous run of tiles; 1: rounds of 32 tiles dealt to the XCDs in turn
     int stagger;                // start delay unit (s_sleep 127 each) between the 8 phase groups of the first wave of tiles
     double timing_flops;        // host bookkeeping for the measurement hook; unused on the device
@@ -128,7 +129,7 @@ __device__ __forceinline__ uint4 ld_global_16(const bf16* p, bool ok) {
     P "a"(acc[1][2]), P "a"(acc[1][3]), P "a"(acc[2][0]), P "a"(acc[2][1]), P "a"(acc[2][2]), P "a"(acc[2][3]),      \
     P "a"(acc[3][0]), P "a"(acc[3][1]), P "a"(acc[3][2]), P "a"(acc[3][3])
 
-// PLAIN: no bias, no IA3 scale, no pre-adapter output (checked by the host).  The plain
+// PLAIN: no bias, no IA3 scale, no noise effect, no pre-adapter output (checked by the host).  The plain
 // instantiation contains no arithmetic on the accumulators outside the matrix instructions, so
 // they never leave the accumulation registers before the staging loop reads them one by one.
 template <int BM, int BN, int WGM, int WGN, bool NN, bool PLAIN = false>
@@ -505,7 +506,7 @@ symb_gemm_kernel(const GemmParams p) {
         }
     };
     auto stage_out = [&](bf16* __restrict__ dst, bool scale_ia3) __attribute__((always_inline)) {
-        if (PLAIN || (!p.bias && !scale_ia3)) {
+        if (PLAIN || (!p.bias && !scale_ia3 && !p.neff)) {
             for_each_quad([&](int i, int j, int rg, int m, int n) __attribute__((always_inline)) {
                 float v0, v1, v2, v3;
                 read_quad(i, j, rg, v0, v1, v2, v3);
@@ -530,11 +531,23 @@ symb_gemm_kernel(const GemmParams p) {
             for (int i = 0; i < MB; ++i) {
                 const int m = m0 + wm0 + i * 32 + (lane & 31);
                 const bf16* lrow = nullptr;
-                if (scale_ia3 && m < p.M) {
+                const bf16* nrow = nullptr;
+                if ((scale_ia3 || p.neff) && m < p.M) {
                     const int s = seg_of_row(p.off, seg_lo, seg_hi, m);
-                    if (p.seg[s].kind == KIND_IA3) lrow = p.seg[s].A;
+                    if (scale_ia3 && p.seg[s].kind == KIND_IA3) lrow = p.seg[s].A;
+                    if (p.neff) {
+                        const NoiseDesc nd = p.neff[s];
+                        if (nd.ptr) nrow = nd.ptr + (size_t)(nd.rows == 1 ? 0 : m - p.off[s]) * p.N;
+                    }
                 }
-                uint2 lv[NB][4];
+                uint2 lv[NB][4], nv[NB][4];
+#pragma unroll
+                for (int j = 0; j < NB; ++j)
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const int n = nq0 + j * 32 + rg * 8;
+                        nv[j][rg] = (nrow && n < p.N) ? *reinterpret_cast<const uint2*>(nrow + n) : zero2;
+                    }
 #pragma unroll
                 for (int j = 0; j < NB; ++j)
 #pragma unroll
@@ -560,6 +573,12 @@ symb_gemm_kernel(const GemmParams p) {
                             v1 *= bf16_bits_to_f32((unsigned short)(lv[j][rg].x >> 16));
                             v2 *= bf16_bits_to_f32((unsigned short)(lv[j][rg].y & 0xffffu));
                             v3 *= bf16_bits_to_f32((unsigned short)(lv[j][rg].y >> 16));
+                        }
+                        if (p.neff) {              // y = y_noisy - n_eff, still in fp32
+                            v0 -= bf16_bits_to_f32((unsigned short)(nv[j][rg].x & 0xffffu));
+                            v1 -= bf16_bits_to_f32((unsigned short)(nv[j][rg].x >> 16));
+                            v2 -= bf16_bits_to_f32((unsigned short)(nv[j][rg].y & 0xffffu));
+                            v3 -= bf16_bits_to_f32((unsigned short)(nv[j][rg].y >> 16));
                         }
                         uint2 o;
                         o.x = pack2_bf16(v0, v1);
@@ -658,7 +677,7 @@ symb_gemm_kernel(const GemmParams p) {
     if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 4] = __builtin_amdgcn_s_memrealtime();
 #endif
     // ---- final output: bias, IA3 scale, one rounding, whole-row stores
-    stage_out(p.C, p.epi_ia3 != 0);
+    stage_out(p.C, p.epi_ia3 != 0);          // (the noise effect, if any, comes off here; Cbase is never asked for then)
 #ifdef SYMB_GEMM_TRACE
     if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 7] = __builtin_amdgcn_s_memrealtime();
     __builtin_amdgcn_s_waitcnt(0);

@@ -330,7 +330,7 @@ symb_status launch_gemm(symb_handle h, const GemmParams& gp, hipStream_t st) {
     switch (gemm_variant(gp.M, gp.N)) {
         case 0: return launch_gemm_t<256, 256, 2, 4, NN>(h, gp, st);
         case 2:
-            if (!gp.bias && !gp.epi_ia3 && !gp.Cbase) return launch_gemm_t<256, 256, 2, 2, NN, true>(h, gp, st);
+            if (!gp.bias && !gp.epi_ia3 && !gp.Cbase && !gp.neff) return launch_gemm_t<256, 256, 2, 2, NN, true>(h, gp, st);
             return launch_gemm_t<256, 256, 2, 2, NN>(h, gp, st);
         default: return launch_gemm_t<128, 128, 2, 2, NN>(h, gp, st);
     }
@@ -507,14 +507,32 @@ symb_status symb_workspace_bytes(const symb_batch* b, int32_t op, size_t* out) {
 }
 
 // ---------------------------------------------------------------------------------------------
-symb_status symb_base_linear_fwd(symb_handle h, const symb_batch* b, const void* X, const void* W, const void* bias,
-                                 void* Y, void* Ybase, void* ws, size_t ws_bytes, void* stream) {
+// Checks a per-segment noise array (width = row length in elements) and turns it into device descriptors.
+symb_status make_noisedesc(symb_handle h, const symb_batch* b, const symb_noise* noise, const char* what,
+                           std::vector<NoiseDesc>& out) {
+    out.assign(b->num_segments, NoiseDesc{nullptr, 0, 0});
+    for (int i = 0; i < b->num_segments; ++i) {
+        const symb_noise& n = noise[i];
+        if (!n.ptr) continue;
+        const int len = b->seg_offsets[i + 1] - b->seg_offsets[i];
+        if (n.rows != 1 && n.rows != len)
+            return fail(h, SYMB_ERR_INVALID_ARG, "%s of segment %d has %d rows: must be 1 or the segment's %d tokens", what, i, n.rows, len);
+        if (misaligned16(n.ptr)) return fail(h, SYMB_ERR_INVALID_ARG, "%s of segment %d is not 16-byte aligned", what, i);
+        out[i] = NoiseDesc{(const bf16*)n.ptr, n.rows, 0};
+    }
+    return SYMB_OK;
+}
+
+static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* X, const void* W, const void* bias,
+                                const symb_noise* noise_effect, void* Y, void* Ybase, void* ws, size_t ws_bytes, void* stream) {
     symb_status st = check_handle(h);
     if (st != SYMB_OK) return st;
     if ((st = validate(h, b)) != SYMB_OK) return st;
     const BatchInfo bi = inspect(b);
     if (bi.T == 0) return SYMB_OK;
     if (!X || !W || !Y) return fail(h, SYMB_ERR_INVALID_ARG, "X, W and Y are required");
+    std::vector<NoiseDesc> nd;
+    if (noise_effect && (st = make_noisedesc(h, b, noise_effect, "noise effect", nd)) != SYMB_OK) return st;
     if (misaligned16(X) || misaligned16(W) || misaligned16(Y) || misaligned16(Ybase) || misaligned16(bias) || misaligned16(ws))
         return fail(h, SYMB_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
     const WsLayout wl = ws_layout(b, bi, SYMB_OP_FWD, true, false);
@@ -534,6 +552,7 @@ symb_status symb_base_linear_fwd(symb_handle h, const symb_batch* b, const void*
     const size_t o_lo = blob.add(lo.data(), lo.size());
     const size_t o_hi = blob.add(hi.data(), hi.size());
     const size_t o_ch = blob.add(chunks.data(), chunks.size());
+    const size_t o_nd = blob.add(nd.data(), nd.size());
     unsigned char* dev = nullptr;
     if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
 
@@ -566,8 +585,49 @@ symb_status symb_base_linear_fwd(symb_handle h, const symb_batch* b, const void*
     gp.ext = Hs;
     gp.ext_pitch = 2 * bi.max_rpad;
     gp.epi_ia3 = bi.n_ia3 > 0;
+    gp.neff = nd.empty() ? nullptr : (const NoiseDesc*)(dev + o_nd);
     gp.timing_flops = gemm_flops(b, b->d_out, b->d_in, bi.n_lora > 0);
     if ((st = launch_gemm<false>(h, gp, s)) != SYMB_OK) return st;
+    return seal_slot(h, s);
+}
+
+symb_status symb_base_linear_fwd(symb_handle h, const symb_batch* b, const void* X, const void* W, const void* bias,
+                                 void* Y, void* Ybase, void* ws, size_t ws_bytes, void* stream) {
+    return forward_impl(h, b, X, W, bias, nullptr, Y, Ybase, ws, ws_bytes, stream);
+}
+
+symb_status symb_base_linear_fwd_denoise(symb_handle h, const symb_batch* b, const void* Xn, const void* W, const void* bias,
+                                         const symb_noise* noise_effect, void* Y, void* ws, size_t ws_bytes, void* stream) {
+    symb_status st = check_handle(h);
+    if (st != SYMB_OK) return st;
+    if (!noise_effect) return fail(h, SYMB_ERR_INVALID_ARG, "noise_effect is required");
+    return forward_impl(h, b, Xn, W, bias, noise_effect, Y, nullptr, ws, ws_bytes, stream);
+}
+
+symb_status symb_noise_add(symb_handle h, const symb_batch* b, const void* X, const symb_noise* noise, void* Xn, void* stream) {
+    symb_status st = check_handle(h);
+    if (st != SYMB_OK) return st;
+    if ((st = validate(h, b)) != SYMB_OK) return st;
+    if (!noise) return fail(h, SYMB_ERR_INVALID_ARG, "noise is required");
+    const BatchInfo bi = inspect(b);
+    if (bi.T == 0) return SYMB_OK;
+    if (!X || !Xn) return fail(h, SYMB_ERR_INVALID_ARG, "X and Xn are required");
+    if (misaligned16(X) || misaligned16(Xn)) return fail(h, SYMB_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
+    std::vector<NoiseDesc> nd;
+    if ((st = make_noisedesc(h, b, noise, "noise", nd)) != SYMB_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    std::vector<RowChunk> chunks;
+    plan_chunks(b, kSkinnyRows, false, chunks);
+    Blob blob;
+    const size_t o_off = blob.add(b->seg_offsets, (size_t)bi.S + 1);
+    const size_t o_ch = blob.add(chunks.data(), chunks.size());
+    const size_t o_nd = blob.add(nd.data(), nd.size());
+    unsigned char* dev = nullptr;
+    if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
+    NoiseAddParams np{(const bf16*)X, (bf16*)Xn, b->d_in, (const RowChunk*)(dev + o_ch), (const int32_t*)(dev + o_off),
+                      (const NoiseDesc*)(dev + o_nd)};
+    hipLaunchKernelGGL(symb_noise_add_kernel, dim3((unsigned)chunks.size()), dim3(256), 0, s, np);
+    SYMB_HIP(h, hipGetLastError());
     return seal_slot(h, s);
 }
 

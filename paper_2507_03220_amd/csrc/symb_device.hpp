@@ -26,6 +26,13 @@ struct SegDesc {
     float* dB;
 };
 
+// A segment's noise (or noise-effect) rows: rows == 1 broadcasts, else one row per token of the segment.
+struct NoiseDesc {
+    const bf16* ptr;   // null: none for this segment
+    int32_t rows;
+    int32_t pad;
+};
+
 // Round-to-nearest-even fp32 -> bf16 (finite inputs; NaN stays NaN).
 __device__ __forceinline__ unsigned short f32_to_bf16_bits(float f) {
     unsigned int u = __builtin_bit_cast(unsigned int, f);

@@ -290,3 +290,54 @@ def test_adapter_grad_can_reuse_dh_from_the_input_gradient_call():
     sb.symb_adapter_grad(h, b3, Xd, dYd, Yb, sb.SYMB_GRAD_OVERWRITE | sb.SYMB_GRAD_REUSE_DH | sb.SYMB_GRAD_REUSE_HS, ws)
     torch.cuda.synchronize()
     same(plain, both)
+
+
+@pytest.mark.parametrize("shape", [dict(d_in=264, d_out=392, lens=[150, 1, 70, 0, 33]),          # 128x128 tiles
+                                   dict(d_in=200, d_out=6208, lens=[700, 5, 795, 2, 40])])       # 256x256 tiles
+def test_privacy_flow_noise_add_and_denoised_forward(shape):
+    """Sec. 3.8: x + n bit-exact against the oracle's prepass; the denoised forward (noise effect taken
+    off in the epilogue) against the oracle's eqs. (1)-(3) on the same noisy input, usual bar; and
+    the result is the plain layer output up to the roundings the flow adds."""
+    d_in, d_out, lens = shape["d_in"], shape["d_out"], shape["lens"]
+    p = make_problem(31, d_in, d_out, lens, [L, I, N, L, I], [8, 24, 5])
+    off, T = p["off"], p["T"]
+    rng = np.random.default_rng(77)
+    nb = lambda shp: synth.f32_to_bf16_bits(rng.standard_normal(shp).astype(np.float32))
+    noise = [nb((lens[0], d_in)), nb((1, d_in)), None, None, nb((1, d_in))]       # per token, broadcast, none
+    Xn_ref = oracle.noise_add(off, p["X"], noise)
+    h = gh.handle()
+    dev = gh.upload_adapters(p["ads"], d_in, d_out, grads=False)
+    b = sb.Batch(d_in, d_out, off, dev.descs)
+    Xd, Wd, bd = gh.to_dev(p["X"]), gh.to_dev(p["W"]), gh.to_dev(p["bias"])
+    nd = [gh.to_dev(n) for n in noise]
+    Xn = torch.empty_like(Xd)
+    sb.symb_noise_add(h, b, Xd, nd, Xn)
+    torch.cuda.synchronize()
+    assert np.array_equal(gh.bf16_bits(Xn), Xn_ref), "x + n must match bit for bit"
+    # (1) noise effect: the noise rows as a batch of their own, the clients' adapters, no bias
+    keep = [i for i, n in enumerate(noise) if n is not None]
+    noff = np.zeros(len(keep) + 1, dtype=np.int32)
+    noff[1:] = np.cumsum([noise[i].shape[0] for i in keep])
+    nbatch = sb.Batch(d_in, d_out, noff, [dev.descs[i] for i in keep])
+    Nd = torch.cat([nd[i] for i in keep], dim=0).contiguous()
+    Neff = torch.empty((int(noff[-1]), d_out), device="cuda", dtype=torch.bfloat16)
+    sb.symb_base_linear_fwd(h, nbatch, Nd, Wd, None, Neff, None, gh.workspace(nbatch, sb.SYMB_OP_FWD))
+    neff = [None] * len(noise)
+    for q, i in enumerate(keep):
+        neff[i] = Neff[int(noff[q]):int(noff[q + 1])]
+    # (2) + (3)
+    Y = torch.empty((T, d_out), device="cuda", dtype=torch.bfloat16)
+    sb.symb_base_linear_fwd_denoise(h, b, Xn, Wd, bd, neff, Y, gh.workspace(b, sb.SYMB_OP_FWD))
+    torch.cuda.synchronize()
+    oads = oracle_ads(p["ads"])
+    Yr = oracle.forward_private(off, oads, Xn_ref, p["W"], p["bias"], noise)
+    assert_close(gh.bf16_to_f64(Y), Yr, "denoised Y", out_bf16=True)
+    _, Yplain = oracle.forward(off, oads, p["X"], p["W"], p["bias"])
+    from helpers import rel_fro
+    assert rel_fro(gh.bf16_to_f64(Y), Yplain) < 1e-2          # x + n is rounded to bf16 once: not the 4e-3 bar
+    # a noise tensor with the wrong number of rows is refused before anything is launched
+    bad = list(nd)
+    bad[0] = nd[0][:2]
+    with pytest.raises(sb.SymbError) as e:
+        sb.symb_noise_add(h, b, Xd, bad, Xn)
+    assert e.value.status == sb.SYMB_ERR_INVALID_ARG

@@ -331,6 +331,73 @@ def test_noise_effect_subtraction_is_exact():
     np.testing.assert_array_equal(y_noisy - n_eff, y)
 
 
+def _round_to_bf16_by_definition(v: Fraction) -> Fraction:
+    """Nearest value with an 8-bit significand, ties to the even significand (normal range)."""
+    if v == 0:
+        return Fraction(0)
+    a, e = abs(v), 0
+    while a >= 2 ** (e + 1):
+        e += 1
+    while a < 2 ** e:
+        e -= 1
+    q = Fraction(2) ** (e - 7)                  # spacing of 8-bit significands in [2^e, 2^(e+1))
+    k = a / q
+    lo = k.numerator // k.denominator
+    r = k - lo
+    if r > Fraction(1, 2) or (r == Fraction(1, 2) and lo % 2 == 1):
+        lo += 1
+    return (q * lo) * (1 if v > 0 else -1)
+
+
+def test_noise_add_rounds_the_exact_sum_once():
+    """Client prepass x + n (Sec. 3.8): against the exact rational sum rounded by the definition of
+    round-to-nearest-even; broadcast, per-token and absent noise, one empty segment."""
+    rng = np.random.default_rng(33)
+    d = 7
+    off = np.array([0, 3, 3, 8, 10], dtype=np.int32)
+    X = synth.f32_to_bf16_bits(rng.standard_normal((10, d)).astype(np.float32))
+    per_tok = synth.f32_to_bf16_bits(rng.standard_normal((3, d)).astype(np.float32))
+    bcast = synth.f32_to_bf16_bits(rng.standard_normal((1, d)).astype(np.float32))
+    noise = [per_tok, None, bcast, None]
+    out = oracle.noise_add(off, X, noise)
+    xf, of = synth.bf16_bits_to_f64(X), synth.bf16_bits_to_f64(out)
+    for t in range(10):
+        seg = int(np.searchsorted(off, t, side="right") - 1)
+        for k in range(d):
+            if noise[seg] is None:
+                assert out[t, k] == X[t, k]
+                continue
+            n = synth.bf16_bits_to_f64(noise[seg])[0 if noise[seg].shape[0] == 1 else t - off[seg], k]
+            want = _round_to_bf16_by_definition(Fraction(float(xf[t, k])) + Fraction(float(n)))
+            assert Fraction(float(of[t, k])) == want, (t, k)
+    with pytest.raises(ValueError):
+        oracle.noise_add(off, X, [np.zeros((2, d), np.uint16), None, None, None])   # 2 rows for a 3-token segment
+
+
+def test_private_forward_equals_plain_forward_for_every_adapter_kind():
+    """Eqs. (1)-(3) of Sec. 3.8 with adapters on: the layer plus a LoRA / IA3 adapter is still linear, so
+    noise added before and its bias-free effect removed after leave the plain result, exactly when
+    x + n needs no rounding.  A noise effect computed with the bias in would fail this."""
+    p = tiny_problem(seed=5, d_in=6, d_out=4, lens=(3, 0, 2, 2, 4))
+    rng = np.random.default_rng(5)
+    off, ads = p["off"], p["ads"]
+    X = grid_bits(rng, (p["T"], 6), -6, 6)
+    noise = [grid_bits(rng, (3, 6), -6, 6), None, grid_bits(rng, (1, 6), -6, 6), None, grid_bits(rng, (4, 6), -6, 6)]
+    Xn = oracle.noise_add(off, X, noise)
+    # on this grid the sums are exact: Xn holds x + n itself
+    full = np.zeros((p["T"], 6))
+    for i, n in enumerate(noise):
+        if n is not None:
+            full[off[i]:off[i + 1]] = f64(n) if n.shape[0] > 1 else np.repeat(f64(n), off[i + 1] - off[i], axis=0)
+    np.testing.assert_array_equal(f64(Xn), f64(X) + full)
+    _, y = oracle.forward(off, ads, X, p["W"], p["bias"])
+    yp = oracle.forward_private(off, ads, Xn, p["W"], p["bias"], noise)
+    np.testing.assert_allclose(yp, y, rtol=0, atol=1e-11)
+    # rows subset
+    rows = np.array([10, 0, 5], dtype=np.int32)
+    np.testing.assert_array_equal(oracle.forward_private(off, ads, Xn, p["W"], p["bias"], noise, rows=rows), yp[rows])
+
+
 # ---------------------------------------------------------------------------
 # P9: adapter-index probe with exactly representable values
 # ---------------------------------------------------------------------------
