@@ -105,11 +105,18 @@ typedef struct {
     void* dB;          /* DEVICE fp32, layout of B; NULL = no gradient wanted */
 } symb_adapter;
 
+/* Storage of the frozen weight.  The base layers the paper serves are nn.Linear or Conv1D
+ * (Sec. 3.7, 3.8): the same linear map, the weight stored output-major or input-major. */
+typedef enum { SYMB_WEIGHT_LINEAR = 0,   /* W [d_out][d_in]: y = x W^T + b  (nn.Linear) */
+               SYMB_WEIGHT_CONV1D = 1    /* W [d_in][d_out]: y = x W + b    (Conv1D of GPT-2-style models) */
+             } symb_weight_layout;
+
 /* A flattened batch (Sec. 3.7): segment offsets plus one adapter per segment. */
 typedef struct {
     int32_t d_in, d_out, num_segments;
     const int32_t* seg_offsets;    /* HOST, num_segments+1 entries, off[0]=0, non-decreasing; T = off[S] */
     const symb_adapter* adapters;  /* HOST, num_segments entries */
+    int32_t weight_layout;         /* symb_weight_layout of the W passed with this batch; adapters keep their layouts */
 } symb_batch;
 
 typedef struct symb_context* symb_handle;

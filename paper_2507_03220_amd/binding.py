@@ -22,6 +22,7 @@ SYMB_OP_FWD, SYMB_OP_BWD_INPUT, SYMB_OP_ADAPTER_GRAD = range(3)
 SYMB_BWD_FULL, SYMB_BWD_BASE_ONLY = 0, 1
 SYMB_GRAD_OVERWRITE, SYMB_GRAD_ACCUMULATE, SYMB_GRAD_REUSE_DH, SYMB_GRAD_REUSE_HS = 0, 1, 2, 4
 SYMB_MAX_RANK = 128
+SYMB_WEIGHT_LINEAR, SYMB_WEIGHT_CONV1D = 0, 1
 
 EXPORTS = ("symb_create", "symb_destroy", "symb_validate_batch", "symb_debug_row_segment_map",
            "symb_plan_row_tiles", "symb_workspace_bytes", "symb_base_linear_fwd",
@@ -41,7 +42,8 @@ class symb_noise(C.Structure):
 
 class symb_batch(C.Structure):
     _fields_ = [("d_in", C.c_int32), ("d_out", C.c_int32), ("num_segments", C.c_int32),
-                ("seg_offsets", C.POINTER(C.c_int32)), ("adapters", C.POINTER(symb_adapter))]
+                ("seg_offsets", C.POINTER(C.c_int32)), ("adapters", C.POINTER(symb_adapter)),
+                ("weight_layout", C.c_int32)]
 
 
 class SymbError(RuntimeError):
@@ -119,7 +121,8 @@ class Adapter:
 class Batch:
     """Owns the C arrays of one symb_batch (host offsets + per-segment descriptors)."""
 
-    def __init__(self, d_in: int, d_out: int, seg_offsets: Sequence[int], adapters: Sequence[Adapter]):
+    def __init__(self, d_in: int, d_out: int, seg_offsets: Sequence[int], adapters: Sequence[Adapter],
+                 weight_layout: int = 0):
         S = len(adapters)
         if len(seg_offsets) != S + 1:
             raise ValueError("seg_offsets must have num_segments + 1 entries")
@@ -130,7 +133,7 @@ class Batch:
             d = self._ad[i]
             d.kind, d.rank, d.scale = int(a.kind), int(a.rank), float(a.scale)
             d.A, d.B, d.dA, d.dB = _ptr(a.A), _ptr(a.B), _ptr(a.dA), _ptr(a.dB)
-        self.c = symb_batch(int(d_in), int(d_out), S, self._off, self._ad)
+        self.c = symb_batch(int(d_in), int(d_out), S, self._off, self._ad, int(weight_layout))
         self.d_in, self.d_out, self.S = int(d_in), int(d_out), S
         self.T = int(seg_offsets[-1]) if S >= 0 and len(seg_offsets) else 0
 

@@ -186,6 +186,25 @@ __global__ void __launch_bounds__(256) symb_pack_bt_kernel(const PackParams p) {
     for (int q = 0; q < sd.rpad; ++q) dst[(size_t)q * p.d_out + j] = (q < sd.rank) ? src[q] : (unsigned short)0;
 }
 
+// Packs A_i [r][d_in] into A_i^T [d_in][r] (exactly r columns): the adapter-side operand of the
+// input gradient when the base weight is stored input-major (the K-contiguous GEMM then wants the
+// adapter rows rank-contiguous per input column).  grid.y = segment, grid.x covers d_in.
+struct PackAtParams {
+    const SegDesc* seg;
+    bf16* packed;
+    const int64_t* packed_off;
+    int d_in;
+};
+__global__ void __launch_bounds__(256) symb_pack_at_kernel(const PackAtParams p) {
+    const SegDesc sd = p.seg[blockIdx.y];
+    if (sd.kind != KIND_LORA) return;
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    if (k >= p.d_in) return;
+    unsigned short* dst = reinterpret_cast<unsigned short*>(p.packed + p.packed_off[blockIdx.y]) + (size_t)k * sd.rank;
+    const unsigned short* src = reinterpret_cast<const unsigned short*>(sd.A);
+    for (int q = 0; q < sd.rank; ++q) dst[q] = src[(size_t)q * p.d_in + k];
+}
+
 // -------------------------------------------------------------------------------------------
 // LoRA parameter gradients of one segment, contraction over its tokens:
 //   G[c][pp] = sum_t R[t][c] * L[t][pp]

@@ -73,6 +73,8 @@ symb_status validate(symb_handle h, const symb_batch* b) {
     if (!b) return fail(h, SYMB_ERR_INVALID_ARG, "batch is null");
     if (b->d_in <= 0 || b->d_out <= 0) return fail(h, SYMB_ERR_INVALID_ARG, "d_in and d_out must be positive");
     if ((b->d_in % 8) || (b->d_out % 8)) return fail(h, SYMB_ERR_INVALID_ARG, "d_in and d_out must be multiples of 8");
+    if (b->weight_layout != SYMB_WEIGHT_LINEAR && b->weight_layout != SYMB_WEIGHT_CONV1D)
+        return fail(h, SYMB_ERR_INVALID_ARG, "unknown weight layout %d", b->weight_layout);
     if (b->num_segments < 0) return fail(h, SYMB_ERR_INVALID_ARG, "num_segments is negative");
     if (!b->seg_offsets) return fail(h, SYMB_ERR_INVALID_ARG, "seg_offsets is null");
     if (b->num_segments > 0 && !b->adapters) return fail(h, SYMB_ERR_INVALID_ARG, "adapters is null");
@@ -141,7 +143,8 @@ struct BatchInfo {
     int S = 0, T = 0;
     int n_lora = 0, n_ia3 = 0;
     int max_rpad = 0;
-    size_t packed_elems = 0;   // sum rpad_i * d_out over LoRA segments
+    size_t packed_elems = 0;   // sum rpad_i * d_out over LoRA segments (packed B^T)
+    size_t packed_at_elems = 0;// sum r_i * d_in over LoRA segments (packed A^T, input-major weight only)
 };
 
 BatchInfo inspect(const symb_batch* b) {
@@ -154,6 +157,7 @@ BatchInfo inspect(const symb_batch* b) {
             ++bi.n_lora;
             bi.max_rpad = std::max(bi.max_rpad, rpad_of(a.rank));
             bi.packed_elems += (size_t)rpad_of(a.rank) * b->d_out;
+            bi.packed_at_elems += align_up((size_t)a.rank * b->d_in, 8);
         } else if (a.kind == SYMB_ADAPTER_IA3) {
             ++bi.n_ia3;
         }
@@ -170,6 +174,7 @@ struct WsLayout {
     size_t dh_off = 0, dh_bytes = 0;      // dH  [T][2*max_rpad] bf16
     size_t pk_off = 0, pk_bytes = 0;      // packed B^T
     size_t sc_off = 0, sc_bytes = 0;      // IA3-scaled copy of dY [T][d_out] bf16
+    size_t pa_off = 0, pa_bytes = 0;      // packed A^T (input-major weight, input gradient only)
     size_t total = 0;
 };
 
@@ -182,8 +187,13 @@ WsLayout ws_layout(const symb_batch* b, const BatchInfo& bi, int op, bool full_b
         cur += align_up(n, 256);
     };
     const size_t hb = (size_t)bi.T * (2 * bi.max_rpad) * 2;   // value + residual halves
+    const bool conv1d = b->weight_layout == SYMB_WEIGHT_CONV1D;
     if (op == SYMB_OP_FWD) {
         if (bi.n_lora) take(w.h_off, w.h_bytes, hb);
+        if (bi.n_lora && conv1d) {            // the N-contiguous GEMM wants B_i^T: same packing as the input gradient's
+            take(w.dh_off, w.dh_bytes, hb);   // (gap: keeps packed B^T where the other operations have it)
+            take(w.pk_off, w.pk_bytes, bi.packed_elems * 2);
+        }
     } else if (op == SYMB_OP_BWD_INPUT) {
         if (full_bwd && bi.n_lora) {
             take(w.h_off, w.h_bytes, hb);     // not touched here: keeps the forward call's Hs intact
@@ -191,6 +201,7 @@ WsLayout ws_layout(const symb_batch* b, const BatchInfo& bi, int op, bool full_b
             take(w.pk_off, w.pk_bytes, bi.packed_elems * 2);
         }
         if (full_bwd && bi.n_ia3) take(w.sc_off, w.sc_bytes, (size_t)bi.T * b->d_out * 2);
+        if (full_bwd && bi.n_lora && conv1d) take(w.pa_off, w.pa_bytes, bi.packed_at_elems * 2);
     } else {
         if (any_lora_grad) {
             take(w.h_off, w.h_bytes, hb);
@@ -546,18 +557,39 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     std::vector<RowChunk> chunks;
     plan_chunks(b, kSkinnyRows, true, chunks);
     const std::vector<SegDesc> sd = make_segdesc(b);
+    unsigned char* wsb = (unsigned char*)ws;
+    // Input-major weight: the forward is the N-contiguous GEMM, whose LoRA steps read the adapter
+    // side as [rank][d_out] rows: B_i^T, packed into the workspace; a second descriptor set points there.
+    const bool conv1d = b->weight_layout == SYMB_WEIGHT_CONV1D;
+    std::vector<SegDesc> sd_gemm = sd;
+    std::vector<int64_t> pk_off(bi.S, 0);
+    if (conv1d && bi.n_lora) {
+        int64_t cur = 0;
+        for (int i = 0; i < bi.S; ++i)
+            if (sd[i].kind == KIND_LORA) {
+                pk_off[i] = cur;
+                sd_gemm[i].A = (const bf16*)(wsb + wl.pk_off) + cur;
+                cur += (int64_t)sd[i].rpad * b->d_out;
+            }
+    }
     Blob blob;
     const size_t o_seg = blob.add(sd.data(), sd.size());
+    const size_t o_segg = blob.add(sd_gemm.data(), sd_gemm.size());
     const size_t o_off = blob.add(b->seg_offsets, (size_t)bi.S + 1);
     const size_t o_lo = blob.add(lo.data(), lo.size());
     const size_t o_hi = blob.add(hi.data(), hi.size());
     const size_t o_ch = blob.add(chunks.data(), chunks.size());
     const size_t o_nd = blob.add(nd.data(), nd.size());
+    const size_t o_pk = blob.add(pk_off.data(), pk_off.size());
     unsigned char* dev = nullptr;
     if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
 
-    unsigned char* wsb = (unsigned char*)ws;
     bf16* Hs = bi.n_lora ? (bf16*)(wsb + wl.h_off) : nullptr;
+    if (conv1d && bi.n_lora) {
+        PackParams pp{(const SegDesc*)(dev + o_seg), (bf16*)(wsb + wl.pk_off), (const int64_t*)(dev + o_pk), b->d_out};
+        hipLaunchKernelGGL(symb_pack_bt_kernel, dim3((b->d_out + 255) / 256, bi.S), dim3(256), 0, s, pp);
+        SYMB_HIP(h, hipGetLastError());
+    }
     if (bi.n_lora) {
         SkinnyParams sp{};
         sp.L = (const bf16*)X;
@@ -579,7 +611,7 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     gp.N = b->d_out;
     gp.K = b->d_in;
     gp.off = (const int32_t*)(dev + o_off);
-    gp.seg = (const SegDesc*)(dev + o_seg);
+    gp.seg = (const SegDesc*)(dev + o_segg);
     gp.tile_seg_lo = (const int32_t*)(dev + o_lo);
     gp.tile_seg_hi = (const int32_t*)(dev + o_hi);
     gp.ext = Hs;
@@ -587,7 +619,9 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     gp.epi_ia3 = bi.n_ia3 > 0;
     gp.neff = nd.empty() ? nullptr : (const NoiseDesc*)(dev + o_nd);
     gp.timing_flops = gemm_flops(b, b->d_out, b->d_in, bi.n_lora > 0);
-    if ((st = launch_gemm<false>(h, gp, s)) != SYMB_OK) return st;
+    // W [d_out][d_in]: K-contiguous weight rows.  W [d_in][d_out]: the weight is the [K][N] operand.
+    st = conv1d ? launch_gemm<true>(h, gp, s) : launch_gemm<false>(h, gp, s);
+    if (st != SYMB_OK) return st;
     return seal_slot(h, s);
 }
 
@@ -657,29 +691,45 @@ symb_status symb_base_linear_bwd_input(symb_handle h, const symb_batch* b, const
     if (lora) plan_chunks(b, kSkinnyRows, true, chunks);
     if (ia3) plan_chunks(b, kSkinnyRows, false, all_chunks);
     const std::vector<SegDesc> sd = make_segdesc(b);
-    std::vector<int64_t> pk_off(bi.S, 0);
+    unsigned char* wsb = (unsigned char*)ws;
+    // Input-major weight: the input gradient is the K-contiguous GEMM (W rows are d_out long),
+    // whose LoRA steps read the adapter side as [d_in][rank] rows: A_i^T, packed into the workspace.
+    const bool conv1d = b->weight_layout == SYMB_WEIGHT_CONV1D;
+    std::vector<SegDesc> sd_gemm = sd;
+    std::vector<int64_t> pk_off(bi.S, 0), pa_off(bi.S, 0);
     {
-        int64_t cur = 0;
+        int64_t cur = 0, cura = 0;
         for (int i = 0; i < bi.S; ++i)
             if (sd[i].kind == KIND_LORA) {
                 pk_off[i] = cur;
                 cur += (int64_t)sd[i].rpad * b->d_out;
+                if (conv1d && lora) {
+                    pa_off[i] = cura;
+                    sd_gemm[i].B = (const bf16*)(wsb + wl.pa_off) + cura;
+                    cura += (int64_t)align_up((size_t)sd[i].rank * b->d_in, 8);
+                }
             }
     }
     Blob blob;
     const size_t o_seg = blob.add(sd.data(), sd.size());
+    const size_t o_segg = blob.add(sd_gemm.data(), sd_gemm.size());
     const size_t o_off = blob.add(b->seg_offsets, (size_t)bi.S + 1);
     const size_t o_lo = blob.add(lo.data(), lo.size());
     const size_t o_hi = blob.add(hi.data(), hi.size());
     const size_t o_ch = blob.add(chunks.data(), chunks.size());
     const size_t o_all = blob.add(all_chunks.data(), all_chunks.size());
     const size_t o_pk = blob.add(pk_off.data(), pk_off.size());
+    const size_t o_pa = blob.add(pa_off.data(), pa_off.size());
     unsigned char* dev = nullptr;
     if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
 
-    unsigned char* wsb = (unsigned char*)ws;
     const bf16* a_op = (const bf16*)dY;
     bf16* dH = nullptr;
+    if (lora && conv1d) {
+        PackAtParams pa{(const SegDesc*)(dev + o_seg), (bf16*)(wsb + wl.pa_off), (const int64_t*)(dev + o_pa), b->d_in};
+        hipLaunchKernelGGL(symb_pack_at_kernel, dim3((b->d_in + 255) / 256, bi.S), dim3(256), 0, s, pa);
+        SYMB_HIP(h, hipGetLastError());
+    }
     if (lora) {
         dH = (bf16*)(wsb + wl.dh_off);
         PackParams pp{(const SegDesc*)(dev + o_seg), (bf16*)(wsb + wl.pk_off), (const int64_t*)(dev + o_pk), b->d_out};
@@ -711,14 +761,16 @@ symb_status symb_base_linear_bwd_input(symb_handle h, const symb_batch* b, const
     gp.N = b->d_in;
     gp.K = b->d_out;
     gp.off = (const int32_t*)(dev + o_off);
-    gp.seg = (const SegDesc*)(dev + o_seg);
+    gp.seg = (const SegDesc*)(dev + o_segg);
     gp.tile_seg_lo = (const int32_t*)(dev + o_lo);
     gp.tile_seg_hi = (const int32_t*)(dev + o_hi);
     gp.ext = dH;
     gp.ext_pitch = 2 * bi.max_rpad;
     gp.epi_ia3 = 0;
     gp.timing_flops = gemm_flops(b, b->d_in, b->d_out, lora);
-    if ((st = launch_gemm<true>(h, gp, s)) != SYMB_OK) return st;
+    // W [d_out][d_in] is the [K][N] operand of dX = dY W; W [d_in][d_out] gives K-contiguous rows.
+    st = conv1d ? launch_gemm<false>(h, gp, s) : launch_gemm<true>(h, gp, s);
+    if (st != SYMB_OK) return st;
     return seal_slot(h, s);
 }
 

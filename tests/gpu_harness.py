@@ -84,13 +84,18 @@ def stream_ptr() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
-def forward(off, ads: Sequence[HostAdapter], X, W, bias=None, want_base=True):
+def weight_to_dev(W: np.ndarray, conv1d: bool):
+    """W is given as [d_out][d_in]; an input-major (Conv1D) layer stores its transpose [d_in][d_out]."""
+    return to_dev(np.ascontiguousarray(W.T) if conv1d else W)
+
+
+def forward(off, ads: Sequence[HostAdapter], X, W, bias=None, want_base=True, conv1d=False):
     """Returns (Y, Ybase) device tensors [T, d_out] bf16 (Ybase None if not wanted)."""
     d_out, d_in = W.shape
     dev = upload_adapters(ads, d_in, d_out, grads=False)
-    batch = sb.Batch(d_in, d_out, off, dev.descs)
+    batch = sb.Batch(d_in, d_out, off, dev.descs, sb.SYMB_WEIGHT_CONV1D if conv1d else sb.SYMB_WEIGHT_LINEAR)
     T = int(off[-1])
-    Xd, Wd, bd = to_dev(X), to_dev(W), to_dev(bias)
+    Xd, Wd, bd = to_dev(X), weight_to_dev(W, conv1d), to_dev(bias)
     Y = torch.full((T, d_out), float("nan"), device="cuda", dtype=torch.bfloat16)
     Yb = torch.full((T, d_out), float("nan"), device="cuda", dtype=torch.bfloat16) if want_base else None
     ws = workspace(batch, sb.SYMB_OP_FWD)
@@ -99,12 +104,12 @@ def forward(off, ads: Sequence[HostAdapter], X, W, bias=None, want_base=True):
     return Y, Yb
 
 
-def backward_input(off, ads: Sequence[HostAdapter], dY, W, base_only=False):
+def backward_input(off, ads: Sequence[HostAdapter], dY, W, base_only=False, conv1d=False):
     d_out, d_in = W.shape
     dev = upload_adapters(ads, d_in, d_out, grads=False)
-    batch = sb.Batch(d_in, d_out, off, dev.descs)
+    batch = sb.Batch(d_in, d_out, off, dev.descs, sb.SYMB_WEIGHT_CONV1D if conv1d else sb.SYMB_WEIGHT_LINEAR)
     T = int(off[-1])
-    gd, Wd = to_dev(dY), to_dev(W)
+    gd, Wd = to_dev(dY), weight_to_dev(W, conv1d)
     dX = torch.full((T, d_in), float("nan"), device="cuda", dtype=torch.bfloat16)
     ws = workspace(batch, sb.SYMB_OP_BWD_INPUT)
     sb.symb_base_linear_bwd_input(handle(), batch, gd, Wd, dX,

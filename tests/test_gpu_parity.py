@@ -341,3 +341,24 @@ def test_privacy_flow_noise_add_and_denoised_forward(shape):
     with pytest.raises(sb.SymbError) as e:
         sb.symb_noise_add(h, b, Xd, bad, Xn)
     assert e.value.status == sb.SYMB_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("case", [
+    dict(seed=41, d_in=320, d_out=264, lens=[130, 1, 0, 77, 1, 300, 64], kinds=[L, I, L, N, L, L, I], ranks=[8, 16, 5, 24, 33]),
+    dict(seed=42, d_in=136, d_out=6208, lens=[700, 5, 795], kinds=[L, I, L], ranks=[16, 8]),      # 256x256 tiles, forward
+    dict(seed=43, d_in=6208, d_out=136, lens=[700, 5, 795], kinds=[L, I, L], ranks=[16, 5]),      # 256x256 tiles, backward
+])
+def test_input_major_weight_layout(case):
+    """Conv1D-style storage W [d_in][d_out] (Sec. 3.7, 3.8: the base layers are nn.Linear or Conv1D):
+    the same linear map, so the oracle is unchanged and only the GPU gets the transposed array."""
+    c = dict(case)
+    p = make_problem(c.pop("seed"), c.pop("d_in"), c.pop("d_out"), c.pop("lens"), c.pop("kinds"), c.pop("ranks"))
+    oads, off = oracle_ads(p["ads"]), p["off"]
+    Y, Yb = gh.forward(off, p["ads"], p["X"], p["W"], p["bias"], want_base=True, conv1d=True)
+    Y0r, Yr = oracle.forward(off, oads, p["X"], p["W"], p["bias"])
+    assert_close(gh.bf16_to_f64(Y), Yr, "conv1d Y", out_bf16=True)
+    assert_close(gh.bf16_to_f64(Yb), Y0r, "conv1d Ybase", out_bf16=True)
+    for base_only in (False, True):
+        dX = gh.backward_input(off, p["ads"], p["dY"], p["W"], base_only=base_only, conv1d=True)
+        dXr = oracle.backward_input(off, oads, p["dY"], p["W"], base_only=base_only)
+        assert_close(gh.bf16_to_f64(dX), dXr, f"conv1d dX base_only={base_only}", out_bf16=True)

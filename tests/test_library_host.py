@@ -113,9 +113,20 @@ def test_workspace_bytes_formula():
     # Hs (left alone by the input-gradient call), dH, packed B^T, IA3-scaled dY
     assert sb.symb_workspace_bytes(b, sb.SYMB_OP_BWD_INPUT) == 2 * up(T * rp * 2) + up(packed) + up(T * 128 * 2)
     assert sb.symb_workspace_bytes(b, sb.SYMB_OP_ADAPTER_GRAD) == 2 * up(T * rp * 2) + up(packed)   # Hs, dH, packed B^T
+    # input-major (Conv1D) weight: forward also packs B^T (at the offset the other operations use), the
+    # input gradient also packs A^T (5*64 and 40*64 elements, each rounded up to 8)
+    c = sb.Batch(64, 128, [0, 10, 20, 30, 100], ads, sb.SYMB_WEIGHT_CONV1D)
+    assert sb.symb_workspace_bytes(c, sb.SYMB_OP_FWD) == 2 * up(T * rp * 2) + up(packed)
+    assert sb.symb_workspace_bytes(c, sb.SYMB_OP_BWD_INPUT) == 2 * up(T * rp * 2) + up(packed) + up(T * 128 * 2) + up((5 * 64 + 40 * 64) * 2)
+    assert sb.symb_workspace_bytes(c, sb.SYMB_OP_ADAPTER_GRAD) == 2 * up(T * rp * 2) + up(packed)
     none = sb.Batch(64, 128, [0, 100], [sb.Adapter()])
     for op in (sb.SYMB_OP_FWD, sb.SYMB_OP_BWD_INPUT, sb.SYMB_OP_ADAPTER_GRAD):
         assert sb.symb_workspace_bytes(none, op) == 0
+
+
+def test_unknown_weight_layout_is_rejected():
+    b = sb.Batch(64, 64, [0, 4], [sb.Adapter()], weight_layout=7)
+    assert sb.lib().symb_validate_batch(b.ref()) == sb.SYMB_ERR_INVALID_ARG
 
 
 def test_compute_entry_points_fail_cleanly_without_gpu():
