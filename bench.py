@@ -103,6 +103,36 @@ def cpu_baseline(cfg: str, budget_s: float = 20.0) -> dict:
             "seconds": total_t}
 
 
+def per_projection(runs, stream_obj, stream, reps: int = 5) -> list:
+    """Median event time of each call of each projection, run alone (outside the timed region)."""
+    import statistics
+    import torch
+    out = []
+
+    def timed(fn):
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream_obj)
+            fn()
+            e1.record(stream_obj)
+            e1.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return statistics.median(ts)
+
+    for r in runs:
+        fl = r.flops()
+        t_f = timed(lambda: r.fwd(stream))
+        t_b = timed(lambda: r.bwd_input(stream))
+        r.bwd_input(stream)
+        t_g = timed(lambda: r.adapter_grad(stream))       # stand-alone: recomputes Hs and dH
+        out.append({"name": r.name, "d_in": r.d_in, "d_out": r.d_out,
+                    "fwd_ms": round(t_f, 4), "bwd_input_ms": round(t_b, 4), "adapter_grad_ms": round(t_g, 4),
+                    "fwd_tflops": round((fl["base_fwd"] + fl["ad_fwd"]) / t_f / 1e9, 1),
+                    "bwd_input_tflops": round(fl["base_bwd"] / t_b / 1e9, 1)})
+    return out
+
+
 def measured_traffic(variant: int):
     """HBM bytes per launch of the dominant GEMM kernel, from the rocprofv3 --pmc summary
     committed under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy); None if absent."""
@@ -124,6 +154,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-detail", action="store_true", help="skip the per-projection timings taken after the timed region")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (counter calibration under rocprofv3 --pmc)")
@@ -217,6 +248,8 @@ def main() -> int:
             "traffic": measured_traffic(dom),
         },
     }
+    if not args.no_detail:
+        out["per_projection"] = per_projection(runs, stream_obj, stream)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, args.cpu_budget)
         out["cpu_baseline"]["value"] = float("%.3g" % out["cpu_baseline"]["value"])

@@ -99,9 +99,9 @@ typedef struct {
     int32_t kind;      /* symb_adapter_kind */
     int32_t rank;      /* LoRA: r >= 1 (any integer up to SYMB_MAX_RANK); otherwise ignored */
     float scale;       /* LoRA: s = alpha / r, passed explicitly; otherwise ignored */
-    const void* A;     /* DEVICE. LoRA: bf16 [rank][d_in].  IA3: bf16 l[d_out] */
+    const void* A;     /* DEVICE. LoRA: bf16 [rank][d_in].  IA3: bf16 l[d_out].  IA3_IN: bf16 l[d_in] */
     const void* B;     /* DEVICE. LoRA: bf16 [d_out][rank].  otherwise NULL */
-    void* dA;          /* DEVICE fp32, layout of A (IA3: dl[d_out]); NULL = no gradient wanted */
+    void* dA;          /* DEVICE fp32, layout of A (IA3: dl[d_out], IA3_IN: dl[d_in]); NULL = no gradient wanted */
     void* dB;          /* DEVICE fp32, layout of B; NULL = no gradient wanted */
 } symb_adapter;
 
@@ -194,6 +194,12 @@ symb_status symb_base_linear_fwd_denoise(symb_handle h, const symb_batch* b, con
 symb_status symb_base_linear_bwd_input(symb_handle h, const symb_batch* b, const void* dY,
                                        const void* W, void* dX, uint32_t flags, void* ws,
                                        size_t ws_bytes, void* stream);
+/* The same, with an optional second output dXbase [T'][d_in] bf16 DEVICE: the input gradient
+ * before the input-side adapter terms (LoRA branch, IA3 input scale), i.e. what the paper's
+ * executor hands back (Sec. 3.6).  A client with an IA3_IN adapter keeps it for dl (below). */
+symb_status symb_base_linear_bwd_input_ex(symb_handle h, const symb_batch* b, const void* dY,
+                                          const void* W, void* dX, void* dXbase, uint32_t flags,
+                                          void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Adapter gradients per segment (the client-side autograd of Sec. 3.2, fused here):
@@ -206,6 +212,11 @@ symb_status symb_base_linear_bwd_input(symb_handle h, const symb_batch* b, const
 symb_status symb_adapter_grad(symb_handle h, const symb_batch* b, const void* X, const void* dY,
                               const void* Ybase, uint32_t flags, void* ws, size_t ws_bytes,
                               void* stream);
+/* The same, with dXbase [T'][d_in] bf16 DEVICE (from symb_base_linear_bwd_input_ex), required iff
+ * some IA3_IN segment wants dl:  dl_i[k] = sum_t X[t][k] * dXbase[t][k]. */
+symb_status symb_adapter_grad_ex(symb_handle h, const symb_batch* b, const void* X, const void* dY,
+                                 const void* Ybase, const void* dXbase, uint32_t flags, void* ws,
+                                 size_t ws_bytes, void* stream);
 
 /*
  * Measurement hook (not part of the method): while enabled, every launch of the base

@@ -207,9 +207,11 @@ def lora_grad(off, adapters: Sequence[Adapter], X: np.ndarray, dY: np.ndarray, i
 
 
 def ia3_grad(off, adapters: Sequence[Adapter], X: np.ndarray, dY: np.ndarray, W: np.ndarray,
-             bias: Optional[np.ndarray], i: int, cols=None, Y0_saved: Optional[np.ndarray] = None) -> np.ndarray:
+             bias: Optional[np.ndarray], i: int, cols=None, Y0_saved: Optional[np.ndarray] = None,
+             G_saved: Optional[np.ndarray] = None) -> np.ndarray:
     """Returns dl (fp64) of IA3 / IA3_IN segment i for the listed channels (default: all).
-    Y0_saved: optional bf16 bits [T, d_out] of the base output the client kept from forward."""
+    Y0_saved: optional bf16 bits [T, d_out] of the base output the client kept from forward (IA3).
+    G_saved: optional bf16 bits [T, d_in] of the input gradient dY W the executor returned (IA3_IN)."""
     off = _i32(off)
     S = len(off) - 1
     d_out, d_in = W.shape
@@ -222,7 +224,7 @@ def ia3_grad(off, adapters: Sequence[Adapter], X: np.ndarray, dY: np.ndarray, W:
                                     off.ctypes.data_as(C.c_void_p), ad, _u16(X), _u16(dY), _u16(W),
                                     _u16(bias), _u16(Y0_saved), C.c_int32(i), C.c_int32(n),
                                     None if cols_a is None else cols_a.ctypes.data_as(C.c_void_p),
-                                    dl.ctypes.data_as(C.c_void_p))
+                                    dl.ctypes.data_as(C.c_void_p), _u16(G_saved))
     if rc:
         raise ValueError("oracle ia3_grad: bad arguments")
     return dl

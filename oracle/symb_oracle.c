@@ -332,11 +332,14 @@ int orc_lora_grad_segment(int32_t d_in, int32_t d_out, int32_t S, const int32_t*
  * its forward pass (Sec. 3.2: a fine-tuning client saves the layer's input and output
  * tensors for the backward pass; Sec. 4: they are 16-bit).  When given, it stands for
  * Y0[t][j] in the sum above instead of the value recomputed from X and W.
+ * G_saved (IA3_IN only, may be NULL): likewise the [T][d_in] bf16 input gradient dY W the
+ * executor returned to the client (Sec. 3.6), standing for G[t][k].
  */
 int orc_ia3_grad_segment(int32_t d_in, int32_t d_out, int32_t S, const int32_t* off,
                          const orc_adapter* ad, const uint16_t* X, const uint16_t* dY,
                          const uint16_t* W, const uint16_t* bias, const uint16_t* Y0_saved,
-                         int32_t i, int32_t ncols, const int32_t* cols, double* dl_out) {
+                         int32_t i, int32_t ncols, const int32_t* cols, double* dl_out,
+                         const uint16_t* G_saved) {
     if (orc_check_offsets(S, off) || i < 0 || i >= S) return 1;
     const int kind = ad[i].kind;
     if (kind != ORC_IA3 && kind != ORC_IA3_IN) return 1;
@@ -355,6 +358,8 @@ int orc_ia3_grad_segment(int32_t d_in, int32_t d_out, int32_t S, const int32_t* 
                 for (int32_t k = 0; k < d_in; ++k) y0 += bf(x[k]) * bf(W[(size_t)c * d_in + k]);
                 if (bias) y0 += bf(bias[c]);
                 v += bf(g[c]) * y0;
+            } else if (G_saved) {
+                v += bf(x[c]) * bf(G_saved[(size_t)(lo + u) * d_in + c]);
             } else {
                 double G = 0.0;
                 for (int32_t j = 0; j < d_out; ++j) G += bf(g[j]) * bf(W[(size_t)j * d_in + c]);

@@ -26,7 +26,8 @@ SYMB_WEIGHT_LINEAR, SYMB_WEIGHT_CONV1D = 0, 1
 
 EXPORTS = ("symb_create", "symb_destroy", "symb_validate_batch", "symb_debug_row_segment_map",
            "symb_plan_row_tiles", "symb_workspace_bytes", "symb_base_linear_fwd",
-           "symb_base_linear_bwd_input", "symb_adapter_grad", "symb_noise_add", "symb_base_linear_fwd_denoise",
+           "symb_base_linear_bwd_input", "symb_base_linear_bwd_input_ex", "symb_adapter_grad", "symb_adapter_grad_ex",
+           "symb_noise_add", "symb_base_linear_fwd_denoise",
            "symb_status_string", "symb_last_error",
            "symb_debug_gemm_timing_enable", "symb_debug_gemm_timing_read")
 
@@ -74,6 +75,8 @@ def lib() -> C.CDLL:
         l.symb_base_linear_fwd.argtypes = [vp, bp, vp, vp, vp, vp, vp, vp, sz, vp]
         l.symb_base_linear_bwd_input.argtypes = [vp, bp, vp, vp, vp, u32, vp, sz, vp]
         l.symb_adapter_grad.argtypes = [vp, bp, vp, vp, vp, u32, vp, sz, vp]
+        l.symb_base_linear_bwd_input_ex.argtypes = [vp, bp, vp, vp, vp, vp, u32, vp, sz, vp]
+        l.symb_adapter_grad_ex.argtypes = [vp, bp, vp, vp, vp, vp, u32, vp, sz, vp]
         l.symb_noise_add.argtypes = [vp, bp, vp, C.POINTER(symb_noise), vp, vp]
         l.symb_base_linear_fwd_denoise.argtypes = [vp, bp, vp, vp, vp, C.POINTER(symb_noise), vp, vp, sz, vp]
         l.symb_debug_gemm_timing_enable.argtypes = [vp, i32]
@@ -225,6 +228,20 @@ def symb_base_linear_bwd_input(handle, batch: Batch, dY, W, dX, flags: int = SYM
     wp, wb = _ws_args(ws)
     _check(lib().symb_base_linear_bwd_input(handle, batch.ref(), _ptr(dY), _ptr(W), _ptr(dX), int(flags),
                                             wp, wb, stream or None), handle)
+
+
+def symb_base_linear_bwd_input_ex(handle, batch: Batch, dY, W, dX, dXbase=None, flags: int = SYMB_BWD_FULL, ws=None,
+                                  stream: int = 0) -> None:
+    wp, wb = _ws_args(ws)
+    _check(lib().symb_base_linear_bwd_input_ex(handle, batch.ref(), _ptr(dY), _ptr(W), _ptr(dX), _ptr(dXbase),
+                                               int(flags), wp, wb, stream or None), handle)
+
+
+def symb_adapter_grad_ex(handle, batch: Batch, X, dY, Ybase=None, dXbase=None, flags: int = SYMB_GRAD_OVERWRITE,
+                         ws=None, stream: int = 0) -> None:
+    wp, wb = _ws_args(ws)
+    _check(lib().symb_adapter_grad_ex(handle, batch.ref(), _ptr(X), _ptr(dY), _ptr(Ybase), _ptr(dXbase), int(flags),
+                                      wp, wb, stream or None), handle)
 
 
 def symb_adapter_grad(handle, batch: Batch, X, dY, Ybase=None, flags: int = SYMB_GRAD_OVERWRITE, ws=None,

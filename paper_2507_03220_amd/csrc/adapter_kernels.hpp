@@ -402,19 +402,20 @@ __global__ void __launch_bounds__(256) symb_ia3_grad_kernel(const Ia3GradParams 
 
 // -------------------------------------------------------------------------------------------
 // Row scale for the IA3 backward:  out[t][j] = bf16( dY[t][j] * l_seg(t)[j] ) for IA3 rows,
-// a plain copy for the others.  One workgroup per row chunk from the work list.
+// a plain copy for the others (and, with X and kind = IA3_IN, the input scale of the forward).  One workgroup per row chunk from the work list.
 // -------------------------------------------------------------------------------------------
 struct ScaleParams {
-    const bf16* dY;
+    const bf16* dY;           // [T][d_out]: rows to scale (dY for the IA3 backward, X for the IA3_IN forward)
     bf16* out;
-    int d_out;
+    int d_out;                // row width
     const RowChunk* chunks;
     const SegDesc* seg;
+    int kind;                 // segments of this kind are scaled by their vector, the others copied
 };
 __global__ void __launch_bounds__(256) symb_ia3_scale_rows_kernel(const ScaleParams p) {
     const RowChunk ch = p.chunks[blockIdx.x];
     const SegDesc sd = p.seg[ch.seg];
-    const bool ia3 = sd.kind == KIND_IA3;
+    const bool ia3 = sd.kind == p.kind;
     const int nchunk = p.d_out >> 3;
     // a thread keeps its 8 columns and walks the chunk's rows, four rows in flight
     for (int c = threadIdx.x; c < nchunk; c += 256) {

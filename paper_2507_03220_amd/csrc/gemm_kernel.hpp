@@ -38,7 +38,8 @@ struct GemmParams {
     const bf16* ext;            // [M][ext_pitch] bf16: Hs (forward) or dH (backward), per row rpad values
                                 // then rpad residuals of the row's own segment; null = no LoRA term
     int ext_pitch;
-    int epi_ia3;                // forward: scale rows of IA3 segments by l_i[n]
+    int epi_ia3;                // 0, or the adapter kind whose rows the epilogue scales by its vector l_i[n]
+                                // (IA3 in the forward, IA3_IN in the input gradient)
     const NoiseDesc* neff;      // device [S] or null: per-segment noise effect subtracted last (privacy flow)
     int walk;                   // 0: each XCD walks one contiguous run of tiles; 1: rounds of 32 tiles dealt to the XCDs in turn
     int stagger;                // start delay unit (s_sleep 127 each) between the 8 phase groups of the first wave of tiles
@@ -534,7 +535,7 @@ symb_gemm_kernel(const GemmParams p) {
                 const bf16* nrow = nullptr;
                 if ((scale_ia3 || p.neff) && m < p.M) {
                     const int s = seg_of_row(p.off, seg_lo, seg_hi, m);
-                    if (scale_ia3 && p.seg[s].kind == KIND_IA3) lrow = p.seg[s].A;
+                    if (scale_ia3 && p.seg[s].kind == p.epi_ia3) lrow = p.seg[s].A;
                     if (p.neff) {
                         const NoiseDesc nd = p.neff[s];
                         if (nd.ptr) nrow = nd.ptr + (size_t)(nd.rows == 1 ? 0 : m - p.off[s]) * p.N;

@@ -102,7 +102,10 @@ symb_status validate(symb_handle h, const symb_batch* b) {
                     return fail(h, SYMB_ERR_INVALID_ARG, "segment %d: adapter pointer misaligned", i);
                 break;
             case SYMB_ADAPTER_IA3_IN:
-                return fail(h, SYMB_ERR_UNSUPPORTED, "segment %d: IA3 input scaling is not built on the GPU", i);
+                if (!a.A) return fail(h, SYMB_ERR_INVALID_ARG, "segment %d: IA3 input scaling needs its vector in A", i);
+                if (((uintptr_t)a.A & 15) || ((uintptr_t)a.dA & 15))
+                    return fail(h, SYMB_ERR_INVALID_ARG, "segment %d: adapter pointer misaligned", i);
+                break;
             default: return fail(h, SYMB_ERR_INVALID_ARG, "segment %d: unknown adapter kind %d", i, a.kind);
         }
     }
@@ -141,7 +144,7 @@ void plan_chunks(const symb_batch* b, int rows, bool lora_only, std::vector<RowC
 
 struct BatchInfo {
     int S = 0, T = 0;
-    int n_lora = 0, n_ia3 = 0;
+    int n_lora = 0, n_ia3 = 0, n_ia3in = 0;
     int max_rpad = 0;
     size_t packed_elems = 0;   // sum rpad_i * d_out over LoRA segments (packed B^T)
     size_t packed_at_elems = 0;// sum r_i * d_in over LoRA segments (packed A^T, input-major weight only)
@@ -160,6 +163,8 @@ BatchInfo inspect(const symb_batch* b) {
             bi.packed_at_elems += align_up((size_t)a.rank * b->d_in, 8);
         } else if (a.kind == SYMB_ADAPTER_IA3) {
             ++bi.n_ia3;
+        } else if (a.kind == SYMB_ADAPTER_IA3_IN) {
+            ++bi.n_ia3in;
         }
     }
     return bi;
@@ -173,7 +178,7 @@ struct WsLayout {
     size_t h_off = 0, h_bytes = 0;        // Hs  [T][2*max_rpad] bf16
     size_t dh_off = 0, dh_bytes = 0;      // dH  [T][2*max_rpad] bf16
     size_t pk_off = 0, pk_bytes = 0;      // packed B^T
-    size_t sc_off = 0, sc_bytes = 0;      // IA3-scaled copy of dY [T][d_out] bf16
+    size_t sc_off = 0, sc_bytes = 0;      // IA3-scaled copy of dY [T][d_out] (input gradient) or of X [T][d_in] (forward, IA3_IN) bf16
     size_t pa_off = 0, pa_bytes = 0;      // packed A^T (input-major weight, input gradient only)
     size_t total = 0;
 };
@@ -194,6 +199,7 @@ WsLayout ws_layout(const symb_batch* b, const BatchInfo& bi, int op, bool full_b
             take(w.dh_off, w.dh_bytes, hb);   // (gap: keeps packed B^T where the other operations have it)
             take(w.pk_off, w.pk_bytes, bi.packed_elems * 2);
         }
+        if (bi.n_ia3in) take(w.sc_off, w.sc_bytes, (size_t)bi.T * b->d_in * 2);   // X with IA3_IN rows scaled
     } else if (op == SYMB_OP_BWD_INPUT) {
         if (full_bwd && bi.n_lora) {
             take(w.h_off, w.h_bytes, hb);     // not touched here: keeps the forward call's Hs intact
@@ -554,8 +560,9 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     const int bm = gemm_tile_m(bi.T, b->d_out);
     std::vector<int32_t> lo, hi;
     plan_row_tiles(b, bm, lo, hi);
-    std::vector<RowChunk> chunks;
+    std::vector<RowChunk> chunks, all_chunks;
     plan_chunks(b, kSkinnyRows, true, chunks);
+    if (bi.n_ia3in) plan_chunks(b, kSkinnyRows, false, all_chunks);
     const std::vector<SegDesc> sd = make_segdesc(b);
     unsigned char* wsb = (unsigned char*)ws;
     // Input-major weight: the forward is the N-contiguous GEMM, whose LoRA steps read the adapter
@@ -581,9 +588,20 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     const size_t o_ch = blob.add(chunks.data(), chunks.size());
     const size_t o_nd = blob.add(nd.data(), nd.size());
     const size_t o_pk = blob.add(pk_off.data(), pk_off.size());
+    const size_t o_all = blob.add(all_chunks.data(), all_chunks.size());
     unsigned char* dev = nullptr;
     if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
 
+    // IA3 input scaling: the GEMM multiplies a copy of X whose IA3_IN rows are scaled by l_i
+    // (LoRA segments, if any, still shrink the caller's X: their rows are not touched by the copy)
+    const bf16* x_op = (const bf16*)X;
+    if (bi.n_ia3in) {
+        ScaleParams sc{(const bf16*)X, (bf16*)(wsb + wl.sc_off), b->d_in, (const RowChunk*)(dev + o_all),
+                       (const SegDesc*)(dev + o_seg), KIND_IA3_IN};
+        hipLaunchKernelGGL(symb_ia3_scale_rows_kernel, dim3((unsigned)all_chunks.size()), dim3(256), 0, s, sc);
+        SYMB_HIP(h, hipGetLastError());
+        x_op = (const bf16*)(wsb + wl.sc_off);
+    }
     bf16* Hs = bi.n_lora ? (bf16*)(wsb + wl.h_off) : nullptr;
     if (conv1d && bi.n_lora) {
         PackParams pp{(const SegDesc*)(dev + o_seg), (bf16*)(wsb + wl.pk_off), (const int64_t*)(dev + o_pk), b->d_out};
@@ -602,7 +620,7 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
         if ((st = launch_skinny(h, sp, (int)chunks.size(), bi.max_rpad, s)) != SYMB_OK) return st;
     }
     GemmParams gp{};
-    gp.Aop = (const bf16*)X;
+    gp.Aop = x_op;
     gp.Bop = (const bf16*)W;
     gp.C = (bf16*)Y;
     gp.Cbase = (bf16*)Ybase;
@@ -616,7 +634,7 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     gp.tile_seg_hi = (const int32_t*)(dev + o_hi);
     gp.ext = Hs;
     gp.ext_pitch = 2 * bi.max_rpad;
-    gp.epi_ia3 = bi.n_ia3 > 0;
+    gp.epi_ia3 = bi.n_ia3 > 0 ? KIND_IA3 : 0;
     gp.neff = nd.empty() ? nullptr : (const NoiseDesc*)(dev + o_nd);
     gp.timing_flops = gemm_flops(b, b->d_out, b->d_in, bi.n_lora > 0);
     // W [d_out][d_in]: K-contiguous weight rows.  W [d_in][d_out]: the weight is the [K][N] operand.
@@ -668,6 +686,11 @@ symb_status symb_noise_add(symb_handle h, const symb_batch* b, const void* X, co
 // ---------------------------------------------------------------------------------------------
 symb_status symb_base_linear_bwd_input(symb_handle h, const symb_batch* b, const void* dY, const void* W, void* dX,
                                        uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
+    return symb_base_linear_bwd_input_ex(h, b, dY, W, dX, nullptr, flags, ws, ws_bytes, stream);
+}
+
+symb_status symb_base_linear_bwd_input_ex(symb_handle h, const symb_batch* b, const void* dY, const void* W, void* dX,
+                                          void* dXbase, uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
     symb_status st = check_handle(h);
     if (st != SYMB_OK) return st;
     if ((st = validate(h, b)) != SYMB_OK) return st;
@@ -675,7 +698,7 @@ symb_status symb_base_linear_bwd_input(symb_handle h, const symb_batch* b, const
     const BatchInfo bi = inspect(b);
     if (bi.T == 0) return SYMB_OK;
     if (!dY || !W || !dX) return fail(h, SYMB_ERR_INVALID_ARG, "dY, W and dX are required");
-    if (misaligned16(dY) || misaligned16(W) || misaligned16(dX) || misaligned16(ws))
+    if (misaligned16(dY) || misaligned16(W) || misaligned16(dX) || misaligned16(dXbase) || misaligned16(ws))
         return fail(h, SYMB_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
     const bool full = flags == SYMB_BWD_FULL;
     const WsLayout wl = ws_layout(b, bi, SYMB_OP_BWD_INPUT, full, false);
@@ -748,7 +771,7 @@ symb_status symb_base_linear_bwd_input(symb_handle h, const symb_batch* b, const
         if ((st = launch_skinny(h, sp, (int)chunks.size(), bi.max_rpad, s)) != SYMB_OK) return st;
     }
     if (ia3) {
-        ScaleParams sc{(const bf16*)dY, (bf16*)(wsb + wl.sc_off), b->d_out, (const RowChunk*)(dev + o_all), (const SegDesc*)(dev + o_seg)};
+        ScaleParams sc{(const bf16*)dY, (bf16*)(wsb + wl.sc_off), b->d_out, (const RowChunk*)(dev + o_all), (const SegDesc*)(dev + o_seg), KIND_IA3};
         hipLaunchKernelGGL(symb_ia3_scale_rows_kernel, dim3((unsigned)all_chunks.size()), dim3(256), 0, s, sc);
         SYMB_HIP(h, hipGetLastError());
         a_op = (const bf16*)(wsb + wl.sc_off);
@@ -757,6 +780,7 @@ symb_status symb_base_linear_bwd_input(symb_handle h, const symb_batch* b, const
     gp.Aop = a_op;
     gp.Bop = (const bf16*)W;
     gp.C = (bf16*)dX;
+    gp.Cbase = (bf16*)dXbase;
     gp.M = bi.T;
     gp.N = b->d_in;
     gp.K = b->d_out;
@@ -766,7 +790,7 @@ symb_status symb_base_linear_bwd_input(symb_handle h, const symb_batch* b, const
     gp.tile_seg_hi = (const int32_t*)(dev + o_hi);
     gp.ext = dH;
     gp.ext_pitch = 2 * bi.max_rpad;
-    gp.epi_ia3 = 0;
+    gp.epi_ia3 = (full && bi.n_ia3in > 0) ? KIND_IA3_IN : 0;      // dX rows of IA3_IN segments: l_i * (dY W)
     gp.timing_flops = gemm_flops(b, b->d_in, b->d_out, lora);
     // W [d_out][d_in] is the [K][N] operand of dX = dY W; W [d_in][d_out] gives K-contiguous rows.
     st = conv1d ? launch_gemm<false>(h, gp, s) : launch_gemm<true>(h, gp, s);
@@ -777,6 +801,11 @@ symb_status symb_base_linear_bwd_input(symb_handle h, const symb_batch* b, const
 // ---------------------------------------------------------------------------------------------
 symb_status symb_adapter_grad(symb_handle h, const symb_batch* b, const void* X, const void* dY, const void* Ybase,
                               uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
+    return symb_adapter_grad_ex(h, b, X, dY, Ybase, nullptr, flags, ws, ws_bytes, stream);
+}
+
+symb_status symb_adapter_grad_ex(symb_handle h, const symb_batch* b, const void* X, const void* dY, const void* Ybase,
+                                 const void* dXbase, uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
     symb_status st = check_handle(h);
     if (st != SYMB_OK) return st;
     if ((st = validate(h, b)) != SYMB_OK) return st;
@@ -787,13 +816,13 @@ symb_status symb_adapter_grad(symb_handle h, const symb_batch* b, const void* X,
     if (!X || !dY) {
         if (bi.T > 0) return fail(h, SYMB_ERR_INVALID_ARG, "X and dY are required");
     }
-    if (misaligned16(X) || misaligned16(dY) || misaligned16(Ybase) || misaligned16(ws))
+    if (misaligned16(X) || misaligned16(dY) || misaligned16(Ybase) || misaligned16(dXbase) || misaligned16(ws))
         return fail(h, SYMB_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
     const bool acc = (flags & SYMB_GRAD_ACCUMULATE) != 0;
     hipStream_t s = (hipStream_t)stream;
 
     // Which segments want which gradient.  Empty segments: zeros when overwriting, nothing otherwise.
-    std::vector<int32_t> want_a, want_b, want_l;
+    std::vector<int32_t> want_a, want_b, want_l, want_lin;
     std::vector<std::pair<float*, size_t>> zero_fill;
     int grad_max_rpad = 0;
     for (int i = 0; i < bi.S; ++i) {
@@ -814,8 +843,16 @@ symb_status symb_adapter_grad(symb_handle h, const symb_batch* b, const void* X,
                 continue;
             }
             want_l.push_back(i);
+        } else if (a.kind == SYMB_ADAPTER_IA3_IN && a.dA) {
+            if (empty) {
+                if (!acc) zero_fill.emplace_back((float*)a.dA, (size_t)b->d_in);
+                continue;
+            }
+            want_lin.push_back(i);
         }
     }
+    if (!want_lin.empty() && !dXbase)
+        return fail(h, SYMB_ERR_INVALID_ARG, "an IA3_IN segment wants dl but dXbase (the input gradient before the input scale) is null");
     if (!want_l.empty() && !Ybase)
         return fail(h, SYMB_ERR_INVALID_ARG, "an IA3 segment wants dl but Ybase (the pre-adapter output) is null");
     const bool any_lora = !want_a.empty() || !want_b.empty();
@@ -826,7 +863,7 @@ symb_status symb_adapter_grad(symb_handle h, const symb_batch* b, const void* X,
         hipLaunchKernelGGL(symb_fill_zero_kernel, dim3((unsigned)std::min<size_t>((z.second + 255) / 256, 1024)), dim3(256), 0, s, z.first, z.second);
         SYMB_HIP(h, hipGetLastError());
     }
-    if (!any_lora && want_l.empty()) return SYMB_OK;
+    if (!any_lora && want_l.empty() && want_lin.empty()) return SYMB_OK;
 
     // Row chunks of the LoRA segments that want a gradient (Hs for dB, dH for dA).
     std::vector<RowChunk> ch_h, ch_dh;
@@ -855,6 +892,7 @@ symb_status symb_adapter_grad(symb_handle h, const symb_batch* b, const void* X,
     const size_t o_wa = blob.add(want_a.data(), want_a.size());
     const size_t o_wb = blob.add(want_b.data(), want_b.size());
     const size_t o_wl = blob.add(want_l.data(), want_l.size());
+    const size_t o_wli = blob.add(want_lin.data(), want_lin.size());
     unsigned char* dev = nullptr;
     if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
     unsigned char* wsb = (unsigned char*)ws;
@@ -901,6 +939,11 @@ symb_status symb_adapter_grad(symb_handle h, const symb_batch* b, const void* X,
     if (!want_l.empty()) {
         Ia3GradParams ip{(const bf16*)dY, (const bf16*)Ybase, b->d_out, doff, dseg, (const int32_t*)(dev + o_wl), acc ? 1 : 0};
         hipLaunchKernelGGL(symb_ia3_grad_kernel, dim3((b->d_out + IA3_GRAD_COLS - 1) / IA3_GRAD_COLS, (unsigned)want_l.size()), dim3(256), 0, s, ip);
+        SYMB_HIP(h, hipGetLastError());
+    }
+    if (!want_lin.empty()) {     // dl_i[k] = sum_t X[t][k] * (dY W)[t][k]: the same reduction over the input width
+        Ia3GradParams ip{(const bf16*)X, (const bf16*)dXbase, b->d_in, doff, dseg, (const int32_t*)(dev + o_wli), acc ? 1 : 0};
+        hipLaunchKernelGGL(symb_ia3_grad_kernel, dim3((b->d_in + IA3_GRAD_COLS - 1) / IA3_GRAD_COLS, (unsigned)want_lin.size()), dim3(256), 0, s, ip);
         SYMB_HIP(h, hipGetLastError());
     }
     return seal_slot(h, s);

@@ -50,6 +50,8 @@ def make_problem(seed, d_in, d_out, lens, kinds, ranks, bias=True, scales=None):
             ads.append(gh.HostAdapter(k, r, s, nb((r, d_in), d_in ** -0.5), nb((d_out, r), r ** -0.5)))
         elif k == oracle.IA3:
             ads.append(gh.HostAdapter(k, 0, 0.0, nb((d_out,), 0.1, 1.0)))
+        elif k == oracle.IA3_IN:
+            ads.append(gh.HostAdapter(k, 0, 0.0, nb((d_in,), 0.1, 1.0)))
         else:
             ads.append(gh.HostAdapter())
     return dict(off=off, T=T, d_in=d_in, d_out=d_out, ads=ads,
@@ -244,8 +246,9 @@ def test_errors_enqueue_nothing_and_leave_handle_usable():
     expect(sb.SYMB_ERR_INVALID_ARG, lambda: sb.symb_base_linear_bwd_input(h, good, dYd, W, Y, 5, None))
     expect(sb.SYMB_ERR_INVALID_ARG,            # IA3 segment wants dl but no Ybase given
            lambda: sb.symb_adapter_grad(h, good, X, dYd, None, sb.SYMB_GRAD_OVERWRITE, gh.workspace(good, sb.SYMB_OP_ADAPTER_GRAD)))
-    ia3_in = sb.Batch(64, 72, [0, 11], [sb.Adapter(sb.SYMB_ADAPTER_IA3_IN, 0, 0.0, dev.descs[1].A)])
-    expect(sb.SYMB_ERR_UNSUPPORTED, lambda: sb.symb_base_linear_fwd(h, ia3_in, X, W, None, Y, None, None))
+    ia3_in = sb.Batch(64, 72, [0, 11], [sb.Adapter(sb.SYMB_ADAPTER_IA3_IN, 0, 0.0, dev.descs[1].A, dA=dev.descs[1].dA)])
+    expect(sb.SYMB_ERR_INVALID_ARG,            # IA3_IN segment wants dl but no dXbase given
+           lambda: sb.symb_adapter_grad(h, ia3_in, X, dYd, None, sb.SYMB_GRAD_OVERWRITE, None))
     # the handle still works
     sb.symb_base_linear_fwd(h, good, X, W, None, Y, None, ws)
     torch.cuda.synchronize()
@@ -362,3 +365,50 @@ def test_input_major_weight_layout(case):
         dX = gh.backward_input(off, p["ads"], p["dY"], p["W"], base_only=base_only, conv1d=True)
         dXr = oracle.backward_input(off, oads, p["dY"], p["W"], base_only=base_only)
         assert_close(gh.bf16_to_f64(dX), dXr, f"conv1d dX base_only={base_only}", out_bf16=True)
+
+
+@pytest.mark.parametrize("case", [
+    dict(seed=51, d_in=320, d_out=264, lens=[130, 1, 0, 77, 1, 300, 64], kinds=[L, 3, L, N, 3, I, 3], ranks=[8, 16, 5]),
+    dict(seed=52, d_in=6208, d_out=136, lens=[700, 5, 795], kinds=[3, L, 3], ranks=[16]),        # 256x256 tiles in the input gradient
+    dict(seed=53, d_in=136, d_out=6208, lens=[700, 5, 795], kinds=[3, I, L], ranks=[8], conv1d=True),
+])
+def test_ia3_input_scaling(case):
+    """IA3 on the layer's input (kind 3): Y = (X * l) W^T + b; dX = l * (dY W); dl[k] = sum_t X[t][k] (dY W)[t][k],
+    the last from the input gradient the executor returned (a bf16 tensor: both sides get the oracle's)."""
+    c = dict(case)
+    conv1d = c.pop("conv1d", False)
+    p = make_problem(c.pop("seed"), c.pop("d_in"), c.pop("d_out"), c.pop("lens"), c.pop("kinds"), c.pop("ranks"))
+    oads, off, d_in, d_out, T = oracle_ads(p["ads"]), p["off"], p["d_in"], p["d_out"], p["T"]
+    Y, _ = gh.forward(off, p["ads"], p["X"], p["W"], p["bias"], want_base=False, conv1d=conv1d)
+    _, Yr = oracle.forward(off, oads, p["X"], p["W"], p["bias"])
+    assert_close(gh.bf16_to_f64(Y), Yr, "IA3_IN Y", out_bf16=True)
+    # input gradient with the pre-scale output
+    dev = gh.upload_adapters(p["ads"], d_in, d_out, grads=True)
+    b = sb.Batch(d_in, d_out, off, dev.descs, sb.SYMB_WEIGHT_CONV1D if conv1d else sb.SYMB_WEIGHT_LINEAR)
+    h = gh.handle()
+    gd, Wd, Xd = gh.to_dev(p["dY"]), gh.weight_to_dev(p["W"], conv1d), gh.to_dev(p["X"])
+    dX = torch.full((T, d_in), float("nan"), device="cuda", dtype=torch.bfloat16)
+    G = torch.full((T, d_in), float("nan"), device="cuda", dtype=torch.bfloat16)
+    sb.symb_base_linear_bwd_input_ex(h, b, gd, Wd, dX, G, sb.SYMB_BWD_FULL, gh.workspace(b, sb.SYMB_OP_BWD_INPUT))
+    torch.cuda.synchronize()
+    assert_close(gh.bf16_to_f64(dX), oracle.backward_input(off, oads, p["dY"], p["W"]), "IA3_IN dX", out_bf16=True)
+    Gr = oracle.backward_input(off, oads, p["dY"], p["W"], base_only=True)
+    ia3_rows = np.concatenate([np.arange(off[i], off[i + 1]) for i, a in enumerate(p["ads"]) if a.kind == I] or [np.zeros(0, int)]).astype(int)
+    keep = np.setdiff1d(np.arange(T), ia3_rows)          # rows of output-scaling segments hold the scaled product there
+    assert_close(gh.bf16_to_f64(G)[keep], Gr[keep], "IA3_IN dXbase", out_bf16=True)
+    dXb = gh.backward_input(off, p["ads"], p["dY"], p["W"], base_only=True, conv1d=conv1d)
+    assert_close(gh.bf16_to_f64(dXb), Gr, "IA3_IN dX base only", out_bf16=True)
+    # gradients: both sides take the oracle's G and Y0 rounded to bf16
+    Y0r, _ = oracle.forward(off, oads, p["X"], p["W"], p["bias"])
+    G_saved, Y0_saved = synth.f32_to_bf16_bits(Gr.astype(np.float32)), synth.f32_to_bf16_bits(Y0r.astype(np.float32))
+    sb.symb_adapter_grad_ex(h, b, Xd, gd, gh.to_dev(Y0_saved), gh.to_dev(G_saved), sb.SYMB_GRAD_OVERWRITE,
+                            gh.workspace(b, sb.SYMB_OP_ADAPTER_GRAD))
+    torch.cuda.synchronize()
+    for i, a in enumerate(p["ads"]):
+        if a.kind != 3:
+            continue
+        dl = dev.descs[i].dA.cpu().numpy()
+        if off[i + 1] == off[i]:
+            assert not dl.any()
+        else:
+            assert_close(dl, oracle.ia3_grad(off, oads, p["X"], p["dY"], p["W"], p["bias"], i, G_saved=G_saved), f"IA3_IN dl[{i}]")

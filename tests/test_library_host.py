@@ -69,7 +69,8 @@ def test_validation_rejects_bad_batches():
     assert sb.symb_validate_batch(_batch([0, 4], [sb.Adapter(kind=7)])) == sb.SYMB_ERR_INVALID_ARG
     assert sb.symb_validate_batch(_batch([0, 4], [sb.Adapter(kind=sb.SYMB_ADAPTER_IA3)])) == sb.SYMB_ERR_INVALID_ARG
     assert sb.symb_validate_batch(_batch([0, 4], [sb.Adapter(kind=sb.SYMB_ADAPTER_IA3, A=fake)])) == sb.SYMB_OK
-    assert sb.symb_validate_batch(_batch([0, 4], [sb.Adapter(kind=sb.SYMB_ADAPTER_IA3_IN, A=fake)])) == sb.SYMB_ERR_UNSUPPORTED
+    assert sb.symb_validate_batch(_batch([0, 4], [sb.Adapter(kind=sb.SYMB_ADAPTER_IA3_IN, A=fake)])) == sb.SYMB_OK
+    assert sb.symb_validate_batch(_batch([0, 4], [sb.Adapter(kind=sb.SYMB_ADAPTER_IA3_IN)])) == sb.SYMB_ERR_INVALID_ARG
     assert b"IA3 input scaling" in sb.lib().symb_last_error(None)
 
 

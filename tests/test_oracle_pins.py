@@ -470,3 +470,24 @@ def test_ia3_grad_from_saved_output():
     for q, j in enumerate([3, 1]):
         ref = sum(Fraction(float(f64(dY)[t, j])) * Fraction(float(f64(other)[t, j])) for t in range(2, 7))
         assert got[q] == float(ref)
+
+
+def test_ia3_in_grad_from_saved_input_gradient():
+    """IA3 input scaling: dl[k] = sum_t X[t][k] G[t][k] with G = dY W.  With the G the executor returned
+    (a bf16 tensor) exactly representable, the saved route equals the recomputing one; with an arbitrary
+    saved tensor the sum runs over exactly that tensor."""
+    rng = np.random.default_rng(34)
+    d_in, d_out = 4, 3
+    off = np.array([0, 3, 7], dtype=np.int32)
+    pick = lambda shape: bits_of(rng.choice([-1.0, -0.5, 0.0, 0.5, 1.0], size=shape))
+    X, W, dY = grid_bits(rng, (7, d_in)), pick((d_out, d_in)), pick((7, d_out))
+    ads = [oracle.Adapter(), oracle.Adapter(oracle.IA3_IN, 0, 0.0, grid_bits(rng, (d_in,)))]
+    G = oracle.backward_input(off, ads, dY, W, base_only=True)        # dY W: small multiples of 1/4
+    saved = bits_of(G)
+    np.testing.assert_array_equal(oracle.ia3_grad(off, ads, X, dY, W, None, 1, G_saved=saved),
+                                  oracle.ia3_grad(off, ads, X, dY, W, None, 1))
+    other = grid_bits(rng, (7, d_in))
+    got = oracle.ia3_grad(off, ads, X, dY, W, None, 1, cols=[2, 0], G_saved=other)
+    for q, k in enumerate([2, 0]):
+        ref = sum(Fraction(float(f64(X)[t, k])) * Fraction(float(f64(other)[t, k])) for t in range(3, 7))
+        assert got[q] == float(ref)
