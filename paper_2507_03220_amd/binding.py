@@ -29,6 +29,8 @@ EXPORTS = ("symb_create", "symb_destroy", "symb_validate_batch", "symb_debug_row
            "symb_base_linear_bwd_input", "symb_base_linear_bwd_input_ex", "symb_adapter_grad", "symb_adapter_grad_ex",
            "symb_noise_add", "symb_base_linear_fwd_denoise",
            "symb_status_string", "symb_last_error",
+           "symb_batcher_create", "symb_batcher_destroy", "symb_batcher_submit", "symb_batcher_pending",
+           "symb_batcher_next_due", "symb_batcher_take",
            "symb_debug_gemm_timing_enable", "symb_debug_gemm_timing_read")
 
 
