@@ -7,7 +7,8 @@ adapter gradients (dA, dB, dl), all through the C ABI.  Inputs are resident in H
 the timed region.  Default workload: the Gemma2-27B-shaped layer with 20 LoRA clients x
 1024 tokens (T = 20480), ranks from {8, 16}.
 
-Prints ONE JSON line (see README/DESIGN for the fields).  Run with --gpus 1 only.
+Prints ONE JSON line: metric, value (whole-step TFLOP/s), timing, the roofline of the dominant GEMM kernel,
+per-projection timings and the oracle timed on the host cores.  Run with --gpus 1 only.
 """
 from __future__ import annotations
 
