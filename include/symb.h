@@ -202,6 +202,23 @@ symb_status symb_base_linear_bwd_input_ex(symb_handle h, const symb_batch* b, co
                                           void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Per-client buffers (Sec. 3.4: the executor and a local client share pre-allocated buffers).  The
+ * same forward / input gradient with the rows of segment i read from X_seg[i] (dY_seg[i]) and
+ * written to Y_seg[i] (dX_seg[i]) instead of one flattened tensor each: no concatenation before
+ * the call, no split after it.  The arrays are HOST arrays of num_segments DEVICE pointers (dense
+ * bf16 rows, 16-byte aligned; an empty segment's entry is ignored).  An output buffer must not
+ * overlap any input buffer.  The input buffers of one call must lie within one 4 GiB window
+ * (SYMB_ERR_UNSUPPORTED otherwise): carve them from one arena.  No Ybase / dXbase output and no
+ * IA3 input scaling in this form.
+ */
+symb_status symb_base_linear_fwd_seg(symb_handle h, const symb_batch* b, const void* const* X_seg,
+                                     const void* W, const void* bias, void* const* Y_seg, void* ws,
+                                     size_t ws_bytes, void* stream);
+symb_status symb_base_linear_bwd_input_seg(symb_handle h, const symb_batch* b, const void* const* dY_seg,
+                                           const void* W, void* const* dX_seg, uint32_t flags, void* ws,
+                                           size_t ws_bytes, void* stream);
+
+/*
  * Adapter gradients per segment (the client-side autograd of Sec. 3.2, fused here):
  * for every segment whose descriptor has dA / dB non-NULL, writes (OVERWRITE) or adds
  * to (ACCUMULATE; flags may be OR-ed with SYMB_GRAD_REUSE_DH / SYMB_GRAD_REUSE_HS) dA_i, dB_i (LoRA) or dl_i (IA3, through dA).  An empty segment

@@ -27,7 +27,7 @@ SYMB_WEIGHT_LINEAR, SYMB_WEIGHT_CONV1D = 0, 1
 EXPORTS = ("symb_create", "symb_destroy", "symb_validate_batch", "symb_debug_row_segment_map",
            "symb_plan_row_tiles", "symb_workspace_bytes", "symb_base_linear_fwd",
            "symb_base_linear_bwd_input", "symb_base_linear_bwd_input_ex", "symb_adapter_grad", "symb_adapter_grad_ex",
-           "symb_noise_add", "symb_base_linear_fwd_denoise",
+           "symb_noise_add", "symb_base_linear_fwd_denoise", "symb_base_linear_fwd_seg", "symb_base_linear_bwd_input_seg",
            "symb_status_string", "symb_last_error",
            "symb_batcher_create", "symb_batcher_destroy", "symb_batcher_submit", "symb_batcher_pending",
            "symb_batcher_next_due", "symb_batcher_take",
@@ -79,6 +79,8 @@ def lib() -> C.CDLL:
         l.symb_adapter_grad.argtypes = [vp, bp, vp, vp, vp, u32, vp, sz, vp]
         l.symb_base_linear_bwd_input_ex.argtypes = [vp, bp, vp, vp, vp, vp, u32, vp, sz, vp]
         l.symb_adapter_grad_ex.argtypes = [vp, bp, vp, vp, vp, vp, u32, vp, sz, vp]
+        l.symb_base_linear_fwd_seg.argtypes = [vp, bp, C.POINTER(vp), vp, vp, C.POINTER(vp), vp, sz, vp]
+        l.symb_base_linear_bwd_input_seg.argtypes = [vp, bp, C.POINTER(vp), vp, C.POINTER(vp), u32, vp, sz, vp]
         l.symb_noise_add.argtypes = [vp, bp, vp, C.POINTER(symb_noise), vp, vp]
         l.symb_base_linear_fwd_denoise.argtypes = [vp, bp, vp, vp, vp, C.POINTER(symb_noise), vp, vp, sz, vp]
         l.symb_debug_gemm_timing_enable.argtypes = [vp, i32]
@@ -210,6 +212,25 @@ def _noise_array(batch: Batch, noise: Sequence):
         else:
             arr[i].ptr, arr[i].rows = _ptr(n), int(n.shape[0]) if n.dim() > 1 else 1
     return arr
+
+
+def _ptr_array(batch: Batch, tensors: Sequence):
+    if len(tensors) != batch.S:
+        raise ValueError("one buffer per segment")
+    return (C.c_void_p * max(batch.S, 1))(*[_ptr(t) for t in tensors])
+
+
+def symb_base_linear_fwd_seg(handle, batch: Batch, X_seg: Sequence, W, bias, Y_seg: Sequence, ws=None, stream: int = 0) -> None:
+    wp, wb = _ws_args(ws)
+    _check(lib().symb_base_linear_fwd_seg(handle, batch.ref(), _ptr_array(batch, X_seg), _ptr(W), _ptr(bias),
+                                          _ptr_array(batch, Y_seg), wp, wb, stream or None), handle)
+
+
+def symb_base_linear_bwd_input_seg(handle, batch: Batch, dY_seg: Sequence, W, dX_seg: Sequence, flags: int = SYMB_BWD_FULL,
+                                   ws=None, stream: int = 0) -> None:
+    wp, wb = _ws_args(ws)
+    _check(lib().symb_base_linear_bwd_input_seg(handle, batch.ref(), _ptr_array(batch, dY_seg), _ptr(W),
+                                                _ptr_array(batch, dX_seg), int(flags), wp, wb, stream or None), handle)
 
 
 def symb_noise_add(handle, batch: Batch, X, noise: Sequence, Xn, stream: int = 0) -> None:

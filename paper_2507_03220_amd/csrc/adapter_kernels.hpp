@@ -30,6 +30,8 @@ struct SkinnyParams {
     const bf16* packed;       // backward: base of packed B^T area, else null
     const int64_t* packed_off;// backward: element offset of segment i's [rpad][K] block
     int use_packed;
+    const bf16* const* L_seg; // device [S] or null: rows of segment i start at L_seg[i] instead of L + off[i] * K
+    const int32_t* off;       // device [S+1] (read only with L_seg)
 };
 
 constexpr int SKINNY_ROWS = 32;     // rows per workgroup (two 16-row MFMA blocks per wavefront)
@@ -45,8 +47,9 @@ symb_skinny_kernel(const SkinnyParams p) {
     const int trow = lane & 15, kq = lane >> 4;
     // rows past the chunk are clamped onto its last row; their results are never stored
     const bf16* lrow[2];
+    const bf16* const lbase = p.L_seg ? p.L_seg[ch.seg] - (size_t)p.off[ch.seg] * p.K : p.L;
 #pragma unroll
-    for (int b = 0; b < 2; ++b) lrow[b] = p.L + (size_t)(ch.row0 + min(b * 16 + trow, ch.nrows - 1)) * p.K + kq * 8;
+    for (int b = 0; b < 2; ++b) lrow[b] = lbase + (size_t)(ch.row0 + min(b * 16 + trow, ch.nrows - 1)) * p.K + kq * 8;
     const bf16* rbase = p.use_packed ? (p.packed + p.packed_off[ch.seg]) : sd.A;
     const int rrows = p.use_packed ? sd.rpad : sd.rank;  // valid adapter rows; the rest count as zero
     const bf16* rrow[RB];
@@ -411,12 +414,15 @@ struct ScaleParams {
     const RowChunk* chunks;
     const SegDesc* seg;
     int kind;                 // segments of this kind are scaled by their vector, the others copied
+    const bf16* const* in_seg;// device [S] or null: input rows of segment i start at in_seg[i]
+    const int32_t* off;       // device [S+1] (read only with in_seg)
 };
 __global__ void __launch_bounds__(256) symb_ia3_scale_rows_kernel(const ScaleParams p) {
     const RowChunk ch = p.chunks[blockIdx.x];
     const SegDesc sd = p.seg[ch.seg];
     const bool ia3 = sd.kind == p.kind;
     const int nchunk = p.d_out >> 3;
+    const bf16* const in = p.in_seg ? p.in_seg[ch.seg] - (size_t)p.off[ch.seg] * p.d_out : p.dY;
     // a thread keeps its 8 columns and walks the chunk's rows, four rows in flight
     for (int c = threadIdx.x; c < nchunk; c += 256) {
         uint4 l = make_uint4(0u, 0u, 0u, 0u);
@@ -440,12 +446,12 @@ __global__ void __launch_bounds__(256) symb_ia3_scale_rows_kernel(const ScalePar
         for (; t + 4 <= ch.nrows; t += 4) {
             uint4 g[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) g[u] = *reinterpret_cast<const uint4*>(p.dY + (size_t)(ch.row0 + t + u) * p.d_out + col);
+            for (int u = 0; u < 4; ++u) g[u] = *reinterpret_cast<const uint4*>(in + (size_t)(ch.row0 + t + u) * p.d_out + col);
 #pragma unroll
             for (int u = 0; u < 4; ++u) *reinterpret_cast<uint4*>(p.out + (size_t)(ch.row0 + t + u) * p.d_out + col) = scaled(g[u]);
         }
         for (; t < ch.nrows; ++t) {
-            const uint4 g = *reinterpret_cast<const uint4*>(p.dY + (size_t)(ch.row0 + t) * p.d_out + col);
+            const uint4 g = *reinterpret_cast<const uint4*>(in + (size_t)(ch.row0 + t) * p.d_out + col);
             *reinterpret_cast<uint4*>(p.out + (size_t)(ch.row0 + t) * p.d_out + col) = scaled(g);
         }
     }

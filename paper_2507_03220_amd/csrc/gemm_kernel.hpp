@@ -24,7 +24,7 @@
 namespace symb {
 
 struct GemmParams {
-    const bf16* Aop;            // [M][K]
+    const bf16* Aop;            // [M][K] (null when the rows come from per-segment buffers, see a_seg)
     const bf16* Bop;            // NT: [N][K]   NN: [K][N]
     bf16* C;                    // [M][N]
     bf16* Cbase;                // [M][N] or null: accumulator (+bias) before the adapter term
@@ -40,6 +40,12 @@ struct GemmParams {
     int ext_pitch;
     int epi_ia3;                // 0, or the adapter kind whose rows the epilogue scales by its vector l_i[n]
                                 // (IA3 in the forward, IA3_IN in the input gradient)
+    // Per-segment buffers instead of flat tensors (device arrays of S pointers, or null): row t of
+    // segment i is a_seg[i] + (t - off[i]) * K resp. c_seg[i] + (t - off[i]) * N.  All a_seg buffers lie
+    // within 4 GiB above a_base (checked by the host), so lane offsets from a_base fit 32 bits.
+    const bf16* const* a_seg;
+    const bf16* a_base;
+    bf16* const* c_seg;
     const NoiseDesc* neff;      // device [S] or null: per-segment noise effect subtracted last (privacy flow)
     int walk;                   // 0: each XCD walks one contiguous run of tiles; 1: rounds of 32 tiles dealt to the XCDs in turn
     int stagger;                // start delay unit (s_sleep 127 each) between the 8 phase groups of the first wave of tiles
@@ -181,6 +187,14 @@ symb_gemm_kernel(const GemmParams p) {
     const int wm0 = (wave / WGN) * TT::WTM, wn0 = (wave % WGN) * TT::WTN;
     // segment range of this row tile, fetched now so that its latency hides under the main loop
     const int seg_lo = p.tile_seg_lo[tm], seg_hi = p.tile_seg_hi[tm];
+    // row m (< M) of the activation operand: in the flat tensor or in its segment's own buffer
+    auto a_row = [&](int m) __attribute__((always_inline)) -> const bf16* {
+        if (!p.a_seg) return p.Aop + (size_t)m * p.K;
+        const int s = seg_of_row(p.off, seg_lo, seg_hi, m);
+        return p.a_seg[s] + (size_t)(m - p.off[s]) * p.K;
+    };
+    // loads address their rows as 32-bit offsets from this pointer
+    const bf16* const a_tile = p.a_seg ? p.a_base : p.Aop + (size_t)m0 * p.K;
 
     floatx16 acc[MB][NB];
 #pragma unroll
@@ -230,7 +244,7 @@ symb_gemm_kernel(const GemmParams p) {
 #pragma unroll
     for (int j = 0; j < AI; ++j) {
         const int row = (wave * AI + j) * 16 + (lane >> 2), kc = (lane & 3) ^ ((row >> 2) & 3);
-        a_off[j] = (unsigned)(min(m0 + row, p.M - 1) - m0) * (unsigned)p.K + kc * 8;
+        a_off[j] = (unsigned)(a_row(min(m0 + row, p.M - 1)) - a_tile) + kc * 8;
     }
 #pragma unroll
     for (int j = 0; j < BI; ++j) {
@@ -243,7 +257,6 @@ symb_gemm_kernel(const GemmParams p) {
             b_off[j] = (unsigned)krow * (unsigned)p.N + (unsigned)min(nc * 8, p.N - 8 - n0);
         }
     }
-    const bf16* const a_tile = p.Aop + (size_t)m0 * p.K;
     const bf16* const b_tile = NN ? (p.Bop + n0) : (p.Bop + (size_t)n0 * p.K);
     typedef __attribute__((address_space(3))) void lds_void_t;
     typedef __attribute__((address_space(1))) const void glb_void_t;
@@ -264,7 +277,7 @@ symb_gemm_kernel(const GemmParams p) {
         const bool kok = (k0 + lkc) < p.K;
 #pragma unroll
         for (int i = 0; i < CA; ++i)
-            ra[i] = ld_global_16(p.Aop + (size_t)min(m0 + lrow + i * RSTEP, p.M - 1) * p.K + k0 + lkc, kok);
+            ra[i] = ld_global_16(a_row(min(m0 + lrow + i * RSTEP, p.M - 1)) + k0 + lkc, kok);
 #pragma unroll
         for (int i = 0; i < CB; ++i) {
             if constexpr (!NN)
@@ -398,7 +411,7 @@ symb_gemm_kernel(const GemmParams p) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int row = (wave * 8 + j) * 8 + (lane >> 3), kc = (lane & 7) ^ swz_row(row);
-                ab[j] = ((unsigned)(min(m0 + row, p.M - 1) - m0) * (unsigned)p.K + kc * 8) * 2u;
+                ab[j] = ((unsigned)(a_row(min(m0 + row, p.M - 1)) - a_tile) + kc * 8) * 2u;
                 if constexpr (!NN) {
                     bb[j] = ((unsigned)(min(n0 + row, p.N - 1) - n0) * (unsigned)p.K + kc * 8) * 2u;
                 } else {
@@ -595,14 +608,21 @@ symb_gemm_kernel(const GemmParams p) {
 #ifdef SYMB_GEMM_TRACE
         if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 9] = __builtin_amdgcn_s_memrealtime();
 #endif
+        const bool to_seg = p.c_seg != nullptr && dst == p.C;   // the final output goes to the segments' own buffers
         constexpr int LPR = BN / 8;                  // lanes per row (16 bytes each)
         constexpr int RPI = 64 / LPR;                // rows per store instruction
         const int col = (lane % LPR) * 8;
 #pragma unroll 4
         for (int r = wave * RPI + lane / LPR; r < BM; r += (NT / 64) * RPI) {
             const int m = m0 + r, n = n0 + col;
-            if (m < p.M && n < p.N)
-                *reinterpret_cast<uint4*>(dst + (size_t)m * p.N + n) = *reinterpret_cast<const uint4*>(smem + r * CP + col * 2);
+            if (m < p.M && n < p.N) {
+                bf16* rowp = dst + (size_t)m * p.N;
+                if (to_seg) {
+                    const int s = seg_of_row(p.off, seg_lo, seg_hi, m);
+                    rowp = p.c_seg[s] + (size_t)(m - p.off[s]) * p.N;
+                }
+                *reinterpret_cast<uint4*>(rowp + n) = *reinterpret_cast<const uint4*>(smem + r * CP + col * 2);
+            }
         }
     };
 

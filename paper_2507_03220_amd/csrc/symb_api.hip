@@ -540,14 +540,42 @@ symb_status make_noisedesc(symb_handle h, const symb_batch* b, const symb_noise*
     return SYMB_OK;
 }
 
+// Per-segment buffers (one DEVICE pointer per segment, HOST array): alignment, presence for
+// non-empty segments, and, for the GEMM's activation operand, that they all lie inside one 4 GiB
+// window (lane offsets are 32 bits wide).  *base receives the lowest address.
+symb_status check_seg_ptrs(symb_handle h, const symb_batch* b, const void* const* seg, size_t row_bytes, const char* what,
+                           bool need_window, const void** base) {
+    uintptr_t lo = UINTPTR_MAX, hi = 0;
+    for (int i = 0; i < b->num_segments; ++i) {
+        const size_t n = (size_t)(b->seg_offsets[i + 1] - b->seg_offsets[i]);
+        if (!n) continue;
+        if (!seg[i]) return fail(h, SYMB_ERR_INVALID_ARG, "%s of segment %d is null", what, i);
+        if (misaligned16(seg[i])) return fail(h, SYMB_ERR_INVALID_ARG, "%s of segment %d is not 16-byte aligned", what, i);
+        lo = std::min(lo, (uintptr_t)seg[i]);
+        hi = std::max(hi, (uintptr_t)seg[i] + n * row_bytes);
+    }
+    if (need_window && hi > lo && hi - lo > ((uint64_t)1 << 32) - 65536)
+        return fail(h, SYMB_ERR_UNSUPPORTED, "%s buffers span %zu bytes: they must lie within one 4 GiB window", what, (size_t)(hi - lo));
+    if (base) *base = (const void*)(lo == UINTPTR_MAX ? 0 : lo);
+    return SYMB_OK;
+}
+
 static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* X, const void* W, const void* bias,
-                                const symb_noise* noise_effect, void* Y, void* Ybase, void* ws, size_t ws_bytes, void* stream) {
+                                const symb_noise* noise_effect, void* Y, void* Ybase, void* ws, size_t ws_bytes, void* stream,
+                                const void* const* X_seg = nullptr, void* const* Y_seg = nullptr) {
     symb_status st = check_handle(h);
     if (st != SYMB_OK) return st;
     if ((st = validate(h, b)) != SYMB_OK) return st;
     const BatchInfo bi = inspect(b);
     if (bi.T == 0) return SYMB_OK;
-    if (!X || !W || !Y) return fail(h, SYMB_ERR_INVALID_ARG, "X, W and Y are required");
+    const bool seg_io = X_seg != nullptr;
+    const void* x_base = nullptr;
+    if (seg_io) {
+        if (!Y_seg || !W) return fail(h, SYMB_ERR_INVALID_ARG, "X_seg, Y_seg and W are required");
+        if (bi.n_ia3in) return fail(h, SYMB_ERR_UNSUPPORTED, "IA3 input scaling is not available with per-segment buffers");
+        if ((st = check_seg_ptrs(h, b, X_seg, (size_t)b->d_in * 2, "X", true, &x_base)) != SYMB_OK) return st;
+        if ((st = check_seg_ptrs(h, b, (const void* const*)Y_seg, (size_t)b->d_out * 2, "Y", false, nullptr)) != SYMB_OK) return st;
+    } else if (!X || !W || !Y) return fail(h, SYMB_ERR_INVALID_ARG, "X, W and Y are required");
     std::vector<NoiseDesc> nd;
     if (noise_effect && (st = make_noisedesc(h, b, noise_effect, "noise effect", nd)) != SYMB_OK) return st;
     if (misaligned16(X) || misaligned16(W) || misaligned16(Y) || misaligned16(Ybase) || misaligned16(bias) || misaligned16(ws))
@@ -589,6 +617,8 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     const size_t o_nd = blob.add(nd.data(), nd.size());
     const size_t o_pk = blob.add(pk_off.data(), pk_off.size());
     const size_t o_all = blob.add(all_chunks.data(), all_chunks.size());
+    const size_t o_xs = blob.add(X_seg, seg_io ? (size_t)bi.S : 0);
+    const size_t o_ys = blob.add(Y_seg, seg_io ? (size_t)bi.S : 0);
     unsigned char* dev = nullptr;
     if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
 
@@ -597,7 +627,7 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     const bf16* x_op = (const bf16*)X;
     if (bi.n_ia3in) {
         ScaleParams sc{(const bf16*)X, (bf16*)(wsb + wl.sc_off), b->d_in, (const RowChunk*)(dev + o_all),
-                       (const SegDesc*)(dev + o_seg), KIND_IA3_IN};
+                       (const SegDesc*)(dev + o_seg), KIND_IA3_IN, nullptr, nullptr};
         hipLaunchKernelGGL(symb_ia3_scale_rows_kernel, dim3((unsigned)all_chunks.size()), dim3(256), 0, s, sc);
         SYMB_HIP(h, hipGetLastError());
         x_op = (const bf16*)(wsb + wl.sc_off);
@@ -617,10 +647,20 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
         sp.chunks = (const RowChunk*)(dev + o_ch);
         sp.seg = (const SegDesc*)(dev + o_seg);
         sp.use_packed = 0;
+        if (seg_io) {
+            sp.L_seg = (const bf16* const*)(dev + o_xs);
+            sp.off = (const int32_t*)(dev + o_off);
+        }
         if ((st = launch_skinny(h, sp, (int)chunks.size(), bi.max_rpad, s)) != SYMB_OK) return st;
     }
     GemmParams gp{};
     gp.Aop = x_op;
+    if (seg_io) {
+        gp.Aop = nullptr;
+        gp.a_seg = (const bf16* const*)(dev + o_xs);
+        gp.a_base = (const bf16*)x_base;
+        gp.c_seg = (bf16* const*)(dev + o_ys);
+    }
     gp.Bop = (const bf16*)W;
     gp.C = (bf16*)Y;
     gp.Cbase = (bf16*)Ybase;
@@ -646,6 +686,14 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
 symb_status symb_base_linear_fwd(symb_handle h, const symb_batch* b, const void* X, const void* W, const void* bias,
                                  void* Y, void* Ybase, void* ws, size_t ws_bytes, void* stream) {
     return forward_impl(h, b, X, W, bias, nullptr, Y, Ybase, ws, ws_bytes, stream);
+}
+
+symb_status symb_base_linear_fwd_seg(symb_handle h, const symb_batch* b, const void* const* X_seg, const void* W,
+                                     const void* bias, void* const* Y_seg, void* ws, size_t ws_bytes, void* stream) {
+    symb_status st = check_handle(h);
+    if (st != SYMB_OK) return st;
+    if (!X_seg || !Y_seg) return fail(h, SYMB_ERR_INVALID_ARG, "X_seg and Y_seg are required");
+    return forward_impl(h, b, nullptr, W, bias, nullptr, nullptr, nullptr, ws, ws_bytes, stream, X_seg, Y_seg);
 }
 
 symb_status symb_base_linear_fwd_denoise(symb_handle h, const symb_batch* b, const void* Xn, const void* W, const void* bias,
@@ -684,20 +732,45 @@ symb_status symb_noise_add(symb_handle h, const symb_batch* b, const void* X, co
 }
 
 // ---------------------------------------------------------------------------------------------
+static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const void* dY, const void* W, void* dX,
+                                       void* dXbase, uint32_t flags, void* ws, size_t ws_bytes, void* stream,
+                                       const void* const* dY_seg, void* const* dX_seg);
+
 symb_status symb_base_linear_bwd_input(symb_handle h, const symb_batch* b, const void* dY, const void* W, void* dX,
                                        uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
-    return symb_base_linear_bwd_input_ex(h, b, dY, W, dX, nullptr, flags, ws, ws_bytes, stream);
+    return backward_input_impl(h, b, dY, W, dX, nullptr, flags, ws, ws_bytes, stream, nullptr, nullptr);
 }
 
 symb_status symb_base_linear_bwd_input_ex(symb_handle h, const symb_batch* b, const void* dY, const void* W, void* dX,
                                           void* dXbase, uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
+    return backward_input_impl(h, b, dY, W, dX, dXbase, flags, ws, ws_bytes, stream, nullptr, nullptr);
+}
+
+symb_status symb_base_linear_bwd_input_seg(symb_handle h, const symb_batch* b, const void* const* dY_seg, const void* W,
+                                           void* const* dX_seg, uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
+    symb_status st = check_handle(h);
+    if (st != SYMB_OK) return st;
+    if (!dY_seg || !dX_seg) return fail(h, SYMB_ERR_INVALID_ARG, "dY_seg and dX_seg are required");
+    return backward_input_impl(h, b, nullptr, W, nullptr, nullptr, flags, ws, ws_bytes, stream, dY_seg, dX_seg);
+}
+
+static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const void* dY, const void* W, void* dX,
+                                       void* dXbase, uint32_t flags, void* ws, size_t ws_bytes, void* stream,
+                                       const void* const* dY_seg, void* const* dX_seg) {
     symb_status st = check_handle(h);
     if (st != SYMB_OK) return st;
     if ((st = validate(h, b)) != SYMB_OK) return st;
     if (flags != SYMB_BWD_FULL && flags != SYMB_BWD_BASE_ONLY) return fail(h, SYMB_ERR_INVALID_ARG, "unknown backward flag %u", flags);
     const BatchInfo bi = inspect(b);
     if (bi.T == 0) return SYMB_OK;
-    if (!dY || !W || !dX) return fail(h, SYMB_ERR_INVALID_ARG, "dY, W and dX are required");
+    const bool seg_io = dY_seg != nullptr;
+    const void* g_base = nullptr;
+    if (seg_io) {
+        if (!W) return fail(h, SYMB_ERR_INVALID_ARG, "W is required");
+        const bool copy_first = flags == SYMB_BWD_FULL && bi.n_ia3 > 0;     // then the GEMM reads the scaled copy, not the buffers
+        if ((st = check_seg_ptrs(h, b, dY_seg, (size_t)b->d_out * 2, "dY", !copy_first, &g_base)) != SYMB_OK) return st;
+        if ((st = check_seg_ptrs(h, b, (const void* const*)dX_seg, (size_t)b->d_in * 2, "dX", false, nullptr)) != SYMB_OK) return st;
+    } else if (!dY || !W || !dX) return fail(h, SYMB_ERR_INVALID_ARG, "dY, W and dX are required");
     if (misaligned16(dY) || misaligned16(W) || misaligned16(dX) || misaligned16(dXbase) || misaligned16(ws))
         return fail(h, SYMB_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
     const bool full = flags == SYMB_BWD_FULL;
@@ -743,6 +816,8 @@ symb_status symb_base_linear_bwd_input_ex(symb_handle h, const symb_batch* b, co
     const size_t o_all = blob.add(all_chunks.data(), all_chunks.size());
     const size_t o_pk = blob.add(pk_off.data(), pk_off.size());
     const size_t o_pa = blob.add(pa_off.data(), pa_off.size());
+    const size_t o_gs = blob.add(dY_seg, seg_io ? (size_t)bi.S : 0);
+    const size_t o_xs = blob.add(dX_seg, seg_io ? (size_t)bi.S : 0);
     unsigned char* dev = nullptr;
     if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
 
@@ -768,10 +843,17 @@ symb_status symb_base_linear_bwd_input_ex(symb_handle h, const symb_batch* b, co
         sp.packed = (const bf16*)(wsb + wl.pk_off);
         sp.packed_off = (const int64_t*)(dev + o_pk);
         sp.use_packed = 1;
+        if (seg_io) {
+            sp.L_seg = (const bf16* const*)(dev + o_gs);
+            sp.off = (const int32_t*)(dev + o_off);
+        }
         if ((st = launch_skinny(h, sp, (int)chunks.size(), bi.max_rpad, s)) != SYMB_OK) return st;
     }
+    bool a_from_seg = seg_io;
     if (ia3) {
-        ScaleParams sc{(const bf16*)dY, (bf16*)(wsb + wl.sc_off), b->d_out, (const RowChunk*)(dev + o_all), (const SegDesc*)(dev + o_seg), KIND_IA3};
+        a_from_seg = false;
+        ScaleParams sc{(const bf16*)dY, (bf16*)(wsb + wl.sc_off), b->d_out, (const RowChunk*)(dev + o_all), (const SegDesc*)(dev + o_seg), KIND_IA3,
+                       seg_io ? (const bf16* const*)(dev + o_gs) : nullptr, (const int32_t*)(dev + o_off)};
         hipLaunchKernelGGL(symb_ia3_scale_rows_kernel, dim3((unsigned)all_chunks.size()), dim3(256), 0, s, sc);
         SYMB_HIP(h, hipGetLastError());
         a_op = (const bf16*)(wsb + wl.sc_off);
@@ -781,6 +863,12 @@ symb_status symb_base_linear_bwd_input_ex(symb_handle h, const symb_batch* b, co
     gp.Bop = (const bf16*)W;
     gp.C = (bf16*)dX;
     gp.Cbase = (bf16*)dXbase;
+    if (a_from_seg) {
+        gp.Aop = nullptr;
+        gp.a_seg = (const bf16* const*)(dev + o_gs);
+        gp.a_base = (const bf16*)g_base;
+    }
+    if (seg_io) gp.c_seg = (bf16* const*)(dev + o_xs);
     gp.M = bi.T;
     gp.N = b->d_in;
     gp.K = b->d_out;

@@ -412,3 +412,68 @@ def test_ia3_input_scaling(case):
             assert not dl.any()
         else:
             assert_close(dl, oracle.ia3_grad(off, oads, p["X"], p["dY"], p["W"], p["bias"], i, G_saved=G_saved), f"IA3_IN dl[{i}]")
+
+
+@pytest.mark.parametrize("case", [
+    dict(seed=61, d_in=320, d_out=264, lens=[130, 1, 0, 77, 1, 300, 64], kinds=[L, I, L, N, L, L, I], ranks=[8, 16, 5, 24, 33]),
+    dict(seed=62, d_in=136, d_out=6208, lens=[700, 5, 795], kinds=[L, I, L], ranks=[16, 8]),
+    dict(seed=63, d_in=6208, d_out=136, lens=[700, 5, 795], kinds=[L, N, L], ranks=[16, 5]),
+])
+def test_per_segment_buffers(case):
+    """Rows read from and written to one buffer per client, carved in shuffled order and with gaps
+    from one arena (Sec. 3.4: pre-allocated client buffers), against the flat oracle result."""
+    c = dict(case)
+    p = make_problem(c.pop("seed"), c.pop("d_in"), c.pop("d_out"), c.pop("lens"), c.pop("kinds"), c.pop("ranks"))
+    off, d_in, d_out, T, S = p["off"], p["d_in"], p["d_out"], p["T"], len(p["ads"])
+    oads = oracle_ads(p["ads"])
+    h = gh.handle()
+    dev = gh.upload_adapters(p["ads"], d_in, d_out, grads=False)
+    b = sb.Batch(d_in, d_out, off, dev.descs)
+    rng = np.random.default_rng(5)
+
+    def carve(width, src_bits=None):
+        """One arena; segment i gets its own region (random order, 16-byte aligned gaps of junk between)."""
+        order = rng.permutation(S)
+        sizes = {int(i): int(off[i + 1] - off[i]) * width for i in order}
+        gaps = {int(i): 8 * int(rng.integers(1, 40)) for i in order}
+        arena = torch.full((sum(sizes.values()) + sum(gaps.values()) + 8,), float("nan"), device="cuda", dtype=torch.bfloat16)
+        views, cur = [None] * S, 0
+        for i in order:
+            i = int(i)
+            cur += gaps[i]
+            n = int(off[i + 1] - off[i])
+            views[i] = arena[cur:cur + sizes[i]].view(n, width) if n else None
+            if n and src_bits is not None:
+                views[i].copy_(gh.to_dev(np.ascontiguousarray(src_bits[off[i]:off[i + 1]])))
+            cur += sizes[i]
+        return arena, views
+
+    def gather(views, width):
+        out = np.zeros((T, width))
+        for i, v in enumerate(views):
+            if v is not None:
+                out[off[i]:off[i + 1]] = gh.bf16_to_f64(v)
+        return out
+
+    Wd, bd = gh.to_dev(p["W"]), gh.to_dev(p["bias"])
+    _, Xv = carve(d_in, p["X"])
+    _, Yv = carve(d_out)
+    sb.symb_base_linear_fwd_seg(h, b, Xv, Wd, bd, Yv, gh.workspace(b, sb.SYMB_OP_FWD))
+    torch.cuda.synchronize()
+    _, Yr = oracle.forward(off, oads, p["X"], p["W"], p["bias"])
+    assert_close(gather(Yv, d_out), Yr, "per-segment Y", out_bf16=True)
+    for base_only in (False, True):
+        _, Gv = carve(d_out, p["dY"])
+        _, DXv = carve(d_in)
+        sb.symb_base_linear_bwd_input_seg(h, b, Gv, Wd, DXv, sb.SYMB_BWD_BASE_ONLY if base_only else sb.SYMB_BWD_FULL,
+                                          gh.workspace(b, sb.SYMB_OP_BWD_INPUT))
+        torch.cuda.synchronize()
+        assert_close(gather(DXv, d_in), oracle.backward_input(off, oads, p["dY"], p["W"], base_only=base_only),
+                     f"per-segment dX base_only={base_only}", out_bf16=True)
+    # buffers more than 4 GiB apart are refused before any launch (fake addresses: nothing is dereferenced)
+    far = [int(Xv[i].data_ptr()) if Xv[i] is not None else 0 for i in range(S)]
+    first = next(i for i in range(S) if Xv[i] is not None)
+    far[first] += 5 << 30
+    with pytest.raises(sb.SymbError) as e:
+        sb.symb_base_linear_fwd_seg(h, b, far, Wd, bd, Yv, gh.workspace(b, sb.SYMB_OP_FWD))
+    assert e.value.status == sb.SYMB_ERR_UNSUPPORTED
