@@ -42,6 +42,7 @@ struct symb_context {
     bool slot_used[kSlots] = {};
     int next_slot = 0;
     std::string error;
+    std::vector<const void*> lds_attr_set;       // kernels whose dynamic-LDS limit was raised on this context's device
     // measurement hook: event pairs around GEMM launches
     bool timing = false;
     std::vector<hipEvent_t> tev;                 // 2 * kMaxTimed events, created on first enable
@@ -280,10 +281,11 @@ template <int BM, int BN, int WGM, int WGN, bool NN, bool PLAIN = false>
 symb_status launch_gemm_t(symb_handle h, GemmParams gp, hipStream_t st) {
     using TT = GemmTile<BM, BN, WGM, WGN, NN>;
     auto kfn = symb_gemm_kernel<BM, BN, WGM, WGN, NN, PLAIN>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        SYMB_HIP(h, hipFuncSetAttribute(reinterpret_cast<const void*>(kfn), hipFuncAttributeMaxDynamicSharedMemorySize, TT::SMEM));
-        attr_set = true;
+    // once per context (= per device): the attribute belongs to the device the kernel is loaded on
+    const void* kptr = reinterpret_cast<const void*>(kfn);
+    if (std::find(h->lds_attr_set.begin(), h->lds_attr_set.end(), kptr) == h->lds_attr_set.end()) {
+        SYMB_HIP(h, hipFuncSetAttribute(kptr, hipFuncAttributeMaxDynamicSharedMemorySize, TT::SMEM));
+        h->lds_attr_set.push_back(kptr);
     }
     gp.num_m_tiles = (gp.M + BM - 1) / BM;
     gp.num_n_tiles = (gp.N + BN - 1) / BN;
