@@ -209,7 +209,8 @@ symb_status symb_base_linear_bwd_input_ex(symb_handle h, const symb_batch* b, co
  * bf16 rows, 16-byte aligned; an empty segment's entry is ignored).  An output buffer must not
  * overlap any input buffer.  The input buffers of one call must lie within one 4 GiB window
  * (SYMB_ERR_UNSUPPORTED otherwise): carve them from one arena.  No Ybase / dXbase output and no
- * IA3 input scaling in this form.
+ * IA3 input scaling in this form (a client that needs Ybase for an IA3 gradient keeps its own
+ * output of an all-NONE call, which is the paper's flow).
  */
 symb_status symb_base_linear_fwd_seg(symb_handle h, const symb_batch* b, const void* const* X_seg,
                                      const void* W, const void* bias, void* const* Y_seg, void* ws,
@@ -217,6 +218,11 @@ symb_status symb_base_linear_fwd_seg(symb_handle h, const symb_batch* b, const v
 symb_status symb_base_linear_bwd_input_seg(symb_handle h, const symb_batch* b, const void* const* dY_seg,
                                            const void* W, void* const* dX_seg, uint32_t flags, void* ws,
                                            size_t ws_bytes, void* stream);
+/* Adapter gradients from per-client buffers (Ybase_seg may be NULL if no IA3 segment wants dl; no
+ * window restriction here; the SYMB_GRAD_REUSE_* flags work as in the flat call). */
+symb_status symb_adapter_grad_seg(symb_handle h, const symb_batch* b, const void* const* X_seg,
+                                  const void* const* dY_seg, const void* const* Ybase_seg, uint32_t flags,
+                                  void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Adapter gradients per segment (the client-side autograd of Sec. 3.2, fused here):

@@ -28,6 +28,7 @@ EXPORTS = ("symb_create", "symb_destroy", "symb_validate_batch", "symb_debug_row
            "symb_plan_row_tiles", "symb_workspace_bytes", "symb_base_linear_fwd",
            "symb_base_linear_bwd_input", "symb_base_linear_bwd_input_ex", "symb_adapter_grad", "symb_adapter_grad_ex",
            "symb_noise_add", "symb_base_linear_fwd_denoise", "symb_base_linear_fwd_seg", "symb_base_linear_bwd_input_seg",
+           "symb_adapter_grad_seg",
            "symb_status_string", "symb_last_error",
            "symb_batcher_create", "symb_batcher_destroy", "symb_batcher_submit", "symb_batcher_pending",
            "symb_batcher_next_due", "symb_batcher_take",
@@ -81,6 +82,7 @@ def lib() -> C.CDLL:
         l.symb_adapter_grad_ex.argtypes = [vp, bp, vp, vp, vp, vp, u32, vp, sz, vp]
         l.symb_base_linear_fwd_seg.argtypes = [vp, bp, C.POINTER(vp), vp, vp, C.POINTER(vp), vp, sz, vp]
         l.symb_base_linear_bwd_input_seg.argtypes = [vp, bp, C.POINTER(vp), vp, C.POINTER(vp), u32, vp, sz, vp]
+        l.symb_adapter_grad_seg.argtypes = [vp, bp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), u32, vp, sz, vp]
         l.symb_noise_add.argtypes = [vp, bp, vp, C.POINTER(symb_noise), vp, vp]
         l.symb_base_linear_fwd_denoise.argtypes = [vp, bp, vp, vp, vp, C.POINTER(symb_noise), vp, vp, sz, vp]
         l.symb_debug_gemm_timing_enable.argtypes = [vp, i32]
@@ -231,6 +233,14 @@ def symb_base_linear_bwd_input_seg(handle, batch: Batch, dY_seg: Sequence, W, dX
     wp, wb = _ws_args(ws)
     _check(lib().symb_base_linear_bwd_input_seg(handle, batch.ref(), _ptr_array(batch, dY_seg), _ptr(W),
                                                 _ptr_array(batch, dX_seg), int(flags), wp, wb, stream or None), handle)
+
+
+def symb_adapter_grad_seg(handle, batch: Batch, X_seg: Sequence, dY_seg: Sequence, Ybase_seg=None,
+                          flags: int = SYMB_GRAD_OVERWRITE, ws=None, stream: int = 0) -> None:
+    wp, wb = _ws_args(ws)
+    _check(lib().symb_adapter_grad_seg(handle, batch.ref(), _ptr_array(batch, X_seg), _ptr_array(batch, dY_seg),
+                                       None if Ybase_seg is None else _ptr_array(batch, Ybase_seg), int(flags),
+                                       wp, wb, stream or None), handle)
 
 
 def symb_noise_add(handle, batch: Batch, X, noise: Sequence, Xn, stream: int = 0) -> None:

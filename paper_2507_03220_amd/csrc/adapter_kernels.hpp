@@ -225,6 +225,7 @@ struct GradParams {
     const SegDesc* seg;
     const int32_t* seg_list;  // device: segments that want this gradient (grid.y indexes it)
     int accumulate;
+    const bf16* const* R_seg; // device [S] or null: rows of segment i of R start at R_seg[i]
 };
 
 constexpr int GRAD_CT = 128;       // columns per workgroup
@@ -252,6 +253,7 @@ symb_lora_grad_kernel(const GradParams p) {
     const int s = p.seg_list[blockIdx.y];
     const SegDesc sd = p.seg[s];
     const int t_lo = p.off[s], t_hi = p.off[s + 1];
+    const bf16* const rbase = p.R_seg ? p.R_seg[s] - (size_t)t_lo * p.ncols : p.R;
     const int c0 = blockIdx.x * GRAD_CT;
     const int nb = sd.rpad >> 4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -272,7 +274,7 @@ symb_lora_grad_kernel(const GradParams p) {
             const int c = tid + i * 256, tr = c >> 4, cc = c & 15;
             const bool ok = (t0 + tr) < t_hi && (c0 + cc * 8) < p.ncols;
             rr[i] = make_uint4(0u, 0u, 0u, 0u);
-            if (ok) rr[i] = *reinterpret_cast<const uint4*>(p.R + (size_t)(t0 + tr) * p.ncols + c0 + cc * 8);
+            if (ok) rr[i] = *reinterpret_cast<const uint4*>(rbase + (size_t)(t0 + tr) * p.ncols + c0 + cc * 8);
         }
         __syncthreads();     // previous step's LDS reads are done
 #pragma unroll
@@ -353,12 +355,16 @@ struct Ia3GradParams {
     const SegDesc* seg;
     const int32_t* seg_list;
     int accumulate;
+    const bf16* const* dY_seg;   // device [S] or null: per-segment buffers of the first / second operand
+    const bf16* const* Y0_seg;
 };
 constexpr int IA3_GRAD_COLS = 128;
 __global__ void __launch_bounds__(256) symb_ia3_grad_kernel(const Ia3GradParams p) {
     __shared__ float red[16][16][9];
     const int s = p.seg_list[blockIdx.y];
     const int t_lo = p.off[s], t_hi = p.off[s + 1];
+    const bf16* const gbase = p.dY_seg ? p.dY_seg[s] - (size_t)t_lo * p.d_out : p.dY;
+    const bf16* const ybase = p.Y0_seg ? p.Y0_seg[s] - (size_t)t_lo * p.d_out : p.Y0;
     const int cc = threadIdx.x & 15, tl = threadIdx.x >> 4;
     const int c = blockIdx.x * IA3_GRAD_COLS + cc * 8;
     float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -376,15 +382,15 @@ __global__ void __launch_bounds__(256) symb_ia3_grad_kernel(const Ia3GradParams 
             uint4 g[4], y[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                g[u] = *reinterpret_cast<const uint4*>(p.dY + (size_t)(t + 16 * u) * p.d_out + c);
-                y[u] = *reinterpret_cast<const uint4*>(p.Y0 + (size_t)(t + 16 * u) * p.d_out + c);
+                g[u] = *reinterpret_cast<const uint4*>(gbase + (size_t)(t + 16 * u) * p.d_out + c);
+                y[u] = *reinterpret_cast<const uint4*>(ybase + (size_t)(t + 16 * u) * p.d_out + c);
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) fma8(g[u], y[u]);
         }
         for (; t < t_hi; t += 16) {
-            const uint4 g = *reinterpret_cast<const uint4*>(p.dY + (size_t)t * p.d_out + c);
-            const uint4 y = *reinterpret_cast<const uint4*>(p.Y0 + (size_t)t * p.d_out + c);
+            const uint4 g = *reinterpret_cast<const uint4*>(gbase + (size_t)t * p.d_out + c);
+            const uint4 y = *reinterpret_cast<const uint4*>(ybase + (size_t)t * p.d_out + c);
             fma8(g, y);
         }
     }

@@ -889,13 +889,31 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
 }
 
 // ---------------------------------------------------------------------------------------------
+static symb_status adapter_grad_impl(symb_handle h, const symb_batch* b, const void* X, const void* dY, const void* Ybase,
+                                     const void* dXbase, uint32_t flags, void* ws, size_t ws_bytes, void* stream,
+                                     const void* const* X_seg, const void* const* dY_seg, const void* const* Ybase_seg);
+
 symb_status symb_adapter_grad(symb_handle h, const symb_batch* b, const void* X, const void* dY, const void* Ybase,
                               uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
-    return symb_adapter_grad_ex(h, b, X, dY, Ybase, nullptr, flags, ws, ws_bytes, stream);
+    return adapter_grad_impl(h, b, X, dY, Ybase, nullptr, flags, ws, ws_bytes, stream, nullptr, nullptr, nullptr);
 }
 
 symb_status symb_adapter_grad_ex(symb_handle h, const symb_batch* b, const void* X, const void* dY, const void* Ybase,
                                  const void* dXbase, uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
+    return adapter_grad_impl(h, b, X, dY, Ybase, dXbase, flags, ws, ws_bytes, stream, nullptr, nullptr, nullptr);
+}
+
+symb_status symb_adapter_grad_seg(symb_handle h, const symb_batch* b, const void* const* X_seg, const void* const* dY_seg,
+                                  const void* const* Ybase_seg, uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
+    symb_status st = check_handle(h);
+    if (st != SYMB_OK) return st;
+    if (!X_seg || !dY_seg) return fail(h, SYMB_ERR_INVALID_ARG, "X_seg and dY_seg are required");
+    return adapter_grad_impl(h, b, nullptr, nullptr, nullptr, nullptr, flags, ws, ws_bytes, stream, X_seg, dY_seg, Ybase_seg);
+}
+
+static symb_status adapter_grad_impl(symb_handle h, const symb_batch* b, const void* X, const void* dY, const void* Ybase,
+                                     const void* dXbase, uint32_t flags, void* ws, size_t ws_bytes, void* stream,
+                                     const void* const* X_seg, const void* const* dY_seg, const void* const* Ybase_seg) {
     symb_status st = check_handle(h);
     if (st != SYMB_OK) return st;
     if ((st = validate(h, b)) != SYMB_OK) return st;
@@ -903,7 +921,18 @@ symb_status symb_adapter_grad_ex(symb_handle h, const symb_batch* b, const void*
         return fail(h, SYMB_ERR_INVALID_ARG, "unknown gradient flag %u", flags);
     const bool reuse_dh = (flags & SYMB_GRAD_REUSE_DH) != 0, reuse_hs = (flags & SYMB_GRAD_REUSE_HS) != 0;
     const BatchInfo bi = inspect(b);
-    if (!X || !dY) {
+    const bool seg_io = X_seg != nullptr;
+    if (seg_io) {
+        if (bi.n_ia3in) return fail(h, SYMB_ERR_UNSUPPORTED, "IA3 input scaling is not available with per-segment buffers");
+        if ((st = check_seg_ptrs(h, b, X_seg, (size_t)b->d_in * 2, "X", false, nullptr)) != SYMB_OK) return st;
+        if ((st = check_seg_ptrs(h, b, dY_seg, (size_t)b->d_out * 2, "dY", false, nullptr)) != SYMB_OK) return st;
+        if (Ybase_seg) {
+            for (int i = 0; i < bi.S; ++i)
+                if (b->adapters[i].kind == SYMB_ADAPTER_IA3 && b->adapters[i].dA && b->seg_offsets[i + 1] > b->seg_offsets[i] &&
+                    (!Ybase_seg[i] || misaligned16(Ybase_seg[i])))
+                    return fail(h, SYMB_ERR_INVALID_ARG, "Ybase of IA3 segment %d is null or misaligned", i);
+        }
+    } else if (!X || !dY) {
         if (bi.T > 0) return fail(h, SYMB_ERR_INVALID_ARG, "X and dY are required");
     }
     if (misaligned16(X) || misaligned16(dY) || misaligned16(Ybase) || misaligned16(dXbase) || misaligned16(ws))
@@ -943,7 +972,7 @@ symb_status symb_adapter_grad_ex(symb_handle h, const symb_batch* b, const void*
     }
     if (!want_lin.empty() && !dXbase)
         return fail(h, SYMB_ERR_INVALID_ARG, "an IA3_IN segment wants dl but dXbase (the input gradient before the input scale) is null");
-    if (!want_l.empty() && !Ybase)
+    if (!want_l.empty() && !(seg_io ? (const void*)Ybase_seg : Ybase))
         return fail(h, SYMB_ERR_INVALID_ARG, "an IA3 segment wants dl but Ybase (the pre-adapter output) is null");
     const bool any_lora = !want_a.empty() || !want_b.empty();
     const WsLayout wl = ws_layout(b, bi, SYMB_OP_ADAPTER_GRAD, true, any_lora);
@@ -983,6 +1012,9 @@ symb_status symb_adapter_grad_ex(symb_handle h, const symb_batch* b, const void*
     const size_t o_wb = blob.add(want_b.data(), want_b.size());
     const size_t o_wl = blob.add(want_l.data(), want_l.size());
     const size_t o_wli = blob.add(want_lin.data(), want_lin.size());
+    const size_t o_xs = blob.add(X_seg, seg_io ? (size_t)bi.S : 0);
+    const size_t o_gs = blob.add(dY_seg, seg_io ? (size_t)bi.S : 0);
+    const size_t o_ys = blob.add(Ybase_seg, (seg_io && Ybase_seg) ? (size_t)bi.S : 0);
     unsigned char* dev = nullptr;
     if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
     unsigned char* wsb = (unsigned char*)ws;
@@ -999,10 +1031,14 @@ symb_status symb_adapter_grad_ex(symb_handle h, const symb_batch* b, const void*
             sp.chunks = (const RowChunk*)(dev + o_chh);
             sp.seg = dseg;
             sp.use_packed = 0;
+            if (seg_io) {
+                sp.L_seg = (const bf16* const*)(dev + o_xs);
+                sp.off = doff;
+            }
             if ((st = launch_skinny(h, sp, (int)ch_h.size(), grad_max_rpad, s)) != SYMB_OK) return st;
         }
         GradParams gp{(const bf16*)dY, (const bf16*)(wsb + wl.h_off), b->d_out, 2 * bi.max_rpad, doff, dseg,
-                      (const int32_t*)(dev + o_wb), acc ? 1 : 0};
+                      (const int32_t*)(dev + o_wb), acc ? 1 : 0, seg_io ? (const bf16* const*)(dev + o_gs) : nullptr};
         if ((st = launch_grad<true>(h, gp, (int)want_b.size(), grad_max_rpad, s)) != SYMB_OK) return st;
     }
     if (!want_a.empty()) {       // dA_i = dH_i^T X_i
@@ -1020,19 +1056,25 @@ symb_status symb_adapter_grad_ex(symb_handle h, const symb_batch* b, const void*
             sp.packed = (const bf16*)(wsb + wl.pk_off);
             sp.packed_off = (const int64_t*)(dev + o_pk);
             sp.use_packed = 1;
+            if (seg_io) {
+                sp.L_seg = (const bf16* const*)(dev + o_gs);
+                sp.off = doff;
+            }
             if ((st = launch_skinny(h, sp, (int)ch_dh.size(), grad_max_rpad, s)) != SYMB_OK) return st;
         }
         GradParams gp{(const bf16*)X, (const bf16*)(wsb + wl.dh_off), b->d_in, 2 * bi.max_rpad, doff, dseg,
-                      (const int32_t*)(dev + o_wa), acc ? 1 : 0};
+                      (const int32_t*)(dev + o_wa), acc ? 1 : 0, seg_io ? (const bf16* const*)(dev + o_xs) : nullptr};
         if ((st = launch_grad<false>(h, gp, (int)want_a.size(), grad_max_rpad, s)) != SYMB_OK) return st;
     }
     if (!want_l.empty()) {
-        Ia3GradParams ip{(const bf16*)dY, (const bf16*)Ybase, b->d_out, doff, dseg, (const int32_t*)(dev + o_wl), acc ? 1 : 0};
+        Ia3GradParams ip{(const bf16*)dY, (const bf16*)Ybase, b->d_out, doff, dseg, (const int32_t*)(dev + o_wl), acc ? 1 : 0,
+                         seg_io ? (const bf16* const*)(dev + o_gs) : nullptr, seg_io ? (const bf16* const*)(dev + o_ys) : nullptr};
         hipLaunchKernelGGL(symb_ia3_grad_kernel, dim3((b->d_out + IA3_GRAD_COLS - 1) / IA3_GRAD_COLS, (unsigned)want_l.size()), dim3(256), 0, s, ip);
         SYMB_HIP(h, hipGetLastError());
     }
     if (!want_lin.empty()) {     // dl_i[k] = sum_t X[t][k] * (dY W)[t][k]: the same reduction over the input width
-        Ia3GradParams ip{(const bf16*)X, (const bf16*)dXbase, b->d_in, doff, dseg, (const int32_t*)(dev + o_wli), acc ? 1 : 0};
+        Ia3GradParams ip{(const bf16*)X, (const bf16*)dXbase, b->d_in, doff, dseg, (const int32_t*)(dev + o_wli), acc ? 1 : 0,
+                         nullptr, nullptr};
         hipLaunchKernelGGL(symb_ia3_grad_kernel, dim3((b->d_in + IA3_GRAD_COLS - 1) / IA3_GRAD_COLS, (unsigned)want_lin.size()), dim3(256), 0, s, ip);
         SYMB_HIP(h, hipGetLastError());
     }

@@ -470,6 +470,25 @@ def test_per_segment_buffers(case):
         torch.cuda.synchronize()
         assert_close(gather(DXv, d_in), oracle.backward_input(off, oads, p["dY"], p["W"], base_only=base_only),
                      f"per-segment dX base_only={base_only}", out_bf16=True)
+    # adapter gradients from the same kind of buffers (the IA3 gradient takes the oracle's Y0 rounded to bf16)
+    grads = gh.upload_adapters(p["ads"], d_in, d_out, grads=True)
+    bg = sb.Batch(d_in, d_out, off, grads.descs)
+    Y0r, _ = oracle.forward(off, oads, p["X"], p["W"], p["bias"])
+    Y0_saved = synth.f32_to_bf16_bits(Y0r.astype(np.float32))
+    _, Gv = carve(d_out, p["dY"])
+    _, Y0v = carve(d_out, Y0_saved)
+    sb.symb_adapter_grad_seg(h, bg, Xv, Gv, Y0v, sb.SYMB_GRAD_OVERWRITE, gh.workspace(bg, sb.SYMB_OP_ADAPTER_GRAD))
+    torch.cuda.synchronize()
+    for i, a in enumerate(p["ads"]):
+        if off[i + 1] == off[i]:
+            continue
+        if a.kind == L:
+            dAr, dBr = oracle.lora_grad(off, oads, p["X"], p["dY"], i)
+            assert_close(grads.descs[i].dA.cpu().numpy(), dAr, f"per-segment dA[{i}]")
+            assert_close(grads.descs[i].dB.cpu().numpy(), dBr, f"per-segment dB[{i}]")
+        elif a.kind == I:
+            dlr = oracle.ia3_grad(off, oads, p["X"], p["dY"], p["W"], p["bias"], i, Y0_saved=Y0_saved)
+            assert_close(grads.descs[i].dA.cpu().numpy(), dlr, f"per-segment dl[{i}]")
     # buffers more than 4 GiB apart are refused before any launch (fake addresses: nothing is dereferenced)
     far = [int(Xv[i].data_ptr()) if Xv[i] is not None else 0 for i in range(S)]
     first = next(i for i in range(S) if Xv[i] is not None)
