@@ -11,12 +11,14 @@
 // epilogue with the optional bias, the optional store of the pre-adapter output and
 // the IA3 per-channel scale of each row's own segment.
 //
-// Tiling (gfx950): one workgroup owns a BM x BN tile of C; K is walked in steps of 64
-// through double-buffered LDS; WGM x WGN wavefronts of 64 lanes each own a
-// (BM/WGM) x (BN/WGN) sub-tile as 32x32 blocks of v_mfma_f32_32x32x16_bf16.  The MFMA
-// is issued as (weight fragment, activation fragment), so a lane ends up holding, for
-// one row m, runs of 4 consecutive n: rows keep their own segment in the epilogue and
-// the store is 8 bytes per lane.
+// Tiling (gfx950): one workgroup owns a BM x BN tile of C; WGM x WGN wavefronts of 64 lanes each
+// own a (BM/WGM) x (BN/WGN) sub-tile as 32x32 blocks of v_mfma_f32_32x32x16_bf16.  Operands go
+// from global memory straight into an LDS ring (no register hop).  The 256x256 / 4-wavefront
+// instantiation walks K in 64-k stages (whole 128-byte lines per request) with a hand-scheduled
+// assembly main loop (gemm_mainloop_asm.hpp); the other instantiations walk 32-k stages with a
+// compiler-scheduled loop.  The MFMA is issued as (weight fragment, activation fragment), so a
+// lane ends up holding, for one row m, runs of 4 consecutive n: rows keep their own segment in
+// the epilogue, which stages the bf16 tile through LDS and writes whole rows.
 #pragma once
 #include "gemm_mainloop_asm.hpp"
 #include "symb_device.hpp"
@@ -371,7 +373,9 @@ symb_gemm_kernel(const GemmParams p) {
         }
     };
 
-    // ---- main loop over the full 32-k stages.  NSTAGE LDS buffers form a ring; the loads of
+    // ---- main loop over the full stages.
+    // Assembly variant (64-k stages, ring of three A and two B units): see gemm_mainloop_asm.hpp.
+    // Compiler-scheduled variants (32-k stages): NSTAGE LDS buffers form a ring; the loads of
     // stage t + NSTAGE are issued as soon as every wavefront is done with stage t, i.e. NSTAGE - 1
     // iterations before they are needed.  Per iteration: MFMAs of k-step 0 run while the fragments
     // of k-step 1 are read; then this wavefront's loads of the next stage are awaited, one barrier
