@@ -496,3 +496,20 @@ def test_per_segment_buffers(case):
     with pytest.raises(sb.SymbError) as e:
         sb.symb_base_linear_fwd_seg(h, b, far, Wd, bd, Yv, gh.workspace(b, sb.SYMB_OP_FWD))
     assert e.value.status == sb.SYMB_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("d_in", [64, 72, 128, 192, 200, 320])
+def test_large_tile_kernel_with_one_to_five_k_stages(d_in):
+    """The 256x256 kernel's main loop has a prologue, a steady loop and two closing stages: shapes with
+    1, 2, 3 and 5 full 64-k stages, with and without a K remainder, wide enough to select that kernel."""
+    p = make_problem(70 + d_in, d_in, 6208, [700, 5, 795], [L, N, I], [16])
+    oads, off = oracle_ads(p["ads"]), p["off"]
+    Y, Yb = gh.forward(off, p["ads"], p["X"], p["W"], p["bias"], want_base=True)
+    Y0r, Yr = oracle.forward(off, oads, p["X"], p["W"], p["bias"])
+    assert_close(gh.bf16_to_f64(Y), Yr, f"Y d_in={d_in}", out_bf16=True)
+    assert_close(gh.bf16_to_f64(Yb), Y0r, f"Ybase d_in={d_in}", out_bf16=True)
+    # the same K extents in the input gradient: d_out takes the role of K there
+    q = make_problem(170 + d_in, 6208, d_in, [700, 5, 795], [L, N, I], [16])
+    dX = gh.backward_input(q["off"], q["ads"], q["dY"], q["W"])
+    assert_close(gh.bf16_to_f64(dX), oracle.backward_input(q["off"], oracle_ads(q["ads"]), q["dY"], q["W"]),
+                 f"dX d_out={d_in}", out_bf16=True)
