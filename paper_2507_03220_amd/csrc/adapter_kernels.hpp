@@ -34,7 +34,11 @@ struct SkinnyParams {
     const int32_t* off;       // device [S+1] (read only with L_seg)
 };
 
-constexpr int SKINNY_ROWS = 32;     // rows per workgroup (two 16-row MFMA blocks per wavefront)
+#ifndef SYMB_SKINNY_BLKS
+#define SYMB_SKINNY_BLKS 2
+#endif
+constexpr int SKINNY_BLKS = SYMB_SKINNY_BLKS;          // 16-row MFMA blocks per wavefront
+constexpr int SKINNY_ROWS = 16 * SKINNY_BLKS;          // rows per workgroup
 
 template <int RB>
 __global__ void __launch_bounds__(256)
@@ -46,10 +50,10 @@ symb_skinny_kernel(const SkinnyParams p) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int trow = lane & 15, kq = lane >> 4;
     // rows past the chunk are clamped onto its last row; their results are never stored
-    const bf16* lrow[2];
+    const bf16* lrow[SKINNY_BLKS];
     const bf16* const lbase = p.L_seg ? p.L_seg[ch.seg] - (size_t)p.off[ch.seg] * p.K : p.L;
 #pragma unroll
-    for (int b = 0; b < 2; ++b) lrow[b] = lbase + (size_t)(ch.row0 + min(b * 16 + trow, ch.nrows - 1)) * p.K + kq * 8;
+    for (int b = 0; b < SKINNY_BLKS; ++b) lrow[b] = lbase + (size_t)(ch.row0 + min(b * 16 + trow, ch.nrows - 1)) * p.K + kq * 8;
     const bf16* rbase = p.use_packed ? (p.packed + p.packed_off[ch.seg]) : sd.A;
     const int rrows = p.use_packed ? sd.rpad : sd.rank;  // valid adapter rows; the rest count as zero
     const bf16* rrow[RB];
@@ -60,9 +64,9 @@ symb_skinny_kernel(const SkinnyParams p) {
         rrow[j] = rbase + (size_t)(r_ok[j] ? (j * 16 + trow) : 0) * p.K + kq * 8;
     }
 
-    floatx4 acc[2][RB];
+    floatx4 acc[SKINNY_BLKS][RB];
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < SKINNY_BLKS; ++b)
 #pragma unroll
         for (int j = 0; j < RB; ++j) acc[b][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
@@ -70,13 +74,13 @@ symb_skinny_kernel(const SkinnyParams p) {
     // row data (the HBM stream) of the next slice is requested before the current slice is
     // multiplied, so a wavefront always has 8 KiB of it in flight; the adapter rows come from L2.
     const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
-    auto load_l = [&](uint4 (&lv)[2][4], int k) __attribute__((always_inline)) {
+    auto load_l = [&](uint4 (&lv)[SKINNY_BLKS][4], int k) __attribute__((always_inline)) {
 #pragma unroll
         for (int h = 0; h < 4; ++h)
 #pragma unroll
-            for (int b = 0; b < 2; ++b) lv[b][h] = *reinterpret_cast<const uint4*>(lrow[b] + k + h * 32);
+            for (int b = 0; b < SKINNY_BLKS; ++b) lv[b][h] = *reinterpret_cast<const uint4*>(lrow[b] + k + h * 32);
     };
-    auto step = [&](const uint4 (&lv)[2][4], int k) __attribute__((always_inline)) {
+    auto step = [&](const uint4 (&lv)[SKINNY_BLKS][4], int k) __attribute__((always_inline)) {
         uint4 rv[RB][4];
 #pragma unroll
         for (int h = 0; h < 4; ++h)
@@ -90,13 +94,13 @@ symb_skinny_kernel(const SkinnyParams p) {
                 if (j < nb) {
                     const bf16x8 rf = __builtin_bit_cast(bf16x8, r_ok[j] ? rv[j][h] : zero4);
 #pragma unroll
-                    for (int b = 0; b < 2; ++b)
+                    for (int b = 0; b < SKINNY_BLKS; ++b)
                         acc[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rf, __builtin_bit_cast(bf16x8, lv[b][h]), acc[b][j], 0, 0, 0);
                 }
     };
     int k0 = wave * 128;
     if (k0 + 128 <= p.K) {
-        uint4 la[2][4], lb[2][4];
+        uint4 la[SKINNY_BLKS][4], lb[SKINNY_BLKS][4];
         load_l(la, k0);
         while (true) {
             const int k1 = k0 + 512;
@@ -117,15 +121,15 @@ symb_skinny_kernel(const SkinnyParams p) {
 #pragma unroll
         for (int h = 0; h < 4; ++h) {
             const bool kok = (k0 + h * 32 + kq * 8) < p.K;
-            uint4 lv[2];
+            uint4 lv[SKINNY_BLKS];
 #pragma unroll
-            for (int b = 0; b < 2; ++b) lv[b] = kok ? *reinterpret_cast<const uint4*>(lrow[b] + k0 + h * 32) : zero4;
+            for (int b = 0; b < SKINNY_BLKS; ++b) lv[b] = kok ? *reinterpret_cast<const uint4*>(lrow[b] + k0 + h * 32) : zero4;
 #pragma unroll
             for (int j = 0; j < RB; ++j)
                 if (j < nb) {
                     const uint4 rv = (kok && r_ok[j]) ? *reinterpret_cast<const uint4*>(rrow[j] + k0 + h * 32) : zero4;
 #pragma unroll
-                    for (int b = 0; b < 2; ++b)
+                    for (int b = 0; b < SKINNY_BLKS; ++b)
                         acc[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rv), __builtin_bit_cast(bf16x8, lv[b]), acc[b][j], 0, 0, 0);
                 }
         }
@@ -133,7 +137,7 @@ symb_skinny_kernel(const SkinnyParams p) {
     // lane holds out[t = b*16 + trow][p = j*16 + 4*kq + q]
     if (wave > 0) {
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < SKINNY_BLKS; ++b)
 #pragma unroll
             for (int j = 0; j < RB; ++j)
                 if (j < nb)
@@ -145,7 +149,7 @@ symb_skinny_kernel(const SkinnyParams p) {
     // rpad rounding residuals (also bf16): value + residual carries ~16 significand bits on.
     if (wave == 0) {
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
+        for (int b = 0; b < SKINNY_BLKS; ++b) {
             const int t = b * 16 + trow;
             if (t < ch.nrows) {
                 bf16* row = p.out + (size_t)(ch.row0 + t) * p.out_pitch;
