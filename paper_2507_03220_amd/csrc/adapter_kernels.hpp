@@ -40,6 +40,81 @@ struct SkinnyParams {
 constexpr int SKINNY_BLKS = SYMB_SKINNY_BLKS;          // 16-row MFMA blocks per wavefront
 constexpr int SKINNY_ROWS = 16 * SKINNY_BLKS;          // rows per workgroup
 
+// acc[b][j] += sum over this wavefront's share of K of  L-rows (16-row block b) x R-rows (16-row block j):
+// lane (trow = lane % 16, kq = lane / 16) supplies row trow and k-offsets kq*8..kq*8+7 of each 32-k step
+// for both operands; the result lane holds acc[b][j][q] = dot(L row b*16 + trow, R row j*16 + 4*kq + q).
+// lrow / rrow already point at the lane's first 8 elements (row start + kq*8); r_ok masks R rows that
+// count as zero; nb = R blocks in use.
+template <int RB>
+__device__ __forceinline__ void skinny_dot(const bf16* (&lrow)[SKINNY_BLKS], const bf16* (&rrow)[RB],
+                                           bool (&r_ok)[RB], int nb, int K, int wave, int kq,
+                                           floatx4 (&acc)[SKINNY_BLKS][RB]) {
+    // Each wavefront takes every 4th 128-element slice of K (256 bytes per row per step).  The
+    // row data (the HBM stream) of the next slice is requested before the current slice is
+    // multiplied, so a wavefront always has 8 KiB of it in flight; the adapter rows come from L2.
+    const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
+    auto load_l = [&](uint4 (&lv)[SKINNY_BLKS][4], int k) __attribute__((always_inline)) {
+#pragma unroll
+        for (int h = 0; h < 4; ++h)
+#pragma unroll
+            for (int b = 0; b < SKINNY_BLKS; ++b) lv[b][h] = *reinterpret_cast<const uint4*>(lrow[b] + k + h * 32);
+    };
+    auto step = [&](const uint4 (&lv)[SKINNY_BLKS][4], int k) __attribute__((always_inline)) {
+        uint4 rv[RB][4];
+#pragma unroll
+        for (int h = 0; h < 4; ++h)
+#pragma unroll
+            for (int j = 0; j < RB; ++j)
+                if (j < nb) rv[j][h] = *reinterpret_cast<const uint4*>(rrow[j] + k + h * 32);
+#pragma unroll
+        for (int h = 0; h < 4; ++h)
+#pragma unroll
+            for (int j = 0; j < RB; ++j)
+                if (j < nb) {
+                    const bf16x8 rf = __builtin_bit_cast(bf16x8, r_ok[j] ? rv[j][h] : zero4);
+#pragma unroll
+                    for (int b = 0; b < SKINNY_BLKS; ++b)
+                        acc[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rf, __builtin_bit_cast(bf16x8, lv[b][h]), acc[b][j], 0, 0, 0);
+                }
+    };
+    int k0 = wave * 128;
+    if (k0 + 128 <= K) {
+        uint4 la[SKINNY_BLKS][4], lb[SKINNY_BLKS][4];
+        load_l(la, k0);
+        while (true) {
+            const int k1 = k0 + 512;
+            const bool more1 = k1 + 128 <= K;
+            if (more1) load_l(lb, k1);
+            step(la, k0);
+            k0 = k1;
+            if (!more1) break;
+            const int k2 = k1 + 512;
+            const bool more2 = k2 + 128 <= K;
+            if (more2) load_l(la, k2);
+            step(lb, k1);
+            k0 = k2;
+            if (!more2) break;
+        }
+    }
+    for (; k0 < K; k0 += 512) {                        // the slice that crosses the end of K
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            const bool kok = (k0 + h * 32 + kq * 8) < K;
+            uint4 lv[SKINNY_BLKS];
+#pragma unroll
+            for (int b = 0; b < SKINNY_BLKS; ++b) lv[b] = kok ? *reinterpret_cast<const uint4*>(lrow[b] + k0 + h * 32) : zero4;
+#pragma unroll
+            for (int j = 0; j < RB; ++j)
+                if (j < nb) {
+                    const uint4 rv = (kok && r_ok[j]) ? *reinterpret_cast<const uint4*>(rrow[j] + k0 + h * 32) : zero4;
+#pragma unroll
+                    for (int b = 0; b < SKINNY_BLKS; ++b)
+                        acc[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rv), __builtin_bit_cast(bf16x8, lv[b]), acc[b][j], 0, 0, 0);
+                }
+        }
+    }
+}
+
 template <int RB>
 __global__ void __launch_bounds__(256)
 symb_skinny_kernel(const SkinnyParams p) {
@@ -70,70 +145,7 @@ symb_skinny_kernel(const SkinnyParams p) {
 #pragma unroll
         for (int j = 0; j < RB; ++j) acc[b][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    // Each wavefront takes every 4th 128-element slice of K (256 bytes per row per step).  The
-    // row data (the HBM stream) of the next slice is requested before the current slice is
-    // multiplied, so a wavefront always has 8 KiB of it in flight; the adapter rows come from L2.
-    const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
-    auto load_l = [&](uint4 (&lv)[SKINNY_BLKS][4], int k) __attribute__((always_inline)) {
-#pragma unroll
-        for (int h = 0; h < 4; ++h)
-#pragma unroll
-            for (int b = 0; b < SKINNY_BLKS; ++b) lv[b][h] = *reinterpret_cast<const uint4*>(lrow[b] + k + h * 32);
-    };
-    auto step = [&](const uint4 (&lv)[SKINNY_BLKS][4], int k) __attribute__((always_inline)) {
-        uint4 rv[RB][4];
-#pragma unroll
-        for (int h = 0; h < 4; ++h)
-#pragma unroll
-            for (int j = 0; j < RB; ++j)
-                if (j < nb) rv[j][h] = *reinterpret_cast<const uint4*>(rrow[j] + k + h * 32);
-#pragma unroll
-        for (int h = 0; h < 4; ++h)
-#pragma unroll
-            for (int j = 0; j < RB; ++j)
-                if (j < nb) {
-                    const bf16x8 rf = __builtin_bit_cast(bf16x8, r_ok[j] ? rv[j][h] : zero4);
-#pragma unroll
-                    for (int b = 0; b < SKINNY_BLKS; ++b)
-                        acc[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rf, __builtin_bit_cast(bf16x8, lv[b][h]), acc[b][j], 0, 0, 0);
-                }
-    };
-    int k0 = wave * 128;
-    if (k0 + 128 <= p.K) {
-        uint4 la[SKINNY_BLKS][4], lb[SKINNY_BLKS][4];
-        load_l(la, k0);
-        while (true) {
-            const int k1 = k0 + 512;
-            const bool more1 = k1 + 128 <= p.K;
-            if (more1) load_l(lb, k1);
-            step(la, k0);
-            k0 = k1;
-            if (!more1) break;
-            const int k2 = k1 + 512;
-            const bool more2 = k2 + 128 <= p.K;
-            if (more2) load_l(la, k2);
-            step(lb, k1);
-            k0 = k2;
-            if (!more2) break;
-        }
-    }
-    for (; k0 < p.K; k0 += 512) {                        // the slice that crosses the end of K
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            const bool kok = (k0 + h * 32 + kq * 8) < p.K;
-            uint4 lv[SKINNY_BLKS];
-#pragma unroll
-            for (int b = 0; b < SKINNY_BLKS; ++b) lv[b] = kok ? *reinterpret_cast<const uint4*>(lrow[b] + k0 + h * 32) : zero4;
-#pragma unroll
-            for (int j = 0; j < RB; ++j)
-                if (j < nb) {
-                    const uint4 rv = (kok && r_ok[j]) ? *reinterpret_cast<const uint4*>(rrow[j] + k0 + h * 32) : zero4;
-#pragma unroll
-                    for (int b = 0; b < SKINNY_BLKS; ++b)
-                        acc[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rv), __builtin_bit_cast(bf16x8, lv[b]), acc[b][j], 0, 0, 0);
-                }
-        }
-    }
+    skinny_dot<RB>(lrow, rrow, r_ok, nb, p.K, wave, kq, acc);
     // lane holds out[t = b*16 + trow][p = j*16 + 4*kq + q]
     if (wave > 0) {
 #pragma unroll
@@ -172,6 +184,101 @@ symb_skinny_kernel(const SkinnyParams p) {
                     }
             }
         }
+    }
+}
+
+// -------------------------------------------------------------------------------------------
+// Forward for a batch of at most 128 rows (a handful of decode steps, Sec. 4's inference clients):
+//   Y[t][n] = sum_k X[t][k] W[n][k] (+ b[n]) (+ sum_p Hs[t][p] B_i[n][p])  (* l_i[n])
+// With so few rows a tiled GEMM launches too few workgroups to stream W at HBM speed.  Here a
+// workgroup owns 32 output columns: it streams those 32 rows of W once (the 4 wavefronts split K),
+// multiplies them with all rows of X (from L2) and finishes each (row, column) pair with its row's
+// own adapter.  Same arithmetic as the tiled path: fp32 accumulation, Hs as value + residual, one
+// rounding.  RB = row blocks of 16 (T <= 16 RB).
+// -------------------------------------------------------------------------------------------
+struct RowGemvParams {
+    const bf16* W;            // [N][K]
+    const bf16* X;            // [T][K]
+    bf16* Y;                  // [T][N]
+    const bf16* bias;         // [N] or null
+    int K, N, T, S;
+    const int32_t* off;       // device [S+1]
+    const SegDesc* seg;       // device [S]
+    const bf16* Hs;           // [T][hs_pitch] or null (no LoRA segment)
+    int hs_pitch;
+};
+
+template <int RB>
+__global__ void __launch_bounds__(256)
+symb_rowgemv_kernel(const RowGemvParams p) {
+    __shared__ float red[3][SKINNY_ROWS][RB * 16 + 4];   // partial sums of wavefronts 1..3; red[0] then holds the totals
+    __shared__ int srow[RB * 16];                        // segment of each row
+    static_assert(SKINNY_BLKS == 2, "a workgroup owns 32 columns");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int trow = lane & 15, kq = lane >> 4;
+    const int n0 = blockIdx.x * SKINNY_ROWS;
+    if (tid < RB * 16) {
+        int s = 0;
+        if (tid < p.T) while (s + 1 < p.S && tid >= p.off[s + 1]) ++s;
+        srow[tid] = s;
+    }
+    // columns past N are clamped onto the last one; their results are never stored
+    const bf16* lrow[SKINNY_BLKS];
+#pragma unroll
+    for (int b = 0; b < SKINNY_BLKS; ++b) lrow[b] = p.W + (size_t)min(n0 + b * 16 + trow, p.N - 1) * p.K + kq * 8;
+    const bf16* rrow[RB];
+    bool r_ok[RB];
+#pragma unroll
+    for (int j = 0; j < RB; ++j) {
+        r_ok[j] = (j * 16 + trow) < p.T;
+        rrow[j] = p.X + (size_t)(r_ok[j] ? (j * 16 + trow) : 0) * p.K + kq * 8;
+    }
+    floatx4 acc[SKINNY_BLKS][RB];
+#pragma unroll
+    for (int b = 0; b < SKINNY_BLKS; ++b)
+#pragma unroll
+        for (int j = 0; j < RB; ++j) acc[b][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    skinny_dot<RB>(lrow, rrow, r_ok, RB, p.K, wave, kq, acc);
+    // lane holds dot(W row n0 + b*16 + trow, X row j*16 + 4*kq + q) over its wavefront's share of K
+    if (wave > 0) {
+#pragma unroll
+        for (int b = 0; b < SKINNY_BLKS; ++b)
+#pragma unroll
+            for (int j = 0; j < RB; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) red[wave - 1][b * 16 + trow][j * 16 + kq * 4 + q] = acc[b][j][q];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int b = 0; b < SKINNY_BLKS; ++b)
+#pragma unroll
+            for (int j = 0; j < RB; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int c = b * 16 + trow, t = j * 16 + kq * 4 + q;
+                    red[0][c][t] = acc[b][j][q] + red[0][c][t] + red[1][c][t] + red[2][c][t];
+                }
+    }
+    __syncthreads();
+    // every thread finishes (row, column) pairs: column fastest, so a row's 32 outputs are one 64-byte store run
+    for (int e = tid; e < p.T * SKINNY_ROWS; e += 256) {
+        const int t = e / SKINNY_ROWS, c = e % SKINNY_ROWS, n = n0 + c;
+        if (n >= p.N) continue;
+        float v = red[0][c][t];
+        if (p.bias) v += bf16_bits_to_f32(reinterpret_cast<const unsigned short*>(p.bias)[n]);
+        const SegDesc sd = p.seg[srow[t]];
+        if (sd.kind == KIND_LORA) {
+            const unsigned short* hrow = reinterpret_cast<const unsigned short*>(p.Hs) + (size_t)t * p.hs_pitch;
+            const unsigned short* brow = reinterpret_cast<const unsigned short*>(sd.B) + (size_t)n * sd.rank;
+            float u = 0.f;
+            for (int q = 0; q < sd.rank; ++q)
+                u += (bf16_bits_to_f32(hrow[q]) + bf16_bits_to_f32(hrow[sd.rpad + q])) * bf16_bits_to_f32(brow[q]);
+            v += u;
+        } else if (sd.kind == KIND_IA3) {
+            v *= bf16_bits_to_f32(reinterpret_cast<const unsigned short*>(sd.A)[n]);
+        }
+        reinterpret_cast<unsigned short*>(p.Y)[(size_t)t * p.N + n] = (unsigned short)(pack2_bf16(v, 0.f) & 0xffffu);
     }
 }
 

@@ -655,6 +655,20 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
         }
         if ((st = launch_skinny(h, sp, (int)chunks.size(), bi.max_rpad, s)) != SYMB_OK) return st;
     }
+    // A handful of rows (decode steps): stream W once with one workgroup per 32 output columns
+    // instead of a tiled GEMM that would launch only a few dozen workgroups.
+    static const bool small_path = [] { const char* e = getenv("SYMB_SMALL_T"); return !e || atoi(e) != 0; }();
+    if (small_path && bi.T <= 128 && !conv1d && !seg_io && !Ybase && nd.empty() && bi.n_ia3in == 0) {
+        RowGemvParams rp{(const bf16*)W, (const bf16*)X, (bf16*)Y, (const bf16*)bias, b->d_in, b->d_out, bi.T, bi.S,
+                         (const int32_t*)(dev + o_off), (const SegDesc*)(dev + o_seg), Hs, 2 * bi.max_rpad};
+        const dim3 grid((b->d_out + SKINNY_ROWS - 1) / SKINNY_ROWS);
+        if (bi.T <= 16) hipLaunchKernelGGL(symb_rowgemv_kernel<1>, grid, dim3(256), 0, s, rp);
+        else if (bi.T <= 32) hipLaunchKernelGGL(symb_rowgemv_kernel<2>, grid, dim3(256), 0, s, rp);
+        else if (bi.T <= 64) hipLaunchKernelGGL(symb_rowgemv_kernel<4>, grid, dim3(256), 0, s, rp);
+        else hipLaunchKernelGGL(symb_rowgemv_kernel<8>, grid, dim3(256), 0, s, rp);
+        SYMB_HIP(h, hipGetLastError());
+        return seal_slot(h, s);
+    }
     GemmParams gp{};
     gp.Aop = x_op;
     if (seg_io) {

@@ -513,3 +513,20 @@ def test_large_tile_kernel_with_one_to_five_k_stages(d_in):
     dX = gh.backward_input(q["off"], q["ads"], q["dY"], q["W"])
     assert_close(gh.bf16_to_f64(dX), oracle.backward_input(q["off"], oracle_ads(q["ads"]), q["dY"], q["W"]),
                  f"dX d_out={d_in}", out_bf16=True)
+
+
+@pytest.mark.parametrize("lens", [[1], [16], [9, 0, 8], [1, 1, 20, 1, 1, 24], [30, 1, 40, 29], [1] * 48, [50, 78]])
+def test_forward_of_a_handful_of_rows(lens):
+    """Batches of at most 128 rows (decode steps) take a kernel of their own that streams W once:
+    1, 16, 17, 48, 100 and 128 rows; K with a remainder, d_out not a multiple of 32; every adapter
+    kind, ranks 1..128, bias."""
+    kinds = [L, I, N, L, L, I]
+    p = make_problem(90 + len(lens), 200, 392, lens, kinds, [1, 128, 24, 8, 100])
+    assert p["T"] <= 128
+    Y, _ = gh.forward(p["off"], p["ads"], p["X"], p["W"], p["bias"], want_base=False)
+    _, Yr = oracle.forward(p["off"], oracle_ads(p["ads"]), p["X"], p["W"], p["bias"])
+    assert_close(gh.bf16_to_f64(Y), Yr, f"small-batch Y lens={lens}", out_bf16=True)
+    q = make_problem(190 + len(lens), 4096, 4096, lens, [L], [16], bias=False)          # a decode batch on a real layer width
+    Y, _ = gh.forward(q["off"], q["ads"], q["X"], q["W"], None, want_base=False)
+    _, Yr = oracle.forward(q["off"], oracle_ads(q["ads"]), q["X"], q["W"], None)
+    assert_close(gh.bf16_to_f64(Y), Yr, f"decode batch Y lens={lens}", out_bf16=True)
