@@ -33,6 +33,31 @@ __global__ void __launch_bounds__(512) mfma_rand(const bf16x8* __restrict__ src,
   if (threadIdx.x == 0) { clk[blockIdx.x * 2] = c1 - c0; clk[blockIdx.x * 2 + 1] = r1 - r0; }
 }
 
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+// the same flops through v_mfma_f32_16x16x32_bf16: 32 independent 16x16 accumulators per wavefront
+__global__ void __launch_bounds__(512) mfma_rand16(const bf16x8* __restrict__ src, float* out, int iters, unsigned long long* clk) {
+  unsigned long long c0 = __builtin_readcyclecounter(), r0 = __builtin_amdgcn_s_memrealtime();
+  floatx4 acc[32];
+  for (int i = 0; i < 32; ++i) for (int r = 0; r < 4; ++r) acc[i][r] = 0.f;
+  bf16x8 a[8], b[4];
+  for (int i = 0; i < 8; ++i) a[i] = src[(blockIdx.x * 6 + (i % 4)) * 512 + (threadIdx.x + 37 * (i / 4)) % 512];
+  for (int i = 0; i < 4; ++i) b[i] = src[(blockIdx.x * 6 + 4 + (i % 2)) * 512 + (threadIdx.x + 91 * (i / 2)) % 512];
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i * 4 + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[j], a[i], acc[i * 4 + j], 0, 0, 0);
+    bf16x8 t = a[0];
+#pragma unroll
+    for (int i = 0; i < 7; ++i) a[i] = a[i + 1];
+    a[7] = t;
+  }
+  float s = 0; for (int i = 0; i < 32; ++i) for (int r = 0; r < 4; ++r) s += acc[i][r];
+  unsigned long long c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
+  out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+  if (threadIdx.x == 0) { clk[blockIdx.x * 2] = c1 - c0; clk[blockIdx.x * 2 + 1] = r1 - r0; }
+}
+
 int main(int argc, char** argv) {
   const bool constant = argc > 1 && !strcmp(argv[1], "--constant");   // all operands 1.0: few toggling bits
   const size_t n = 256 * 6 * 512 * 8;
@@ -49,6 +74,15 @@ int main(int argc, char** argv) {
     CK(hipMemcpy(hc, clk, 4096, hipMemcpyDeviceToHost));
     double cyc = 0, rt = 0; for (int i = 0; i < 256; ++i) { cyc += (double)hc[2 * i]; rt += (double)hc[2 * i + 1]; }
     printf("v_mfma_f32_32x32x16_bf16, %s operands in registers, 256 workgroups x 8 wavefronts, %.1f ms: %.1f TFLOP/s (%.1f%% of the 2500 TFLOP/s nominal peak); cycle counter / 100 MHz real-time counter = %.0f MHz\n",
+           constant ? "constant" : "N(0,1)", ms, fl / ms / 1e9, fl / ms / 1e9 / 25.0, cyc / rt * 100.0);
+  }
+  // per iteration and wavefront: 32 x 16384 flops, the same as 16 of the 32x32x16 instructions
+  for (int iters : {100000, 400000}) {
+    CK(hipEventRecord(e0)); mfma_rand16<<<256, 512>>>((const bf16x8*)d, out, iters / 2, clk); CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
+    double fl = 256.0 * 8 * (iters / 2) * 32 * 16384.0;
+    CK(hipMemcpy(hc, clk, 4096, hipMemcpyDeviceToHost));
+    double cyc = 0, rt = 0; for (int i = 0; i < 256; ++i) { cyc += (double)hc[2 * i]; rt += (double)hc[2 * i + 1]; }
+    printf("v_mfma_f32_16x16x32_bf16, %s operands in registers, 256 workgroups x 8 wavefronts, %.1f ms: %.1f TFLOP/s (%.1f%% of the 2500 TFLOP/s nominal peak); cycle counter / 100 MHz real-time counter = %.0f MHz\n",
            constant ? "constant" : "N(0,1)", ms, fl / ms / 1e9, fl / ms / 1e9 / 25.0, cyc / rt * 100.0);
   }
   return 0;
