@@ -1,0 +1,383 @@
+// The 256x256-tile base GEMM on v_mfma_f32_16x16x32_bf16 (4 wavefronts, each 128x128 of C).
+//
+// Computes what symb_gemm_kernel computes (gemm_kernel.hpp: the frozen weight's product with the
+// LoRA term of each row's segment fused in as extra k-steps, bias / IA3 scale / noise effect in
+// the epilogue), with the same GemmParams, tile walk, LDS ring and 64-k stages.  What differs is
+// the matrix instruction: with Gaussian operands the power-limited chip sustains about 12 % more
+// flops on the 16x16x32 form than on the 32x32x16 form.
+//
+// A wavefront's 128x128 of C is 8x8 blocks of 16x16, 4 registers each: all 256 accumulation
+// registers.  They are not C++ objects: every piece of code that touches one is an assembly
+// template that names a0..a255 literally (gemm16_asm.hpp; block (i, j) is a[4(8i+j) .. +3]), and
+// the compiler-generated code between the templates must not use accumulation registers for
+// anything (a CPU test inspects the generated assembly for that).  The MFMA is issued as (weight
+// fragment, activation fragment): a lane ends up with C[16i + l%16][16j + 4(l/16) + 0..3].
+#pragma once
+#include <type_traits>
+
+#include "gemm16_asm.hpp"
+#include "gemm_kernel.hpp"
+
+namespace symb {
+
+struct Gemm16Tile {
+    static constexpr int BM = 256, BN = 256, NT = 256, BK = 64;
+    static constexpr int UNIT = 32768;                   // one operand's 64-k stage
+    static constexpr int C_PITCH = BN * 2 + 16, C_BYTES = BM * C_PITCH;
+    static constexpr int SMEM = 5 * UNIT;                // three A units, two B units
+    static_assert(C_BYTES <= SMEM, "the staged output tile must fit the ring");
+};
+
+// N-contiguous weight unit: [64 k][256 n] bf16, 512 B per k-row, 16-byte chunk nc of row k stored
+// at nc ^ swz.  The transposing read of one 16-lane group fetches 4 k-rows x 32 B: the (k & 3)
+// term lays those side by side (128 B), the (k >> 3) term moves the next group to the other half
+// of the banks.
+__device__ __forceinline__ int swz_nmajor16(int k) { return ((k & 3) << 1) ^ (((k >> 3) & 1) << 3); }
+__device__ __forceinline__ int lds_off_nmajor16(int k, int nc) { return k * 512 + ((nc ^ swz_nmajor16(k)) << 4); }
+
+template <int I0, int I1, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I0 < I1) {
+        f(std::integral_constant<int, I0>{});
+        static_for<I0 + 1, I1>(f);
+    }
+}
+
+// The four accumulators of block R / 4 of this lane.
+template <int R>
+__device__ __forceinline__ void acc16_read4(float& v0, float& v1, float& v2, float& v3) {
+    asm volatile("v_accvgpr_read_b32 %0, a[%4]\n\tv_accvgpr_read_b32 %1, a[%5]\n\t"
+                 "v_accvgpr_read_b32 %2, a[%6]\n\tv_accvgpr_read_b32 %3, a[%7]"
+                 : "=v"(v0), "=v"(v1), "=v"(v2), "=v"(v3)
+                 : "n"(R), "n"(R + 1), "n"(R + 2), "n"(R + 3));
+}
+
+// PLAIN: no bias, no IA3 scale, no noise effect, no pre-adapter output (checked by the host).
+template <bool NN, bool PLAIN>
+__global__ void __launch_bounds__(256)
+symb_gemm16_kernel(const GemmParams p) {
+    using TT = Gemm16Tile;
+    constexpr int BM = TT::BM, BN = TT::BN, NT = TT::NT, BK = TT::BK, CP = TT::C_PITCH;
+    constexpr int CA = BM * 8 / NT, CB = BN * 8 / NT;      // 16-byte chunks per thread of a register-staged tile
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* const sA = smem;                        // register-staged tiles (K remainder, LoRA term)
+    unsigned char* const sB = smem + TT::UNIT;
+
+    // ---- tile of this workgroup (same walk as symb_gemm_kernel)
+    const int total = p.num_m_tiles * p.num_n_tiles;
+    int lin;
+    if (p.walk == 1) {
+        const int k = blockIdx.x >> 3;
+        lin = (((k >> 5) << 3) + (blockIdx.x & 7)) * 32 + (k & 31);
+        if (lin >= total) return;
+    } else {
+        const int per_xcd = (total + 7) >> 3;
+        lin = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+        if (lin >= total || (int)(blockIdx.x >> 3) >= per_xcd) return;
+    }
+    const int width = p.group_m * p.num_n_tiles;
+    const int first_m = (lin / width) * p.group_m;
+    const int gsz = min(p.num_m_tiles - first_m, p.group_m);
+    const int tm = first_m + (lin % width) % gsz;
+    const int tn = (lin % width) / gsz;
+    const int m0 = tm * BM, n0 = tn * BN;
+#ifdef SYMB_GEMM_TRACE
+    if (p.trace && threadIdx.x == 0) { p.trace[(size_t)lin * 16 + 0] = __builtin_amdgcn_s_memrealtime(); p.trace[(size_t)lin * 16 + 5] = __builtin_readcyclecounter(); }
+#endif
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 128;
+    const int l15 = lane & 15, lg = lane >> 4;
+    const int seg_lo = p.tile_seg_lo[tm], seg_hi = p.tile_seg_hi[tm];
+    auto a_row = [&](int m) __attribute__((always_inline)) -> const bf16* {
+        if (!p.a_seg) return p.Aop + (size_t)m * p.K;
+        const int s = seg_of_row(p.off, seg_lo, seg_hi, m);
+        return p.a_seg[s] + (size_t)(m - p.off[s]) * p.K;
+    };
+    const bf16* const a_tile = p.a_seg ? p.a_base : p.Aop + (size_t)m0 * p.K;
+    const bf16* const b_tile = NN ? (p.Bop + n0) : (p.Bop + (size_t)n0 * p.K);
+    const unsigned lds0 = (unsigned)(size_t)smem;          // LDS byte address of the dynamic segment
+
+    asm volatile(SYMB_GEMM16_ZERO ::: SYMB_GEMM16_ACLOBBERS);
+
+    // ---- register-staged 64-k tile (K remainder, LoRA term).  Chunk i of a thread sits 32 rows
+    // (K-contiguous tiles) or 8 k-rows (N-contiguous weight tile) below chunk 0.
+    constexpr int RSTEP = NT / 8, KSTEP = NT / (BN / 8);
+    const int lrow = tid >> 3, lkc = (tid & 7) * 8;
+    const int nn_k = tid / (BN / 8), nn_nc = tid % (BN / 8);
+    const int a_lds0 = lds_off_kmajor(lrow, tid & 7);
+    const int b_lds0 = NN ? lds_off_nmajor16(nn_k, nn_nc) : a_lds0;
+    uint4 ra[CA], rb[CB];
+    auto lds_store_a = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < CA; ++i) *reinterpret_cast<uint4*>(sA + a_lds0 + i * RSTEP * 128) = ra[i];
+    };
+    auto lds_store_b = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+            if constexpr (!NN) *reinterpret_cast<uint4*>(sB + b_lds0 + i * RSTEP * 128) = rb[i];
+            else *reinterpret_cast<uint4*>(sB + ((b_lds0 + i * KSTEP * (BN * 2)) ^ ((i & 1) << 7))) = rb[i];   // k + 8 flips the swizzle's high term
+        }
+    };
+    auto gload_tail = [&](int k0) __attribute__((always_inline)) {
+        const bool kok = (k0 + lkc) < p.K;
+#pragma unroll
+        for (int i = 0; i < CA; ++i)
+            ra[i] = ld_global_16(a_row(min(m0 + lrow + i * RSTEP, p.M - 1)) + k0 + lkc, kok);
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+            if constexpr (!NN)
+                rb[i] = ld_global_16(p.Bop + (size_t)min(n0 + lrow + i * RSTEP, p.N - 1) * p.K + k0 + lkc, kok);
+            else {
+                const int kr = k0 + nn_k + i * KSTEP;
+                rb[i] = ld_global_16(p.Bop + (size_t)min(kr, p.K - 1) * p.N + n0 + min(nn_nc * 8, p.N - 8 - n0), kr < p.K);
+            }
+        }
+    };
+    // Lane byte offsets of the MFMA fragments of 32-k step ks inside an operand's 64-k tile: a lane
+    // holds row l%16, k = 32 ks + 8 (l/16) .. +7.  For the N-contiguous weight one address per
+    // 16-column block j (the transposing read: lane jj of a 16-lane group fetches k-row jj/4, columns
+    // 4 (jj%4) .. +3, and receives column jj, 4 k-rows; a second read 4 k-rows down completes 8 k).
+    auto frag_a = [&](int ks) __attribute__((always_inline)) { return (unsigned)lds_off_kmajor(wm0 + l15, ks * 4 + lg); };
+    auto frag_b_nt = [&](int ks) __attribute__((always_inline)) { return (unsigned)lds_off_kmajor(wn0 + l15, ks * 4 + lg); };
+    auto frag_b_nn = [&](int j) __attribute__((always_inline)) {
+        const int k = lg * 8 + (l15 >> 2), n = wn0 + j * 16 + ((l15 & 3) << 2);
+        return (unsigned)(lds_off_nmajor16(k, n >> 3) + ((n & 7) << 1));
+    };
+    // nks 32-wide k-steps over the register-staged tile
+    auto compute = [&](int nks) __attribute__((always_inline)) {
+        for (int ks = 0; ks < nks; ++ks) {
+            const unsigned va = lds0 + frag_a(ks);
+            if constexpr (!NN) {
+                const unsigned vb = lds0 + TT::UNIT + frag_b_nt(ks);
+                asm volatile(SYMB_GEMM16_KSTEP32_NT : : "v"(va), "v"(vb)
+                             : "memory", SYMB_GEMM16_VCLOBBERS, SYMB_GEMM16_ACLOBBERS);
+            } else {
+                unsigned vb[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) vb[j] = lds0 + TT::UNIT + frag_b_nn(j) + ks * 32 * (BN * 2);
+                asm volatile(SYMB_GEMM16_KSTEP32_NN : : "v"(va), "v"(vb[0]), "v"(vb[1]), "v"(vb[2]), "v"(vb[3]),
+                             "v"(vb[4]), "v"(vb[5]), "v"(vb[6]), "v"(vb[7])
+                             : "memory", SYMB_GEMM16_VCLOBBERS, SYMB_GEMM16_ACLOBBERS);
+            }
+        }
+    };
+
+    // ---- main loop over the full 64-k stages (gemm16_asm.hpp)
+    const int KF = p.K / 64;
+    if (KF > 0) {
+        unsigned vA[2], vB[8];
+        vA[0] = lds0 + frag_a(0);
+        vA[1] = lds0 + frag_a(1);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) vB[j] = lds0 + (NN ? frag_b_nn(j) : frag_b_nt(j & 1));
+        // Global byte offsets of this lane's eight loads per operand and stage.  One load instruction
+        // fills 1 KiB of consecutive LDS: 8 rows of a K-contiguous unit or 2 k-rows of the
+        // N-contiguous unit; the lane -> chunk map is the inverse of the LDS swizzle.  Rows / columns
+        // outside the problem are clamped onto the last valid one and never stored.
+        unsigned ab[8], bb[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int row = (wave * 8 + j) * 8 + (lane >> 3), kc = (lane & 7) ^ swz_row(row);
+            ab[j] = ((unsigned)(a_row(min(m0 + row, p.M - 1)) - a_tile) + kc * 8) * 2u;
+            if constexpr (!NN) {
+                bb[j] = ((unsigned)(min(n0 + row, p.N - 1) - n0) * (unsigned)p.K + kc * 8) * 2u;
+            } else {
+                const int krow = (wave * 8 + j) * 2 + (lane >> 5), nc = (lane & 31) ^ swz_nmajor16(krow);
+                bb[j] = ((unsigned)krow * (unsigned)p.N + (unsigned)min(nc * 8, p.N - 8 - n0)) * 2u;
+            }
+        }
+        const unsigned long long ga = (unsigned long long)a_tile, gb = (unsigned long long)b_tile;
+        const unsigned stride_b = NN ? 128u * (unsigned)p.N : 128u;
+        const unsigned swa = (unsigned)__builtin_amdgcn_readfirstlane((int)lds0 + wave * 8192);
+#define SYMB_GEMM16_LOOP_OPERANDS                                                                                   \
+    :                                                                                                              \
+    : "v"(vA[0]), "v"(vA[1]), "v"(vB[0]), "v"(vB[1]), "v"(vB[2]), "v"(vB[3]), "v"(vB[4]), "v"(vB[5]), "v"(vB[6]),  \
+      "v"(vB[7]), "v"(ab[0]), "v"(ab[1]), "v"(ab[2]), "v"(ab[3]), "v"(ab[4]), "v"(ab[5]), "v"(ab[6]), "v"(ab[7]),  \
+      "v"(bb[0]), "v"(bb[1]), "v"(bb[2]), "v"(bb[3]), "v"(bb[4]), "v"(bb[5]), "v"(bb[6]), "v"(bb[7]),              \
+      "s"(ga), "s"(gb), "s"(stride_b), "s"(KF), "s"(swa)                                                           \
+    : "memory", "scc", SYMB_GEMM16_SCLOBBERS, SYMB_GEMM16_VCLOBBERS, SYMB_GEMM16_ACLOBBERS
+#ifdef SYMB_GEMM_TRACE
+        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 1] = __builtin_amdgcn_s_memrealtime();
+#endif
+        if constexpr (NN) asm volatile(SYMB_GEMM16_LOOP_NN SYMB_GEMM16_LOOP_OPERANDS);
+#ifdef SYMB_GEMM_PROBE
+        else if (p.probe == 1) asm volatile(SYMB_GEMM16_LOOP_NT_NOLOAD SYMB_GEMM16_LOOP_OPERANDS);
+#endif
+        else asm volatile(SYMB_GEMM16_LOOP_NT SYMB_GEMM16_LOOP_OPERANDS);
+#undef SYMB_GEMM16_LOOP_OPERANDS
+        __builtin_amdgcn_s_barrier();                      // everything landed and read before LDS is reused
+#ifdef SYMB_GEMM_TRACE
+        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 2] = __builtin_amdgcn_s_memrealtime();
+#endif
+    }
+    if (KF * 64 < p.K) {
+        gload_tail(KF * 64);
+        lds_store_a();
+        lds_store_b();
+        __syncthreads();
+        compute((p.K - KF * 64 + 31) >> 5);
+        __syncthreads();
+    }
+
+    // ---- output staging: the bf16 tile goes through LDS and leaves as whole 512-byte rows
+    const unsigned c_lane = (unsigned)((wm0 + l15) * CP + (wn0 + lg * 4) * 2);   // this lane's C[.][.] of block (0, 0)
+    auto stage_out = [&](bf16* __restrict__ dst, bool scale_ia3) __attribute__((always_inline)) {
+        if (PLAIN || (!p.bias && !scale_ia3 && !p.neff)) {
+            asm volatile(SYMB_GEMM16_STAGE_OUT : : "v"(lds0 + c_lane) : "memory", SYMB_GEMM16_VCLOBBERS);
+        } else if constexpr (!PLAIN) {
+            // bias of this lane's 8 column quads, once; IA3 vector and noise effect of each row's own
+            // segment per row block
+            const uint2 zero2 = make_uint2(0u, 0u);
+            const int nq0 = n0 + wn0 + lg * 4;
+            uint2 bv[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int n = nq0 + j * 16;
+                bv[j] = (p.bias && n < p.N) ? *reinterpret_cast<const uint2*>(p.bias + n) : zero2;
+            }
+            static_for<0, 8>([&](auto I) __attribute__((always_inline)) {
+                constexpr int i = decltype(I)::value;
+                const int m = m0 + wm0 + i * 16 + l15;
+                const bf16* lrow = nullptr;
+                const bf16* nrow = nullptr;
+                if ((scale_ia3 || p.neff) && m < p.M) {
+                    const int s = seg_of_row(p.off, seg_lo, seg_hi, m);
+                    if (scale_ia3 && p.seg[s].kind == p.epi_ia3) lrow = p.seg[s].A;
+                    if (p.neff) {
+                        const NoiseDesc nd = p.neff[s];
+                        if (nd.ptr) nrow = nd.ptr + (size_t)(nd.rows == 1 ? 0 : m - p.off[s]) * p.N;
+                    }
+                }
+                uint2 lv[8], nv[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int n = nq0 + j * 16;
+                    nv[j] = (nrow && n < p.N) ? *reinterpret_cast<const uint2*>(nrow + n) : zero2;
+                    lv[j] = (lrow && n < p.N) ? *reinterpret_cast<const uint2*>(lrow + n) : make_uint2(0x3f803f80u, 0x3f803f80u);
+                }
+                static_for<0, 8>([&](auto J) __attribute__((always_inline)) {
+                    constexpr int j = decltype(J)::value;
+                    float v0, v1, v2, v3;
+                    acc16_read4<4 * (8 * i + j)>(v0, v1, v2, v3);
+                    if (p.bias) {
+                        v0 += bf16_bits_to_f32((unsigned short)(bv[j].x & 0xffffu));
+                        v1 += bf16_bits_to_f32((unsigned short)(bv[j].x >> 16));
+                        v2 += bf16_bits_to_f32((unsigned short)(bv[j].y & 0xffffu));
+                        v3 += bf16_bits_to_f32((unsigned short)(bv[j].y >> 16));
+                    }
+                    if (scale_ia3) {           // rows of other kinds carry ones (exact)
+                        v0 *= bf16_bits_to_f32((unsigned short)(lv[j].x & 0xffffu));
+                        v1 *= bf16_bits_to_f32((unsigned short)(lv[j].x >> 16));
+                        v2 *= bf16_bits_to_f32((unsigned short)(lv[j].y & 0xffffu));
+                        v3 *= bf16_bits_to_f32((unsigned short)(lv[j].y >> 16));
+                    }
+                    if (p.neff) {              // y = y_noisy - n_eff, still in fp32
+                        v0 -= bf16_bits_to_f32((unsigned short)(nv[j].x & 0xffffu));
+                        v1 -= bf16_bits_to_f32((unsigned short)(nv[j].x >> 16));
+                        v2 -= bf16_bits_to_f32((unsigned short)(nv[j].y & 0xffffu));
+                        v3 -= bf16_bits_to_f32((unsigned short)(nv[j].y >> 16));
+                    }
+                    uint2 o;
+                    o.x = pack2_bf16(v0, v1);
+                    o.y = pack2_bf16(v2, v3);
+                    *reinterpret_cast<uint2*>(smem + c_lane + i * 16 * CP + j * 32) = o;
+                });
+            });
+        }
+#ifdef SYMB_GEMM_TRACE
+        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 8] = __builtin_amdgcn_s_memrealtime();
+#endif
+        __syncthreads();
+#ifdef SYMB_GEMM_TRACE
+        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 9] = __builtin_amdgcn_s_memrealtime();
+#endif
+        const bool to_seg = p.c_seg != nullptr && dst == p.C;   // the final output goes to the segments' own buffers
+        const int col = (lane & 31) * 8;
+#pragma unroll 4
+        for (int r = wave * 2 + (lane >> 5); r < BM; r += 8) {
+            const int m = m0 + r, n = n0 + col;
+            if (m < p.M && n < p.N) {
+                bf16* rowp = dst + (size_t)m * p.N;
+                if (to_seg) {
+                    const int s = seg_of_row(p.off, seg_lo, seg_hi, m);
+                    rowp = p.c_seg[s] + (size_t)(m - p.off[s]) * p.N;
+                }
+                *reinterpret_cast<uint4*>(rowp + n) = *reinterpret_cast<const uint4*>(smem + r * CP + col * 2);
+            }
+        }
+    };
+
+    // ---- optional store of the pre-adapter output (accumulator + bias, before the LoRA term)
+    if constexpr (!PLAIN) {
+        if (p.Cbase) {
+            stage_out(p.Cbase, false);
+            __syncthreads();                         // LDS is reused by the LoRA tiles below
+        }
+    }
+
+    // ---- LoRA term: extra k-steps per LoRA segment that meets this row tile
+    if (p.ext) {
+        for (int s = seg_lo; s <= seg_hi; ++s) {
+            const SegDesc sd = p.seg[s];
+            const int r_lo = max(p.off[s], m0), r_hi = min(min(p.off[s + 1], m0 + BM), p.M);
+            if (sd.kind != KIND_LORA || r_hi <= r_lo) continue;      // uniform over the workgroup
+            const int kext = 2 * sd.rpad;                           // value half, then residual half (a multiple of 32)
+            for (int kc0 = 0; kc0 < kext; kc0 += BK) {
+                // activation-side tile: rows of this segment only, others zero
+#pragma unroll
+                for (int i = 0; i < CA; ++i) {
+                    const int c = tid + i * NT, row = c >> 3, kc = c & 7, m = m0 + row;
+                    const bool ok = m >= r_lo && m < r_hi && (kc0 + kc * 8) < kext;
+                    ra[i] = ld_global_16(p.ext + (size_t)(ok ? m : 0) * p.ext_pitch + kc0 + kc * 8, ok);
+                }
+                lds_store_a();
+                // adapter-side tile
+#pragma unroll
+                for (int i = 0; i < CB; ++i) {
+                    const int c = tid + i * NT;
+                    if constexpr (!NN) {       // B_i [N][rank], rank-contiguous
+                        const int row = c >> 3, kc = c & 7, n = n0 + row;
+                        const int pk = kc0 + kc * 8, pp = pk >= sd.rpad ? pk - sd.rpad : pk;   // both halves meet the same B_i
+                        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+                        if (n < p.N && pk < kext && pp < sd.rank) {
+                            const bf16* src = sd.B + (size_t)n * sd.rank + pp;
+                            if ((sd.rank & 7) == 0) {
+                                v = *reinterpret_cast<const uint4*>(src);
+                            } else {
+                                unsigned short e[8];
+#pragma unroll
+                                for (int q = 0; q < 8; ++q)
+                                    e[q] = (pp + q < sd.rank) ? reinterpret_cast<const unsigned short*>(src)[q] : (unsigned short)0;
+                                v.x = e[0] | ((unsigned)e[1] << 16); v.y = e[2] | ((unsigned)e[3] << 16);
+                                v.z = e[4] | ((unsigned)e[5] << 16); v.w = e[6] | ((unsigned)e[7] << 16);
+                            }
+                        }
+                        rb[i] = v;
+                    } else {                   // A_i [rank][N], N-contiguous
+                        const int krow = c / (BN / 8), nc = c % (BN / 8), n = n0 + nc * 8;
+                        const int pk = kc0 + krow, pp = pk >= sd.rpad ? pk - sd.rpad : pk;
+                        const bool ok = pk < kext && pp < sd.rank && n < p.N;
+                        rb[i] = ld_global_16(sd.A + (size_t)(ok ? pp : 0) * p.N + (ok ? n : 0), ok);
+                    }
+                }
+                lds_store_b();
+                __syncthreads();
+                compute(min(BK, kext - kc0) >> 5);
+                __syncthreads();
+            }
+        }
+    }
+
+#ifdef SYMB_GEMM_TRACE
+    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 4] = __builtin_amdgcn_s_memrealtime();
+#endif
+    // ---- final output: bias, IA3 scale, noise effect, one rounding, whole-row stores
+    stage_out(p.C, p.epi_ia3 != 0);
+#ifdef SYMB_GEMM_TRACE
+    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 7] = __builtin_amdgcn_s_memrealtime();
+    __builtin_amdgcn_s_waitcnt(0);
+    if (p.trace && threadIdx.x == 0) { p.trace[(size_t)lin * 16 + 3] = __builtin_amdgcn_s_memrealtime(); p.trace[(size_t)lin * 16 + 6] = __builtin_readcyclecounter(); }
+#endif
+}
+
+}  // namespace symb

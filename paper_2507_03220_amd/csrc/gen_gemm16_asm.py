@@ -1,0 +1,300 @@
+#!/usr/bin/env python3
+"""Writes gemm16_asm.hpp: the assembly of the 256x256 base GEMM built on v_mfma_f32_16x16x32_bf16.
+
+Run `python gen_gemm16_asm.py` after changing the schedule; the output is committed, the build
+does not run this script.
+
+Why this instruction: the chip is power-limited, and with N(0,1) operands the 16x16x32 form
+sustains 12 % more flops than the 32x32x16 form (it touches each accumulator once per 32 k
+instead of once per 16 k).  Why everything that touches an accumulator is assembly: a wavefront
+owns 128x128 of C as 8x8 blocks of 16x16, 4 registers each, i.e. all 256 accumulation registers,
+and the instruction writes 4-register blocks.  An inline-assembly operand cannot name part of a
+register tuple, and 64 four-register operands are more than the compiler copes with, so the
+accumulators are not C++ objects at all: block (i, j) lives in a[4(8i+j) : 4(8i+j)+3], every
+template names these registers literally, and the compiler-generated code in between never
+touches an accumulation register (a CPU test checks the generated assembly for that).
+
+Lane layout of the instruction, issued as (weight fragment, activation fragment): an operand
+lane l holds row l%16, k = 8(l/16) .. 8(l/16)+7 of its 16x32 fragment; the result lane holds
+C[m = 16i + l%16][n = 16j + 4(l/16) + e], e = 0..3: four consecutive columns of one row.
+
+Main loop, per 64-k stage P (ring of three A and two B units of 32 KiB in LDS, as in the
+32x32x16 kernel): two 32-k steps of 64 MFMAs each, fragment sets F0/F1 alternating.
+  step 0: MFMAs on F0 while the step-1 fragments of stage P are read into F1; the eight loads
+          of A(P+2) go out, one per eight MFMAs; then wait for this wavefront's loads of stage
+          P+1, barrier (stage P+1 complete for everybody, both units of stage P free);
+  step 1: MFMAs on F1 while the step-0 fragments of stage P+1 are read into F0; the eight loads
+          of B(P+2) go out during the first 16 MFMAs.
+The last two stages run copies of the body without loads.
+"""
+import os
+
+F = {0: 128, 1: 192}          # first VGPR of fragment set 0 / 1 (A: 8 x 4 regs, then B: 8 x 4 regs)
+VT = 116                      # address temporaries v116..v127
+S_GA, S_GB = 80, 82
+S_CNT, S_ACUR, S_ANXT, S_ANN, S_BCUR, S_BNXT, S_T0, S_T1 = range(84, 92)
+LOAD_MOD = (" " + os.environ["SYMB_GEN_LOAD_MOD"]) if os.environ.get("SYMB_GEN_LOAD_MOD") else ""   # tuning: cache policy bits
+UNIT = 32768                  # one operand's 64-k stage
+A_BASES = (0, UNIT, 2 * UNIT)
+B_BASES = (3 * UNIT, 4 * UNIT)
+C_PITCH = 528                 # bytes per row of the staged bf16 output tile (256 * 2 + 16)
+
+# operand numbers of the main loop
+VA = (0, 1)                   # A fragment lane offsets, 32-k step 0 / 1
+VB = tuple(range(2, 10))      # NT: B lane offsets for step 0 / 1 in VB[0], VB[1]; NN: one per 16-column block
+AV = tuple(range(10, 18))     # global byte offsets of this lane's 8 A loads
+BV = tuple(range(18, 26))     # global byte offsets of this lane's 8 B loads
+GA, GB, STRIDE_B, KF, SWA = 26, 27, 28, 29, 30
+
+# The compiler does not look inside an assembly statement: whatever it places right after one
+# must not meet a matrix instruction that is still writing its result.
+MFMA_DRAIN = ["s_nop 15", "s_nop 7"]
+BLOCKS = [(i, j) for i in range(8) for j in range(8)]
+
+
+def acc(i, j):
+    b = 4 * (8 * i + j)
+    return f"a[{b}:{b + 3}]"
+
+
+def fa(s, i):
+    b = F[s] + 4 * i
+    return f"v[{b}:{b + 3}]"
+
+
+def fb(s, j):
+    b = F[s] + 32 + 4 * j
+    return f"v[{b}:{b + 3}]"
+
+
+def fb_half(s, j, h):
+    b = F[s] + 32 + 4 * j + 2 * h
+    return f"v[{b}:{b + 1}]"
+
+
+def mfma(s, i, j):
+    return f"v_mfma_f32_16x16x32_bf16 {acc(i, j)}, {fb(s, j)}, {fa(s, i)}, {acc(i, j)}"
+
+
+def frag_reads(nn, dst, sa, sb, ks, va=None, vb=None):
+    """The LDS reads that fill fragment set `dst` with 32-k step `ks` of the stage whose A / B units
+    start at SGPR `sa` / `sb` (or, with va / vb given, at those address operands).  A list of slots:
+    each read, preceded by the address add it needs."""
+    slots = []
+    if va is None:
+        a_addr = f"v{VT}"
+        a_pre = [f"v_add_u32 v{VT}, s{sa}, %{VA[ks]}"]
+    else:
+        a_addr, a_pre = va, []
+    for i in range(8):
+        slots.append((a_pre if i == 0 else []) + [f"ds_read_b128 {fa(dst, i)}, {a_addr} offset:{2048 * i}"])
+    if not nn:
+        if vb is None:
+            b_addr = f"v{VT + 1}"
+            b_pre = [f"v_add_u32 v{VT + 1}, s{sb}, %{VB[ks]}"]
+        else:
+            b_addr, b_pre = vb[0], []
+        for j in range(8):
+            slots.append((b_pre if j == 0 else []) + [f"ds_read_b128 {fb(dst, j)}, {b_addr} offset:{2048 * j}"])
+    else:
+        for j in range(8):
+            if vb is None:
+                addr = f"v{VT + 1 + j}"
+                pre = [f"v_add_u32 {addr}, s{sb}, %{VB[j]}"]
+            else:
+                addr, pre = vb[j], []
+            for h in range(2):
+                slots.append((pre if h == 0 else []) +
+                             [f"ds_read_b64_tr_b16 {fb_half(dst, j, h)}, {addr} offset:{16384 * ks + 2048 * h}"])
+    return slots
+
+
+def unit_loads(sdst, which, js):
+    """Per load two slots: the LDS destination into m0, then the load itself (the instruction that
+    sits between them covers the wait state an m0 write needs).  s{T0} holds unit + wavefront base."""
+    V, G = (AV, S_GA) if which == "A" else (BV, S_GB)
+    return [f"s_add_u32 s{S_T0}, s{sdst}, %{SWA}"], \
+           [([f"s_add_u32 m0, s{S_T0}, {1024 * j}"], [f"global_load_lds_dwordx4 %{V[j]}, s[{G}:{G + 1}]" + LOAD_MOD]) for j in js]
+
+
+def unit_loads_flat(sdst, which, js):
+    pre, pairs = unit_loads(sdst, which, js)
+    out = list(pre)
+    for a, b in pairs:
+        out += a + ["s_nop 0"] + b
+    return out
+
+
+def advance(which, cond=None):
+    G, step = (S_GA, "128") if which == "A" else (S_GB, f"%{STRIDE_B}")
+    if cond is None:
+        pre = [f"s_mov_b32 s{S_T1}, {step}"] if which == "B" else []
+        src = f"s{S_T1}" if which == "B" else step
+        return pre + [f"s_add_u32 s{G}, s{G}, {src}", f"s_addc_u32 s{G + 1}, s{G + 1}, 0"]
+    return [f"s_cmp_gt_u32 %{KF}, {cond}",
+            f"s_cselect_b32 s{S_T1}, {step}, 0",
+            f"s_add_u32 s{G}, s{G}, s{S_T1}", f"s_addc_u32 s{G + 1}, s{G + 1}, 0"]
+
+
+def weave(mf, reads, pairs, first, every):
+    """One MFMA, then at most two other instructions: reads go one per MFMA from the start; load
+    number j puts its m0 write after MFMA first + every*j and the load after the next MFMA."""
+    slots = [[] for _ in mf]
+    for k, r in enumerate(reads):
+        slots[k] += r
+    for j, (a, b) in enumerate(pairs):
+        slots[first + every * j] += a
+        slots[first + every * j + 1] += b
+    out = []
+    for m, s in zip(mf, slots):
+        assert len(s) <= 3
+        out.append(m)
+        out += s
+    return out
+
+
+def rotate():
+    return [f"s_mov_b32 s{S_T0}, s{S_ACUR}", f"s_mov_b32 s{S_ACUR}, s{S_ANXT}", f"s_mov_b32 s{S_ANXT}, s{S_ANN}",
+            f"s_mov_b32 s{S_ANN}, s{S_T0}",
+            f"s_mov_b32 s{S_T0}, s{S_BCUR}", f"s_mov_b32 s{S_BCUR}, s{S_BNXT}", f"s_mov_b32 s{S_BNXT}, s{S_T0}"]
+
+
+def body(nn, loads_on, last):
+    L = []
+    # step 0
+    reads = frag_reads(nn, 1, S_ACUR, S_BCUR, 1)
+    pre, pairs = unit_loads(S_ANN, "A", range(8)) if loads_on else ([], [])
+    L += pre
+    L += weave([mfma(0, i, j) for i, j in BLOCKS], reads, pairs, 2, 7)
+    if loads_on:
+        L += advance("A")
+    if last:
+        L += ["s_waitcnt lgkmcnt(0)"]
+    else:
+        L += [f"s_waitcnt vmcnt({8 if loads_on else 0}) lgkmcnt(0)", "s_barrier"]
+    # step 1
+    reads = [] if last else frag_reads(nn, 0, S_ANXT, S_BNXT, 0)
+    pre, pairs = unit_loads(S_BCUR, "B", range(8)) if loads_on else ([], [])
+    L += pre
+    L += weave([mfma(1, i, j) for i, j in BLOCKS], reads, pairs, 1, 4)
+    if loads_on:
+        L += advance("B")
+    if not last:
+        L += ["s_waitcnt lgkmcnt(0)"]
+    return L
+
+
+def build(nn, no_loads=False):
+    L = []
+    L += [f"s_mov_b64 s[{S_GA}:{S_GA + 1}], %{GA}", f"s_mov_b64 s[{S_GB}:{S_GB + 1}], %{GB}",
+          f"s_sub_u32 s{S_CNT}, %{KF}, 2",
+          f"s_mov_b32 s{S_ACUR}, {A_BASES[0]}", f"s_mov_b32 s{S_ANXT}, {A_BASES[1]}", f"s_mov_b32 s{S_ANN}, {A_BASES[2]}",
+          f"s_mov_b32 s{S_BCUR}, {B_BASES[0]}", f"s_mov_b32 s{S_BNXT}, {B_BASES[1]}"]
+    for n, (sa, sb) in enumerate(((S_ACUR, S_BCUR), (S_ANXT, S_BNXT))):
+        for which, sd in (("A", sa), ("B", sb)):
+            L += unit_loads_flat(sd, which, range(8))
+            L += advance(which, cond=1) if n == 0 else advance(which)
+    L += ["s_waitcnt vmcnt(16)", "s_barrier"]
+    for r in frag_reads(nn, 0, S_ACUR, S_BCUR, 0):
+        L += r
+    L += ["s_waitcnt lgkmcnt(0)"]
+    L += [f"s_cmp_lt_u32 %{KF}, 3", "s_cbranch_scc1 2f"]
+    L.append("1:")
+    L += body(nn, not no_loads, False)
+    L += rotate()
+    L += [f"s_sub_u32 s{S_CNT}, s{S_CNT}, 1", f"s_cmp_lg_u32 s{S_CNT}, 0", "s_cbranch_scc1 1b"]
+    L.append("2:")
+    L += [f"s_cmp_lt_u32 %{KF}, 2", "s_cbranch_scc1 3f"]
+    L += body(nn, False, False)
+    L += rotate()
+    L.append("3:")
+    L += body(nn, False, True)
+    L.append("s_waitcnt vmcnt(0)")
+    L += MFMA_DRAIN
+    return L
+
+
+def build_kstep32(nn):
+    """One 32-wide k-step on a register-staged 64-k tile (K remainder, LoRA term): read the sixteen
+    fragments, wait, 64 MFMAs.  Operands: %0 A fragment address, %1 (K-contiguous W) or %1-%8
+    (N-contiguous W, one per 16-column block) B addresses; the 32-k half is already in them."""
+    L = []
+    for r in frag_reads(nn, 0, None, None, 0, va="%0", vb=[f"%{1 + j}" for j in range(8)]):
+        L += r
+    L.append("s_waitcnt lgkmcnt(0)")
+    L += [mfma(0, i, j) for i, j in BLOCKS]
+    L += MFMA_DRAIN
+    return L
+
+
+def build_zero():
+    return [f"v_accvgpr_write_b32 a{n}, 0" for n in range(256)] + ["s_nop 3"]
+
+
+def build_stage_out():
+    """The whole 128x128 wavefront tile, rounded to bf16, into the LDS staging tile.  %0: LDS byte
+    address of this lane's (m = l%16, n = 4(l/16)) inside the wavefront's part of the tile."""
+    L = []
+    for n, (i, j) in enumerate(BLOCKS):
+        t = 128 + (n % 8) * 6
+        b = 4 * (8 * i + j)
+        for e in range(4):
+            L.append(f"v_accvgpr_read_b32 v{t + e}, a{b + e}")
+        L.append(f"v_cvt_pk_bf16_f32 v{t + 4}, v{t}, v{t + 1}")
+        L.append(f"v_cvt_pk_bf16_f32 v{t + 5}, v{t + 2}, v{t + 3}")
+        L.append(f"ds_write_b64 %0, v[{t + 4}:{t + 5}] offset:{i * 16 * C_PITCH + j * 32}")
+    L.append("s_waitcnt lgkmcnt(0)")
+    return L
+
+
+def emit(name, lines):
+    out = [f"#define {name} \\"]
+    for l in lines:
+        out.append(f'    "{l}\\n\\t" \\')
+    out.append('    ""')
+    return "\n".join(out)
+
+
+def main():
+    here = os.path.dirname(os.path.abspath(__file__))
+    vclob = ", ".join(f'"v{r}"' for r in range(VT, 256))
+    aclob = ", ".join(f'"a{r}"' for r in range(256))
+    sclob = ", ".join(f'"s{r}"' for r in range(80, 92))
+    text = f"""// GENERATED by gen_gemm16_asm.py -- do not edit by hand.
+// Assembly of the 256x256 / 4-wavefront base GEMM on v_mfma_f32_16x16x32_bf16 for gfx950.
+// The accumulators are not operands: block (i, j) of a wavefront's 8x8 blocks of 16x16 lives in
+// a[4(8i+j) : 4(8i+j)+3] in every template.
+// Main loop operands: %0,%1 A fragment lane offsets for 32-k step 0 / 1 inside an A unit; %2-%9 B
+// fragment lane offsets inside a B unit (K-contiguous W: step 0 / 1 in %2,%3; N-contiguous W: one per
+// 16-column block); %10-%17 / %18-%25 global byte offsets of this lane's eight A / eight B loads per
+// stage; %26,%27 global base of the A / B stage (64-bit SGPR); %28 byte stride of B between stages;
+// %29 number of 64-k stages (>= 1); %30 LDS byte address of the dynamic segment + this wavefront's
+// first load inside a unit (wave * 8192).  LDS: A units at 0/32/64 KiB, B units at 96/128 KiB.
+// Fixed registers: s80-s91, v{VT}-v255 (fragment sets at v{F[0]} and v{F[1]}), a0-a255.
+#pragma once
+{emit("SYMB_GEMM16_LOOP_NT", build(False))}
+
+{emit("SYMB_GEMM16_LOOP_NN", build(True))}
+
+{emit("SYMB_GEMM16_KSTEP32_NT", build_kstep32(False))}
+
+{emit("SYMB_GEMM16_KSTEP32_NN", build_kstep32(True))}
+
+{emit("SYMB_GEMM16_ZERO", build_zero())}
+
+{emit("SYMB_GEMM16_STAGE_OUT", build_stage_out())}
+
+#ifdef SYMB_GEMM_PROBE   // tuning builds only: the same loop without its in-loop global loads
+{emit("SYMB_GEMM16_LOOP_NT_NOLOAD", build(False, no_loads=True))}
+#endif
+
+#define SYMB_GEMM16_VCLOBBERS {vclob}
+#define SYMB_GEMM16_ACLOBBERS {aclob}
+#define SYMB_GEMM16_SCLOBBERS {sclob}
+"""
+    with open(os.path.join(here, "gemm16_asm.hpp"), "w") as f:
+        f.write(text)
+
+
+if __name__ == "__main__":
+    main()

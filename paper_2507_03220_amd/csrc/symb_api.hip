@@ -16,6 +16,7 @@
 #include <vector>
 
 #include "adapter_kernels.hpp"
+#include "gemm16_kernel.hpp"
 #include "gemm_kernel.hpp"
 
 using namespace symb;
@@ -277,14 +278,12 @@ struct GemmChoice {
     int bm;
 };
 
-template <int BM, int BN, int WGM, int WGN, bool NN, bool PLAIN = false>
-symb_status launch_gemm_t(symb_handle h, GemmParams gp, hipStream_t st) {
-    using TT = GemmTile<BM, BN, WGM, WGN, NN>;
-    auto kfn = symb_gemm_kernel<BM, BN, WGM, WGN, NN, PLAIN>;
+template <class KFN>
+symb_status launch_gemm_fn(symb_handle h, GemmParams gp, hipStream_t st, KFN kfn, int BM, int BN, int threads, int smem, bool nn) {
     // once per context (= per device): the attribute belongs to the device the kernel is loaded on
     const void* kptr = reinterpret_cast<const void*>(kfn);
     if (std::find(h->lds_attr_set.begin(), h->lds_attr_set.end(), kptr) == h->lds_attr_set.end()) {
-        SYMB_HIP(h, hipFuncSetAttribute(kptr, hipFuncAttributeMaxDynamicSharedMemorySize, TT::SMEM));
+        SYMB_HIP(h, hipFuncSetAttribute(kptr, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
         h->lds_attr_set.push_back(kptr);
     }
     gp.num_m_tiles = (gp.M + BM - 1) / BM;
@@ -309,13 +308,23 @@ symb_status launch_gemm_t(symb_handle h, GemmParams gp, hipStream_t st) {
     const bool timed = h->timing && (int)h->timed.size() < kMaxTimed;
     const size_t slot = h->timed.size();
     if (timed) SYMB_HIP(h, hipEventRecord(h->tev[2 * slot], st));
-    hipLaunchKernelGGL(kfn, dim3(grid), dim3(TT::NT), TT::SMEM, st, gp);
+    hipLaunchKernelGGL(kfn, dim3(grid), dim3(threads), smem, st, gp);
     SYMB_HIP(h, hipGetLastError());
     if (timed) {
         SYMB_HIP(h, hipEventRecord(h->tev[2 * slot + 1], st));
-        h->timed.push_back({NN ? 1 : 0, gp.timing_flops});
+        h->timed.push_back({nn ? 1 : 0, gp.timing_flops});
     }
     return SYMB_OK;
+}
+
+template <int BM, int BN, int WGM, int WGN, bool NN, bool PLAIN = false>
+symb_status launch_gemm_t(symb_handle h, const GemmParams& gp, hipStream_t st) {
+    using TT = GemmTile<BM, BN, WGM, WGN, NN>;
+    return launch_gemm_fn(h, gp, st, symb_gemm_kernel<BM, BN, WGM, WGN, NN, PLAIN>, BM, BN, TT::NT, TT::SMEM, NN);
+}
+template <bool NN, bool PLAIN>
+symb_status launch_gemm16_t(symb_handle h, const GemmParams& gp, hipStream_t st) {
+    return launch_gemm_fn(h, gp, st, symb_gemm16_kernel<NN, PLAIN>, 256, 256, Gemm16Tile::NT, Gemm16Tile::SMEM, NN);
 }
 
 // Algorithmic work of one GEMM launch: 2 M N K plus the fused LoRA term.
@@ -331,16 +340,17 @@ double gemm_flops(const symb_batch* b, int N, int K, bool lora) {
 
 // Tile variants: 0 = 256x256 tile, 8 wavefronts (2x4), compiler-scheduled main loop;
 // 1 = 128x128 tile, 4 wavefronts (2x2), compiler-scheduled; 2 = 256x256 tile, 4 wavefronts (2x2),
-// hand-scheduled assembly main loop (the default for large problems).
+// hand-scheduled assembly main loop on the 32x32x16 matrix instruction; 3 = the same tile and loop
+// structure on the 16x16x32 instruction (gemm16_kernel.hpp; the default for large problems).
 // SYMB_GEMM_VARIANT overrides the choice (tuning aid).
 int gemm_variant(int M, int N) {
     static const int forced = [] {
         const char* e = getenv("SYMB_GEMM_VARIANT");
         return e ? atoi(e) : -1;
     }();
-    if (forced >= 0 && forced <= 2) return forced;
+    if (forced >= 0 && forced <= 3) return forced;
     const long big = (long)((M + 255) / 256) * ((N + 255) / 256);
-    return big >= 128 ? 2 : 1;
+    return big >= 128 ? 3 : 1;
 }
 int gemm_tile_m(int M, int N) { return gemm_variant(M, N) == 1 ? 128 : 256; }
 
@@ -351,6 +361,9 @@ symb_status launch_gemm(symb_handle h, const GemmParams& gp, hipStream_t st) {
         case 2:
             if (!gp.bias && !gp.epi_ia3 && !gp.Cbase && !gp.neff) return launch_gemm_t<256, 256, 2, 2, NN, true>(h, gp, st);
             return launch_gemm_t<256, 256, 2, 2, NN>(h, gp, st);
+        case 3:
+            if (!gp.bias && !gp.epi_ia3 && !gp.Cbase && !gp.neff) return launch_gemm16_t<NN, true>(h, gp, st);
+            return launch_gemm16_t<NN, false>(h, gp, st);
         default: return launch_gemm_t<128, 128, 2, 2, NN>(h, gp, st);
     }
 }

@@ -1,0 +1,73 @@
+"""The 16x16x32 GEMM kernel keeps its accumulators in a0..a255 behind the compiler's back: every
+instruction that touches an accumulation register sits inside one of its assembly templates.  This
+test compiles the device code to assembly and checks that the compiler-generated code of those
+kernels between the templates names no accumulation register and spills nothing that could land in
+one.  No GPU needed (hipcc cross-compiles)."""
+import os
+import re
+import subprocess
+import tempfile
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "paper_2507_03220_amd", "csrc", "symb_api.hip")
+
+
+@pytest.fixture(scope="module")
+def device_asm():
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    with tempfile.TemporaryDirectory() as d:
+        out = os.path.join(d, "symb.s")
+        subprocess.check_call([hipcc, "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Xclang", "-target-feature",
+                               "-Xclang", "-packed-fp32-ops", "--cuda-device-only", "-S", "-o", out, SRC],
+                              stderr=subprocess.DEVNULL)
+        return open(out).read()
+
+
+def _kernels(text):
+    """{mangled name: [(line, inside an assembly template?)]} of the symb_gemm16_kernel instantiations."""
+    out, name, inside = {}, None, False
+    for raw in text.splitlines():
+        s = raw.strip()
+        m = re.match(r"^(_ZN4symb18symb_gemm16_kernel\w+):", s)
+        if m:
+            name, inside = m.group(1), False
+            out[name] = []
+            continue
+        if s.startswith(".Lfunc_end"):
+            name = None
+        if name is None:
+            continue
+        if "ASMSTART" in s:
+            inside = True
+        elif "ASMEND" in s:
+            inside = False
+        else:
+            out[name].append((s.split(";")[0], inside))
+    return out
+
+
+def test_compiler_code_never_touches_accumulation_registers(device_asm):
+    ks = _kernels(device_asm)
+    assert len(ks) == 4, sorted(ks)               # {K-contiguous, N-contiguous weight} x {plain, full epilogue}
+    for name, lines in ks.items():
+        inside = [c for c, i in lines if i]
+        outside = [c for c, i in lines if not i]
+        assert sum("v_mfma_f32_16x16x32_bf16" in c for c in inside) > 500, name
+        offenders = [c for c in outside if re.search(r"\ba\d+\b|\ba\[\d+", c) or "accvgpr" in c or "v_mfma" in c]
+        assert not offenders, (name, offenders[:5])
+
+
+def test_plain_kernels_use_no_scratch_memory(device_asm):
+    for name, lines in _kernels(device_asm).items():
+        if name.endswith("Lb1EEEvNS_10GemmParamsE"):      # PLAIN = true
+            assert not [c for c, _ in lines if "scratch_" in c], name
+
+
+def test_kernel_descriptors_claim_the_whole_register_file(device_asm):
+    # 256 architectural + 256 accumulation registers per lane: one wavefront per SIMD
+    for m in re.finditer(r"\.amdhsa_kernel (_ZN4symb18symb_gemm16_kernel\w+)(.*?)\.end_amdhsa_kernel", device_asm, re.S):
+        body = m.group(2)
+        assert re.search(r"\.amdhsa_next_free_vgpr 512\b", body), m.group(1)
+        assert re.search(r"\.amdhsa_accum_offset 256\b", body), m.group(1)
