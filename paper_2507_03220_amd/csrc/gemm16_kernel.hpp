@@ -202,6 +202,8 @@ symb_gemm16_kernel(const GemmParams p) {
         if constexpr (NN) asm volatile(SYMB_GEMM16_LOOP_NN SYMB_GEMM16_LOOP_OPERANDS);
 #ifdef SYMB_GEMM_PROBE
         else if (p.probe == 1) asm volatile(SYMB_GEMM16_LOOP_NT_NOLOAD SYMB_GEMM16_LOOP_OPERANDS);
+        else if (p.probe == 2) asm volatile(SYMB_GEMM16_LOOP_NT_NOREAD SYMB_GEMM16_LOOP_OPERANDS);
+        else if (p.probe == 5) asm volatile(SYMB_GEMM16_LOOP_NT_NOBAR SYMB_GEMM16_LOOP_OPERANDS);
 #endif
         else asm volatile(SYMB_GEMM16_LOOP_NT SYMB_GEMM16_LOOP_OPERANDS);
 #undef SYMB_GEMM16_LOOP_OPERANDS

@@ -34,6 +34,7 @@ VT = 116                      # address temporaries v116..v127
 S_GA, S_GB = 80, 82
 S_CNT, S_ACUR, S_ANXT, S_ANN, S_BCUR, S_BNXT, S_T0, S_T1 = range(84, 92)
 LOAD_MOD = (" " + os.environ["SYMB_GEN_LOAD_MOD"]) if os.environ.get("SYMB_GEN_LOAD_MOD") else ""   # tuning: cache policy bits
+SPLIT_READS = os.environ.get("SYMB_GEN_SPLIT_READS", "1") == "1"   # 16-byte fragment reads as two 8-byte reads
 UNIT = 32768                  # one operand's 64-k stage
 A_BASES = (0, UNIT, 2 * UNIT)
 B_BASES = (3 * UNIT, 4 * UNIT)
@@ -87,7 +88,12 @@ def frag_reads(nn, dst, sa, sb, ks, va=None, vb=None):
     else:
         a_addr, a_pre = va, []
     for i in range(8):
-        slots.append((a_pre if i == 0 else []) + [f"ds_read_b128 {fa(dst, i)}, {a_addr} offset:{2048 * i}"])
+        b = F[dst] + 4 * i
+        if SPLIT_READS:
+            slots.append((a_pre if i == 0 else []) + [f"ds_read_b64 v[{b}:{b + 1}], {a_addr} offset:{2048 * i}"])
+            slots.append([f"ds_read_b64 v[{b + 2}:{b + 3}], {a_addr} offset:{2048 * i + 8}"])
+        else:
+            slots.append((a_pre if i == 0 else []) + [f"ds_read_b128 {fa(dst, i)}, {a_addr} offset:{2048 * i}"])
     if not nn:
         if vb is None:
             b_addr = f"v{VT + 1}"
@@ -95,7 +101,11 @@ def frag_reads(nn, dst, sa, sb, ks, va=None, vb=None):
         else:
             b_addr, b_pre = vb[0], []
         for j in range(8):
-            slots.append((b_pre if j == 0 else []) + [f"ds_read_b128 {fb(dst, j)}, {b_addr} offset:{2048 * j}"])
+            if SPLIT_READS:
+                slots.append((b_pre if j == 0 else []) + [f"ds_read_b64 {fb_half(dst, j, 0)}, {b_addr} offset:{2048 * j}"])
+                slots.append([f"ds_read_b64 {fb_half(dst, j, 1)}, {b_addr} offset:{2048 * j + 8}"])
+            else:
+                slots.append((b_pre if j == 0 else []) + [f"ds_read_b128 {fb(dst, j)}, {b_addr} offset:{2048 * j}"])
     else:
         for j in range(8):
             if vb is None:
@@ -137,19 +147,21 @@ def advance(which, cond=None):
 
 
 def weave(mf, reads, pairs, first, every):
-    """One MFMA, then at most two other instructions: reads go one per MFMA from the start; load
-    number j puts its m0 write after MFMA first + every*j and the load after the next MFMA."""
-    slots = [[] for _ in mf]
-    for k, r in enumerate(reads):
-        slots[k] += r
+    """One MFMA, then one other instruction (plus the address add a read may carry): load number j
+    puts its m0 write after MFMA first + every*j and the load after the next MFMA; the reads take
+    the free places from the start."""
+    slots = [None] * len(mf)
     for j, (a, b) in enumerate(pairs):
-        slots[first + every * j] += a
-        slots[first + every * j + 1] += b
+        slots[first + every * j] = a
+        slots[first + every * j + 1] = b
+    free = [k for k, s in enumerate(slots) if s is None]
+    assert len(reads) <= len(free)
+    for k, r in zip(free, reads):
+        slots[k] = r
     out = []
     for m, s in zip(mf, slots):
-        assert len(s) <= 3
         out.append(m)
-        out += s
+        out += s or []
     return out
 
 
@@ -159,10 +171,10 @@ def rotate():
             f"s_mov_b32 s{S_T0}, s{S_BCUR}", f"s_mov_b32 s{S_BCUR}, s{S_BNXT}", f"s_mov_b32 s{S_BNXT}, s{S_T0}"]
 
 
-def body(nn, loads_on, last):
+def body(nn, loads_on, last, no_reads=False, no_barrier=False):
     L = []
     # step 0
-    reads = frag_reads(nn, 1, S_ACUR, S_BCUR, 1)
+    reads = [] if no_reads else frag_reads(nn, 1, S_ACUR, S_BCUR, 1)
     pre, pairs = unit_loads(S_ANN, "A", range(8)) if loads_on else ([], [])
     L += pre
     L += weave([mfma(0, i, j) for i, j in BLOCKS], reads, pairs, 2, 7)
@@ -171,9 +183,9 @@ def body(nn, loads_on, last):
     if last:
         L += ["s_waitcnt lgkmcnt(0)"]
     else:
-        L += [f"s_waitcnt vmcnt({8 if loads_on else 0}) lgkmcnt(0)", "s_barrier"]
+        L += [f"s_waitcnt vmcnt({8 if loads_on else 0}) lgkmcnt(0)"] + ([] if no_barrier else ["s_barrier"])
     # step 1
-    reads = [] if last else frag_reads(nn, 0, S_ANXT, S_BNXT, 0)
+    reads = [] if (last or no_reads) else frag_reads(nn, 0, S_ANXT, S_BNXT, 0)
     pre, pairs = unit_loads(S_BCUR, "B", range(8)) if loads_on else ([], [])
     L += pre
     L += weave([mfma(1, i, j) for i, j in BLOCKS], reads, pairs, 1, 4)
@@ -184,7 +196,7 @@ def body(nn, loads_on, last):
     return L
 
 
-def build(nn, no_loads=False):
+def build(nn, no_loads=False, no_reads=False, no_barrier=False):
     L = []
     L += [f"s_mov_b64 s[{S_GA}:{S_GA + 1}], %{GA}", f"s_mov_b64 s[{S_GB}:{S_GB + 1}], %{GB}",
           f"s_sub_u32 s{S_CNT}, %{KF}, 2",
@@ -200,15 +212,15 @@ def build(nn, no_loads=False):
     L += ["s_waitcnt lgkmcnt(0)"]
     L += [f"s_cmp_lt_u32 %{KF}, 3", "s_cbranch_scc1 2f"]
     L.append("1:")
-    L += body(nn, not no_loads, False)
+    L += body(nn, not no_loads, False, no_reads, no_barrier)
     L += rotate()
     L += [f"s_sub_u32 s{S_CNT}, s{S_CNT}, 1", f"s_cmp_lg_u32 s{S_CNT}, 0", "s_cbranch_scc1 1b"]
     L.append("2:")
     L += [f"s_cmp_lt_u32 %{KF}, 2", "s_cbranch_scc1 3f"]
-    L += body(nn, False, False)
+    L += body(nn, False, False, no_reads, no_barrier)
     L += rotate()
     L.append("3:")
-    L += body(nn, False, True)
+    L += body(nn, False, True, no_reads, no_barrier)
     L.append("s_waitcnt vmcnt(0)")
     L += MFMA_DRAIN
     return L
@@ -286,6 +298,10 @@ def main():
 
 #ifdef SYMB_GEMM_PROBE   // tuning builds only: the same loop without its in-loop global loads
 {emit("SYMB_GEMM16_LOOP_NT_NOLOAD", build(False, no_loads=True))}
+
+{emit("SYMB_GEMM16_LOOP_NT_NOREAD", build(False, no_loads=True, no_reads=True))}
+
+{emit("SYMB_GEMM16_LOOP_NT_NOBAR", build(False, no_loads=True, no_reads=True, no_barrier=True))}
 #endif
 
 #define SYMB_GEMM16_VCLOBBERS {vclob}
