@@ -57,7 +57,7 @@ template <bool NN, bool PLAIN>
 __global__ void __launch_bounds__(256)
 symb_gemm16_kernel(const GemmParams p) {
     using TT = Gemm16Tile;
-    constexpr int BM = TT::BM, BN = TT::BN, NT = TT::NT, BK = TT::BK, CP = TT::C_PITCH;
+    constexpr int BM = TT::BM, BN = TT::BN, NT = TT::NT, CP = TT::C_PITCH;
     constexpr int CA = BM * 8 / NT, CB = BN * 8 / NT;      // 16-byte chunks per thread of a register-staged tile
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char* const sA = smem;                        // register-staged tiles (K remainder, LoRA term)
@@ -97,7 +97,6 @@ symb_gemm16_kernel(const GemmParams p) {
     const bf16* const b_tile = NN ? (p.Bop + n0) : (p.Bop + (size_t)n0 * p.K);
     const unsigned lds0 = (unsigned)(size_t)smem;          // LDS byte address of the dynamic segment
 
-    asm volatile(SYMB_GEMM16_ZERO ::: SYMB_GEMM16_ACLOBBERS);
 
     // ---- register-staged 64-k tile (K remainder, LoRA term).  Chunk i of a thread sits 32 rows
     // (K-contiguous tiles) or 8 k-rows (N-contiguous weight tile) below chunk 0.
@@ -133,6 +132,67 @@ symb_gemm16_kernel(const GemmParams p) {
             }
         }
     };
+    // ---- LoRA term, first part: its k-steps are 32 wide (value half and residual half of a rank
+    // block of 16), staged through registers, 4 chunks of 16 bytes per thread and operand.  A step is
+    // (segment es, first extended column ekc); ext_seek moves es to the next LoRA segment with rows
+    // in this tile, ext_load fetches the step.  The first step is fetched here, so that its latency
+    // hides under the main loop.
+    constexpr int EC = 4;
+    const int e_lds0 = lds_off_kmajor(tid >> 2, tid & 3);   // K-contiguous 32-k tile: chunk i sits 64 rows below chunk 0
+    uint4 ea[EC], eb[EC];
+    int es = seg_lo, ekc = 0, e_lo = 0, e_hi = 0;
+    SegDesc esd;
+    auto ext_seek = [&]() __attribute__((always_inline)) -> bool {
+        for (; es <= seg_hi; ++es) {
+            esd = p.seg[es];
+            e_lo = max(p.off[es], m0);
+            e_hi = min(min(p.off[es + 1], m0 + BM), p.M);
+            if (esd.kind == KIND_LORA && e_hi > e_lo) return true;      // uniform over the workgroup
+        }
+        return false;
+    };
+    auto ext_load = [&]() __attribute__((always_inline)) {
+        // activation-side tile: rows of this segment only, others zero
+#pragma unroll
+        for (int i = 0; i < EC; ++i) {
+            const int m = m0 + (tid >> 2) + i * 64;
+            const bool ok = m >= e_lo && m < e_hi;
+            ea[i] = ld_global_16(p.ext + (size_t)(ok ? m : 0) * p.ext_pitch + ekc + (tid & 3) * 8, ok);
+        }
+        // adapter-side tile; both halves of the extended columns meet the same adapter matrix
+#pragma unroll
+        for (int i = 0; i < EC; ++i) {
+            if constexpr (!NN) {       // B_i [N][rank], rank-contiguous
+                const int n = n0 + (tid >> 2) + i * 64;
+                const int pk = ekc + (tid & 3) * 8, pp = pk >= esd.rpad ? pk - esd.rpad : pk;
+                uint4 v = make_uint4(0u, 0u, 0u, 0u);
+                if (n < p.N && pp < esd.rank) {
+                    const bf16* src = esd.B + (size_t)n * esd.rank + pp;
+                    if ((esd.rank & 7) == 0) {
+                        v = *reinterpret_cast<const uint4*>(src);
+                    } else {
+                        unsigned short e[8];
+#pragma unroll
+                        for (int q = 0; q < 8; ++q)
+                            e[q] = (pp + q < esd.rank) ? reinterpret_cast<const unsigned short*>(src)[q] : (unsigned short)0;
+                        v.x = e[0] | ((unsigned)e[1] << 16); v.y = e[2] | ((unsigned)e[3] << 16);
+                        v.z = e[4] | ((unsigned)e[5] << 16); v.w = e[6] | ((unsigned)e[7] << 16);
+                    }
+                }
+                eb[i] = v;
+            } else {                   // A_i [rank][N], N-contiguous
+                const int n = n0 + nn_nc * 8;
+                const int pk = ekc + nn_k + i * KSTEP, pp = pk >= esd.rpad ? pk - esd.rpad : pk;
+                const bool ok = pp < esd.rank && n < p.N;
+                eb[i] = ld_global_16(esd.A + (size_t)(ok ? pp : 0) * p.N + (ok ? n : 0), ok);
+            }
+        }
+    };
+    bool ext_more = p.ext != nullptr && ext_seek();
+    if (ext_more) ext_load();
+
+    asm volatile(SYMB_GEMM16_ZERO ::: SYMB_GEMM16_ACLOBBERS);
+
     // Lane byte offsets of the MFMA fragments of 32-k step ks inside an operand's 64-k tile: a lane
     // holds row l%16, k = 32 ks + 8 (l/16) .. +7.  For the N-contiguous weight one address per
     // 16-column block j (the transposing read: lane jj of a 16-lane group fetches k-row jj/4, columns
@@ -317,57 +377,26 @@ symb_gemm16_kernel(const GemmParams p) {
         }
     }
 
-    // ---- LoRA term: extra k-steps per LoRA segment that meets this row tile
-    if (p.ext) {
-        for (int s = seg_lo; s <= seg_hi; ++s) {
-            const SegDesc sd = p.seg[s];
-            const int r_lo = max(p.off[s], m0), r_hi = min(min(p.off[s + 1], m0 + BM), p.M);
-            if (sd.kind != KIND_LORA || r_hi <= r_lo) continue;      // uniform over the workgroup
-            const int kext = 2 * sd.rpad;                           // value half, then residual half (a multiple of 32)
-            for (int kc0 = 0; kc0 < kext; kc0 += BK) {
-                // activation-side tile: rows of this segment only, others zero
+    // ---- LoRA term: extra 32-wide k-steps per LoRA segment that meets this row tile.  The loads of
+    // the first step went out before the main loop; those of each further step go out before the
+    // MFMAs of the step before it.
+    while (ext_more) {
 #pragma unroll
-                for (int i = 0; i < CA; ++i) {
-                    const int c = tid + i * NT, row = c >> 3, kc = c & 7, m = m0 + row;
-                    const bool ok = m >= r_lo && m < r_hi && (kc0 + kc * 8) < kext;
-                    ra[i] = ld_global_16(p.ext + (size_t)(ok ? m : 0) * p.ext_pitch + kc0 + kc * 8, ok);
-                }
-                lds_store_a();
-                // adapter-side tile
-#pragma unroll
-                for (int i = 0; i < CB; ++i) {
-                    const int c = tid + i * NT;
-                    if constexpr (!NN) {       // B_i [N][rank], rank-contiguous
-                        const int row = c >> 3, kc = c & 7, n = n0 + row;
-                        const int pk = kc0 + kc * 8, pp = pk >= sd.rpad ? pk - sd.rpad : pk;   // both halves meet the same B_i
-                        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-                        if (n < p.N && pk < kext && pp < sd.rank) {
-                            const bf16* src = sd.B + (size_t)n * sd.rank + pp;
-                            if ((sd.rank & 7) == 0) {
-                                v = *reinterpret_cast<const uint4*>(src);
-                            } else {
-                                unsigned short e[8];
-#pragma unroll
-                                for (int q = 0; q < 8; ++q)
-                                    e[q] = (pp + q < sd.rank) ? reinterpret_cast<const unsigned short*>(src)[q] : (unsigned short)0;
-                                v.x = e[0] | ((unsigned)e[1] << 16); v.y = e[2] | ((unsigned)e[3] << 16);
-                                v.z = e[4] | ((unsigned)e[5] << 16); v.w = e[6] | ((unsigned)e[7] << 16);
-                            }
-                        }
-                        rb[i] = v;
-                    } else {                   // A_i [rank][N], N-contiguous
-                        const int krow = c / (BN / 8), nc = c % (BN / 8), n = n0 + nc * 8;
-                        const int pk = kc0 + krow, pp = pk >= sd.rpad ? pk - sd.rpad : pk;
-                        const bool ok = pk < kext && pp < sd.rank && n < p.N;
-                        rb[i] = ld_global_16(sd.A + (size_t)(ok ? pp : 0) * p.N + (ok ? n : 0), ok);
-                    }
-                }
-                lds_store_b();
-                __syncthreads();
-                compute(min(BK, kext - kc0) >> 5);
-                __syncthreads();
-            }
+        for (int i = 0; i < EC; ++i) {
+            *reinterpret_cast<uint4*>(sA + e_lds0 + i * 8192) = ea[i];
+            if constexpr (!NN) *reinterpret_cast<uint4*>(sB + e_lds0 + i * 8192) = eb[i];
+            else *reinterpret_cast<uint4*>(sB + ((b_lds0 + i * KSTEP * (BN * 2)) ^ ((i & 1) << 7))) = eb[i];
         }
+        __syncthreads();
+        ekc += 32;
+        if (ekc >= 2 * esd.rpad) {
+            ++es;
+            ekc = 0;
+            ext_more = ext_seek();
+        }
+        if (ext_more) ext_load();
+        compute(1);
+        __syncthreads();
     }
 
 #ifdef SYMB_GEMM_TRACE

@@ -11,16 +11,17 @@
 // epilogue with the optional bias, the optional store of the pre-adapter output and
 // the IA3 per-channel scale of each row's own segment.
 //
-// Tiling (gfx950): one workgroup owns a BM x BN tile of C; WGM x WGN wavefronts of 64 lanes each
-// own a (BM/WGM) x (BN/WGN) sub-tile as 32x32 blocks of v_mfma_f32_32x32x16_bf16.  Operands go
-// from global memory straight into an LDS ring (no register hop).  The 256x256 / 4-wavefront
-// instantiation walks K in 64-k stages (whole 128-byte lines per request) with a hand-scheduled
-// assembly main loop (gemm_mainloop_asm.hpp); the other instantiations walk 32-k stages with a
-// compiler-scheduled loop.  The MFMA is issued as (weight fragment, activation fragment), so a
-// lane ends up holding, for one row m, runs of 4 consecutive n: rows keep their own segment in
-// the epilogue, which stages the bf16 tile through LDS and writes whole rows.
+// Two kernels compute this.  Large problems: symb_gemm16_kernel (gemm16_kernel.hpp), a 256x256 tile
+// with a hand-scheduled assembly main loop.  Small problems: symb_gemm_kernel below, instantiated
+// for a 128x128 tile.  Tiling of the kernel below (gfx950): one workgroup owns a BM x BN tile of C;
+// WGM x WGN wavefronts of 64 lanes each own a (BM/WGM) x (BN/WGN) sub-tile as 32x32 blocks of
+// v_mfma_f32_32x32x16_bf16.  Operands go from global memory straight into an LDS ring (no register
+// hop) in 32-k stages, with a compiler-scheduled loop.  The MFMA is issued as (weight fragment,
+// activation fragment), so a lane ends up holding, for one row m, runs of 4 consecutive n: rows
+// keep their own segment in the epilogue, which stages the bf16 tile through LDS and writes whole
+// rows.  This file also holds what both kernels share: the parameter block, the LDS layout of a
+// K-contiguous 64-k tile and the predicated 16-byte load.
 #pragma once
-#include "gemm_mainloop_asm.hpp"
 #include "symb_device.hpp"
 
 namespace symb {
@@ -50,13 +51,12 @@ struct GemmParams {
     bf16* const* c_seg;
     const NoiseDesc* neff;      // device [S] or null: per-segment noise effect subtracted last (privacy flow)
     int walk;                   // 0: each XCD walks one contiguous run of tiles; 1: rounds of 32 tiles dealt to the XCDs in turn
-    int stagger;                // start delay unit (s_sleep 127 each) between the 8 phase groups of the first wave of tiles
     double timing_flops;        // host bookkeeping for the measurement hook; unused on the device
 #ifdef SYMB_GEMM_TRACE
     unsigned long long* trace;  // tuning builds only: 16 timestamp slots per tile
 #endif
 #ifdef SYMB_GEMM_PROBE
-    int probe;                  // tuning builds only: 1 = no in-loop global loads, 2 = nor LDS reads
+    int probe;                  // tuning builds only (256x256 kernel): 1 = no in-loop global loads, 2 = nor LDS reads, 5 = nor barriers
 #endif
 };
 
@@ -81,12 +81,8 @@ struct GemmTile {
     static constexpr int A_STAGE = BM * GEMM_SK * 2, B_STAGE = BN * GEMM_SK * 2, STAGE_BYTES = A_STAGE + B_STAGE;
     static constexpr int C_PITCH = BN * 2 + 16, C_BYTES = BM * C_PITCH;     // epilogue staging of the bf16 tile
     static constexpr int CA = BM * 8 / NT, CB = BN * 8 / NT;   // 16-byte chunks per thread per K-step
-    // 256x256 with 4 wavefronts: the hand-scheduled assembly main loop (gemm_mainloop_asm.hpp),
-    // 64-k stages of 32 KiB per operand, three A units and two B units = all 160 KiB of LDS
-    static constexpr bool ASM_LOOP = (BM == 256 && BN == 256 && WGM == 2 && WGN == 2);
-    static constexpr int SK = ASM_LOOP ? 64 : GEMM_SK;         // k per main-loop stage
-    static constexpr int UNIT = 32768, B_UNIT0 = 3 * UNIT;      // assembly loop: unit size, first B unit
-    static constexpr int SMEM_RING = ASM_LOOP ? 5 * UNIT : GEMM_NSTAGE * STAGE_BYTES;
+    static constexpr int SK = GEMM_SK;                         // k per main-loop stage
+    static constexpr int SMEM_RING = GEMM_NSTAGE * STAGE_BYTES;
     static constexpr int SMEM_IN = (2 * (A_BYTES + B_BYTES) > SMEM_RING) ? 2 * (A_BYTES + B_BYTES) : SMEM_RING;
     static constexpr int SMEM = SMEM_IN > C_BYTES ? SMEM_IN : C_BYTES;
     static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tile must be made of 32x32 blocks");
@@ -132,16 +128,7 @@ __device__ __forceinline__ uint4 ld_global_16(const bf16* p, bool ok) {
     return v;
 }
 
-// Accumulator operands of the assembly templates (4-wavefront 256x256 tile), i-major.
-#define SYMB_ACC16(P)                                                                                              \
-    P "a"(acc[0][0]), P "a"(acc[0][1]), P "a"(acc[0][2]), P "a"(acc[0][3]), P "a"(acc[1][0]), P "a"(acc[1][1]),      \
-    P "a"(acc[1][2]), P "a"(acc[1][3]), P "a"(acc[2][0]), P "a"(acc[2][1]), P "a"(acc[2][2]), P "a"(acc[2][3]),      \
-    P "a"(acc[3][0]), P "a"(acc[3][1]), P "a"(acc[3][2]), P "a"(acc[3][3])
-
-// PLAIN: no bias, no IA3 scale, no noise effect, no pre-adapter output (checked by the host).  The plain
-// instantiation contains no arithmetic on the accumulators outside the matrix instructions, so
-// they never leave the accumulation registers before the staging loop reads them one by one.
-template <int BM, int BN, int WGM, int WGN, bool NN, bool PLAIN = false>
+template <int BM, int BN, int WGM, int WGN, bool NN>
 __global__ void __launch_bounds__(WGM * WGN * 64)
 symb_gemm_kernel(const GemmParams p) {
     using TT = GemmTile<BM, BN, WGM, WGN, NN>;
@@ -165,9 +152,6 @@ symb_gemm_kernel(const GemmParams p) {
         lin = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
         if (lin >= total || (int)(blockIdx.x >> 3) >= per_xcd) return;
     }
-#ifdef SYMB_GEMM_PROBE
-    if (p.probe == 4 && (blockIdx.x & 7) != 0) return;     // tuning: only one XCD works
-#endif
     const int width = p.group_m * p.num_n_tiles;
     const int first_m = (lin / width) * p.group_m;
     const int gsz = min(p.num_m_tiles - first_m, p.group_m);
@@ -175,13 +159,6 @@ symb_gemm_kernel(const GemmParams p) {
     const int tn = (lin % width) / gsz;
     const int m0 = tm * BM, n0 = tn * BN;
 
-    // Tiles all take the same time, so workgroups that start together also reach their epilogue
-    // together and the whole chip stops multiplying while one burst of stores drains.  Delaying
-    // the first resident workgroup of each CU by a phase (8 phases) keeps the bursts apart.
-    if (p.stagger > 0 && blockIdx.x < 8 * 32) {
-        const int phase = (blockIdx.x >> 3) & 7;
-        for (int i = 0; i < phase * p.stagger; ++i) __builtin_amdgcn_s_sleep(127);
-    }
 #ifdef SYMB_GEMM_TRACE
     if (p.trace && threadIdx.x == 0) { p.trace[(size_t)lin * 16 + 0] = __builtin_amdgcn_s_memrealtime(); p.trace[(size_t)lin * 16 + 5] = __builtin_readcyclecounter(); }
 #endif
@@ -337,45 +314,18 @@ symb_gemm_kernel(const GemmParams p) {
         }
         __builtin_amdgcn_sched_group_barrier(0x008, MB * NB - (MB + NB), 0);
     };
-    // Plain (not pipelined) pass over the register-staged tile in buffer 0; K remainder and LoRA
-    // term.  The 4-wavefront variant keeps its accumulators pinned in the accumulation registers,
-    // so its k-steps are assembly here too (nothing outside assembly ever writes an accumulator).
-    const unsigned lds0 = (unsigned)(size_t)smem;          // LDS byte address of the dynamic segment
+    // Plain (not pipelined) pass over the register-staged tile in buffer 0; K remainder and LoRA term.
     auto compute = [&](int nks) __attribute__((always_inline)) {
-        if constexpr (TT::ASM_LOOP) {
-            const int r31 = lane & 31, hi = lane >> 5;
-            for (int ks = 0; ks < nks; ++ks) {
-                const unsigned va = lds0 + (unsigned)lds_off_kmajor(wm0 + r31, ks * 2 + hi);
-                if constexpr (!NN) {
-                    const unsigned vb = lds0 + 2 * TT::A_BYTES + (unsigned)lds_off_kmajor(wn0 + r31, ks * 2 + hi);
-                    asm volatile(SYMB_GEMM_KSTEP64_NT : SYMB_ACC16("+") : "v"(va), "v"(vb) : SYMB_GEMM_LOOP_CLOBBERS);
-                } else {
-                    const int g = lane >> 4, jj = lane & 15;
-                    const int k = ks * 16 + ((g >> 1) << 3) + (jj >> 2);
-                    unsigned vb[4];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int n = wn0 + j * 32 + ((g & 1) << 4) + ((jj & 3) << 2);
-                        vb[j] = lds0 + 2 * TT::A_BYTES + (unsigned)lds_off_nmajor<BN>(k, n >> 3) + ((n & 7) << 1);
-                    }
-                    asm volatile(SYMB_GEMM_KSTEP64_NN : SYMB_ACC16("+") : "v"(va), "v"(vb[0]), "v"(vb[1]), "v"(vb[2]), "v"(vb[3])
-                                 : SYMB_GEMM_LOOP_CLOBBERS);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int ks = 0; ks < BK / 16; ++ks) {
-                if (ks < nks) {
-                    load_frags(0, ks, 0);
-                    mfma_set(0);
-                }
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            if (ks < nks) {
+                load_frags(0, ks, 0);
+                mfma_set(0);
             }
         }
     };
 
-    // ---- main loop over the full stages.
-    // Assembly variant (64-k stages, ring of three A and two B units): see gemm_mainloop_asm.hpp.
-    // Compiler-scheduled variants (32-k stages): NSTAGE LDS buffers form a ring; the loads of
+    // ---- main loop over the full stages.  NSTAGE LDS buffers form a ring; the loads of
     // stage t + NSTAGE are issued as soon as every wavefront is done with stage t, i.e. NSTAGE - 1
     // iterations before they are needed.  Per iteration: MFMAs of k-step 0 run while the fragments
     // of k-step 1 are read; then this wavefront's loads of the next stage are awaited, one barrier
@@ -387,72 +337,7 @@ symb_gemm_kernel(const GemmParams p) {
     constexpr int VM_STEADY = LPS * (NS - 2);                  // younger stages that may stay in flight
     static_assert(LPS * (NS - 1) < 64, "vmcnt is a 6-bit counter");
     const int KF = p.K / TT::SK;                               // full stages
-    if constexpr (TT::ASM_LOOP) {
-        if (KF > 0) {
-            // Lane byte offsets of the MFMA fragments inside an operand's 64-k unit.  K-contiguous
-            // units use the layout of lds_off_kmajor, the N-contiguous weight unit that of
-            // lds_off_nmajor (read through the transposing LDS load, see lds_read_frag_nmajor).
-            const int r31 = lane & 31, hi = lane >> 5;
-            unsigned vA[4], vB[4];
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) vA[ks] = lds0 + (unsigned)lds_off_kmajor(wm0 + r31, ks * 2 + hi);
-            if constexpr (!NN) {
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) vB[ks] = lds0 + (unsigned)lds_off_kmajor(wn0 + r31, ks * 2 + hi);
-            } else {
-                const int g = lane >> 4, jj = lane & 15, kk = (jj >> 2) & 3;
-                const int krow = ((g >> 1) << 3) + (jj >> 2), c2 = ((g & 1) << 1) + ((jj & 3) >> 1);
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    vB[j] = lds0 + (unsigned)(krow * (BN * 2) + (((wn0 >> 3) + ((j ^ kk) << 2) + c2) << 4) + ((jj & 1) << 3));
-            }
-            // Global byte offsets of this lane's eight loads per operand and stage.  One load
-            // instruction fills 1 KiB of consecutive LDS: 8 rows of a K-contiguous unit (8 lanes
-            // cover one whole 128-byte line) or 2 k-rows of the N-contiguous unit; the lane ->
-            // chunk map is the inverse of the LDS swizzle.  Rows / columns outside the problem
-            // are clamped onto the last valid one and never stored.
-            unsigned ab[8], bb[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int row = (wave * 8 + j) * 8 + (lane >> 3), kc = (lane & 7) ^ swz_row(row);
-                ab[j] = ((unsigned)(a_row(min(m0 + row, p.M - 1)) - a_tile) + kc * 8) * 2u;
-                if constexpr (!NN) {
-                    bb[j] = ((unsigned)(min(n0 + row, p.N - 1) - n0) * (unsigned)p.K + kc * 8) * 2u;
-                } else {
-                    const int krow = (wave * 8 + j) * 2 + (lane >> 5), nc = (lane & 31) ^ ((krow & 3) << 2);
-                    bb[j] = ((unsigned)krow * (unsigned)p.N + (unsigned)min(nc * 8, p.N - 8 - n0)) * 2u;
-                }
-            }
-#ifdef SYMB_GEMM_PROBE
-            const unsigned long long ga = (unsigned long long)(p.probe == 3 ? p.Aop : a_tile), gb = (unsigned long long)(p.probe == 3 ? p.Bop : b_tile);
-#else
-            const unsigned long long ga = (unsigned long long)a_tile, gb = (unsigned long long)b_tile;
-#endif
-            const unsigned stride_b = NN ? 128u * (unsigned)p.N : 128u;
-            const unsigned swa = (unsigned)__builtin_amdgcn_readfirstlane((int)lds0 + wave * 8192);
-#define SYMB_GEMM_LOOP_OPERANDS                                                                                     \
-    : SYMB_ACC16("+")                                                                                              \
-    : "v"(vA[0]), "v"(vA[1]), "v"(vA[2]), "v"(vA[3]), "v"(vB[0]), "v"(vB[1]), "v"(vB[2]), "v"(vB[3]),              \
-      "v"(ab[0]), "v"(ab[1]), "v"(ab[2]), "v"(ab[3]), "v"(ab[4]), "v"(ab[5]), "v"(ab[6]), "v"(ab[7]),              \
-      "v"(bb[0]), "v"(bb[1]), "v"(bb[2]), "v"(bb[3]), "v"(bb[4]), "v"(bb[5]), "v"(bb[6]), "v"(bb[7]),              \
-      "s"(ga), "s"(gb), "s"(stride_b), "s"(KF), "s"(swa)                                                           \
-    : SYMB_GEMM_LOOP_CLOBBERS
-#ifdef SYMB_GEMM_TRACE
-            if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 1] = __builtin_amdgcn_s_memrealtime();
-#endif
-            if constexpr (NN) asm volatile(SYMB_GEMM_LOOP_NN SYMB_GEMM_LOOP_OPERANDS);
-#ifdef SYMB_GEMM_PROBE
-            else if (p.probe == 1) asm volatile(SYMB_GEMM_LOOP_NT_NOLOAD SYMB_GEMM_LOOP_OPERANDS);
-            else if (p.probe == 2) asm volatile(SYMB_GEMM_LOOP_NT_NOREAD SYMB_GEMM_LOOP_OPERANDS);
-#endif
-            else asm volatile(SYMB_GEMM_LOOP_NT SYMB_GEMM_LOOP_OPERANDS);
-#undef SYMB_GEMM_LOOP_OPERANDS
-            __builtin_amdgcn_s_barrier();                      // everything landed and read before LDS is reused
-#ifdef SYMB_GEMM_TRACE
-            if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 2] = __builtin_amdgcn_s_memrealtime();
-#endif
-        }
-    } else if (KF > 0) {
+    if (KF > 0) {
 #pragma unroll
         for (int t = 0; t < NS; ++t) stage_issue(t, min(t, KF - 1));
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(LPS * (NS - 1)));
@@ -508,23 +393,12 @@ symb_gemm_kernel(const GemmParams p) {
         }
     };
     constexpr int CP = TT::C_PITCH;                  // bytes per staged row (BN * 2 + 16: bank spread)
-    // The four accumulators of one quad.  In the assembly variant they are read by instructions
-    // placed here and now: left to the compiler, all 256 accumulation registers are copied out
-    // ahead of the loops, which needs more registers than there are.
     auto read_quad = [&](int i, int j, int rg, float& v0, float& v1, float& v2, float& v3) __attribute__((always_inline)) {
-        if constexpr (TT::ASM_LOOP) {
-            asm volatile("v_accvgpr_read_b32 %0, %4\n\tv_accvgpr_read_b32 %1, %5\n\t"
-                         "v_accvgpr_read_b32 %2, %6\n\tv_accvgpr_read_b32 %3, %7"
-                         : "=v"(v0), "=v"(v1), "=v"(v2), "=v"(v3)
-                         : "a"(acc[i][j][rg * 4 + 0]), "a"(acc[i][j][rg * 4 + 1]), "a"(acc[i][j][rg * 4 + 2]),
-                           "a"(acc[i][j][rg * 4 + 3]));
-        } else {
-            v0 = acc[i][j][rg * 4 + 0]; v1 = acc[i][j][rg * 4 + 1];
-            v2 = acc[i][j][rg * 4 + 2]; v3 = acc[i][j][rg * 4 + 3];
-        }
+        v0 = acc[i][j][rg * 4 + 0]; v1 = acc[i][j][rg * 4 + 1];
+        v2 = acc[i][j][rg * 4 + 2]; v3 = acc[i][j][rg * 4 + 3];
     };
     auto stage_out = [&](bf16* __restrict__ dst, bool scale_ia3) __attribute__((always_inline)) {
-        if (PLAIN || (!p.bias && !scale_ia3 && !p.neff)) {
+        if (!p.bias && !scale_ia3 && !p.neff) {
             for_each_quad([&](int i, int j, int rg, int m, int n) __attribute__((always_inline)) {
                 float v0, v1, v2, v3;
                 read_quad(i, j, rg, v0, v1, v2, v3);
@@ -533,7 +407,7 @@ symb_gemm_kernel(const GemmParams p) {
                 o.y = pack2_bf16(v2, v3);
                 *reinterpret_cast<uint2*>(smem + (m - m0) * CP + (n - n0) * 2) = o;
             });
-        } else if constexpr (!PLAIN) {
+        } else {
             // bias of this lane's 16 column quads, once; IA3 vector of each row's own segment per row block
             const uint2 zero2 = make_uint2(0u, 0u);
             const int nq0 = n0 + wn0 + ((lane >> 5) << 2);
@@ -631,22 +505,14 @@ symb_gemm_kernel(const GemmParams p) {
     };
 
     // ---- optional store of the pre-adapter output (accumulator + bias, before the LoRA term)
-    if constexpr (!PLAIN) {
-        if (p.Cbase) {
-            stage_out(p.Cbase, false);
-            __syncthreads();                         // LDS is reused by the LoRA tiles below
-        }
+    if (p.Cbase) {
+        stage_out(p.Cbase, false);
+        __syncthreads();                             // LDS is reused by the LoRA tiles below
     }
 
     // ---- LoRA term: extra K-steps per LoRA segment that meets this row tile
     if (p.ext) {
-        // Empty statements that name every accumulator as an accumulation-register operand, here and
-        // at the top of each segment's pass: without these anchors the register allocator moves most
-        // of the accumulators to scratch memory around this loop nest (about 190 registers per lane
-        // written out and read back per tile, more HBM traffic than the output itself).
-        if constexpr (TT::ASM_LOOP) asm volatile("" : SYMB_ACC16("+"));
         for (int s = seg_lo; s <= seg_hi; ++s) {
-            if constexpr (TT::ASM_LOOP) asm volatile("" : SYMB_ACC16("+"));
             const SegDesc sd = p.seg[s];
             const int r_lo = max(p.off[s], m0), r_hi = min(min(p.off[s + 1], m0 + BM), p.M);
             if (sd.kind != KIND_LORA || r_hi <= r_lo) continue;      // uniform over the workgroup
@@ -659,7 +525,6 @@ symb_gemm_kernel(const GemmParams p) {
                     const bool ok = m >= r_lo && m < r_hi && (kc0 + kc * 8) < kext;
                     ra[i] = ld_global_16(p.ext + (size_t)(ok ? m : 0) * p.ext_pitch + kc0 + kc * 8, ok);
                 }
-                if constexpr (TT::ASM_LOOP) lds_store_a(0);    // one operand at a time: fewer registers live at once
                 // adapter-side tile
 #pragma unroll
                 for (int i = 0; i < CB; ++i) {
@@ -689,8 +554,7 @@ symb_gemm_kernel(const GemmParams p) {
                         rb[i] = ld_global_16(sd.A + (size_t)(ok ? pp : 0) * p.N + (ok ? n : 0), ok);
                     }
                 }
-                if constexpr (TT::ASM_LOOP) lds_store_b(0);
-                else lds_store(0);
+                lds_store(0);
                 __syncthreads();
                 compute(min(BK, kext - kc0) >> 4);
                 __syncthreads();

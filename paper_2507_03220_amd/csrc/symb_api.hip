@@ -289,10 +289,6 @@ symb_status launch_gemm_fn(symb_handle h, GemmParams gp, hipStream_t st, KFN kfn
     gp.num_m_tiles = (gp.M + BM - 1) / BM;
     gp.num_n_tiles = (gp.N + BN - 1) / BN;
     gp.group_m = 8;
-    {
-        static const int stagger = [] { const char* e = getenv("SYMB_GEMM_STAGGER"); return e ? atoi(e) : 0; }();
-        gp.stagger = stagger;
-    }
 #ifdef SYMB_GEMM_PROBE
     { const char* e = getenv("SYMB_GEMM_PROBE"); gp.probe = e ? atoi(e) : 0; }
 #endif
@@ -317,10 +313,10 @@ symb_status launch_gemm_fn(symb_handle h, GemmParams gp, hipStream_t st, KFN kfn
     return SYMB_OK;
 }
 
-template <int BM, int BN, int WGM, int WGN, bool NN, bool PLAIN = false>
+template <int BM, int BN, int WGM, int WGN, bool NN>
 symb_status launch_gemm_t(symb_handle h, const GemmParams& gp, hipStream_t st) {
     using TT = GemmTile<BM, BN, WGM, WGN, NN>;
-    return launch_gemm_fn(h, gp, st, symb_gemm_kernel<BM, BN, WGM, WGN, NN, PLAIN>, BM, BN, TT::NT, TT::SMEM, NN);
+    return launch_gemm_fn(h, gp, st, symb_gemm_kernel<BM, BN, WGM, WGN, NN>, BM, BN, TT::NT, TT::SMEM, NN);
 }
 template <bool NN, bool PLAIN>
 symb_status launch_gemm16_t(symb_handle h, const GemmParams& gp, hipStream_t st) {
@@ -338,17 +334,16 @@ double gemm_flops(const symb_batch* b, int N, int K, bool lora) {
     return f;
 }
 
-// Tile variants: 0 = 256x256 tile, 8 wavefronts (2x4), compiler-scheduled main loop;
-// 1 = 128x128 tile, 4 wavefronts (2x2), compiler-scheduled; 2 = 256x256 tile, 4 wavefronts (2x2),
-// hand-scheduled assembly main loop on the 32x32x16 matrix instruction; 3 = the same tile and loop
-// structure on the 16x16x32 instruction (gemm16_kernel.hpp; the default for large problems).
-// SYMB_GEMM_VARIANT overrides the choice (tuning aid).
+// Tile variants: 1 = 128x128 tile, 4 wavefronts (2x2), compiler-scheduled loop on the 32x32x16 matrix
+// instruction; 3 = 256x256 tile, 4 wavefronts (2x2), hand-scheduled assembly loop on the 16x16x32
+// instruction (gemm16_kernel.hpp), taken when the problem has enough such tiles to fill the chip.
+// SYMB_GEMM_VARIANT = 1 or 3 overrides the choice (tuning aid).
 int gemm_variant(int M, int N) {
     static const int forced = [] {
         const char* e = getenv("SYMB_GEMM_VARIANT");
         return e ? atoi(e) : -1;
     }();
-    if (forced >= 0 && forced <= 3) return forced;
+    if (forced == 1 || forced == 3) return forced;
     const long big = (long)((M + 255) / 256) * ((N + 255) / 256);
     return big >= 128 ? 3 : 1;
 }
@@ -356,16 +351,11 @@ int gemm_tile_m(int M, int N) { return gemm_variant(M, N) == 1 ? 128 : 256; }
 
 template <bool NN>
 symb_status launch_gemm(symb_handle h, const GemmParams& gp, hipStream_t st) {
-    switch (gemm_variant(gp.M, gp.N)) {
-        case 0: return launch_gemm_t<256, 256, 2, 4, NN>(h, gp, st);
-        case 2:
-            if (!gp.bias && !gp.epi_ia3 && !gp.Cbase && !gp.neff) return launch_gemm_t<256, 256, 2, 2, NN, true>(h, gp, st);
-            return launch_gemm_t<256, 256, 2, 2, NN>(h, gp, st);
-        case 3:
-            if (!gp.bias && !gp.epi_ia3 && !gp.Cbase && !gp.neff) return launch_gemm16_t<NN, true>(h, gp, st);
-            return launch_gemm16_t<NN, false>(h, gp, st);
-        default: return launch_gemm_t<128, 128, 2, 2, NN>(h, gp, st);
+    if (gemm_variant(gp.M, gp.N) == 3) {
+        if (!gp.bias && !gp.epi_ia3 && !gp.Cbase && !gp.neff) return launch_gemm16_t<NN, true>(h, gp, st);
+        return launch_gemm16_t<NN, false>(h, gp, st);
     }
+    return launch_gemm_t<128, 128, 2, 2, NN>(h, gp, st);
 }
 
 template <int RB>
