@@ -354,17 +354,31 @@ symb_gemm16_kernel(const GemmParams p) {
         if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 9] = __builtin_amdgcn_s_memrealtime();
 #endif
         const bool to_seg = p.c_seg != nullptr && dst == p.C;   // the final output goes to the segments' own buffers
-        const int col = (lane & 31) * 8;
-#pragma unroll 4
-        for (int r = wave * 2 + (lane >> 5); r < BM; r += 8) {
-            const int m = m0 + r, n = n0 + col;
-            if (m < p.M && n < p.N) {
-                bf16* rowp = dst + (size_t)m * p.N;
-                if (to_seg) {
-                    const int s = seg_of_row(p.off, seg_lo, seg_hi, m);
-                    rowp = p.c_seg[s] + (size_t)(m - p.off[s]) * p.N;
+        const int col = (lane & 31) * 8, r0 = wave * 2 + (lane >> 5);
+        const bool nok = n0 + col < p.N;
+        if (!to_seg) {
+            // 32 rows per lane, in two batches: sixteen LDS reads in flight, then their sixteen stores
+            bf16* const out0 = dst + (size_t)(m0 + r0) * p.N + n0 + col;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                uint4 v[16];
+#pragma unroll
+                for (int q = 0; q < 16; ++q) v[q] = *reinterpret_cast<const uint4*>(smem + (r0 + (half * 16 + q) * 8) * CP + col * 2);
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int r = r0 + (half * 16 + q) * 8;
+                    if (nok && m0 + r < p.M) *reinterpret_cast<uint4*>(out0 + (size_t)((half * 16 + q) * 8) * p.N) = v[q];
                 }
-                *reinterpret_cast<uint4*>(rowp + n) = *reinterpret_cast<const uint4*>(smem + r * CP + col * 2);
+            }
+        } else {
+#pragma unroll 4
+            for (int r = r0; r < BM; r += 8) {
+                const int m = m0 + r;
+                if (m < p.M && nok) {
+                    const int s = seg_of_row(p.off, seg_lo, seg_hi, m);
+                    bf16* rowp = p.c_seg[s] + (size_t)(m - p.off[s]) * p.N;
+                    *reinterpret_cast<uint4*>(rowp + n0 + col) = *reinterpret_cast<const uint4*>(smem + r * CP + col * 2);
+                }
             }
         }
     };
