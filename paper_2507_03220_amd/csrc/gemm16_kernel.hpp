@@ -30,9 +30,9 @@ struct Gemm16Tile {
 
 // N-contiguous weight unit: [64 k][256 n] bf16, 512 B per k-row, 16-byte chunk nc of row k stored
 // at nc ^ swz.  The transposing read of one 16-lane group fetches 4 k-rows x 32 B: the (k & 3)
-// term lays those side by side (128 B), the (k >> 3) term moves the next group to the other half
-// of the banks.
-__device__ __forceinline__ int swz_nmajor16(int k) { return ((k & 3) << 1) ^ (((k >> 3) & 1) << 3); }
+// term lays those side by side (128 B), the (k >> 2) term moves the next group (4 k-rows further)
+// to the other half of the banks.
+__device__ __forceinline__ int swz_nmajor16(int k) { return ((k & 3) << 1) ^ (((k >> 2) & 1) << 3); }
 __device__ __forceinline__ int lds_off_nmajor16(int k, int nc) { return k * 512 + ((nc ^ swz_nmajor16(k)) << 4); }
 
 template <int I0, int I1, class F>
@@ -114,7 +114,7 @@ symb_gemm16_kernel(const GemmParams p) {
 #pragma unroll
         for (int i = 0; i < CB; ++i) {
             if constexpr (!NN) *reinterpret_cast<uint4*>(sB + b_lds0 + i * RSTEP * 128) = rb[i];
-            else *reinterpret_cast<uint4*>(sB + ((b_lds0 + i * KSTEP * (BN * 2)) ^ ((i & 1) << 7))) = rb[i];   // k + 8 flips the swizzle's high term
+            else *reinterpret_cast<uint4*>(sB + b_lds0 + i * KSTEP * (BN * 2)) = rb[i];
         }
     };
     auto gload_tail = [&](int k0) __attribute__((always_inline)) {
@@ -193,29 +193,35 @@ symb_gemm16_kernel(const GemmParams p) {
 
     asm volatile(SYMB_GEMM16_ZERO ::: SYMB_GEMM16_ACLOBBERS);
 
-    // Lane byte offsets of the MFMA fragments of 32-k step ks inside an operand's 64-k tile: a lane
-    // holds row l%16, k = 32 ks + 8 (l/16) .. +7.  For the N-contiguous weight one address per
-    // 16-column block j (the transposing read: lane jj of a 16-lane group fetches k-row jj/4, columns
-    // 4 (jj%4) .. +3, and receives column jj, 4 k-rows; a second read 4 k-rows down completes 8 k).
-    auto frag_a = [&](int ks) __attribute__((always_inline)) { return (unsigned)lds_off_kmajor(wm0 + l15, ks * 4 + lg); };
-    auto frag_b_nt = [&](int ks) __attribute__((always_inline)) { return (unsigned)lds_off_kmajor(wn0 + l15, ks * 4 + lg); };
+    // Lane byte offsets of the MFMA fragments of 32-k step ks inside an operand's 64-k tile.  Lane
+    // group g = l/16 holds row l%16 and k = 32 ks + 16 q + 8 (g/2) + 4 (g%2) + 0..3, q = 0, 1 (one
+    // 8-byte read each: half g%2 of 16-byte chunk 4 ks + 2 q + g/2).  For the N-contiguous weight one
+    // address per 16-column block j serves both reads (the transposing read: lane jj of a 16-lane
+    // group fetches k-row jj/4, columns 4 (jj%4) .. +3, and receives column jj of 4 k-rows; the
+    // second read, 16 k-rows down, is a constant offset away).
+    auto frag_a = [&](int ks, int q) __attribute__((always_inline)) {
+        return (unsigned)(lds_off_kmajor(wm0 + l15, ks * 4 + q * 2 + (lg >> 1)) + ((lg & 1) << 3));
+    };
+    auto frag_b_nt = [&](int ks, int q) __attribute__((always_inline)) {
+        return (unsigned)(lds_off_kmajor(wn0 + l15, ks * 4 + q * 2 + (lg >> 1)) + ((lg & 1) << 3));
+    };
     auto frag_b_nn = [&](int j) __attribute__((always_inline)) {
-        const int k = lg * 8 + (l15 >> 2), n = wn0 + j * 16 + ((l15 & 3) << 2);
+        const int k = (lg >> 1) * 8 + (lg & 1) * 4 + (l15 >> 2), n = wn0 + j * 16 + ((l15 & 3) << 2);
         return (unsigned)(lds_off_nmajor16(k, n >> 3) + ((n & 7) << 1));
     };
     // nks 32-wide k-steps over the register-staged tile
     auto compute = [&](int nks) __attribute__((always_inline)) {
         for (int ks = 0; ks < nks; ++ks) {
-            const unsigned va = lds0 + frag_a(ks);
+            const unsigned va0 = lds0 + frag_a(ks, 0), va1 = lds0 + frag_a(ks, 1);
             if constexpr (!NN) {
-                const unsigned vb = lds0 + TT::UNIT + frag_b_nt(ks);
-                asm volatile(SYMB_GEMM16_KSTEP32_NT : : "v"(va), "v"(vb)
+                const unsigned vb0 = lds0 + TT::UNIT + frag_b_nt(ks, 0), vb1 = lds0 + TT::UNIT + frag_b_nt(ks, 1);
+                asm volatile(SYMB_GEMM16_KSTEP32_NT : : "v"(va0), "v"(va1), "v"(vb0), "v"(vb1)
                              : "memory", SYMB_GEMM16_VCLOBBERS, SYMB_GEMM16_ACLOBBERS);
             } else {
                 unsigned vb[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) vb[j] = lds0 + TT::UNIT + frag_b_nn(j) + ks * 32 * (BN * 2);
-                asm volatile(SYMB_GEMM16_KSTEP32_NN : : "v"(va), "v"(vb[0]), "v"(vb[1]), "v"(vb[2]), "v"(vb[3]),
+                asm volatile(SYMB_GEMM16_KSTEP32_NN : : "v"(va0), "v"(va1), "v"(vb[0]), "v"(vb[1]), "v"(vb[2]), "v"(vb[3]),
                              "v"(vb[4]), "v"(vb[5]), "v"(vb[6]), "v"(vb[7])
                              : "memory", SYMB_GEMM16_VCLOBBERS, SYMB_GEMM16_ACLOBBERS);
             }
@@ -225,11 +231,11 @@ symb_gemm16_kernel(const GemmParams p) {
     // ---- main loop over the full 64-k stages (gemm16_asm.hpp)
     const int KF = p.K / 64;
     if (KF > 0) {
-        unsigned vA[2], vB[8];
-        vA[0] = lds0 + frag_a(0);
-        vA[1] = lds0 + frag_a(1);
+        unsigned vA[4], vB[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) vB[j] = lds0 + (NN ? frag_b_nn(j) : frag_b_nt(j & 1));
+        for (int j = 0; j < 4; ++j) vA[j] = lds0 + frag_a(j >> 1, j & 1);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) vB[j] = lds0 + (NN ? frag_b_nn(j) : frag_b_nt((j >> 1) & 1, j & 1));
         // Global byte offsets of this lane's eight loads per operand and stage.  One load instruction
         // fills 1 KiB of consecutive LDS: 8 rows of a K-contiguous unit or 2 k-rows of the
         // N-contiguous unit; the lane -> chunk map is the inverse of the LDS swizzle.  Rows / columns
@@ -251,8 +257,8 @@ symb_gemm16_kernel(const GemmParams p) {
         const unsigned swa = (unsigned)__builtin_amdgcn_readfirstlane((int)lds0 + wave * 8192);
 #define SYMB_GEMM16_LOOP_OPERANDS                                                                                   \
     :                                                                                                              \
-    : "v"(vA[0]), "v"(vA[1]), "v"(vB[0]), "v"(vB[1]), "v"(vB[2]), "v"(vB[3]), "v"(vB[4]), "v"(vB[5]), "v"(vB[6]),  \
-      "v"(vB[7]), "v"(ab[0]), "v"(ab[1]), "v"(ab[2]), "v"(ab[3]), "v"(ab[4]), "v"(ab[5]), "v"(ab[6]), "v"(ab[7]),  \
+    : "v"(vA[0]), "v"(vA[1]), "v"(vA[2]), "v"(vA[3]), "v"(vB[0]), "v"(vB[1]), "v"(vB[2]), "v"(vB[3]), "v"(vB[4]),  \
+      "v"(vB[5]), "v"(vB[6]), "v"(vB[7]), "v"(ab[0]), "v"(ab[1]), "v"(ab[2]), "v"(ab[3]), "v"(ab[4]), "v"(ab[5]), "v"(ab[6]), "v"(ab[7]),  \
       "v"(bb[0]), "v"(bb[1]), "v"(bb[2]), "v"(bb[3]), "v"(bb[4]), "v"(bb[5]), "v"(bb[6]), "v"(bb[7]),              \
       "s"(ga), "s"(gb), "s"(stride_b), "s"(KF), "s"(swa)                                                           \
     : "memory", "scc", SYMB_GEMM16_SCLOBBERS, SYMB_GEMM16_VCLOBBERS, SYMB_GEMM16_ACLOBBERS
@@ -399,7 +405,7 @@ symb_gemm16_kernel(const GemmParams p) {
         for (int i = 0; i < EC; ++i) {
             *reinterpret_cast<uint4*>(sA + e_lds0 + i * 8192) = ea[i];
             if constexpr (!NN) *reinterpret_cast<uint4*>(sB + e_lds0 + i * 8192) = eb[i];
-            else *reinterpret_cast<uint4*>(sB + ((b_lds0 + i * KSTEP * (BN * 2)) ^ ((i & 1) << 7))) = eb[i];
+            else *reinterpret_cast<uint4*>(sB + b_lds0 + i * KSTEP * (BN * 2)) = eb[i];
         }
         __syncthreads();
         ekc += 32;

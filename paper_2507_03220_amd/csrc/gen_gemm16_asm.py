@@ -15,11 +15,16 @@ template names these registers literally, and the compiler-generated code in bet
 touches an accumulation register (a CPU test checks the generated assembly for that).
 
 Lane layout of the instruction, issued as (weight fragment, activation fragment): an operand
-lane l holds row l%16, k = 8(l/16) .. 8(l/16)+7 of its 16x32 fragment; the result lane holds
-C[m = 16i + l%16][n = 16j + 4(l/16) + e], e = 0..3: four consecutive columns of one row.
+lane l holds row l%16 and eight of the 32 k of its 16x32 fragment; which eight does not matter as
+long as both operands agree (the instruction multiplies register element e of lane group l/16 of
+one operand with the same element of the same lane group of the other).  Here lane group g holds
+k = 8(g/2) + 4(g%2) + 0..3 and the same + 16: every 16-byte fragment quad is filled by two 8-byte
+LDS reads (a wavefront alone on its SIMD issues in order, and a 16-byte read holds up the next
+16-cycle MFMA where an 8-byte read does not), and with this choice the 32 lanes the LDS serves per
+clock read both halves of 16 different 16-byte chunks, i.e. all 64 banks once.  The result lane
+holds C[m = 16i + l%16][n = 16j + 4(l/16) + e], e = 0..3: four consecutive columns of one row.
 
-Main loop, per 64-k stage P (ring of three A and two B units of 32 KiB in LDS, as in the
-32x32x16 kernel): two 32-k steps of 64 MFMAs each, fragment sets F0/F1 alternating.
+Main loop, per 64-k stage P (ring of three A and two B units of 32 KiB in LDS): two 32-k steps of 64 MFMAs each, fragment sets F0/F1 alternating.
   step 0: MFMAs on F0 while the step-1 fragments of stage P are read into F1; the eight loads
           of A(P+2) go out, one per eight MFMAs; then wait for this wavefront's loads of stage
           P+1, barrier (stage P+1 complete for everybody, both units of stage P free);
@@ -34,18 +39,17 @@ VT = 116                      # address temporaries v116..v127
 S_GA, S_GB = 80, 82
 S_CNT, S_ACUR, S_ANXT, S_ANN, S_BCUR, S_BNXT, S_T0, S_T1 = range(84, 92)
 LOAD_MOD = (" " + os.environ["SYMB_GEN_LOAD_MOD"]) if os.environ.get("SYMB_GEN_LOAD_MOD") else ""   # tuning: cache policy bits
-SPLIT_READS = os.environ.get("SYMB_GEN_SPLIT_READS", "1") == "1"   # 16-byte fragment reads as two 8-byte reads
 UNIT = 32768                  # one operand's 64-k stage
 A_BASES = (0, UNIT, 2 * UNIT)
 B_BASES = (3 * UNIT, 4 * UNIT)
 C_PITCH = 528                 # bytes per row of the staged bf16 output tile (256 * 2 + 16)
 
 # operand numbers of the main loop
-VA = (0, 1)                   # A fragment lane offsets, 32-k step 0 / 1
-VB = tuple(range(2, 10))      # NT: B lane offsets for step 0 / 1 in VB[0], VB[1]; NN: one per 16-column block
-AV = tuple(range(10, 18))     # global byte offsets of this lane's 8 A loads
-BV = tuple(range(18, 26))     # global byte offsets of this lane's 8 B loads
-GA, GB, STRIDE_B, KF, SWA = 26, 27, 28, 29, 30
+VA = (0, 1, 2, 3)             # A fragment lane offsets: 32-k step 0 first / second read, step 1 first / second read
+VB = tuple(range(4, 12))      # K-contiguous W: as VA in VB[0..3]; N-contiguous W: one per 16-column block
+AV = tuple(range(12, 20))     # global byte offsets of this lane's 8 A loads
+BV = tuple(range(20, 28))     # global byte offsets of this lane's 8 B loads
+GA, GB, STRIDE_B, KF, SWA = 28, 29, 30, 31, 32
 
 # The compiler does not look inside an assembly statement: whatever it places right after one
 # must not meet a matrix instruction that is still writing its result.
@@ -80,42 +84,37 @@ def mfma(s, i, j):
 def frag_reads(nn, dst, sa, sb, ks, va=None, vb=None):
     """The LDS reads that fill fragment set `dst` with 32-k step `ks` of the stage whose A / B units
     start at SGPR `sa` / `sb` (or, with va / vb given, at those address operands).  A list of slots:
-    each read, preceded by the address add it needs."""
+    each read, preceded by the address add it needs.  A fragment register quad is filled by two
+    8-byte reads with an address each (see the lane layout above)."""
     slots = []
-    if va is None:
-        a_addr = f"v{VT}"
-        a_pre = [f"v_add_u32 v{VT}, s{sa}, %{VA[ks]}"]
-    else:
-        a_addr, a_pre = va, []
-    for i in range(8):
-        b = F[dst] + 4 * i
-        if SPLIT_READS:
-            slots.append((a_pre if i == 0 else []) + [f"ds_read_b64 v[{b}:{b + 1}], {a_addr} offset:{2048 * i}"])
-            slots.append([f"ds_read_b64 v[{b + 2}:{b + 3}], {a_addr} offset:{2048 * i + 8}"])
+    for q in range(2):
+        if va is None:
+            addr = f"v{VT + q}"
+            pre = [f"v_add_u32 {addr}, s{sa}, %{VA[2 * ks + q]}"]
         else:
-            slots.append((a_pre if i == 0 else []) + [f"ds_read_b128 {fa(dst, i)}, {a_addr} offset:{2048 * i}"])
+            addr, pre = va[q], []
+        for i in range(8):
+            b = F[dst] + 4 * i + 2 * q
+            slots.append((pre if i == 0 else []) + [f"ds_read_b64 v[{b}:{b + 1}], {addr} offset:{2048 * i}"])
     if not nn:
-        if vb is None:
-            b_addr = f"v{VT + 1}"
-            b_pre = [f"v_add_u32 v{VT + 1}, s{sb}, %{VB[ks]}"]
-        else:
-            b_addr, b_pre = vb[0], []
-        for j in range(8):
-            if SPLIT_READS:
-                slots.append((b_pre if j == 0 else []) + [f"ds_read_b64 {fb_half(dst, j, 0)}, {b_addr} offset:{2048 * j}"])
-                slots.append([f"ds_read_b64 {fb_half(dst, j, 1)}, {b_addr} offset:{2048 * j + 8}"])
+        for q in range(2):
+            if vb is None:
+                addr = f"v{VT + 2 + q}"
+                pre = [f"v_add_u32 {addr}, s{sb}, %{VB[2 * ks + q]}"]
             else:
-                slots.append((b_pre if j == 0 else []) + [f"ds_read_b128 {fb(dst, j)}, {b_addr} offset:{2048 * j}"])
+                addr, pre = vb[q], []
+            for j in range(8):
+                slots.append((pre if j == 0 else []) + [f"ds_read_b64 {fb_half(dst, j, q)}, {addr} offset:{2048 * j}"])
     else:
         for j in range(8):
             if vb is None:
-                addr = f"v{VT + 1 + j}"
+                addr = f"v{VT + 2 + j}"
                 pre = [f"v_add_u32 {addr}, s{sb}, %{VB[j]}"]
             else:
                 addr, pre = vb[j], []
-            for h in range(2):
-                slots.append((pre if h == 0 else []) +
-                             [f"ds_read_b64_tr_b16 {fb_half(dst, j, h)}, {addr} offset:{16384 * ks + 2048 * h}"])
+            for q in range(2):
+                slots.append((pre if q == 0 else []) +
+                             [f"ds_read_b64_tr_b16 {fb_half(dst, j, q)}, {addr} offset:{16384 * ks + 8192 * q}"])
     return slots
 
 
@@ -228,10 +227,11 @@ def build(nn, no_loads=False, no_reads=False, no_barrier=False):
 
 def build_kstep32(nn):
     """One 32-wide k-step on a register-staged 64-k tile (K remainder, LoRA term): read the sixteen
-    fragments, wait, 64 MFMAs.  Operands: %0 A fragment address, %1 (K-contiguous W) or %1-%8
-    (N-contiguous W, one per 16-column block) B addresses; the 32-k half is already in them."""
+    fragments, wait, 64 MFMAs.  Operands: %0, %1 A fragment addresses (first / second read); B
+    addresses %2, %3 (K-contiguous W) or %2-%9 (N-contiguous W, one per 16-column block); the 32-k
+    half is already in them."""
     L = []
-    for r in frag_reads(nn, 0, None, None, 0, va="%0", vb=[f"%{1 + j}" for j in range(8)]):
+    for r in frag_reads(nn, 0, None, None, 0, va=["%0", "%1"], vb=[f"%{2 + j}" for j in range(8)]):
         L += r
     L.append("s_waitcnt lgkmcnt(0)")
     L += [mfma(0, i, j) for i, j in BLOCKS]
@@ -276,12 +276,13 @@ def main():
 // Assembly of the 256x256 / 4-wavefront base GEMM on v_mfma_f32_16x16x32_bf16 for gfx950.
 // The accumulators are not operands: block (i, j) of a wavefront's 8x8 blocks of 16x16 lives in
 // a[4(8i+j) : 4(8i+j)+3] in every template.
-// Main loop operands: %0,%1 A fragment lane offsets for 32-k step 0 / 1 inside an A unit; %2-%9 B
-// fragment lane offsets inside a B unit (K-contiguous W: step 0 / 1 in %2,%3; N-contiguous W: one per
-// 16-column block); %10-%17 / %18-%25 global byte offsets of this lane's eight A / eight B loads per
-// stage; %26,%27 global base of the A / B stage (64-bit SGPR); %28 byte stride of B between stages;
-// %29 number of 64-k stages (>= 1); %30 LDS byte address of the dynamic segment + this wavefront's
-// first load inside a unit (wave * 8192).  LDS: A units at 0/32/64 KiB, B units at 96/128 KiB.
+// Main loop operands: %0-%3 A fragment lane offsets inside an A unit (32-k step 0 first / second
+// read, step 1 first / second read); %4-%11 B fragment lane offsets inside a B unit (K-contiguous W:
+// as for A in %4-%7; N-contiguous W: one per 16-column block); %12-%19 / %20-%27 global byte offsets
+// of this lane's eight A / eight B loads per stage; %28,%29 global base of the A / B stage (64-bit
+// SGPR); %30 byte stride of B between stages; %31 number of 64-k stages (>= 1); %32 LDS byte address
+// of the dynamic segment + this wavefront's first load inside a unit (wave * 8192).  LDS: A units at
+// 0/32/64 KiB, B units at 96/128 KiB.
 // Fixed registers: s80-s91, v{VT}-v255 (fragment sets at v{F[0]} and v{F[1]}), a0-a255.
 #pragma once
 {emit("SYMB_GEMM16_LOOP_NT", build(False))}

@@ -124,6 +124,10 @@ def test_cfg1_tiny_full():
     # wide enough for the 256x256 variant (>= 128 big tiles): M 1500 (ragged), N 6200/K 136
     dict(seed=2, d_in=136, d_out=6208, lens=[700, 5, 795], kinds=[L, I, L], ranks=[16, 8]),
     dict(seed=3, d_in=6208, d_out=136, lens=[700, 5, 795], kinds=[L, I, L], ranks=[16, 8]),
+    # the 256x256 kernel's LoRA steps: ranks that need 1, 2, 3, 4 and 8 steps of 32 extended columns, tiles
+    # that hold several LoRA segments (a step fetched while another one multiplies), odd ranks, K tail
+    dict(seed=9, d_in=200, d_out=6208, lens=[300, 1, 200, 2, 57, 0, 940], kinds=[L, L, I, L, L, L, L], ranks=[128, 40, 5, 64, 16, 24, 33]),
+    dict(seed=10, d_in=6208, d_out=200, lens=[300, 1, 200, 2, 57, 0, 940], kinds=[L, L, N, L, L, L, L], ranks=[128, 40, 5, 64, 16, 24, 33]),
     # all kinds NONE: the paper's plain executor
     dict(seed=4, d_in=256, d_out=512, lens=[100, 156], kinds=[N], ranks=[1]),
     # rank 1, rank 128 (max), rank 100, K tail (d_in not a multiple of 64)
