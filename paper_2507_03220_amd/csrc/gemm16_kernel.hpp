@@ -209,21 +209,22 @@ symb_gemm16_kernel(const GemmParams p) {
         const int k = (lg >> 1) * 8 + (lg & 1) * 4 + (l15 >> 2), n = wn0 + j * 16 + ((l15 & 3) << 2);
         return (unsigned)(lds_off_nmajor16(k, n >> 3) + ((n & 7) << 1));
     };
-    // nks 32-wide k-steps over the register-staged tile
-    auto compute = [&](int nks) __attribute__((always_inline)) {
+    // nks 32-wide k-steps over the register-staged tile; rows: bit i set = this wavefront's 16-row
+    // block i may hold non-zero activation rows
+    auto compute = [&](int nks, unsigned rows) __attribute__((always_inline)) {
         for (int ks = 0; ks < nks; ++ks) {
             const unsigned va0 = lds0 + frag_a(ks, 0), va1 = lds0 + frag_a(ks, 1);
             if constexpr (!NN) {
                 const unsigned vb0 = lds0 + TT::UNIT + frag_b_nt(ks, 0), vb1 = lds0 + TT::UNIT + frag_b_nt(ks, 1);
-                asm volatile(SYMB_GEMM16_KSTEP32_NT : : "v"(va0), "v"(va1), "v"(vb0), "v"(vb1)
-                             : "memory", SYMB_GEMM16_VCLOBBERS, SYMB_GEMM16_ACLOBBERS);
+                asm volatile(SYMB_GEMM16_KSTEP32_NT : : "v"(va0), "v"(va1), "v"(vb0), "v"(vb1), "s"(rows)
+                             : "memory", "scc", SYMB_GEMM16_VCLOBBERS, SYMB_GEMM16_ACLOBBERS);
             } else {
                 unsigned vb[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) vb[j] = lds0 + TT::UNIT + frag_b_nn(j) + ks * 32 * (BN * 2);
                 asm volatile(SYMB_GEMM16_KSTEP32_NN : : "v"(va0), "v"(va1), "v"(vb[0]), "v"(vb[1]), "v"(vb[2]), "v"(vb[3]),
-                             "v"(vb[4]), "v"(vb[5]), "v"(vb[6]), "v"(vb[7])
-                             : "memory", SYMB_GEMM16_VCLOBBERS, SYMB_GEMM16_ACLOBBERS);
+                             "v"(vb[4]), "v"(vb[5]), "v"(vb[6]), "v"(vb[7]), "s"(rows)
+                             : "memory", "scc", SYMB_GEMM16_VCLOBBERS, SYMB_GEMM16_ACLOBBERS);
             }
         }
     };
@@ -283,7 +284,7 @@ symb_gemm16_kernel(const GemmParams p) {
         lds_store_a();
         lds_store_b();
         __syncthreads();
-        compute((p.K - KF * 64 + 31) >> 5);
+        compute((p.K - KF * 64 + 31) >> 5, 0xffu);
         __syncthreads();
     }
 
@@ -401,6 +402,11 @@ symb_gemm16_kernel(const GemmParams p) {
     // the first step went out before the main loop; those of each further step go out before the
     // MFMAs of the step before it.
     while (ext_more) {
+        // this wavefront's 16-row blocks that hold rows of the step's segment (the other rows of the
+        // activation-side tile are zero)
+        const int b_lo = max(e_lo - (m0 + wm0), 0) >> 4, b_hi = min((e_hi - 1 - (m0 + wm0)) >> 4, 7);
+        const unsigned rows = (unsigned)__builtin_amdgcn_readfirstlane(
+            (e_hi > m0 + wm0 && b_lo <= b_hi) ? (int)((0xffu >> (7 - b_hi)) & (0xffu << b_lo)) : 0);
 #pragma unroll
         for (int i = 0; i < EC; ++i) {
             *reinterpret_cast<uint4*>(sA + e_lds0 + i * 8192) = ea[i];
@@ -415,7 +421,7 @@ symb_gemm16_kernel(const GemmParams p) {
             ext_more = ext_seek();
         }
         if (ext_more) ext_load();
-        compute(1);
+        compute(1, rows);
         __syncthreads();
     }
 

@@ -226,16 +226,29 @@ def build(nn, no_loads=False, no_reads=False, no_barrier=False):
 
 
 def build_kstep32(nn):
-    """One 32-wide k-step on a register-staged 64-k tile (K remainder, LoRA term): read the sixteen
-    fragments, wait, 64 MFMAs.  Operands: %0, %1 A fragment addresses (first / second read); B
-    addresses %2, %3 (K-contiguous W) or %2-%9 (N-contiguous W, one per 16-column block); the 32-k
-    half is already in them."""
-    L = []
-    for r in frag_reads(nn, 0, None, None, 0, va=["%0", "%1"], vb=[f"%{2 + j}" for j in range(8)]):
+    """One 32-wide k-step on a register-staged 64-k tile (K remainder, LoRA term): read the
+    fragments, wait, MFMAs.  Operands: %0, %1 A fragment addresses (first / second read); B
+    addresses %2, %3 (K-contiguous W) or %2-%9 (N-contiguous W, one per 16-column block), the 32-k
+    half already in them; last operand (%4 resp. %10): SGPR mask of this wavefront's eight 16-row
+    blocks -- a block whose bit is clear holds only zero rows of the activation-side tile (rows of
+    other segments in a LoRA step), so its reads and MFMAs are skipped."""
+    mask = "%10" if nn else "%4"
+    L = [f"s_cmp_eq_u32 {mask}, 0", "s_cbranch_scc1 19f"]
+    reads = frag_reads(nn, 0, None, None, 0, va=["%0", "%1"], vb=[f"%{2 + j}" for j in range(8)])
+    a_reads, b_reads = reads[:16], reads[16:]          # A: q-major (8 blocks of read 0, then 8 of read 1)
+    for r in b_reads:
         L += r
+    for i in range(8):
+        L += [f"s_bitcmp1_b32 {mask}, {i}", f"s_cbranch_scc0 {20 + i}f"]
+        L += a_reads[i] + a_reads[8 + i]
+        L.append(f"{20 + i}:")
     L.append("s_waitcnt lgkmcnt(0)")
-    L += [mfma(0, i, j) for i, j in BLOCKS]
+    for i in range(8):
+        L += [f"s_bitcmp1_b32 {mask}, {i}", f"s_cbranch_scc0 {30 + i}f"]
+        L += [mfma(0, i, j) for j in range(8)]
+        L.append(f"{30 + i}:")
     L += MFMA_DRAIN
+    L.append("19:")
     return L
 
 
