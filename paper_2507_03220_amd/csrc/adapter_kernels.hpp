@@ -59,13 +59,17 @@ __device__ __forceinline__ void skinny_dot(const bf16* (&lrow)[SKINNY_BLKS], con
 #pragma unroll
             for (int b = 0; b < SKINNY_BLKS; ++b) lv[b][h] = *reinterpret_cast<const uint4*>(lrow[b] + k + h * 32);
     };
-    auto step = [&](const uint4 (&lv)[SKINNY_BLKS][4], int k) __attribute__((always_inline)) {
-        uint4 rv[RB][4];
+    // The memory counter retires loads in order: waiting for the adapter rows of the current slice
+    // also waits for every load issued before them.  So they are requested first and the row data
+    // of the next slice after them: the wait before the MFMAs then leaves that next slice in flight.
+    auto load_r = [&](uint4 (&rv)[RB][4], int k) __attribute__((always_inline)) {
 #pragma unroll
         for (int h = 0; h < 4; ++h)
 #pragma unroll
             for (int j = 0; j < RB; ++j)
                 if (j < nb) rv[j][h] = *reinterpret_cast<const uint4*>(rrow[j] + k + h * 32);
+    };
+    auto mul = [&](const uint4 (&lv)[SKINNY_BLKS][4], const uint4 (&rv)[RB][4]) __attribute__((always_inline)) {
 #pragma unroll
         for (int h = 0; h < 4; ++h)
 #pragma unroll
@@ -77,23 +81,35 @@ __device__ __forceinline__ void skinny_dot(const bf16* (&lrow)[SKINNY_BLKS], con
                         acc[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rf, __builtin_bit_cast(bf16x8, lv[b][h]), acc[b][j], 0, 0, 0);
                 }
     };
+    // Full slices of this wavefront: k0 = wave * 128 + 512 s, s < ns.  The loop body holds no
+    // conditional load, so the compiler's wait counts are exact (a load that may or may not have
+    // been issued makes it wait for everything).
     int k0 = wave * 128;
-    if (k0 + 128 <= K) {
-        uint4 la[SKINNY_BLKS][4], lb[SKINNY_BLKS][4];
+    const int ns = K >= k0 + 128 ? (K - k0 - 128) / 512 + 1 : 0;
+    if (ns > 0) {
+        uint4 la[SKINNY_BLKS][4], lb[SKINNY_BLKS][4], rv[RB][4];
         load_l(la, k0);
-        while (true) {
-            const int k1 = k0 + 512;
-            const bool more1 = k1 + 128 <= K;
-            if (more1) load_l(lb, k1);
-            step(la, k0);
-            k0 = k1;
-            if (!more1) break;
-            const int k2 = k1 + 512;
-            const bool more2 = k2 + 128 <= K;
-            if (more2) load_l(la, k2);
-            step(lb, k1);
-            k0 = k2;
-            if (!more2) break;
+        int s = 0;
+        for (; s + 2 < ns; s += 2) {                   // two slices per trip, each with its successor requested first
+            load_r(rv, k0);
+            load_l(lb, k0 + 512);
+            mul(la, rv);
+            load_r(rv, k0 + 512);
+            load_l(la, k0 + 1024);
+            mul(lb, rv);
+            k0 += 1024;
+        }
+        if (ns - s == 2) {
+            load_r(rv, k0);
+            load_l(lb, k0 + 512);
+            mul(la, rv);
+            load_r(rv, k0 + 512);
+            mul(lb, rv);
+            k0 += 1024;
+        } else {
+            load_r(rv, k0);
+            mul(la, rv);
+            k0 += 512;
         }
     }
     for (; k0 < K; k0 += 512) {                        // the slice that crosses the end of K
