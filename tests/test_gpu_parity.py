@@ -130,6 +130,7 @@ def test_cfg1_tiny_full():
     dict(seed=10, d_in=6208, d_out=200, lens=[300, 1, 200, 2, 57, 0, 940], kinds=[L, L, N, L, L, L, L], ranks=[128, 40, 5, 64, 16, 24, 33]),
     # the 256x256 kernel on one partial row tile and 129 column tiles, the last of them 8 columns wide
     dict(seed=11, d_in=136, d_out=32776, lens=[100, 1, 49], kinds=[L, I, L], ranks=[16, 8, 40]),
+    dict(seed=12, d_in=32776, d_out=136, lens=[100, 1, 49], kinds=[L, N, L], ranks=[16, 8, 40]),      # the same in the input gradient
     # all kinds NONE: the paper's plain executor
     dict(seed=4, d_in=256, d_out=512, lens=[100, 156], kinds=[N], ranks=[1]),
     # rank 1, rank 128 (max), rank 100, K tail (d_in not a multiple of 64)
