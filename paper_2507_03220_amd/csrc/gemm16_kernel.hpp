@@ -97,7 +97,6 @@ symb_gemm16_kernel(const GemmParams p) {
     const bf16* const b_tile = NN ? (p.Bop + n0) : (p.Bop + (size_t)n0 * p.K);
     const unsigned lds0 = (unsigned)(size_t)smem;          // LDS byte address of the dynamic segment
 
-
     // ---- register-staged 64-k tile (K remainder, LoRA term).  Chunk i of a thread sits 32 rows
     // (K-contiguous tiles) or 8 k-rows (N-contiguous weight tile) below chunk 0.
     constexpr int RSTEP = NT / 8, KSTEP = NT / (BN / 8);
