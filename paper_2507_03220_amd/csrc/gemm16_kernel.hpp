@@ -190,7 +190,6 @@ symb_gemm16_kernel(const GemmParams p) {
     bool ext_more = p.ext != nullptr && ext_seek();
     if (ext_more) ext_load();
 
-    asm volatile(SYMB_GEMM16_ZERO ::: SYMB_GEMM16_ACLOBBERS);
 
     // Lane byte offsets of the MFMA fragments of 32-k step ks inside an operand's 64-k tile.  Lane
     // group g = l/16 holds row l%16 and k = 32 ks + 16 q + 8 (g/2) + 4 (g%2) + 0..3, q = 0, 1 (one
@@ -230,6 +229,7 @@ symb_gemm16_kernel(const GemmParams p) {
 
     // ---- main loop over the full 64-k stages (gemm16_asm.hpp)
     const int KF = p.K / 64;
+    if (KF == 0) asm volatile(SYMB_GEMM16_ZERO ::: SYMB_GEMM16_ACLOBBERS);   // otherwise the main loop zeroes them
     if (KF > 0) {
         unsigned vA[4], vB[8];
 #pragma unroll

@@ -205,6 +205,7 @@ def build(nn, no_loads=False, no_reads=False, no_barrier=False):
         for which, sd in (("A", sa), ("B", sb)):
             L += unit_loads_flat(sd, which, range(8))
             L += advance(which, cond=1) if n == 0 else advance(which)
+    L += build_zero()                                  # while the first two stages are on their way
     L += ["s_waitcnt vmcnt(16)", "s_barrier"]
     for r in frag_reads(nn, 0, S_ACUR, S_BCUR, 0):
         L += r
@@ -296,6 +297,8 @@ def main():
 // SGPR); %30 byte stride of B between stages; %31 number of 64-k stages (>= 1); %32 LDS byte address
 // of the dynamic segment + this wavefront's first load inside a unit (wave * 8192).  LDS: A units at
 // 0/32/64 KiB, B units at 96/128 KiB.
+// The main loop zeroes the accumulators itself (after issuing its first loads); SYMB_GEMM16_ZERO is
+// for a K extent without a single full stage.
 // Fixed registers: s80-s91, v{VT}-v255 (fragment sets at v{F[0]} and v{F[1]}), a0-a255.
 #pragma once
 {emit("SYMB_GEMM16_LOOP_NT", build(False))}

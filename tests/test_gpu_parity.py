@@ -505,10 +505,11 @@ def test_per_segment_buffers(case):
     assert e.value.status == sb.SYMB_ERR_UNSUPPORTED
 
 
-@pytest.mark.parametrize("d_in", [64, 72, 128, 192, 200, 320])
+@pytest.mark.parametrize("d_in", [40, 64, 72, 128, 192, 200, 320])
 def test_large_tile_kernel_with_one_to_five_k_stages(d_in):
     """The 256x256 kernel's main loop has a prologue, a steady loop and two closing stages: shapes with
-    1, 2, 3 and 5 full 64-k stages, with and without a K remainder, wide enough to select that kernel."""
+    0 (remainder only), 1, 2, 3 and 5 full 64-k stages, with and without a K remainder, wide enough to select
+    that kernel."""
     p = make_problem(70 + d_in, d_in, 6208, [700, 5, 795], [L, N, I], [16])
     oads, off = oracle_ads(p["ads"]), p["off"]
     Y, Yb = gh.forward(off, p["ads"], p["X"], p["W"], p["bias"], want_base=True)
