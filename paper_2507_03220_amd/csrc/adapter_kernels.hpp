@@ -391,11 +391,14 @@ symb_lora_grad_kernel(const GradParams p) {
 #pragma unroll
         for (int j = 0; j < RB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    // R tile: 32 rows x 16 chunks of 8 columns = 512 chunks, 2 per thread.  L tile: 32 x (rpad/8) chunks.
+    // R tile: 32 rows x 16 chunks of 8 columns = 512 chunks, 2 per thread.  L tile: 32 x (rpad/4) chunks,
+    // at most NLC per thread.  The chunks of the next 32 tokens are requested right after this step's
+    // chunks went to LDS, so they travel while this step multiplies.
+    constexpr int NLC = (GRAD_TT * 4 * RB + 255) / 256;
     const int lw = sd.rpad >> 2;                       // 16-byte chunks per L row: 2 * rpad bf16
     const int l_chunks = GRAD_TT * lw;
-    for (int t0 = t_lo; t0 < t_hi; t0 += GRAD_TT) {
-        uint4 rr[2];
+    uint4 rr[2], lv[NLC];
+    auto fetch = [&](int t0) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int c = tid + i * 256, tr = c >> 4, cc = c & 15;
@@ -403,19 +406,28 @@ symb_lora_grad_kernel(const GradParams p) {
             rr[i] = make_uint4(0u, 0u, 0u, 0u);
             if (ok) rr[i] = *reinterpret_cast<const uint4*>(rbase + (size_t)(t0 + tr) * p.ncols + c0 + cc * 8);
         }
+#pragma unroll
+        for (int i = 0; i < NLC; ++i) {
+            const int c = tid + i * 256, tr = c / lw, pc = c % lw;
+            lv[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (c < l_chunks && (t0 + tr) < t_hi) lv[i] = *reinterpret_cast<const uint4*>(p.L + (size_t)(t0 + tr) * p.l_pitch + pc * 8);
+        }
+    };
+    if (t_lo < t_hi) fetch(t_lo);
+    for (int t0 = t_lo; t0 < t_hi; t0 += GRAD_TT) {
         __syncthreads();     // previous step's LDS reads are done
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int c = tid + i * 256, tr = c >> 4, cc = c & 15;
             *reinterpret_cast<uint4*>(sR + tr * GRAD_RPITCH + cc * 16) = rr[i];
         }
-        for (int c = tid; c < l_chunks; c += 256) {
-            const int tr = c / lw, pc = c % lw;
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if ((t0 + tr) < t_hi) v = *reinterpret_cast<const uint4*>(p.L + (size_t)(t0 + tr) * p.l_pitch + pc * 8);
-            *reinterpret_cast<uint4*>(sL + tr * LP + pc * 16) = v;
+#pragma unroll
+        for (int i = 0; i < NLC; ++i) {
+            const int c = tid + i * 256, tr = c / lw, pc = c % lw;
+            if (c < l_chunks) *reinterpret_cast<uint4*>(sL + tr * LP + pc * 16) = lv[i];
         }
         __syncthreads();
+        if (t0 + GRAD_TT < t_hi) fetch(t0 + GRAD_TT);
         bf16x8 rf[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) rf[i] = lds_read_tr_16x32(sR, GRAD_RPITCH, wave * 32 + i * 16, lane);
