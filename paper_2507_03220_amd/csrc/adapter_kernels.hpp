@@ -52,7 +52,6 @@ __device__ __forceinline__ void skinny_dot(const bf16* (&lrow)[SKINNY_BLKS], con
     // Each wavefront takes every 4th 128-element slice of K (256 bytes per row per step).  The
     // row data (the HBM stream) of the next slice is requested before the current slice is
     // multiplied, so a wavefront always has 8 KiB of it in flight; the adapter rows come from L2.
-    const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
     auto load_l = [&](uint4 (&lv)[SKINNY_BLKS][4], int k) __attribute__((always_inline)) {
 #pragma unroll
         for (int h = 0; h < 4; ++h)
@@ -75,7 +74,7 @@ __device__ __forceinline__ void skinny_dot(const bf16* (&lrow)[SKINNY_BLKS], con
 #pragma unroll
             for (int j = 0; j < RB; ++j)
                 if (j < nb) {
-                    const bf16x8 rf = __builtin_bit_cast(bf16x8, r_ok[j] ? rv[j][h] : zero4);
+                    const bf16x8 rf = __builtin_bit_cast(bf16x8, r_ok[j] ? rv[j][h] : make_uint4(0u, 0u, 0u, 0u));
 #pragma unroll
                     for (int b = 0; b < SKINNY_BLKS; ++b)
                         acc[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rf, __builtin_bit_cast(bf16x8, lv[b][h]), acc[b][j], 0, 0, 0);
@@ -118,11 +117,11 @@ __device__ __forceinline__ void skinny_dot(const bf16* (&lrow)[SKINNY_BLKS], con
             const bool kok = (k0 + h * 32 + kq * 8) < K;
             uint4 lv[SKINNY_BLKS];
 #pragma unroll
-            for (int b = 0; b < SKINNY_BLKS; ++b) lv[b] = kok ? *reinterpret_cast<const uint4*>(lrow[b] + k0 + h * 32) : zero4;
+            for (int b = 0; b < SKINNY_BLKS; ++b) lv[b] = kok ? *reinterpret_cast<const uint4*>(lrow[b] + k0 + h * 32) : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
             for (int j = 0; j < RB; ++j)
                 if (j < nb) {
-                    const uint4 rv = (kok && r_ok[j]) ? *reinterpret_cast<const uint4*>(rrow[j] + k0 + h * 32) : zero4;
+                    const uint4 rv = (kok && r_ok[j]) ? *reinterpret_cast<const uint4*>(rrow[j] + k0 + h * 32) : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
                     for (int b = 0; b < SKINNY_BLKS; ++b)
                         acc[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rv), __builtin_bit_cast(bf16x8, lv[b]), acc[b][j], 0, 0, 0);

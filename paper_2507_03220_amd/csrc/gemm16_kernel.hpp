@@ -295,13 +295,12 @@ symb_gemm16_kernel(const GemmParams p) {
         } else if constexpr (!PLAIN) {
             // bias of this lane's 8 column quads, once; IA3 vector and noise effect of each row's own
             // segment per row block
-            const uint2 zero2 = make_uint2(0u, 0u);
             const int nq0 = n0 + wn0 + lg * 4;
             uint2 bv[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int n = nq0 + j * 16;
-                bv[j] = (p.bias && n < p.N) ? *reinterpret_cast<const uint2*>(p.bias + n) : zero2;
+                bv[j] = (p.bias && n < p.N) ? *reinterpret_cast<const uint2*>(p.bias + n) : make_uint2(0u, 0u);
             }
             static_for<0, 8>([&](auto I) __attribute__((always_inline)) {
                 constexpr int i = decltype(I)::value;
@@ -320,7 +319,7 @@ symb_gemm16_kernel(const GemmParams p) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const int n = nq0 + j * 16;
-                    nv[j] = (nrow && n < p.N) ? *reinterpret_cast<const uint2*>(nrow + n) : zero2;
+                    nv[j] = (nrow && n < p.N) ? *reinterpret_cast<const uint2*>(nrow + n) : make_uint2(0u, 0u);
                     lv[j] = (lrow && n < p.N) ? *reinterpret_cast<const uint2*>(lrow + n) : make_uint2(0x3f803f80u, 0x3f803f80u);
                 }
                 static_for<0, 8>([&](auto J) __attribute__((always_inline)) {

@@ -409,7 +409,6 @@ symb_gemm_kernel(const GemmParams p) {
             });
         } else {
             // bias of this lane's 16 column quads, once; IA3 vector of each row's own segment per row block
-            const uint2 zero2 = make_uint2(0u, 0u);
             const int nq0 = n0 + wn0 + ((lane >> 5) << 2);
             uint2 bv[NB][4];
 #pragma unroll
@@ -417,7 +416,7 @@ symb_gemm_kernel(const GemmParams p) {
 #pragma unroll
                 for (int rg = 0; rg < 4; ++rg) {
                     const int n = nq0 + j * 32 + rg * 8;
-                    bv[j][rg] = (p.bias && n < p.N) ? *reinterpret_cast<const uint2*>(p.bias + n) : zero2;
+                    bv[j][rg] = (p.bias && n < p.N) ? *reinterpret_cast<const uint2*>(p.bias + n) : make_uint2(0u, 0u);
                 }
 #pragma unroll
             for (int i = 0; i < MB; ++i) {
@@ -438,7 +437,7 @@ symb_gemm_kernel(const GemmParams p) {
 #pragma unroll
                     for (int rg = 0; rg < 4; ++rg) {
                         const int n = nq0 + j * 32 + rg * 8;
-                        nv[j][rg] = (nrow && n < p.N) ? *reinterpret_cast<const uint2*>(nrow + n) : zero2;
+                        nv[j][rg] = (nrow && n < p.N) ? *reinterpret_cast<const uint2*>(nrow + n) : make_uint2(0u, 0u);
                     }
 #pragma unroll
                 for (int j = 0; j < NB; ++j)
