@@ -122,6 +122,22 @@ __device__ __forceinline__ bf16x8 lds_read_frag_nmajor(const unsigned char* buf,
     return __builtin_bit_cast(bf16x8, v);
 }
 
+// The same fragment, requested without the compiler knowing it is an LDS read: lo / hi are valid only
+// after a later s_waitcnt lgkmcnt(0).  For the main loop, whose stages arrive by LDS DMA
+// (global_load_lds): there the compiler makes every transposing LDS read (an intrinsic without
+// memory operands) wait for all DMA loads in flight, the next stages' included, which serialises
+// the loop on memory latency.  The loop's own waits and barriers already order these reads after
+// the DMA of their stage.
+template <int BN>
+__device__ __forceinline__ void lds_request_frag_nmajor(const unsigned char* buf, int nb, int k16, int lane, uint2& lo, uint2& hi) {
+    const int g = lane >> 4, jj = lane & 15;
+    const int n = nb + ((g & 1) << 4) + ((jj & 3) << 2);
+    const int k = k16 + ((g >> 1) << 3) + (jj >> 2);
+    const unsigned a = (unsigned)(size_t)(buf + lds_off_nmajor<BN>(k, n >> 3) + ((n & 7) << 1));
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(a));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(a), "n"(4 * BN * 2));   // 4 k-rows down: same swizzle
+}
+
 __device__ __forceinline__ uint4 ld_global_16(const bf16* p, bool ok) {
     uint4 v = make_uint4(0u, 0u, 0u, 0u);
     if (ok) v = *reinterpret_cast<const uint4*>(p);
@@ -283,7 +299,9 @@ symb_gemm_kernel(const GemmParams p) {
             else wb[set][j] = lds_read_frag_nmajor<BN>(bufB, wn0 + j * 32, ks * 16, lane);
         }
     };
-    // from a 32-k main-loop stage
+    // from a 32-k main-loop stage.  N-contiguous weight: the fragments are only requested here
+    // (halves in wlo / whi); settle(set) waits for them and puts them together.
+    uint2 wlo[2][NB], whi[2][NB];
     auto load_frags32 = [&](int stage, int ks, int set) __attribute__((always_inline)) {
         const unsigned char* bufA = smem + stage * TT::STAGE_BYTES;
         const unsigned char* bufB = bufA + TT::A_STAGE;
@@ -293,7 +311,19 @@ symb_gemm_kernel(const GemmParams p) {
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
             if constexpr (!NN) wb[set][j] = lds_read_frag_k32(bufB, wn0 + j * 32 + (lane & 31), ks * 2 + (lane >> 5));
-            else wb[set][j] = lds_read_frag_nmajor<BN>(bufB, wn0 + j * 32, ks * 16, lane);
+            else lds_request_frag_nmajor<BN>(bufB, wn0 + j * 32, ks * 16, lane, wlo[set][j], whi[set][j]);
+        }
+    };
+    auto settle = [&](int set) __attribute__((always_inline)) {
+        if constexpr (NN) {
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wlo[set][0]), "+v"(whi[set][0]));
+#pragma unroll
+            for (int j = 1; j < NB; ++j) asm volatile("" : "+v"(wlo[set][j]), "+v"(whi[set][j]));   // valid from here on as well
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                const uint4 v = make_uint4(wlo[set][j].x, wlo[set][j].y, whi[set][j].x, whi[set][j].y);
+                wb[set][j] = __builtin_bit_cast(bf16x8, v);
+            }
         }
     };
     auto mfma_set = [&](int set) __attribute__((always_inline)) {
@@ -349,17 +379,20 @@ symb_gemm_kernel(const GemmParams p) {
         int stage = 0;
         for (int kt = 0; kt < KF; ++kt) {
             const int nxt = (stage + 1 == NS) ? 0 : stage + 1;
+            settle(0);
             load_frags32(stage, 1, 1);
             mfma_set(0);
             interleave_hint();
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(VM_STEADY) & lgkmcnt0_mask());
             __builtin_amdgcn_s_barrier();
             stage_issue(stage, min(kt + NS, KF - 1));
+            settle(1);
             load_frags32(nxt, 0, 0);
             mfma_set(1);
             interleave_hint();
             stage = nxt;
         }
+        settle(0);                                             // the last iteration's request for a stage nobody multiplies
         __builtin_amdgcn_s_waitcnt(0);                         // everything landed before LDS is reused
         __builtin_amdgcn_s_barrier();
 #ifdef SYMB_GEMM_TRACE
