@@ -193,6 +193,20 @@ def test_stateless_and_deterministic():
             assert torch.equal(d1.dB, d2.dB)
 
 
+@pytest.mark.parametrize("dims", [(136, 6208), (6208, 136)])
+def test_large_tile_kernel_is_deterministic(dims):
+    """The 256x256 kernel (forward for the first shape, input gradient for the second): two runs of the
+    same call, with another call in between, give the same bits."""
+    d_in, d_out = dims
+    p = make_problem(13, d_in, d_out, [700, 5, 795], [L, I, L], [16, 40])
+    y1 = gh.bf16_bits(gh.forward(p["off"], p["ads"], p["X"], p["W"], p["bias"])[0])
+    x1 = gh.bf16_bits(gh.backward_input(p["off"], p["ads"], p["dY"], p["W"]))
+    y2 = gh.bf16_bits(gh.forward(p["off"], p["ads"], p["X"], p["W"], p["bias"])[0])
+    x2 = gh.bf16_bits(gh.backward_input(p["off"], p["ads"], p["dY"], p["W"]))
+    np.testing.assert_array_equal(y1, y2)
+    np.testing.assert_array_equal(x1, x2)
+
+
 def test_backward_batch_is_independent_of_forward_batch():
     """Backward on a regrouped subset of the forward clients gives the same rows (bitwise)."""
     p = make_problem(12, 264, 320, [130, 1, 77, 300], [L, I, L, N], [8, 16])
