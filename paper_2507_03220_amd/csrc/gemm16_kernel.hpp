@@ -1,4 +1,8 @@
-// The 256x256-tile base GEMM on v_mfma_f32_16x16x32_bf16 (4 wavefronts, each 128x128 of C).
+// The base GEMM on v_mfma_f32_16x16x32_bf16: 4 wavefronts (2x2), each NBLK x NBLK blocks of 16x16 of C.
+// NBLK = 8: 256x256 tile of the workgroup, all 256 accumulation registers per wavefront, 160 KiB of
+// LDS, for launches with enough such tiles to fill the chip.  NBLK = 4: 128x128 tile, 64 accumulation
+// registers, 80 KiB of LDS, two workgroups per CU, for everything smaller.  The text below describes
+// the 256x256 case; the 128x128 one is the same code with half the extents.
 //
 // Computes what symb_gemm_kernel computes (gemm_kernel.hpp: the frozen weight's product with the
 // LoRA term of each row's segment fused in as extra k-steps, bias / IA3 scale / noise effect in
@@ -20,20 +24,24 @@
 
 namespace symb {
 
+template <int NBLK>
 struct Gemm16Tile {
-    static constexpr int BM = 256, BN = 256, NT = 256, BK = 64;
-    static constexpr int UNIT = 32768;                   // one operand's 64-k stage
+    static_assert(NBLK == 8 || NBLK == 4, "256x256 or 128x128 tile");
+    static constexpr int BM = 32 * NBLK, BN = 32 * NBLK, NT = 256, BK = 64;
+    static constexpr int WT = 16 * NBLK;                 // rows and columns of a wavefront's part
+    static constexpr int UNIT = BM * 128;                // one operand's 64-k stage
     static constexpr int C_PITCH = BN * 2 + 16, C_BYTES = BM * C_PITCH;
     static constexpr int SMEM = 5 * UNIT;                // three A units, two B units
     static_assert(C_BYTES <= SMEM, "the staged output tile must fit the ring");
 };
 
-// N-contiguous weight unit: [64 k][256 n] bf16, 512 B per k-row, 16-byte chunk nc of row k stored
-// at nc ^ swz.  The transposing read of one 16-lane group fetches 4 k-rows x 32 B: the (k & 3)
-// term lays those side by side (128 B), the (k >> 2) term moves the next group (4 k-rows further)
-// to the other half of the banks.
+// N-contiguous weight unit: [64 k][BN n] bf16, 16-byte chunk nc of row k stored at nc ^ swz.  The
+// transposing read of one 16-lane group fetches 4 k-rows x 32 B: the (k & 3) term lays those side
+// by side (128 B), the (k >> 2) term moves the next group (4 k-rows further) to the other half of
+// the banks.
 __device__ __forceinline__ int swz_nmajor16(int k) { return ((k & 3) << 1) ^ (((k >> 2) & 1) << 3); }
-__device__ __forceinline__ int lds_off_nmajor16(int k, int nc) { return k * 512 + ((nc ^ swz_nmajor16(k)) << 4); }
+template <int BN>
+__device__ __forceinline__ int lds_off_nmajor16(int k, int nc) { return k * (BN * 2) + ((nc ^ swz_nmajor16(k)) << 4); }
 
 template <int I0, int I1, class F>
 __device__ __forceinline__ void static_for(F&& f) {
@@ -53,11 +61,11 @@ __device__ __forceinline__ void acc16_read4(float& v0, float& v1, float& v2, flo
 }
 
 // PLAIN: no bias, no IA3 scale, no noise effect, no pre-adapter output (checked by the host).
-template <bool NN, bool PLAIN>
+template <int NBLK, bool NN, bool PLAIN>
 __global__ void __launch_bounds__(256)
 symb_gemm16_kernel(const GemmParams p) {
-    using TT = Gemm16Tile;
-    constexpr int BM = TT::BM, BN = TT::BN, NT = TT::NT, CP = TT::C_PITCH;
+    using TT = Gemm16Tile<NBLK>;
+    constexpr int BM = TT::BM, BN = TT::BN, NT = TT::NT, CP = TT::C_PITCH, WT = TT::WT;
     constexpr int CA = BM * 8 / NT, CB = BN * 8 / NT;      // 16-byte chunks per thread of a register-staged tile
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char* const sA = smem;                        // register-staged tiles (K remainder, LoRA term)
@@ -85,7 +93,7 @@ symb_gemm16_kernel(const GemmParams p) {
     if (p.trace && threadIdx.x == 0) { p.trace[(size_t)lin * 16 + 0] = __builtin_amdgcn_s_memrealtime(); p.trace[(size_t)lin * 16 + 5] = __builtin_readcyclecounter(); }
 #endif
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 128;
+    const int wm0 = (wave >> 1) * WT, wn0 = (wave & 1) * WT;
     const int l15 = lane & 15, lg = lane >> 4;
     const int seg_lo = p.tile_seg_lo[tm], seg_hi = p.tile_seg_hi[tm];
     auto a_row = [&](int m) __attribute__((always_inline)) -> const bf16* {
@@ -98,12 +106,12 @@ symb_gemm16_kernel(const GemmParams p) {
     const unsigned lds0 = (unsigned)(size_t)smem;          // LDS byte address of the dynamic segment
 
     // ---- register-staged 64-k tile (K remainder, LoRA term).  Chunk i of a thread sits 32 rows
-    // (K-contiguous tiles) or 8 k-rows (N-contiguous weight tile) below chunk 0.
+    // (K-contiguous tiles) or KSTEP k-rows (N-contiguous weight tile) below chunk 0.
     constexpr int RSTEP = NT / 8, KSTEP = NT / (BN / 8);
     const int lrow = tid >> 3, lkc = (tid & 7) * 8;
     const int nn_k = tid / (BN / 8), nn_nc = tid % (BN / 8);
     const int a_lds0 = lds_off_kmajor(lrow, tid & 7);
-    const int b_lds0 = NN ? lds_off_nmajor16(nn_k, nn_nc) : a_lds0;
+    const int b_lds0 = NN ? lds_off_nmajor16<BN>(nn_k, nn_nc) : a_lds0;
     uint4 ra[CA], rb[CB];
     auto lds_store_a = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -136,7 +144,7 @@ symb_gemm16_kernel(const GemmParams p) {
     // (segment es, first extended column ekc); ext_seek moves es to the next LoRA segment with rows
     // in this tile, ext_load fetches the step.  The first step is fetched here, so that its latency
     // hides under the main loop.
-    constexpr int EC = 4;
+    constexpr int EC = BM / 64;                              // 16-byte chunks per thread of a 32-k tile
     const int e_lds0 = lds_off_kmajor(tid >> 2, tid & 3);   // K-contiguous 32-k tile: chunk i sits 64 rows below chunk 0
     uint4 ea[EC], eb[EC];
     int es = seg_lo, ekc = 0, e_lo = 0, e_hi = 0;
@@ -205,7 +213,7 @@ symb_gemm16_kernel(const GemmParams p) {
     };
     auto frag_b_nn = [&](int j) __attribute__((always_inline)) {
         const int k = (lg >> 1) * 8 + (lg & 1) * 4 + (l15 >> 2), n = wn0 + j * 16 + ((l15 & 3) << 2);
-        return (unsigned)(lds_off_nmajor16(k, n >> 3) + ((n & 7) << 1));
+        return (unsigned)(lds_off_nmajor16<BN>(k, n >> 3) + ((n & 7) << 1));
     };
     // nks 32-wide k-steps over the register-staged tile; rows: bit i set = this wavefront's 16-row
     // block i may hold non-zero activation rows
@@ -214,47 +222,64 @@ symb_gemm16_kernel(const GemmParams p) {
             const unsigned va0 = lds0 + frag_a(ks, 0), va1 = lds0 + frag_a(ks, 1);
             if constexpr (!NN) {
                 const unsigned vb0 = lds0 + TT::UNIT + frag_b_nt(ks, 0), vb1 = lds0 + TT::UNIT + frag_b_nt(ks, 1);
-                asm volatile(SYMB_GEMM16_KSTEP32_NT : : "v"(va0), "v"(va1), "v"(vb0), "v"(vb1), "s"(rows)
-                             : "memory", "scc", SYMB_GEMM16_VCLOBBERS, SYMB_GEMM16_ACLOBBERS);
+                if constexpr (NBLK == 8)
+                    asm volatile(SYMB_GEMM16_KSTEP32_NT : : "v"(va0), "v"(va1), "v"(vb0), "v"(vb1), "s"(rows)
+                                 : "memory", "scc", SYMB_GEMM16_VCLOBBERS, SYMB_GEMM16_ACLOBBERS);
+                else
+                    asm volatile(SYMB_GEMM16S_KSTEP32_NT : : "v"(va0), "v"(va1), "v"(vb0), "v"(vb1), "s"(rows)
+                                 : "memory", "scc", SYMB_GEMM16S_VCLOBBERS, SYMB_GEMM16S_ACLOBBERS);
             } else {
-                unsigned vb[8];
+                unsigned vb[NBLK];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) vb[j] = lds0 + TT::UNIT + frag_b_nn(j) + ks * 32 * (BN * 2);
-                asm volatile(SYMB_GEMM16_KSTEP32_NN : : "v"(va0), "v"(va1), "v"(vb[0]), "v"(vb[1]), "v"(vb[2]), "v"(vb[3]),
-                             "v"(vb[4]), "v"(vb[5]), "v"(vb[6]), "v"(vb[7]), "s"(rows)
-                             : "memory", "scc", SYMB_GEMM16_VCLOBBERS, SYMB_GEMM16_ACLOBBERS);
+                for (int j = 0; j < NBLK; ++j) vb[j] = lds0 + TT::UNIT + frag_b_nn(j) + ks * 32 * (BN * 2);
+                if constexpr (NBLK == 8)
+                    asm volatile(SYMB_GEMM16_KSTEP32_NN : : "v"(va0), "v"(va1), "v"(vb[0]), "v"(vb[1]), "v"(vb[2]), "v"(vb[3]),
+                                 "v"(vb[4]), "v"(vb[5]), "v"(vb[6]), "v"(vb[7]), "s"(rows)
+                                 : "memory", "scc", SYMB_GEMM16_VCLOBBERS, SYMB_GEMM16_ACLOBBERS);
+                else
+                    asm volatile(SYMB_GEMM16S_KSTEP32_NN : : "v"(va0), "v"(va1), "v"(vb[0]), "v"(vb[1]), "v"(vb[2]), "v"(vb[3]), "s"(rows)
+                                 : "memory", "scc", SYMB_GEMM16S_VCLOBBERS, SYMB_GEMM16S_ACLOBBERS);
             }
         }
     };
 
     // ---- main loop over the full 64-k stages (gemm16_asm.hpp)
     const int KF = p.K / 64;
-    if (KF == 0) asm volatile(SYMB_GEMM16_ZERO ::: SYMB_GEMM16_ACLOBBERS);   // otherwise the main loop zeroes them
+    if (KF == 0) {                                         // otherwise the main loop zeroes them
+        if constexpr (NBLK == 8) asm volatile(SYMB_GEMM16_ZERO ::: SYMB_GEMM16_ACLOBBERS);
+        else asm volatile(SYMB_GEMM16S_ZERO ::: SYMB_GEMM16S_ACLOBBERS);
+    }
     if (KF > 0) {
-        unsigned vA[4], vB[8];
+        constexpr int NVB = NBLK > 4 ? NBLK : 4;
+        unsigned vA[4], vB[NVB];
 #pragma unroll
         for (int j = 0; j < 4; ++j) vA[j] = lds0 + frag_a(j >> 1, j & 1);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) vB[j] = lds0 + (NN ? frag_b_nn(j) : frag_b_nt((j >> 1) & 1, j & 1));
-        // Global byte offsets of this lane's eight loads per operand and stage.  One load instruction
-        // fills 1 KiB of consecutive LDS: 8 rows of a K-contiguous unit or 2 k-rows of the
+        for (int j = 0; j < NVB; ++j) vB[j] = lds0 + (NN ? frag_b_nn(j % NBLK) : frag_b_nt((j >> 1) & 1, j & 1));
+        // Global byte offsets of this lane's NBLK loads per operand and stage.  One load instruction
+        // fills 1 KiB of consecutive LDS: 8 rows of a K-contiguous unit or 1024 / (2 BN) k-rows of the
         // N-contiguous unit; the lane -> chunk map is the inverse of the LDS swizzle.  Rows / columns
         // outside the problem are clamped onto the last valid one and never stored.
-        unsigned ab[8], bb[8];
+        unsigned ab[NBLK], bb[NBLK];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int row = (wave * 8 + j) * 8 + (lane >> 3), kc = (lane & 7) ^ swz_row(row);
+        for (int j = 0; j < NBLK; ++j) {
+            const int row = (wave * NBLK + j) * 8 + (lane >> 3), kc = (lane & 7) ^ swz_row(row);
             ab[j] = ((unsigned)(a_row(min(m0 + row, p.M - 1)) - a_tile) + kc * 8) * 2u;
             if constexpr (!NN) {
                 bb[j] = ((unsigned)(min(n0 + row, p.N - 1) - n0) * (unsigned)p.K + kc * 8) * 2u;
             } else {
-                const int krow = (wave * 8 + j) * 2 + (lane >> 5), nc = (lane & 31) ^ swz_nmajor16(krow);
+                constexpr int CPR = BN / 8;                     // 16-byte chunks per k-row
+                const int krow = (wave * NBLK + j) * (64 / CPR) + lane / CPR, nc = (lane % CPR) ^ swz_nmajor16(krow);
                 bb[j] = ((unsigned)krow * (unsigned)p.N + (unsigned)min(nc * 8, p.N - 8 - n0)) * 2u;
             }
         }
         const unsigned long long ga = (unsigned long long)a_tile, gb = (unsigned long long)b_tile;
         const unsigned stride_b = NN ? 128u * (unsigned)p.N : 128u;
-        const unsigned swa = (unsigned)__builtin_amdgcn_readfirstlane((int)lds0 + wave * 8192);
+        const unsigned swa = (unsigned)__builtin_amdgcn_readfirstlane((int)lds0 + wave * (1024 * NBLK));
+#ifdef SYMB_GEMM_TRACE
+        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 1] = __builtin_amdgcn_s_memrealtime();
+#endif
+        if constexpr (NBLK == 8) {
 #define SYMB_GEMM16_LOOP_OPERANDS                                                                                   \
     :                                                                                                              \
     : "v"(vA[0]), "v"(vA[1]), "v"(vA[2]), "v"(vA[3]), "v"(vB[0]), "v"(vB[1]), "v"(vB[2]), "v"(vB[3]), "v"(vB[4]),  \
@@ -262,17 +287,25 @@ symb_gemm16_kernel(const GemmParams p) {
       "v"(bb[0]), "v"(bb[1]), "v"(bb[2]), "v"(bb[3]), "v"(bb[4]), "v"(bb[5]), "v"(bb[6]), "v"(bb[7]),              \
       "s"(ga), "s"(gb), "s"(stride_b), "s"(KF), "s"(swa)                                                           \
     : "memory", "scc", SYMB_GEMM16_SCLOBBERS, SYMB_GEMM16_VCLOBBERS, SYMB_GEMM16_ACLOBBERS
-#ifdef SYMB_GEMM_TRACE
-        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 1] = __builtin_amdgcn_s_memrealtime();
-#endif
-        if constexpr (NN) asm volatile(SYMB_GEMM16_LOOP_NN SYMB_GEMM16_LOOP_OPERANDS);
+            if constexpr (NN) asm volatile(SYMB_GEMM16_LOOP_NN SYMB_GEMM16_LOOP_OPERANDS);
 #ifdef SYMB_GEMM_PROBE
-        else if (p.probe == 1) asm volatile(SYMB_GEMM16_LOOP_NT_NOLOAD SYMB_GEMM16_LOOP_OPERANDS);
-        else if (p.probe == 2) asm volatile(SYMB_GEMM16_LOOP_NT_NOREAD SYMB_GEMM16_LOOP_OPERANDS);
-        else if (p.probe == 5) asm volatile(SYMB_GEMM16_LOOP_NT_NOBAR SYMB_GEMM16_LOOP_OPERANDS);
+            else if (p.probe == 1) asm volatile(SYMB_GEMM16_LOOP_NT_NOLOAD SYMB_GEMM16_LOOP_OPERANDS);
+            else if (p.probe == 2) asm volatile(SYMB_GEMM16_LOOP_NT_NOREAD SYMB_GEMM16_LOOP_OPERANDS);
+            else if (p.probe == 5) asm volatile(SYMB_GEMM16_LOOP_NT_NOBAR SYMB_GEMM16_LOOP_OPERANDS);
 #endif
-        else asm volatile(SYMB_GEMM16_LOOP_NT SYMB_GEMM16_LOOP_OPERANDS);
+            else asm volatile(SYMB_GEMM16_LOOP_NT SYMB_GEMM16_LOOP_OPERANDS);
 #undef SYMB_GEMM16_LOOP_OPERANDS
+        } else {
+#define SYMB_GEMM16S_LOOP_OPERANDS                                                                                  \
+    :                                                                                                              \
+    : "v"(vA[0]), "v"(vA[1]), "v"(vA[2]), "v"(vA[3]), "v"(vB[0]), "v"(vB[1]), "v"(vB[2]), "v"(vB[3]),              \
+      "v"(ab[0]), "v"(ab[1]), "v"(ab[2]), "v"(ab[3]), "v"(bb[0]), "v"(bb[1]), "v"(bb[2]), "v"(bb[3]),              \
+      "s"(ga), "s"(gb), "s"(stride_b), "s"(KF), "s"(swa)                                                           \
+    : "memory", "scc", SYMB_GEMM16_SCLOBBERS, SYMB_GEMM16S_VCLOBBERS, SYMB_GEMM16S_ACLOBBERS
+            if constexpr (NN) asm volatile(SYMB_GEMM16S_LOOP_NN SYMB_GEMM16S_LOOP_OPERANDS);
+            else asm volatile(SYMB_GEMM16S_LOOP_NT SYMB_GEMM16S_LOOP_OPERANDS);
+#undef SYMB_GEMM16S_LOOP_OPERANDS
+        }
         __builtin_amdgcn_s_barrier();                      // everything landed and read before LDS is reused
 #ifdef SYMB_GEMM_TRACE
         if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 2] = __builtin_amdgcn_s_memrealtime();
@@ -283,7 +316,7 @@ symb_gemm16_kernel(const GemmParams p) {
         lds_store_a();
         lds_store_b();
         __syncthreads();
-        compute((p.K - KF * 64 + 31) >> 5, 0xffu);
+        compute((p.K - KF * 64 + 31) >> 5, (1u << NBLK) - 1);
         __syncthreads();
     }
 
@@ -291,18 +324,19 @@ symb_gemm16_kernel(const GemmParams p) {
     const unsigned c_lane = (unsigned)((wm0 + l15) * CP + (wn0 + lg * 4) * 2);   // this lane's C[.][.] of block (0, 0)
     auto stage_out = [&](bf16* __restrict__ dst, bool scale_ia3) __attribute__((always_inline)) {
         if (PLAIN || (!p.bias && !scale_ia3 && !p.neff)) {
-            asm volatile(SYMB_GEMM16_STAGE_OUT : : "v"(lds0 + c_lane) : "memory", SYMB_GEMM16_VCLOBBERS);
+            if constexpr (NBLK == 8) asm volatile(SYMB_GEMM16_STAGE_OUT : : "v"(lds0 + c_lane) : "memory", SYMB_GEMM16_VCLOBBERS);
+            else asm volatile(SYMB_GEMM16S_STAGE_OUT : : "v"(lds0 + c_lane) : "memory", SYMB_GEMM16S_VCLOBBERS);
         } else if constexpr (!PLAIN) {
-            // bias of this lane's 8 column quads, once; IA3 vector and noise effect of each row's own
+            // bias of this lane's column quads, once; IA3 vector and noise effect of each row's own
             // segment per row block
             const int nq0 = n0 + wn0 + lg * 4;
-            uint2 bv[8];
+            uint2 bv[NBLK];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
+            for (int j = 0; j < NBLK; ++j) {
                 const int n = nq0 + j * 16;
                 bv[j] = (p.bias && n < p.N) ? *reinterpret_cast<const uint2*>(p.bias + n) : make_uint2(0u, 0u);
             }
-            static_for<0, 8>([&](auto I) __attribute__((always_inline)) {
+            static_for<0, NBLK>([&](auto I) __attribute__((always_inline)) {
                 constexpr int i = decltype(I)::value;
                 const int m = m0 + wm0 + i * 16 + l15;
                 const bf16* lrow = nullptr;
@@ -315,17 +349,17 @@ symb_gemm16_kernel(const GemmParams p) {
                         if (nd.ptr) nrow = nd.ptr + (size_t)(nd.rows == 1 ? 0 : m - p.off[s]) * p.N;
                     }
                 }
-                uint2 lv[8], nv[8];
+                uint2 lv[NBLK], nv[NBLK];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
+                for (int j = 0; j < NBLK; ++j) {
                     const int n = nq0 + j * 16;
                     nv[j] = (nrow && n < p.N) ? *reinterpret_cast<const uint2*>(nrow + n) : make_uint2(0u, 0u);
                     lv[j] = (lrow && n < p.N) ? *reinterpret_cast<const uint2*>(lrow + n) : make_uint2(0x3f803f80u, 0x3f803f80u);
                 }
-                static_for<0, 8>([&](auto J) __attribute__((always_inline)) {
+                static_for<0, NBLK>([&](auto J) __attribute__((always_inline)) {
                     constexpr int j = decltype(J)::value;
                     float v0, v1, v2, v3;
-                    acc16_read4<4 * (8 * i + j)>(v0, v1, v2, v3);
+                    acc16_read4<4 * (NBLK * i + j)>(v0, v1, v2, v3);
                     if (p.bias) {
                         v0 += bf16_bits_to_f32((unsigned short)(bv[j].x & 0xffffu));
                         v1 += bf16_bits_to_f32((unsigned short)(bv[j].x >> 16));
@@ -359,25 +393,28 @@ symb_gemm16_kernel(const GemmParams p) {
         if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 9] = __builtin_amdgcn_s_memrealtime();
 #endif
         const bool to_seg = p.c_seg != nullptr && dst == p.C;   // the final output goes to the segments' own buffers
-        const int col = (lane & 31) * 8, r0 = wave * 2 + (lane >> 5);
+        constexpr int LPR = BN / 8;                  // lanes per row (16 bytes each)
+        constexpr int RPP = 256 / LPR;               // rows per pass of the workgroup
+        constexpr int NPASS = BM / RPP, BATCH = NPASS < 16 ? NPASS : 16;
+        const int col = (lane % LPR) * 8, r0 = wave * (64 / LPR) + lane / LPR;
         const bool nok = n0 + col < p.N;
         if (!to_seg) {
-            // 32 rows per lane, in two batches: sixteen LDS reads in flight, then their sixteen stores
+            // NPASS rows per lane, in batches: up to sixteen LDS reads in flight, then their stores
             bf16* const out0 = dst + (size_t)(m0 + r0) * p.N + n0 + col;
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                uint4 v[16];
+            for (int part = 0; part < NPASS / BATCH; ++part) {
+                uint4 v[BATCH];
 #pragma unroll
-                for (int q = 0; q < 16; ++q) v[q] = *reinterpret_cast<const uint4*>(smem + (r0 + (half * 16 + q) * 8) * CP + col * 2);
+                for (int q = 0; q < BATCH; ++q) v[q] = *reinterpret_cast<const uint4*>(smem + (r0 + (part * BATCH + q) * RPP) * CP + col * 2);
 #pragma unroll
-                for (int q = 0; q < 16; ++q) {
-                    const int r = r0 + (half * 16 + q) * 8;
-                    if (nok && m0 + r < p.M) *reinterpret_cast<uint4*>(out0 + (size_t)((half * 16 + q) * 8) * p.N) = v[q];
+                for (int q = 0; q < BATCH; ++q) {
+                    const int r = r0 + (part * BATCH + q) * RPP;
+                    if (nok && m0 + r < p.M) *reinterpret_cast<uint4*>(out0 + (size_t)((part * BATCH + q) * RPP) * p.N) = v[q];
                 }
             }
         } else {
 #pragma unroll 4
-            for (int r = r0; r < BM; r += 8) {
+            for (int r = r0; r < BM; r += RPP) {
                 const int m = m0 + r;
                 if (m < p.M && nok) {
                     const int s = seg_of_row(p.off, seg_lo, seg_hi, m);
@@ -402,9 +439,10 @@ symb_gemm16_kernel(const GemmParams p) {
     while (ext_more) {
         // this wavefront's 16-row blocks that hold rows of the step's segment (the other rows of the
         // activation-side tile are zero)
-        const int b_lo = max(e_lo - (m0 + wm0), 0) >> 4, b_hi = min((e_hi - 1 - (m0 + wm0)) >> 4, 7);
+        constexpr unsigned ALL = (1u << NBLK) - 1;
+        const int b_lo = max(e_lo - (m0 + wm0), 0) >> 4, b_hi = min((e_hi - 1 - (m0 + wm0)) >> 4, NBLK - 1);
         const unsigned rows = (unsigned)__builtin_amdgcn_readfirstlane(
-            (e_hi > m0 + wm0 && b_lo <= b_hi) ? (int)((0xffu >> (7 - b_hi)) & (0xffu << b_lo)) : 0);
+            (e_hi > m0 + wm0 && b_lo <= b_hi) ? (int)((ALL >> (NBLK - 1 - b_hi)) & (ALL << b_lo) & ALL) : 0);
 #pragma unroll
         for (int i = 0; i < EC; ++i) {
             *reinterpret_cast<uint4*>(sA + e_lds0 + i * 8192) = ea[i];

@@ -34,31 +34,39 @@ The last two stages run copies of the body without loads.
 """
 import os
 
-F = {0: 128, 1: 192}          # first VGPR of fragment set 0 / 1 (A: 8 x 4 regs, then B: 8 x 4 regs)
 VT = 116                      # address temporaries v116..v127
 S_GA, S_GB = 80, 82
 S_CNT, S_ACUR, S_ANXT, S_ANN, S_BCUR, S_BNXT, S_T0, S_T1 = range(84, 92)
 LOAD_MOD = (" " + os.environ["SYMB_GEN_LOAD_MOD"]) if os.environ.get("SYMB_GEN_LOAD_MOD") else ""   # tuning: cache policy bits
-UNIT = 32768                  # one operand's 64-k stage
-A_BASES = (0, UNIT, 2 * UNIT)
-B_BASES = (3 * UNIT, 4 * UNIT)
-C_PITCH = 528                 # bytes per row of the staged bf16 output tile (256 * 2 + 16)
-
-# operand numbers of the main loop
-VA = (0, 1, 2, 3)             # A fragment lane offsets: 32-k step 0 first / second read, step 1 first / second read
-VB = tuple(range(4, 12))      # K-contiguous W: as VA in VB[0..3]; N-contiguous W: one per 16-column block
-AV = tuple(range(12, 20))     # global byte offsets of this lane's 8 A loads
-BV = tuple(range(20, 28))     # global byte offsets of this lane's 8 B loads
-GA, GB, STRIDE_B, KF, SWA = 28, 29, 30, 31, 32
 
 # The compiler does not look inside an assembly statement: whatever it places right after one
 # must not meet a matrix instruction that is still writing its result.
 MFMA_DRAIN = ["s_nop 15", "s_nop 7"]
-BLOCKS = [(i, j) for i in range(8) for j in range(8)]
+
+
+def configure(nb):
+    """Sets the tile-dependent constants: nb = 16x16 blocks per wavefront and dimension (8: 256x256
+    tile of the workgroup, 4: 128x128)."""
+    global VTOP, NB, F, UNIT, A_BASES, B_BASES, C_PITCH, NPITCH, VA, VB, AV, BV, GA, GB, STRIDE_B, KF, SWA, BLOCKS
+    NB = nb
+    VTOP = 128 + 16 * nb                        # one past the last VGPR the templates use (256 / 192)
+    F = {0: 128, 1: 128 + 8 * nb}               # first VGPR of fragment set 0 / 1 (A: nb x 4 regs, then B: nb x 4 regs)
+    UNIT = 4096 * nb                            # one operand's 64-k stage: 32 nb rows x 128 bytes
+    A_BASES = (0, UNIT, 2 * UNIT)
+    B_BASES = (3 * UNIT, 4 * UNIT)
+    C_PITCH = 64 * nb + 16                      # bytes per row of the staged bf16 output tile
+    NPITCH = 64 * nb                            # bytes per k-row of an N-contiguous weight unit
+    # operand numbers of the main loop
+    VA = (0, 1, 2, 3)                           # A fragment lane offsets: 32-k step 0 first / second read, step 1 first / second read
+    VB = tuple(range(4, 4 + max(4, nb)))        # K-contiguous W: as VA in VB[0..3]; N-contiguous W: one per 16-column block
+    AV = tuple(range(VB[-1] + 1, VB[-1] + 1 + nb))   # global byte offsets of this lane's nb A loads
+    BV = tuple(range(AV[-1] + 1, AV[-1] + 1 + nb))   # global byte offsets of this lane's nb B loads
+    GA, GB, STRIDE_B, KF, SWA = (BV[-1] + 1 + x for x in range(5))
+    BLOCKS = [(i, j) for i in range(nb) for j in range(nb)]
 
 
 def acc(i, j):
-    b = 4 * (8 * i + j)
+    b = 4 * (NB * i + j)
     return f"a[{b}:{b + 3}]"
 
 
@@ -68,12 +76,12 @@ def fa(s, i):
 
 
 def fb(s, j):
-    b = F[s] + 32 + 4 * j
+    b = F[s] + 4 * NB + 4 * j
     return f"v[{b}:{b + 3}]"
 
 
 def fb_half(s, j, h):
-    b = F[s] + 32 + 4 * j + 2 * h
+    b = F[s] + 4 * NB + 4 * j + 2 * h
     return f"v[{b}:{b + 1}]"
 
 
@@ -93,7 +101,7 @@ def frag_reads(nn, dst, sa, sb, ks, va=None, vb=None):
             pre = [f"v_add_u32 {addr}, s{sa}, %{VA[2 * ks + q]}"]
         else:
             addr, pre = va[q], []
-        for i in range(8):
+        for i in range(NB):
             b = F[dst] + 4 * i + 2 * q
             slots.append((pre if i == 0 else []) + [f"ds_read_b64 v[{b}:{b + 1}], {addr} offset:{2048 * i}"])
     if not nn:
@@ -103,10 +111,10 @@ def frag_reads(nn, dst, sa, sb, ks, va=None, vb=None):
                 pre = [f"v_add_u32 {addr}, s{sb}, %{VB[2 * ks + q]}"]
             else:
                 addr, pre = vb[q], []
-            for j in range(8):
+            for j in range(NB):
                 slots.append((pre if j == 0 else []) + [f"ds_read_b64 {fb_half(dst, j, q)}, {addr} offset:{2048 * j}"])
     else:
-        for j in range(8):
+        for j in range(NB):
             if vb is None:
                 addr = f"v{VT + 2 + j}"
                 pre = [f"v_add_u32 {addr}, s{sb}, %{VB[j]}"]
@@ -114,7 +122,7 @@ def frag_reads(nn, dst, sa, sb, ks, va=None, vb=None):
                 addr, pre = vb[j], []
             for q in range(2):
                 slots.append((pre if q == 0 else []) +
-                             [f"ds_read_b64_tr_b16 {fb_half(dst, j, q)}, {addr} offset:{16384 * ks + 8192 * q}"])
+                             [f"ds_read_b64_tr_b16 {fb_half(dst, j, q)}, {addr} offset:{32 * NPITCH * ks + 16 * NPITCH * q}"])
     return slots
 
 
@@ -149,6 +157,25 @@ def weave(mf, reads, pairs, first, every):
     """One MFMA, then one other instruction (plus the address add a read may carry): load number j
     puts its m0 write after MFMA first + every*j and the load after the next MFMA; the reads take
     the free places from the start."""
+    if len(reads) + 2 * len(pairs) > len(mf):
+        # small tile: more other instructions than MFMAs.  Groups (a read with its address add, or a
+        # load with its m0 write and the wait state between them) are dealt evenly over the MFMAs,
+        # a load after every fourth read.
+        groups, rd = [], list(reads)
+        ld = [a + ["s_nop 0"] + b for a, b in pairs]
+        while rd or ld:
+            groups += rd[:4]
+            rd = rd[4:]
+            if ld:
+                groups.append(ld.pop(0))
+        out, g = [], 0
+        for k, m in enumerate(mf):
+            out.append(m)
+            upto = (k + 1) * len(groups) // len(mf)
+            while g < upto:
+                out += groups[g]
+                g += 1
+        return out
     slots = [None] * len(mf)
     for j, (a, b) in enumerate(pairs):
         slots[first + every * j] = a
@@ -174,7 +201,7 @@ def body(nn, loads_on, last, no_reads=False, no_barrier=False):
     L = []
     # step 0
     reads = [] if no_reads else frag_reads(nn, 1, S_ACUR, S_BCUR, 1)
-    pre, pairs = unit_loads(S_ANN, "A", range(8)) if loads_on else ([], [])
+    pre, pairs = unit_loads(S_ANN, "A", range(NB)) if loads_on else ([], [])
     L += pre
     L += weave([mfma(0, i, j) for i, j in BLOCKS], reads, pairs, 2, 7)
     if loads_on:
@@ -182,10 +209,10 @@ def body(nn, loads_on, last, no_reads=False, no_barrier=False):
     if last:
         L += ["s_waitcnt lgkmcnt(0)"]
     else:
-        L += [f"s_waitcnt vmcnt({8 if loads_on else 0}) lgkmcnt(0)"] + ([] if no_barrier else ["s_barrier"])
+        L += [f"s_waitcnt vmcnt({NB if loads_on else 0}) lgkmcnt(0)"] + ([] if no_barrier else ["s_barrier"])
     # step 1
     reads = [] if (last or no_reads) else frag_reads(nn, 0, S_ANXT, S_BNXT, 0)
-    pre, pairs = unit_loads(S_BCUR, "B", range(8)) if loads_on else ([], [])
+    pre, pairs = unit_loads(S_BCUR, "B", range(NB)) if loads_on else ([], [])
     L += pre
     L += weave([mfma(1, i, j) for i, j in BLOCKS], reads, pairs, 1, 4)
     if loads_on:
@@ -203,10 +230,10 @@ def build(nn, no_loads=False, no_reads=False, no_barrier=False):
           f"s_mov_b32 s{S_BCUR}, {B_BASES[0]}", f"s_mov_b32 s{S_BNXT}, {B_BASES[1]}"]
     for n, (sa, sb) in enumerate(((S_ACUR, S_BCUR), (S_ANXT, S_BNXT))):
         for which, sd in (("A", sa), ("B", sb)):
-            L += unit_loads_flat(sd, which, range(8))
+            L += unit_loads_flat(sd, which, range(NB))
             L += advance(which, cond=1) if n == 0 else advance(which)
     L += build_zero()                                  # while the first two stages are on their way
-    L += ["s_waitcnt vmcnt(16)", "s_barrier"]
+    L += [f"s_waitcnt vmcnt({2 * NB})", "s_barrier"]
     for r in frag_reads(nn, 0, S_ACUR, S_BCUR, 0):
         L += r
     L += ["s_waitcnt lgkmcnt(0)"]
@@ -229,24 +256,24 @@ def build(nn, no_loads=False, no_reads=False, no_barrier=False):
 def build_kstep32(nn):
     """One 32-wide k-step on a register-staged 64-k tile (K remainder, LoRA term): read the
     fragments, wait, MFMAs.  Operands: %0, %1 A fragment addresses (first / second read); B
-    addresses %2, %3 (K-contiguous W) or %2-%9 (N-contiguous W, one per 16-column block), the 32-k
-    half already in them; last operand (%4 resp. %10): SGPR mask of this wavefront's eight 16-row
-    blocks -- a block whose bit is clear holds only zero rows of the activation-side tile (rows of
-    other segments in a LoRA step), so its reads and MFMAs are skipped."""
-    mask = "%10" if nn else "%4"
+    addresses %2, %3 (K-contiguous W) or one per 16-column block from %2 on (N-contiguous W), the
+    32-k half already in them; last operand: SGPR mask of this wavefront's 16-row blocks -- a block
+    whose bit is clear holds only zero rows of the activation-side tile (rows of other segments in a
+    LoRA step), so its reads and MFMAs are skipped."""
+    mask = f"%{2 + NB}" if nn else "%4"
     L = [f"s_cmp_eq_u32 {mask}, 0", "s_cbranch_scc1 19f"]
-    reads = frag_reads(nn, 0, None, None, 0, va=["%0", "%1"], vb=[f"%{2 + j}" for j in range(8)])
-    a_reads, b_reads = reads[:16], reads[16:]          # A: q-major (8 blocks of read 0, then 8 of read 1)
+    reads = frag_reads(nn, 0, None, None, 0, va=["%0", "%1"], vb=[f"%{2 + j}" for j in range(NB)])
+    a_reads, b_reads = reads[:2 * NB], reads[2 * NB:]   # A: q-major (NB blocks of read 0, then NB of read 1)
     for r in b_reads:
         L += r
-    for i in range(8):
+    for i in range(NB):
         L += [f"s_bitcmp1_b32 {mask}, {i}", f"s_cbranch_scc0 {20 + i}f"]
-        L += a_reads[i] + a_reads[8 + i]
+        L += a_reads[i] + a_reads[NB + i]
         L.append(f"{20 + i}:")
     L.append("s_waitcnt lgkmcnt(0)")
-    for i in range(8):
+    for i in range(NB):
         L += [f"s_bitcmp1_b32 {mask}, {i}", f"s_cbranch_scc0 {30 + i}f"]
-        L += [mfma(0, i, j) for j in range(8)]
+        L += [mfma(0, i, j) for j in range(NB)]
         L.append(f"{30 + i}:")
     L += MFMA_DRAIN
     L.append("19:")
@@ -254,16 +281,16 @@ def build_kstep32(nn):
 
 
 def build_zero():
-    return [f"v_accvgpr_write_b32 a{n}, 0" for n in range(256)] + ["s_nop 3"]
+    return [f"v_accvgpr_write_b32 a{n}, 0" for n in range(4 * NB * NB)] + ["s_nop 3"]
 
 
 def build_stage_out():
-    """The whole 128x128 wavefront tile, rounded to bf16, into the LDS staging tile.  %0: LDS byte
-    address of this lane's (m = l%16, n = 4(l/16)) inside the wavefront's part of the tile."""
+    """The whole wavefront tile, rounded to bf16, into the LDS staging tile.  %0: LDS byte address of
+    this lane's (m = l%16, n = 4(l/16)) inside the wavefront's part of the tile."""
     L = []
     for n, (i, j) in enumerate(BLOCKS):
         t = 128 + (n % 8) * 6
-        b = 4 * (8 * i + j)
+        b = 4 * (NB * i + j)
         for e in range(4):
             L.append(f"v_accvgpr_read_b32 v{t + e}, a{b + e}")
         L.append(f"v_cvt_pk_bf16_f32 v{t + 4}, v{t}, v{t + 1}")
@@ -281,48 +308,61 @@ def emit(name, lines):
     return "\n".join(out)
 
 
+def section(prefix):
+    """The templates of the configured tile under the macro prefix `prefix`."""
+    vclob = ", ".join(f'"v{r}"' for r in range(VT, VTOP))
+    aclob = ", ".join(f'"a{r}"' for r in range(4 * NB * NB))
+    return f"""// ---- {32 * NB}x{32 * NB} tile: a wavefront owns {NB}x{NB} blocks, block (i, j) in a[4({NB}i+j) : 4({NB}i+j)+3].
+// Main loop operands: %0-%3 A fragment lane offsets inside an A unit (32-k step 0 first / second
+// read, step 1 first / second read); %{VB[0]}-%{VB[-1]} B fragment lane offsets inside a B unit (K-contiguous W:
+// as for A in %4-%7; N-contiguous W: one per 16-column block); %{AV[0]}-%{AV[-1]} / %{BV[0]}-%{BV[-1]} global byte offsets
+// of this lane's {NB} A / {NB} B loads per stage; %{GA},%{GB} global base of the A / B stage (64-bit SGPR);
+// %{STRIDE_B} byte stride of B between stages; %{KF} number of 64-k stages (>= 1); %{SWA} LDS byte address of the
+// dynamic segment + this wavefront's first load inside a unit (wave * {1024 * NB}).  LDS: units of
+// {UNIT // 1024} KiB, A at unit 0/1/2, B at unit 3/4.  Fixed registers: s80-s91, v{VT}-v{VTOP - 1} (fragment sets at
+// v{F[0]} and v{F[1]}), a0-a{4 * NB * NB - 1}.
+{emit(prefix + "_LOOP_NT", build(False))}
+
+{emit(prefix + "_LOOP_NN", build(True))}
+
+{emit(prefix + "_KSTEP32_NT", build_kstep32(False))}
+
+{emit(prefix + "_KSTEP32_NN", build_kstep32(True))}
+
+{emit(prefix + "_ZERO", build_zero())}
+
+{emit(prefix + "_STAGE_OUT", build_stage_out())}
+
+#define {prefix}_VCLOBBERS {vclob}
+#define {prefix}_ACLOBBERS {aclob}
+"""
+
+
 def main():
     here = os.path.dirname(os.path.abspath(__file__))
-    vclob = ", ".join(f'"v{r}"' for r in range(VT, 256))
-    aclob = ", ".join(f'"a{r}"' for r in range(256))
     sclob = ", ".join(f'"s{r}"' for r in range(80, 92))
-    text = f"""// GENERATED by gen_gemm16_asm.py -- do not edit by hand.
-// Assembly of the 256x256 / 4-wavefront base GEMM on v_mfma_f32_16x16x32_bf16 for gfx950.
-// The accumulators are not operands: block (i, j) of a wavefront's 8x8 blocks of 16x16 lives in
-// a[4(8i+j) : 4(8i+j)+3] in every template.
-// Main loop operands: %0-%3 A fragment lane offsets inside an A unit (32-k step 0 first / second
-// read, step 1 first / second read); %4-%11 B fragment lane offsets inside a B unit (K-contiguous W:
-// as for A in %4-%7; N-contiguous W: one per 16-column block); %12-%19 / %20-%27 global byte offsets
-// of this lane's eight A / eight B loads per stage; %28,%29 global base of the A / B stage (64-bit
-// SGPR); %30 byte stride of B between stages; %31 number of 64-k stages (>= 1); %32 LDS byte address
-// of the dynamic segment + this wavefront's first load inside a unit (wave * 8192).  LDS: A units at
-// 0/32/64 KiB, B units at 96/128 KiB.
-// The main loop zeroes the accumulators itself (after issuing its first loads); SYMB_GEMM16_ZERO is
-// for a K extent without a single full stage.
-// Fixed registers: s80-s91, v{VT}-v255 (fragment sets at v{F[0]} and v{F[1]}), a0-a255.
-#pragma once
-{emit("SYMB_GEMM16_LOOP_NT", build(False))}
-
-{emit("SYMB_GEMM16_LOOP_NN", build(True))}
-
-{emit("SYMB_GEMM16_KSTEP32_NT", build_kstep32(False))}
-
-{emit("SYMB_GEMM16_KSTEP32_NN", build_kstep32(True))}
-
-{emit("SYMB_GEMM16_ZERO", build_zero())}
-
-{emit("SYMB_GEMM16_STAGE_OUT", build_stage_out())}
-
-#ifdef SYMB_GEMM_PROBE   // tuning builds only: the same loop without its in-loop global loads
+    configure(8)
+    big = section("SYMB_GEMM16")
+    probe = f"""#ifdef SYMB_GEMM_PROBE   // tuning builds only: the 256x256 loop without its in-loop global loads / LDS reads / barriers
 {emit("SYMB_GEMM16_LOOP_NT_NOLOAD", build(False, no_loads=True))}
 
 {emit("SYMB_GEMM16_LOOP_NT_NOREAD", build(False, no_loads=True, no_reads=True))}
 
 {emit("SYMB_GEMM16_LOOP_NT_NOBAR", build(False, no_loads=True, no_reads=True, no_barrier=True))}
 #endif
-
-#define SYMB_GEMM16_VCLOBBERS {vclob}
-#define SYMB_GEMM16_ACLOBBERS {aclob}
+"""
+    configure(4)
+    small = section("SYMB_GEMM16S")
+    text = f"""// GENERATED by gen_gemm16_asm.py -- do not edit by hand.
+// Assembly of the 4-wavefront base GEMM on v_mfma_f32_16x16x32_bf16 for gfx950, for a 256x256 tile
+// (macros SYMB_GEMM16_*) and a 128x128 tile (SYMB_GEMM16S_*).  The accumulators are not operands:
+// every template names the accumulation registers literally.  The main loop zeroes the
+// accumulators itself (after issuing its first loads); *_ZERO is for a K extent without a single
+// full stage.
+#pragma once
+{big}
+{probe}
+{small}
 #define SYMB_GEMM16_SCLOBBERS {sclob}
 """
     with open(os.path.join(here, "gemm16_asm.hpp"), "w") as f:

@@ -50,11 +50,11 @@ def _kernels(text):
 
 def test_compiler_code_never_touches_accumulation_registers(device_asm):
     ks = _kernels(device_asm)
-    assert len(ks) == 4, sorted(ks)               # {K-contiguous, N-contiguous weight} x {plain, full epilogue}
+    assert len(ks) == 8, sorted(ks)               # {256x256, 128x128 tile} x {K-contiguous, N-contiguous weight} x {plain, full epilogue}
     for name, lines in ks.items():
         inside = [c for c, i in lines if i]
         outside = [c for c, i in lines if not i]
-        assert sum("v_mfma_f32_16x16x32_bf16" in c for c in inside) > 500, name
+        assert sum("v_mfma_f32_16x16x32_bf16" in c for c in inside) > (500 if "ILi8E" in name else 120), name
         offenders = [c for c in outside if re.search(r"\ba\d+\b|\ba\[\d+", c) or "accvgpr" in c or "v_mfma" in c]
         assert not offenders, (name, offenders[:5])
 
@@ -71,8 +71,12 @@ def test_no_kernel_uses_scratch_memory(device_asm):
 
 
 def test_kernel_descriptors_claim_the_whole_register_file(device_asm):
-    # 256 architectural + 256 accumulation registers per lane: one wavefront per SIMD
+    # 256x256 tile: 256 architectural + 256 accumulation registers per lane, one wavefront per SIMD;
+    # 128x128 tile: 192 + 64, two wavefronts per SIMD (two workgroups of 80 KiB LDS per CU)
+    n = 0
     for m in re.finditer(r"\.amdhsa_kernel (_ZN4symb18symb_gemm16_kernel\w+)(.*?)\.end_amdhsa_kernel", device_asm, re.S):
-        body = m.group(2)
-        assert re.search(r"\.amdhsa_next_free_vgpr 512\b", body), m.group(1)
-        assert re.search(r"\.amdhsa_accum_offset 256\b", body), m.group(1)
+        body, big = m.group(2), "ILi8E" in m.group(1)
+        assert re.search(r"\.amdhsa_next_free_vgpr %d\b" % (512 if big else 256), body), m.group(1)
+        assert re.search(r"\.amdhsa_accum_offset %d\b" % (256 if big else 192), body), m.group(1)
+        n += 1
+    assert n == 8
