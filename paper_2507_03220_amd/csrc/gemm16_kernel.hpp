@@ -60,6 +60,14 @@ __device__ __forceinline__ void acc16_read4(float& v0, float& v1, float& v2, flo
                  : "n"(R), "n"(R + 1), "n"(R + 2), "n"(R + 3));
 }
 
+template <int R>
+__device__ __forceinline__ void acc16_write4(float v0, float v1, float v2, float v3) {
+    asm volatile("v_accvgpr_write_b32 a[%4], %0\n\tv_accvgpr_write_b32 a[%5], %1\n\t"
+                 "v_accvgpr_write_b32 a[%6], %2\n\tv_accvgpr_write_b32 a[%7], %3"
+                 :
+                 : "v"(v0), "v"(v1), "v"(v2), "v"(v3), "n"(R), "n"(R + 1), "n"(R + 2), "n"(R + 3));
+}
+
 // PLAIN: no bias, no IA3 scale, no noise effect, no pre-adapter output (checked by the host).
 template <int NBLK, bool NN, bool PLAIN>
 __global__ void __launch_bounds__(256)
@@ -72,16 +80,21 @@ symb_gemm16_kernel(const GemmParams p) {
     unsigned char* const sB = smem + TT::UNIT;
 
     // ---- tile of this workgroup (same walk as symb_gemm_kernel)
+    // With a K-split (k_parts > 1: launches with too few tiles to fill the chip) every tile is
+    // computed by k_parts workgroups, one per K range, neighbours in the XCD's walk.
     const int total = p.num_m_tiles * p.num_n_tiles;
-    int lin;
+    const int nparts = p.k_parts > 1 ? p.k_parts : 1;
+    int lin, part = 0;
     if (p.walk == 1) {
         const int k = blockIdx.x >> 3;
         lin = (((k >> 5) << 3) + (blockIdx.x & 7)) * 32 + (k & 31);
         if (lin >= total) return;
     } else {
         const int per_xcd = (total + 7) >> 3;
-        lin = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-        if (lin >= total || (int)(blockIdx.x >> 3) >= per_xcd) return;
+        const int item = blockIdx.x >> 3, li = item / nparts;
+        part = item - li * nparts;
+        lin = (blockIdx.x & 7) * per_xcd + li;
+        if (lin >= total || li >= per_xcd) return;
     }
     const int width = p.group_m * p.num_n_tiles;
     const int first_m = (lin / width) * p.group_m;
@@ -195,7 +208,8 @@ symb_gemm16_kernel(const GemmParams p) {
             }
         }
     };
-    bool ext_more = p.ext != nullptr && ext_seek();
+    const bool last_part = part == nparts - 1;      // the K remainder and the LoRA steps go with the last K range
+    bool ext_more = last_part && p.ext != nullptr && ext_seek();
     if (ext_more) ext_load();
 
 
@@ -244,7 +258,9 @@ symb_gemm16_kernel(const GemmParams p) {
     };
 
     // ---- main loop over the full 64-k stages (gemm16_asm.hpp)
-    const int KF = p.K / 64;
+    const int KFT = p.K / 64;                              // full stages of the whole K extent
+    const int st0 = (int)((long long)KFT * part / nparts);
+    const int KF = (int)((long long)KFT * (part + 1) / nparts) - st0;   // this workgroup's stages: [st0, st0 + KF)
     if (KF == 0) {                                         // otherwise the main loop zeroes them
         if constexpr (NBLK == 8) asm volatile(SYMB_GEMM16_ZERO ::: SYMB_GEMM16_ACLOBBERS);
         else asm volatile(SYMB_GEMM16S_ZERO ::: SYMB_GEMM16S_ACLOBBERS);
@@ -273,7 +289,8 @@ symb_gemm16_kernel(const GemmParams p) {
                 bb[j] = ((unsigned)krow * (unsigned)p.N + (unsigned)min(nc * 8, p.N - 8 - n0)) * 2u;
             }
         }
-        const unsigned long long ga = (unsigned long long)a_tile, gb = (unsigned long long)b_tile;
+        const unsigned long long ga = (unsigned long long)(a_tile + (size_t)st0 * 64);
+        const unsigned long long gb = (unsigned long long)(b_tile + (NN ? (size_t)st0 * 64 * p.N : (size_t)st0 * 64));
         const unsigned stride_b = NN ? 128u * (unsigned)p.N : 128u;
         const unsigned swa = (unsigned)__builtin_amdgcn_readfirstlane((int)lds0 + wave * (1024 * NBLK));
 #ifdef SYMB_GEMM_TRACE
@@ -311,12 +328,12 @@ symb_gemm16_kernel(const GemmParams p) {
         if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 2] = __builtin_amdgcn_s_memrealtime();
 #endif
     }
-    if (KF * 64 < p.K) {
-        gload_tail(KF * 64);
+    if (last_part && KFT * 64 < p.K) {
+        gload_tail(KFT * 64);
         lds_store_a();
         lds_store_b();
         __syncthreads();
-        compute((p.K - KF * 64 + 31) >> 5, (1u << NBLK) - 1);
+        compute((p.K - KFT * 64 + 31) >> 5, (1u << NBLK) - 1);
         __syncthreads();
     }
 
@@ -459,6 +476,59 @@ symb_gemm16_kernel(const GemmParams p) {
         if (ext_more) ext_load();
         compute(1, rows);
         __syncthreads();
+    }
+
+    // ---- K-split tile: every part leaves its accumulators in the workspace (register order: 1 KiB
+    // per wavefront and 16x16 block); the part that arrives last adds all of them up in part order
+    // (so the sum does not depend on who was last) and writes the tile.
+    if (nparts > 1) {
+        constexpr int PT = BM * BN;                  // floats per partial tile
+        float* const tile_parts = p.partial + (size_t)lin * nparts * PT;
+        const unsigned lane_off = (unsigned)(wave * (NBLK * NBLK * 1024) + lane * 16);
+        const unsigned long long mine = (unsigned long long)(tile_parts + (size_t)part * PT);
+        if constexpr (NBLK == 8) asm volatile(SYMB_GEMM16_STORE_PARTIAL : : "v"(lane_off), "s"(mine) : "memory", SYMB_GEMM16_VCLOBBERS);
+        else asm volatile(SYMB_GEMM16S_STORE_PARTIAL : : "v"(lane_off), "s"(mine) : "memory", SYMB_GEMM16S_VCLOBBERS);
+        // No device-scope fence (on this chip it writes back and invalidates the XCD's whole L2, tens
+        // of microseconds with the outputs of other tiles in it).  None is needed: the parts of a tile
+        // run on one XCD (same blockIdx & 7), i.e. behind one L2; the template above returns when its
+        // stores are acknowledged by that L2 (write-through L1); the counter is bumped after that;
+        // and the reader's L1 holds no line of the partial tiles (nobody read them in this launch).
+        __syncthreads();
+        int* const flag = reinterpret_cast<int*>(smem);
+        if (tid == 0) *flag = atomicAdd(p.k_count + lin, 1);
+        __syncthreads();
+        const bool last_arrival = *flag == nparts - 1;
+        __syncthreads();                             // the flag's LDS word is part of the staging tile
+        if (!last_arrival) return;
+        const float4* src = reinterpret_cast<const float4*>(tile_parts) + wave * (NBLK * NBLK * 64) + lane;
+        if constexpr (NBLK == 4) {
+            // a part's sixteen blocks are requested together (the accumulator writes below are
+            // assembly statements, which the loads could not be moved across)
+            float4 sum[16];
+#pragma unroll
+            for (int b = 0; b < 16; ++b) sum[b] = src[b * 64];
+            for (int q = 1; q < nparts; ++q) {
+                float4 v[16];
+#pragma unroll
+                for (int b = 0; b < 16; ++b) v[b] = src[(size_t)q * (PT / 4) + b * 64];
+#pragma unroll
+                for (int b = 0; b < 16; ++b) { sum[b].x += v[b].x; sum[b].y += v[b].y; sum[b].z += v[b].z; sum[b].w += v[b].w; }
+            }
+            static_for<0, 16>([&](auto B) __attribute__((always_inline)) {
+                constexpr int b = decltype(B)::value;
+                acc16_write4<4 * b>(sum[b].x, sum[b].y, sum[b].z, sum[b].w);
+            });
+        } else {
+            static_for<0, NBLK * NBLK>([&](auto B) __attribute__((always_inline)) {
+                constexpr int b = decltype(B)::value;
+                float4 sum = src[b * 64];
+                for (int q = 1; q < nparts; ++q) {
+                    const float4 v = src[(size_t)q * (PT / 4) + b * 64];
+                    sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+                }
+                acc16_write4<4 * b>(sum.x, sum.y, sum.z, sum.w);
+            });
+        }
     }
 
 #ifdef SYMB_GEMM_TRACE

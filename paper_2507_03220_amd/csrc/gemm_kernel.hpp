@@ -50,6 +50,11 @@ struct GemmParams {
     const bf16* a_base;
     bf16* const* c_seg;
     const NoiseDesc* neff;      // device [S] or null: per-segment noise effect subtracted last (privacy flow)
+    // K-split (symb_gemm16_kernel only; k_parts <= 1: off): every tile is computed by k_parts
+    // workgroups; partial holds k_parts fp32 tiles per tile, k_count one zeroed arrival counter per tile.
+    int k_parts;
+    float* partial;
+    int* k_count;
     int walk;                   // 0: each XCD walks one contiguous run of tiles; 1: rounds of 32 tiles dealt to the XCDs in turn
     double timing_flops;        // host bookkeeping for the measurement hook; unused on the device
 #ifdef SYMB_GEMM_TRACE

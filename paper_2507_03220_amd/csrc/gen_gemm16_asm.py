@@ -300,6 +300,19 @@ def build_stage_out():
     return L
 
 
+def build_store_partial():
+    """All accumulators as fp32 to global memory in register order: block b of a wavefront is 1 KiB,
+    16 bytes per lane.  %0: byte offset of this lane's 16 bytes of block 0 inside the partial tile
+    (wave * NB * NB KiB + lane * 16); %1: 64-bit base of the partial tile (SGPR pair)."""
+    L = [f"v_mov_b32 v{VT}, %0"]
+    for b in range(NB * NB):
+        L.append(f"global_store_dwordx4 v{VT}, a[{4 * b}:{4 * b + 3}], %1 offset:{(b % 4) * 1024}")
+        if b % 4 == 3 and b != NB * NB - 1:
+            L.append(f"v_add_u32 v{VT}, 4096, v{VT}")
+    L.append("s_waitcnt vmcnt(0)")
+    return L
+
+
 def emit(name, lines):
     out = [f"#define {name} \\"]
     for l in lines:
@@ -332,6 +345,8 @@ def section(prefix):
 {emit(prefix + "_ZERO", build_zero())}
 
 {emit(prefix + "_STAGE_OUT", build_stage_out())}
+
+{emit(prefix + "_STORE_PARTIAL", build_store_partial())}
 
 #define {prefix}_VCLOBBERS {vclob}
 #define {prefix}_ACLOBBERS {aclob}

@@ -172,6 +172,54 @@ BatchInfo inspect(const symb_batch* b) {
     return bi;
 }
 
+// Tile variants: 3 = 256x256 tile, 4 wavefronts (2x2), hand-scheduled assembly loop on the 16x16x32
+// matrix instruction (gemm16_kernel.hpp), taken when the problem has enough such tiles to fill the
+// chip; 2 = the same kernel with a 128x128 tile, for everything smaller; 1 = 128x128 tile,
+// compiler-scheduled loop on the 32x32x16 instruction (gemm_kernel.hpp), kept as a cross-check.
+// SYMB_GEMM_VARIANT = 1, 2 or 3 overrides the choice (tuning aid).
+int gemm_variant(int M, int N) {
+    static const int forced = [] {
+        const char* e = getenv("SYMB_GEMM_VARIANT");
+        return e ? atoi(e) : -1;
+    }();
+    if (forced >= 1 && forced <= 3) return forced;
+    const long big = (long)((M + 255) / 256) * ((N + 255) / 256);
+    return big >= 128 ? 3 : 2;
+}
+int gemm_tile_m(int M, int N) { return gemm_variant(M, N) == 3 ? 256 : 128; }
+
+int gemm_walk() {
+    static const int walk = [] { const char* e = getenv("SYMB_GEMM_WALK"); return e ? atoi(e) : 0; }();
+    return walk;
+}
+
+// K-split for launches of the 128x128-tile kernel that leave most of the chip idle (batches of a few
+// hundred rows on a 4096-wide layer: 96 tiles for 256 CUs, each workgroup walking the whole K extent
+// alone, which is a chain of load and LDS latencies, about 0.5 us per 64 k).  Every tile is then
+// computed by `parts` workgroups, one per K range, which leave fp32 partial tiles (64 KiB each) in
+// the workspace; the last one to arrive adds them up in part order and writes the tile, which costs
+// about 3 us per part.  parts = 320 / tiles, at most 8 and at most one per 8 stages: three parts for
+// 96 tiles, none from 161 tiles on.  SYMB_GEMM_KSPLIT=0 turns it off, SYMB_GEMM_KSPLIT=n replaces
+// the 320 (tuning aids).
+struct SplitPlan {
+    int parts = 1;        // K ranges per tile (1: no split)
+    int tiles = 0;        // 128x128 tiles of the launch
+    size_t bytes = 0;     // partial tiles: tiles * parts * 128 * 128 * 4
+};
+SplitPlan gemm_split_plan(int M, int N, int K) {
+    SplitPlan s;
+    static const int target = [] { const char* e = getenv("SYMB_GEMM_KSPLIT"); return e ? atoi(e) : 320; }();
+    if (target <= 0 || M <= 0 || gemm_walk() != 0 || gemm_variant(M, N) != 2) return s;
+    const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
+    const int KF = K / 64;
+    const int P = std::min({8, KF / 8, (int)(target / tiles)});
+    if (P < 2) return s;
+    s.parts = P;
+    s.tiles = (int)tiles;
+    s.bytes = (size_t)tiles * P * 128 * 128 * 4;
+    return s;
+}
+
 // Workspace layout (all regions 256-byte aligned, in this order; absent regions have size 0).
 // Hs, dH and packed B^T sit at the same offsets for all three operations of one batch, so that a
 // gradient call on the same workspace can take over what the forward call (Hs) and the
@@ -182,6 +230,7 @@ struct WsLayout {
     size_t pk_off = 0, pk_bytes = 0;      // packed B^T
     size_t sc_off = 0, sc_bytes = 0;      // IA3-scaled copy of dY [T][d_out] (input gradient) or of X [T][d_in] (forward, IA3_IN) bf16
     size_t pa_off = 0, pa_bytes = 0;      // packed A^T (input-major weight, input gradient only)
+    size_t tp_off = 0, tp_bytes = 0;      // fp32 partial tiles of a K-split GEMM (see gemm_split_plan); last, optional
     size_t total = 0;
 };
 
@@ -216,6 +265,13 @@ WsLayout ws_layout(const symb_batch* b, const BatchInfo& bi, int op, bool full_b
             take(w.dh_off, w.dh_bytes, hb);
             take(w.pk_off, w.pk_bytes, bi.packed_elems * 2);
         }
+    }
+    if (op == SYMB_OP_FWD) {
+        const SplitPlan sp = gemm_split_plan(bi.T, b->d_out, b->d_in);
+        if (sp.parts > 1) take(w.tp_off, w.tp_bytes, sp.bytes);
+    } else if (op == SYMB_OP_BWD_INPUT) {
+        const SplitPlan sp = gemm_split_plan(bi.T, b->d_in, b->d_out);
+        if (sp.parts > 1) take(w.tp_off, w.tp_bytes, sp.bytes);
     }
     w.total = cur;
     return w;
@@ -295,12 +351,10 @@ symb_status launch_gemm_fn(symb_handle h, GemmParams gp, hipStream_t st, KFN kfn
 #ifdef SYMB_GEMM_TRACE
     { const char* e = getenv("SYMB_TRACE_PTR"); gp.trace = e ? (unsigned long long*)strtoull(e, nullptr, 0) : nullptr; }
 #endif
-    {
-        static const int walk = [] { const char* e = getenv("SYMB_GEMM_WALK"); return e ? atoi(e) : 0; }();
-        gp.walk = walk;
-    }
+    gp.walk = gemm_walk();
     const int total = gp.num_m_tiles * gp.num_n_tiles;
-    const int grid = gp.walk == 1 ? ((total + 255) / 256) * 256 : ((total + 7) / 8) * 8;
+    int grid = gp.walk == 1 ? ((total + 255) / 256) * 256 : ((total + 7) / 8) * 8;
+    if (gp.k_parts > 1) grid *= gp.k_parts;
     const bool timed = h->timing && (int)h->timed.size() < kMaxTimed;
     const size_t slot = h->timed.size();
     if (timed) SYMB_HIP(h, hipEventRecord(h->tev[2 * slot], st));
@@ -334,22 +388,6 @@ double gemm_flops(const symb_batch* b, int N, int K, bool lora) {
                 f += 2.0 * (b->seg_offsets[i + 1] - b->seg_offsets[i]) * (double)b->adapters[i].rank * N;
     return f;
 }
-
-// Tile variants: 3 = 256x256 tile, 4 wavefronts (2x2), hand-scheduled assembly loop on the 16x16x32
-// matrix instruction (gemm16_kernel.hpp), taken when the problem has enough such tiles to fill the
-// chip; 2 = the same kernel with a 128x128 tile, for everything smaller; 1 = 128x128 tile,
-// compiler-scheduled loop on the 32x32x16 instruction (gemm_kernel.hpp), kept as a cross-check.
-// SYMB_GEMM_VARIANT = 1, 2 or 3 overrides the choice (tuning aid).
-int gemm_variant(int M, int N) {
-    static const int forced = [] {
-        const char* e = getenv("SYMB_GEMM_VARIANT");
-        return e ? atoi(e) : -1;
-    }();
-    if (forced >= 1 && forced <= 3) return forced;
-    const long big = (long)((M + 255) / 256) * ((N + 255) / 256);
-    return big >= 128 ? 3 : 2;
-}
-int gemm_tile_m(int M, int N) { return gemm_variant(M, N) == 3 ? 256 : 128; }
 
 template <bool NN>
 symb_status launch_gemm(symb_handle h, const GemmParams& gp, hipStream_t st) {
@@ -589,8 +627,11 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     if (misaligned16(X) || misaligned16(W) || misaligned16(Y) || misaligned16(Ybase) || misaligned16(bias) || misaligned16(ws))
         return fail(h, SYMB_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
     const WsLayout wl = ws_layout(b, bi, SYMB_OP_FWD, true, false);
-    if (wl.total > ws_bytes || (wl.total && !ws))
-        return fail(h, SYMB_ERR_WORKSPACE_TOO_SMALL, "forward needs %zu workspace bytes, got %zu", wl.total, ws_bytes);
+    const size_t ws_need = wl.tp_bytes ? wl.tp_off : wl.total;     // the K-split's partial tiles are optional
+    if (ws_need > ws_bytes || (ws_need && !ws))
+        return fail(h, SYMB_ERR_WORKSPACE_TOO_SMALL, "forward needs %zu workspace bytes, got %zu", ws_need, ws_bytes);
+    const SplitPlan ksp = gemm_split_plan(bi.T, b->d_out, b->d_in);
+    const bool k_split = wl.tp_bytes && ws && ws_bytes >= wl.total && !Ybase;
     hipStream_t s = (hipStream_t)stream;
 
     const int bm = gemm_tile_m(bi.T, b->d_out);
@@ -627,6 +668,8 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     const size_t o_all = blob.add(all_chunks.data(), all_chunks.size());
     const size_t o_xs = blob.add(X_seg, seg_io ? (size_t)bi.S : 0);
     const size_t o_ys = blob.add(Y_seg, seg_io ? (size_t)bi.S : 0);
+    const std::vector<int32_t> k_zero(k_split ? ksp.tiles : 0, 0);
+    const size_t o_kc = blob.add(k_zero.data(), k_zero.size());   // arrival counters of the K-split tiles
     unsigned char* dev = nullptr;
     if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
 
@@ -699,6 +742,11 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     gp.epi_ia3 = bi.n_ia3 > 0 ? KIND_IA3 : 0;
     gp.neff = nd.empty() ? nullptr : (const NoiseDesc*)(dev + o_nd);
     gp.timing_flops = gemm_flops(b, b->d_out, b->d_in, bi.n_lora > 0);
+    if (k_split) {
+        gp.k_parts = ksp.parts;
+        gp.partial = (float*)(wsb + wl.tp_off);
+        gp.k_count = (int*)(dev + o_kc);
+    }
     // W [d_out][d_in]: K-contiguous weight rows.  W [d_in][d_out]: the weight is the [K][N] operand.
     st = conv1d ? launch_gemm<true>(h, gp, s) : launch_gemm<false>(h, gp, s);
     if (st != SYMB_OK) return st;
@@ -797,8 +845,11 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
         return fail(h, SYMB_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
     const bool full = flags == SYMB_BWD_FULL;
     const WsLayout wl = ws_layout(b, bi, SYMB_OP_BWD_INPUT, full, false);
-    if (wl.total > ws_bytes || (wl.total && !ws))
-        return fail(h, SYMB_ERR_WORKSPACE_TOO_SMALL, "backward needs %zu workspace bytes, got %zu", wl.total, ws_bytes);
+    const size_t ws_need = wl.tp_bytes ? wl.tp_off : wl.total;     // the K-split's partial tiles are optional
+    if (ws_need > ws_bytes || (ws_need && !ws))
+        return fail(h, SYMB_ERR_WORKSPACE_TOO_SMALL, "backward needs %zu workspace bytes, got %zu", ws_need, ws_bytes);
+    const SplitPlan ksp = gemm_split_plan(bi.T, b->d_in, b->d_out);
+    const bool k_split = wl.tp_bytes && ws && ws_bytes >= wl.total && !dXbase;
     hipStream_t s = (hipStream_t)stream;
     const bool lora = full && bi.n_lora > 0, ia3 = full && bi.n_ia3 > 0;
 
@@ -840,6 +891,8 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     const size_t o_pa = blob.add(pa_off.data(), pa_off.size());
     const size_t o_gs = blob.add(dY_seg, seg_io ? (size_t)bi.S : 0);
     const size_t o_xs = blob.add(dX_seg, seg_io ? (size_t)bi.S : 0);
+    const std::vector<int32_t> k_zero(k_split ? ksp.tiles : 0, 0);
+    const size_t o_kc = blob.add(k_zero.data(), k_zero.size());   // arrival counters of the K-split tiles
     unsigned char* dev = nullptr;
     if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
 
@@ -902,6 +955,11 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     gp.ext_pitch = 2 * bi.max_rpad;
     gp.epi_ia3 = (full && bi.n_ia3in > 0) ? KIND_IA3_IN : 0;      // dX rows of IA3_IN segments: l_i * (dY W)
     gp.timing_flops = gemm_flops(b, b->d_in, b->d_out, lora);
+    if (k_split) {
+        gp.k_parts = ksp.parts;
+        gp.partial = (float*)(wsb + wl.tp_off);
+        gp.k_count = (int*)(dev + o_kc);
+    }
     // W [d_out][d_in] is the [K][N] operand of dX = dY W; W [d_in][d_out] gives K-contiguous rows.
     st = conv1d ? launch_gemm<false>(h, gp, s) : launch_gemm<true>(h, gp, s);
     if (st != SYMB_OK) return st;

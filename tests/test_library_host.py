@@ -125,6 +125,20 @@ def test_workspace_bytes_formula():
         assert sb.symb_workspace_bytes(none, op) == 0
 
 
+def test_workspace_includes_partial_tiles_of_a_k_split():
+    # 378 rows on a 4096 x 4096 layer: 3 x 32 = 96 tiles of 128 x 128 for 256 CUs; every tile is computed
+    # by 320 // 96 = 3 workgroups, one per K range, each leaving a 64 KiB fp32 partial tile
+    none = sb.Batch(4096, 4096, [0, 378], [sb.Adapter()])
+    assert sb.symb_workspace_bytes(none, sb.SYMB_OP_FWD) == 96 * 3 * 128 * 128 * 4
+    assert sb.symb_workspace_bytes(none, sb.SYMB_OP_BWD_INPUT) == 96 * 3 * 128 * 128 * 4
+    assert sb.symb_workspace_bytes(none, sb.SYMB_OP_ADAPTER_GRAD) == 0
+    # K = 448 = 7 stages of 64: too short to split; 1500 rows: 12 x 32 = 384 tiles, enough workgroups
+    assert sb.symb_workspace_bytes(sb.Batch(448, 4096, [0, 378], [sb.Adapter()]), sb.SYMB_OP_FWD) == 0
+    assert sb.symb_workspace_bytes(sb.Batch(4096, 4096, [0, 1500], [sb.Adapter()]), sb.SYMB_OP_FWD) == 0
+    # 20480 rows: 256 x 256 tiles, no split
+    assert sb.symb_workspace_bytes(sb.Batch(4096, 4096, [0, 20480], [sb.Adapter()]), sb.SYMB_OP_FWD) == 0
+
+
 def test_unknown_weight_layout_is_rejected():
     b = sb.Batch(64, 64, [0, 4], [sb.Adapter()], weight_layout=7)
     assert sb.lib().symb_validate_batch(b.ref()) == sb.SYMB_ERR_INVALID_ARG
