@@ -239,7 +239,7 @@ def main() -> int:
         "algorithmic_tflop_per_step": round(fl["total"] / 1e12, 4),
         "roofline": {
             "bound": "mfma",
-            "kernel": "symb_gemm16_kernel<%s,true>" % ("true" if dom else "false"),
+            "kernel": "symb_gemm16_kernel<8,%s,true>" % ("true" if dom else "false"),
             "achieved": round(achieved, 2),
             "peak": BF16_MFMA_PEAK_TFLOPS,
             "unit": "TFLOP/s",

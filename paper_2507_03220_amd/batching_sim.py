@@ -138,7 +138,8 @@ def main() -> int:
         A = (torch.randn((args.rank, args.d_in), device="cuda", generator=g) * args.d_in ** -0.5).to(torch.bfloat16)
         B = (torch.randn((args.d_out, args.rank), device="cuda", generator=g) * args.rank ** -0.5).to(torch.bfloat16)
         ads.append(sb.Adapter(sb.SYMB_ADAPTER_LORA, args.rank, 2.0, A, B))
-    ws = torch.empty(max_rows * 2 * 16 * ((args.rank + 15) // 16) * 2 + 4096, device="cuda", dtype=torch.uint8)
+    # Hs of the largest batch, plus room for the fp32 partial tiles of a K-split launch (at most 320 tiles of 64 KiB)
+    ws = torch.empty(max_rows * 2 * 16 * ((args.rank + 15) // 16) * 2 + 4096 + (24 << 20), device="cuda", dtype=torch.uint8)
     layer = (h, X, W, Y, ads, ws)
     policies = [("alone", dict(base=0.0, per_tok=0.0, max_wait=0.0, cap=1)),
                 ("as-it-comes", dict(base=0.0, per_tok=0.0, max_wait=0.0, cap=max_rows)),

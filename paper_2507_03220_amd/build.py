@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "libsymb.so")
 SOURCES = [os.path.join(HERE, "csrc", "symb_api.hip"), os.path.join(HERE, "csrc", "symb_batcher.hip")]
 DEPS = SOURCES + [os.path.join(HERE, "csrc", f) for f in
-                  ("gemm_kernel.hpp", "gemm16_kernel.hpp", "gemm16_asm.hpp", "adapter_kernels.hpp", "symb_device.hpp")] + \
+                  ("gemm16_kernel.hpp", "gemm16_asm.hpp", "adapter_kernels.hpp", "symb_device.hpp")] + \
     [os.path.join(os.path.dirname(HERE), "include", f) for f in ("symb.h", "symb_batcher.h")]
 
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-shared", "-fPIC",

@@ -1,28 +1,90 @@
-// The base GEMM on v_mfma_f32_16x16x32_bf16: 4 wavefronts (2x2), each NBLK x NBLK blocks of 16x16 of C.
+// bf16 MFMA GEMM of the frozen base weight with the per-segment adapter fused in.
+//
+//   forward  (NN = false):  C[m][n] = sum_k Aop[m][k] * Bop[n][k]   (Bop = W [d_out][d_in], K-contiguous)
+//   backward (NN = true) :  C[m][n] = sum_k Aop[m][k] * Bop[k][n]   (Bop = W [d_out][d_in], N-contiguous)
+//
+// plus, for every LoRA segment that meets the row tile, extra K-steps
+//   forward : C += Hs[m][p] * B_i[n][p]      (Hs = s_i * X A_i^T from the shrink kernel)
+//   backward: C += dH[m][p] * A_i[p][n]      (dH = s_i * dY B_i)
+// where Hs / dH arrive as a bf16 value plus a bf16 rounding residual (two 16-wide rank blocks per
+// 32-wide K-step), accumulated in the same fp32 accumulators before the single rounding to bf16,
+// and an epilogue with the optional bias, the optional store of the pre-adapter output, the IA3
+// per-channel scale of each row's own segment and the privacy flow's noise effect.
+//
+// One kernel on v_mfma_f32_16x16x32_bf16: 4 wavefronts (2x2), each NBLK x NBLK blocks of 16x16 of C.
 // NBLK = 8: 256x256 tile of the workgroup, all 256 accumulation registers per wavefront, 160 KiB of
 // LDS, for launches with enough such tiles to fill the chip.  NBLK = 4: 128x128 tile, 64 accumulation
 // registers, 80 KiB of LDS, two workgroups per CU, for everything smaller.  The text below describes
-// the 256x256 case; the 128x128 one is the same code with half the extents.
-//
-// Computes what symb_gemm_kernel computes (gemm_kernel.hpp: the frozen weight's product with the
-// LoRA term of each row's segment fused in as extra k-steps, bias / IA3 scale / noise effect in
-// the epilogue), with the same GemmParams, tile walk, LDS ring and 64-k stages.  What differs is
-// the matrix instruction: with Gaussian operands the power-limited chip sustains about 12 % more
-// flops on the 16x16x32 form than on the 32x32x16 form.
+// the 256x256 case; the 128x128 one is the same code with half the extents.  Why this instruction:
+// with Gaussian operands the power-limited chip sustains about 12 % more flops on the 16x16x32 form
+// than on the 32x32x16 form.
 //
 // A wavefront's 128x128 of C is 8x8 blocks of 16x16, 4 registers each: all 256 accumulation
 // registers.  They are not C++ objects: every piece of code that touches one is an assembly
 // template that names a0..a255 literally (gemm16_asm.hpp; block (i, j) is a[4(8i+j) .. +3]), and
 // the compiler-generated code between the templates must not use accumulation registers for
 // anything (a CPU test inspects the generated assembly for that).  The MFMA is issued as (weight
-// fragment, activation fragment): a lane ends up with C[16i + l%16][16j + 4(l/16) + 0..3].
+// fragment, activation fragment): a lane ends up with C[16i + l%16][16j + 4(l/16) + 0..3], i.e. runs
+// of 4 consecutive n of one row m: rows keep their own segment in the epilogue, which stages the
+// bf16 tile through LDS and writes whole rows.
 #pragma once
 #include <type_traits>
 
 #include "gemm16_asm.hpp"
-#include "gemm_kernel.hpp"
+#include "symb_device.hpp"
 
 namespace symb {
+
+struct GemmParams {
+    const bf16* Aop;            // [M][K] (null when the rows come from per-segment buffers, see a_seg)
+    const bf16* Bop;            // NT: [N][K]   NN: [K][N]
+    bf16* C;                    // [M][N]
+    bf16* Cbase;                // [M][N] or null: accumulator (+bias) before the adapter term
+    const bf16* bias;           // [N] or null
+    int M, N, K;
+    int num_m_tiles, num_n_tiles, group_m;
+    const int32_t* off;         // device [S+1]
+    const SegDesc* seg;         // device [S]
+    const int32_t* tile_seg_lo; // device [num_m_tiles]: first / last non-empty segment meeting the row tile
+    const int32_t* tile_seg_hi;
+    const bf16* ext;            // [M][ext_pitch] bf16: Hs (forward) or dH (backward), per row rpad values
+                                // then rpad residuals of the row's own segment; null = no LoRA term
+    int ext_pitch;
+    int epi_ia3;                // 0, or the adapter kind whose rows the epilogue scales by its vector l_i[n]
+                                // (IA3 in the forward, IA3_IN in the input gradient)
+    // Per-segment buffers instead of flat tensors (device arrays of S pointers, or null): row t of
+    // segment i is a_seg[i] + (t - off[i]) * K resp. c_seg[i] + (t - off[i]) * N.  All a_seg buffers lie
+    // within 4 GiB above a_base (checked by the host), so lane offsets from a_base fit 32 bits.
+    const bf16* const* a_seg;
+    const bf16* a_base;
+    bf16* const* c_seg;
+    const NoiseDesc* neff;      // device [S] or null: per-segment noise effect subtracted last (privacy flow)
+    // K-split (k_parts <= 1: off): every tile is computed by k_parts
+    // workgroups; partial holds k_parts fp32 tiles per tile, k_count one zeroed arrival counter per tile.
+    int k_parts;
+    float* partial;
+    int* k_count;
+    int walk;                   // 0: each XCD walks one contiguous run of tiles; 1: rounds of 32 tiles dealt to the XCDs in turn
+    double timing_flops;        // host bookkeeping for the measurement hook; unused on the device
+#ifdef SYMB_GEMM_TRACE
+    unsigned long long* trace;  // tuning builds only: 16 timestamp slots per tile
+#endif
+#ifdef SYMB_GEMM_PROBE
+    int probe;                  // tuning builds only (256x256 kernel): 1 = no in-loop global loads, 2 = nor LDS reads, 5 = nor barriers
+#endif
+};
+
+// 16-byte chunk swizzle of a K-contiguous tile row (8 chunks of 8 bf16 per row).
+__device__ __forceinline__ int swz_row(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+
+// K-contiguous tile: [rows][64] bf16, 128 B per row, chunk kc stored at kc ^ swz_row(row).
+__device__ __forceinline__ int lds_off_kmajor(int row, int kc) { return row * 128 + ((kc ^ swz_row(row)) << 4); }
+
+__device__ __forceinline__ uint4 ld_global_16(const bf16* p, bool ok) {
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (ok) v = *reinterpret_cast<const uint4*>(p);
+    return v;
+}
 
 template <int NBLK>
 struct Gemm16Tile {
@@ -79,7 +141,7 @@ symb_gemm16_kernel(const GemmParams p) {
     unsigned char* const sA = smem;                        // register-staged tiles (K remainder, LoRA term)
     unsigned char* const sB = smem + TT::UNIT;
 
-    // ---- tile of this workgroup (same walk as symb_gemm_kernel)
+    // ---- tile of this workgroup
     // With a K-split (k_parts > 1: launches with too few tiles to fill the chip) every tile is
     // computed by k_parts workgroups, one per K range, neighbours in the XCD's walk.
     const int total = p.num_m_tiles * p.num_n_tiles;

@@ -17,7 +17,6 @@
 
 #include "adapter_kernels.hpp"
 #include "gemm16_kernel.hpp"
-#include "gemm_kernel.hpp"
 
 using namespace symb;
 
@@ -172,17 +171,15 @@ BatchInfo inspect(const symb_batch* b) {
     return bi;
 }
 
-// Tile variants: 3 = 256x256 tile, 4 wavefronts (2x2), hand-scheduled assembly loop on the 16x16x32
-// matrix instruction (gemm16_kernel.hpp), taken when the problem has enough such tiles to fill the
-// chip; 2 = the same kernel with a 128x128 tile, for everything smaller; 1 = 128x128 tile,
-// compiler-scheduled loop on the 32x32x16 instruction (gemm_kernel.hpp), kept as a cross-check.
-// SYMB_GEMM_VARIANT = 1, 2 or 3 overrides the choice (tuning aid).
+// Tile variants of the GEMM kernel (gemm16_kernel.hpp): 3 = 256x256 tile, taken when the problem has
+// enough such tiles to fill the chip; 2 = 128x128 tile, for everything smaller.
+// SYMB_GEMM_VARIANT = 2 or 3 overrides the choice (tuning aid).
 int gemm_variant(int M, int N) {
     static const int forced = [] {
         const char* e = getenv("SYMB_GEMM_VARIANT");
         return e ? atoi(e) : -1;
     }();
-    if (forced >= 1 && forced <= 3) return forced;
+    if (forced == 2 || forced == 3) return forced;
     const long big = (long)((M + 255) / 256) * ((N + 255) / 256);
     return big >= 128 ? 3 : 2;
 }
@@ -367,11 +364,6 @@ symb_status launch_gemm_fn(symb_handle h, GemmParams gp, hipStream_t st, KFN kfn
     return SYMB_OK;
 }
 
-template <int BM, int BN, int WGM, int WGN, bool NN>
-symb_status launch_gemm_t(symb_handle h, const GemmParams& gp, hipStream_t st) {
-    using TT = GemmTile<BM, BN, WGM, WGN, NN>;
-    return launch_gemm_fn(h, gp, st, symb_gemm_kernel<BM, BN, WGM, WGN, NN>, BM, BN, TT::NT, TT::SMEM, NN);
-}
 template <int NBLK, bool NN, bool PLAIN>
 symb_status launch_gemm16_t(symb_handle h, const GemmParams& gp, hipStream_t st) {
     using TT = Gemm16Tile<NBLK>;
@@ -392,11 +384,8 @@ double gemm_flops(const symb_batch* b, int N, int K, bool lora) {
 template <bool NN>
 symb_status launch_gemm(symb_handle h, const GemmParams& gp, hipStream_t st) {
     const bool plain = !gp.bias && !gp.epi_ia3 && !gp.Cbase && !gp.neff;
-    switch (gemm_variant(gp.M, gp.N)) {
-        case 3: return plain ? launch_gemm16_t<8, NN, true>(h, gp, st) : launch_gemm16_t<8, NN, false>(h, gp, st);
-        case 2: return plain ? launch_gemm16_t<4, NN, true>(h, gp, st) : launch_gemm16_t<4, NN, false>(h, gp, st);
-        default: return launch_gemm_t<128, 128, 2, 2, NN>(h, gp, st);
-    }
+    if (gemm_variant(gp.M, gp.N) == 3) return plain ? launch_gemm16_t<8, NN, true>(h, gp, st) : launch_gemm16_t<8, NN, false>(h, gp, st);
+    return plain ? launch_gemm16_t<4, NN, true>(h, gp, st) : launch_gemm16_t<4, NN, false>(h, gp, st);
 }
 
 template <int RB>
