@@ -141,12 +141,14 @@ symb_status symb_plan_row_tiles(const symb_batch* b, int32_t tile_m, int32_t* se
                                 int32_t* seg_hi, int32_t* num_tiles);
 
 /* Bytes of caller-owned device workspace an operation needs for this batch (may be 0).
- * Host-only.  For a forward or input-gradient call on a batch of a few hundred rows the
- * figure ends with a region for fp32 partial tiles: such a call computes every output tile
- * in several workgroups, one per range of the inner dimension (the batch alone would leave
- * most of the chip idle).  That region is optional: a workspace that covers everything
- * before it (in particular none at all for a batch without adapters) makes the call run
- * without the split, only slower; anything smaller fails with SYMB_ERR_WORKSPACE_TOO_SMALL. */
+ * Host-only.  For some forward and input-gradient calls the figure ends with a region for
+ * fp32 partial tiles: such a call computes output tiles in several workgroups, one per
+ * range of the inner dimension -- every tile of a batch of a few hundred rows (which alone
+ * would leave most of the chip idle), or the tiles of a last round of workgroups that
+ * would be less than half full (up to 64 MiB).  That region is optional: a workspace that
+ * covers everything before it (in particular none at all for a batch without adapters)
+ * makes the call run without the split, only slower; anything smaller fails with
+ * SYMB_ERR_WORKSPACE_TOO_SMALL. */
 symb_status symb_workspace_bytes(const symb_batch* b, int32_t op, size_t* out);
 
 /*

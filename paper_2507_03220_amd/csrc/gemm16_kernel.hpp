@@ -59,9 +59,10 @@ struct GemmParams {
     const bf16* a_base;
     bf16* const* c_seg;
     const NoiseDesc* neff;      // device [S] or null: per-segment noise effect subtracted last (privacy flow)
-    // K-split (k_parts <= 1: off): every tile is computed by k_parts
-    // workgroups; partial holds k_parts fp32 tiles per tile, k_count one zeroed arrival counter per tile.
-    int k_parts;
+    // K-split (k_parts <= 1: off): of every XCD's run of tiles, those from number k_whole on are computed
+    // by k_parts workgroups each; partial holds k_parts fp32 tiles per split tile, k_count one zeroed
+    // arrival counter per split tile.
+    int k_parts, k_whole;
     float* partial;
     int* k_count;
     int walk;                   // 0: each XCD walks one contiguous run of tiles; 1: rounds of 32 tiles dealt to the XCDs in turn
@@ -142,19 +143,27 @@ symb_gemm16_kernel(const GemmParams p) {
     unsigned char* const sB = smem + TT::UNIT;
 
     // ---- tile of this workgroup
-    // With a K-split (k_parts > 1: launches with too few tiles to fill the chip) every tile is
-    // computed by k_parts workgroups, one per K range, neighbours in the XCD's walk.
+    // Every XCD (blockIdx & 7) walks a contiguous run of per_xcd tiles.  With a K-split (k_parts > 1)
+    // the tiles of that run from number k_whole on are computed by k_parts workgroups each, one per
+    // K range, neighbours in the XCD's walk: all tiles of a launch too small to fill the chip
+    // (k_whole = 0), or the tiles of a last, mostly empty round.
     const int total = p.num_m_tiles * p.num_n_tiles;
-    const int nparts = p.k_parts > 1 ? p.k_parts : 1;
-    int lin, part = 0;
+    int lin, part = 0, nparts = 1, slot = 0;
     if (p.walk == 1) {
         const int k = blockIdx.x >> 3;
         lin = (((k >> 5) << 3) + (blockIdx.x & 7)) * 32 + (k & 31);
         if (lin >= total) return;
     } else {
         const int per_xcd = (total + 7) >> 3;
-        const int item = blockIdx.x >> 3, li = item / nparts;
-        part = item - li * nparts;
+        const int item = blockIdx.x >> 3;
+        int li = item;
+        if (p.k_parts > 1 && item >= p.k_whole) {
+            const int j = item - p.k_whole;
+            li = p.k_whole + j / p.k_parts;
+            nparts = p.k_parts;
+            part = j - (li - p.k_whole) * nparts;
+            slot = (blockIdx.x & 7) * (per_xcd - p.k_whole) + (li - p.k_whole);   // partial tiles and counter of this tile
+        }
         lin = (blockIdx.x & 7) * per_xcd + li;
         if (lin >= total || li >= per_xcd) return;
     }
@@ -545,7 +554,7 @@ symb_gemm16_kernel(const GemmParams p) {
     // (so the sum does not depend on who was last) and writes the tile.
     if (nparts > 1) {
         constexpr int PT = BM * BN;                  // floats per partial tile
-        float* const tile_parts = p.partial + (size_t)lin * nparts * PT;
+        float* const tile_parts = p.partial + (size_t)slot * nparts * PT;
         const unsigned lane_off = (unsigned)(wave * (NBLK * NBLK * 1024) + lane * 16);
         const unsigned long long mine = (unsigned long long)(tile_parts + (size_t)part * PT);
         if constexpr (NBLK == 8) asm volatile(SYMB_GEMM16_STORE_PARTIAL : : "v"(lane_off), "s"(mine) : "memory", SYMB_GEMM16_VCLOBBERS);
@@ -557,38 +566,53 @@ symb_gemm16_kernel(const GemmParams p) {
         // and the reader's L1 holds no line of the partial tiles (nobody read them in this launch).
         __syncthreads();
         int* const flag = reinterpret_cast<int*>(smem);
-        if (tid == 0) *flag = atomicAdd(p.k_count + lin, 1);
+        if (tid == 0) *flag = atomicAdd(p.k_count + slot, 1);
         __syncthreads();
         const bool last_arrival = *flag == nparts - 1;
         __syncthreads();                             // the flag's LDS word is part of the staging tile
         if (!last_arrival) return;
         const float4* src = reinterpret_cast<const float4*>(tile_parts) + wave * (NBLK * NBLK * 64) + lane;
-        if constexpr (NBLK == 4) {
-            // a part's sixteen blocks are requested together (the accumulator writes below are
-            // assembly statements, which the loads could not be moved across)
-            float4 sum[16];
+        // Blocks are requested in groups (the accumulator writes below are assembly statements, which the
+        // loads could not be moved across): sixteen blocks of one part at a time, or, with at most four
+        // parts, eight blocks of all parts at once, which halves the number of round trips.
+        if (nparts <= 4) {
+            static_for<2, 5>([&](auto NPC) __attribute__((always_inline)) {
+                constexpr int NP = decltype(NPC)::value;
+                if (nparts != NP) return;
+                static_for<0, NBLK * NBLK / 8>([&](auto G) __attribute__((always_inline)) {
+                    constexpr int g = decltype(G)::value;
+                    float4 v[NP][8];
 #pragma unroll
-            for (int b = 0; b < 16; ++b) sum[b] = src[b * 64];
-            for (int q = 1; q < nparts; ++q) {
-                float4 v[16];
+                    for (int q = 0; q < NP; ++q)
 #pragma unroll
-                for (int b = 0; b < 16; ++b) v[b] = src[(size_t)q * (PT / 4) + b * 64];
+                        for (int b = 0; b < 8; ++b) v[q][b] = src[(size_t)q * (PT / 4) + (g * 8 + b) * 64];
 #pragma unroll
-                for (int b = 0; b < 16; ++b) { sum[b].x += v[b].x; sum[b].y += v[b].y; sum[b].z += v[b].z; sum[b].w += v[b].w; }
-            }
-            static_for<0, 16>([&](auto B) __attribute__((always_inline)) {
-                constexpr int b = decltype(B)::value;
-                acc16_write4<4 * b>(sum[b].x, sum[b].y, sum[b].z, sum[b].w);
+                    for (int q = 1; q < NP; ++q)
+#pragma unroll
+                        for (int b = 0; b < 8; ++b) { v[0][b].x += v[q][b].x; v[0][b].y += v[q][b].y; v[0][b].z += v[q][b].z; v[0][b].w += v[q][b].w; }
+                    static_for<0, 8>([&](auto B) __attribute__((always_inline)) {
+                        constexpr int b = decltype(B)::value;
+                        acc16_write4<4 * (g * 8 + b)>(v[0][b].x, v[0][b].y, v[0][b].z, v[0][b].w);
+                    });
+                });
             });
         } else {
-            static_for<0, NBLK * NBLK>([&](auto B) __attribute__((always_inline)) {
-                constexpr int b = decltype(B)::value;
-                float4 sum = src[b * 64];
+            static_for<0, NBLK * NBLK / 16>([&](auto G) __attribute__((always_inline)) {
+                constexpr int g = decltype(G)::value;
+                float4 sum[16];
+#pragma unroll
+                for (int b = 0; b < 16; ++b) sum[b] = src[(g * 16 + b) * 64];
                 for (int q = 1; q < nparts; ++q) {
-                    const float4 v = src[(size_t)q * (PT / 4) + b * 64];
-                    sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+                    float4 v[16];
+#pragma unroll
+                    for (int b = 0; b < 16; ++b) v[b] = src[(size_t)q * (PT / 4) + (g * 16 + b) * 64];
+#pragma unroll
+                    for (int b = 0; b < 16; ++b) { sum[b].x += v[b].x; sum[b].y += v[b].y; sum[b].z += v[b].z; sum[b].w += v[b].w; }
                 }
-                acc16_write4<4 * b>(sum.x, sum.y, sum.z, sum.w);
+                static_for<0, 16>([&](auto B) __attribute__((always_inline)) {
+                    constexpr int b = decltype(B)::value;
+                    acc16_write4<4 * (g * 16 + b)>(sum[b].x, sum[b].y, sum[b].z, sum[b].w);
+                });
             });
         }
     }

@@ -190,30 +190,50 @@ int gemm_walk() {
     return walk;
 }
 
-// K-split for launches of the 128x128-tile kernel that leave most of the chip idle (batches of a few
-// hundred rows on a 4096-wide layer: 96 tiles for 256 CUs, each workgroup walking the whole K extent
-// alone, which is a chain of load and LDS latencies, about 0.5 us per 64 k).  Every tile is then
-// computed by `parts` workgroups, one per K range, which leave fp32 partial tiles (64 KiB each) in
-// the workspace; the last one to arrive adds them up in part order and writes the tile, which costs
-// about 3 us per part.  parts = 320 / tiles, at most 8 and at most one per 8 stages: three parts for
-// 96 tiles, none from 161 tiles on.  SYMB_GEMM_KSPLIT=0 turns it off, SYMB_GEMM_KSPLIT=n replaces
-// the 320 (tuning aids).
+// K-split.  Every XCD walks a contiguous run of per_xcd = ceil(tiles / 8) tiles; the tiles of that run
+// from number `whole` on are computed by `parts` workgroups each, one per K range, which leave fp32
+// partial tiles in the workspace; the last one to arrive adds them up in part order and writes the
+// tile.  Two uses:
+//  * 128x128 tiles, launches that leave most of the chip idle (batches of a few hundred rows on a
+//    4096-wide layer: 96 tiles for 256 CUs, each workgroup walking the whole K extent alone, a chain
+//    of load and LDS latencies of about 0.5 us per 64 k): all tiles split (whole = 0),
+//    parts = 320 / tiles: three parts for 96 tiles, none from 161 tiles on.
+//  * 256x256 tiles, one workgroup per CU, 32 CUs per XCD: a run of per_xcd tiles ends in a round of
+//    rem = per_xcd % 32 tiles that takes as long as a full one.  If rem <= 16 these last tiles are
+//    split into parts = 32 / rem (at most 4), so the last round is full and 1 / parts as long, plus
+//    the sum of the partial tiles (256 KiB each).
+// parts is at most 8 and at most one per 8 stages of 64 k.  SYMB_GEMM_KSPLIT=0 turns both off,
+// SYMB_GEMM_KSPLIT=n replaces the 320 (tuning aids).
 struct SplitPlan {
-    int parts = 1;        // K ranges per tile (1: no split)
-    int tiles = 0;        // 128x128 tiles of the launch
-    size_t bytes = 0;     // partial tiles: tiles * parts * 128 * 128 * 4
+    int parts = 1;        // K ranges per split tile (1: no split)
+    int whole = 0;        // tiles per XCD that stay whole
+    int slots = 0;        // split tiles of the launch (over all XCDs): arrival counters
+    size_t bytes = 0;     // partial tiles: slots * parts * tile rows * tile columns * 4
 };
 SplitPlan gemm_split_plan(int M, int N, int K) {
     SplitPlan s;
     static const int target = [] { const char* e = getenv("SYMB_GEMM_KSPLIT"); return e ? atoi(e) : 320; }();
-    if (target <= 0 || M <= 0 || gemm_walk() != 0 || gemm_variant(M, N) != 2) return s;
-    const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
+    static const int tail_max = [] { const char* e = getenv("SYMB_GEMM_KSPLIT_TAIL"); return e ? atoi(e) : 4; }();
+    if (target <= 0 || M <= 0 || gemm_walk() != 0) return s;
     const int KF = K / 64;
-    const int P = std::min({8, KF / 8, (int)(target / tiles)});
-    if (P < 2) return s;
-    s.parts = P;
-    s.tiles = (int)tiles;
-    s.bytes = (size_t)tiles * P * 128 * 128 * 4;
+    if (gemm_variant(M, N) == 2) {
+        const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
+        const int P = std::min({8, KF / 8, (int)(target / tiles)});
+        if (P < 2) return s;
+        s.parts = P;
+        s.slots = (int)tiles;                  // whole = 0: a tile's slot is its number in the walk
+        s.bytes = (size_t)tiles * P * 128 * 128 * 4;
+    } else {
+        const long tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
+        const int per_xcd = (int)((tiles + 7) / 8), rem = per_xcd % 32;
+        if (rem == 0) return s;
+        const int P = std::min({tail_max, KF / 8, 32 / rem});
+        if (P < 2) return s;
+        s.parts = P;
+        s.whole = per_xcd - rem;
+        s.slots = 8 * rem;
+        s.bytes = (size_t)s.slots * P * 256 * 256 * 4;
+    }
     return s;
 }
 
@@ -350,8 +370,9 @@ symb_status launch_gemm_fn(symb_handle h, GemmParams gp, hipStream_t st, KFN kfn
 #endif
     gp.walk = gemm_walk();
     const int total = gp.num_m_tiles * gp.num_n_tiles;
-    int grid = gp.walk == 1 ? ((total + 255) / 256) * 256 : ((total + 7) / 8) * 8;
-    if (gp.k_parts > 1) grid *= gp.k_parts;
+    const int per_xcd = (total + 7) / 8;
+    int grid = gp.walk == 1 ? ((total + 255) / 256) * 256 : per_xcd * 8;
+    if (gp.k_parts > 1) grid = 8 * (gp.k_whole + (per_xcd - gp.k_whole) * gp.k_parts);
     const bool timed = h->timing && (int)h->timed.size() < kMaxTimed;
     const size_t slot = h->timed.size();
     if (timed) SYMB_HIP(h, hipEventRecord(h->tev[2 * slot], st));
@@ -657,7 +678,7 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     const size_t o_all = blob.add(all_chunks.data(), all_chunks.size());
     const size_t o_xs = blob.add(X_seg, seg_io ? (size_t)bi.S : 0);
     const size_t o_ys = blob.add(Y_seg, seg_io ? (size_t)bi.S : 0);
-    const std::vector<int32_t> k_zero(k_split ? ksp.tiles : 0, 0);
+    const std::vector<int32_t> k_zero(k_split ? ksp.slots : 0, 0);
     const size_t o_kc = blob.add(k_zero.data(), k_zero.size());   // arrival counters of the K-split tiles
     unsigned char* dev = nullptr;
     if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
@@ -733,6 +754,7 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     gp.timing_flops = gemm_flops(b, b->d_out, b->d_in, bi.n_lora > 0);
     if (k_split) {
         gp.k_parts = ksp.parts;
+        gp.k_whole = ksp.whole;
         gp.partial = (float*)(wsb + wl.tp_off);
         gp.k_count = (int*)(dev + o_kc);
     }
@@ -880,7 +902,7 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     const size_t o_pa = blob.add(pa_off.data(), pa_off.size());
     const size_t o_gs = blob.add(dY_seg, seg_io ? (size_t)bi.S : 0);
     const size_t o_xs = blob.add(dX_seg, seg_io ? (size_t)bi.S : 0);
-    const std::vector<int32_t> k_zero(k_split ? ksp.tiles : 0, 0);
+    const std::vector<int32_t> k_zero(k_split ? ksp.slots : 0, 0);
     const size_t o_kc = blob.add(k_zero.data(), k_zero.size());   // arrival counters of the K-split tiles
     unsigned char* dev = nullptr;
     if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
@@ -946,6 +968,7 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     gp.timing_flops = gemm_flops(b, b->d_in, b->d_out, lora);
     if (k_split) {
         gp.k_parts = ksp.parts;
+        gp.k_whole = ksp.whole;
         gp.partial = (float*)(wsb + wl.tp_off);
         gp.k_count = (int*)(dev + o_kc);
     }

@@ -131,6 +131,10 @@ def test_cfg1_tiny_full():
     # the 256x256 kernel on one partial row tile and 129 column tiles, the last of them 8 columns wide
     dict(seed=11, d_in=136, d_out=32776, lens=[100, 1, 49], kinds=[L, I, L], ranks=[16, 8, 40]),
     dict(seed=12, d_in=32776, d_out=136, lens=[100, 1, 49], kinds=[L, N, L], ranks=[16, 8, 40]),      # the same in the input gradient
+    # 266 tiles of 256x256: each XCD's run of 34 tiles ends two tiles into a second round; those are split
+    # over four K ranges each (fp32 partial tiles in the workspace); ragged last row tile, 8-column last tile
+    dict(seed=13, d_in=2056, d_out=33800, lens=[120, 1, 99, 80], kinds=[L, I, L, N], ranks=[16, 8, 40]),
+    dict(seed=14, d_in=33800, d_out=2056, lens=[120, 1, 99, 80], kinds=[L, N, L, L], ranks=[16, 8, 40, 24]),   # the same in the input gradient
     # all kinds NONE: the paper's plain executor
     dict(seed=4, d_in=256, d_out=512, lens=[100, 156], kinds=[N], ranks=[1]),
     # rank 1, rank 128 (max), rank 100, K tail (d_in not a multiple of 64)

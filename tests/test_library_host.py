@@ -135,8 +135,15 @@ def test_workspace_includes_partial_tiles_of_a_k_split():
     # K = 448 = 7 stages of 64: too short to split; 1500 rows: 12 x 32 = 384 tiles, enough workgroups
     assert sb.symb_workspace_bytes(sb.Batch(448, 4096, [0, 378], [sb.Adapter()]), sb.SYMB_OP_FWD) == 0
     assert sb.symb_workspace_bytes(sb.Batch(4096, 4096, [0, 1500], [sb.Adapter()]), sb.SYMB_OP_FWD) == 0
-    # 20480 rows: 256 x 256 tiles, no split
+    # 20480 rows: 80 x 16 tiles of 256 x 256, 160 per XCD = 5 full rounds of its 32 CUs: no split
     assert sb.symb_workspace_bytes(sb.Batch(4096, 4096, [0, 20480], [sb.Adapter()]), sb.SYMB_OP_FWD) == 0
+    # 9049 rows: 36 x 16 = 576 tiles, 72 per XCD: the last 8 of them would be a round of their own and are
+    # split over 32 // 8 = 4 K ranges each (8 XCDs x 8 tiles x 4 partial tiles of 256 KiB)
+    assert sb.symb_workspace_bytes(sb.Batch(4096, 4096, [0, 9049], [sb.Adapter()]), sb.SYMB_OP_FWD) == 8 * 8 * 4 * 256 * 256 * 4
+    # 20480 rows on 4608 -> 2048: 640 tiles, 80 per XCD, the last 16 split in two
+    assert sb.symb_workspace_bytes(sb.Batch(4608, 2048, [0, 20480], [sb.Adapter()]), sb.SYMB_OP_FWD) == 8 * 16 * 2 * 256 * 256 * 4
+    # ... 1440 tiles, 180 per XCD: a last round of 20 tiles is more than half full and stays whole
+    assert sb.symb_workspace_bytes(sb.Batch(4096, 4608, [0, 20480], [sb.Adapter()]), sb.SYMB_OP_FWD) == 0
 
 
 def test_unknown_weight_layout_is_rejected():
