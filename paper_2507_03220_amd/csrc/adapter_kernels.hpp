@@ -501,19 +501,32 @@ __global__ void __launch_bounds__(256) symb_pack_at_kernel(const PackAtParams p)
 //   G[c][pp] = sum_t R[t][c] * L[t][pp]
 //   dB_i (CMAJOR = true ): R = dY, L = Hs -> out[c * rank + pp]      ([d_out][r])
 //   dA_i (CMAJOR = false): R = X,  L = dH -> out[pp * ncols + c]     ([r][d_in])
-// A workgroup owns 128 columns of one segment and walks its tokens 32 at a time through
+// A workgroup owns 128 columns of one work item and walks its tokens 32 at a time through
 // LDS; both MFMA operands are token-strided in memory and are read with the transposing
-// LDS load.  Fixed summation order: results do not depend on the launch.
+// LDS load.  A work item is a whole segment, or, for a segment of more than GRAD_SPLIT_MIN
+// tokens, one of its runs of GRAD_SPLIT tokens: a long segment walked by one workgroup per
+// column block would set the time of the whole launch.  Such a run leaves its sum in the
+// workspace (same layout as the result) and symb_grad_reduce_kernel adds the runs up in
+// order.  Fixed summation order, a function of the segment's length alone: results do not
+// depend on the launch or on the rest of the batch.
 // -------------------------------------------------------------------------------------------
+constexpr int GRAD_SPLIT = 1024;       // tokens per run of a split segment (a multiple of GRAD_TT)
+constexpr int GRAD_SPLIT_MIN = 1536;   // segments up to this length stay whole
+struct GradItem {
+    int32_t seg, t_lo, t_hi;  // tokens [t_lo, t_hi) of segment seg
+    int32_t direct;           // 1: the result goes to the segment's dA / dB; 0: to partial + partial_off
+    int64_t partial_off;      // in floats
+};
 struct GradParams {
     const bf16* R;            // [T][ncols]
     const bf16* L;            // [T][l_pitch]: per row rpad_i values then rpad_i residuals (see skinny kernel)
     int ncols, l_pitch;
     const int32_t* off;
     const SegDesc* seg;
-    const int32_t* seg_list;  // device: segments that want this gradient (grid.y indexes it)
+    const GradItem* items;    // device: the work of this launch (grid.y indexes it)
     int accumulate;
     const bf16* const* R_seg; // device [S] or null: rows of segment i of R start at R_seg[i]
+    float* partial;           // workspace region of the split segments' runs
 };
 
 constexpr int GRAD_CT = 128;       // columns per workgroup
@@ -538,10 +551,11 @@ symb_lora_grad_kernel(const GradParams p) {
     constexpr int LP = 2 * RB * 16 * 2 + 16;           // LDS row pitch of the L tile (value | residual) in bytes
     __shared__ __attribute__((aligned(16))) unsigned char sR[GRAD_TT * GRAD_RPITCH];
     __shared__ __attribute__((aligned(16))) unsigned char sL[GRAD_TT * LP];
-    const int s = p.seg_list[blockIdx.y];
+    const GradItem it = p.items[blockIdx.y];
+    const int s = it.seg;
     const SegDesc sd = p.seg[s];
-    const int t_lo = p.off[s], t_hi = p.off[s + 1];
-    const bf16* const rbase = p.R_seg ? p.R_seg[s] - (size_t)t_lo * p.ncols : p.R;
+    const int t_lo = it.t_lo, t_hi = it.t_hi;
+    const bf16* const rbase = p.R_seg ? p.R_seg[s] - (size_t)p.off[s] * p.ncols : p.R;
     const int c0 = blockIdx.x * GRAD_CT;
     const int nb = sd.rpad >> 4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -553,42 +567,47 @@ symb_lora_grad_kernel(const GradParams p) {
         for (int j = 0; j < RB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     // R tile: 32 rows x 16 chunks of 8 columns = 512 chunks, 2 per thread.  L tile: 32 x (rpad/4) chunks,
-    // at most NLC per thread.  The chunks of the next 32 tokens are requested right after this step's
-    // chunks went to LDS, so they travel while this step multiplies.
+    // at most NLC per thread.  Three register sets: the chunks of tokens t0 + 64 are requested while the
+    // step at t0 multiplies, so a request has two steps to arrive (a step is far shorter than the memory
+    // latency, and a launch over a few segments has too few workgroups per CU to hide it otherwise).
+    // Every load is unconditional (out-of-range chunks read a valid address and count as zero when they
+    // go to LDS) and is requested by an assembly statement, with the wait written out in step(): loads
+    // the compiler can see it puts under the condition again, and then waits for all of them, the newest
+    // request included.
     constexpr int NLC = (GRAD_TT * 4 * RB + 255) / 256;
     const int lw = sd.rpad >> 2;                       // 16-byte chunks per L row: 2 * rpad bf16
     const int l_chunks = GRAD_TT * lw;
-    uint4 rr[2], lv[NLC];
-    auto fetch = [&](int t0) __attribute__((always_inline)) {
+    struct Stage { u32x4 rr[2]; u32x4 lv[NLC]; };
+    const bool col_ok = (c0 + (tid & 15) * 8) < p.ncols;
+    auto fetch = [&](Stage& sg, int t0) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int c = tid + i * 256, tr = c >> 4, cc = c & 15;
-            const bool ok = (t0 + tr) < t_hi && (c0 + cc * 8) < p.ncols;
-            rr[i] = make_uint4(0u, 0u, 0u, 0u);
-            if (ok) rr[i] = *reinterpret_cast<const uint4*>(rbase + (size_t)(t0 + tr) * p.ncols + c0 + cc * 8);
+            const bf16* src = rbase + (size_t)min(t0 + tr, t_hi - 1) * p.ncols + c0 + (col_ok ? cc * 8 : 0);
+            asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(sg.rr[i]) : "v"(src));
         }
 #pragma unroll
         for (int i = 0; i < NLC; ++i) {
             const int c = tid + i * 256, tr = c / lw, pc = c % lw;
-            lv[i] = make_uint4(0u, 0u, 0u, 0u);
-            if (c < l_chunks && (t0 + tr) < t_hi) lv[i] = *reinterpret_cast<const uint4*>(p.L + (size_t)(t0 + tr) * p.l_pitch + pc * 8);
+            const bf16* src = p.L + (size_t)min(t0 + tr, t_hi - 1) * p.l_pitch + pc * 8;
+            asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(sg.lv[i]) : "v"(src));
         }
     };
-    if (t_lo < t_hi) fetch(t_lo);
-    for (int t0 = t_lo; t0 < t_hi; t0 += GRAD_TT) {
-        __syncthreads();     // previous step's LDS reads are done
+    // the chunks of tokens t0.., landed (see step), go to LDS
+    auto put = [&](const Stage& sg, int t0) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int c = tid + i * 256, tr = c >> 4, cc = c & 15;
-            *reinterpret_cast<uint4*>(sR + tr * GRAD_RPITCH + cc * 16) = rr[i];
+            const bool ok = (t0 + tr) < t_hi && col_ok;
+            *reinterpret_cast<u32x4*>(sR + tr * GRAD_RPITCH + cc * 16) = ok ? sg.rr[i] : u32x4{0u, 0u, 0u, 0u};
         }
 #pragma unroll
         for (int i = 0; i < NLC; ++i) {
             const int c = tid + i * 256, tr = c / lw, pc = c % lw;
-            if (c < l_chunks) *reinterpret_cast<uint4*>(sL + tr * LP + pc * 16) = lv[i];
+            if (c < l_chunks) *reinterpret_cast<u32x4*>(sL + tr * LP + pc * 16) = (t0 + tr) < t_hi ? sg.lv[i] : u32x4{0u, 0u, 0u, 0u};
         }
-        __syncthreads();
-        if (t0 + GRAD_TT < t_hi) fetch(t0 + GRAD_TT);
+    };
+    auto multiply = [&]() __attribute__((always_inline)) {
         bf16x8 rf[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) rf[i] = lds_read_tr_16x32(sR, GRAD_RPITCH, wave * 32 + i * 16, lane);
@@ -606,8 +625,33 @@ symb_lora_grad_kernel(const GradParams p) {
                 }
             }
         }
+    };
+    if (t_lo < t_hi) {
+        Stage sg0, sg1, sg2;
+        fetch(sg0, t_lo);
+        fetch(sg1, t_lo + GRAD_TT);
+        // cur: requested two fetches ago, so one fetch (2 + NLC loads, in order) may still be in flight
+        auto step = [&](Stage& cur, Stage& nxt, int t0) __attribute__((always_inline)) {
+            asm volatile("s_waitcnt vmcnt(%0)" : : "n"(2 + NLC) : "memory");
+#pragma unroll
+            for (int i = 0; i < 2; ++i) asm volatile("" : "+v"(cur.rr[i]));
+#pragma unroll
+            for (int i = 0; i < NLC; ++i) asm volatile("" : "+v"(cur.lv[i]));
+            __syncthreads();     // previous step's LDS reads are done
+            put(cur, t0);
+            __syncthreads();
+            fetch(nxt, t0 + 2 * GRAD_TT);
+            multiply();
+        };
+        for (int t0 = t_lo; t0 < t_hi; t0 += 3 * GRAD_TT) {
+            step(sg0, sg2, t0);
+            if (t0 + GRAD_TT < t_hi) step(sg1, sg0, t0 + GRAD_TT);
+            if (t0 + 2 * GRAD_TT < t_hi) step(sg2, sg1, t0 + 2 * GRAD_TT);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" : : : "memory");     // the requests past the end
     }
-    float* out = CMAJOR ? sd.dB : sd.dA;
+    float* out = it.direct ? (CMAJOR ? sd.dB : sd.dA) : p.partial + it.partial_off;
+    const bool accumulate = it.direct && p.accumulate;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -617,14 +661,17 @@ symb_lora_grad_kernel(const GradParams p) {
                     // lane: column c = .. + (lane & 15); registers: pp = j*16 + 4*(lane >> 4) + q
                     const int c = c0 + wave * 32 + i * 16 + (lane & 15);
                     if (c < p.ncols) {
+                        const int pp0 = j * 16 + ((lane >> 4) << 2);
+                        float* dst = out + (size_t)c * sd.rank + pp0;
+                        float old[4] = {0.f, 0.f, 0.f, 0.f};        // all four read before the first store
+                        if (accumulate) {
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const int pp = j * 16 + ((lane >> 4) << 2) + q;
-                            if (pp < sd.rank) {
-                                float* dst = out + (size_t)c * sd.rank + pp;
-                                *dst = p.accumulate ? (*dst + acc[i][j][q]) : acc[i][j][q];
-                            }
+                            for (int q = 0; q < 4; ++q)
+                                if (pp0 + q < sd.rank) old[q] = dst[q];
                         }
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            if (pp0 + q < sd.rank) dst[q] = old[q] + acc[i][j][q];
                     }
                 } else {
                     // lane: pp = j*16 + (lane & 15); registers: column c = .. + 4*(lane >> 4) + q
@@ -633,12 +680,42 @@ symb_lora_grad_kernel(const GradParams p) {
                     if (pp < sd.rank && c < p.ncols) {
                         float4* dst = reinterpret_cast<float4*>(out + (size_t)pp * p.ncols + c);
                         float4 v = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
-                        if (p.accumulate) { const float4 o = *dst; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
+                        if (accumulate) { const float4 o = *dst; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
                         *dst = v;
                     }
                 }
             }
         }
+}
+
+// Sums the runs of the split segments (see GradItem) into their dA / dB: element by element,
+//   out = (accumulate ? out : 0) + (run 0 + run 1 + ...), the runs in this order.
+// grid.y indexes the split segments; every thread owns four consecutive floats at a time.
+struct GradReduceItem {
+    int32_t seg, nruns;
+    int64_t partial_off;      // run 0, in floats; run q follows at + q * rank * ncols
+};
+struct GradReduceParams {
+    const SegDesc* seg;
+    const GradReduceItem* items;
+    const float* partial;
+    int ncols, cmajor, accumulate;
+};
+__global__ void __launch_bounds__(256) symb_grad_reduce_kernel(const GradReduceParams p) {
+    const GradReduceItem it = p.items[blockIdx.y];
+    const SegDesc sd = p.seg[it.seg];
+    const size_t n = (size_t)sd.rank * p.ncols;          // a multiple of 4: ncols is a multiple of 8
+    float* const out = p.cmajor ? sd.dB : sd.dA;
+    const float* const run0 = p.partial + it.partial_off;
+    for (size_t e = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4; e < n; e += (size_t)gridDim.x * 1024) {
+        float4 v = *reinterpret_cast<const float4*>(run0 + e);
+        for (int q = 1; q < it.nruns; ++q) {
+            const float4 a = *reinterpret_cast<const float4*>(run0 + (size_t)q * n + e);
+            v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+        }
+        if (p.accumulate) { const float4 o = *reinterpret_cast<const float4*>(out + e); v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
+        *reinterpret_cast<float4*>(out + e) = v;
+    }
 }
 
 // -------------------------------------------------------------------------------------------

@@ -237,6 +237,22 @@ SplitPlan gemm_split_plan(int M, int N, int K) {
     return s;
 }
 
+// LoRA gradients of long segments: a segment of more than GRAD_SPLIT_MIN tokens is walked in runs of
+// GRAD_SPLIT tokens, each by workgroups of its own, which leave fp32 sums of the result's size in the
+// workspace; a second kernel adds the runs up in order.  Number of runs of a segment of n tokens:
+int grad_runs(int n) { return n > GRAD_SPLIT_MIN ? (n + GRAD_SPLIT - 1) / GRAD_SPLIT : 1; }
+// Floats of workspace the runs of dB (of_b) or dA take for this batch.
+size_t grad_split_floats(const symb_batch* b, bool of_b) {
+    size_t n = 0;
+    for (int i = 0; i < b->num_segments; ++i) {
+        const symb_adapter& a = b->adapters[i];
+        if (a.kind != SYMB_ADAPTER_LORA || !(of_b ? a.dB : a.dA)) continue;
+        const int runs = grad_runs(b->seg_offsets[i + 1] - b->seg_offsets[i]);
+        if (runs > 1) n += (size_t)runs * a.rank * (of_b ? b->d_out : b->d_in);
+    }
+    return n;
+}
+
 // Workspace layout (all regions 256-byte aligned, in this order; absent regions have size 0).
 // Hs, dH and packed B^T sit at the same offsets for all three operations of one batch, so that a
 // gradient call on the same workspace can take over what the forward call (Hs) and the
@@ -247,6 +263,7 @@ struct WsLayout {
     size_t pk_off = 0, pk_bytes = 0;      // packed B^T
     size_t sc_off = 0, sc_bytes = 0;      // IA3-scaled copy of dY [T][d_out] (input gradient) or of X [T][d_in] (forward, IA3_IN) bf16
     size_t pa_off = 0, pa_bytes = 0;      // packed A^T (input-major weight, input gradient only)
+    size_t gr_off = 0, gr_bytes = 0;      // fp32 runs of the LoRA gradients of split segments (see grad_split)
     size_t tp_off = 0, tp_bytes = 0;      // fp32 partial tiles of a K-split GEMM (see gemm_split_plan); last, optional
     size_t total = 0;
 };
@@ -281,6 +298,8 @@ WsLayout ws_layout(const symb_batch* b, const BatchInfo& bi, int op, bool full_b
             take(w.h_off, w.h_bytes, hb);
             take(w.dh_off, w.dh_bytes, hb);
             take(w.pk_off, w.pk_bytes, bi.packed_elems * 2);
+            const size_t gr = std::max(grad_split_floats(b, true), grad_split_floats(b, false)) * 4;   // dB's runs, then dA's, in the same place
+            if (gr) take(w.gr_off, w.gr_bytes, gr);
         }
     }
     if (op == SYMB_OP_FWD) {
@@ -424,8 +443,8 @@ symb_status launch_skinny(symb_handle h, const SkinnyParams& sp, int nchunks, in
 }
 
 template <int RB, bool CM>
-void launch_grad_rb(const GradParams& gp, int nseg, hipStream_t st) {
-    hipLaunchKernelGGL((symb_lora_grad_kernel<RB, CM>), dim3((gp.ncols + GRAD_CT - 1) / GRAD_CT, nseg), dim3(256), 0, st, gp);
+void launch_grad_rb(const GradParams& gp, int nitems, hipStream_t st) {
+    hipLaunchKernelGGL((symb_lora_grad_kernel<RB, CM>), dim3((gp.ncols + GRAD_CT - 1) / GRAD_CT, nitems), dim3(256), 0, st, gp);
 }
 template <bool CM>
 symb_status launch_grad(symb_handle h, const GradParams& gp, int nseg, int max_rpad, hipStream_t st) {
@@ -434,6 +453,14 @@ symb_status launch_grad(symb_handle h, const GradParams& gp, int nseg, int max_r
     else if (max_rpad <= 32) launch_grad_rb<2, CM>(gp, nseg, st);
     else if (max_rpad <= 64) launch_grad_rb<4, CM>(gp, nseg, st);
     else launch_grad_rb<8, CM>(gp, nseg, st);
+    SYMB_HIP(h, hipGetLastError());
+    return SYMB_OK;
+}
+// Adds up the runs of the split segments (none: nothing to do).  At most 128 * 36864 floats per segment
+// at 1024 per workgroup and pass.
+symb_status launch_grad_reduce(symb_handle h, const GradReduceParams& rp, int nsplit, hipStream_t st) {
+    if (nsplit == 0) return SYMB_OK;
+    hipLaunchKernelGGL(symb_grad_reduce_kernel, dim3(1024, nsplit), dim3(256), 0, st, rp);
     SYMB_HIP(h, hipGetLastError());
     return SYMB_OK;
 }
@@ -1092,14 +1119,35 @@ static symb_status adapter_grad_impl(symb_handle h, const symb_batch* b, const v
                 cur += (int64_t)sd[i].rpad * b->d_out;
             }
     }
+    // Work items of the two gradient launches: whole segments, or the runs of long ones (see grad_runs).
+    auto plan_items = [&](const std::vector<int32_t>& want, int ncols, std::vector<GradItem>& items, std::vector<GradReduceItem>& red) {
+        int64_t cur = 0;
+        for (int i : want) {
+            const int lo = b->seg_offsets[i], hi = b->seg_offsets[i + 1], runs = grad_runs(hi - lo);
+            if (runs == 1) {
+                items.push_back(GradItem{i, lo, hi, 1, 0});
+                continue;
+            }
+            const int64_t n = (int64_t)b->adapters[i].rank * ncols;
+            red.push_back(GradReduceItem{i, runs, cur});
+            for (int q = 0; q < runs; ++q, cur += n)
+                items.push_back(GradItem{i, lo + q * GRAD_SPLIT, std::min(hi, lo + (q + 1) * GRAD_SPLIT), 0, cur});
+        }
+    };
+    std::vector<GradItem> it_a, it_b;
+    std::vector<GradReduceItem> red_a, red_b;
+    plan_items(want_b, b->d_out, it_b, red_b);
+    plan_items(want_a, b->d_in, it_a, red_a);
     Blob blob;
     const size_t o_seg = blob.add(sd.data(), sd.size());
     const size_t o_off = blob.add(b->seg_offsets, (size_t)bi.S + 1);
+    const size_t o_ita = blob.add(it_a.data(), it_a.size());
+    const size_t o_itb = blob.add(it_b.data(), it_b.size());
+    const size_t o_rda = blob.add(red_a.data(), red_a.size());
+    const size_t o_rdb = blob.add(red_b.data(), red_b.size());
     const size_t o_chh = blob.add(ch_h.data(), ch_h.size());
     const size_t o_chd = blob.add(ch_dh.data(), ch_dh.size());
     const size_t o_pk = blob.add(pk_off.data(), pk_off.size());
-    const size_t o_wa = blob.add(want_a.data(), want_a.size());
-    const size_t o_wb = blob.add(want_b.data(), want_b.size());
     const size_t o_wl = blob.add(want_l.data(), want_l.size());
     const size_t o_wli = blob.add(want_lin.data(), want_lin.size());
     const size_t o_xs = blob.add(X_seg, seg_io ? (size_t)bi.S : 0);
@@ -1128,8 +1176,11 @@ static symb_status adapter_grad_impl(symb_handle h, const symb_batch* b, const v
             if ((st = launch_skinny(h, sp, (int)ch_h.size(), grad_max_rpad, s)) != SYMB_OK) return st;
         }
         GradParams gp{(const bf16*)dY, (const bf16*)(wsb + wl.h_off), b->d_out, 2 * bi.max_rpad, doff, dseg,
-                      (const int32_t*)(dev + o_wb), acc ? 1 : 0, seg_io ? (const bf16* const*)(dev + o_gs) : nullptr};
-        if ((st = launch_grad<true>(h, gp, (int)want_b.size(), grad_max_rpad, s)) != SYMB_OK) return st;
+                      (const GradItem*)(dev + o_itb), acc ? 1 : 0, seg_io ? (const bf16* const*)(dev + o_gs) : nullptr,
+                      (float*)(wsb + wl.gr_off)};
+        if ((st = launch_grad<true>(h, gp, (int)it_b.size(), grad_max_rpad, s)) != SYMB_OK) return st;
+        if ((st = launch_grad_reduce(h, GradReduceParams{dseg, (const GradReduceItem*)(dev + o_rdb), (const float*)(wsb + wl.gr_off), b->d_out, 1, acc ? 1 : 0},
+                                     (int)red_b.size(), s)) != SYMB_OK) return st;
     }
     if (!want_a.empty()) {       // dA_i = dH_i^T X_i
         if (!reuse_dh) {
@@ -1153,8 +1204,11 @@ static symb_status adapter_grad_impl(symb_handle h, const symb_batch* b, const v
             if ((st = launch_skinny(h, sp, (int)ch_dh.size(), grad_max_rpad, s)) != SYMB_OK) return st;
         }
         GradParams gp{(const bf16*)X, (const bf16*)(wsb + wl.dh_off), b->d_in, 2 * bi.max_rpad, doff, dseg,
-                      (const int32_t*)(dev + o_wa), acc ? 1 : 0, seg_io ? (const bf16* const*)(dev + o_xs) : nullptr};
-        if ((st = launch_grad<false>(h, gp, (int)want_a.size(), grad_max_rpad, s)) != SYMB_OK) return st;
+                      (const GradItem*)(dev + o_ita), acc ? 1 : 0, seg_io ? (const bf16* const*)(dev + o_xs) : nullptr,
+                      (float*)(wsb + wl.gr_off)};
+        if ((st = launch_grad<false>(h, gp, (int)it_a.size(), grad_max_rpad, s)) != SYMB_OK) return st;
+        if ((st = launch_grad_reduce(h, GradReduceParams{dseg, (const GradReduceItem*)(dev + o_rda), (const float*)(wsb + wl.gr_off), b->d_in, 0, acc ? 1 : 0},
+                                     (int)red_a.size(), s)) != SYMB_OK) return st;
     }
     if (!want_l.empty()) {
         Ia3GradParams ip{(const bf16*)dY, (const bf16*)Ybase, b->d_out, doff, dseg, (const int32_t*)(dev + o_wl), acc ? 1 : 0,

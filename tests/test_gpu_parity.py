@@ -135,6 +135,9 @@ def test_cfg1_tiny_full():
     # over four K ranges each (fp32 partial tiles in the workspace); ragged last row tile, 8-column last tile
     dict(seed=13, d_in=2056, d_out=33800, lens=[120, 1, 99, 80], kinds=[L, I, L, N], ranks=[16, 8, 40]),
     dict(seed=14, d_in=33800, d_out=2056, lens=[120, 1, 99, 80], kinds=[L, N, L, L], ranks=[16, 8, 40, 24]),   # the same in the input gradient
+    # segments of more than 1536 tokens: their LoRA gradients are summed in runs of 1024 tokens (1537: two runs,
+    # the second of 513 tokens; 1536 stays whole)
+    dict(seed=15, d_in=136, d_out=200, lens=[1700, 3, 2100, 1536, 1537], kinds=[L, L, L, L, L], ranks=[8, 16, 40, 4, 128]),
     # all kinds NONE: the paper's plain executor
     dict(seed=4, d_in=256, d_out=512, lens=[100, 156], kinds=[N], ranks=[1]),
     # rank 1, rank 128 (max), rank 100, K tail (d_in not a multiple of 64)
@@ -224,8 +227,9 @@ def test_backward_batch_is_independent_of_forward_batch():
     np.testing.assert_array_equal(sub, dX[idx])
 
 
-def test_gradient_accumulate_adds():
-    p = make_problem(13, 136, 264, [90, 33], [L, I], [8])
+@pytest.mark.parametrize("lens", [[90, 33], [1700, 33, 2100]])      # the second: segments whose gradients are summed in runs of 1024 tokens
+def test_gradient_accumulate_adds(lens):
+    p = make_problem(13, 136, 264, lens, [L, I, L][:len(lens)], [8, 1, 24][:len(lens)])
     _, Yb = gh.forward(p["off"], p["ads"], p["X"], p["W"], p["bias"])
     g = gh.adapter_grad(p["off"], p["ads"], p["X"], p["dY"], Yb)
     once = [(d.dA.clone() if d.dA is not None else None, d.dB.clone() if d.dB is not None else None) for d in g.descs]

@@ -125,6 +125,21 @@ def test_workspace_bytes_formula():
         assert sb.symb_workspace_bytes(none, op) == 0
 
 
+def test_workspace_includes_the_runs_of_long_segments_gradients():
+    # LoRA gradients of a segment of more than 1536 tokens are summed in runs of 1024 tokens, each run an
+    # fp32 array of the gradient's size in the workspace; dB's runs and dA's share the place
+    fake = 0x1000
+    up = lambda n: (n + 255) // 256 * 256
+    ads = [sb.Adapter(sb.SYMB_ADAPTER_LORA, 5, 1.0, fake, fake, fake, fake),      # 2100 tokens: 3 runs
+           sb.Adapter(sb.SYMB_ADAPTER_LORA, 40, 1.0, fake, fake, fake, fake),     # 1536 tokens: stays whole
+           sb.Adapter(sb.SYMB_ADAPTER_LORA, 8, 1.0, fake, fake)]                  # 1700 tokens, no gradients wanted
+    b = sb.Batch(64, 128, [0, 2100, 3636, 5336], ads)
+    T, rp = 5336, 2 * 48
+    base = 2 * up(T * rp * 2) + up((16 + 48 + 16) * 128 * 2)                     # Hs, dH, packed B^T
+    assert sb.symb_workspace_bytes(b, sb.SYMB_OP_ADAPTER_GRAD) == base + up(3 * 5 * 128 * 4)
+    assert sb.symb_workspace_bytes(b, sb.SYMB_OP_FWD) == up(T * rp * 2)
+
+
 def test_workspace_includes_partial_tiles_of_a_k_split():
     # 378 rows on a 4096 x 4096 layer: 3 x 32 = 96 tiles of 128 x 128 for 256 CUs; every tile is computed
     # by 320 // 96 = 3 workgroups, one per K range, each leaving a 64 KiB fp32 partial tile
