@@ -225,35 +225,40 @@ __device__ __forceinline__ void skinny_stream(const bf16* (&lrow)[SKINNY_BLKS], 
             }
     };
     // ---- full slices of this wavefront: k = wave * SK + 4 SK s, s < ns, through LDS.  Slices 0 .. np-1
-    // are requested up front; iteration s requests slice s + np (while there is one) into the buffer
-    // iteration s - 1 has finished reading, after the adapter rows of slice s: the memory counter
-    // retires in order, so the wait for slice s and its adapter rows leaves exactly the newest slice's
-    // DPS requests in flight.
+    // and the adapter rows of slice 0 are requested up front; iteration s requests the adapter rows of
+    // slice s + 1 and then slice s + np (while there are such) into the buffer iteration s - 1 has
+    // finished reading.  The memory counter retires in order, so the wait for slice s and its adapter
+    // rows leaves exactly these two requests in flight (NR and DPS loads).
+    constexpr int NR = NB * NH;
     int k0 = wave * ST::SK;
     const int ns = K >= k0 + ST::SK ? (K - k0 - ST::SK) / (4 * ST::SK) + 1 : 0;
     const int np = ns < ST::NBUF - 1 ? ns : ST::NBUF - 1;
     for (int d = 0; d < np; ++d) dma(d, k0 + d * 4 * ST::SK);
     int cur = 0, nxt = np;                               // buffer of slice s, of slice s + np
     int s = 0;
-    for (; s + np < ns; ++s) {
-        u32x4 rv[NB][NH];
-        load_r(rv, k0);
-        dma(nxt, k0 + np * 4 * ST::SK);
-        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(ST::DPS) : "memory");
-        settle_r(rv);
-        mul(cur, rv);                                    // returns with its LDS reads complete: the buffer may be requested again
+    u32x4 ra[NB][NH], rb[NB][NH];
+    if (ns > 0) load_r(ra, k0);
+    auto slice = [&](u32x4 (&rc)[NB][NH], u32x4 (&rn)[NB][NH]) __attribute__((always_inline)) {
+        if (s + np < ns) {                               // np >= 1: there is a slice s + 1 as well
+            load_r(rn, k0 + 4 * ST::SK);
+            dma(nxt, k0 + np * 4 * ST::SK);
+            asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NR + ST::DPS) : "memory");
+        } else if (s + 1 < ns) {
+            load_r(rn, k0 + 4 * ST::SK);
+            asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NR) : "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+        }
+        settle_r(rc);
+        mul(cur, rc);                                    // returns with its LDS reads complete: the buffer may be requested again
         cur = cur + 1 == ST::NBUF ? 0 : cur + 1;
         nxt = nxt + 1 == ST::NBUF ? 0 : nxt + 1;
         k0 += 4 * ST::SK;
-    }
-    for (; s < ns; ++s) {                                // the last np slices: nothing left to request
-        u32x4 rv[NB][NH];
-        load_r(rv, k0);
-        asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
-        settle_r(rv);
-        mul(cur, rv);
-        cur = cur + 1 == ST::NBUF ? 0 : cur + 1;
-        k0 += 4 * ST::SK;
+        ++s;
+    };
+    while (s < ns) {
+        slice(ra, rb);
+        if (s < ns) slice(rb, ra);
     }
     // ---- the slice that crosses the end of K: masked fragments straight from global memory
     if (k0 < K) {
