@@ -51,11 +51,16 @@ __device__ __forceinline__ unsigned int pack2_bf16(float lo, float hi) {
     return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, bf16x2_t));
 }
 
-// Segment of row t among segments [lo, hi]: off[i] <= t < off[i+1].  Empty segments never match.
+// Segment of row t among segments [lo, hi], off[lo] <= t < off[hi + 1]: the one with off[i] <= t < off[i+1]
+// (empty segments never match).  Bisection: a row tile of decode steps holds dozens of one-row segments,
+// and every probe is a memory access.
 __device__ __forceinline__ int seg_of_row(const int32_t* __restrict__ off, int lo, int hi, int t) {
-    int s = lo;
-    while (s < hi && t >= off[s + 1]) ++s;
-    return s;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (t >= off[mid]) lo = mid;       // the largest i with off[i] <= t
+        else hi = mid - 1;
+    }
+    return lo;
 }
 
 }  // namespace symb
