@@ -225,40 +225,37 @@ __device__ __forceinline__ void skinny_stream(const bf16* (&lrow)[SKINNY_BLKS], 
             }
     };
     // ---- full slices of this wavefront: k = wave * SK + 4 SK s, s < ns, through LDS.  Slices 0 .. np-1
-    // and the adapter rows of slice 0 are requested up front; iteration s requests the adapter rows of
-    // slice s + 1 and then slice s + np (while there are such) into the buffer iteration s - 1 has
-    // finished reading.  The memory counter retires in order, so the wait for slice s and its adapter
-    // rows leaves exactly these two requests in flight (NR and DPS loads).
-    constexpr int NR = NB * NH;
+    // are requested up front; iteration s requests slice s + np (while there is one) into the buffer
+    // iteration s - 1 has finished reading, after the adapter rows of slice s: the memory counter
+    // retires in order, so the wait for slice s and its adapter rows leaves exactly the newest slice's
+    // DPS requests in flight.  The adapter rows are requested and awaited within one iteration: a
+    // register that is still in flight must not live across the loop edge, where the compiler may
+    // copy it (requesting them a slice ahead was worth 2 % and did exactly that).
     int k0 = wave * ST::SK;
     const int ns = K >= k0 + ST::SK ? (K - k0 - ST::SK) / (4 * ST::SK) + 1 : 0;
     const int np = ns < ST::NBUF - 1 ? ns : ST::NBUF - 1;
     for (int d = 0; d < np; ++d) dma(d, k0 + d * 4 * ST::SK);
     int cur = 0, nxt = np;                               // buffer of slice s, of slice s + np
     int s = 0;
-    u32x4 ra[NB][NH], rb[NB][NH];
-    if (ns > 0) load_r(ra, k0);
-    auto slice = [&](u32x4 (&rc)[NB][NH], u32x4 (&rn)[NB][NH]) __attribute__((always_inline)) {
-        if (s + np < ns) {                               // np >= 1: there is a slice s + 1 as well
-            load_r(rn, k0 + 4 * ST::SK);
-            dma(nxt, k0 + np * 4 * ST::SK);
-            asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NR + ST::DPS) : "memory");
-        } else if (s + 1 < ns) {
-            load_r(rn, k0 + 4 * ST::SK);
-            asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NR) : "memory");
-        } else {
-            asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
-        }
-        settle_r(rc);
-        mul(cur, rc);                                    // returns with its LDS reads complete: the buffer may be requested again
+    for (; s + np < ns; ++s) {
+        u32x4 rv[NB][NH];
+        load_r(rv, k0);
+        dma(nxt, k0 + np * 4 * ST::SK);
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(ST::DPS) : "memory");
+        settle_r(rv);
+        mul(cur, rv);                                    // returns with its LDS reads complete: the buffer may be requested again
         cur = cur + 1 == ST::NBUF ? 0 : cur + 1;
         nxt = nxt + 1 == ST::NBUF ? 0 : nxt + 1;
         k0 += 4 * ST::SK;
-        ++s;
-    };
-    while (s < ns) {
-        slice(ra, rb);
-        if (s < ns) slice(rb, ra);
+    }
+    for (; s < ns; ++s) {                                // the last np slices: nothing left to request
+        u32x4 rv[NB][NH];
+        load_r(rv, k0);
+        asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+        settle_r(rv);
+        mul(cur, rv);
+        cur = cur + 1 == ST::NBUF ? 0 : cur + 1;
+        k0 += 4 * ST::SK;
     }
     // ---- the slice that crosses the end of K: masked fragments straight from global memory
     if (k0 < K) {
@@ -506,7 +503,7 @@ __global__ void __launch_bounds__(256) symb_pack_at_kernel(const PackAtParams p)
 //   G[c][pp] = sum_t R[t][c] * L[t][pp]
 //   dB_i (CMAJOR = true ): R = dY, L = Hs -> out[c * rank + pp]      ([d_out][r])
 //   dA_i (CMAJOR = false): R = X,  L = dH -> out[pp * ncols + c]     ([r][d_in])
-// A workgroup owns 128 columns of one work item and walks its tokens 32 at a time through
+// A workgroup owns 256 columns (128 at ranks above 32) of one work item and walks its tokens 32 at a time through
 // LDS; both MFMA operands are token-strided in memory and are read with the transposing
 // LDS load.  A work item is a whole segment, or, for a segment of more than GRAD_SPLIT_MIN
 // tokens, one of its runs of GRAD_SPLIT tokens: a long segment walked by one workgroup per
@@ -534,9 +531,8 @@ struct GradParams {
     float* partial;           // workspace region of the split segments' runs
 };
 
-constexpr int GRAD_CT = 128;       // columns per workgroup
+template <int RB> constexpr int GRAD_CT = RB <= 2 ? 256 : 128;   // columns per workgroup (512-byte row pieces where the registers allow)
 constexpr int GRAD_TT = 32;        // tokens per step
-constexpr int GRAD_RPITCH = GRAD_CT * 2 + 16;   // LDS row pitch of the R tile in bytes
 
 __device__ __forceinline__ bf16x8 lds_read_tr_16x32(const unsigned char* base, int pitch_bytes, int col0, int lane) {
     // tile [32 t][cols] (column-contiguous); returns for lane l: column col0 + (l & 15), t = 8*(l >> 4) + 0..7
@@ -553,25 +549,28 @@ __device__ __forceinline__ bf16x8 lds_read_tr_16x32(const unsigned char* base, i
 template <int RB, bool CMAJOR>
 __global__ void __launch_bounds__(256)
 symb_lora_grad_kernel(const GradParams p) {
+    constexpr int CT = GRAD_CT<RB>, NI = CT / 64;           // columns per workgroup, 16-column blocks per wavefront
+    constexpr int RPITCH = CT * 2 + 16;                    // LDS row pitch of the R tile in bytes
+    constexpr int LPRW = CT / 8, NRC = GRAD_TT * LPRW / 256;   // 16-byte chunks per R row, R chunks per thread
     constexpr int LP = 2 * RB * 16 * 2 + 16;           // LDS row pitch of the L tile (value | residual) in bytes
-    __shared__ __attribute__((aligned(16))) unsigned char sR[GRAD_TT * GRAD_RPITCH];
+    __shared__ __attribute__((aligned(16))) unsigned char sR[GRAD_TT * RPITCH];
     __shared__ __attribute__((aligned(16))) unsigned char sL[GRAD_TT * LP];
     const GradItem it = p.items[blockIdx.y];
     const int s = it.seg;
     const SegDesc sd = p.seg[s];
     const int t_lo = it.t_lo, t_hi = it.t_hi;
     const bf16* const rbase = p.R_seg ? p.R_seg[s] - (size_t)p.off[s] * p.ncols : p.R;
-    const int c0 = blockIdx.x * GRAD_CT;
+    const int c0 = blockIdx.x * CT;
     const int nb = sd.rpad >> 4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-    floatx4 acc[2][RB];
+    floatx4 acc[NI][RB];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
         for (int j = 0; j < RB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    // R tile: 32 rows x 16 chunks of 8 columns = 512 chunks, 2 per thread.  L tile: 32 x (rpad/4) chunks,
+    // R tile: 32 rows x CT/8 chunks of 8 columns, NRC per thread.  L tile: 32 x (rpad/4) chunks,
     // at most NLC per thread.  Three register sets: the chunks of tokens t0 + 64 are requested while the
     // step at t0 multiplies, so a request has two steps to arrive (a step is far shorter than the memory
     // latency, and a launch over a few segments has too few workgroups per CU to hide it otherwise).
@@ -582,12 +581,12 @@ symb_lora_grad_kernel(const GradParams p) {
     constexpr int NLC = (GRAD_TT * 4 * RB + 255) / 256;
     const int lw = sd.rpad >> 2;                       // 16-byte chunks per L row: 2 * rpad bf16
     const int l_chunks = GRAD_TT * lw;
-    struct Stage { u32x4 rr[2]; u32x4 lv[NLC]; };
-    const bool col_ok = (c0 + (tid & 15) * 8) < p.ncols;
+    struct Stage { u32x4 rr[NRC]; u32x4 lv[NLC]; };
+    const bool col_ok = (c0 + (tid % LPRW) * 8) < p.ncols;
     auto fetch = [&](Stage& sg, int t0) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int c = tid + i * 256, tr = c >> 4, cc = c & 15;
+        for (int i = 0; i < NRC; ++i) {
+            const int c = tid + i * 256, tr = c / LPRW, cc = c % LPRW;
             const bf16* src = rbase + (size_t)min(t0 + tr, t_hi - 1) * p.ncols + c0 + (col_ok ? cc * 8 : 0);
             asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(sg.rr[i]) : "v"(src));
         }
@@ -601,10 +600,10 @@ symb_lora_grad_kernel(const GradParams p) {
     // the chunks of tokens t0.., landed (see step), go to LDS
     auto put = [&](const Stage& sg, int t0) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int c = tid + i * 256, tr = c >> 4, cc = c & 15;
+        for (int i = 0; i < NRC; ++i) {
+            const int c = tid + i * 256, tr = c / LPRW, cc = c % LPRW;
             const bool ok = (t0 + tr) < t_hi && col_ok;
-            *reinterpret_cast<u32x4*>(sR + tr * GRAD_RPITCH + cc * 16) = ok ? sg.rr[i] : u32x4{0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4*>(sR + tr * RPITCH + cc * 16) = ok ? sg.rr[i] : u32x4{0u, 0u, 0u, 0u};
         }
 #pragma unroll
         for (int i = 0; i < NLC; ++i) {
@@ -613,9 +612,9 @@ symb_lora_grad_kernel(const GradParams p) {
         }
     };
     auto multiply = [&]() __attribute__((always_inline)) {
-        bf16x8 rf[2];
+        bf16x8 rf[NI];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) rf[i] = lds_read_tr_16x32(sR, GRAD_RPITCH, wave * 32 + i * 16, lane);
+        for (int i = 0; i < NI; ++i) rf[i] = lds_read_tr_16x32(sR, RPITCH, wave * (NI * 16) + i * 16, lane);
 #pragma unroll
         for (int j = 0; j < RB; ++j) {
             if (j < nb) {
@@ -623,7 +622,7 @@ symb_lora_grad_kernel(const GradParams p) {
                 for (int half = 0; half < 2; ++half) {      // bf16 value, then its rounding residual
                     const bf16x8 lf = lds_read_tr_16x32(sL, LP, half * sd.rpad + j * 16, lane);
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) {
+                    for (int i = 0; i < NI; ++i) {
                         if constexpr (CMAJOR) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lf, rf[i], acc[i][j], 0, 0, 0);
                         else acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rf[i], lf, acc[i][j], 0, 0, 0);
                     }
@@ -635,11 +634,11 @@ symb_lora_grad_kernel(const GradParams p) {
         Stage sg0, sg1, sg2;
         fetch(sg0, t_lo);
         fetch(sg1, t_lo + GRAD_TT);
-        // cur: requested two fetches ago, so one fetch (2 + NLC loads, in order) may still be in flight
+        // cur: requested two fetches ago, so one fetch (NRC + NLC loads, in order) may still be in flight
         auto step = [&](Stage& cur, Stage& nxt, int t0) __attribute__((always_inline)) {
-            asm volatile("s_waitcnt vmcnt(%0)" : : "n"(2 + NLC) : "memory");
+            asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NRC + NLC) : "memory");
 #pragma unroll
-            for (int i = 0; i < 2; ++i) asm volatile("" : "+v"(cur.rr[i]));
+            for (int i = 0; i < NRC; ++i) asm volatile("" : "+v"(cur.rr[i]));
 #pragma unroll
             for (int i = 0; i < NLC; ++i) asm volatile("" : "+v"(cur.lv[i]));
             __syncthreads();     // previous step's LDS reads are done
@@ -658,13 +657,13 @@ symb_lora_grad_kernel(const GradParams p) {
     float* out = it.direct ? (CMAJOR ? sd.dB : sd.dA) : p.partial + it.partial_off;
     const bool accumulate = it.direct && p.accumulate;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
         for (int j = 0; j < RB; ++j) {
             if (j < nb) {
                 if constexpr (CMAJOR) {
                     // lane: column c = .. + (lane & 15); registers: pp = j*16 + 4*(lane >> 4) + q
-                    const int c = c0 + wave * 32 + i * 16 + (lane & 15);
+                    const int c = c0 + wave * (NI * 16) + i * 16 + (lane & 15);
                     if (c < p.ncols) {
                         const int pp0 = j * 16 + ((lane >> 4) << 2);
                         float* dst = out + (size_t)c * sd.rank + pp0;
@@ -681,7 +680,7 @@ symb_lora_grad_kernel(const GradParams p) {
                 } else {
                     // lane: pp = j*16 + (lane & 15); registers: column c = .. + 4*(lane >> 4) + q
                     const int pp = j * 16 + (lane & 15);
-                    const int c = c0 + wave * 32 + i * 16 + ((lane >> 4) << 2);
+                    const int c = c0 + wave * (NI * 16) + i * 16 + ((lane >> 4) << 2);
                     if (pp < sd.rank && c < p.ncols) {
                         float4* dst = reinterpret_cast<float4*>(out + (size_t)pp * p.ncols + c);
                         float4 v = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);

@@ -444,7 +444,7 @@ symb_status launch_skinny(symb_handle h, const SkinnyParams& sp, int nchunks, in
 
 template <int RB, bool CM>
 void launch_grad_rb(const GradParams& gp, int nitems, hipStream_t st) {
-    hipLaunchKernelGGL((symb_lora_grad_kernel<RB, CM>), dim3((gp.ncols + GRAD_CT - 1) / GRAD_CT, nitems), dim3(256), 0, st, gp);
+    hipLaunchKernelGGL((symb_lora_grad_kernel<RB, CM>), dim3((gp.ncols + GRAD_CT<RB> - 1) / GRAD_CT<RB>, nitems), dim3(256), 0, st, gp);
 }
 template <bool CM>
 symb_status launch_grad(symb_handle h, const GradParams& gp, int nseg, int max_rpad, hipStream_t st) {

@@ -80,3 +80,53 @@ def test_kernel_descriptors_claim_the_whole_register_file(device_asm):
         assert re.search(r"\.amdhsa_accum_offset %d\b" % (256 if big else 192), body), m.group(1)
         n += 1
     assert n == 8
+
+
+def _regs(operand):
+    """VGPR numbers named by an operand like v5 or v[6:9]."""
+    m = re.fullmatch(r"v\[(\d+):(\d+)\]", operand)
+    if m:
+        return set(range(int(m.group(1)), int(m.group(2)) + 1))
+    m = re.fullmatch(r"v(\d+)", operand)
+    return {int(m.group(1))} if m else set()
+
+
+def test_results_of_assembly_issued_loads_are_untouched_until_their_wait(device_asm):
+    # The skinny and gradient kernels request global and LDS data from assembly statements and wait for
+    # it with an s_waitcnt of their own; the compiler does not know the registers are still in flight.
+    # Nothing it generates between such a request and the next explicit wait may read or write them
+    # (a register copy placed there would copy stale data; requesting the skinny kernel's adapter rows a
+    # slice ahead, in registers that lived across the loop edge, produced exactly that).  Checked per
+    # straight-line stretch of the generated code: a label ends the stretch.
+    checked = 0
+    for m in re.finditer(r"^(_ZN4symb(?:18symb_skinny_kernel|21symb_lora_grad_kernel)\w+):(.*?)^\.Lfunc_end", device_asm, re.S | re.M):
+        pending, inside = set(), False
+        for raw in m.group(2).splitlines():
+            s = raw.strip().split(";")[0].strip() if "ASM" not in raw else raw.strip()
+            if "ASMSTART" in s:
+                inside = True
+                continue
+            if "ASMEND" in s:
+                inside = False
+                continue
+            if s.endswith(":") or re.match(r"^\.LBB\w+:", s):
+                pending.clear()
+                continue
+            if not s or s.startswith("."):
+                continue
+            op, _, rest = s.partition(" ")
+            args = [a.strip() for a in rest.split(",")]
+            if inside and (op == "global_load_dwordx4" or op == "ds_read_b128"):
+                pending |= _regs(args[0])
+                checked += 1
+                continue
+            if inside and op == "s_waitcnt":
+                if "vmcnt" in rest or "lgkmcnt" in rest:
+                    pending.clear()
+                continue
+            touched = set()
+            for a in args:
+                for tok in re.findall(r"v\[\d+:\d+\]|v\d+", a):
+                    touched |= _regs(tok)
+            assert not (touched & pending), (m.group(1), s, sorted(touched & pending))
+    assert checked > 50
