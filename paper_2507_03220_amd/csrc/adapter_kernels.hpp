@@ -574,10 +574,10 @@ symb_lora_grad_kernel(const GradParams p) {
     // at most NLC per thread.  Three register sets: the chunks of tokens t0 + 64 are requested while the
     // step at t0 multiplies, so a request has two steps to arrive (a step is far shorter than the memory
     // latency, and a launch over a few segments has too few workgroups per CU to hide it otherwise).
-    // Every load is unconditional (out-of-range chunks read a valid address and count as zero when they
-    // go to LDS) and is requested by an assembly statement, with the wait written out in step(): loads
-    // the compiler can see it puts under the condition again, and then waits for all of them, the newest
-    // request included.
+    // Every load is unconditional: out-of-range chunks read a valid address and count as zero when they go
+    // to LDS, two steps later.  (With the zeroing next to the load the compiler puts the load under the
+    // condition, and a load that may or may not have been issued makes it wait for all of them, the
+    // newest request included.)
     constexpr int NLC = (GRAD_TT * 4 * RB + 255) / 256;
     const int lw = sd.rpad >> 2;                       // 16-byte chunks per L row: 2 * rpad bf16
     const int l_chunks = GRAD_TT * lw;
@@ -587,14 +587,12 @@ symb_lora_grad_kernel(const GradParams p) {
 #pragma unroll
         for (int i = 0; i < NRC; ++i) {
             const int c = tid + i * 256, tr = c / LPRW, cc = c % LPRW;
-            const bf16* src = rbase + (size_t)min(t0 + tr, t_hi - 1) * p.ncols + c0 + (col_ok ? cc * 8 : 0);
-            asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(sg.rr[i]) : "v"(src));
+            sg.rr[i] = ld_glb16(rbase + (size_t)min(t0 + tr, t_hi - 1) * p.ncols + c0 + (col_ok ? cc * 8 : 0));
         }
 #pragma unroll
         for (int i = 0; i < NLC; ++i) {
             const int c = tid + i * 256, tr = c / lw, pc = c % lw;
-            const bf16* src = p.L + (size_t)min(t0 + tr, t_hi - 1) * p.l_pitch + pc * 8;
-            asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(sg.lv[i]) : "v"(src));
+            sg.lv[i] = ld_glb16(p.L + (size_t)min(t0 + tr, t_hi - 1) * p.l_pitch + pc * 8);
         }
     };
     // the chunks of tokens t0.., landed (see step), go to LDS
@@ -634,13 +632,8 @@ symb_lora_grad_kernel(const GradParams p) {
         Stage sg0, sg1, sg2;
         fetch(sg0, t_lo);
         fetch(sg1, t_lo + GRAD_TT);
-        // cur: requested two fetches ago, so one fetch (NRC + NLC loads, in order) may still be in flight
+        // cur was requested two fetches ago: the compiler's wait for it leaves the newest fetch in flight
         auto step = [&](Stage& cur, Stage& nxt, int t0) __attribute__((always_inline)) {
-            asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NRC + NLC) : "memory");
-#pragma unroll
-            for (int i = 0; i < NRC; ++i) asm volatile("" : "+v"(cur.rr[i]));
-#pragma unroll
-            for (int i = 0; i < NLC; ++i) asm volatile("" : "+v"(cur.lv[i]));
             __syncthreads();     // previous step's LDS reads are done
             put(cur, t0);
             __syncthreads();
@@ -652,7 +645,6 @@ symb_lora_grad_kernel(const GradParams p) {
             if (t0 + GRAD_TT < t_hi) step(sg1, sg0, t0 + GRAD_TT);
             if (t0 + 2 * GRAD_TT < t_hi) step(sg2, sg1, t0 + 2 * GRAD_TT);
         }
-        asm volatile("s_waitcnt vmcnt(0)" : : : "memory");     // the requests past the end
     }
     float* out = it.direct ? (CMAJOR ? sd.dB : sd.dA) : p.partial + it.partial_off;
     const bool accumulate = it.direct && p.accumulate;
