@@ -64,7 +64,7 @@ typedef enum {
     SYMB_OK = 0,
     SYMB_ERR_INVALID_ARG = 1,         /* null pointer, bad dimension, bad flag, misaligned pointer */
     SYMB_ERR_BAD_SEGMENTS = 2,        /* off[0] != 0 or offsets decrease */
-    SYMB_ERR_UNSUPPORTED = 3,         /* valid request this build cannot run (e.g. IA3_IN, rank > SYMB_MAX_RANK) */
+    SYMB_ERR_UNSUPPORTED = 3,         /* valid request this build cannot run (e.g. rank > SYMB_MAX_RANK) */
     SYMB_ERR_WORKSPACE_TOO_SMALL = 4,
     SYMB_ERR_DEVICE = 5               /* a HIP call failed; see symb_last_error */
 } symb_status;
@@ -73,7 +73,7 @@ typedef enum {
     SYMB_ADAPTER_NONE = 0,
     SYMB_ADAPTER_LORA = 1,
     SYMB_ADAPTER_IA3 = 2,             /* output scaling, l[d_out] */
-    SYMB_ADAPTER_IA3_IN = 3           /* input scaling, l[d_in]: defined, not built on the GPU -> UNSUPPORTED */
+    SYMB_ADAPTER_IA3_IN = 3           /* input scaling, l[d_in]: y = (l * x) W^T */
 } symb_adapter_kind;
 
 enum { SYMB_MAX_RANK = 128 };

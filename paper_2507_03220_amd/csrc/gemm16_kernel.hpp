@@ -51,6 +51,7 @@ struct GemmParams {
                                 // then rpad residuals of the row's own segment; null = no LoRA term
     int ext_pitch;
     int epi_ia3;                // 0, or the adapter kind whose rows the epilogue scales by its vector l_i[n]
+    const int32_t* tile_epi;    // with epi_ia3: per row tile, 1 if it holds rows of such a segment (the others take the plain epilogue)
                                 // (IA3 in the forward, IA3_IN in the input gradient)
     // Per-segment buffers instead of flat tensors (device arrays of S pointers, or null): row t of
     // segment i is a_seg[i] + (t - off[i]) * K resp. c_seg[i] + (t - off[i]) * N.  All a_seg buffers lie
@@ -621,7 +622,7 @@ symb_gemm16_kernel(const GemmParams p) {
     if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 4] = __builtin_amdgcn_s_memrealtime();
 #endif
     // ---- final output: bias, IA3 scale, noise effect, one rounding, whole-row stores
-    stage_out(p.C, p.epi_ia3 != 0);
+    stage_out(p.C, p.epi_ia3 != 0 && p.tile_epi[tm] != 0);
 #ifdef SYMB_GEMM_TRACE
     if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 7] = __builtin_amdgcn_s_memrealtime();
     __builtin_amdgcn_s_waitcnt(0);

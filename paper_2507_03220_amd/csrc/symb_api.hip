@@ -134,6 +134,14 @@ void plan_row_tiles(const symb_batch* b, int tile_m, std::vector<int32_t>& lo, s
     }
 }
 
+// Per row tile: 1 if one of its segments is of `kind` (the tiles whose epilogue has rows to scale).
+std::vector<int32_t> plan_tile_kind(const symb_batch* b, const std::vector<int32_t>& lo, const std::vector<int32_t>& hi, int kind) {
+    std::vector<int32_t> v(lo.size(), 0);
+    for (size_t u = 0; u < lo.size(); ++u)
+        for (int i = lo[u]; i <= hi[u] && !v[u]; ++i) v[u] = b->adapters[i].kind == kind;
+    return v;
+}
+
 void plan_chunks(const symb_batch* b, int rows, bool lora_only, std::vector<RowChunk>& out) {
     out.clear();
     for (int i = 0; i < b->num_segments; ++i) {
@@ -699,6 +707,8 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     const size_t o_off = blob.add(b->seg_offsets, (size_t)bi.S + 1);
     const size_t o_lo = blob.add(lo.data(), lo.size());
     const size_t o_hi = blob.add(hi.data(), hi.size());
+    const std::vector<int32_t> tile_epi = plan_tile_kind(b, lo, hi, SYMB_ADAPTER_IA3);
+    const size_t o_te = blob.add(tile_epi.data(), tile_epi.size());
     const size_t o_ch = blob.add(chunks.data(), chunks.size());
     const size_t o_nd = blob.add(nd.data(), nd.size());
     const size_t o_pk = blob.add(pk_off.data(), pk_off.size());
@@ -777,6 +787,7 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     gp.ext = Hs;
     gp.ext_pitch = 2 * bi.max_rpad;
     gp.epi_ia3 = bi.n_ia3 > 0 ? KIND_IA3 : 0;
+    gp.tile_epi = (const int32_t*)(dev + o_te);
     gp.neff = nd.empty() ? nullptr : (const NoiseDesc*)(dev + o_nd);
     gp.timing_flops = gemm_flops(b, b->d_out, b->d_in, bi.n_lora > 0);
     if (k_split) {
@@ -923,6 +934,8 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     const size_t o_off = blob.add(b->seg_offsets, (size_t)bi.S + 1);
     const size_t o_lo = blob.add(lo.data(), lo.size());
     const size_t o_hi = blob.add(hi.data(), hi.size());
+    const std::vector<int32_t> tile_epi = plan_tile_kind(b, lo, hi, SYMB_ADAPTER_IA3_IN);
+    const size_t o_te = blob.add(tile_epi.data(), tile_epi.size());
     const size_t o_ch = blob.add(chunks.data(), chunks.size());
     const size_t o_all = blob.add(all_chunks.data(), all_chunks.size());
     const size_t o_pk = blob.add(pk_off.data(), pk_off.size());
@@ -992,6 +1005,7 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     gp.ext = dH;
     gp.ext_pitch = 2 * bi.max_rpad;
     gp.epi_ia3 = (full && bi.n_ia3in > 0) ? KIND_IA3_IN : 0;      // dX rows of IA3_IN segments: l_i * (dY W)
+    gp.tile_epi = (const int32_t*)(dev + o_te);
     gp.timing_flops = gemm_flops(b, b->d_in, b->d_out, lora);
     if (k_split) {
         gp.k_parts = ksp.parts;
