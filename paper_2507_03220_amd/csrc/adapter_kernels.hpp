@@ -17,9 +17,9 @@ struct RowChunk {
 // value plus a bf16 residual (out[t][rpad_i + p])
 //   forward shrink : L = X  [T][K=d_in],  R_i = A_i  [r][d_in]
 //   backward dH    : L = dY [T][K=d_out], R_i = B_i^T packed [rpad][d_out] (see pack kernel)
-// A workgroup owns 32 rows; its 4 wavefronts split K in interleaved 128-element steps, read
-// MFMA fragments straight from global memory (each row is read as whole 128-byte lines, the
-// adapter rows come from L2), and meet in LDS for the final sum.  RB = max rank blocks of 16.
+// A workgroup owns 32 rows; its 4 wavefronts split K in interleaved slices, bring the rows in
+// through LDS (see SkinnyStage below), take the adapter rows from L2, and meet in LDS for the
+// final sum.  RB = max rank blocks of 16.
 // -------------------------------------------------------------------------------------------
 struct SkinnyParams {
     const bf16* L;            // [T][K]
@@ -40,6 +40,8 @@ struct SkinnyParams {
 constexpr int SKINNY_BLKS = SYMB_SKINNY_BLKS;          // 16-row MFMA blocks per wavefront
 constexpr int SKINNY_ROWS = 16 * SKINNY_BLKS;          // rows per workgroup
 
+// The same inner product with the MFMA fragments read straight from global memory (used by the
+// small-batch forward kernel below, whose "rows" are 32 rows of W and whose "adapter rows" are X):
 // acc[b][j] += sum over this wavefront's share of K of  L-rows (16-row block b) x R-rows (16-row block j):
 // lane (trow = lane % 16, kq = lane / 16) supplies row trow and k-offsets kq*8..kq*8+7 of each 32-k step
 // for both operands; the result lane holds acc[b][j][q] = dot(L row b*16 + trow, R row j*16 + 4*kq + q).

@@ -374,10 +374,6 @@ std::vector<SegDesc> make_segdesc(const symb_batch* b) {
 }
 
 // ---- GEMM launch -----------------------------------------------------------------------------
-struct GemmChoice {
-    int bm;
-};
-
 template <class KFN>
 symb_status launch_gemm_fn(symb_handle h, GemmParams gp, hipStream_t st, KFN kfn, int BM, int BN, int threads, int smem, bool nn) {
     // once per context (= per device): the attribute belongs to the device the kernel is loaded on
