@@ -145,7 +145,7 @@ symb_status symb_plan_row_tiles(const symb_batch* b, int32_t tile_m, int32_t* se
  * fp32 partial tiles: such a call computes output tiles in several workgroups, one per
  * range of the inner dimension -- every tile of a batch of a few hundred rows (which alone
  * would leave most of the chip idle), or the tiles of a last round of workgroups that
- * would be less than half full (up to 64 MiB).  That region is optional: a workspace that
+ * would be partly empty (up to 160 MiB).  That region is optional: a workspace that
  * covers everything before it (in particular none at all for a batch without adapters)
  * makes the call run without the split, only slower; anything smaller fails with
  * SYMB_ERR_WORKSPACE_TOO_SMALL. */

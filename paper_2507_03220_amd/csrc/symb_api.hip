@@ -207,9 +207,11 @@ int gemm_walk() {
 //    of load and LDS latencies of about 0.5 us per 64 k): all tiles split (whole = 0),
 //    parts = 320 / tiles: three parts for 96 tiles, none from 161 tiles on.
 //  * 256x256 tiles, one workgroup per CU, 32 CUs per XCD: a run of per_xcd tiles ends in a round of
-//    rem = per_xcd % 32 tiles that takes as long as a full one.  If rem <= 16 these last tiles are
-//    split into parts = 32 / rem (at most 4), so the last round is full and 1 / parts as long, plus
-//    the sum of the partial tiles (256 KiB each).
+//    rem = per_xcd % 32 tiles that takes as long as a full one.  These last tiles are split into the
+//    number of parts (at most 4) that makes the round shortest by a simple model of its time: e.g.
+//    4 parts for 8 tiles (a quarter of a tile's time), 3 parts for 20 tiles of a long K (60
+//    workgroups in two passes of a third each), none where the sum of the partial tiles (256 KiB
+//    each) would cost what the split saves.
 // parts is at most 8 and at most one per 8 stages of 64 k.  SYMB_GEMM_KSPLIT=0 turns both off,
 // SYMB_GEMM_KSPLIT=n replaces the 320 (tuning aids).
 struct SplitPlan {
@@ -235,8 +237,16 @@ SplitPlan gemm_split_plan(int M, int N, int K) {
         const long tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
         const int per_xcd = (int)((tiles + 7) / 8), rem = per_xcd % 32;
         if (rem == 0) return s;
-        const int P = std::min({tail_max, KF / 8, 32 / rem});
-        if (P < 2) return s;
+        // The last round takes ceil(rem * P / 32) / P of a tile's time (a tile: about 1.45 us per stage)
+        // plus, when split, about 8 + 4 P us for storing and adding up the partial tiles.
+        const double tile_us = 1.45 * KF;
+        int P = 1;
+        double best = tile_us;
+        for (int q = 2; q <= std::min(tail_max, KF / 8); ++q) {
+            const double us = (double)((rem * q + 31) / 32) / q * tile_us + 8.0 + 4.0 * q;
+            if (us < best - 4.0) { best = us; P = q; }      // a gain of a few us is not worth the traffic
+        }
+        if (P < 2 || best > 0.85 * tile_us) return s;      // nor is a gain of less than 15 % of the round
         s.parts = P;
         s.whole = per_xcd - rem;
         s.slots = 8 * rem;

@@ -153,11 +153,15 @@ def test_workspace_includes_partial_tiles_of_a_k_split():
     # 20480 rows: 80 x 16 tiles of 256 x 256, 160 per XCD = 5 full rounds of its 32 CUs: no split
     assert sb.symb_workspace_bytes(sb.Batch(4096, 4096, [0, 20480], [sb.Adapter()]), sb.SYMB_OP_FWD) == 0
     # 9049 rows: 36 x 16 = 576 tiles, 72 per XCD: the last 8 of them would be a round of their own and are
-    # split over 32 // 8 = 4 K ranges each (8 XCDs x 8 tiles x 4 partial tiles of 256 KiB)
-    assert sb.symb_workspace_bytes(sb.Batch(4096, 4096, [0, 9049], [sb.Adapter()]), sb.SYMB_OP_FWD) == 8 * 8 * 4 * 256 * 256 * 4
+    # split over 3 K ranges each (24 workgroups on the XCD's 32 CUs; a fourth part would save less than it costs
+    # to add up): 8 XCDs x 8 tiles x 3 partial tiles of 256 KiB
+    assert sb.symb_workspace_bytes(sb.Batch(4096, 4096, [0, 9049], [sb.Adapter()]), sb.SYMB_OP_FWD) == 8 * 8 * 3 * 256 * 256 * 4
     # 20480 rows on 4608 -> 2048: 640 tiles, 80 per XCD, the last 16 split in two
     assert sb.symb_workspace_bytes(sb.Batch(4608, 2048, [0, 20480], [sb.Adapter()]), sb.SYMB_OP_FWD) == 8 * 16 * 2 * 256 * 256 * 4
-    # ... 1440 tiles, 180 per XCD: a last round of 20 tiles is more than half full and stays whole
+    # ... 1440 tiles, 180 per XCD, a last round of 20 tiles: in three parts they are 60 workgroups, two passes of
+    # a third of a tile's time each.  Worth it on the long inner dimension (input gradient of 36864 -> 4608:
+    # 576 stages per tile); on 4096 stages of work the sum of the partial tiles would eat the gain
+    assert sb.symb_workspace_bytes(sb.Batch(36864, 4608, [0, 20480], [sb.Adapter()]), sb.SYMB_OP_FWD) == 8 * 20 * 3 * 256 * 256 * 4
     assert sb.symb_workspace_bytes(sb.Batch(4096, 4608, [0, 20480], [sb.Adapter()]), sb.SYMB_OP_FWD) == 0
 
 
