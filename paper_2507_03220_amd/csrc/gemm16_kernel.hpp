@@ -146,7 +146,7 @@ symb_gemm16_kernel(const GemmParams p) {
     // ---- tile of this workgroup
     // Every XCD (blockIdx & 7) walks a contiguous run of per_xcd tiles.  With a K-split (k_parts > 1)
     // the tiles of that run from number k_whole on are computed by k_parts workgroups each, one per
-    // K range, neighbours in the XCD's walk: all tiles of a launch too small to fill the chip
+    // K range, all on this XCD: all tiles of a launch too small to fill the chip
     // (k_whole = 0), or the tiles of a last, mostly empty round.
     const int total = p.num_m_tiles * p.num_n_tiles;
     int lin, part = 0, nparts = 1, slot = 0;
@@ -159,11 +159,14 @@ symb_gemm16_kernel(const GemmParams p) {
         const int item = blockIdx.x >> 3;
         int li = item;
         if (p.k_parts > 1 && item >= p.k_whole) {
-            const int j = item - p.k_whole;
-            li = p.k_whole + j / p.k_parts;
+            // part-major: first every split tile's last K range (the one that also has the LoRA steps
+            // and the K remainder to do), then the one before ...: tiles that run side by side then walk
+            // the same K range and share their operand panels in L2
+            const int j = item - p.k_whole, nsplit = per_xcd - p.k_whole;
             nparts = p.k_parts;
-            part = j - (li - p.k_whole) * nparts;
-            slot = (blockIdx.x & 7) * (per_xcd - p.k_whole) + (li - p.k_whole);   // partial tiles and counter of this tile
+            part = nparts - 1 - j / nsplit;
+            li = p.k_whole + j % nsplit;
+            slot = (blockIdx.x & 7) * nsplit + (li - p.k_whole);   // partial tiles and counter of this tile
         }
         lin = (blockIdx.x & 7) * per_xcd + li;
         if (lin >= total || li >= per_xcd) return;
