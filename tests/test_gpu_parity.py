@@ -447,6 +447,9 @@ def test_ia3_input_scaling(case):
     dict(seed=61, d_in=320, d_out=264, lens=[130, 1, 0, 77, 1, 300, 64], kinds=[L, I, L, N, L, L, I], ranks=[8, 16, 5, 24, 33]),
     dict(seed=62, d_in=136, d_out=6208, lens=[700, 5, 795], kinds=[L, I, L], ranks=[16, 8]),
     dict(seed=63, d_in=6208, d_out=136, lens=[700, 5, 795], kinds=[L, N, L], ranks=[16, 5]),
+    # 266 tiles of 256x256 with the last round split over K ranges, rows from and to per-client buffers
+    dict(seed=64, d_in=2056, d_out=33800, lens=[120, 1, 99, 80], kinds=[L, I, L, N], ranks=[16, 8, 40]),
+    dict(seed=65, d_in=33800, d_out=2056, lens=[120, 1, 99, 80], kinds=[L, N, L, L], ranks=[16, 8, 40, 24]),
 ])
 def test_per_segment_buffers(case):
     """Rows read from and written to one buffer per client, carved in shuffled order and with gaps
