@@ -148,7 +148,12 @@ symb_status symb_plan_row_tiles(const symb_batch* b, int32_t tile_m, int32_t* se
  * would be partly empty (up to 160 MiB).  That region is optional: a workspace that
  * covers everything before it (in particular none at all for a batch without adapters)
  * makes the call run without the split, only slower; anything smaller fails with
- * SYMB_ERR_WORKSPACE_TOO_SMALL. */
+ * SYMB_ERR_WORKSPACE_TOO_SMALL.  Every call is deterministic (the same arguments give the
+ * same bits, whatever order the workgroups finish in); a split call sums the inner dimension
+ * in a different order than an unsplit one, so the two can differ in the last rounding.  For
+ * SYMB_OP_ADAPTER_GRAD the figure includes room for the partial sums of LoRA gradients of
+ * segments longer than 1536 tokens (summed in runs of 1024 tokens, the runs added in order: a
+ * segment's gradient does not depend on what else is in the batch). */
 symb_status symb_workspace_bytes(const symb_batch* b, int32_t op, size_t* out);
 
 /*
