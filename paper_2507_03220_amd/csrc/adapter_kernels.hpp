@@ -138,19 +138,22 @@ __device__ __forceinline__ void skinny_dot(const bf16* (&lrow)[SKINNY_BLKS], con
 // brings its K slices (SKINNY_ROWS rows x SK elements) in through LDS DMA, whole rows of the slice
 // per request, into NBUF buffers of its own (no workgroup barrier in the loop), and reads the
 // fragments from LDS.  The 16-byte chunks of a row are stored at chunk ^ f(row), so the 16 rows a
-// fragment read touches fall on different banks.  Measured on 1.5 GB inputs: 4.0 -> 5.0 TB/s; 128-
-// element slices beat 64-element ones at rank <= 32 and lose at rank 128 (the adapter rows of a slice
-// stay in registers: 128 of them at rank 128), a third buffer or a third workgroup per CU changes nothing.
+// fragment read touches fall on different banks.  The adapter rows of a slice (from L2) come the same
+// way, into one more buffer.  Measured on 1.5 GB inputs: 4.0 -> 5.0 TB/s; 128-element slices are best
+// at rank <= 16, 64-element ones above (LDS for the adapter rows); a third buffer or a third workgroup
+// per CU changes nothing.
 template <int RB>
 struct SkinnyStage {
-    static constexpr int SK = RB >= 4 ? 64 : 128;         // K elements per slice
+    static constexpr int SK = RB >= 2 ? 64 : 128;         // K elements per slice
     static constexpr int NBUF = 2;                        // slices a wavefront keeps in LDS
     static constexpr int ROW_BYTES = SK * 2;
     static constexpr int LPR = ROW_BYTES / 16;            // lanes (16-byte chunks) per row
     static constexpr int RPI = 64 / LPR;                  // rows per DMA request of one wavefront
     static constexpr int DPS = SKINNY_ROWS / RPI;         // DMA requests per slice
     static constexpr int SLICE = SKINNY_ROWS * ROW_BYTES;
-    static constexpr int BYTES = 4 * NBUF * SLICE;
+    static constexpr int RSLICE = RB * 16 * ROW_BYTES;    // the adapter rows of one slice (one buffer)
+    static constexpr int WAVE_BYTES = NBUF * SLICE + RSLICE;
+    static constexpr int BYTES = 4 * WAVE_BYTES;
     static_assert(SK == 64 || SK == 128, "a row of a slice is one or two 128-byte lines");
     __device__ static constexpr int swz(int r) { return (r / (16 / LPR)) & (LPR - 1); }
 };
@@ -170,51 +173,67 @@ __device__ __forceinline__ u32x4 ld_glb16(const bf16* p) {
 // lane brings in with DMA request i of a slice (at k = 0); wbuf = this wavefront's slice buffers.
 template <int RB, int NB>
 __device__ __forceinline__ void skinny_stream(const bf16* (&lrow)[SKINNY_BLKS], const bf16* (&rrow)[RB], const bool (&r_ok)[RB],
-                                              const bf16* (&src)[SkinnyStage<RB>::DPS], unsigned char* wbuf, int K, int wave,
-                                              int trow, int kq, floatx4 (&acc)[SKINNY_BLKS][RB]) {
+                                              const bf16* (&src)[SkinnyStage<RB>::DPS], const bf16* rbase, int rrows,
+                                              unsigned char* wbuf, int K, int wave, int lane, floatx4 (&acc)[SKINNY_BLKS][RB]) {
     using ST = SkinnyStage<RB>;
     constexpr int NH = ST::SK / 32;                      // MFMA k-steps per slice
-    unsigned foff[SKINNY_BLKS][NH];                      // fragment (b, h) of this lane within a slice buffer
+    constexpr int NRD = NB * 16 / ST::RPI;               // DMA requests for the adapter rows of a slice
+    const int trow = lane & 15, kq = lane >> 4;
+    unsigned char* const rbuf = wbuf + ST::NBUF * ST::SLICE;
+    unsigned foff[SKINNY_BLKS][NH], roff[NB][NH];        // fragment (b, h) / (j, h) of this lane within a slice buffer
 #pragma unroll
-    for (int b = 0; b < SKINNY_BLKS; ++b)
+    for (int h = 0; h < NH; ++h) {
 #pragma unroll
-        for (int h = 0; h < NH; ++h) {
+        for (int b = 0; b < SKINNY_BLKS; ++b) {
             const int r = b * 16 + trow;
             foff[b][h] = (unsigned)(size_t)wbuf + (unsigned)(r * ST::ROW_BYTES + (((h * 4 + kq) ^ ST::swz(r)) * 16));
         }
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int r = j * 16 + trow;
+            roff[j][h] = (unsigned)(size_t)rbuf + (unsigned)(r * ST::ROW_BYTES + (((h * 4 + kq) ^ ST::swz(r)) * 16));
+        }
+    }
+    // The adapter rows (from L2) come in by LDS DMA as well, whole row pieces per request: fragment loads
+    // straight from global memory are 64-byte pieces of 16 rows each, twice the requests for the bytes.
+    // Rows past the adapter's last are read from row 0 and count as zero (r_ok).
+    const bf16* rsrc[NRD];
+#pragma unroll
+    for (int i = 0; i < NRD; ++i) {
+        const int r = i * ST::RPI + lane / ST::LPR;
+        rsrc[i] = rbase + (size_t)(r < rrows ? r : 0) * K + (((lane % ST::LPR) ^ ST::swz(r)) * 8);
+    }
     auto dma = [&](int buf, int k) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < ST::DPS; ++i)
             __builtin_amdgcn_global_load_lds((glb_void_t*)(src[i] + k), (lds_void_t*)(wbuf + buf * ST::SLICE + i * 1024), 16, 0, 0);
     };
-    // Adapter rows (from L2) and fragment reads are assembly statements with waits of their own: while an
-    // LDS DMA request is in flight the compiler makes every load result it can see wait for all memory
-    // traffic of the wavefront, the slices requested ahead included.  Each result is tied ("+v") to
-    // the wait that covers it, so no use can move in front of that wait.
-    auto load_r = [&](u32x4 (&rv)[NB][NH], int k) __attribute__((always_inline)) {
+    auto dma_r = [&](int k) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
-#pragma unroll
-            for (int h = 0; h < NH; ++h)
-                asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(rv[j][h]) : "v"(rrow[j] + k), "n"(h * 64));
+        for (int i = 0; i < NRD; ++i)
+            __builtin_amdgcn_global_load_lds((glb_void_t*)(rsrc[i] + k), (lds_void_t*)(rbuf + i * 1024), 16, 0, 0);
     };
-    auto settle_r = [&](u32x4 (&rv)[NB][NH]) __attribute__((always_inline)) {
+    // The fragment reads are assembly statements with a wait of their own: while an LDS DMA request is in
+    // flight the compiler makes every load result it can see wait for all memory traffic of the
+    // wavefront, the slice requested ahead included.  Each result is tied ("+v") to the wait that
+    // covers it, so no use can move in front of that wait.  mul() returns with its LDS reads
+    // complete: both buffers it read may be requested again.
+    auto mul = [&](int buf) __attribute__((always_inline)) {
+        u32x4 lv[SKINNY_BLKS][NH], rv[NB][NH];
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            if constexpr (NH == 4) asm volatile("" : "+v"(rv[j][0]), "+v"(rv[j][1]), "+v"(rv[j][2]), "+v"(rv[j][3]));
-            else asm volatile("" : "+v"(rv[j][0]), "+v"(rv[j][1]));
+        for (int h = 0; h < NH; ++h) {
+#pragma unroll
+            for (int b = 0; b < SKINNY_BLKS; ++b) asm volatile("ds_read_b128 %0, %1" : "=v"(lv[b][h]) : "v"(foff[b][h] + buf * ST::SLICE));
+#pragma unroll
+            for (int j = 0; j < NB; ++j) asm volatile("ds_read_b128 %0, %1" : "=v"(rv[j][h]) : "v"(roff[j][h]));
         }
-    };
-    auto mul = [&](int buf, const u32x4 (&rv)[NB][NH]) __attribute__((always_inline)) {
-        u32x4 lv[SKINNY_BLKS][NH];
+        asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");
 #pragma unroll
-        for (int b = 0; b < SKINNY_BLKS; ++b)
+        for (int h = 0; h < NH; ++h) {
 #pragma unroll
-            for (int h = 0; h < NH; ++h) asm volatile("ds_read_b128 %0, %1" : "=v"(lv[b][h]) : "v"(foff[b][h] + buf * ST::SLICE));
+            for (int b = 0; b < SKINNY_BLKS; ++b) asm volatile("" : "+v"(lv[b][h]));
 #pragma unroll
-        for (int b = 0; b < SKINNY_BLKS; ++b) {
-            if constexpr (NH == 4) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(lv[b][0]), "+v"(lv[b][1]), "+v"(lv[b][2]), "+v"(lv[b][3]));
-            else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(lv[b][0]), "+v"(lv[b][1]));
+            for (int j = 0; j < NB; ++j) asm volatile("" : "+v"(rv[j][h]));
         }
 #pragma unroll
         for (int h = 0; h < NH; ++h)
@@ -230,9 +249,7 @@ __device__ __forceinline__ void skinny_stream(const bf16* (&lrow)[SKINNY_BLKS], 
     // are requested up front; iteration s requests slice s + np (while there is one) into the buffer
     // iteration s - 1 has finished reading, after the adapter rows of slice s: the memory counter
     // retires in order, so the wait for slice s and its adapter rows leaves exactly the newest slice's
-    // DPS requests in flight.  The adapter rows are requested and awaited within one iteration: a
-    // register that is still in flight must not live across the loop edge, where the compiler may
-    // copy it (requesting them a slice ahead was worth 2 % and did exactly that).
+    // DPS requests in flight.
     int k0 = wave * ST::SK;
     const int ns = K >= k0 + ST::SK ? (K - k0 - ST::SK) / (4 * ST::SK) + 1 : 0;
     const int np = ns < ST::NBUF - 1 ? ns : ST::NBUF - 1;
@@ -240,22 +257,18 @@ __device__ __forceinline__ void skinny_stream(const bf16* (&lrow)[SKINNY_BLKS], 
     int cur = 0, nxt = np;                               // buffer of slice s, of slice s + np
     int s = 0;
     for (; s + np < ns; ++s) {
-        u32x4 rv[NB][NH];
-        load_r(rv, k0);
+        dma_r(k0);
         dma(nxt, k0 + np * 4 * ST::SK);
         asm volatile("s_waitcnt vmcnt(%0)" : : "n"(ST::DPS) : "memory");
-        settle_r(rv);
-        mul(cur, rv);                                    // returns with its LDS reads complete: the buffer may be requested again
+        mul(cur);
         cur = cur + 1 == ST::NBUF ? 0 : cur + 1;
         nxt = nxt + 1 == ST::NBUF ? 0 : nxt + 1;
         k0 += 4 * ST::SK;
     }
     for (; s < ns; ++s) {                                // the last np slices: nothing left to request
-        u32x4 rv[NB][NH];
-        load_r(rv, k0);
+        dma_r(k0);
         asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
-        settle_r(rv);
-        mul(cur, rv);
+        mul(cur);
         cur = cur + 1 == ST::NBUF ? 0 : cur + 1;
         k0 += 4 * ST::SK;
     }
@@ -325,7 +338,7 @@ symb_skinny_kernel(const SkinnyParams p) {
 #pragma unroll
         for (int j = 0; j < RB; ++j) acc[b][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    skinny_stream_dispatch<RB>(nb, lrow, rrow, r_ok, src, smem + wave * (ST::NBUF * ST::SLICE), p.K, wave, trow, kq, acc);
+    skinny_stream_dispatch<RB>(nb, lrow, rrow, r_ok, src, rbase, rrows, smem + wave * ST::WAVE_BYTES, p.K, wave, lane, acc);
     __syncthreads();                                     // every wavefront is done with its slice buffers
     // lane holds out[t = b*16 + trow][p = j*16 + 4*kq + q]
     if (wave > 0) {
