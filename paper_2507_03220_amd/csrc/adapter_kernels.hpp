@@ -382,7 +382,8 @@ symb_skinny_kernel(const SkinnyParams p) {
 }
 
 // -------------------------------------------------------------------------------------------
-// Forward for a batch of at most 128 rows (a handful of decode steps, Sec. 4's inference clients):
+// Forward for a batch of at most 16 RB rows (a handful of decode steps, Sec. 4's inference clients;
+// the library uses RB = 1: beyond 16 rows the tiled kernel with its K-split is faster):
 //   Y[t][n] = sum_k X[t][k] W[n][k] (+ b[n]) (+ sum_p Hs[t][p] B_i[n][p])  (* l_i[n])
 // With so few rows a tiled GEMM launches too few workgroups to stream W at HBM speed.  Here a
 // workgroup owns 32 output columns: it streams those 32 rows of W once (the 4 wavefronts split K),

@@ -757,17 +757,18 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
         }
         if ((st = launch_skinny(h, sp, (int)chunks.size(), bi.max_rpad, s)) != SYMB_OK) return st;
     }
-    // A handful of rows (decode steps): stream W once with one workgroup per 32 output columns
-    // instead of a tiled GEMM that would launch only a few dozen workgroups.
+    // A handful of rows (decode steps) on a layer of moderate size: stream W once with one workgroup
+    // per 32 output columns.  Measured against the tiled kernel with its K-split (33-40 us per call
+    // from 4 to 64 rows): 27-32 us up to 16 rows on 4096 x 4096, but slower from 24 rows on, and on
+    // 4096 x 11008 at any row count (this kernel streams W at 2.7 TB/s only).  SYMB_SMALL_T=0 turns
+    // it off (tuning aid).
     static const bool small_path = [] { const char* e = getenv("SYMB_SMALL_T"); return !e || atoi(e) != 0; }();
-    if (small_path && bi.T <= 128 && !conv1d && !seg_io && !Ybase && nd.empty() && bi.n_ia3in == 0) {
+    if (small_path && bi.T <= 16 && (long long)b->d_in * b->d_out <= 24ll << 20 && !conv1d && !seg_io && !Ybase && nd.empty() &&
+        bi.n_ia3in == 0) {
         RowGemvParams rp{(const bf16*)W, (const bf16*)X, (bf16*)Y, (const bf16*)bias, b->d_in, b->d_out, bi.T, bi.S,
                          (const int32_t*)(dev + o_off), (const SegDesc*)(dev + o_seg), Hs, 2 * bi.max_rpad};
         const dim3 grid((b->d_out + SKINNY_ROWS - 1) / SKINNY_ROWS);
-        if (bi.T <= 16) hipLaunchKernelGGL(symb_rowgemv_kernel<1>, grid, dim3(256), 0, s, rp);
-        else if (bi.T <= 32) hipLaunchKernelGGL(symb_rowgemv_kernel<2>, grid, dim3(256), 0, s, rp);
-        else if (bi.T <= 64) hipLaunchKernelGGL(symb_rowgemv_kernel<4>, grid, dim3(256), 0, s, rp);
-        else hipLaunchKernelGGL(symb_rowgemv_kernel<8>, grid, dim3(256), 0, s, rp);
+        hipLaunchKernelGGL(symb_rowgemv_kernel<1>, grid, dim3(256), 0, s, rp);
         SYMB_HIP(h, hipGetLastError());
         return seal_slot(h, s);
     }

@@ -555,9 +555,9 @@ def test_large_tile_kernel_with_one_to_five_k_stages(d_in):
 
 @pytest.mark.parametrize("lens", [[1], [16], [9, 0, 8], [1, 1, 20, 1, 1, 24], [30, 1, 40, 29], [1] * 48, [50, 78]])
 def test_forward_of_a_handful_of_rows(lens):
-    """Batches of at most 128 rows (decode steps) take a kernel of their own that streams W once:
-    1, 16, 17, 48, 100 and 128 rows; K with a remainder, d_out not a multiple of 32; every adapter
-    kind, ranks 1..128, bias."""
+    """Batches of at most 16 rows (decode steps) take a kernel of their own that streams W once, larger
+    ones the 128x128 tiles with every tile split over K ranges: 1, 16, 17, 48, 100 and 128 rows; K with
+    a remainder, d_out not a multiple of 32; every adapter kind, ranks 1..128, bias."""
     kinds = [L, I, N, L, L, I]
     p = make_problem(90 + len(lens), 200, 392, lens, kinds, [1, 128, 24, 8, 100])
     assert p["T"] <= 128
