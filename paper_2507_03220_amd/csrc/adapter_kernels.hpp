@@ -40,98 +40,6 @@ struct SkinnyParams {
 constexpr int SKINNY_BLKS = SYMB_SKINNY_BLKS;          // 16-row MFMA blocks per wavefront
 constexpr int SKINNY_ROWS = 16 * SKINNY_BLKS;          // rows per workgroup
 
-// The same inner product with the MFMA fragments read straight from global memory (used by the
-// small-batch forward kernel below, whose "rows" are 32 rows of W and whose "adapter rows" are X):
-// acc[b][j] += sum over this wavefront's share of K of  L-rows (16-row block b) x R-rows (16-row block j):
-// lane (trow = lane % 16, kq = lane / 16) supplies row trow and k-offsets kq*8..kq*8+7 of each 32-k step
-// for both operands; the result lane holds acc[b][j][q] = dot(L row b*16 + trow, R row j*16 + 4*kq + q).
-// lrow / rrow already point at the lane's first 8 elements (row start + kq*8); r_ok masks R rows that
-// count as zero; nb = R blocks in use.
-template <int RB>
-__device__ __forceinline__ void skinny_dot(const bf16* (&lrow)[SKINNY_BLKS], const bf16* (&rrow)[RB],
-                                           bool (&r_ok)[RB], int nb, int K, int wave, int kq,
-                                           floatx4 (&acc)[SKINNY_BLKS][RB]) {
-    // Each wavefront takes every 4th 128-element slice of K (256 bytes per row per step).  The
-    // row data (the HBM stream) of the next slice is requested before the current slice is
-    // multiplied, so a wavefront always has 8 KiB of it in flight; the adapter rows come from L2.
-    auto load_l = [&](uint4 (&lv)[SKINNY_BLKS][4], int k) __attribute__((always_inline)) {
-#pragma unroll
-        for (int h = 0; h < 4; ++h)
-#pragma unroll
-            for (int b = 0; b < SKINNY_BLKS; ++b) lv[b][h] = *reinterpret_cast<const uint4*>(lrow[b] + k + h * 32);
-    };
-    // The memory counter retires loads in order: waiting for the adapter rows of the current slice
-    // also waits for every load issued before them.  So they are requested first and the row data
-    // of the next slice after them: the wait before the MFMAs then leaves that next slice in flight.
-    auto load_r = [&](uint4 (&rv)[RB][4], int k) __attribute__((always_inline)) {
-#pragma unroll
-        for (int h = 0; h < 4; ++h)
-#pragma unroll
-            for (int j = 0; j < RB; ++j)
-                if (j < nb) rv[j][h] = *reinterpret_cast<const uint4*>(rrow[j] + k + h * 32);
-    };
-    auto mul = [&](const uint4 (&lv)[SKINNY_BLKS][4], const uint4 (&rv)[RB][4]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int h = 0; h < 4; ++h)
-#pragma unroll
-            for (int j = 0; j < RB; ++j)
-                if (j < nb) {
-                    const bf16x8 rf = __builtin_bit_cast(bf16x8, r_ok[j] ? rv[j][h] : make_uint4(0u, 0u, 0u, 0u));
-#pragma unroll
-                    for (int b = 0; b < SKINNY_BLKS; ++b)
-                        acc[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rf, __builtin_bit_cast(bf16x8, lv[b][h]), acc[b][j], 0, 0, 0);
-                }
-    };
-    // Full slices of this wavefront: k0 = wave * 128 + 512 s, s < ns.  The loop body holds no
-    // conditional load, so the compiler's wait counts are exact (a load that may or may not have
-    // been issued makes it wait for everything).
-    int k0 = wave * 128;
-    const int ns = K >= k0 + 128 ? (K - k0 - 128) / 512 + 1 : 0;
-    if (ns > 0) {
-        uint4 la[SKINNY_BLKS][4], lb[SKINNY_BLKS][4], rv[RB][4];
-        load_l(la, k0);
-        int s = 0;
-        for (; s + 2 < ns; s += 2) {                   // two slices per trip, each with its successor requested first
-            load_r(rv, k0);
-            load_l(lb, k0 + 512);
-            mul(la, rv);
-            load_r(rv, k0 + 512);
-            load_l(la, k0 + 1024);
-            mul(lb, rv);
-            k0 += 1024;
-        }
-        if (ns - s == 2) {
-            load_r(rv, k0);
-            load_l(lb, k0 + 512);
-            mul(la, rv);
-            load_r(rv, k0 + 512);
-            mul(lb, rv);
-            k0 += 1024;
-        } else {
-            load_r(rv, k0);
-            mul(la, rv);
-            k0 += 512;
-        }
-    }
-    for (; k0 < K; k0 += 512) {                        // the slice that crosses the end of K
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            const bool kok = (k0 + h * 32 + kq * 8) < K;
-            uint4 lv[SKINNY_BLKS];
-#pragma unroll
-            for (int b = 0; b < SKINNY_BLKS; ++b) lv[b] = kok ? *reinterpret_cast<const uint4*>(lrow[b] + k0 + h * 32) : make_uint4(0u, 0u, 0u, 0u);
-#pragma unroll
-            for (int j = 0; j < RB; ++j)
-                if (j < nb) {
-                    const uint4 rv = (kok && r_ok[j]) ? *reinterpret_cast<const uint4*>(rrow[j] + k0 + h * 32) : make_uint4(0u, 0u, 0u, 0u);
-#pragma unroll
-                    for (int b = 0; b < SKINNY_BLKS; ++b)
-                        acc[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rv), __builtin_bit_cast(bf16x8, lv[b]), acc[b][j], 0, 0, 0);
-                }
-        }
-    }
-}
-
 // The skinny kernel's row stream.  A lane of an MFMA operand holds 16 bytes of one row, so fragment
 // loads straight from global memory touch 16 cache lines per 16 lanes, 16 bytes of each; the
 // memory pipeline then runs at a fraction of what whole-line requests reach.  Here every wavefront
@@ -142,17 +50,18 @@ __device__ __forceinline__ void skinny_dot(const bf16* (&lrow)[SKINNY_BLKS], con
 // way, into one more buffer.  Measured on 1.5 GB inputs: 4.0 -> 5.0 TB/s; 128-element slices are best
 // at rank <= 16, 64-element ones above (LDS for the adapter rows); a third buffer or a third workgroup
 // per CU changes nothing.
-template <int RB>
+template <int RB, int NBUF_ = 2, bool RDEEP_ = false>
 struct SkinnyStage {
     static constexpr int SK = RB >= 2 ? 64 : 128;         // K elements per slice
-    static constexpr int NBUF = 2;                        // slices a wavefront keeps in LDS
+    static constexpr int NBUF = NBUF_;                    // slices a wavefront keeps in LDS
+    static constexpr bool RDEEP = RDEEP_;                 // the adapter rows are requested with their slice, NBUF deep as well
     static constexpr int ROW_BYTES = SK * 2;
     static constexpr int LPR = ROW_BYTES / 16;            // lanes (16-byte chunks) per row
     static constexpr int RPI = 64 / LPR;                  // rows per DMA request of one wavefront
     static constexpr int DPS = SKINNY_ROWS / RPI;         // DMA requests per slice
     static constexpr int SLICE = SKINNY_ROWS * ROW_BYTES;
     static constexpr int RSLICE = RB * 16 * ROW_BYTES;    // the adapter rows of one slice (one buffer)
-    static constexpr int WAVE_BYTES = NBUF * SLICE + RSLICE;
+    static constexpr int WAVE_BYTES = NBUF * SLICE + (RDEEP ? NBUF : 1) * RSLICE;
     static constexpr int BYTES = 4 * WAVE_BYTES;
     static_assert(SK == 64 || SK == 128, "a row of a slice is one or two 128-byte lines");
     __device__ static constexpr int swz(int r) { return (r / (16 / LPR)) & (LPR - 1); }
@@ -171,11 +80,10 @@ __device__ __forceinline__ u32x4 ld_glb16(const bf16* p) {
 // loop holds no conditional load: the compiler's wait counts for the adapter rows are then exact).
 // lrow / rrow point at the lane's first 8 elements (row start + kq*8); src[i] at the 16 bytes this
 // lane brings in with DMA request i of a slice (at k = 0); wbuf = this wavefront's slice buffers.
-template <int RB, int NB>
+template <int RB, int NB, class ST = SkinnyStage<RB>>
 __device__ __forceinline__ void skinny_stream(const bf16* (&lrow)[SKINNY_BLKS], const bf16* (&rrow)[RB], const bool (&r_ok)[RB],
-                                              const bf16* (&src)[SkinnyStage<RB>::DPS], const bf16* rbase, int rrows,
+                                              const bf16* (&src)[ST::DPS], const bf16* rbase, int rrows,
                                               unsigned char* wbuf, int K, int wave, int lane, floatx4 (&acc)[SKINNY_BLKS][RB]) {
-    using ST = SkinnyStage<RB>;
     constexpr int NH = ST::SK / 32;                      // MFMA k-steps per slice
     constexpr int NRD = NB * 16 / ST::RPI;               // DMA requests for the adapter rows of a slice
     const int trow = lane & 15, kq = lane >> 4;
@@ -208,10 +116,10 @@ __device__ __forceinline__ void skinny_stream(const bf16* (&lrow)[SKINNY_BLKS], 
         for (int i = 0; i < ST::DPS; ++i)
             __builtin_amdgcn_global_load_lds((glb_void_t*)(src[i] + k), (lds_void_t*)(wbuf + buf * ST::SLICE + i * 1024), 16, 0, 0);
     };
-    auto dma_r = [&](int k) __attribute__((always_inline)) {
+    auto dma_r = [&](int buf, int k) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NRD; ++i)
-            __builtin_amdgcn_global_load_lds((glb_void_t*)(rsrc[i] + k), (lds_void_t*)(rbuf + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((glb_void_t*)(rsrc[i] + k), (lds_void_t*)(rbuf + (ST::RDEEP ? buf * ST::RSLICE : 0) + i * 1024), 16, 0, 0);
     };
     // The fragment reads are assembly statements with a wait of their own: while an LDS DMA request is in
     // flight the compiler makes every load result it can see wait for all memory traffic of the
@@ -225,7 +133,7 @@ __device__ __forceinline__ void skinny_stream(const bf16* (&lrow)[SKINNY_BLKS], 
 #pragma unroll
             for (int b = 0; b < SKINNY_BLKS; ++b) asm volatile("ds_read_b128 %0, %1" : "=v"(lv[b][h]) : "v"(foff[b][h] + buf * ST::SLICE));
 #pragma unroll
-            for (int j = 0; j < NB; ++j) asm volatile("ds_read_b128 %0, %1" : "=v"(rv[j][h]) : "v"(roff[j][h]));
+            for (int j = 0; j < NB; ++j) asm volatile("ds_read_b128 %0, %1" : "=v"(rv[j][h]) : "v"(roff[j][h] + (ST::RDEEP ? buf * ST::RSLICE : 0)));
         }
         asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");
 #pragma unroll
@@ -253,20 +161,29 @@ __device__ __forceinline__ void skinny_stream(const bf16* (&lrow)[SKINNY_BLKS], 
     int k0 = wave * ST::SK;
     const int ns = K >= k0 + ST::SK ? (K - k0 - ST::SK) / (4 * ST::SK) + 1 : 0;
     const int np = ns < ST::NBUF - 1 ? ns : ST::NBUF - 1;
-    for (int d = 0; d < np; ++d) dma(d, k0 + d * 4 * ST::SK);
+    for (int d = 0; d < np; ++d) {
+        dma(d, k0 + d * 4 * ST::SK);
+        if constexpr (ST::RDEEP) dma_r(d, k0 + d * 4 * ST::SK);
+    }
     int cur = 0, nxt = np;                               // buffer of slice s, of slice s + np
     int s = 0;
     for (; s + np < ns; ++s) {
-        dma_r(k0);
-        dma(nxt, k0 + np * 4 * ST::SK);
-        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(ST::DPS) : "memory");
+        if constexpr (ST::RDEEP) {                       // slice and adapter rows together, NBUF - 1 of them in flight
+            dma(nxt, k0 + np * 4 * ST::SK);
+            dma_r(nxt, k0 + np * 4 * ST::SK);
+            asm volatile("s_waitcnt vmcnt(%0)" : : "n"((ST::NBUF - 1) * (ST::DPS + NRD)) : "memory");
+        } else {
+            dma_r(0, k0);
+            dma(nxt, k0 + np * 4 * ST::SK);
+            asm volatile("s_waitcnt vmcnt(%0)" : : "n"(ST::DPS) : "memory");
+        }
         mul(cur);
         cur = cur + 1 == ST::NBUF ? 0 : cur + 1;
         nxt = nxt + 1 == ST::NBUF ? 0 : nxt + 1;
         k0 += 4 * ST::SK;
     }
     for (; s < ns; ++s) {                                // the last np slices: nothing left to request
-        dma_r(k0);
+        if constexpr (!ST::RDEEP) dma_r(0, k0);
         asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
         mul(cur);
         cur = cur + 1 == ST::NBUF ? 0 : cur + 1;
@@ -386,8 +303,8 @@ symb_skinny_kernel(const SkinnyParams p) {
 // the library uses RB = 1: beyond 16 rows the tiled kernel with its K-split is faster):
 //   Y[t][n] = sum_k X[t][k] W[n][k] (+ b[n]) (+ sum_p Hs[t][p] B_i[n][p])  (* l_i[n])
 // With so few rows a tiled GEMM launches too few workgroups to stream W at HBM speed.  Here a
-// workgroup owns 32 output columns: it streams those 32 rows of W once (the 4 wavefronts split K),
-// multiplies them with all rows of X (from L2) and finishes each (row, column) pair with its row's
+// workgroup owns 32 output columns: it streams those 32 rows of W once (the 4 wavefronts split K;
+// through LDS, like the skinny kernel's rows), multiplies them with all rows of X (from L2) and finishes each (row, column) pair with its row's
 // own adapter.  Same arithmetic as the tiled path: fp32 accumulation, Hs as value + residual, one
 // rounding.  RB = row blocks of 16 (T <= 16 RB).
 // -------------------------------------------------------------------------------------------
@@ -406,10 +323,13 @@ struct RowGemvParams {
 template <int RB>
 __global__ void __launch_bounds__(256)
 symb_rowgemv_kernel(const RowGemvParams p) {
+    using ST = SkinnyStage<RB, 3, true>;                 // W rows and X rows of a slice together, two slices ahead:
+    // with one workgroup per 32 columns there are few wavefronts, each must keep a lot in flight
+    __shared__ __align__(16) unsigned char stage[ST::BYTES];
     __shared__ float red[3][SKINNY_ROWS][RB * 16 + 4];   // partial sums of wavefronts 1..3; red[0] then holds the totals
     __shared__ int srow[RB * 16];                        // segment of each row
     static_assert(SKINNY_BLKS == 2, "a workgroup owns 32 columns");
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int trow = lane & 15, kq = lane >> 4;
     const int n0 = blockIdx.x * SKINNY_ROWS;
     if (tid < RB * 16) {
@@ -433,7 +353,13 @@ symb_rowgemv_kernel(const RowGemvParams p) {
     for (int b = 0; b < SKINNY_BLKS; ++b)
 #pragma unroll
         for (int j = 0; j < RB; ++j) acc[b][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-    skinny_dot<RB>(lrow, rrow, r_ok, RB, p.K, wave, kq, acc);
+    const bf16* src[ST::DPS];                            // this lane's 16 bytes of DMA request i of a slice (at k = 0)
+#pragma unroll
+    for (int i = 0; i < ST::DPS; ++i) {
+        const int r = i * ST::RPI + lane / ST::LPR;
+        src[i] = p.W + (size_t)min(n0 + r, p.N - 1) * p.K + (((lane % ST::LPR) ^ ST::swz(r)) * 8);
+    }
+    skinny_stream<RB, RB, ST>(lrow, rrow, r_ok, src, p.X, p.T, stage + wave * ST::WAVE_BYTES, p.K, wave, lane, acc);
     // lane holds dot(W row n0 + b*16 + trow, X row j*16 + 4*kq + q) over its wavefront's share of K
     if (wave > 0) {
 #pragma unroll

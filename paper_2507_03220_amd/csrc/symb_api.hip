@@ -759,9 +759,9 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     }
     // A handful of rows (decode steps) on a layer of moderate size: stream W once with one workgroup
     // per 32 output columns.  Measured against the tiled kernel with its K-split (33-40 us per call
-    // from 4 to 64 rows): 27-32 us up to 16 rows on 4096 x 4096, but slower from 24 rows on, and on
-    // 4096 x 11008 at any row count (this kernel streams W at 2.7 TB/s only).  SYMB_SMALL_T=0 turns
-    // it off (tuning aid).
+    // from 4 to 64 rows): 22-26 us up to 16 rows on 4096 x 4096, but slower from 24 rows on, and on
+    // 4096 x 11008 at any row count (344 workgroups of 152 KiB LDS: a second, third-full round).
+    // SYMB_SMALL_T=0 turns it off (tuning aid).
     static const bool small_path = [] { const char* e = getenv("SYMB_SMALL_T"); return !e || atoi(e) != 0; }();
     if (small_path && bi.T <= 16 && (long long)b->d_in * b->d_out <= 24ll << 20 && !conv1d && !seg_io && !Ybase && nd.empty() &&
         bi.n_ia3in == 0) {
