@@ -92,14 +92,14 @@ def _regs(operand):
 
 
 def test_results_of_assembly_issued_loads_are_untouched_until_their_wait(device_asm):
-    # The skinny and gradient kernels request global and LDS data from assembly statements and wait for
+    # The skinny and small-batch kernels request LDS data from assembly statements and wait for
     # it with an s_waitcnt of their own; the compiler does not know the registers are still in flight.
     # Nothing it generates between such a request and the next explicit wait may read or write them
     # (a register copy placed there would copy stale data; requesting the skinny kernel's adapter rows a
     # slice ahead, in registers that lived across the loop edge, produced exactly that).  Checked per
     # straight-line stretch of the generated code: a label ends the stretch.
     checked = 0
-    for m in re.finditer(r"^(_ZN4symb(?:18symb_skinny_kernel|21symb_lora_grad_kernel)\w+):(.*?)^\.Lfunc_end", device_asm, re.S | re.M):
+    for m in re.finditer(r"^(_ZN4symb(?:18symb_skinny_kernel|19symb_rowgemv_kernel|21symb_lora_grad_kernel)\w+):(.*?)^\.Lfunc_end", device_asm, re.S | re.M):
         pending, inside = set(), False
         for raw in m.group(2).splitlines():
             s = raw.strip().split(";")[0].strip() if "ASM" not in raw else raw.strip()
