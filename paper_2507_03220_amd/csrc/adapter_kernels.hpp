@@ -209,16 +209,19 @@ __device__ __forceinline__ void skinny_stream(const bf16* (&lrow)[SKINNY_BLKS], 
 }
 
 // Calls skinny_stream<RB, nb> for the run-time nb in 1..RB.
-template <int RB, int NB = 1, typename... Args>
+template <int RB, class ST, int NB = 1, typename... Args>
 __device__ __forceinline__ void skinny_stream_dispatch(int nb, Args&&... args) {
-    if (nb == NB) skinny_stream<RB, NB>(args...);
-    else if constexpr (NB < RB) skinny_stream_dispatch<RB, NB + 1>(nb, args...);
+    if (nb == NB) skinny_stream<RB, NB, ST>(args...);
+    else if constexpr (NB < RB) skinny_stream_dispatch<RB, ST, NB + 1>(nb, args...);
 }
 
-template <int RB>
+// DEEP: three buffers with the adapter rows beside each slice, two slices in flight per wavefront.  For
+// launches of few chunks, where a workgroup has a compute unit to itself and its time is the chain of
+// memory latencies along K rather than bandwidth.
+template <int RB, bool DEEP = false>
 __global__ void __launch_bounds__(256)
 symb_skinny_kernel(const SkinnyParams p) {
-    using ST = SkinnyStage<RB>;
+    using ST = SkinnyStage<RB, DEEP ? 3 : 2, DEEP>;
     constexpr int RED_BYTES = 3 * SKINNY_ROWS * (RB * 16 + 4) * 4;
     // slice buffers of the 4 wavefronts; afterwards the partial sums of wavefronts 1..3
     __shared__ __align__(16) unsigned char smem[ST::BYTES > RED_BYTES ? ST::BYTES : RED_BYTES];
@@ -255,7 +258,7 @@ symb_skinny_kernel(const SkinnyParams p) {
 #pragma unroll
         for (int j = 0; j < RB; ++j) acc[b][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    skinny_stream_dispatch<RB>(nb, lrow, rrow, r_ok, src, rbase, rrows, smem + wave * ST::WAVE_BYTES, p.K, wave, lane, acc);
+    skinny_stream_dispatch<RB, ST>(nb, lrow, rrow, r_ok, src, rbase, rrows, smem + wave * ST::WAVE_BYTES, p.K, wave, lane, acc);
     __syncthreads();                                     // every wavefront is done with its slice buffers
     // lane holds out[t = b*16 + trow][p = j*16 + 4*kq + q]
     if (wave > 0) {

@@ -442,9 +442,17 @@ symb_status launch_gemm(symb_handle h, const GemmParams& gp, hipStream_t st) {
     return plain ? launch_gemm16_t<4, NN, true>(h, gp, st) : launch_gemm16_t<4, NN, false>(h, gp, st);
 }
 
+// Up to one workgroup per compute unit the deep-prefetch build is used (where its buffers fit in LDS).
 template <int RB>
 void launch_skinny_rb(const SkinnyParams& sp, int nchunks, hipStream_t st) {
-    hipLaunchKernelGGL(symb_skinny_kernel<RB>, dim3(nchunks), dim3(256), 0, st, sp);
+    static const bool deep_ok = [] { const char* e = getenv("SYMB_SKINNY_DEEP"); return !e || atoi(e) != 0; }();
+    if constexpr (RB <= 4) {
+        if (deep_ok && nchunks <= 256) {
+            hipLaunchKernelGGL((symb_skinny_kernel<RB, true>), dim3(nchunks), dim3(256), 0, st, sp);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((symb_skinny_kernel<RB, false>), dim3(nchunks), dim3(256), 0, st, sp);
 }
 symb_status launch_skinny(symb_handle h, const SkinnyParams& sp, int nchunks, int max_rpad, hipStream_t st) {
     if (nchunks == 0) return SYMB_OK;
