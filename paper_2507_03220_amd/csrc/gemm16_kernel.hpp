@@ -570,7 +570,12 @@ symb_gemm16_kernel(const GemmParams p) {
         // and the reader's L1 holds no line of the partial tiles (nobody read them in this launch).
         __syncthreads();
         int* const flag = reinterpret_cast<int*>(smem);
-        if (tid == 0) *flag = atomicAdd(p.k_count + slot, 1);
+        if (tid == 0) {
+            const int seen = atomicAdd(p.k_count + slot, 1);
+            // the last arrival leaves the counter as it found the launch: zero, for the next one
+            if (seen == nparts - 1) __hip_atomic_store(p.k_count + slot, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *flag = seen;
+        }
         __syncthreads();
         const bool last_arrival = *flag == nparts - 1;
         __syncthreads();                             // the flag's LDS word is part of the staging tile

@@ -219,6 +219,55 @@ def test_large_tile_kernel_is_deterministic(dims):
     np.testing.assert_array_equal(x1, x2)
 
 
+def test_calls_that_find_their_descriptors_in_place():
+    """A call whose descriptors are the bytes of an earlier call on the same stream reads the copy already
+    on the device.  Three rounds of forward, input gradient and adapter gradients on the same device
+    buffers (a launch that splits every tile over K ranges: its arrival counters live with the
+    descriptors), the adapter matrices rewritten in place before the last round: every round gives
+    the bits a fresh handle gives, and the last one agrees with the oracle."""
+    p = make_problem(21, 4096, 520, [700, 5, 795], [L, I, L], [16, 40])
+    off, d_in, d_out, T = p["off"], p["d_in"], p["d_out"], p["T"]
+    dev = gh.upload_adapters(p["ads"], d_in, d_out, grads=True)
+    batch = sb.Batch(d_in, d_out, off, dev.descs)
+    Xd, Wd, bd, gd = gh.to_dev(p["X"]), gh.to_dev(p["W"]), gh.to_dev(p["bias"]), gh.to_dev(p["dY"])
+    ws = torch.empty(max(sb.symb_workspace_bytes(batch, op) for op in (sb.SYMB_OP_FWD, sb.SYMB_OP_BWD_INPUT, sb.SYMB_OP_ADAPTER_GRAD)),
+                     device="cuda", dtype=torch.uint8)
+    Y = torch.empty((T, d_out), device="cuda", dtype=torch.bfloat16)
+    dX = torch.empty((T, d_in), device="cuda", dtype=torch.bfloat16)
+    Yb = gh.forward(off, p["ads"], p["X"], p["W"], p["bias"], want_base=True)[1]
+
+    def run(h):
+        Y.fill_(float("nan")); dX.fill_(float("nan"))
+        for d in dev.descs:
+            for g in (d.dA, d.dB):
+                if g is not None:
+                    g.fill_(float("nan"))
+        sb.symb_base_linear_fwd(h, batch, Xd, Wd, bd, Y, None, ws, gh.stream_ptr())
+        sb.symb_base_linear_bwd_input(h, batch, gd, Wd, dX, sb.SYMB_BWD_FULL, ws, gh.stream_ptr())
+        sb.symb_adapter_grad(h, batch, Xd, gd, Yb, sb.SYMB_GRAD_OVERWRITE, ws, gh.stream_ptr())
+        torch.cuda.synchronize()
+        return [gh.bf16_bits(Y), gh.bf16_bits(dX)] + [g.cpu().numpy().copy() for d in dev.descs for g in (d.dA, d.dB) if g is not None]
+
+    fresh = sb.symb_create(0)
+    try:
+        want = run(fresh)
+        for _ in range(2):
+            for a, b in zip(run(gh.handle()), want):
+                np.testing.assert_array_equal(a, b)
+        q = make_problem(22, d_in, d_out, [700, 5, 795], [L, I, L], [16, 40])
+        for d, a in zip(dev.descs, q["ads"]):
+            if a.kind == L:
+                d.A.copy_(gh.to_dev(a.A)); d.B.copy_(gh.to_dev(a.B))
+        got = run(gh.handle())
+    finally:
+        sb.symb_destroy(fresh)
+    assert not np.array_equal(got[0], want[0])
+    for i in (0, 2):
+        p["ads"][i].A, p["ads"][i].B = q["ads"][i].A, q["ads"][i].B
+    _, Yr = oracle.forward(off, oracle_ads(p["ads"]), p["X"], p["W"], p["bias"])
+    assert_close(gh.bf16_to_f64(Y), Yr, "descriptors in place: Y", out_bf16=True)
+
+
 def test_backward_batch_is_independent_of_forward_batch():
     """Backward on a regrouped subset of the forward clients gives the same rows (bitwise)."""
     p = make_problem(12, 264, 320, [130, 1, 77, 300], [L, I, L, N], [8, 16])
