@@ -192,6 +192,7 @@ def main() -> int:
     torch.cuda.synchronize()
 
     sb.symb_debug_gemm_timing_enable(h, True)
+    desc0 = sb.symb_debug_descriptor_stats(h)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -249,6 +250,9 @@ def main() -> int:
             "traffic": measured_traffic(dom),
         },
     }
+    # calls of the timed region that sent their descriptors / found them on the device from an earlier step
+    desc1 = sb.symb_debug_descriptor_stats(h)
+    out["descriptors"] = {"sent": desc1[0] - desc0[0], "in_place": desc1[1] - desc0[1]}
     if not args.no_detail:
         out["per_projection"] = per_projection(runs, stream_obj, stream)
     if not args.no_cpu_baseline:

@@ -122,7 +122,10 @@ typedef struct {
 typedef struct symb_context* symb_handle;
 
 /* Creates a context on HIP device `device`: descriptor staging (pinned host ring +
- * device ring).  The only call that allocates.  SYMB_ERR_DEVICE if HIP fails. */
+ * device ring, 32 slots of 2 MiB each).  The only call that allocates.  A later call
+ * whose offsets, adapters and buffers give the same descriptor bytes as an earlier call
+ * on the same stream reads the copy already on the device instead of sending it again.
+ * SYMB_ERR_DEVICE if HIP fails. */
 symb_status symb_create(symb_handle* out, int device);
 symb_status symb_destroy(symb_handle h);
 
@@ -266,6 +269,10 @@ symb_status symb_adapter_grad_ex(symb_handle h, const symb_batch* b, const void*
 symb_status symb_debug_gemm_timing_enable(symb_handle h, int32_t on);
 symb_status symb_debug_gemm_timing_read(symb_handle h, int32_t variant, double* ms_total,
                                         int64_t* launches, double* flops_total);
+
+/* Test aid: how many calls on this handle so far sent their descriptors to the device
+ * (`sent`) and how many found them already there (`in_place`); see symb_create. */
+symb_status symb_debug_descriptor_stats(symb_handle h, int64_t* sent, int64_t* in_place);
 
 const char* symb_status_string(symb_status s);
 /* Text of the last error on this handle (h == NULL: of handle-free calls on this thread). */

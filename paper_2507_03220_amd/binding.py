@@ -32,7 +32,7 @@ EXPORTS = ("symb_create", "symb_destroy", "symb_validate_batch", "symb_debug_row
            "symb_status_string", "symb_last_error",
            "symb_batcher_create", "symb_batcher_destroy", "symb_batcher_submit", "symb_batcher_pending",
            "symb_batcher_next_due", "symb_batcher_take",
-           "symb_debug_gemm_timing_enable", "symb_debug_gemm_timing_read")
+           "symb_debug_gemm_timing_enable", "symb_debug_gemm_timing_read", "symb_debug_descriptor_stats")
 
 
 class symb_adapter(C.Structure):
@@ -88,6 +88,7 @@ def lib() -> C.CDLL:
         l.symb_debug_gemm_timing_enable.argtypes = [vp, i32]
         l.symb_debug_gemm_timing_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64),
                                                   C.POINTER(C.c_double)]
+        l.symb_debug_descriptor_stats.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         l.symb_status_string.argtypes = [C.c_int]
         l.symb_status_string.restype = C.c_char_p
         l.symb_last_error.argtypes = [vp]
@@ -286,6 +287,13 @@ def symb_adapter_grad(handle, batch: Batch, X, dY, Ybase=None, flags: int = SYMB
 
 def symb_debug_gemm_timing_enable(handle, on: bool) -> None:
     _check(lib().symb_debug_gemm_timing_enable(handle, 1 if on else 0), handle)
+
+
+def symb_debug_descriptor_stats(handle):
+    """Returns (sent, in_place): calls that sent their descriptors / found them on the device."""
+    a, b = C.c_int64(0), C.c_int64(0)
+    _check(lib().symb_debug_descriptor_stats(handle, C.byref(a), C.byref(b)), handle)
+    return a.value, b.value
 
 
 def symb_debug_gemm_timing_read(handle, variant: int):

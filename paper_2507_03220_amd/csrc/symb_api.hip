@@ -47,6 +47,7 @@ struct symb_context {
     size_t slot_size[kSlots] = {};
     uint64_t slot_hash[kSlots] = {};
     hipStream_t slot_stream[kSlots] = {};
+    int64_t desc_sent = 0, desc_in_place = 0;
     std::string error;
     std::vector<const void*> lds_attr_set;       // kernels whose dynamic-LDS limit was raised on this context's device
     // measurement hook: event pairs around GEMM launches
@@ -374,6 +375,7 @@ symb_status upload(symb_handle h, const Blob& blob, hipStream_t st, unsigned cha
             if (h->slot_used[j] && h->slot_size[j] == n && h->slot_hash[j] == hash && h->slot_stream[j] == st &&
                 memcmp(h->host_ring + (size_t)j * kSlotBytes, blob.bytes.data(), n) == 0) {
                 h->cur_slot = j;
+                ++h->desc_in_place;
                 *dev_base = h->dev_ring + (size_t)j * kSlotBytes;
                 return SYMB_OK;
             }
@@ -386,6 +388,7 @@ symb_status upload(symb_handle h, const Blob& blob, hipStream_t st, unsigned cha
     unsigned char* dp = h->dev_ring + (size_t)slot * kSlotBytes;
     memcpy(hp, blob.bytes.data(), n);
     SYMB_HIP(h, hipMemcpyAsync(dp, hp, n, hipMemcpyHostToDevice, st));
+    ++h->desc_sent;
     h->slot_size[slot] = n;
     h->slot_hash[slot] = hash;
     h->slot_stream[slot] = st;
@@ -570,6 +573,14 @@ symb_status symb_create(symb_handle* out, int device) {
         }
     }
     *out = c;
+    return SYMB_OK;
+}
+
+symb_status symb_debug_descriptor_stats(symb_handle h, int64_t* sent, int64_t* in_place) {
+    symb_status st = check_handle(h);
+    if (st != SYMB_OK) return st;
+    if (sent) *sent = h->desc_sent;
+    if (in_place) *in_place = h->desc_in_place;
     return SYMB_OK;
 }
 

@@ -251,14 +251,20 @@ def test_calls_that_find_their_descriptors_in_place():
     fresh = sb.symb_create(0)
     try:
         want = run(fresh)
+        assert sb.symb_debug_descriptor_stats(fresh) == (3, 0)
+        run(gh.handle())
+        before = sb.symb_debug_descriptor_stats(gh.handle())
         for _ in range(2):
             for a, b in zip(run(gh.handle()), want):
                 np.testing.assert_array_equal(a, b)
+        after = sb.symb_debug_descriptor_stats(gh.handle())
+        assert (after[0] - before[0], after[1] - before[1]) == (0, 6)
         q = make_problem(22, d_in, d_out, [700, 5, 795], [L, I, L], [16, 40])
         for d, a in zip(dev.descs, q["ads"]):
             if a.kind == L:
                 d.A.copy_(gh.to_dev(a.A)); d.B.copy_(gh.to_dev(a.B))
         got = run(gh.handle())
+        assert sb.symb_debug_descriptor_stats(gh.handle()) == (after[0], after[1] + 3)
     finally:
         sb.symb_destroy(fresh)
     assert not np.array_equal(got[0], want[0])
