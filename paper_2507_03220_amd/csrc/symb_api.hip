@@ -814,7 +814,7 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     }
     // A handful of rows (decode steps) on a layer of moderate size: stream W once with one workgroup
     // per 32 output columns.  Measured against the tiled kernel with its K-split (33-40 us per call
-    // from 4 to 64 rows): 22-26 us up to 16 rows on 4096 x 4096, but slower from 24 rows on, and on
+    // from 4 to 64 rows): 17-20 us up to 16 rows on 4096 x 4096 (descriptors in place), but slower from 24 rows on, and on
     // 4096 x 11008 at any row count (344 workgroups of 152 KiB LDS: a second, third-full round).
     // SYMB_SMALL_T=0 turns it off (tuning aid).
     static const bool small_path = [] { const char* e = getenv("SYMB_SMALL_T"); return !e || atoi(e) != 0; }();
