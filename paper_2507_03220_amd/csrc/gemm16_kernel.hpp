@@ -233,9 +233,13 @@ symb_gemm16_kernel(const GemmParams p) {
     // in this tile, ext_load fetches the step.  The first step is fetched here, so that its latency
     // hides under the main loop.
     constexpr int EC = BM / 64;                              // 16-byte chunks per thread of a 32-k tile
-    const int e_lds0 = lds_off_kmajor(tid >> 2, tid & 3);   // K-contiguous 32-k tile: chunk i sits 64 rows below chunk 0
-    uint4 ea[EC], eb[EC];
+    // K-contiguous 32-k tile: chunk i sits 64 rows below chunk 0.  Steps alternate between the two 32-k
+    // halves of the 64-k tile, so a step's stores never meet the reads of the step before it.
+    const int e_lds[2] = {lds_off_kmajor(tid >> 2, tid & 3), lds_off_kmajor(tid >> 2, 4 + (tid & 3))};
+    uint4 ea[2][EC], eb[2][EC];                              // two steps in flight
+    int e_rlo[2] = {0, 0}, e_rhi[2] = {0, 0};                // the rows of the segment of the step in each set
     int es = seg_lo, ekc = 0, e_lo = 0, e_hi = 0;
+    bool ext_more = false;                                   // a further step exists at (es, ekc)
     SegDesc esd;
     auto ext_seek = [&]() __attribute__((always_inline)) -> bool {
         for (; es <= seg_hi; ++es) {
@@ -246,13 +250,15 @@ symb_gemm16_kernel(const GemmParams p) {
         }
         return false;
     };
-    auto ext_load = [&]() __attribute__((always_inline)) {
+    // Fetches the step at (es, ekc) into register set SET and moves on to the step after it.
+    auto ext_load = [&](auto SETC) __attribute__((always_inline)) {
+        constexpr int SET = decltype(SETC)::value;
         // activation-side tile: rows of this segment only, others zero
 #pragma unroll
         for (int i = 0; i < EC; ++i) {
             const int m = m0 + (tid >> 2) + i * 64;
             const bool ok = m >= e_lo && m < e_hi;
-            ea[i] = ld_global_16(p.ext + (size_t)(ok ? m : 0) * p.ext_pitch + ekc + (tid & 3) * 8, ok);
+            ea[SET][i] = ld_global_16(p.ext + (size_t)(ok ? m : 0) * p.ext_pitch + ekc + (tid & 3) * 8, ok);
         }
         // adapter-side tile; both halves of the extended columns meet the same adapter matrix
 #pragma unroll
@@ -274,18 +280,29 @@ symb_gemm16_kernel(const GemmParams p) {
                         v.z = e[4] | ((unsigned)e[5] << 16); v.w = e[6] | ((unsigned)e[7] << 16);
                     }
                 }
-                eb[i] = v;
+                eb[SET][i] = v;
             } else {                   // A_i [rank][N], N-contiguous
                 const int n = n0 + nn_nc * 8;
                 const int pk = ekc + nn_k + i * KSTEP, pp = pk >= esd.rpad ? pk - esd.rpad : pk;
                 const bool ok = pp < esd.rank && n < p.N;
-                eb[i] = ld_global_16(esd.A + (size_t)(ok ? pp : 0) * p.N + (ok ? n : 0), ok);
+                eb[SET][i] = ld_global_16(esd.A + (size_t)(ok ? pp : 0) * p.N + (ok ? n : 0), ok);
             }
         }
+        e_rlo[SET] = e_lo;
+        e_rhi[SET] = e_hi;
+        ekc += 32;
+        if (ekc >= 2 * esd.rpad) {
+            ++es;
+            ekc = 0;
+            ext_more = ext_seek();
+        }
     };
+    using ext_set0 = std::integral_constant<int, 0>;
+    using ext_set1 = std::integral_constant<int, 1>;
     const bool last_part = part == nparts - 1;      // the K remainder and the LoRA steps go with the last K range
-    bool ext_more = last_part && p.ext != nullptr && ext_seek();
-    if (ext_more) ext_load();
+    ext_more = last_part && p.ext != nullptr && ext_seek();
+    bool ext_have0 = ext_more, ext_have1 = false;   // set 0 / set 1 holds a step that has not run yet
+    if (ext_have0) ext_load(ext_set0{});
 
 
     // Lane byte offsets of the MFMA fragments of 32-k step ks inside an operand's 64-k tile.  Lane
@@ -306,8 +323,8 @@ symb_gemm16_kernel(const GemmParams p) {
     };
     // nks 32-wide k-steps over the register-staged tile; rows: bit i set = this wavefront's 16-row
     // block i may hold non-zero activation rows
-    auto compute = [&](int nks, unsigned rows) __attribute__((always_inline)) {
-        for (int ks = 0; ks < nks; ++ks) {
+    auto compute = [&](int ks0, int nks, unsigned rows) __attribute__((always_inline)) {
+        for (int ks = ks0; ks < ks0 + nks; ++ks) {
             const unsigned va0 = lds0 + frag_a(ks, 0), va1 = lds0 + frag_a(ks, 1);
             if constexpr (!NN) {
                 const unsigned vb0 = lds0 + TT::UNIT + frag_b_nt(ks, 0), vb1 = lds0 + TT::UNIT + frag_b_nt(ks, 1);
@@ -408,7 +425,7 @@ symb_gemm16_kernel(const GemmParams p) {
         lds_store_a();
         lds_store_b();
         __syncthreads();
-        compute((p.K - KFT * 64 + 31) >> 5, (1u << NBLK) - 1);
+        compute(0, (p.K - KFT * 64 + 31) >> 5, (1u << NBLK) - 1);
         __syncthreads();
     }
 
@@ -525,32 +542,55 @@ symb_gemm16_kernel(const GemmParams p) {
         }
     }
 
-    // ---- LoRA term: extra 32-wide k-steps per LoRA segment that meets this row tile.  The loads of
-    // the first step went out before the main loop; those of each further step go out before the
-    // MFMAs of the step before it.
-    while (ext_more) {
-        // this wavefront's 16-row blocks that hold rows of the step's segment (the other rows of the
-        // activation-side tile are zero)
-        constexpr unsigned ALL = (1u << NBLK) - 1;
-        const int b_lo = max(e_lo - (m0 + wm0), 0) >> 4, b_hi = min((e_hi - 1 - (m0 + wm0)) >> 4, NBLK - 1);
-        const unsigned rows = (unsigned)__builtin_amdgcn_readfirstlane(
-            (e_hi > m0 + wm0 && b_lo <= b_hi) ? (int)((ALL >> (NBLK - 1 - b_hi)) & (ALL << b_lo) & ALL) : 0);
+    // ---- LoRA term: extra 32-wide k-steps per LoRA segment that meets this row tile.  Two steps are
+    // in flight: the loads of the first went out before the main loop, those of the second go out here,
+    // and each step, once its registers are in LDS, requests the step after the next into them.  (A step
+    // computes little; with one step in flight every step waited out its own loads.)  One barrier per
+    // step is enough because consecutive steps use different halves of the staged tile: whoever stores
+    // step k + 1 has passed the barrier of step k, which every wavefront reaches after its MFMAs of
+    // step k - 1, the last reader of that half.
+    // (The 256x256 tile on an N-contiguous weight has no registers left for the second set: it keeps
+    // one step in flight, still alternating the halves.)
+    constexpr bool EXT_TWO = !(NN && NBLK == 8);
+    if (ext_have0) {
+        if constexpr (EXT_TWO) {
+            ext_have1 = ext_more;
+            if (ext_have1) ext_load(ext_set1{});
+        }
+        auto ext_step = [&](auto SETC, auto HALFC, bool& have) __attribute__((always_inline)) {
+            constexpr int SET = decltype(SETC)::value, HALF = decltype(HALFC)::value;
+            // this wavefront's 16-row blocks that hold rows of the step's segment (the other rows of the
+            // activation-side tile are zero)
+            constexpr unsigned ALL = (1u << NBLK) - 1;
+            const int r_lo = e_rlo[SET], r_hi = e_rhi[SET];
+            const int b_lo = max(r_lo - (m0 + wm0), 0) >> 4, b_hi = min((r_hi - 1 - (m0 + wm0)) >> 4, NBLK - 1);
+            const unsigned rows = (unsigned)__builtin_amdgcn_readfirstlane(
+                (r_hi > m0 + wm0 && b_lo <= b_hi) ? (int)((ALL >> (NBLK - 1 - b_hi)) & (ALL << b_lo) & ALL) : 0);
 #pragma unroll
-        for (int i = 0; i < EC; ++i) {
-            *reinterpret_cast<uint4*>(sA + e_lds0 + i * 8192) = ea[i];
-            if constexpr (!NN) *reinterpret_cast<uint4*>(sB + e_lds0 + i * 8192) = eb[i];
-            else *reinterpret_cast<uint4*>(sB + b_lds0 + i * KSTEP * (BN * 2)) = eb[i];
+            for (int i = 0; i < EC; ++i) {
+                *reinterpret_cast<uint4*>(sA + e_lds[HALF] + i * 8192) = ea[SET][i];
+                if constexpr (!NN) *reinterpret_cast<uint4*>(sB + e_lds[HALF] + i * 8192) = eb[SET][i];
+                else *reinterpret_cast<uint4*>(sB + b_lds0 + (HALF * 32 + i * KSTEP) * (BN * 2)) = eb[SET][i];
+            }
+            __syncthreads();
+            have = ext_more;
+            if (have) ext_load(SETC);
+            compute(HALF, 1, rows);
+        };
+        if constexpr (EXT_TWO) {
+            while (ext_have0) {
+                ext_step(ext_set0{}, ext_set0{}, ext_have0);
+                if (!ext_have1) break;               // then there was no step to request into set 0 either
+                ext_step(ext_set1{}, ext_set1{}, ext_have1);
+            }
+        } else {
+            while (ext_have0) {
+                ext_step(ext_set0{}, ext_set0{}, ext_have0);
+                if (!ext_have0) break;
+                ext_step(ext_set0{}, ext_set1{}, ext_have0);
+            }
         }
-        __syncthreads();
-        ekc += 32;
-        if (ekc >= 2 * esd.rpad) {
-            ++es;
-            ekc = 0;
-            ext_more = ext_seek();
-        }
-        if (ext_more) ext_load();
-        compute(1, rows);
-        __syncthreads();
+        __syncthreads();                             // LDS goes to the output tile / the arrival flag next
     }
 
     // ---- K-split tile: every part leaves its accumulators in the workspace (register order: 1 KiB
