@@ -159,8 +159,8 @@ symb_gemm16_kernel(const GemmParams p) {
         const int item = blockIdx.x >> 3;
         int li = item;
         if (p.k_parts > 1 && item >= p.k_whole) {
-            // part-major: first every split tile's last K range (the one that also has the LoRA steps
-            // and the K remainder to do), then the one before ...: tiles that run side by side then walk
+            // part-major: first every split tile's last K range (the one that also has the K remainder
+            // to do), then the one before ...: tiles that run side by side then walk
             // the same K range and share their operand panels in L2
             const int j = item - p.k_whole, nsplit = per_xcd - p.k_whole;
             nparts = p.k_parts;
@@ -236,8 +236,10 @@ symb_gemm16_kernel(const GemmParams p) {
     // K-contiguous 32-k tile: chunk i sits 64 rows below chunk 0.  Steps alternate between the two 32-k
     // halves of the 64-k tile, so a step's stores never meet the reads of the step before it.
     const int e_lds[2] = {lds_off_kmajor(tid >> 2, tid & 3), lds_off_kmajor(tid >> 2, 4 + (tid & 3))};
-    uint4 ea[2][EC], eb[2][EC];                              // two steps in flight
-    int e_rlo[2] = {0, 0}, e_rhi[2] = {0, 0};                // the rows of the segment of the step in each set
+    constexpr int ESETS = (NN ? 1 : 2) + (NBLK == 8 ? 0 : 1);  // steps in flight (register sets): what fits without spilling
+    uint4 ea[ESETS][EC], eb[ESETS][EC];
+    int e_rlo[ESETS] = {}, e_rhi[ESETS] = {};                // the rows of the segment of the step in each set
+    bool e_have[ESETS] = {};                                 // the set holds a step that has not run yet
     int es = seg_lo, ekc = 0, e_lo = 0, e_hi = 0;
     bool ext_more = false;                                   // a further step exists at (es, ekc)
     SegDesc esd;
@@ -250,7 +252,27 @@ symb_gemm16_kernel(const GemmParams p) {
         }
         return false;
     };
-    // Fetches the step at (es, ekc) into register set SET and moves on to the step after it.
+    // The parts of a K-split 128x128 tile share the tile's steps out: step number e_no (counted over the
+    // tile) belongs to part e_no % nparts.  Any part may take any step, the partial tiles are added up
+    // anyway; left to the last part alone, a tile of many short segments had its steps one after the
+    // other behind that part's share of K while the other parts were done (a call of 128 rows in 16
+    // segments: 43.6 -> 34.2 us).  The split last round of 256x256 tiles keeps them with the last part
+    // (sharing them out there measured 0.4 % slower on the mixed workload).
+    int e_no = 0;
+    auto ext_next = [&]() __attribute__((always_inline)) {
+        ekc += 32;
+        ++e_no;
+        if (ekc >= 2 * esd.rpad) {
+            ++es;
+            ekc = 0;
+            ext_more = ext_seek();
+        }
+    };
+    auto ext_skip = [&]() __attribute__((always_inline)) {
+        if (nparts > 1)
+            while (ext_more && (NBLK == 8 ? nparts - 1 : e_no % nparts) != part) ext_next();
+    };
+    // Fetches the step at (es, ekc) into register set SET and moves on to this part's next step.
     auto ext_load = [&](auto SETC) __attribute__((always_inline)) {
         constexpr int SET = decltype(SETC)::value;
         // activation-side tile: rows of this segment only, others zero
@@ -290,19 +312,14 @@ symb_gemm16_kernel(const GemmParams p) {
         }
         e_rlo[SET] = e_lo;
         e_rhi[SET] = e_hi;
-        ekc += 32;
-        if (ekc >= 2 * esd.rpad) {
-            ++es;
-            ekc = 0;
-            ext_more = ext_seek();
-        }
+        ext_next();
+        ext_skip();
     };
-    using ext_set0 = std::integral_constant<int, 0>;
-    using ext_set1 = std::integral_constant<int, 1>;
-    const bool last_part = part == nparts - 1;      // the K remainder and the LoRA steps go with the last K range
-    ext_more = last_part && p.ext != nullptr && ext_seek();
-    bool ext_have0 = ext_more, ext_have1 = false;   // set 0 / set 1 holds a step that has not run yet
-    if (ext_have0) ext_load(ext_set0{});
+    const bool last_part = part == nparts - 1;      // the K remainder goes with the last K range
+    ext_more = p.ext != nullptr && ext_seek();
+    ext_skip();
+    e_have[0] = ext_more;
+    if (e_have[0]) ext_load(std::integral_constant<int, 0>{});
 
 
     // Lane byte offsets of the MFMA fragments of 32-k step ks inside an operand's 64-k tile.  Lane
@@ -542,21 +559,23 @@ symb_gemm16_kernel(const GemmParams p) {
         }
     }
 
-    // ---- LoRA term: extra 32-wide k-steps per LoRA segment that meets this row tile.  Two steps are
-    // in flight: the loads of the first went out before the main loop, those of the second go out here,
-    // and each step, once its registers are in LDS, requests the step after the next into them.  (A step
-    // computes little; with one step in flight every step waited out its own loads.)  One barrier per
+    // ---- LoRA term: extra 32-wide k-steps per LoRA segment that meets this row tile.  Several steps
+    // are in flight, each in a register set of its own: the loads of the first went out before the main
+    // loop, those of the others go out here, and each step, once its registers are in LDS, requests the
+    // next step that has no registers yet into them.  (A step computes little; with one step in flight
+    // every step waited out its own loads.)  One barrier per
     // step is enough because consecutive steps use different halves of the staged tile: whoever stores
     // step k + 1 has passed the barrier of step k, which every wavefront reaches after its MFMAs of
     // step k - 1, the last reader of that half.
-    // (The 256x256 tile on an N-contiguous weight has no registers left for the second set: it keeps
-    // one step in flight, still alternating the halves.)
-    constexpr bool EXT_TWO = !(NN && NBLK == 8);
-    if (ext_have0) {
-        if constexpr (EXT_TWO) {
-            ext_have1 = ext_more;
-            if (ext_have1) ext_load(ext_set1{});
-        }
+    // (ESETS steps are in flight: two on a K-contiguous weight and one on an N-contiguous one for the
+    // 256x256 tile, which has no registers left for more; one more each for the 128x128 tile.  Step k
+    // uses set k % ESETS and half k % 2.)
+    if (e_have[0]) {
+        static_for<1, ESETS>([&](auto J) __attribute__((always_inline)) {
+            constexpr int j = decltype(J)::value;
+            e_have[j] = ext_more;
+            if (e_have[j]) ext_load(J);
+        });
         auto ext_step = [&](auto SETC, auto HALFC, bool& have) __attribute__((always_inline)) {
             constexpr int SET = decltype(SETC)::value, HALF = decltype(HALFC)::value;
             // this wavefront's 16-row blocks that hold rows of the step's segment (the other rows of the
@@ -577,18 +596,16 @@ symb_gemm16_kernel(const GemmParams p) {
             if (have) ext_load(SETC);
             compute(HALF, 1, rows);
         };
-        if constexpr (EXT_TWO) {
-            while (ext_have0) {
-                ext_step(ext_set0{}, ext_set0{}, ext_have0);
-                if (!ext_have1) break;               // then there was no step to request into set 0 either
-                ext_step(ext_set1{}, ext_set1{}, ext_have1);
-            }
-        } else {
-            while (ext_have0) {
-                ext_step(ext_set0{}, ext_set0{}, ext_have0);
-                if (!ext_have0) break;
-                ext_step(ext_set0{}, ext_set1{}, ext_have0);
-            }
+        // steps run in the order they were requested, so the first empty set ends the loop
+        constexpr int EPERIOD = (ESETS & 1) ? 2 * ESETS : ESETS;
+        bool ext_done = false;
+        while (!ext_done) {
+            static_for<0, EPERIOD>([&](auto K) __attribute__((always_inline)) {
+                constexpr int k = decltype(K)::value;
+                if (ext_done) return;
+                if (!e_have[k % ESETS]) { ext_done = true; return; }
+                ext_step(std::integral_constant<int, k % ESETS>{}, std::integral_constant<int, k & 1>{}, e_have[k % ESETS]);
+            });
         }
         __syncthreads();                             // LDS goes to the output tile / the arrival flag next
     }
