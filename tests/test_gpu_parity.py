@@ -141,6 +141,12 @@ def test_cfg1_tiny_full():
     # segments of more than 1536 tokens: their LoRA gradients are summed in runs of 1024 tokens (1537: two runs,
     # the second of 513 tokens; 1536 stays whole)
     dict(seed=15, d_in=136, d_out=200, lens=[1700, 3, 2100, 1536, 1537], kinds=[L, L, L, L, L], ranks=[8, 16, 40, 4, 128]),
+    # 128x128 tiles split over K ranges (6 tiles, 4 parts each), many short LoRA segments per tile: the parts
+    # share the tile's LoRA steps out; ranks of 1 to 8 steps, an IA3 and a plain segment in between, K tail
+    dict(seed=16, d_in=2056, d_out=264, lens=[8, 8, 3, 16, 8, 1, 8, 40, 8, 8, 5, 8, 8, 2, 8, 8, 9], kinds=[L, L, I, L, L, L, N, L, L, L, L, L, I, L, L, L, L],
+         ranks=[16, 8, 40, 128, 4, 64, 24]),
+    dict(seed=17, d_in=264, d_out=2056, lens=[8, 8, 3, 16, 8, 1, 8, 40, 8, 8, 5, 8, 8, 2, 8, 8, 9], kinds=[L, L, N, L, L, L, N, L, L, L, L, L, L, L, L, L, L],
+         ranks=[16, 8, 40, 128, 4, 64, 24]),      # the same in the input gradient
     # all kinds NONE: the paper's plain executor
     dict(seed=4, d_in=256, d_out=512, lens=[100, 156], kinds=[N], ranks=[1]),
     # rank 1, rank 128 (max), rank 100, K tail (d_in not a multiple of 64)
