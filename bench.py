@@ -9,6 +9,15 @@ the timed region.  Default workload: the Gemma2-27B-shaped layer with 20 LoRA cl
 
 Prints ONE JSON line: metric, value (whole-step TFLOP/s), timing, the roofline of the dominant GEMM kernel,
 per-projection timings and the oracle timed on the host cores.  Run with --gpus 1 only.
+
+What `value` is timed on: K steps back to back on one stream, host wall clock between two device
+synchronisations, the library's host work of every call included.  The steps repeat one batch
+layout (the same 20 clients with the same lengths, as in a fine-tuning job), so after the warm-up
+every call finds its descriptors on the device and sends nothing; `ms_per_step_descriptors_sent`
+is the same region timed again with that reuse switched off (every call uploads its descriptors,
+as a job whose batch layout changes from call to call does).  `ms_per_step_median` / `_min` are
+per-step event times of the same timed region; `fwd_only_ms` / `bwd_only_ms` time the forward calls
+and the backward calls (input gradient + adapter gradients) of all projections on their own.
 """
 from __future__ import annotations
 
@@ -134,9 +143,12 @@ def per_projection(runs, stream_obj, stream, reps: int = 5) -> list:
     return out
 
 
-def measured_traffic(variant: int):
-    """HBM bytes per launch of the dominant GEMM kernel, from the rocprofv3 --pmc summary
-    committed under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy); None if absent."""
+def measured_traffic(cfg: str, variant: int):
+    """HBM/fabric bytes per launch of the dominant GEMM kernel.  Not measured in this run: read from the
+    rocprofv3 --pmc summary committed under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy),
+    which exists for cfg4's 256x256 instantiations only; None otherwise."""
+    if cfg != "cfg4" or variant not in (0, 1):
+        return None
     path = os.path.join(ROOT, "profiles", "cfg4_gemm_hbm_traffic.txt")
     key = "traffic_bytes_per_launch_nn:" if variant else "traffic_bytes_per_launch_nt:"
     try:
@@ -146,6 +158,55 @@ def measured_traffic(variant: int):
     except OSError:
         pass
     return None
+
+
+def kernel_name(variant: int) -> str:
+    return "symb_gemm16_kernel<%d,%s,%s>" % (4 if variant & 2 else 8, "true" if variant & 1 else "false",
+                                             "false" if variant & 4 else "true")
+
+
+def timed_steps(runs, stream_obj, stream, steps: int):
+    """K steps back to back; returns (wall ms of the whole region, per-step event times in ms)."""
+    import torch
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev[0].record(stream_obj)
+    for k in range(steps):
+        step(runs, stream)
+        ev[k + 1].record(stream_obj)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return wall_ms, [ev[k].elapsed_time(ev[k + 1]) for k in range(steps)]
+
+
+def phase_only(runs, stream_obj, stream, reps: int = 5):
+    """Median event time of all forward calls / all backward calls of the layer, each phase on its own."""
+    import statistics
+    import torch
+
+    def timed(fn):
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream_obj)
+            fn()
+            e1.record(stream_obj)
+            e1.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return statistics.median(ts)
+
+    def fwd():
+        for r in runs:
+            r.fwd(stream)
+
+    def bwd():
+        for r in runs:
+            r.bwd_input(stream)
+            r.adapter_grad(stream, reuse_dh=True, reuse_hs=True)
+    t_f = timed(fwd)
+    fwd()                                                   # Hs of every projection back in its workspace
+    return t_f, timed(bwd)
 
 
 def main() -> int:
@@ -193,28 +254,30 @@ def main() -> int:
 
     sb.symb_debug_gemm_timing_enable(h, True)
     desc0 = sb.symb_debug_descriptor_stats(h)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    e0.record(stream_obj)
-    for _ in range(args.steps):
-        step(runs, stream)
-    e1.record(stream_obj)
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    ev_ms = e0.elapsed_time(e1)
+    wall_ms, step_ms = timed_steps(runs, stream_obj, stream, args.steps)
+    ev_ms = sum(step_ms)
     ms_per_step = wall_ms / args.steps
+    desc1 = sb.symb_debug_descriptor_stats(h)
 
     fl = {k: sum(r.flops()[k] for r in runs) for k in runs[0].flops()}
     tflops = fl["total"] / (ms_per_step * 1e-3) / 1e12
     tokens = wl.T
-    timing = [sb.symb_debug_gemm_timing_read(h, v) for v in (0, 1)]
+    timing = {v: sb.symb_debug_gemm_timing_read(h, v) for v in range(8)}
     sb.symb_debug_gemm_timing_enable(h, False)
-    dom = 0 if timing[0][0] >= timing[1][0] else 1
+    dom = max(timing, key=lambda v: timing[v][0])
     ms_tot, n_launch, fl_tot = timing[dom]
     avg_ms = ms_tot / max(n_launch, 1)
     achieved = (fl_tot / max(n_launch, 1)) / (avg_ms * 1e-3) / 1e12 if n_launch else 0.0
-    gemm_ms_per_step = (timing[0][0] + timing[1][0]) / args.steps
+    gemm_ms_per_step = sum(t[0] for t in timing.values()) / args.steps
+    # the same region with every call sending its descriptors
+    sb.symb_debug_set_option(h, sb.SYMB_OPT_DESCRIPTOR_REUSE, 0)
+    step(runs, stream)
+    wall_sent_ms, _ = timed_steps(runs, stream_obj, stream, args.steps)
+    desc2 = sb.symb_debug_descriptor_stats(h)
+    sb.symb_debug_set_option(h, sb.SYMB_OPT_DESCRIPTOR_REUSE, 1)
+    step(runs, stream)
+    fwd_ms, bwd_ms = phase_only(runs, stream_obj, stream)
+    import statistics
     out = {
         "metric": "fwd+bwd base+adapter layer TFLOP/s",
         "value": round(tflops, 2),
@@ -232,6 +295,15 @@ def main() -> int:
                                f"projections {','.join(f'{r.name}:{r.d_in}->{r.d_out}' for r in runs)}; "
                                "fwd + dX + adapter grads per projection",
                    "tokens": tokens, "clients": len(wl.clients)},
+        "value_timed_on": "descriptors found in place (the steps repeat one batch layout)",
+        "ms_per_step_median": round(statistics.median(step_ms), 4),
+        "ms_per_step_min": round(min(step_ms), 4),
+        "ms_per_step_descriptors_sent": round(wall_sent_ms / args.steps, 4),
+        "tflops_descriptors_sent": round(fl["total"] / (wall_sent_ms / args.steps * 1e-3) / 1e12, 2),
+        "fwd_only_ms": round(fwd_ms, 4),
+        "bwd_only_ms": round(bwd_ms, 4),
+        "fwd_only_tflops": round((fl["base_fwd"] + fl["ad_fwd"]) / fwd_ms / 1e9, 1),
+        "bwd_only_tflops": round((fl["base_bwd"] + fl["ad_bwd"]) / bwd_ms / 1e9, 1),
         "mfma_util": round(tflops / BF16_MFMA_PEAK_TFLOPS, 4),
         "token_layers_per_s": round(tokens / (ms_per_step * 1e-3), 1),
         "model_equiv_tokens_per_s": round(tokens / (ms_per_step * 1e-3) / 46.0, 1) if args.config == "cfg4" else None,
@@ -240,19 +312,24 @@ def main() -> int:
         "algorithmic_tflop_per_step": round(fl["total"] / 1e12, 4),
         "roofline": {
             "bound": "mfma",
-            "kernel": "symb_gemm16_kernel<8,%s,true>" % ("true" if dom else "false"),
+            "kernel": kernel_name(dom),
             "achieved": round(achieved, 2),
             "peak": BF16_MFMA_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4),
             "avg_launch_ms": round(avg_ms, 4),
             "launches": n_launch,
-            "traffic": measured_traffic(dom),
+            "traffic": measured_traffic(args.config, dom),
+            "traffic_source": "stored: profiles/cfg4_gemm_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; not measured in this run)"
+                              if measured_traffic(args.config, dom) is not None else None,
         },
+        "gemm_kernels": {kernel_name(v): {"launches": t[1], "ms_per_step": round(t[0] / args.steps, 4),
+                                          "tflops": round(t[2] / (t[0] * 1e-3) / 1e12, 1) if t[0] > 0 else None}
+                         for v, t in timing.items() if t[1]},
     }
     # calls of the timed region that sent their descriptors / found them on the device from an earlier step
-    desc1 = sb.symb_debug_descriptor_stats(h)
-    out["descriptors"] = {"sent": desc1[0] - desc0[0], "in_place": desc1[1] - desc0[1]}
+    out["descriptors"] = {"sent": desc1[0] - desc0[0], "in_place": desc1[1] - desc0[1],
+                          "sent_in_second_region": desc2[0] - desc1[0]}
     if not args.no_detail:
         out["per_projection"] = per_projection(runs, stream_obj, stream)
     if not args.no_cpu_baseline:

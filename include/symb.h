@@ -78,7 +78,9 @@ typedef enum {
 
 enum { SYMB_MAX_RANK = 128 };
 
-typedef enum { SYMB_OP_FWD = 0, SYMB_OP_BWD_INPUT = 1, SYMB_OP_ADAPTER_GRAD = 2 } symb_op;
+typedef enum { SYMB_OP_FWD = 0, SYMB_OP_BWD_INPUT = 1, SYMB_OP_ADAPTER_GRAD = 2,
+               /* the per-segment forms called with output buffers that overlap input buffers (see below) */
+               SYMB_OP_FWD_INPLACE = 3, SYMB_OP_BWD_INPUT_INPLACE = 4 } symb_op;
 
 /* flags of symb_base_linear_bwd_input */
 enum { SYMB_BWD_FULL = 0,             /* dX includes each segment's adapter branch */
@@ -217,15 +219,25 @@ symb_status symb_base_linear_bwd_input_ex(symb_handle h, const symb_batch* b, co
                                           void* ws, size_t ws_bytes, void* stream);
 
 /*
- * Per-client buffers (Sec. 3.4: the executor and a local client share pre-allocated buffers).  The
+ * Per-client buffers (Sec. 3.5: the executor and a local client share pre-allocated buffers).  The
  * same forward / input gradient with the rows of segment i read from X_seg[i] (dY_seg[i]) and
  * written to Y_seg[i] (dX_seg[i]) instead of one flattened tensor each: no concatenation before
  * the call, no split after it.  The arrays are HOST arrays of num_segments DEVICE pointers (dense
- * bf16 rows, 16-byte aligned; an empty segment's entry is ignored).  An output buffer must not
- * overlap any input buffer.  The input buffers of one call must lie within one 4 GiB window
- * (SYMB_ERR_UNSUPPORTED otherwise): carve them from one arena.  No Ybase / dXbase output and no
- * IA3 input scaling in this form (a client that needs Ybase for an IA3 gradient keeps its own
- * output of an all-NONE call, which is the paper's flow).
+ * bf16 rows, 16-byte aligned; an empty segment's entry is ignored).  The input buffers of one call
+ * must lie within one 4 GiB window (SYMB_ERR_UNSUPPORTED otherwise): carve them from one arena.
+ * No Ybase / dXbase output and no IA3 input scaling in this form (a client that needs Ybase for an
+ * IA3 gradient keeps its own output of an all-NONE call, which is the paper's flow).
+ *
+ * One buffer per client for both directions (Sec. 3.5: each client pre-allocates a single tensor of
+ * batch x sequence x max(d_in, d_out) elements and every layer's input and output travel through
+ * it): an output buffer may overlap any input buffer of the call, in particular
+ * Y_seg[i] == X_seg[i] (dX_seg[i] == dY_seg[i]), rows dense at their own widths.  The library
+ * detects the overlap; such a call computes into a flat copy in the workspace and then scatters
+ * the rows, in stream order, so every input row is read before any output row lands.  It needs the
+ * larger workspace that SYMB_OP_FWD_INPLACE / SYMB_OP_BWD_INPUT_INPLACE report (the plain figure
+ * plus T x width x 2 bytes; SYMB_ERR_WORKSPACE_TOO_SMALL otherwise) and costs one extra pass over
+ * the output.  Output buffers must not overlap each other.  After an in-place input gradient dY is
+ * gone: run symb_adapter_grad_seg first.
  */
 symb_status symb_base_linear_fwd_seg(symb_handle h, const symb_batch* b, const void* const* X_seg,
                                      const void* W, const void* bias, void* const* Y_seg, void* ws,
@@ -259,8 +271,10 @@ symb_status symb_adapter_grad_ex(symb_handle h, const symb_batch* b, const void*
 /*
  * Measurement hook (not part of the method): while enabled, every launch of the base
  * GEMM kernel is bracketed by a pair of HIP events on the caller's stream, so a bench
- * can read that kernel's own duration inside its timed region.  `variant` 0 = forward
- * kernel (W read K-contiguous), 1 = input-gradient kernel (W read N-contiguous).
+ * can read that kernel's own duration inside its timed region.  `variant` names the
+ * instantiation symb_gemm16_kernel<NBLK, NN, PLAIN>: bit 0 = NN (the weight is read
+ * N-contiguous: input gradient of an nn.Linear weight), bit 1 = the 128x128 tile (NBLK 4, else
+ * 256x256, NBLK 8), bit 2 = the full epilogue (PLAIN false); 0..7.
  * read synchronises on the recorded events and returns the totals since the last
  * enable call (which clears them).  At most 4096 launches are recorded after an
  * enable; later ones are not timed.  `flops_total` is the algorithmic work of those launches
@@ -269,6 +283,27 @@ symb_status symb_adapter_grad_ex(symb_handle h, const symb_batch* b, const void*
 symb_status symb_debug_gemm_timing_enable(symb_handle h, int32_t on);
 symb_status symb_debug_gemm_timing_read(symb_handle h, int32_t variant, double* ms_total,
                                         int64_t* launches, double* flops_total);
+
+/*
+ * Measurement switches (not part of the method), per handle, all on by default; value 0 turns one
+ * off.  symb_workspace_bytes does not depend on them.
+ *   SYMB_OPT_DESCRIPTOR_REUSE    a call whose descriptor bytes are already on the device reads them in
+ *                                place (off: every call sends them, as a job whose batch layout
+ *                                changes from call to call does)
+ *   SYMB_OPT_K_SPLIT             output tiles computed by several workgroups, one per K range
+ *   SYMB_OPT_SMALL_BATCH_KERNELS the weight-streaming kernels for calls of at most 16 rows
+ *   SYMB_OPT_SKINNY_DEEP         the deep-prefetch build of the LoRA shrink for launches of few workgroups
+ */
+typedef enum { SYMB_OPT_DESCRIPTOR_REUSE = 0, SYMB_OPT_K_SPLIT = 1, SYMB_OPT_SMALL_BATCH_KERNELS = 2,
+               SYMB_OPT_SKINNY_DEEP = 3 } symb_debug_option;
+symb_status symb_debug_set_option(symb_handle h, int32_t option, int32_t value);
+
+/* The K-split keeps all workgroups of one output tile on one XCD (behind one L2), which relies on
+ * the dispatcher sending workgroup number g to XCD g mod 8.  symb_create measures that (a probe
+ * launch records the hardware XCD id of 2048 workgroups); *holds is 1 if every workgroup of a residue
+ * class mod 8 ran on the same XCD, and only then is the K-split ever used on this handle.
+ * xcc_of_residue (8 entries, may be NULL) receives the XCD id seen for residues 0..7. */
+symb_status symb_debug_xcd_rule(symb_handle h, int32_t* holds, int32_t* xcc_of_residue);
 
 /* Test aid: how many calls on this handle so far sent their descriptors to the device
  * (`sent`) and how many found them already there (`in_place`); see symb_create. */

@@ -167,6 +167,29 @@ def forward_private(off, adapters: Sequence[Adapter], Xn: np.ndarray, W: np.ndar
     return Y
 
 
+def forward_denoise(off, adapters: Sequence[Adapter], Xn: np.ndarray, W: np.ndarray, bias: Optional[np.ndarray],
+                    neff: Sequence[Optional[np.ndarray]], rows=None) -> np.ndarray:
+    """y = (layer(xn) + b) - neff with the noise effect given as the bf16 tensor the client kept
+    (steps (2) and (3) of Sec. 3.8); neff[i]: None or bf16 bits [rows][d_out]; fp64 [nrows, d_out]."""
+    off = _i32(off)
+    S = len(off) - 1
+    d_out, d_in = W.shape
+    assert Xn.shape[1] == d_in and Xn.shape[0] >= off[-1]
+    rows_a = None if rows is None else _i32(rows)
+    n = int(off[-1]) if rows is None else len(rows_a)
+    keep, ptrs, nrows = _noise_args(off, neff, d_out)
+    Y = np.empty((n, d_out), dtype=np.float64)
+    ad = _pack(adapters, d_in, d_out)
+    rc = lib().orc_forward_denoise_rows(C.c_int32(d_in), C.c_int32(d_out), C.c_int32(S),
+                                        off.ctypes.data_as(C.c_void_p), ad, _u16(Xn), _u16(W), _u16(bias), ptrs,
+                                        nrows.ctypes.data_as(C.c_void_p), C.c_int32(n),
+                                        None if rows_a is None else rows_a.ctypes.data_as(C.c_void_p),
+                                        Y.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise ValueError("oracle forward_denoise: bad offsets, noise-effect rows or row index")
+    return Y
+
+
 def backward_input(off, adapters: Sequence[Adapter], dY: np.ndarray, W: np.ndarray,
                    rows=None, base_only: bool = False) -> np.ndarray:
     off = _i32(off)

@@ -107,7 +107,11 @@ int orc_forward_rows(int32_t d_in, int32_t d_out, int32_t S, const int32_t* off,
     for (int32_t q = 0; q < nrows; ++q) {
         int32_t t = rows ? rows[q] : q;
         int32_t i = seg_of(S, off, t);
-        if (i < 0) { bad = 1; continue; }
+        if (i < 0) {
+#pragma omp atomic write
+            bad = 1;
+            continue;
+        }
         const orc_adapter* a = &ad[i];
         const uint16_t* x = X + (size_t)t * d_in;
         double* H = NULL;
@@ -217,6 +221,33 @@ int orc_forward_private_rows(int32_t d_in, int32_t d_out, int32_t S, const int32
 }
 
 /*
+ * orc_forward_denoise_rows: steps (2) and (3) alone, with the noise effect given.  The client
+ * computes n_eff once per noise value and keeps it for later iterations (Sec. 3.8); what it keeps
+ * is a 16-bit activation tensor like any other it holds (Sec. 4), so here neff[i] is bf16,
+ * rows_of[i] rows of width d_out (one broadcast row or one per token; NULL = nothing to take
+ * off), and for the listed rows
+ *   y = (layer(xn) + b, the row's adapter applied) - neff,
+ * the layer evaluated by orc_forward_rows, the stored value widened exactly, nothing rounded.
+ */
+int orc_forward_denoise_rows(int32_t d_in, int32_t d_out, int32_t S, const int32_t* off,
+                             const orc_adapter* ad, const uint16_t* Xn, const uint16_t* W,
+                             const uint16_t* bias, const uint16_t* const* neff, const int32_t* rows_of,
+                             int32_t nrows, const int32_t* rows, double* Y_out) {
+    if (orc_check_offsets(S, off)) return 1;
+    for (int32_t i = 0; i < S; ++i)
+        if (neff[i] && rows_of[i] != 1 && rows_of[i] != off[i + 1] - off[i]) return 1;
+    int rc = orc_forward_rows(d_in, d_out, S, off, ad, Xn, W, bias, nrows, rows, NULL, Y_out);        /* (2) */
+    if (rc) return rc;
+    for (int32_t q = 0; q < nrows; ++q) {                                                            /* (3) */
+        const int32_t t = rows ? rows[q] : q, i = seg_of(S, off, t);
+        if (!neff[i]) continue;
+        const uint16_t* n = neff[i] + (size_t)(rows_of[i] == 1 ? 0 : t - off[i]) * d_out;
+        for (int32_t j = 0; j < d_out; ++j) Y_out[(size_t)q * d_out + j] -= bf(n[j]);
+    }
+    return 0;
+}
+
+/*
  * Input gradient for the listed rows of a backward batch (its own offsets/adapters).
  *   NONE:   dX[t][k] = sum_j dY[t][j] W[j][k]
  *   LORA:   dH[t][p] = s * sum_j dY[t][j] B[j][p]
@@ -235,7 +266,11 @@ int orc_backward_input_rows(int32_t d_in, int32_t d_out, int32_t S, const int32_
     for (int32_t q = 0; q < nrows; ++q) {
         int32_t t = rows ? rows[q] : q;
         int32_t i = seg_of(S, off, t);
-        if (i < 0) { bad = 1; continue; }
+        if (i < 0) {
+#pragma omp atomic write
+            bad = 1;
+            continue;
+        }
         const orc_adapter* a = &ad[i];
         int kind = base_only ? ORC_NONE : a->kind;
         const uint16_t* g = dY + (size_t)t * d_out;

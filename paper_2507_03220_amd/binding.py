@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libsymb.so")
 SYMB_OK, SYMB_ERR_INVALID_ARG, SYMB_ERR_BAD_SEGMENTS, SYMB_ERR_UNSUPPORTED, \
     SYMB_ERR_WORKSPACE_TOO_SMALL, SYMB_ERR_DEVICE = range(6)
 SYMB_ADAPTER_NONE, SYMB_ADAPTER_LORA, SYMB_ADAPTER_IA3, SYMB_ADAPTER_IA3_IN = range(4)
-SYMB_OP_FWD, SYMB_OP_BWD_INPUT, SYMB_OP_ADAPTER_GRAD = range(3)
+SYMB_OP_FWD, SYMB_OP_BWD_INPUT, SYMB_OP_ADAPTER_GRAD, SYMB_OP_FWD_INPLACE, SYMB_OP_BWD_INPUT_INPLACE = range(5)
+SYMB_OPT_DESCRIPTOR_REUSE, SYMB_OPT_K_SPLIT, SYMB_OPT_SMALL_BATCH_KERNELS, SYMB_OPT_SKINNY_DEEP = range(4)
 SYMB_BWD_FULL, SYMB_BWD_BASE_ONLY = 0, 1
 SYMB_GRAD_OVERWRITE, SYMB_GRAD_ACCUMULATE, SYMB_GRAD_REUSE_DH, SYMB_GRAD_REUSE_HS = 0, 1, 2, 4
 SYMB_MAX_RANK = 128
@@ -32,7 +33,8 @@ EXPORTS = ("symb_create", "symb_destroy", "symb_validate_batch", "symb_debug_row
            "symb_status_string", "symb_last_error",
            "symb_batcher_create", "symb_batcher_destroy", "symb_batcher_submit", "symb_batcher_pending",
            "symb_batcher_next_due", "symb_batcher_take",
-           "symb_debug_gemm_timing_enable", "symb_debug_gemm_timing_read", "symb_debug_descriptor_stats")
+           "symb_debug_gemm_timing_enable", "symb_debug_gemm_timing_read", "symb_debug_descriptor_stats",
+           "symb_debug_set_option", "symb_debug_xcd_rule")
 
 
 class symb_adapter(C.Structure):
@@ -89,6 +91,8 @@ def lib() -> C.CDLL:
         l.symb_debug_gemm_timing_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64),
                                                   C.POINTER(C.c_double)]
         l.symb_debug_descriptor_stats.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+        l.symb_debug_set_option.argtypes = [vp, i32, i32]
+        l.symb_debug_xcd_rule.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
         l.symb_status_string.argtypes = [C.c_int]
         l.symb_status_string.restype = C.c_char_p
         l.symb_last_error.argtypes = [vp]
@@ -301,3 +305,15 @@ def symb_debug_gemm_timing_read(handle, variant: int):
     ms, n, fl = C.c_double(0), C.c_int64(0), C.c_double(0)
     _check(lib().symb_debug_gemm_timing_read(handle, int(variant), C.byref(ms), C.byref(n), C.byref(fl)), handle)
     return ms.value, n.value, fl.value
+
+
+def symb_debug_set_option(handle, option: int, value: int) -> None:
+    _check(lib().symb_debug_set_option(handle, int(option), int(value)), handle)
+
+
+def symb_debug_xcd_rule(handle):
+    """Returns (holds, [XCD id seen for workgroup ids 0..7])."""
+    ok = C.c_int32(0)
+    ids = (C.c_int32 * 8)()
+    _check(lib().symb_debug_xcd_rule(handle, C.byref(ok), ids), handle)
+    return bool(ok.value), list(ids)

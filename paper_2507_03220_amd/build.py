@@ -43,17 +43,18 @@ def build(force: bool = True, verbose: bool = False) -> str:
 
 
 def build_tool(name: str) -> str:
-    """Compiles a stand-alone measurement (csrc/<name>.hip) into paper_2507_03220_amd/<name>."""
-    out = os.path.join(HERE, name)
+    """Compiles a stand-alone measurement program (measure/<name>.hip: not part of the library; the
+    summaries under profiles/ that quote it give the command) into measure/<name>."""
+    out = os.path.join(HERE, "measure", name)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     subprocess.check_call([hipcc, "-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
-                           "-packed-fp32-ops", "-o", out, os.path.join(HERE, "csrc", name + ".hip")],
+                           "-packed-fp32-ops", "-o", out, os.path.join(HERE, "measure", name + ".hip")],
                           stderr=subprocess.DEVNULL)
     return out
 
 
 def build_ceiling() -> str:
-    """The MFMA ceiling measurement (csrc/mfma_ceiling.hip)."""
+    """The MFMA ceiling measurement (measure/mfma_ceiling.hip)."""
     return build_tool("mfma_ceiling")
 
 

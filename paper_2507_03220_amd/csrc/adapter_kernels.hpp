@@ -820,6 +820,27 @@ __global__ void __launch_bounds__(256) symb_noise_add_kernel(const NoiseAddParam
     }
 }
 
+// -------------------------------------------------------------------------------------------
+// Row scatter of a per-segment call whose output went through a flat copy in the workspace:
+// row t of segment i moves from in[t] to out_seg[i][t - off[i]].  One workgroup per row chunk.
+// -------------------------------------------------------------------------------------------
+struct ScatterParams {
+    const bf16* in;           // [T][width]
+    int width;
+    const RowChunk* chunks;
+    bf16* const* out_seg;     // device [S]
+    const int32_t* off;       // device [S+1]
+};
+__global__ void __launch_bounds__(256) symb_scatter_rows_kernel(const ScatterParams p) {
+    const RowChunk ch = p.chunks[blockIdx.x];
+    const int nchunk = p.width >> 3;
+    bf16* const out = p.out_seg[ch.seg] - (size_t)p.off[ch.seg] * p.width;
+    for (int e = threadIdx.x; e < ch.nrows * nchunk; e += 256) {
+        const size_t at = (size_t)(ch.row0 + e / nchunk) * p.width + (size_t)(e % nchunk) * 8;
+        *reinterpret_cast<uint4*>(out + at) = *reinterpret_cast<const uint4*>(p.in + at);
+    }
+}
+
 __global__ void __launch_bounds__(256) symb_fill_zero_kernel(float* dst, size_t n) {
     for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = 0.f;
 }

@@ -66,14 +66,7 @@ struct GemmParams {
     int k_parts, k_whole;
     float* partial;
     int* k_count;
-    int walk;                   // 0: each XCD walks one contiguous run of tiles; 1: rounds of 32 tiles dealt to the XCDs in turn
     double timing_flops;        // host bookkeeping for the measurement hook; unused on the device
-#ifdef SYMB_GEMM_TRACE
-    unsigned long long* trace;  // tuning builds only: 16 timestamp slots per tile
-#endif
-#ifdef SYMB_GEMM_PROBE
-    int probe;                  // tuning builds only (256x256 kernel): 1 = no in-loop global loads, 2 = nor LDS reads, 5 = nor barriers
-#endif
 };
 
 // 16-byte chunk swizzle of a K-contiguous tile row (8 chunks of 8 bf16 per row).
@@ -150,11 +143,7 @@ symb_gemm16_kernel(const GemmParams p) {
     // (k_whole = 0), or the tiles of a last, mostly empty round.
     const int total = p.num_m_tiles * p.num_n_tiles;
     int lin, part = 0, nparts = 1, slot = 0;
-    if (p.walk == 1) {
-        const int k = blockIdx.x >> 3;
-        lin = (((k >> 5) << 3) + (blockIdx.x & 7)) * 32 + (k & 31);
-        if (lin >= total) return;
-    } else {
+    {
         const int per_xcd = (total + 7) >> 3;
         const int item = blockIdx.x >> 3;
         int li = item;
@@ -177,9 +166,6 @@ symb_gemm16_kernel(const GemmParams p) {
     const int tm = first_m + (lin % width) % gsz;
     const int tn = (lin % width) / gsz;
     const int m0 = tm * BM, n0 = tn * BN;
-#ifdef SYMB_GEMM_TRACE
-    if (p.trace && threadIdx.x == 0) { p.trace[(size_t)lin * 16 + 0] = __builtin_amdgcn_s_memrealtime(); p.trace[(size_t)lin * 16 + 5] = __builtin_readcyclecounter(); }
-#endif
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave >> 1) * WT, wn0 = (wave & 1) * WT;
     const int l15 = lane & 15, lg = lane >> 4;
@@ -402,9 +388,6 @@ symb_gemm16_kernel(const GemmParams p) {
         const unsigned long long gb = (unsigned long long)(b_tile + (NN ? (size_t)st0 * 64 * p.N : (size_t)st0 * 64));
         const unsigned stride_b = NN ? 128u * (unsigned)p.N : 128u;
         const unsigned swa = (unsigned)__builtin_amdgcn_readfirstlane((int)lds0 + wave * (1024 * NBLK));
-#ifdef SYMB_GEMM_TRACE
-        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 1] = __builtin_amdgcn_s_memrealtime();
-#endif
         if constexpr (NBLK == 8) {
 #define SYMB_GEMM16_LOOP_OPERANDS                                                                                   \
     :                                                                                                              \
@@ -414,11 +397,6 @@ symb_gemm16_kernel(const GemmParams p) {
       "s"(ga), "s"(gb), "s"(stride_b), "s"(KF), "s"(swa)                                                           \
     : "memory", "scc", SYMB_GEMM16_SCLOBBERS, SYMB_GEMM16_VCLOBBERS, SYMB_GEMM16_ACLOBBERS
             if constexpr (NN) asm volatile(SYMB_GEMM16_LOOP_NN SYMB_GEMM16_LOOP_OPERANDS);
-#ifdef SYMB_GEMM_PROBE
-            else if (p.probe == 1) asm volatile(SYMB_GEMM16_LOOP_NT_NOLOAD SYMB_GEMM16_LOOP_OPERANDS);
-            else if (p.probe == 2) asm volatile(SYMB_GEMM16_LOOP_NT_NOREAD SYMB_GEMM16_LOOP_OPERANDS);
-            else if (p.probe == 5) asm volatile(SYMB_GEMM16_LOOP_NT_NOBAR SYMB_GEMM16_LOOP_OPERANDS);
-#endif
             else asm volatile(SYMB_GEMM16_LOOP_NT SYMB_GEMM16_LOOP_OPERANDS);
 #undef SYMB_GEMM16_LOOP_OPERANDS
         } else {
@@ -433,9 +411,6 @@ symb_gemm16_kernel(const GemmParams p) {
 #undef SYMB_GEMM16S_LOOP_OPERANDS
         }
         __builtin_amdgcn_s_barrier();                      // everything landed and read before LDS is reused
-#ifdef SYMB_GEMM_TRACE
-        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 2] = __builtin_amdgcn_s_memrealtime();
-#endif
     }
     if (last_part && KFT * 64 < p.K) {
         gload_tail(KFT * 64);
@@ -511,13 +486,7 @@ symb_gemm16_kernel(const GemmParams p) {
                 });
             });
         }
-#ifdef SYMB_GEMM_TRACE
-        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 8] = __builtin_amdgcn_s_memrealtime();
-#endif
         __syncthreads();
-#ifdef SYMB_GEMM_TRACE
-        if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 9] = __builtin_amdgcn_s_memrealtime();
-#endif
         const bool to_seg = p.c_seg != nullptr && dst == p.C;   // the final output goes to the segments' own buffers
         constexpr int LPR = BN / 8;                  // lanes per row (16 bytes each)
         constexpr int RPP = 256 / LPR;               // rows per pass of the workgroup
@@ -683,16 +652,8 @@ symb_gemm16_kernel(const GemmParams p) {
         }
     }
 
-#ifdef SYMB_GEMM_TRACE
-    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 4] = __builtin_amdgcn_s_memrealtime();
-#endif
     // ---- final output: bias, IA3 scale, noise effect, one rounding, whole-row stores
     stage_out(p.C, p.epi_ia3 != 0 && p.tile_epi[tm] != 0);
-#ifdef SYMB_GEMM_TRACE
-    if (p.trace && threadIdx.x == 0) p.trace[(size_t)lin * 16 + 7] = __builtin_amdgcn_s_memrealtime();
-    __builtin_amdgcn_s_waitcnt(0);
-    if (p.trace && threadIdx.x == 0) { p.trace[(size_t)lin * 16 + 3] = __builtin_amdgcn_s_memrealtime(); p.trace[(size_t)lin * 16 + 6] = __builtin_readcyclecounter(); }
-#endif
 }
 
 }  // namespace symb

@@ -37,7 +37,6 @@ import os
 VT = 116                      # address temporaries v116..v127
 S_GA, S_GB = 80, 82
 S_CNT, S_ACUR, S_ANXT, S_ANN, S_BCUR, S_BNXT, S_T0, S_T1 = range(84, 92)
-LOAD_MOD = (" " + os.environ["SYMB_GEN_LOAD_MOD"]) if os.environ.get("SYMB_GEN_LOAD_MOD") else ""   # tuning: cache policy bits
 
 # The compiler does not look inside an assembly statement: whatever it places right after one
 # must not meet a matrix instruction that is still writing its result.
@@ -131,7 +130,7 @@ def unit_loads(sdst, which, js):
     sits between them covers the wait state an m0 write needs).  s{T0} holds unit + wavefront base."""
     V, G = (AV, S_GA) if which == "A" else (BV, S_GB)
     return [f"s_add_u32 s{S_T0}, s{sdst}, %{SWA}"], \
-           [([f"s_add_u32 m0, s{S_T0}, {1024 * j}"], [f"global_load_lds_dwordx4 %{V[j]}, s[{G}:{G + 1}]" + LOAD_MOD]) for j in js]
+           [([f"s_add_u32 m0, s{S_T0}, {1024 * j}"], [f"global_load_lds_dwordx4 %{V[j]}, s[{G}:{G + 1}]"]) for j in js]
 
 
 def unit_loads_flat(sdst, which, js):
@@ -197,10 +196,10 @@ def rotate():
             f"s_mov_b32 s{S_T0}, s{S_BCUR}", f"s_mov_b32 s{S_BCUR}, s{S_BNXT}", f"s_mov_b32 s{S_BNXT}, s{S_T0}"]
 
 
-def body(nn, loads_on, last, no_reads=False, no_barrier=False):
+def body(nn, loads_on, last):
     L = []
     # step 0
-    reads = [] if no_reads else frag_reads(nn, 1, S_ACUR, S_BCUR, 1)
+    reads = frag_reads(nn, 1, S_ACUR, S_BCUR, 1)
     pre, pairs = unit_loads(S_ANN, "A", range(NB)) if loads_on else ([], [])
     L += pre
     L += weave([mfma(0, i, j) for i, j in BLOCKS], reads, pairs, 2, 7)
@@ -209,9 +208,9 @@ def body(nn, loads_on, last, no_reads=False, no_barrier=False):
     if last:
         L += ["s_waitcnt lgkmcnt(0)"]
     else:
-        L += [f"s_waitcnt vmcnt({NB if loads_on else 0}) lgkmcnt(0)"] + ([] if no_barrier else ["s_barrier"])
+        L += [f"s_waitcnt vmcnt({NB if loads_on else 0}) lgkmcnt(0)", "s_barrier"]
     # step 1
-    reads = [] if (last or no_reads) else frag_reads(nn, 0, S_ANXT, S_BNXT, 0)
+    reads = [] if last else frag_reads(nn, 0, S_ANXT, S_BNXT, 0)
     pre, pairs = unit_loads(S_BCUR, "B", range(NB)) if loads_on else ([], [])
     L += pre
     L += weave([mfma(1, i, j) for i, j in BLOCKS], reads, pairs, 1, 4)
@@ -222,7 +221,7 @@ def body(nn, loads_on, last, no_reads=False, no_barrier=False):
     return L
 
 
-def build(nn, no_loads=False, no_reads=False, no_barrier=False):
+def build(nn):
     L = []
     L += [f"s_mov_b64 s[{S_GA}:{S_GA + 1}], %{GA}", f"s_mov_b64 s[{S_GB}:{S_GB + 1}], %{GB}",
           f"s_sub_u32 s{S_CNT}, %{KF}, 2",
@@ -239,15 +238,15 @@ def build(nn, no_loads=False, no_reads=False, no_barrier=False):
     L += ["s_waitcnt lgkmcnt(0)"]
     L += [f"s_cmp_lt_u32 %{KF}, 3", "s_cbranch_scc1 2f"]
     L.append("1:")
-    L += body(nn, not no_loads, False, no_reads, no_barrier)
+    L += body(nn, True, False)
     L += rotate()
     L += [f"s_sub_u32 s{S_CNT}, s{S_CNT}, 1", f"s_cmp_lg_u32 s{S_CNT}, 0", "s_cbranch_scc1 1b"]
     L.append("2:")
     L += [f"s_cmp_lt_u32 %{KF}, 2", "s_cbranch_scc1 3f"]
-    L += body(nn, False, False, no_reads, no_barrier)
+    L += body(nn, False, False)
     L += rotate()
     L.append("3:")
-    L += body(nn, False, True, no_reads, no_barrier)
+    L += body(nn, False, True)
     L.append("s_waitcnt vmcnt(0)")
     L += MFMA_DRAIN
     return L
@@ -358,14 +357,6 @@ def main():
     sclob = ", ".join(f'"s{r}"' for r in range(80, 92))
     configure(8)
     big = section("SYMB_GEMM16")
-    probe = f"""#ifdef SYMB_GEMM_PROBE   // tuning builds only: the 256x256 loop without its in-loop global loads / LDS reads / barriers
-{emit("SYMB_GEMM16_LOOP_NT_NOLOAD", build(False, no_loads=True))}
-
-{emit("SYMB_GEMM16_LOOP_NT_NOREAD", build(False, no_loads=True, no_reads=True))}
-
-{emit("SYMB_GEMM16_LOOP_NT_NOBAR", build(False, no_loads=True, no_reads=True, no_barrier=True))}
-#endif
-"""
     configure(4)
     small = section("SYMB_GEMM16S")
     text = f"""// GENERATED by gen_gemm16_asm.py -- do not edit by hand.
@@ -376,7 +367,6 @@ def main():
 // full stage.
 #pragma once
 {big}
-{probe}
 {small}
 #define SYMB_GEMM16_SCLOBBERS {sclob}
 """

@@ -20,6 +20,15 @@
 
 using namespace symb;
 
+// One workgroup per entry of `out`: the id of the XCD (hardware register XCC_ID) the workgroup runs on.
+__global__ void symb_xcc_probe_kernel(int* out) {
+    if (threadIdx.x == 0) {
+        unsigned v;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(v));
+        out[blockIdx.x] = (int)(v & 0xfu);
+    }
+}
+
 namespace {
 
 thread_local std::string g_tls_error;
@@ -28,6 +37,7 @@ constexpr int kSlots = 32;                      // descriptor ring depth (a trai
 constexpr size_t kSlotBytes = (size_t)2 << 20;  // capacity of one descriptor blob
 constexpr int kSkinnyRows = SKINNY_ROWS;        // rows per skinny / scale work item
 constexpr int kMaxTimed = 4096;                 // GEMM launches recorded between two timing reads
+constexpr int kXccProbeGroups = 2048;           // workgroups of the XCD-rule measurement (8 rounds of 256)
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int rpad_of(int r) { return (r + 15) / 16 * 16; }
@@ -48,7 +58,14 @@ struct symb_context {
     uint64_t slot_hash[kSlots] = {};
     hipStream_t slot_stream[kSlots] = {};
     int64_t desc_sent = 0, desc_in_place = 0;
+    int call_slot = -1;                   // the slot this call's descriptors went to (-1: none yet)
     std::string error;
+    // measurement switches (symb_debug_set_option); all on by default
+    bool opt_desc_reuse = true, opt_k_split = true, opt_small_rows = true, opt_skinny_deep = true;
+    // Whether workgroup id mod 8 names the XCD a workgroup runs on, measured at creation: the K-split of
+    // the GEMM keeps all parts of a tile on one XCD (behind one L2) and is used only if this holds.
+    bool xcd_rule = false;
+    int xcc_of_residue[8] = {-1, -1, -1, -1, -1, -1, -1, -1};
     std::vector<const void*> lds_attr_set;       // kernels whose dynamic-LDS limit was raised on this context's device
     // measurement hook: event pairs around GEMM launches
     bool timing = false;
@@ -149,10 +166,11 @@ std::vector<int32_t> plan_tile_kind(const symb_batch* b, const std::vector<int32
     return v;
 }
 
-void plan_chunks(const symb_batch* b, int rows, bool lora_only, std::vector<RowChunk>& out) {
+// Row chunks of `rows` rows, never across a segment boundary; only_kind >= 0: of segments of that kind only.
+void plan_chunks(const symb_batch* b, int rows, int only_kind, std::vector<RowChunk>& out) {
     out.clear();
     for (int i = 0; i < b->num_segments; ++i) {
-        if (lora_only && b->adapters[i].kind != SYMB_ADAPTER_LORA) continue;
+        if (only_kind >= 0 && b->adapters[i].kind != only_kind) continue;
         for (int r = b->seg_offsets[i]; r < b->seg_offsets[i + 1]; r += rows)
             out.push_back(RowChunk{i, r, std::min(rows, b->seg_offsets[i + 1] - r), 0});
     }
@@ -188,22 +206,11 @@ BatchInfo inspect(const symb_batch* b) {
 
 // Tile variants of the GEMM kernel (gemm16_kernel.hpp): 3 = 256x256 tile, taken when the problem has
 // enough such tiles to fill the chip; 2 = 128x128 tile, for everything smaller.
-// SYMB_GEMM_VARIANT = 2 or 3 overrides the choice (tuning aid).
 int gemm_variant(int M, int N) {
-    static const int forced = [] {
-        const char* e = getenv("SYMB_GEMM_VARIANT");
-        return e ? atoi(e) : -1;
-    }();
-    if (forced == 2 || forced == 3) return forced;
     const long big = (long)((M + 255) / 256) * ((N + 255) / 256);
     return big >= 128 ? 3 : 2;
 }
 int gemm_tile_m(int M, int N) { return gemm_variant(M, N) == 3 ? 256 : 128; }
-
-int gemm_walk() {
-    static const int walk = [] { const char* e = getenv("SYMB_GEMM_WALK"); return e ? atoi(e) : 0; }();
-    return walk;
-}
 
 // K-split.  Every XCD walks a contiguous run of per_xcd = ceil(tiles / 8) tiles; the tiles of that run
 // from number `whole` on are computed by `parts` workgroups each, one per K range, which leave fp32
@@ -219,8 +226,8 @@ int gemm_walk() {
 //    4 parts for 8 tiles (a quarter of a tile's time), 3 parts for 20 tiles of a long K (60
 //    workgroups in two passes of a third each), none where the sum of the partial tiles (256 KiB
 //    each) would cost what the split saves.
-// parts is at most 8 and at most one per 8 stages of 64 k.  SYMB_GEMM_KSPLIT=0 turns both off,
-// SYMB_GEMM_KSPLIT=n replaces the 320 (tuning aids).
+// parts is at most 8 and at most one per 8 stages of 64 k.  A pure function of the shape: the
+// workspace figure does not depend on the process environment or on the handle.
 struct SplitPlan {
     int parts = 1;        // K ranges per split tile (1: no split)
     int whole = 0;        // tiles per XCD that stay whole
@@ -229,9 +236,8 @@ struct SplitPlan {
 };
 SplitPlan gemm_split_plan(int M, int N, int K) {
     SplitPlan s;
-    static const int target = [] { const char* e = getenv("SYMB_GEMM_KSPLIT"); return e ? atoi(e) : 320; }();
-    static const int tail_max = [] { const char* e = getenv("SYMB_GEMM_KSPLIT_TAIL"); return e ? atoi(e) : 4; }();
-    if (target <= 0 || M <= 0 || gemm_walk() != 0) return s;
+    constexpr int target = 320, tail_max = 4;
+    if (M <= 0) return s;
     const int KF = K / 64;
     if (gemm_variant(M, N) == 2) {
         const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
@@ -288,12 +294,13 @@ struct WsLayout {
     size_t pk_off = 0, pk_bytes = 0;      // packed B^T
     size_t sc_off = 0, sc_bytes = 0;      // IA3-scaled copy of dY [T][d_out] (input gradient) or of X [T][d_in] (forward, IA3_IN) bf16
     size_t pa_off = 0, pa_bytes = 0;      // packed A^T (input-major weight, input gradient only)
+    size_t so_off = 0, so_bytes = 0;      // flat output [T][width] bf16 of a per-segment call whose outputs overlap its inputs
     size_t gr_off = 0, gr_bytes = 0;      // fp32 runs of the LoRA gradients of split segments (see grad_split)
     size_t tp_off = 0, tp_bytes = 0;      // fp32 partial tiles of a K-split GEMM (see gemm_split_plan); last, optional
     size_t total = 0;
 };
 
-WsLayout ws_layout(const symb_batch* b, const BatchInfo& bi, int op, bool full_bwd, bool any_lora_grad) {
+WsLayout ws_layout(const symb_batch* b, const BatchInfo& bi, int op, bool full_bwd, bool any_lora_grad, bool staged_out = false) {
     WsLayout w;
     size_t cur = 0;
     auto take = [&](size_t& off, size_t& bytes, size_t n) {
@@ -327,6 +334,8 @@ WsLayout ws_layout(const symb_batch* b, const BatchInfo& bi, int op, bool full_b
             if (gr) take(w.gr_off, w.gr_bytes, gr);
         }
     }
+    if (staged_out && op != SYMB_OP_ADAPTER_GRAD)
+        take(w.so_off, w.so_bytes, (size_t)bi.T * (op == SYMB_OP_FWD ? b->d_out : b->d_in) * 2);
     if (op == SYMB_OP_FWD) {
         const SplitPlan sp = gemm_split_plan(bi.T, b->d_out, b->d_in);
         if (sp.parts > 1) take(w.tp_off, w.tp_bytes, sp.bytes);
@@ -357,7 +366,7 @@ symb_status upload(symb_handle h, const Blob& blob, hipStream_t st, unsigned cha
     // a launch ends), so a batch that comes again with the same offsets, adapters and buffers -- the
     // next decode step of the same clients, the same projection in the next training step -- finds
     // its descriptors in place.  The pinned copy of a slot is what its device copy holds.
-    static const bool reuse = [] { const char* e = getenv("SYMB_DESC_REUSE"); return !e || atoi(e) != 0; }();
+    const bool reuse = h->opt_desc_reuse;
     const size_t n = blob.bytes.size();
     uint64_t hash = 0x9E3779B97F4A7C15ull ^ n;
     {
@@ -375,6 +384,7 @@ symb_status upload(symb_handle h, const Blob& blob, hipStream_t st, unsigned cha
             if (h->slot_used[j] && h->slot_size[j] == n && h->slot_hash[j] == hash && h->slot_stream[j] == st &&
                 memcmp(h->host_ring + (size_t)j * kSlotBytes, blob.bytes.data(), n) == 0) {
                 h->cur_slot = j;
+                h->call_slot = j;
                 ++h->desc_in_place;
                 *dev_base = h->dev_ring + (size_t)j * kSlotBytes;
                 return SYMB_OK;
@@ -382,6 +392,7 @@ symb_status upload(symb_handle h, const Blob& blob, hipStream_t st, unsigned cha
     const int slot = h->next_slot;
     h->next_slot = (slot + 1) % kSlots;
     h->cur_slot = slot;
+    h->call_slot = slot;
     if (h->slot_used[slot]) SYMB_HIP(h, hipEventSynchronize(h->slot_done[slot]));
     h->slot_used[slot] = false;            // until the copy is enqueued, the slot holds nothing a later call may reuse
     unsigned char* hp = h->host_ring + (size_t)slot * kSlotBytes;
@@ -397,6 +408,18 @@ symb_status upload(symb_handle h, const Blob& blob, hipStream_t st, unsigned cha
     *dev_base = dp;
     return SYMB_OK;
 }
+
+// A call that fails after its descriptors went to a slot may leave that slot's device copy in a state
+// no later call should take over (a GEMM that never ran has not put its K-split counters back to zero, a
+// launch may be half enqueued): unless the call completes, its slot is never matched again.
+struct CallGuard {
+    symb_handle h;
+    bool completed = false;
+    explicit CallGuard(symb_handle h_) : h(h_) { h->call_slot = -1; }
+    ~CallGuard() {
+        if (!completed && h->call_slot >= 0) h->slot_size[h->call_slot] = SIZE_MAX;
+    }
+};
 
 // Marks the slot busy until everything enqueued so far on `st` has run (kernels read it).
 symb_status seal_slot(symb_handle h, hipStream_t st) {
@@ -424,7 +447,7 @@ std::vector<SegDesc> make_segdesc(const symb_batch* b) {
 
 // ---- GEMM launch -----------------------------------------------------------------------------
 template <class KFN>
-symb_status launch_gemm_fn(symb_handle h, GemmParams gp, hipStream_t st, KFN kfn, int BM, int BN, int threads, int smem, bool nn) {
+symb_status launch_gemm_fn(symb_handle h, GemmParams gp, hipStream_t st, KFN kfn, int BM, int BN, int threads, int smem, int variant) {
     // once per context (= per device): the attribute belongs to the device the kernel is loaded on
     const void* kptr = reinterpret_cast<const void*>(kfn);
     if (std::find(h->lds_attr_set.begin(), h->lds_attr_set.end(), kptr) == h->lds_attr_set.end()) {
@@ -434,16 +457,9 @@ symb_status launch_gemm_fn(symb_handle h, GemmParams gp, hipStream_t st, KFN kfn
     gp.num_m_tiles = (gp.M + BM - 1) / BM;
     gp.num_n_tiles = (gp.N + BN - 1) / BN;
     gp.group_m = 8;
-#ifdef SYMB_GEMM_PROBE
-    { const char* e = getenv("SYMB_GEMM_PROBE"); gp.probe = e ? atoi(e) : 0; }
-#endif
-#ifdef SYMB_GEMM_TRACE
-    { const char* e = getenv("SYMB_TRACE_PTR"); gp.trace = e ? (unsigned long long*)strtoull(e, nullptr, 0) : nullptr; }
-#endif
-    gp.walk = gemm_walk();
     const int total = gp.num_m_tiles * gp.num_n_tiles;
     const int per_xcd = (total + 7) / 8;
-    int grid = gp.walk == 1 ? ((total + 255) / 256) * 256 : per_xcd * 8;
+    int grid = per_xcd * 8;
     if (gp.k_parts > 1) grid = 8 * (gp.k_whole + (per_xcd - gp.k_whole) * gp.k_parts);
     const bool timed = h->timing && (int)h->timed.size() < kMaxTimed;
     const size_t slot = h->timed.size();
@@ -452,7 +468,7 @@ symb_status launch_gemm_fn(symb_handle h, GemmParams gp, hipStream_t st, KFN kfn
     SYMB_HIP(h, hipGetLastError());
     if (timed) {
         SYMB_HIP(h, hipEventRecord(h->tev[2 * slot + 1], st));
-        h->timed.push_back({nn ? 1 : 0, gp.timing_flops});
+        h->timed.push_back({variant, gp.timing_flops});
     }
     return SYMB_OK;
 }
@@ -460,7 +476,9 @@ symb_status launch_gemm_fn(symb_handle h, GemmParams gp, hipStream_t st, KFN kfn
 template <int NBLK, bool NN, bool PLAIN>
 symb_status launch_gemm16_t(symb_handle h, const GemmParams& gp, hipStream_t st) {
     using TT = Gemm16Tile<NBLK>;
-    return launch_gemm_fn(h, gp, st, symb_gemm16_kernel<NBLK, NN, PLAIN>, TT::BM, TT::BN, TT::NT, TT::SMEM, NN);
+    // instantiation number of the measurement hook: bit 0 = N-contiguous weight, bit 1 = 128x128 tile, bit 2 = full epilogue
+    constexpr int variant = (NN ? 1 : 0) | (NBLK == 4 ? 2 : 0) | (PLAIN ? 0 : 4);
+    return launch_gemm_fn(h, gp, st, symb_gemm16_kernel<NBLK, NN, PLAIN>, TT::BM, TT::BN, TT::NT, TT::SMEM, variant);
 }
 
 // Algorithmic work of one GEMM launch: 2 M N K plus the fused LoRA term.
@@ -483,8 +501,7 @@ symb_status launch_gemm(symb_handle h, const GemmParams& gp, hipStream_t st) {
 
 // Up to one workgroup per compute unit the deep-prefetch build is used (where its buffers fit in LDS).
 template <int RB>
-void launch_skinny_rb(const SkinnyParams& sp, int nchunks, hipStream_t st) {
-    static const bool deep_ok = [] { const char* e = getenv("SYMB_SKINNY_DEEP"); return !e || atoi(e) != 0; }();
+void launch_skinny_rb(const SkinnyParams& sp, int nchunks, bool deep_ok, hipStream_t st) {
     if constexpr (RB <= 4) {
         if (deep_ok && nchunks <= 256) {
             hipLaunchKernelGGL((symb_skinny_kernel<RB, true>), dim3(nchunks), dim3(256), 0, st, sp);
@@ -495,10 +512,11 @@ void launch_skinny_rb(const SkinnyParams& sp, int nchunks, hipStream_t st) {
 }
 symb_status launch_skinny(symb_handle h, const SkinnyParams& sp, int nchunks, int max_rpad, hipStream_t st) {
     if (nchunks == 0) return SYMB_OK;
-    if (max_rpad <= 16) launch_skinny_rb<1>(sp, nchunks, st);
-    else if (max_rpad <= 32) launch_skinny_rb<2>(sp, nchunks, st);
-    else if (max_rpad <= 64) launch_skinny_rb<4>(sp, nchunks, st);
-    else launch_skinny_rb<8>(sp, nchunks, st);
+    const bool deep = h->opt_skinny_deep;
+    if (max_rpad <= 16) launch_skinny_rb<1>(sp, nchunks, deep, st);
+    else if (max_rpad <= 32) launch_skinny_rb<2>(sp, nchunks, deep, st);
+    else if (max_rpad <= 64) launch_skinny_rb<4>(sp, nchunks, deep, st);
+    else launch_skinny_rb<8>(sp, nchunks, deep, st);
     SYMB_HIP(h, hipGetLastError());
     return SYMB_OK;
 }
@@ -572,7 +590,46 @@ symb_status symb_create(symb_handle* out, int device) {
             return fail(nullptr, SYMB_ERR_DEVICE, "hipEventCreate failed");
         }
     }
+    // The K-split of the GEMM assumes that workgroup id mod 8 names the XCD: measure it.  Every
+    // workgroup of a probe launch records the XCD it ran on; the rule holds if all workgroups of a
+    // residue class report the same one.  (A device with a single XCD passes trivially.)
+    {
+        int* probe = reinterpret_cast<int*>(c->dev_ring);          // the ring is idle: borrow its first 8 KiB
+        std::vector<int> xcc(kXccProbeGroups, -1);
+        hipLaunchKernelGGL(symb_xcc_probe_kernel, dim3(kXccProbeGroups), dim3(64), 0, nullptr, probe);
+        if (hipGetLastError() != hipSuccess ||
+            hipMemcpy(xcc.data(), probe, sizeof(int) * kXccProbeGroups, hipMemcpyDeviceToHost) != hipSuccess) {
+            symb_destroy(c);
+            return fail(nullptr, SYMB_ERR_DEVICE, "XCD probe launch failed");
+        }
+        bool ok = true;
+        for (int i = 0; i < kXccProbeGroups; ++i) ok = ok && xcc[i] == xcc[i & 7];
+        c->xcd_rule = ok;
+        for (int r = 0; r < 8; ++r) c->xcc_of_residue[r] = xcc[r];
+    }
     *out = c;
+    return SYMB_OK;
+}
+
+symb_status symb_debug_set_option(symb_handle h, int32_t option, int32_t value) {
+    symb_status st = check_handle(h);
+    if (st != SYMB_OK) return st;
+    switch (option) {
+        case SYMB_OPT_DESCRIPTOR_REUSE: h->opt_desc_reuse = value != 0; break;
+        case SYMB_OPT_K_SPLIT: h->opt_k_split = value != 0; break;
+        case SYMB_OPT_SMALL_BATCH_KERNELS: h->opt_small_rows = value != 0; break;
+        case SYMB_OPT_SKINNY_DEEP: h->opt_skinny_deep = value != 0; break;
+        default: return fail(h, SYMB_ERR_INVALID_ARG, "unknown option %d", option);
+    }
+    return SYMB_OK;
+}
+
+symb_status symb_debug_xcd_rule(symb_handle h, int32_t* holds, int32_t* xcc_of_residue) {
+    symb_status st = check_handle(h);
+    if (st != SYMB_OK) return st;
+    if (holds) *holds = h->xcd_rule ? 1 : 0;
+    if (xcc_of_residue)
+        for (int r = 0; r < 8; ++r) xcc_of_residue[r] = h->xcc_of_residue[r];
     return SYMB_OK;
 }
 
@@ -669,9 +726,11 @@ symb_status symb_workspace_bytes(const symb_batch* b, int32_t op, size_t* out) {
     symb_status st = validate(nullptr, b);
     if (st != SYMB_OK) return st;
     if (!out) return fail(nullptr, SYMB_ERR_INVALID_ARG, "out is null");
-    if (op < SYMB_OP_FWD || op > SYMB_OP_ADAPTER_GRAD) return fail(nullptr, SYMB_ERR_INVALID_ARG, "unknown op %d", op);
+    if (op < SYMB_OP_FWD || op > SYMB_OP_BWD_INPUT_INPLACE) return fail(nullptr, SYMB_ERR_INVALID_ARG, "unknown op %d", op);
     const BatchInfo bi = inspect(b);
-    *out = ws_layout(b, bi, op, true, wants_lora_grad(b)).total;
+    const bool staged = op == SYMB_OP_FWD_INPLACE || op == SYMB_OP_BWD_INPUT_INPLACE;
+    const int base_op = op == SYMB_OP_FWD_INPLACE ? SYMB_OP_FWD : op == SYMB_OP_BWD_INPUT_INPLACE ? SYMB_OP_BWD_INPUT : op;
+    *out = ws_layout(b, bi, base_op, true, wants_lora_grad(b), staged).total;
     return SYMB_OK;
 }
 
@@ -712,11 +771,33 @@ symb_status check_seg_ptrs(symb_handle h, const symb_batch* b, const void* const
     return SYMB_OK;
 }
 
+// Whether any output buffer of a per-segment call shares bytes with any of its input buffers.
+static bool seg_buffers_overlap(const symb_batch* b, const void* const* in_seg, size_t in_row_bytes, void* const* out_seg,
+                                size_t out_row_bytes) {
+    std::vector<std::pair<uintptr_t, uintptr_t>> in;
+    for (int i = 0; i < b->num_segments; ++i) {
+        const size_t n = (size_t)(b->seg_offsets[i + 1] - b->seg_offsets[i]);
+        if (n) in.emplace_back((uintptr_t)in_seg[i], (uintptr_t)in_seg[i] + n * in_row_bytes);
+    }
+    std::sort(in.begin(), in.end());
+    for (size_t k = 1; k < in.size(); ++k) in[k].second = std::max(in[k].second, in[k - 1].second);   // running end: sorted by start
+    for (int i = 0; i < b->num_segments; ++i) {
+        const size_t n = (size_t)(b->seg_offsets[i + 1] - b->seg_offsets[i]);
+        if (!n) continue;
+        const uintptr_t lo = (uintptr_t)out_seg[i], hi = lo + n * out_row_bytes;
+        // the last input interval that starts before hi: with the running end it tells whether any reaches past lo
+        auto it = std::lower_bound(in.begin(), in.end(), std::make_pair(hi, (uintptr_t)0));
+        if (it != in.begin() && std::prev(it)->second > lo) return true;
+    }
+    return false;
+}
+
 static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* X, const void* W, const void* bias,
                                 const symb_noise* noise_effect, void* Y, void* Ybase, void* ws, size_t ws_bytes, void* stream,
                                 const void* const* X_seg = nullptr, void* const* Y_seg = nullptr) {
     symb_status st = check_handle(h);
     if (st != SYMB_OK) return st;
+    CallGuard guard(h);
     if ((st = validate(h, b)) != SYMB_OK) return st;
     const BatchInfo bi = inspect(b);
     if (bi.T == 0) return SYMB_OK;
@@ -732,20 +813,25 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     if (noise_effect && (st = make_noisedesc(h, b, noise_effect, "noise effect", nd)) != SYMB_OK) return st;
     if (misaligned16(X) || misaligned16(W) || misaligned16(Y) || misaligned16(Ybase) || misaligned16(bias) || misaligned16(ws))
         return fail(h, SYMB_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
-    const WsLayout wl = ws_layout(b, bi, SYMB_OP_FWD, true, false);
+    // Per-segment buffers whose outputs overlap inputs (a client's one buffer used for both, Sec. 3.5):
+    // column tiles of a row tile run at different times, so the GEMM writes a flat copy in the
+    // workspace and a row scatter, after it on the stream, fills the clients' buffers.
+    const bool staged = seg_io && seg_buffers_overlap(b, X_seg, (size_t)b->d_in * 2, Y_seg, (size_t)b->d_out * 2);
+    const WsLayout wl = ws_layout(b, bi, SYMB_OP_FWD, true, false, staged);
     const size_t ws_need = wl.tp_bytes ? wl.tp_off : wl.total;     // the K-split's partial tiles are optional
     if (ws_need > ws_bytes || (ws_need && !ws))
-        return fail(h, SYMB_ERR_WORKSPACE_TOO_SMALL, "forward needs %zu workspace bytes, got %zu", ws_need, ws_bytes);
+        return fail(h, SYMB_ERR_WORKSPACE_TOO_SMALL, "forward needs %zu workspace bytes, got %zu%s", ws_need, ws_bytes,
+                    staged ? " (output buffers overlap input buffers: size the workspace with SYMB_OP_FWD_INPLACE)" : "");
     const SplitPlan ksp = gemm_split_plan(bi.T, b->d_out, b->d_in);
-    const bool k_split = wl.tp_bytes && ws && ws_bytes >= wl.total && !Ybase;
+    const bool k_split = wl.tp_bytes && ws && ws_bytes >= wl.total && !Ybase && h->opt_k_split && h->xcd_rule;
     hipStream_t s = (hipStream_t)stream;
 
     const int bm = gemm_tile_m(bi.T, b->d_out);
     std::vector<int32_t> lo, hi;
     plan_row_tiles(b, bm, lo, hi);
     std::vector<RowChunk> chunks, all_chunks;
-    plan_chunks(b, kSkinnyRows, true, chunks);
-    if (bi.n_ia3in) plan_chunks(b, kSkinnyRows, false, all_chunks);
+    plan_chunks(b, kSkinnyRows, SYMB_ADAPTER_LORA, chunks);
+    if (bi.n_ia3in || staged) plan_chunks(b, kSkinnyRows, -1, all_chunks);
     const std::vector<SegDesc> sd = make_segdesc(b);
     unsigned char* wsb = (unsigned char*)ws;
     // Input-major weight: the forward is the N-contiguous GEMM, whose LoRA steps read the adapter
@@ -816,16 +902,14 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     // per 32 output columns.  Measured against the tiled kernel with its K-split (33-40 us per call
     // from 4 to 64 rows): 17-20 us up to 16 rows on 4096 x 4096 (descriptors in place), but slower from 24 rows on, and on
     // 4096 x 11008 at any row count (344 workgroups of 152 KiB LDS: a second, third-full round).
-    // SYMB_SMALL_T=0 turns it off (tuning aid).
-    static const bool small_path = [] { const char* e = getenv("SYMB_SMALL_T"); return !e || atoi(e) != 0; }();
-    if (small_path && bi.T <= 16 && (long long)b->d_in * b->d_out <= 24ll << 20 && !conv1d && !seg_io && !Ybase && nd.empty() &&
+    if (h->opt_small_rows && bi.T <= 16 && (long long)b->d_in * b->d_out <= 24ll << 20 && !conv1d && !seg_io && !Ybase && nd.empty() &&
         bi.n_ia3in == 0) {
         RowGemvParams rp{(const bf16*)W, (const bf16*)X, (bf16*)Y, (const bf16*)bias, b->d_in, b->d_out, bi.T, bi.S,
                          (const int32_t*)(dev + o_off), (const SegDesc*)(dev + o_seg), Hs, 2 * bi.max_rpad};
         const dim3 grid((b->d_out + SKINNY_ROWS - 1) / SKINNY_ROWS);
         hipLaunchKernelGGL(symb_rowgemv_kernel<1>, grid, dim3(256), 0, s, rp);
         SYMB_HIP(h, hipGetLastError());
-        return seal_slot(h, s);
+        { guard.completed = true; return seal_slot(h, s); }
     }
     GemmParams gp{};
     gp.Aop = x_op;
@@ -833,10 +917,10 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
         gp.Aop = nullptr;
         gp.a_seg = (const bf16* const*)(dev + o_xs);
         gp.a_base = (const bf16*)x_base;
-        gp.c_seg = (bf16* const*)(dev + o_ys);
+        if (!staged) gp.c_seg = (bf16* const*)(dev + o_ys);
     }
     gp.Bop = (const bf16*)W;
-    gp.C = (bf16*)Y;
+    gp.C = staged ? (bf16*)(wsb + wl.so_off) : (bf16*)Y;
     gp.Cbase = (bf16*)Ybase;
     gp.bias = (const bf16*)bias;
     gp.M = bi.T;
@@ -861,7 +945,13 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     // W [d_out][d_in]: K-contiguous weight rows.  W [d_in][d_out]: the weight is the [K][N] operand.
     st = conv1d ? launch_gemm<true>(h, gp, s) : launch_gemm<false>(h, gp, s);
     if (st != SYMB_OK) return st;
-    return seal_slot(h, s);
+    if (staged) {
+        ScatterParams sc{(const bf16*)(wsb + wl.so_off), b->d_out, (const RowChunk*)(dev + o_all), (bf16* const*)(dev + o_ys),
+                         (const int32_t*)(dev + o_off)};
+        hipLaunchKernelGGL(symb_scatter_rows_kernel, dim3((unsigned)all_chunks.size()), dim3(256), 0, s, sc);
+        SYMB_HIP(h, hipGetLastError());
+    }
+    { guard.completed = true; return seal_slot(h, s); }
 }
 
 symb_status symb_base_linear_fwd(symb_handle h, const symb_batch* b, const void* X, const void* W, const void* bias,
@@ -888,6 +978,7 @@ symb_status symb_base_linear_fwd_denoise(symb_handle h, const symb_batch* b, con
 symb_status symb_noise_add(symb_handle h, const symb_batch* b, const void* X, const symb_noise* noise, void* Xn, void* stream) {
     symb_status st = check_handle(h);
     if (st != SYMB_OK) return st;
+    CallGuard guard(h);
     if ((st = validate(h, b)) != SYMB_OK) return st;
     if (!noise) return fail(h, SYMB_ERR_INVALID_ARG, "noise is required");
     const BatchInfo bi = inspect(b);
@@ -898,7 +989,7 @@ symb_status symb_noise_add(symb_handle h, const symb_batch* b, const void* X, co
     if ((st = make_noisedesc(h, b, noise, "noise", nd)) != SYMB_OK) return st;
     hipStream_t s = (hipStream_t)stream;
     std::vector<RowChunk> chunks;
-    plan_chunks(b, kSkinnyRows, false, chunks);
+    plan_chunks(b, kSkinnyRows, -1, chunks);
     Blob blob;
     const size_t o_off = blob.add(b->seg_offsets, (size_t)bi.S + 1);
     const size_t o_ch = blob.add(chunks.data(), chunks.size());
@@ -909,7 +1000,7 @@ symb_status symb_noise_add(symb_handle h, const symb_batch* b, const void* X, co
                       (const NoiseDesc*)(dev + o_nd)};
     hipLaunchKernelGGL(symb_noise_add_kernel, dim3((unsigned)chunks.size()), dim3(256), 0, s, np);
     SYMB_HIP(h, hipGetLastError());
-    return seal_slot(h, s);
+    { guard.completed = true; return seal_slot(h, s); }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -940,6 +1031,7 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
                                        const void* const* dY_seg, void* const* dX_seg) {
     symb_status st = check_handle(h);
     if (st != SYMB_OK) return st;
+    CallGuard guard(h);
     if ((st = validate(h, b)) != SYMB_OK) return st;
     if (flags != SYMB_BWD_FULL && flags != SYMB_BWD_BASE_ONLY) return fail(h, SYMB_ERR_INVALID_ARG, "unknown backward flag %u", flags);
     const BatchInfo bi = inspect(b);
@@ -955,12 +1047,14 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     if (misaligned16(dY) || misaligned16(W) || misaligned16(dX) || misaligned16(dXbase) || misaligned16(ws))
         return fail(h, SYMB_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
     const bool full = flags == SYMB_BWD_FULL;
-    const WsLayout wl = ws_layout(b, bi, SYMB_OP_BWD_INPUT, full, false);
+    const bool staged = seg_io && seg_buffers_overlap(b, dY_seg, (size_t)b->d_out * 2, dX_seg, (size_t)b->d_in * 2);   // see the forward
+    const WsLayout wl = ws_layout(b, bi, SYMB_OP_BWD_INPUT, full, false, staged);
     const size_t ws_need = wl.tp_bytes ? wl.tp_off : wl.total;     // the K-split's partial tiles are optional
     if (ws_need > ws_bytes || (ws_need && !ws))
-        return fail(h, SYMB_ERR_WORKSPACE_TOO_SMALL, "backward needs %zu workspace bytes, got %zu", ws_need, ws_bytes);
+        return fail(h, SYMB_ERR_WORKSPACE_TOO_SMALL, "backward needs %zu workspace bytes, got %zu%s", ws_need, ws_bytes,
+                    staged ? " (output buffers overlap input buffers: size the workspace with SYMB_OP_BWD_INPUT_INPLACE)" : "");
     const SplitPlan ksp = gemm_split_plan(bi.T, b->d_in, b->d_out);
-    const bool k_split = wl.tp_bytes && ws && ws_bytes >= wl.total && !dXbase;
+    const bool k_split = wl.tp_bytes && ws && ws_bytes >= wl.total && !dXbase && h->opt_k_split && h->xcd_rule;
     hipStream_t s = (hipStream_t)stream;
     const bool lora = full && bi.n_lora > 0, ia3 = full && bi.n_ia3 > 0;
 
@@ -968,8 +1062,31 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     std::vector<int32_t> lo, hi;
     plan_row_tiles(b, bm, lo, hi);
     std::vector<RowChunk> chunks, all_chunks;
-    if (lora) plan_chunks(b, kSkinnyRows, true, chunks);
-    if (ia3) plan_chunks(b, kSkinnyRows, false, all_chunks);
+    if (lora) plan_chunks(b, kSkinnyRows, SYMB_ADAPTER_LORA, chunks);
+    // Rows of IA3 segments enter the GEMM scaled by l_i: a scaled copy of those rows goes to the
+    // workspace, and the GEMM takes every row from where it lies (per-row base pointers: the copy for
+    // IA3 rows, the caller's dY for the others).  Lane offsets are 32 bits wide, so this needs all those
+    // rows within one 4 GiB window; failing that, all rows are copied and the GEMM reads the copy alone.
+    unsigned char* const wsb0 = (unsigned char*)ws;
+    std::vector<const void*> mix;           // per segment: where the GEMM reads its rows
+    bool ia3_mixed = false;
+    if (ia3) {
+        mix.assign(bi.S, nullptr);
+        uintptr_t lo_a = UINTPTR_MAX, hi_a = 0;
+        for (int i = 0; i < bi.S; ++i) {
+            const size_t n = (size_t)(b->seg_offsets[i + 1] - b->seg_offsets[i]), row_bytes = (size_t)b->d_out * 2;
+            if (!n) continue;
+            const unsigned char* src = b->adapters[i].kind == SYMB_ADAPTER_IA3
+                                           ? wsb0 + wl.sc_off + (size_t)b->seg_offsets[i] * row_bytes
+                                           : (seg_io ? (const unsigned char*)dY_seg[i] : (const unsigned char*)dY + (size_t)b->seg_offsets[i] * row_bytes);
+            mix[i] = src;
+            lo_a = std::min(lo_a, (uintptr_t)src);
+            hi_a = std::max(hi_a, (uintptr_t)src + n * row_bytes);
+        }
+        ia3_mixed = hi_a > lo_a && hi_a - lo_a <= ((uint64_t)1 << 32) - 65536;
+        if (ia3_mixed) g_base = (const void*)lo_a;
+        plan_chunks(b, kSkinnyRows, ia3_mixed ? (int)SYMB_ADAPTER_IA3 : -1, all_chunks);
+    }
     const std::vector<SegDesc> sd = make_segdesc(b);
     unsigned char* wsb = (unsigned char*)ws;
     // Input-major weight: the input gradient is the K-contiguous GEMM (W rows are d_out long),
@@ -1004,6 +1121,10 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     const size_t o_pa = blob.add(pa_off.data(), pa_off.size());
     const size_t o_gs = blob.add(dY_seg, seg_io ? (size_t)bi.S : 0);
     const size_t o_xs = blob.add(dX_seg, seg_io ? (size_t)bi.S : 0);
+    const size_t o_mix = blob.add(mix.data(), ia3_mixed ? mix.size() : 0);
+    std::vector<RowChunk> row_chunks;
+    if (staged) plan_chunks(b, kSkinnyRows, -1, row_chunks);
+    const size_t o_rows = blob.add(row_chunks.data(), row_chunks.size());
     const std::vector<int32_t> k_zero(k_split ? ksp.slots : 0, 0);
     const size_t o_kc = blob.add(k_zero.data(), k_zero.size());   // arrival counters of the K-split tiles
     unsigned char* dev = nullptr;
@@ -1039,7 +1160,7 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     }
     bool a_from_seg = seg_io;
     if (ia3) {
-        a_from_seg = false;
+        a_from_seg = ia3_mixed;
         ScaleParams sc{(const bf16*)dY, (bf16*)(wsb + wl.sc_off), b->d_out, (const RowChunk*)(dev + o_all), (const SegDesc*)(dev + o_seg), KIND_IA3,
                        seg_io ? (const bf16* const*)(dev + o_gs) : nullptr, (const int32_t*)(dev + o_off)};
         hipLaunchKernelGGL(symb_ia3_scale_rows_kernel, dim3((unsigned)all_chunks.size()), dim3(256), 0, s, sc);
@@ -1053,10 +1174,11 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     gp.Cbase = (bf16*)dXbase;
     if (a_from_seg) {
         gp.Aop = nullptr;
-        gp.a_seg = (const bf16* const*)(dev + o_gs);
+        gp.a_seg = (const bf16* const*)(dev + (ia3_mixed ? o_mix : o_gs));
         gp.a_base = (const bf16*)g_base;
     }
-    if (seg_io) gp.c_seg = (bf16* const*)(dev + o_xs);
+    if (seg_io && !staged) gp.c_seg = (bf16* const*)(dev + o_xs);
+    if (staged) gp.C = (bf16*)(wsb + wl.so_off);
     gp.M = bi.T;
     gp.N = b->d_in;
     gp.K = b->d_out;
@@ -1078,7 +1200,13 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     // W [d_out][d_in] is the [K][N] operand of dX = dY W; W [d_in][d_out] gives K-contiguous rows.
     st = conv1d ? launch_gemm<false>(h, gp, s) : launch_gemm<true>(h, gp, s);
     if (st != SYMB_OK) return st;
-    return seal_slot(h, s);
+    if (staged) {
+        ScatterParams sc{(const bf16*)(wsb + wl.so_off), b->d_in, (const RowChunk*)(dev + o_rows), (bf16* const*)(dev + o_xs),
+                         (const int32_t*)(dev + o_off)};
+        hipLaunchKernelGGL(symb_scatter_rows_kernel, dim3((unsigned)row_chunks.size()), dim3(256), 0, s, sc);
+        SYMB_HIP(h, hipGetLastError());
+    }
+    { guard.completed = true; return seal_slot(h, s); }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1109,6 +1237,7 @@ static symb_status adapter_grad_impl(symb_handle h, const symb_batch* b, const v
                                      const void* const* X_seg, const void* const* dY_seg, const void* const* Ybase_seg) {
     symb_status st = check_handle(h);
     if (st != SYMB_OK) return st;
+    CallGuard guard(h);
     if ((st = validate(h, b)) != SYMB_OK) return st;
     if (flags & ~(uint32_t)(SYMB_GRAD_ACCUMULATE | SYMB_GRAD_REUSE_DH | SYMB_GRAD_REUSE_HS))
         return fail(h, SYMB_ERR_INVALID_ARG, "unknown gradient flag %u", flags);
@@ -1171,11 +1300,16 @@ static symb_status adapter_grad_impl(symb_handle h, const symb_batch* b, const v
     const WsLayout wl = ws_layout(b, bi, SYMB_OP_ADAPTER_GRAD, true, any_lora);
     if (wl.total > ws_bytes || (wl.total && !ws))
         return fail(h, SYMB_ERR_WORKSPACE_TOO_SMALL, "adapter_grad needs %zu workspace bytes, got %zu", wl.total, ws_bytes);
-    for (const auto& z : zero_fill) {       // a fill kernel, not a memset node: safe under graph capture
-        hipLaunchKernelGGL(symb_fill_zero_kernel, dim3((unsigned)std::min<size_t>((z.second + 255) / 256, 1024)), dim3(256), 0, s, z.first, z.second);
-        SYMB_HIP(h, hipGetLastError());
-    }
-    if (!any_lora && want_l.empty() && want_lin.empty()) return SYMB_OK;
+    // zeros of the empty segments: fill kernels, not memset nodes (safe under graph capture); enqueued
+    // only once nothing before the launches can fail any more
+    auto fill_zeros = [&]() -> symb_status {
+        for (const auto& z : zero_fill) {
+            hipLaunchKernelGGL(symb_fill_zero_kernel, dim3((unsigned)std::min<size_t>((z.second + 255) / 256, 1024)), dim3(256), 0, s, z.first, z.second);
+            SYMB_HIP(h, hipGetLastError());
+        }
+        return SYMB_OK;
+    };
+    if (!any_lora && want_l.empty() && want_lin.empty()) return fill_zeros();
 
     // Row chunks of the LoRA segments that want a gradient (Hs for dB, dH for dA).
     std::vector<RowChunk> ch_h, ch_dh;
@@ -1231,6 +1365,7 @@ static symb_status adapter_grad_impl(symb_handle h, const symb_batch* b, const v
     const size_t o_ys = blob.add(Ybase_seg, (seg_io && Ybase_seg) ? (size_t)bi.S : 0);
     unsigned char* dev = nullptr;
     if ((st = upload(h, blob, s, &dev)) != SYMB_OK) return st;
+    if ((st = fill_zeros()) != SYMB_OK) return st;
     unsigned char* wsb = (unsigned char*)ws;
     const SegDesc* dseg = (const SegDesc*)(dev + o_seg);
     const int32_t* doff = (const int32_t*)(dev + o_off);
@@ -1298,7 +1433,7 @@ static symb_status adapter_grad_impl(symb_handle h, const symb_batch* b, const v
         hipLaunchKernelGGL(symb_ia3_grad_kernel, dim3((b->d_in + IA3_GRAD_COLS - 1) / IA3_GRAD_COLS, (unsigned)want_lin.size()), dim3(256), 0, s, ip);
         SYMB_HIP(h, hipGetLastError());
     }
-    return seal_slot(h, s);
+    { guard.completed = true; return seal_slot(h, s); }
 }
 
 }  // extern "C"

@@ -269,8 +269,11 @@ CONFIGS = {
 }
 
 
-def sample_rows(off: np.ndarray, per_segment_random: int, tag: str, seed: int = BASE_SEED) -> np.ndarray:
-    """Rows to spot-check: per segment its first two, last two and some seeded random rows."""
+def sample_rows(off: np.ndarray, per_segment_random: int, tag: str, seed: int = BASE_SEED,
+                block: int = 0) -> np.ndarray:
+    """Rows to spot-check: per segment its first two, last two and `per_segment_random` seeded
+    random rows; with `block` > 0 also one seeded row of every run of `block` consecutive rows of
+    the flattened batch (block = 128: both 128-row halves of every 256-row tile are covered)."""
     g = _rng("rows/" + tag, seed)
     rows: List[int] = []
     for i in range(len(off) - 1):
@@ -280,5 +283,9 @@ def sample_rows(off: np.ndarray, per_segment_random: int, tag: str, seed: int = 
         pick = {lo, min(lo + 1, hi - 1), hi - 1, max(hi - 2, lo)}
         if hi - lo > 4 and per_segment_random > 0:
             pick.update(int(x) for x in g.integers(lo, hi, size=per_segment_random))
-        rows.extend(sorted(pick))
-    return np.asarray(rows, dtype=np.int32)
+        rows.extend(pick)
+    T = int(off[-1])
+    if block > 0:
+        for b0 in range(0, T, block):
+            rows.append(int(g.integers(b0, min(T, b0 + block))))
+    return np.asarray(sorted(set(rows)), dtype=np.int32)

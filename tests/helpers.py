@@ -66,32 +66,53 @@ def max_abs_over_rms(got: np.ndarray, ref: np.ndarray) -> float:
     return err / rms if rms > 0 else err
 
 
-# Parity bar: relative Frobenius error per tensor, and max-abs error measured on the
-# tensor scaled to unit RMS.  A bf16 OUTPUT cannot be closer to the exact value than half
-# an ulp of its own format, which is up to 2^-8 of the element's magnitude, so for tensors
-# the library must deliver in bf16 that unavoidable quantisation term is added per element;
-# fp32 outputs (parameter gradients) get the bare bound.
+# Parity bar: relative Frobenius error <= 4e-3 per tensor, and max-abs error <= 2e-2 measured on
+# the tensor scaled to unit RMS (|err| <= 2e-2 * RMS of the oracle tensor), on every element.
+# One exception, for tensors the library must deliver in bf16 and only for elements beyond
+# 5 RMS: there half an ulp of the output format itself (up to 2^-8 of the magnitude) exceeds
+# 2e-2 * RMS, so no bf16 value can meet the bare bound, and the allowance is
+# max(2e-2 * RMS, 2^-8 |ref|).  Below 5 RMS half an ulp is at most 5 * 2^-8 = 1.95e-2 RMS and
+# the bare bound applies.  fp32 outputs (parameter gradients) get the bare bound everywhere.
 REL_FRO_TOL = 4e-3
 MAX_ABS_TOL = 2e-2
 BF16_HALF_ULP = 2.0 ** -8
+TAIL_RMS = 5.0
+
+# (tensor name, elements beyond 5 RMS, of which outside the bare bound) of every bf16 comparison
+# made in this process: the tests that report how often the tail allowance was needed read it.
+tail_log = []
 
 
-def max_abs_excess(got: np.ndarray, ref: np.ndarray, out_bf16: bool) -> float:
-    """max over elements of |err| / allowed, allowed = MAX_ABS_TOL*RMS (+ 2^-8 |ref| for bf16 outputs)."""
+def max_abs_check(got: np.ndarray, ref: np.ndarray, out_bf16: bool):
+    """Returns (bare max|err|/RMS over all elements, worst |err|/allowed, elements beyond 5 RMS,
+    elements that needed the tail allowance)."""
     ref = ref.astype(np.float64)
     if ref.size == 0:
-        return 0.0
+        return 0.0, 0.0, 0, 0
     rms = float(np.sqrt(np.mean(ref * ref)))
-    allowed = MAX_ABS_TOL * rms + (BF16_HALF_ULP * np.abs(ref) if out_bf16 else 0.0)
     err = np.abs(got.astype(np.float64) - ref)
     if rms == 0.0:
-        return 0.0 if not err.any() else float("inf")
-    return float(np.max(err / allowed))
+        bad = float("inf") if err.any() else 0.0
+        return bad, bad, 0, 0
+    allowed = np.full(ref.shape, MAX_ABS_TOL * rms)
+    n_tail = n_used = 0
+    if out_bf16:
+        tail = np.abs(ref) > TAIL_RMS * rms
+        n_tail = int(tail.sum())
+        if n_tail:
+            allowed[tail] = np.maximum(MAX_ABS_TOL * rms, BF16_HALF_ULP * np.abs(ref[tail]))
+            n_used = int((err[tail] > MAX_ABS_TOL * rms).sum())
+    return float(err.max() / rms), float(np.max(err / allowed)), n_tail, n_used
 
 
 def assert_close(got, ref, what="", out_bf16=False):
-    rf, ex = rel_fro(got, ref), max_abs_excess(got, ref, out_bf16)
-    assert rf <= REL_FRO_TOL, f"{what}: relative Frobenius error {rf:.3e} > {REL_FRO_TOL}"
-    assert ex <= 1.0, f"{what}: max-abs error is {ex:.3f} x the allowed {MAX_ABS_TOL} * RMS" + \
-        (" + bf16 half-ulp" if out_bf16 else "")
-    return rf, ex * MAX_ABS_TOL
+    """Asserts the parity bar; returns (relative Frobenius error, bare max|err| / RMS)."""
+    rf = rel_fro(got, ref)
+    bare, worst, n_tail, n_used = max_abs_check(got, ref, out_bf16)
+    if out_bf16:
+        tail_log.append((what, int(np.asarray(ref).size), n_tail, n_used))
+    assert rf <= REL_FRO_TOL, f"{what}: relative Frobenius error {rf:.3e} > {REL_FRO_TOL} (max_abs/RMS {bare:.3e})"
+    assert worst <= 1.0, (f"{what}: max_abs/RMS {bare:.3e}; worst element is {worst:.3f} x its allowance "
+                          f"({MAX_ABS_TOL} * RMS" + (f", or half a bf16 ulp beyond {TAIL_RMS:g} RMS: {n_tail} such elements, "
+                                                     f"{n_used} of them outside the bare bound)" if out_bf16 else ")"))
+    return rf, bare

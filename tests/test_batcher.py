@@ -78,33 +78,87 @@ def test_batches_match_the_reference_on_a_simulated_executor(seed, pol):
     lib_b.close()
 
 
-def test_small_requests_wait_less_than_large_ones():
-    b = bt.Batcher(50.0, 0.5, 800.0, 4096)
-    b.submit(0, 1, 0, 2048, False, 0.0)                 # may wait min(800, 50 + 1024) = 800
-    assert b.next_due(0) == 800.0
-    b.submit(0, 2, 1, 2, True, 100.0)                   # may wait 51: the queue is now due at 151
-    assert b.next_due(0) == 151.0
-    assert b.take(0, 150.0) == ([], [0])
-    ids, off = b.take(0, 151.0)
+class _Library:
+    """The library's queue (layer 0) behind the four calls the hand-computed cases use."""
+    def __init__(self, *policy):
+        self.b = bt.Batcher(*policy)
+    def submit(self, rid, n_tokens, latency_sensitive, arrival_us):
+        self.b.submit(0, rid, 0, n_tokens, latency_sensitive, arrival_us)
+    def next_due(self):
+        return self.b.next_due(0)
+    def take(self, now_us):
+        ids, off = self.b.take(0, now_us)
+        return ids, off
+    def pending(self):
+        return self.b.pending(0)
+    def close(self):
+        self.b.close()
+
+
+class _Reference:
+    """The plain reference behind the same four calls: the hand-computed cases pin it directly."""
+    def __init__(self, *policy):
+        self.b = ReferenceBatcher(*policy)
+    def submit(self, rid, n_tokens, latency_sensitive, arrival_us):
+        self.b.submit(Request(rid, n_tokens, latency_sensitive, arrival_us))
+    def next_due(self):
+        return self.b.next_due()
+    def take(self, now_us):
+        ids, off = self.b.take(now_us)
+        return ids, off
+    def pending(self):
+        return len(self.b.queue), sum(r.n_tokens for r in self.b.queue)
+    def close(self):
+        pass
+
+
+# Expected values below are worked out by hand from the rule as Sec. 3.7 states it (wait grows with the
+# request's size; inference first; a pre-determined cap), not taken from either implementation.
+@pytest.mark.parametrize("impl", [_Reference, _Library])
+def test_small_requests_wait_less_than_large_ones(impl):
+    b = impl(50.0, 0.5, 800.0, 4096)
+    b.submit(1, 2048, False, 0.0)                       # may wait min(800, 50 + 1024) = 800
+    assert b.next_due() == 800.0
+    b.submit(2, 2, True, 100.0)                         # may wait 51: the queue is now due at 151
+    assert b.next_due() == 151.0
+    assert b.take(150.0) == ([], [0])
+    ids, off = b.take(151.0)
     assert ids == [2, 1] and off == [0, 2, 2050]        # both go, the inference request first
-    assert math.isinf(b.next_due(0))
+    assert math.isinf(b.next_due())
     b.close()
 
 
-def test_token_cap_makes_the_queue_due_at_once_and_cuts_the_batch():
-    b = bt.Batcher(1000.0, 0.0, 1000.0, 1000)
-    b.submit(0, 1, 0, 600, False, 0.0)
-    b.submit(0, 2, 0, 600, False, 10.0)                 # 1200 >= cap: due on arrival
-    b.submit(0, 3, 0, 300, True, 20.0)
-    assert b.next_due(0) == 10.0
-    ids, off = b.take(0, 20.0)
+@pytest.mark.parametrize("impl", [_Reference, _Library])
+def test_token_cap_makes_the_queue_due_at_once_and_cuts_the_batch(impl):
+    b = impl(1000.0, 0.0, 1000.0, 1000)
+    b.submit(1, 600, False, 0.0)
+    b.submit(2, 600, False, 10.0)                       # 1200 >= cap: due on arrival
+    b.submit(3, 300, True, 20.0)
+    assert b.next_due() == 10.0
+    ids, off = b.take(20.0)
     assert ids == [3, 1] and off == [0, 300, 900]       # inference first, then what fits; request 2 stays
-    assert b.pending(0) == (1, 600)
-    b.submit(0, 4, 0, 5000, False, 30.0)                # oversized: runs alone when its turn comes
-    ids, off = b.take(0, 2000.0)
+    assert b.pending() == (1, 600)
+    b.submit(4, 5000, False, 30.0)                      # oversized: runs alone when its turn comes
+    ids, off = b.take(2000.0)
     assert ids == [2] and off == [0, 600]
-    ids, off = b.take(0, 2000.0)
+    ids, off = b.take(2000.0)
     assert ids == [4] and off == [0, 5000]
+    b.close()
+
+
+@pytest.mark.parametrize("impl", [_Reference, _Library])
+def test_only_arrived_requests_are_taken_and_the_wait_is_capped(impl):
+    b = impl(10.0, 1.0, 100.0, 10000)
+    b.submit(1, 50, True, 0.0)                          # may wait 10 + 50 = 60
+    b.submit(2, 500, False, 40.0)                       # may wait min(100, 510) = 100: the cap of the allowance
+    b.submit(3, 5, True, 70.0)                          # arrives after the queue is due
+    assert b.next_due() == 60.0
+    ids, off = b.take(60.0)
+    assert ids == [1, 2] and off == [0, 50, 550]        # request 3 has not arrived at t = 60
+    assert b.pending() == (1, 5)
+    assert b.next_due() == 85.0                         # 70 + (10 + 5)
+    assert b.take(84.0) == ([], [0])
+    assert b.take(85.0) == ([3], [0, 5])
     b.close()
 
 

@@ -1,11 +1,21 @@
-"""GPU parity at the full sizes of the five workload configurations, in the launch
-configuration the bench times (same runner, same buffers, same kernels).
+"""GPU parity at the full sizes of the five workload configurations, through the runner,
+buffers, workspace and call sequence the bench times.
 
-The fp64 oracle cannot compute whole tensors at these sizes, so per segment the first
-two rows, the last two rows and a few seeded random rows of Y, Ybase and dX are compared
-element by element, and the parameter gradients of a seeded subset of the segments are
-compared in full.  Same bar as the small cases (see helpers.py).
+Per projection: (1) a forward that also emits the pre-adapter output (the full-epilogue
+instantiation of the GEMM); (2) the forward exactly as the bench launches it -- no bias, no
+pre-adapter output, the whole workspace, so the plain-epilogue instantiation with its last
+round of tiles split over K ranges where the planner splits it; (3) the input gradient;
+(4) the adapter gradients taking Hs and dH from the workspace as in a bench step, and once
+more recomputing them, which must give the same bits.
+
+The fp64 oracle cannot compute whole tensors at these sizes, so rows of Y, Ybase and dX are
+sampled: per segment its first two and last two rows and 28 seeded random rows, plus one
+seeded row of every run of 128 consecutive rows (both wavefront halves of every 256-row
+tile); sampled rows are compared element by element.  The parameter gradients of every
+fine-tuning segment are compared in full.  Same bar as the small cases (helpers.py).
 """
+import time
+
 import numpy as np
 import pytest
 import torch
@@ -19,6 +29,9 @@ pytestmark = pytest.mark.gpu
 sb = None
 layer = None
 _h = None
+
+ROWS_PER_SEGMENT = 28      # seeded random rows per segment, besides its boundary rows
+ROW_BLOCK = 128            # and one row of every 128 consecutive rows of the batch
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -37,7 +50,8 @@ def _f64(t):
     return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
 
 
-def run_projection(wl, pr, rows_per_seg, grad_segments, with_ybase=False):
+def run_projection(wl, pr):
+    t_start = time.time()
     clients = wl.clients
     host_ads = [synth.make_adapter(wl, pr, c) for c in clients]
     segs = [layer.SegmentSpec(c.n_tokens, a.kind, a.rank, a.scale, a.A, a.B, c.finetune)
@@ -52,29 +66,40 @@ def run_projection(wl, pr, rows_per_seg, grad_segments, with_ybase=False):
     tag = f"{wl.name}/{pr.name}"
     print(f"[{tag}] T={run.T} Tb={run.Tb} d_in={pr.d_in} d_out={pr.d_out}", flush=True)
 
-    # ---- forward on every client
+    # ---- (1) forward on every client, pre-adapter output wanted
+    run.Y.fill_(float("nan"))
     run.fwd(s)
     torch.cuda.synchronize()
     oads = [oracle.Adapter(a.kind, a.rank, a.scale, a.A, a.B) for a in host_ads]
-    rows = synth.sample_rows(off, rows_per_seg, tag)
+    rows = synth.sample_rows(off, ROWS_PER_SEGMENT, tag, block=ROW_BLOCK)
     Y0r, Yr = oracle.forward(off, oads, X, W, None, rows=rows)
     ridx = torch.from_numpy(rows.astype(np.int64)).cuda()
     assert_close(_f64(run.Y.index_select(0, ridx)), Yr, f"{tag} Y", out_bf16=True)
     assert_close(_f64(run.Ybase.index_select(0, ridx)), Y0r, f"{tag} Ybase", out_bf16=True)
 
-    # ---- backward on the fine-tuning clients only (a batch of its own)
+    # ---- (2) the forward as the bench launches it: no pre-adapter output, the whole workspace
+    ybase = run.Ybase
+    run.Ybase = None
+    run.Y.fill_(float("nan"))
+    run.fwd(s)
+    torch.cuda.synchronize()
+    run.Ybase = ybase
+    assert_close(_f64(run.Y.index_select(0, ridx)), Yr, f"{tag} Y (as timed)", out_bf16=True)
+
+    # ---- (3) input gradient of the fine-tuning clients only (a batch of its own)
     boads = [oads[i] for i in ft]
     Xb = np.ascontiguousarray(X[np.concatenate([np.arange(off[i], off[i + 1]) for i in ft])]) if len(ft) != len(clients) else X
+    run.dX.fill_(float("nan"))
     run.bwd_input(s)
     torch.cuda.synchronize()
-    brows = synth.sample_rows(boff, rows_per_seg, tag + "/bwd")
+    brows = synth.sample_rows(boff, ROWS_PER_SEGMENT, tag + "/bwd", block=ROW_BLOCK)
     dXr = oracle.backward_input(boff, boads, dY, W, rows=brows)
     bidx = torch.from_numpy(brows.astype(np.int64)).cuda()
     assert_close(_f64(run.dX.index_select(0, bidx)), dXr, f"{tag} dX", out_bf16=True)
 
-    # ---- adapter gradients; the saved base output fed back is the oracle's, rounded to bf16
-    pick = [q for q in grad_segments if q < len(ft)]
-    ia3_rows = [np.arange(boff[q], boff[q + 1]) for q in pick if boads[q].kind == oracle.IA3]
+    # ---- (4) adapter gradients of every fine-tuning segment; the saved base output fed back for
+    # the IA3 gradients is the oracle's, rounded to bf16
+    ia3_rows = [np.arange(boff[q], boff[q + 1]) for q in range(len(ft)) if boads[q].kind == oracle.IA3]
     Y0_saved = None
     if ia3_rows:
         need = np.concatenate(ia3_rows).astype(np.int32)
@@ -82,49 +107,54 @@ def run_projection(wl, pr, rows_per_seg, grad_segments, with_ybase=False):
         Y0_saved = np.zeros((int(boff[-1]), pr.d_out), dtype=np.uint16)
         Y0_saved[need] = synth.f32_to_bf16_bits(Y0n.astype(np.float32))
         run.Ybase_b = layer.bits_to_dev(Y0_saved)
-    elif any(a.kind == oracle.IA3 for a in boads):
-        run.Ybase_b = torch.zeros((run.Tb, pr.d_out), device="cuda", dtype=torch.bfloat16)
-    run.adapter_grad(s)
+    run.adapter_grad(s, reuse_dh=True, reuse_hs=True)        # as in a bench step
     torch.cuda.synchronize()
-    for q in pick:
+    first = [(d.dA.clone() if d.dA is not None else None, d.dB.clone() if d.dB is not None else None) for d in run.bwd_ad]
+    n_grads = 0
+    for q in range(len(ft)):
         a = boads[q]
         d = run.bwd_ad[q]
         if a.kind == oracle.LORA:
             dAr, dBr = oracle.lora_grad(boff, boads, Xb, dY, q)
             assert_close(d.dA.cpu().numpy(), dAr, f"{tag} dA[{q}]")
             assert_close(d.dB.cpu().numpy(), dBr, f"{tag} dB[{q}]")
+            n_grads += 1
         elif a.kind == oracle.IA3:
             cols = np.unique(np.concatenate([[0, 1, pr.d_out - 1], np.random.default_rng(q).integers(0, pr.d_out, 61)])).astype(np.int32)
             dlr = oracle.ia3_grad(boff, boads, Xb, dY, W, None, q, cols=cols, Y0_saved=Y0_saved)
             assert_close(d.dA.cpu().numpy()[cols], dlr, f"{tag} dl[{q}]")
+            n_grads += 1
+    run.adapter_grad(s)                                       # stand-alone: recomputes Hs and dH
+    torch.cuda.synchronize()
+    for (a1, b1), d in zip(first, run.bwd_ad):
+        if a1 is not None:
+            assert torch.equal(a1, d.dA), f"{tag}: dA differs between the reuse and the recompute route"
+        if b1 is not None:
+            assert torch.equal(b1, d.dB), f"{tag}: dB differs between the reuse and the recompute route"
+    print(f"[{tag}] compared {len(rows)} rows of Y/Ybase, {len(brows)} rows of dX, gradients of {n_grads}/{len(ft)} "
+          f"fine-tuning segments in {time.time() - t_start:.1f}s", flush=True)
     del run
     torch.cuda.empty_cache()
-
-
-def _grad_pick(wl, n, seed):
-    ft = [c for c in wl.clients if c.finetune]
-    g = np.random.default_rng(seed)
-    idx = {0, len(ft) - 1}
-    idx.update(int(x) for x in g.integers(0, len(ft), size=n))
-    return sorted(idx)
+    return len(rows), len(brows), n_grads
 
 
 def test_cfg4_gemma27b_headline():
     wl = synth.cfg4_gemma27b()
     for pr in wl.projections:
-        run_projection(wl, pr, rows_per_seg=2, grad_segments=_grad_pick(wl, 1, 4))
+        nr, nb, ng = run_projection(wl, pr)
+        assert nr >= 640 and nb >= 640 and ng == 20
 
 
 def test_cfg2_llama7b():
     wl = synth.cfg2_llama7b()
     for pr in wl.projections:
-        run_projection(wl, pr, rows_per_seg=3, grad_segments=_grad_pick(wl, 1, 2))
+        run_projection(wl, pr)
 
 
 def test_cfg3_granite20b():
     wl = synth.cfg3_granite20b()
     for pr in wl.projections:
-        run_projection(wl, pr, rows_per_seg=2, grad_segments=_grad_pick(wl, 1, 3))
+        run_projection(wl, pr)
 
 
 @pytest.mark.parametrize("any_rank", [False, True])
@@ -132,4 +162,4 @@ def test_cfg5_mixed_serving_and_tuning(any_rank):
     wl = synth.cfg5_mixed(arbitrary_ranks=any_rank)
     projs = wl.projections if not any_rank else [p for p in wl.projections if p.name in ("q", "gate", "down")]
     for pr in projs:
-        run_projection(wl, pr, rows_per_seg=2, grad_segments=_grad_pick(wl, 3, 5))
+        run_projection(wl, pr)

@@ -398,6 +398,57 @@ def test_private_forward_equals_plain_forward_for_every_adapter_kind():
     np.testing.assert_array_equal(oracle.forward_private(off, ads, Xn, p["W"], p["bias"], noise, rows=rows), yp[rows])
 
 
+def test_denoise_with_a_stored_noise_effect():
+    """Steps (2)-(3) of Sec. 3.8 with the noise effect given as the 16-bit tensor the client kept:
+    (a) against an exact rational evaluation written out here (own loop order; per-token, broadcast
+    and absent noise effects, an empty segment, IA3 scaling the bias too, a row subset);
+    (b) when the stored tensor holds the exact effect of the noise, the result is the plain layer
+    output and agrees with the route that recomputes the effect."""
+    rng = np.random.default_rng(44)
+    d_in, d_out = 6, 4
+    off = np.array([0, 3, 3, 5, 9], dtype=np.int32)
+    l = grid_bits(rng, (d_out,), 4, 12)
+    ads = [oracle.Adapter(), oracle.Adapter(), oracle.Adapter(oracle.IA3, 0, 0.0, l), oracle.Adapter()]
+    Xn = grid_bits(rng, (9, d_in), -6, 6)
+    W, b = grid_bits(rng, (d_out, d_in), -4, 4), grid_bits(rng, (d_out,))
+    neff = [synth.f32_to_bf16_bits(rng.standard_normal((3, d_out)).astype(np.float32)), None,
+            synth.f32_to_bf16_bits(rng.standard_normal((1, d_out)).astype(np.float32)), None]
+    got = oracle.forward_denoise(off, ads, Xn, W, b, neff)
+    F = lambda bits: [[Fraction(float(v)) for v in row] for row in np.atleast_2d(f64(bits))]
+    xf, wf, bf_, lf = F(Xn), F(W), F(b)[0], F(l)[0]
+    for j in range(d_out):
+        for t in range(9):
+            seg = 0 if t < 3 else 2 if t < 5 else 3
+            y = bf_[j]
+            for k in range(d_in):
+                y += wf[j][k] * xf[t][k]
+            if seg == 2:
+                y *= lf[j]
+            if neff[seg] is not None:
+                y -= F(neff[seg])[0 if neff[seg].shape[0] == 1 else t - int(off[seg])][j]
+            assert Fraction(float(got[t, j])) == y, (t, j)
+    rows = np.array([8, 0, 4], dtype=np.int32)
+    np.testing.assert_array_equal(oracle.forward_denoise(off, ads, Xn, W, b, neff, rows=rows), got[rows])
+    with pytest.raises(ValueError):
+        oracle.forward_denoise(off, ads, Xn, W, b, [np.zeros((2, d_out), np.uint16), None, None, None])
+    # (b) small grids: n W^T is exactly representable in bf16, so storing it loses nothing
+    X = grid_bits(rng, (9, d_in), -3, 3)
+    noise = [grid_bits(rng, (3, d_in), -3, 3), None, grid_bits(rng, (1, d_in), -3, 3), None]
+    Xn2 = oracle.noise_add(off, X, noise)
+    stored = []
+    for i, n in enumerate(noise):
+        if n is None:
+            stored.append(None)
+            continue
+        noff = np.array([0, n.shape[0]], dtype=np.int32)
+        _, e = oracle.forward(noff, [ads[i]], n, W, None)
+        stored.append(bits_of(e))                      # asserts exact representability
+    _, y = oracle.forward(off, ads, X, W, b)
+    yd = oracle.forward_denoise(off, ads, Xn2, W, b, stored)
+    np.testing.assert_array_equal(yd, y)
+    np.testing.assert_array_equal(yd, oracle.forward_private(off, ads, Xn2, W, b, noise))
+
+
 # ---------------------------------------------------------------------------
 # P9: adapter-index probe with exactly representable values
 # ---------------------------------------------------------------------------
