@@ -285,6 +285,22 @@ symb_status symb_debug_gemm_timing_read(symb_handle h, int32_t variant, double* 
                                         int64_t* launches, double* flops_total);
 
 /*
+ * For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): symb_base_linear_fwd with its workspace inside the
+ * library, in a file-scope device array of SYMB_STATIC_SCRATCH_BYTES that every GPU the library
+ * runs on holds until the process ends.  Same arguments otherwise, same kernels, same results as
+ * symb_base_linear_fwd given a workspace of that size.  The call allocates nothing and frees
+ * nothing.  A batch whose mandatory workspace (symb_workspace_bytes minus the optional region of
+ * K-split partial tiles) exceeds the array fails with SYMB_ERR_WORKSPACE_TOO_SMALL before anything
+ * is enqueued.  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ * (different streams, different handles) race; keep them on one stream.  Nothing in the array has
+ * to start at zero (every region is written before it is read within the call).
+ */
+enum { SYMB_STATIC_SCRATCH_BYTES = 32 << 20 };
+symb_status symb_base_linear_fwd_static(symb_handle h, const symb_batch* b, const void* X, const void* W,
+                                        const void* bias, void* Y, void* Ybase, void* stream);
+
+/*
  * Measurement switches (not part of the method), per handle, all on by default; value 0 turns one
  * off.  symb_workspace_bytes does not depend on them.
  *   SYMB_OPT_DESCRIPTOR_REUSE    a call whose descriptor bytes are already on the device reads them in

@@ -20,6 +20,7 @@ SYMB_OK, SYMB_ERR_INVALID_ARG, SYMB_ERR_BAD_SEGMENTS, SYMB_ERR_UNSUPPORTED, \
 SYMB_ADAPTER_NONE, SYMB_ADAPTER_LORA, SYMB_ADAPTER_IA3, SYMB_ADAPTER_IA3_IN = range(4)
 SYMB_OP_FWD, SYMB_OP_BWD_INPUT, SYMB_OP_ADAPTER_GRAD, SYMB_OP_FWD_INPLACE, SYMB_OP_BWD_INPUT_INPLACE = range(5)
 SYMB_OPT_DESCRIPTOR_REUSE, SYMB_OPT_K_SPLIT, SYMB_OPT_SMALL_BATCH_KERNELS, SYMB_OPT_SKINNY_DEEP = range(4)
+SYMB_STATIC_SCRATCH_BYTES = 32 << 20
 SYMB_BWD_FULL, SYMB_BWD_BASE_ONLY = 0, 1
 SYMB_GRAD_OVERWRITE, SYMB_GRAD_ACCUMULATE, SYMB_GRAD_REUSE_DH, SYMB_GRAD_REUSE_HS = 0, 1, 2, 4
 SYMB_MAX_RANK = 128
@@ -34,7 +35,7 @@ EXPORTS = ("symb_create", "symb_destroy", "symb_validate_batch", "symb_debug_row
            "symb_batcher_create", "symb_batcher_destroy", "symb_batcher_submit", "symb_batcher_pending",
            "symb_batcher_next_due", "symb_batcher_take",
            "symb_debug_gemm_timing_enable", "symb_debug_gemm_timing_read", "symb_debug_descriptor_stats",
-           "symb_debug_set_option", "symb_debug_xcd_rule")
+           "symb_debug_set_option", "symb_debug_xcd_rule", "symb_base_linear_fwd_static")
 
 
 class symb_adapter(C.Structure):
@@ -93,6 +94,7 @@ def lib() -> C.CDLL:
         l.symb_debug_descriptor_stats.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         l.symb_debug_set_option.argtypes = [vp, i32, i32]
         l.symb_debug_xcd_rule.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
+        l.symb_base_linear_fwd_static.argtypes = [vp, bp, vp, vp, vp, vp, vp, vp]
         l.symb_status_string.argtypes = [C.c_int]
         l.symb_status_string.restype = C.c_char_p
         l.symb_last_error.argtypes = [vp]
@@ -204,6 +206,11 @@ def symb_base_linear_fwd(handle, batch: Batch, X, W, bias, Y, Ybase=None, ws=Non
     wp, wb = _ws_args(ws)
     _check(lib().symb_base_linear_fwd(handle, batch.ref(), _ptr(X), _ptr(W), _ptr(bias), _ptr(Y), _ptr(Ybase),
                                       wp, wb, stream or None), handle)
+
+
+def symb_base_linear_fwd_static(handle, batch: Batch, X, W, bias, Y, Ybase=None, stream: int = 0) -> None:
+    _check(lib().symb_base_linear_fwd_static(handle, batch.ref(), _ptr(X), _ptr(W), _ptr(bias), _ptr(Y), _ptr(Ybase),
+                                             stream or None), handle)
 
 
 def _noise_array(batch: Batch, noise: Sequence):

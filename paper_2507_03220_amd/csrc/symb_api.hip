@@ -20,6 +20,11 @@
 
 using namespace symb;
 
+// Workspace of symb_base_linear_fwd_static: a file-scope array, so that entry point needs no device
+// allocation at all.  In host code this name is only a stand-in for the symbol; the address
+// of each device's copy is asked for once, in symb_create (hipGetSymbolAddress), and kept in the context.
+static __device__ __align__(256) unsigned char symb_static_scratch[SYMB_STATIC_SCRATCH_BYTES];
+
 // One workgroup per entry of `out`: the id of the XCD (hardware register XCC_ID) the workgroup runs on.
 __global__ void symb_xcc_probe_kernel(int* out) {
     if (threadIdx.x == 0) {
@@ -66,6 +71,7 @@ struct symb_context {
     // the GEMM keeps all parts of a tile on one XCD (behind one L2) and is used only if this holds.
     bool xcd_rule = false;
     int xcc_of_residue[8] = {-1, -1, -1, -1, -1, -1, -1, -1};
+    unsigned char* static_scratch = nullptr;     // this device's copy of the file-scope scratch array
     std::vector<const void*> lds_attr_set;       // kernels whose dynamic-LDS limit was raised on this context's device
     // measurement hook: event pairs around GEMM launches
     bool timing = false;
@@ -607,6 +613,14 @@ symb_status symb_create(symb_handle* out, int device) {
         c->xcd_rule = ok;
         for (int r = 0; r < 8; ++r) c->xcc_of_residue[r] = xcc[r];
     }
+    {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(symb_static_scratch)) != hipSuccess || !p) {
+            symb_destroy(c);
+            return fail(nullptr, SYMB_ERR_DEVICE, "hipGetSymbolAddress(symb_static_scratch) failed");
+        }
+        c->static_scratch = static_cast<unsigned char*>(p);
+    }
     *out = c;
     return SYMB_OK;
 }
@@ -957,6 +971,22 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
 symb_status symb_base_linear_fwd(symb_handle h, const symb_batch* b, const void* X, const void* W, const void* bias,
                                  void* Y, void* Ybase, void* ws, size_t ws_bytes, void* stream) {
     return forward_impl(h, b, X, W, bias, nullptr, Y, Ybase, ws, ws_bytes, stream);
+}
+
+// The forward with its workspace in the file-scope scratch array of this device: no device allocation
+// by the library or the caller.  Same kernels and launches as symb_base_linear_fwd.
+symb_status symb_base_linear_fwd_static(symb_handle h, const symb_batch* b, const void* X, const void* W, const void* bias,
+                                        void* Y, void* Ybase, void* stream) {
+    symb_status st = check_handle(h);
+    if (st != SYMB_OK) return st;
+    if ((st = validate(h, b)) != SYMB_OK) return st;
+    const BatchInfo bi = inspect(b);
+    const WsLayout wl = ws_layout(b, bi, SYMB_OP_FWD, true, false);
+    const size_t need = wl.tp_bytes ? wl.tp_off : wl.total;        // the partial tiles of a K-split are used only if they fit too
+    if (need > (size_t)SYMB_STATIC_SCRATCH_BYTES)
+        return fail(h, SYMB_ERR_WORKSPACE_TOO_SMALL, "this batch needs %zu bytes of workspace; the static scratch array holds %zu "
+                    "(use symb_base_linear_fwd with a workspace of the caller's)", need, (size_t)SYMB_STATIC_SCRATCH_BYTES);
+    return forward_impl(h, b, X, W, bias, nullptr, Y, Ybase, h->static_scratch, (size_t)SYMB_STATIC_SCRATCH_BYTES, stream);
 }
 
 symb_status symb_base_linear_fwd_seg(symb_handle h, const symb_batch* b, const void* const* X_seg, const void* W,
