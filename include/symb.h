@@ -166,7 +166,8 @@ symb_status symb_workspace_bytes(const symb_batch* b, int32_t op, size_t* out);
  *   X [T][d_in] bf16 DEVICE, W [d_out][d_in] bf16 DEVICE (nn.Linear layout),
  *   bias [d_out] bf16 DEVICE or NULL, Y [T][d_out] bf16 DEVICE (written),
  *   Ybase [T][d_out] bf16 DEVICE or NULL: if given, receives Y0 (the pre-adapter
- *   output the paper's executor would have returned; needed later for IA3 dl).
+ *   output the paper's executor would have returned; needed later for IA3 dl).  Rows of
+ *   IA3_IN segments hold (l * x) W^T + bias there: their input is scaled before the layer.
  *   ws: DEVICE workspace of at least symb_workspace_bytes(.., SYMB_OP_FWD, ..) bytes.
  */
 symb_status symb_base_linear_fwd(symb_handle h, const symb_batch* b, const void* X, const void* W,

@@ -301,26 +301,97 @@ symb_skinny_kernel(const SkinnyParams p) {
     }
 }
 
+// Transposing LDS read of an MFMA fragment whose k axis runs down the rows of a column-contiguous tile.
+__device__ __forceinline__ bf16x8 lds_read_tr_16x32(const unsigned char* base, int pitch_bytes, int col0, int lane) {
+    // tile [32 t][cols] (column-contiguous); returns for lane l: column col0 + (l & 15), t = 8*(l >> 4) + 0..7
+    const int g = lane >> 4, jj = lane & 15;
+    const unsigned char* p0 = base + (g * 8 + (jj >> 2)) * pitch_bytes + (col0 + ((jj & 3) << 2)) * 2;
+    typedef __attribute__((address_space(3))) shortx4 lds_s4;
+    shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(p0));
+    shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(p0 + 4 * pitch_bytes));
+    typedef __attribute__((__vector_size__(8 * sizeof(short)))) short shortx8;
+    shortx8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
 // -------------------------------------------------------------------------------------------
-// Forward for a batch of at most 16 RB rows (a handful of decode steps, Sec. 4's inference clients;
-// the library uses RB = 1: beyond 16 rows the tiled kernel with its K-split is faster):
-//   Y[t][n] = sum_k X[t][k] W[n][k] (+ b[n]) (+ sum_p Hs[t][p] B_i[n][p])  (* l_i[n])
-// With so few rows a tiled GEMM launches too few workgroups to stream W at HBM speed.  Here a
-// workgroup owns 32 output columns: it streams those 32 rows of W once (the 4 wavefronts split K;
-// through LDS, like the skinny kernel's rows), multiplies them with all rows of X (from L2) and finishes each (row, column) pair with its row's
-// own adapter.  Same arithmetic as the tiled path: fp32 accumulation, Hs as value + residual, one
-// rounding.  RB = row blocks of 16 (T <= 16 RB).
+// Calls of at most 16 rows (decode steps of inference clients, the input gradient of a short
+// fine-tuning segment; Sec. 3.6 / 3.7: such requests interleave with the large ones per layer).
+// A tiled GEMM launches too few workgroups for so few rows to stream the weight at HBM speed, so
+// these calls take kernels of their own that read the weight exactly once:
+//   C[t][n] = sum_k A[t][k] * Wop[n][k]   (the weight read K-contiguous: symb_rowgemv_kernel)
+//   C[t][n] = sum_k A[t][k] * Wop[k][n]   (the weight read N-contiguous: symb_colgemv_kernel,
+//                                          partial sums over K ranges, symb_small_finish_kernel)
+// A is flat [T][K] (per-client buffers and rows that need a scale are gathered into the workspace
+// first: a few KiB).  Every (row, column) result is finished with its row's own adapter by
+// small_epilogue: same arithmetic as the tiled path (fp32 accumulation, Hs / dH as value +
+// residual, one rounding to bf16).
 // -------------------------------------------------------------------------------------------
+struct SmallEpilogue {
+    bf16* C;                  // [T][N] flat, or null with c_seg
+    bf16* Cbase;              // [T][N] or null: the value (+ bias) before the adapter term
+    bf16* const* c_seg;       // device [S] or null: row t of segment i goes to c_seg[i] + (t - off[i]) * N
+    const bf16* bias;         // [N] or null
+    int N, T, S;
+    const int32_t* off;       // device [S+1]
+    const SegDesc* seg;       // device [S]
+    const bf16* ext;          // [T][ext_pitch]: Hs (forward) or dH (input gradient); null = no LoRA term
+    int ext_pitch;
+    int backward;             // 0: forward (+ Hs B_i[n][.], * IA3 l[n], - noise effect); 1: input gradient (+ dH A_i[.][n], * IA3_IN l[n])
+    int lora_term;            // 0: no LoRA term at all (base-only input gradient)
+    const NoiseDesc* neff;    // device [S] or null (forward only)
+};
+
+// Finishes C[t][n] from its fp32 sum v; s = the row's segment.
+__device__ __forceinline__ void small_epilogue(const SmallEpilogue& e, int t, int n, int s, float v) {
+    if (e.bias) v += bf16_bits_to_f32(reinterpret_cast<const unsigned short*>(e.bias)[n]);
+    if (e.Cbase) reinterpret_cast<unsigned short*>(e.Cbase)[(size_t)t * e.N + n] = (unsigned short)(pack2_bf16(v, 0.f) & 0xffffu);
+    const SegDesc sd = e.seg[s];
+    if (sd.kind == KIND_LORA && e.lora_term) {
+        const unsigned short* hrow = reinterpret_cast<const unsigned short*>(e.ext) + (size_t)t * e.ext_pitch;
+        float u = 0.f;
+        if (!e.backward) {
+            const unsigned short* brow = reinterpret_cast<const unsigned short*>(sd.B) + (size_t)n * sd.rank;
+            for (int q = 0; q < sd.rank; ++q)
+                u += (bf16_bits_to_f32(hrow[q]) + bf16_bits_to_f32(hrow[sd.rpad + q])) * bf16_bits_to_f32(brow[q]);
+        } else {
+            const unsigned short* acol = reinterpret_cast<const unsigned short*>(sd.A) + n;
+            for (int q = 0; q < sd.rank; ++q)
+                u += (bf16_bits_to_f32(hrow[q]) + bf16_bits_to_f32(hrow[sd.rpad + q])) * bf16_bits_to_f32(acol[(size_t)q * e.N]);
+        }
+        v += u;
+    } else if (sd.kind == (e.backward ? KIND_IA3_IN : KIND_IA3) && (e.lora_term || !e.backward)) {
+        v *= bf16_bits_to_f32(reinterpret_cast<const unsigned short*>(sd.A)[n]);
+    }
+    if (e.neff) {
+        const NoiseDesc nd = e.neff[s];
+        if (nd.ptr) v -= bf16_bits_to_f32(reinterpret_cast<const unsigned short*>(nd.ptr)[(size_t)(nd.rows == 1 ? 0 : t - e.off[s]) * e.N + n]);
+    }
+    unsigned short* out = e.c_seg ? reinterpret_cast<unsigned short*>(e.c_seg[s]) + (size_t)(t - e.off[s]) * e.N
+                                  : reinterpret_cast<unsigned short*>(e.C) + (size_t)t * e.N;
+    out[n] = (unsigned short)(pack2_bf16(v, 0.f) & 0xffffu);
+}
+
+// Segment of each of the (at most 16 RB) rows, into LDS.
+__device__ __forceinline__ void small_row_segments(const SmallEpilogue& e, int* srow, int nrows_max) {
+    if ((int)threadIdx.x < nrows_max) {
+        int s = 0;
+        if ((int)threadIdx.x < e.T) {
+            while (s + 1 < e.S && (int)threadIdx.x >= e.off[s + 1]) ++s;
+        }
+        srow[threadIdx.x] = s;
+    }
+}
+
+// ---- weight read K-contiguous.  A workgroup owns 32 output columns: it streams those 32 rows of the
+// weight once (the 4 wavefronts split K; through LDS, like the skinny kernel's rows) and multiplies them
+// with all rows of A (from L2).  RB = row blocks of 16 (T <= 16 RB; the library uses RB = 1: beyond 16
+// rows the tiled kernel with its K-split is faster).
 struct RowGemvParams {
     const bf16* W;            // [N][K]
     const bf16* X;            // [T][K]
-    bf16* Y;                  // [T][N]
-    const bf16* bias;         // [N] or null
-    int K, N, T, S;
-    const int32_t* off;       // device [S+1]
-    const SegDesc* seg;       // device [S]
-    const bf16* Hs;           // [T][hs_pitch] or null (no LoRA segment)
-    int hs_pitch;
+    int K;
+    SmallEpilogue epi;
 };
 
 template <int RB>
@@ -332,23 +403,20 @@ symb_rowgemv_kernel(const RowGemvParams p) {
     __shared__ float red[3][SKINNY_ROWS][RB * 16 + 4];   // partial sums of wavefronts 1..3; red[0] then holds the totals
     __shared__ int srow[RB * 16];                        // segment of each row
     static_assert(SKINNY_BLKS == 2, "a workgroup owns 32 columns");
+    const int N = p.epi.N, T = p.epi.T;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int trow = lane & 15, kq = lane >> 4;
     const int n0 = blockIdx.x * SKINNY_ROWS;
-    if (tid < RB * 16) {
-        int s = 0;
-        if (tid < p.T) while (s + 1 < p.S && tid >= p.off[s + 1]) ++s;
-        srow[tid] = s;
-    }
+    small_row_segments(p.epi, srow, RB * 16);
     // columns past N are clamped onto the last one; their results are never stored
     const bf16* lrow[SKINNY_BLKS];
 #pragma unroll
-    for (int b = 0; b < SKINNY_BLKS; ++b) lrow[b] = p.W + (size_t)min(n0 + b * 16 + trow, p.N - 1) * p.K + kq * 8;
+    for (int b = 0; b < SKINNY_BLKS; ++b) lrow[b] = p.W + (size_t)min(n0 + b * 16 + trow, N - 1) * p.K + kq * 8;
     const bf16* rrow[RB];
     bool r_ok[RB];
 #pragma unroll
     for (int j = 0; j < RB; ++j) {
-        r_ok[j] = (j * 16 + trow) < p.T;
+        r_ok[j] = (j * 16 + trow) < T;
         rrow[j] = p.X + (size_t)(r_ok[j] ? (j * 16 + trow) : 0) * p.K + kq * 8;
     }
     floatx4 acc[SKINNY_BLKS][RB];
@@ -360,9 +428,9 @@ symb_rowgemv_kernel(const RowGemvParams p) {
 #pragma unroll
     for (int i = 0; i < ST::DPS; ++i) {
         const int r = i * ST::RPI + lane / ST::LPR;
-        src[i] = p.W + (size_t)min(n0 + r, p.N - 1) * p.K + (((lane % ST::LPR) ^ ST::swz(r)) * 8);
+        src[i] = p.W + (size_t)min(n0 + r, N - 1) * p.K + (((lane % ST::LPR) ^ ST::swz(r)) * 8);
     }
-    skinny_stream<RB, RB, ST>(lrow, rrow, r_ok, src, p.X, p.T, stage + wave * ST::WAVE_BYTES, p.K, wave, lane, acc);
+    skinny_stream<RB, RB, ST>(lrow, rrow, r_ok, src, p.X, T, stage + wave * ST::WAVE_BYTES, p.K, wave, lane, acc);
     // lane holds dot(W row n0 + b*16 + trow, X row j*16 + 4*kq + q) over its wavefront's share of K
     if (wave > 0) {
 #pragma unroll
@@ -386,24 +454,118 @@ symb_rowgemv_kernel(const RowGemvParams p) {
     }
     __syncthreads();
     // every thread finishes (row, column) pairs: column fastest, so a row's 32 outputs are one 64-byte store run
-    for (int e = tid; e < p.T * SKINNY_ROWS; e += 256) {
+    for (int e = tid; e < T * SKINNY_ROWS; e += 256) {
         const int t = e / SKINNY_ROWS, c = e % SKINNY_ROWS, n = n0 + c;
-        if (n >= p.N) continue;
-        float v = red[0][c][t];
-        if (p.bias) v += bf16_bits_to_f32(reinterpret_cast<const unsigned short*>(p.bias)[n]);
-        const SegDesc sd = p.seg[srow[t]];
-        if (sd.kind == KIND_LORA) {
-            const unsigned short* hrow = reinterpret_cast<const unsigned short*>(p.Hs) + (size_t)t * p.hs_pitch;
-            const unsigned short* brow = reinterpret_cast<const unsigned short*>(sd.B) + (size_t)n * sd.rank;
-            float u = 0.f;
-            for (int q = 0; q < sd.rank; ++q)
-                u += (bf16_bits_to_f32(hrow[q]) + bf16_bits_to_f32(hrow[sd.rpad + q])) * bf16_bits_to_f32(brow[q]);
-            v += u;
-        } else if (sd.kind == KIND_IA3) {
-            v *= bf16_bits_to_f32(reinterpret_cast<const unsigned short*>(sd.A)[n]);
-        }
-        reinterpret_cast<unsigned short*>(p.Y)[(size_t)t * p.N + n] = (unsigned short)(pack2_bf16(v, 0.f) & 0xffffu);
+        if (n < N) small_epilogue(p.epi, t, n, srow[t], red[0][c][t]);
     }
+}
+
+// ---- weight read N-contiguous (the input gradient through an nn.Linear weight, the forward through
+// a Conv1D weight).  A workgroup owns COLGEMV_CT columns and one K range: it streams its
+// [K range][CT] block of the weight once, 32 k-rows per step through LDS (three register sets: the
+// rows of step s + 2 are requested while step s multiplies), reads the weight fragments with the
+// transposing LDS load and the A fragments (at most 16 rows, from L2) straight from global memory,
+// and leaves a [T][CT] fp32 partial sum per K range; symb_small_finish_kernel adds the ranges up in
+// order and runs the epilogue.  grid = (ceil(N / CT), K ranges).
+constexpr int COLGEMV_CT = 128;
+struct ColGemvParams {
+    const bf16* W;            // [K][N]
+    const bf16* A;            // [T][K]
+    float* partial;           // [ranges][16][N] fp32 (rows >= T never read back)
+    int K, N, T;
+    int k_per_range;          // a multiple of 32
+};
+__global__ void __launch_bounds__(256)
+symb_colgemv_kernel(const ColGemvParams p) {
+    constexpr int CT = COLGEMV_CT, NI = CT / 64, TT = 32;
+    constexpr int RPITCH = CT * 2 + 16, LPRW = CT / 8, NRC = TT * LPRW / 256;
+    __shared__ __attribute__((aligned(16))) unsigned char sW[TT * RPITCH];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c0 = blockIdx.x * CT;
+    const int k_lo = blockIdx.y * p.k_per_range, k_hi = min(p.K, k_lo + p.k_per_range);
+    floatx4 acc[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    struct Stage { u32x4 w[NRC]; u32x4 a; };
+    const bool col_ok = (c0 + (tid % LPRW) * 8) < p.N;
+    const int arow = lane & 15, akq = lane >> 4;         // this lane's A fragment: row arow, k = 8 akq .. + 7 of the step
+    // every load is unconditional (clamped onto valid addresses) and zeroed when it is used: see symb_lora_grad_kernel
+    auto fetch = [&](Stage& sg, int k0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NRC; ++i) {
+            const int c = tid + i * 256, kr = c / LPRW, cc = c % LPRW;
+            sg.w[i] = ld_glb16(p.W + (size_t)min(k0 + kr, p.K - 1) * p.N + c0 + (col_ok ? cc * 8 : 0));
+        }
+        sg.a = ld_glb16(p.A + (size_t)min(arow, p.T - 1) * p.K + min(k0 + akq * 8, p.K - 8));
+    };
+    auto put = [&](const Stage& sg, int k0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NRC; ++i) {
+            const int c = tid + i * 256, kr = c / LPRW, cc = c % LPRW;
+            const bool ok = (k0 + kr) < k_hi && col_ok;
+            *reinterpret_cast<u32x4*>(sW + kr * RPITCH + cc * 16) = ok ? sg.w[i] : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    auto multiply = [&](const Stage& sg, int k0) __attribute__((always_inline)) {
+        const bool a_ok = arow < p.T && (k0 + akq * 8) < k_hi;          // K and the ranges are multiples of 8
+        const bf16x8 af = __builtin_bit_cast(bf16x8, a_ok ? sg.a : u32x4{0u, 0u, 0u, 0u});
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const bf16x8 wf = lds_read_tr_16x32(sW, RPITCH, wave * (NI * 16) + i * 16, lane);
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, af, acc[i], 0, 0, 0);
+        }
+    };
+    if (k_lo < k_hi) {
+        Stage sg0, sg1, sg2;
+        fetch(sg0, k_lo);
+        fetch(sg1, k_lo + TT);
+        auto step = [&](Stage& cur, Stage& nxt, int k0) __attribute__((always_inline)) {
+            __syncthreads();
+            put(cur, k0);
+            __syncthreads();
+            fetch(nxt, k0 + 2 * TT);
+            multiply(cur, k0);
+        };
+        for (int k0 = k_lo; k0 < k_hi; k0 += 3 * TT) {
+            step(sg0, sg2, k0);
+            if (k0 + TT < k_hi) step(sg1, sg0, k0 + TT);
+            if (k0 + 2 * TT < k_hi) step(sg2, sg1, k0 + 2 * TT);
+        }
+    }
+    // lane holds C[t = lane & 15][n = c0 + wave * NI * 16 + i * 16 + 4 (lane >> 4) + q]
+    float* const out = p.partial + ((size_t)blockIdx.y * 16 + (lane & 15)) * p.N;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int n = c0 + wave * (NI * 16) + i * 16 + ((lane >> 4) << 2);
+        if (n < p.N && (lane & 15) < p.T)
+            *reinterpret_cast<float4*>(out + n) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+    }
+}
+
+// Adds the K ranges of symb_colgemv_kernel up in order and finishes every (row, column) pair.
+struct SmallFinishParams {
+    const float* partial;     // [ranges][16][N]
+    int ranges;
+    SmallEpilogue epi;
+};
+__global__ void __launch_bounds__(256)
+symb_small_finish_kernel(const SmallFinishParams p) {
+    // grid = (column blocks of 256, rows): one (row, column) pair per thread, the ranges four at a time
+    const int n = blockIdx.x * 256 + threadIdx.x, t = blockIdx.y;
+    if (n >= p.epi.N) return;
+    int s = 0;
+    while (s + 1 < p.epi.S && t >= p.epi.off[s + 1]) ++s;
+    const float* src = p.partial + (size_t)t * p.epi.N + n;
+    const size_t stride = (size_t)16 * p.epi.N;
+    float v = 0.f;
+    int r = 0;
+    for (; r + 4 <= p.ranges; r += 4) {
+        const float a0 = src[(size_t)r * stride], a1 = src[(size_t)(r + 1) * stride], a2 = src[(size_t)(r + 2) * stride],
+                    a3 = src[(size_t)(r + 3) * stride];
+        v = (((v + a0) + a1) + a2) + a3;
+    }
+    for (; r < p.ranges; ++r) v += src[(size_t)r * stride];
+    small_epilogue(p.epi, t, n, s, v);
 }
 
 // Packs B_i [d_out][r] into B_i^T [rpad][d_out] (zero rows beyond r) so the backward
@@ -478,18 +640,6 @@ struct GradParams {
 
 template <int RB> constexpr int GRAD_CT = RB <= 2 ? 256 : 128;   // columns per workgroup (512-byte row pieces where the registers allow)
 constexpr int GRAD_TT = 32;        // tokens per step
-
-__device__ __forceinline__ bf16x8 lds_read_tr_16x32(const unsigned char* base, int pitch_bytes, int col0, int lane) {
-    // tile [32 t][cols] (column-contiguous); returns for lane l: column col0 + (l & 15), t = 8*(l >> 4) + 0..7
-    const int g = lane >> 4, jj = lane & 15;
-    const unsigned char* p0 = base + (g * 8 + (jj >> 2)) * pitch_bytes + (col0 + ((jj & 3) << 2)) * 2;
-    typedef __attribute__((address_space(3))) shortx4 lds_s4;
-    shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(p0));
-    shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(p0 + 4 * pitch_bytes));
-    typedef __attribute__((__vector_size__(8 * sizeof(short)))) short shortx8;
-    shortx8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, v);
-}
 
 template <int RB, bool CMAJOR>
 __global__ void __launch_bounds__(256)

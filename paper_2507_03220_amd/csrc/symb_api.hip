@@ -67,6 +67,7 @@ struct symb_context {
     std::string error;
     // measurement switches (symb_debug_set_option); all on by default
     bool opt_desc_reuse = true, opt_k_split = true, opt_small_rows = true, opt_skinny_deep = true;
+    int opt_experiment = 0;
     // Whether workgroup id mod 8 names the XCD a workgroup runs on, measured at creation: the K-split of
     // the GEMM keeps all parts of a tile on one XCD (behind one L2) and is used only if this holds.
     bool xcd_rule = false;
@@ -302,9 +303,27 @@ struct WsLayout {
     size_t pa_off = 0, pa_bytes = 0;      // packed A^T (input-major weight, input gradient only)
     size_t so_off = 0, so_bytes = 0;      // flat output [T][width] bf16 of a per-segment call whose outputs overlap its inputs
     size_t gr_off = 0, gr_bytes = 0;      // fp32 runs of the LoRA gradients of split segments (see grad_split)
-    size_t tp_off = 0, tp_bytes = 0;      // fp32 partial tiles of a K-split GEMM (see gemm_split_plan); last, optional
+    // optional regions (a workspace that ends before them makes the call take the tiled kernel, unsplit):
+    size_t sg_off = 0, sg_bytes = 0;      // calls of at most 16 rows: flat copy of the activation rows [T][K] (gathered / scaled)
+    size_t sp_off = 0, sp_bytes = 0;      // calls of at most 16 rows, weight read N-contiguous: fp32 partial sums per K range
+    size_t tp_off = 0, tp_bytes = 0;      // fp32 partial tiles of a K-split GEMM (see gemm_split_plan); last
+    size_t mandatory = 0;                 // end of the regions a call cannot do without
     size_t total = 0;
 };
+
+// K ranges of the small-batch kernel that reads the weight N-contiguous: enough workgroups to fill the
+// chip (about 512 with the column blocks), at least 128 k per range, at most 8 MiB of partial sums
+// (they are written and read back once: traffic beside the weight's own bytes).
+constexpr int kSmallRows = 16;
+int small_k_ranges(int K, int N) {
+    const int nblk = (N + COLGEMV_CT - 1) / COLGEMV_CT;
+    const long cap = std::max<long>(1, ((long)8 << 20) / ((long)kSmallRows * N * 4));
+    return (int)std::max<long>(1, std::min<long>({(512 + nblk - 1) / nblk, (long)K / 128, cap}));
+}
+int small_k_per_range(int K, int N) {
+    const int r = small_k_ranges(K, N);
+    return (int)align_up((size_t)(K + r - 1) / r, 32);
+}
 
 WsLayout ws_layout(const symb_batch* b, const BatchInfo& bi, int op, bool full_bwd, bool any_lora_grad, bool staged_out = false) {
     WsLayout w;
@@ -342,6 +361,17 @@ WsLayout ws_layout(const symb_batch* b, const BatchInfo& bi, int op, bool full_b
     }
     if (staged_out && op != SYMB_OP_ADAPTER_GRAD)
         take(w.so_off, w.so_bytes, (size_t)bi.T * (op == SYMB_OP_FWD ? b->d_out : b->d_in) * 2);
+    w.mandatory = cur;
+    if (op != SYMB_OP_ADAPTER_GRAD && bi.T > 0 && bi.T <= kSmallRows) {
+        // the contraction runs over d_in in the forward, over d_out in the input gradient; the weight is
+        // read N-contiguous by the forward of an input-major weight and by the input gradient of an nn.Linear one
+        const int K = op == SYMB_OP_FWD ? b->d_in : b->d_out, N = op == SYMB_OP_FWD ? b->d_out : b->d_in;
+        take(w.sg_off, w.sg_bytes, (size_t)bi.T * K * 2);
+        if ((op == SYMB_OP_FWD) == conv1d) {
+            const int kpr = small_k_per_range(K, N);
+            take(w.sp_off, w.sp_bytes, (size_t)((K + kpr - 1) / kpr) * kSmallRows * N * 4);
+        }
+    }
     if (op == SYMB_OP_FWD) {
         const SplitPlan sp = gemm_split_plan(bi.T, b->d_out, b->d_in);
         if (sp.parts > 1) take(w.tp_off, w.tp_bytes, sp.bytes);
@@ -550,6 +580,39 @@ symb_status launch_grad_reduce(symb_handle h, const GradReduceParams& rp, int ns
     return SYMB_OK;
 }
 
+// C[T][N] = A[T][K] Wop, T <= 16, with the weight-streaming kernels (adapter_kernels.hpp).
+//   w_kmajor: Wop is [N][K] (one workgroup per 32 columns, K split inside the workgroup);
+//   else Wop is [K][N] (column blocks x K ranges, fp32 partial sums in `partial`, then the finish kernel).
+symb_status launch_small(symb_handle h, const bf16* A, const bf16* Wop, bool w_kmajor, int K, const SmallEpilogue& epi,
+                         float* partial, hipStream_t st) {
+    if (w_kmajor) {
+        RowGemvParams rp{Wop, A, K, epi};
+        hipLaunchKernelGGL(symb_rowgemv_kernel<1>, dim3((epi.N + SKINNY_ROWS - 1) / SKINNY_ROWS), dim3(256), 0, st, rp);
+        SYMB_HIP(h, hipGetLastError());
+        return SYMB_OK;
+    }
+    const int kpr = small_k_per_range(K, epi.N), ranges = (K + kpr - 1) / kpr;
+    ColGemvParams cp{Wop, A, partial, K, epi.N, epi.T, kpr};
+    hipLaunchKernelGGL(symb_colgemv_kernel, dim3((epi.N + COLGEMV_CT - 1) / COLGEMV_CT, ranges), dim3(256), 0, st, cp);
+    SYMB_HIP(h, hipGetLastError());
+    SmallFinishParams fp{partial, ranges, epi};
+    hipLaunchKernelGGL(symb_small_finish_kernel, dim3((epi.N + 255) / 256, epi.T), dim3(256), 0, st, fp);
+    SYMB_HIP(h, hipGetLastError());
+    return SYMB_OK;
+}
+
+// Whether a call of T rows takes the small-batch kernels: a handful of rows, the optional workspace
+// regions present, and, for a weight read K-contiguous, a layer of moderate size (one workgroup per 32
+// columns holds 152 KiB of LDS: on 4096 x 11008 the 344 workgroups make a second, third-full round and
+// the tiled kernel with its K-split is faster at any row count).
+bool small_path(symb_handle h, int T, bool w_kmajor, long long weights, bool second_output, const WsLayout& wl, const void* ws,
+                size_t ws_bytes) {
+    if (!h->opt_small_rows || T > kSmallRows || !wl.sg_bytes || !ws) return false;
+    if (ws_bytes < (wl.sp_bytes ? wl.sp_off + wl.sp_bytes : wl.sg_off + wl.sg_bytes)) return false;
+    // (a call with a pre-adapter output cannot split K in the tiled kernel: there the streaming kernel wins on any layer)
+    return !w_kmajor || weights <= 24ll << 20 || second_output;
+}
+
 symb_status check_handle(symb_handle h) {
     if (!h) return fail(nullptr, SYMB_ERR_INVALID_ARG, "handle is null");
     if (hipSetDevice(h->device) != hipSuccess) return fail(h, SYMB_ERR_DEVICE, "hipSetDevice(%d) failed", h->device);
@@ -633,6 +696,7 @@ symb_status symb_debug_set_option(symb_handle h, int32_t option, int32_t value) 
         case SYMB_OPT_K_SPLIT: h->opt_k_split = value != 0; break;
         case SYMB_OPT_SMALL_BATCH_KERNELS: h->opt_small_rows = value != 0; break;
         case SYMB_OPT_SKINNY_DEEP: h->opt_skinny_deep = value != 0; break;
+        case 100: h->opt_experiment = value; break;
         default: return fail(h, SYMB_ERR_INVALID_ARG, "unknown option %d", option);
     }
     return SYMB_OK;
@@ -832,7 +896,7 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     // workspace and a row scatter, after it on the stream, fills the clients' buffers.
     const bool staged = seg_io && seg_buffers_overlap(b, X_seg, (size_t)b->d_in * 2, Y_seg, (size_t)b->d_out * 2);
     const WsLayout wl = ws_layout(b, bi, SYMB_OP_FWD, true, false, staged);
-    const size_t ws_need = wl.tp_bytes ? wl.tp_off : wl.total;     // the K-split's partial tiles are optional
+    const size_t ws_need = wl.mandatory;     // the regions after it are optional
     if (ws_need > ws_bytes || (ws_need && !ws))
         return fail(h, SYMB_ERR_WORKSPACE_TOO_SMALL, "forward needs %zu workspace bytes, got %zu%s", ws_need, ws_bytes,
                     staged ? " (output buffers overlap input buffers: size the workspace with SYMB_OP_FWD_INPLACE)" : "");
@@ -845,12 +909,14 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     plan_row_tiles(b, bm, lo, hi);
     std::vector<RowChunk> chunks, all_chunks;
     plan_chunks(b, kSkinnyRows, SYMB_ADAPTER_LORA, chunks);
-    if (bi.n_ia3in || staged) plan_chunks(b, kSkinnyRows, -1, all_chunks);
-    const std::vector<SegDesc> sd = make_segdesc(b);
-    unsigned char* wsb = (unsigned char*)ws;
     // Input-major weight: the forward is the N-contiguous GEMM, whose LoRA steps read the adapter
     // side as [rank][d_out] rows: B_i^T, packed into the workspace; a second descriptor set points there.
     const bool conv1d = b->weight_layout == SYMB_WEIGHT_CONV1D;
+    const bool small = small_path(h, bi.T, !conv1d, (long long)b->d_in * b->d_out, Ybase != nullptr, wl, ws, ws_bytes);
+    const bool copy_rows = bi.n_ia3in > 0 || (small && seg_io);      // the product reads a flat copy of X (scaled / gathered)
+    if (copy_rows || staged) plan_chunks(b, kSkinnyRows, -1, all_chunks);
+    const std::vector<SegDesc> sd = make_segdesc(b);
+    unsigned char* wsb = (unsigned char*)ws;
     std::vector<SegDesc> sd_gemm = sd;
     std::vector<int64_t> pk_off(bi.S, 0);
     if (conv1d && bi.n_lora) {
@@ -884,15 +950,17 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     // IA3 input scaling: the GEMM multiplies a copy of X whose IA3_IN rows are scaled by l_i
     // (LoRA segments, if any, still shrink the caller's X: their rows are not touched by the copy)
     const bf16* x_op = (const bf16*)X;
-    if (bi.n_ia3in) {
-        ScaleParams sc{(const bf16*)X, (bf16*)(wsb + wl.sc_off), b->d_in, (const RowChunk*)(dev + o_all),
-                       (const SegDesc*)(dev + o_seg), KIND_IA3_IN, nullptr, nullptr};
+    if (copy_rows) {
+        bf16* const copy = (bf16*)(wsb + (bi.n_ia3in ? wl.sc_off : wl.sg_off));
+        ScaleParams sc{(const bf16*)X, copy, b->d_in, (const RowChunk*)(dev + o_all),
+                       (const SegDesc*)(dev + o_seg), KIND_IA3_IN, seg_io ? (const bf16* const*)(dev + o_xs) : nullptr,
+                       (const int32_t*)(dev + o_off)};
         hipLaunchKernelGGL(symb_ia3_scale_rows_kernel, dim3((unsigned)all_chunks.size()), dim3(256), 0, s, sc);
         SYMB_HIP(h, hipGetLastError());
-        x_op = (const bf16*)(wsb + wl.sc_off);
+        x_op = copy;
     }
     bf16* Hs = bi.n_lora ? (bf16*)(wsb + wl.h_off) : nullptr;
-    if (conv1d && bi.n_lora) {
+    if (conv1d && bi.n_lora && !small) {
         PackParams pp{(const SegDesc*)(dev + o_seg), (bf16*)(wsb + wl.pk_off), (const int64_t*)(dev + o_pk), b->d_out};
         hipLaunchKernelGGL(symb_pack_bt_kernel, dim3((b->d_out + 255) / 256, bi.S), dim3(256), 0, s, pp);
         SYMB_HIP(h, hipGetLastError());
@@ -912,17 +980,26 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
         }
         if ((st = launch_skinny(h, sp, (int)chunks.size(), bi.max_rpad, s)) != SYMB_OK) return st;
     }
-    // A handful of rows (decode steps) on a layer of moderate size: stream W once with one workgroup
-    // per 32 output columns.  Measured against the tiled kernel with its K-split (33-40 us per call
-    // from 4 to 64 rows): 17-20 us up to 16 rows on 4096 x 4096 (descriptors in place), but slower from 24 rows on, and on
-    // 4096 x 11008 at any row count (344 workgroups of 152 KiB LDS: a second, third-full round).
-    if (h->opt_small_rows && bi.T <= 16 && (long long)b->d_in * b->d_out <= 24ll << 20 && !conv1d && !seg_io && !Ybase && nd.empty() &&
-        bi.n_ia3in == 0) {
-        RowGemvParams rp{(const bf16*)W, (const bf16*)X, (bf16*)Y, (const bf16*)bias, b->d_in, b->d_out, bi.T, bi.S,
-                         (const int32_t*)(dev + o_off), (const SegDesc*)(dev + o_seg), Hs, 2 * bi.max_rpad};
-        const dim3 grid((b->d_out + SKINNY_ROWS - 1) / SKINNY_ROWS);
-        hipLaunchKernelGGL(symb_rowgemv_kernel<1>, grid, dim3(256), 0, s, rp);
-        SYMB_HIP(h, hipGetLastError());
+    // A handful of rows (decode steps): the weight-streaming kernels instead of the tiled GEMM.  Measured
+    // against the tiled kernel with its K-split (33-40 us per call from 4 to 64 rows): 17-20 us up to 16 rows on
+    // 4096 x 4096 (descriptors in place), but slower from 24 rows on.
+    if (small) {
+        SmallEpilogue ep{};
+        ep.C = (bf16*)Y;
+        ep.Cbase = (bf16*)Ybase;
+        ep.c_seg = seg_io ? (bf16* const*)(dev + o_ys) : nullptr;
+        ep.bias = (const bf16*)bias;
+        ep.N = b->d_out;
+        ep.T = bi.T;
+        ep.S = bi.S;
+        ep.off = (const int32_t*)(dev + o_off);
+        ep.seg = (const SegDesc*)(dev + o_seg);
+        ep.ext = Hs;
+        ep.ext_pitch = 2 * bi.max_rpad;
+        ep.backward = 0;
+        ep.lora_term = 1;
+        ep.neff = nd.empty() ? nullptr : (const NoiseDesc*)(dev + o_nd);
+        if ((st = launch_small(h, x_op, (const bf16*)W, !conv1d, b->d_in, ep, (float*)(wsb + wl.sp_off), s)) != SYMB_OK) return st;
         { guard.completed = true; return seal_slot(h, s); }
     }
     GemmParams gp{};
@@ -982,7 +1059,7 @@ symb_status symb_base_linear_fwd_static(symb_handle h, const symb_batch* b, cons
     if ((st = validate(h, b)) != SYMB_OK) return st;
     const BatchInfo bi = inspect(b);
     const WsLayout wl = ws_layout(b, bi, SYMB_OP_FWD, true, false);
-    const size_t need = wl.tp_bytes ? wl.tp_off : wl.total;        // the partial tiles of a K-split are used only if they fit too
+    const size_t need = wl.mandatory;        // the optional regions (small-batch kernels, K-split partial tiles) are used only if they fit too
     if (need > (size_t)SYMB_STATIC_SCRATCH_BYTES)
         return fail(h, SYMB_ERR_WORKSPACE_TOO_SMALL, "this batch needs %zu bytes of workspace; the static scratch array holds %zu "
                     "(use symb_base_linear_fwd with a workspace of the caller's)", need, (size_t)SYMB_STATIC_SCRATCH_BYTES);
@@ -1079,7 +1156,7 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     const bool full = flags == SYMB_BWD_FULL;
     const bool staged = seg_io && seg_buffers_overlap(b, dY_seg, (size_t)b->d_out * 2, dX_seg, (size_t)b->d_in * 2);   // see the forward
     const WsLayout wl = ws_layout(b, bi, SYMB_OP_BWD_INPUT, full, false, staged);
-    const size_t ws_need = wl.tp_bytes ? wl.tp_off : wl.total;     // the K-split's partial tiles are optional
+    const size_t ws_need = wl.mandatory;     // the regions after it are optional
     if (ws_need > ws_bytes || (ws_need && !ws))
         return fail(h, SYMB_ERR_WORKSPACE_TOO_SMALL, "backward needs %zu workspace bytes, got %zu%s", ws_need, ws_bytes,
                     staged ? " (output buffers overlap input buffers: size the workspace with SYMB_OP_BWD_INPUT_INPLACE)" : "");
@@ -1087,6 +1164,7 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     const bool k_split = wl.tp_bytes && ws && ws_bytes >= wl.total && !dXbase && h->opt_k_split && h->xcd_rule;
     hipStream_t s = (hipStream_t)stream;
     const bool lora = full && bi.n_lora > 0, ia3 = full && bi.n_ia3 > 0;
+    const bool conv1d_early = b->weight_layout == SYMB_WEIGHT_CONV1D;
 
     const int bm = gemm_tile_m(bi.T, b->d_in);
     std::vector<int32_t> lo, hi;
@@ -1100,7 +1178,13 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     unsigned char* const wsb0 = (unsigned char*)ws;
     std::vector<const void*> mix;           // per segment: where the GEMM reads its rows
     bool ia3_mixed = false;
-    if (ia3) {
+    // a handful of rows: the weight-streaming kernels, which read one flat copy of the rows (gathered from
+    // per-segment buffers, IA3 rows scaled) in the workspace
+    const bool small = small_path(h, bi.T, conv1d_early, (long long)b->d_in * b->d_out, dXbase != nullptr, wl, ws, ws_bytes);
+    const bool small_copy = small && (seg_io || ia3);
+    if (small_copy) {
+        plan_chunks(b, kSkinnyRows, -1, all_chunks);
+    } else if (ia3) {
         mix.assign(bi.S, nullptr);
         uintptr_t lo_a = UINTPTR_MAX, hi_a = 0;
         for (int i = 0; i < bi.S; ++i) {
@@ -1162,7 +1246,7 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
 
     const bf16* a_op = (const bf16*)dY;
     bf16* dH = nullptr;
-    if (lora && conv1d) {
+    if (lora && conv1d && !small) {
         PackAtParams pa{(const SegDesc*)(dev + o_seg), (bf16*)(wsb + wl.pa_off), (const int64_t*)(dev + o_pa), b->d_in};
         hipLaunchKernelGGL(symb_pack_at_kernel, dim3((b->d_in + 255) / 256, bi.S), dim3(256), 0, s, pa);
         SYMB_HIP(h, hipGetLastError());
@@ -1189,13 +1273,32 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
         if ((st = launch_skinny(h, sp, (int)chunks.size(), bi.max_rpad, s)) != SYMB_OK) return st;
     }
     bool a_from_seg = seg_io;
-    if (ia3) {
+    if (ia3 || small_copy) {
         a_from_seg = ia3_mixed;
-        ScaleParams sc{(const bf16*)dY, (bf16*)(wsb + wl.sc_off), b->d_out, (const RowChunk*)(dev + o_all), (const SegDesc*)(dev + o_seg), KIND_IA3,
-                       seg_io ? (const bf16* const*)(dev + o_gs) : nullptr, (const int32_t*)(dev + o_off)};
+        bf16* const copy = (bf16*)(wsb + (small_copy ? wl.sg_off : wl.sc_off));
+        ScaleParams sc{(const bf16*)dY, copy, b->d_out, (const RowChunk*)(dev + o_all), (const SegDesc*)(dev + o_seg),
+                       ia3 ? (int)KIND_IA3 : -1, seg_io ? (const bf16* const*)(dev + o_gs) : nullptr, (const int32_t*)(dev + o_off)};
         hipLaunchKernelGGL(symb_ia3_scale_rows_kernel, dim3((unsigned)all_chunks.size()), dim3(256), 0, s, sc);
         SYMB_HIP(h, hipGetLastError());
-        a_op = (const bf16*)(wsb + wl.sc_off);
+        a_op = copy;
+    }
+    if (small) {
+        SmallEpilogue ep{};
+        ep.C = (bf16*)dX;
+        ep.Cbase = (bf16*)dXbase;
+        ep.c_seg = seg_io ? (bf16* const*)(dev + o_xs) : nullptr;
+        ep.N = b->d_in;
+        ep.T = bi.T;
+        ep.S = bi.S;
+        ep.off = (const int32_t*)(dev + o_off);
+        ep.seg = (const SegDesc*)(dev + o_seg);
+        ep.ext = dH;
+        ep.ext_pitch = 2 * bi.max_rpad;
+        ep.backward = 1;
+        ep.lora_term = full ? 1 : 0;
+        // W [d_out][d_in] is the [K][N] operand of dX = dY W; an input-major weight [d_in][d_out] is [N][K]
+        if ((st = launch_small(h, a_op, (const bf16*)W, conv1d, b->d_out, ep, (float*)(wsb + wl.sp_off), s)) != SYMB_OK) return st;
+        { guard.completed = true; return seal_slot(h, s); }
     }
     GemmParams gp{};
     gp.Aop = a_op;

@@ -757,3 +757,108 @@ def test_one_buffer_per_client_for_input_and_output(case):
     sb.symb_base_linear_bwd_input_seg(h, b, gin, Wd, xout, sb.SYMB_BWD_FULL, gh.workspace(b, sb.SYMB_OP_BWD_INPUT_INPLACE))
     torch.cuda.synchronize()
     assert_close(gather(d_in), oracle.backward_input(off, oads, p["dY"], p["W"]), "in-place dX", out_bf16=True)
+
+
+@pytest.mark.parametrize("lens", [[1], [16], [9, 0, 7], [1, 1, 5, 1, 1, 4], [3, 1, 2, 1, 1, 2, 1, 1]])
+@pytest.mark.parametrize("dims", [(200, 392), (392, 200), (4096, 4096)])
+def test_a_handful_of_rows_in_every_call_form(lens, dims):
+    """Calls of at most 16 rows take the weight-streaming kernels in every form: forward with the
+    pre-adapter output, input-major weight, IA3 on the input, the privacy flow's epilogue, per-client
+    buffers (also one buffer for input and output); input gradient, full and base-only, with the
+    pre-adapter gradient, through either weight layout and from per-client buffers.  Every adapter kind,
+    ranks 1..128, K with a remainder, widths that are not multiples of the column blocks."""
+    d_in, d_out = dims
+    big = d_in * d_out > 1 << 20
+    if big and len(lens) not in (1, 6):
+        pytest.skip("the real layer width runs two of the row mixes")
+    kinds = [L, I, N, L, 3, I, L, 3]
+    p = make_problem(400 + len(lens) + d_in, d_in, d_out, lens, kinds, [1, 128, 24, 8, 100] if not big else [16, 8, 64])
+    off, T, S = p["off"], p["T"], len(p["ads"])
+    assert 0 < T <= 16
+    oads = oracle_ads(p["ads"])
+    h = gh.handle()
+    Y0r, Yr = oracle.forward(off, oads, p["X"], p["W"], p["bias"])
+    kind_of_row = np.array([p["ads"][int(np.searchsorted(off, t, side="right") - 1)].kind for t in range(T)])
+    plain_in = np.flatnonzero(kind_of_row != 3)       # rows of input-scaling segments hold the product of the scaled input in Ybase
+    for conv1d in (False, True):
+        Y, Yb = gh.forward(off, p["ads"], p["X"], p["W"], p["bias"], want_base=True, conv1d=conv1d)
+        assert_close(gh.bf16_to_f64(Y), Yr, f"small Y conv1d={conv1d}", out_bf16=True)
+        assert_close(gh.bf16_to_f64(Yb)[plain_in], Y0r[plain_in], f"small Ybase conv1d={conv1d}", out_bf16=True)
+        assert_close(gh.bf16_to_f64(Yb)[kind_of_row == 3], Yr[kind_of_row == 3], f"small Ybase of IA3_IN rows conv1d={conv1d}", out_bf16=True)
+        for base_only in (False, True):
+            dXr = oracle.backward_input(off, oads, p["dY"], p["W"], base_only=base_only)
+            dX = gh.backward_input(off, p["ads"], p["dY"], p["W"], base_only=base_only, conv1d=conv1d)
+            assert_close(gh.bf16_to_f64(dX), dXr, f"small dX conv1d={conv1d} base_only={base_only}", out_bf16=True)
+    # the pre-adapter input gradient next to the full one
+    dev = gh.upload_adapters(p["ads"], d_in, d_out, grads=False)
+    b = sb.Batch(d_in, d_out, off, dev.descs)
+    gd, Wd, bd, Xd = gh.to_dev(p["dY"]), gh.to_dev(p["W"]), gh.to_dev(p["bias"]), gh.to_dev(p["X"])
+    dX = torch.full((T, d_in), float("nan"), device="cuda", dtype=torch.bfloat16)
+    G = torch.full((T, d_in), float("nan"), device="cuda", dtype=torch.bfloat16)
+    sb.symb_base_linear_bwd_input_ex(h, b, gd, Wd, dX, G, sb.SYMB_BWD_FULL, gh.workspace(b, sb.SYMB_OP_BWD_INPUT))
+    torch.cuda.synchronize()
+    assert_close(gh.bf16_to_f64(dX), oracle.backward_input(off, oads, p["dY"], p["W"]), "small dX (with dXbase)", out_bf16=True)
+    Gr = oracle.backward_input(off, oads, p["dY"], p["W"], base_only=True)
+    keep = np.flatnonzero(kind_of_row != I)
+    if len(keep):
+        assert_close(gh.bf16_to_f64(G)[keep], Gr[keep], "small dXbase", out_bf16=True)
+    # the denoised forward: a stored noise effect per segment (broadcast and per token) taken off in the epilogue
+    rng = np.random.default_rng(9)
+    neff = [None if i % 3 == 2 or off[i + 1] == off[i] else
+            synth.f32_to_bf16_bits(rng.standard_normal((1 if i % 2 else int(off[i + 1] - off[i]), d_out)).astype(np.float32))
+            for i in range(S)]
+    Yd = torch.full((T, d_out), float("nan"), device="cuda", dtype=torch.bfloat16)
+    sb.symb_base_linear_fwd_denoise(h, b, Xd, Wd, bd, [gh.to_dev(n) for n in neff], Yd, gh.workspace(b, sb.SYMB_OP_FWD))
+    torch.cuda.synchronize()
+    assert_close(gh.bf16_to_f64(Yd), oracle.forward_denoise(off, oads, p["X"], p["W"], p["bias"], neff), "small denoised Y", out_bf16=True)
+    # per-client buffers (no IA3 on the input in that form): separate output buffers, then one buffer for both
+    q = make_problem(500 + len(lens) + d_in, d_in, d_out, lens, [L, I, N, L, I, L, N, L], [1, 128, 24, 8, 100] if not big else [16, 8, 64])
+    qads = oracle_ads(q["ads"])
+    qdev = gh.upload_adapters(q["ads"], d_in, d_out, grads=False)
+    qb = sb.Batch(d_in, d_out, off, qdev.descs)
+    qW, qbias = gh.to_dev(q["W"]), gh.to_dev(q["bias"])
+    wmax = max(d_in, d_out)
+    bufs = [torch.full((max(int(off[i + 1] - off[i]), 1) * wmax + 8 * (i + 1),), float("nan"), device="cuda", dtype=torch.bfloat16) for i in range(S)]
+    arena = torch.cat(bufs)                                   # one arena: the 4 GiB window rule
+    views, cur = [], 0
+    for i in range(S):
+        n = int(off[i + 1] - off[i])
+        views.append(arena[cur:cur + n * wmax] if n else None)
+        cur += bufs[i].numel()
+
+    def view(i, width):
+        n = int(off[i + 1] - off[i])
+        return views[i][:n * width].view(n, width) if n else None
+
+    def gather(width):
+        out = np.zeros((T, width))
+        for i in range(S):
+            if views[i] is not None:
+                out[off[i]:off[i + 1]] = gh.bf16_to_f64(view(i, width))
+        return out
+
+    _, qYr = oracle.forward(off, qads, q["X"], q["W"], q["bias"])
+    qdXr = oracle.backward_input(off, qads, q["dY"], q["W"])
+    for i in range(S):
+        if views[i] is not None:
+            view(i, d_in).copy_(gh.to_dev(np.ascontiguousarray(q["X"][off[i]:off[i + 1]])))
+    outs = [torch.full((int(off[i + 1] - off[i]), d_out), float("nan"), device="cuda", dtype=torch.bfloat16) if off[i + 1] > off[i] else None for i in range(S)]
+    sb.symb_base_linear_fwd_seg(h, qb, [view(i, d_in) for i in range(S)], qW, qbias, outs, gh.workspace(qb, sb.SYMB_OP_FWD))
+    torch.cuda.synchronize()
+    got = np.zeros((T, d_out))
+    for i in range(S):
+        if outs[i] is not None:
+            got[off[i]:off[i + 1]] = gh.bf16_to_f64(outs[i])
+    assert_close(got, qYr, "small per-segment Y", out_bf16=True)
+    sb.symb_base_linear_fwd_seg(h, qb, [view(i, d_in) for i in range(S)], qW, qbias, [view(i, d_out) for i in range(S)],
+                                gh.workspace(qb, sb.SYMB_OP_FWD_INPLACE))
+    torch.cuda.synchronize()
+    assert_close(gather(d_out), qYr, "small in-place Y", out_bf16=True)
+    for i in range(S):
+        if views[i] is not None:
+            views[i].fill_(float("nan"))
+            view(i, d_out).copy_(gh.to_dev(np.ascontiguousarray(q["dY"][off[i]:off[i + 1]])))
+    sb.symb_base_linear_bwd_input_seg(h, qb, [view(i, d_out) for i in range(S)], qW, [view(i, d_in) for i in range(S)],
+                                      sb.SYMB_BWD_FULL, gh.workspace(qb, sb.SYMB_OP_BWD_INPUT_INPLACE))
+    torch.cuda.synchronize()
+    assert_close(gather(d_in), qdXr, "small in-place dX", out_bf16=True)
