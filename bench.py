@@ -2,8 +2,8 @@
 """Benchmark of the segmented base+adapter layer on one MI355X.
 
 A step = one pass of the whole hot path over one synthetic batch: for every projection
-of the layer shape, forward (shrink + fused GEMM), input gradient (dH + fused GEMM) and
-adapter gradients (dA, dB, dl), all through the C ABI.  Inputs are resident in HBM before
+of the layer shape, forward (shrink + fused GEMM), adapter gradients (dB and dH in one pass
+over dY, then dA; dl) and input gradient (fused GEMM taking that dH), all through the C ABI.  Inputs are resident in HBM before
 the timed region.  Default workload: the Gemma2-27B-shaped layer with 20 LoRA clients x
 1024 tokens (T = 20480), ranks from {8, 16}.
 
@@ -59,9 +59,10 @@ def step(runs, stream):
     for r in runs:
         r.fwd(stream)
     for r in runs:
-        r.bwd_input(stream)
-        # same batch, same X, same dY: Hs (forward) and dH (input gradient) are still in the workspace
-        r.adapter_grad(stream, reuse_dh=True, reuse_hs=True)
+        # same batch, same X, same dY, same workspace: the gradient call takes Hs as the forward left it and
+        # forms dB and dH in one pass over dY; the input gradient takes that dH
+        r.adapter_grad(stream, reuse_hs=True)
+        r.bwd_input(stream, reuse_dh=True)
 
 
 def cpu_baseline(cfg: str, budget_s: float = 20.0) -> dict:
@@ -202,8 +203,8 @@ def phase_only(runs, stream_obj, stream, reps: int = 5):
 
     def bwd():
         for r in runs:
-            r.bwd_input(stream)
-            r.adapter_grad(stream, reuse_dh=True, reuse_hs=True)
+            r.adapter_grad(stream, reuse_hs=True)
+            r.bwd_input(stream, reuse_dh=True)
     t_f = timed(fwd)
     fwd()                                                   # Hs of every projection back in its workspace
     return t_f, timed(bwd)

@@ -84,7 +84,14 @@ typedef enum { SYMB_OP_FWD = 0, SYMB_OP_BWD_INPUT = 1, SYMB_OP_ADAPTER_GRAD = 2,
 
 /* flags of symb_base_linear_bwd_input */
 enum { SYMB_BWD_FULL = 0,             /* dX includes each segment's adapter branch */
-       SYMB_BWD_BASE_ONLY = 1 };      /* dX = dY W only: what the paper's executor returns (Sec. 3.6) */
+       SYMB_BWD_BASE_ONLY = 1,        /* dX = dY W only: what the paper's executor returns (Sec. 3.6) */
+       /* (with SYMB_BWD_FULL) dH = s dY B is taken from `ws` instead of being computed: `ws` must be the very
+        * workspace a preceding symb_adapter_grad call used for this same batch and dY (a call that wanted dA
+        * of every LoRA segment, so that it computed dH for all of them), untouched since.  A gradient call
+        * followed by the input gradient this way reads dY twice instead of three times: for ranks up to 16
+        * the gradient call forms dB and dH in one pass.  The caller carries the workspace over; the
+        * library stays stateless. */
+       SYMB_BWD_REUSE_DH = 2 };
 /* flags of symb_adapter_grad */
 enum { SYMB_GRAD_OVERWRITE = 0, SYMB_GRAD_ACCUMULATE = 1,
        /* dH is taken from `ws` instead of being recomputed: `ws` must be the very workspace a

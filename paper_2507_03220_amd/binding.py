@@ -21,7 +21,7 @@ SYMB_ADAPTER_NONE, SYMB_ADAPTER_LORA, SYMB_ADAPTER_IA3, SYMB_ADAPTER_IA3_IN = ra
 SYMB_OP_FWD, SYMB_OP_BWD_INPUT, SYMB_OP_ADAPTER_GRAD, SYMB_OP_FWD_INPLACE, SYMB_OP_BWD_INPUT_INPLACE = range(5)
 SYMB_OPT_DESCRIPTOR_REUSE, SYMB_OPT_K_SPLIT, SYMB_OPT_SMALL_BATCH_KERNELS, SYMB_OPT_SKINNY_DEEP = range(4)
 SYMB_STATIC_SCRATCH_BYTES = 32 << 20
-SYMB_BWD_FULL, SYMB_BWD_BASE_ONLY = 0, 1
+SYMB_BWD_FULL, SYMB_BWD_BASE_ONLY, SYMB_BWD_REUSE_DH = 0, 1, 2
 SYMB_GRAD_OVERWRITE, SYMB_GRAD_ACCUMULATE, SYMB_GRAD_REUSE_DH, SYMB_GRAD_REUSE_HS = 0, 1, 2, 4
 SYMB_MAX_RANK = 128
 SYMB_WEIGHT_LINEAR, SYMB_WEIGHT_CONV1D = 0, 1

@@ -3,6 +3,8 @@
 // of dY.  All of them walk segment-aligned row chunks from a host-built work list, so a
 // chunk never mixes two clients.
 #pragma once
+#include <type_traits>
+
 #include "symb_device.hpp"
 
 namespace symb {
@@ -777,6 +779,237 @@ symb_lora_grad_kernel(const GradParams p) {
                 }
             }
         }
+}
+
+// -------------------------------------------------------------------------------------------
+// dB_i and dH_i in ONE pass over dY (ranks up to 16).  Both products contract dY:
+//   dB_i[c][pp] = sum_t dY[t][c] * Hs[t][pp]            (over the segment's tokens)
+//   dH[t][pp]   = s_i * sum_c dY[t][c] * B_i[c][pp]     (over the output columns)
+// and dY is by far the largest tensor either reads (T x d_out), so reading it once instead of
+// twice saves its bytes.  A workgroup owns G column blocks of 256 columns of one work item
+// (a segment, or a run of a long one) and walks its tokens 32 at a time; per step it visits its
+// column blocks in turn: the dY tile goes through LDS as in symb_lora_grad_kernel and feeds
+// (a) the dB accumulators of that block (transposing LDS reads, token-contracted) and (b) a
+// 32 x 16 partial of dH over the block's columns (plain LDS reads, B_i^T fragments from the
+// packed copy, held in registers).  After the last block of a step the four wavefronts' dH partials
+// meet in LDS and the sum goes to dh_partial[group][t][16]; symb_dh_finish_kernel adds the
+// groups in order, scales by s_i and writes dH as value + residual.  Fixed summation order
+// everywhere: deterministic, no atomics.  dB comes out bit-identical to symb_lora_grad_kernel's.
+// -------------------------------------------------------------------------------------------
+struct DhDbParams {
+    const bf16* R;            // dY [T][ncols]
+    const bf16* L;            // Hs [T][l_pitch]: per row 16 values then 16 residuals
+    const bf16* packed;       // B_i^T [16][ncols] per LoRA segment (symb_pack_bt_kernel), at packed_off[i]
+    const int64_t* packed_off;
+    int ncols, l_pitch;
+    const int32_t* off;
+    const SegDesc* seg;
+    const GradItem* items;
+    int accumulate;
+    const bf16* const* R_seg;
+    float* partial;           // dB runs of split segments
+    float* dh_partial;        // [gridDim.x][T][16] fp32
+    int T;
+};
+
+template <int I0, int I1, class F>
+__device__ __forceinline__ void grad_static_for(F&& f) {
+    if constexpr (I0 < I1) {
+        f(std::integral_constant<int, I0>{});
+        grad_static_for<I0 + 1, I1>(f);
+    }
+}
+
+template <int G>
+__global__ void __launch_bounds__(256)
+symb_lora_dhdb_kernel(const DhDbParams p) {
+    constexpr int CT = 256, NI = CT / 64;
+    constexpr int RPITCH = CT * 2 + 16, LPRW = CT / 8, NRC = GRAD_TT * LPRW / 256;
+    constexpr int LP = 2 * 16 * 2 + 16;
+    __shared__ __attribute__((aligned(16))) unsigned char sR[GRAD_TT * RPITCH];
+    __shared__ __attribute__((aligned(16))) unsigned char sL[GRAD_TT * LP];
+    __shared__ __attribute__((aligned(16))) float red[4][GRAD_TT][16 + 4];
+    const GradItem it = p.items[blockIdx.y];
+    const int s = it.seg;
+    const SegDesc sd = p.seg[s];
+    const int t_lo = it.t_lo, t_hi = it.t_hi;
+    const bf16* const rbase = p.R_seg ? p.R_seg[s] - (size_t)p.off[s] * p.ncols : p.R;
+    const bf16* const bt = p.packed + p.packed_off[s];
+    const int nblk = (p.ncols + CT - 1) / CT;
+    const int cb0 = blockIdx.x * G, ncb = min(G, nblk - cb0);     // this workgroup's column blocks (uniform)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    floatx4 acc[G][NI];                                  // dB of every block of the group
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int i = 0; i < NI; ++i) acc[g][i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // B_i^T fragments of this wavefront's 64 columns of every block: lane holds rank row lane & 15,
+    // columns 8 (lane >> 4) .. + 7 of each of the two 32-column steps
+    u32x4 btf[G][2];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const int c = (cb0 + g) * CT + wave * 64 + ks * 32 + (lane >> 4) * 8;
+            const bool ok = g < ncb && c < p.ncols;
+            btf[g][ks] = ld_glb16(bt + (size_t)(lane & 15) * p.ncols + (ok ? c : 0));
+            if (!ok) btf[g][ks] = u32x4{0u, 0u, 0u, 0u};
+        }
+
+    struct Stage { u32x4 rr[NRC]; u32x4 lv; };
+    const int l_chunks = GRAD_TT * 4;                    // 16-byte chunks of the L tile: 32 rows x 64 bytes (16 values + 16 residuals)
+    const int l_tr = (tid & 127) >> 2, l_pc = tid & 3;    // this thread's chunk of it
+    // unconditional loads, zeroed on their way to LDS (see symb_lora_grad_kernel)
+    auto fetch = [&](Stage& sg, int t0, int g) __attribute__((always_inline)) {
+        const int c0 = (cb0 + min(g, ncb - 1)) * CT;
+        const bool col_ok = (c0 + (tid % LPRW) * 8) < p.ncols;
+#pragma unroll
+        for (int i = 0; i < NRC; ++i) {
+            const int c = tid + i * 256, tr = c / LPRW, cc = c % LPRW;
+            sg.rr[i] = ld_glb16(rbase + (size_t)min(t0 + tr, t_hi - 1) * p.ncols + c0 + (col_ok ? cc * 8 : 0));
+        }
+        sg.lv = ld_glb16(p.L + (size_t)min(t0 + l_tr, t_hi - 1) * p.l_pitch + l_pc * 8);
+    };
+    auto put = [&](const Stage& sg, int t0, int g) __attribute__((always_inline)) {
+        const int c0 = (cb0 + g) * CT;
+        const bool col_ok = (c0 + (tid % LPRW) * 8) < p.ncols;
+#pragma unroll
+        for (int i = 0; i < NRC; ++i) {
+            const int c = tid + i * 256, tr = c / LPRW, cc = c % LPRW;
+            const bool ok = (t0 + tr) < t_hi && col_ok;
+            *reinterpret_cast<u32x4*>(sR + tr * RPITCH + cc * 16) = ok ? sg.rr[i] : u32x4{0u, 0u, 0u, 0u};
+        }
+        if (g == 0 && tid < l_chunks)                    // the Hs rows of a step are the same for all its blocks
+            *reinterpret_cast<u32x4*>(sL + l_tr * LP + l_pc * 16) = (t0 + l_tr) < t_hi ? sg.lv : u32x4{0u, 0u, 0u, 0u};
+    };
+    floatx4 dh[2];                                       // dH partial of the step: token blocks 0 / 1, this wavefront's columns
+    auto multiply = [&](auto GC) __attribute__((always_inline)) {
+        constexpr int g = decltype(GC)::value;
+        bf16x8 rf[NI];
+#pragma unroll
+        for (int i = 0; i < NI; ++i) rf[i] = lds_read_tr_16x32(sR, RPITCH, wave * (NI * 16) + i * 16, lane);
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {           // Hs value, then its rounding residual
+            const bf16x8 lf = lds_read_tr_16x32(sL, LP, half * 16, lane);
+#pragma unroll
+            for (int i = 0; i < NI; ++i) acc[g][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lf, rf[i], acc[g][i], 0, 0, 0);
+        }
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const u32x4 yv = *reinterpret_cast<const u32x4*>(sR + (tb * 16 + (lane & 15)) * RPITCH + (wave * 64 + ks * 32 + (lane >> 4) * 8) * 2);
+                dh[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, btf[g][ks]), __builtin_bit_cast(bf16x8, yv), dh[tb], 0, 0, 0);
+            }
+    };
+    // One tile = (token step, column block), blocks fastest.  Three register sets: the tile two ahead is
+    // requested while the current one multiplies.
+    auto advance = [&](int& t0, int& g) __attribute__((always_inline)) {
+        if (++g == ncb) { g = 0; t0 += GRAD_TT; }
+    };
+    if (t_lo < t_hi) {
+        Stage sg0, sg1, sg2;
+        int ft = t_lo, fg = 0;                           // the next tile to request
+        fetch(sg0, ft, fg); advance(ft, fg);
+        fetch(sg1, ft, fg); advance(ft, fg);
+        int t0 = t_lo, g = 0;                            // the tile being computed
+        auto step = [&](Stage& cur, Stage& nxt) __attribute__((always_inline)) {
+            if (g == 0) dh[0] = dh[1] = floatx4{0.f, 0.f, 0.f, 0.f};
+            __syncthreads();                             // the previous tile's LDS reads are done
+            put(cur, t0, g);
+            __syncthreads();
+            fetch(nxt, ft, fg); advance(ft, fg);
+            // the block index selects registers: dispatch on it (uniform)
+            grad_static_for<0, G>([&](auto GC) __attribute__((always_inline)) {
+                if (g == decltype(GC)::value) multiply(GC);
+            });
+            if (g == ncb - 1) {
+                // the step's dH partial over this workgroup's columns: wavefronts meet in LDS, fixed order
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb)
+                    *reinterpret_cast<float4*>(&red[wave][tb * 16 + (lane & 15)][(lane >> 4) * 4]) = make_float4(dh[tb][0], dh[tb][1], dh[tb][2], dh[tb][3]);
+                __syncthreads();
+                if (tid < GRAD_TT * 4) {
+                    const int tr = tid >> 2, q = (tid & 3) * 4;
+                    if (t0 + tr < t_hi) {
+                        float4 v = *reinterpret_cast<const float4*>(&red[0][tr][q]);
+#pragma unroll
+                        for (int w = 1; w < 4; ++w) {
+                            const float4 a = *reinterpret_cast<const float4*>(&red[w][tr][q]);
+                            v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+                        }
+                        *reinterpret_cast<float4*>(p.dh_partial + ((size_t)blockIdx.x * p.T + t0 + tr) * 16 + q) = v;
+                    }
+                }
+            }
+            advance(t0, g);
+        };
+        while (t0 < t_hi) {
+            step(sg0, sg2);
+            if (t0 < t_hi) step(sg1, sg0);
+            if (t0 < t_hi) step(sg2, sg1);
+        }
+    }
+    // ---- dB of every block, as symb_lora_grad_kernel<1, true> writes it
+    float* out = it.direct ? sd.dB : p.partial + it.partial_off;
+    const bool accumulate = it.direct && p.accumulate;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        if (g < ncb) {
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                const int c = (cb0 + g) * CT + wave * (NI * 16) + i * 16 + (lane & 15);
+                if (c < p.ncols) {
+                    const int pp0 = (lane >> 4) << 2;
+                    float* dst = out + (size_t)c * sd.rank + pp0;
+                    float old[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (accumulate) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            if (pp0 + q < sd.rank) old[q] = dst[q];
+                    }
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (pp0 + q < sd.rank) dst[q] = old[q] + acc[g][i][q];
+                }
+            }
+        }
+    }
+}
+
+// dH of the rows of one chunk from the groups' partial sums: dH[t][pp] = s_i * (group 0 + group 1 + ...),
+// written as a bf16 value plus its bf16 rounding residual (the layout the skinny kernel writes).
+struct DhFinishParams {
+    const float* dh_partial;  // [groups][T][16]
+    int groups, T;
+    bf16* out;                // [T][out_pitch]
+    int out_pitch;
+    const RowChunk* chunks;
+    const SegDesc* seg;
+};
+__global__ void __launch_bounds__(128)
+symb_dh_finish_kernel(const DhFinishParams p) {
+    const RowChunk ch = p.chunks[blockIdx.x];
+    const SegDesc sd = p.seg[ch.seg];
+    const int tr = threadIdx.x >> 2, q = (threadIdx.x & 3) * 4;
+    if (tr >= ch.nrows) return;
+    const size_t row = (size_t)(ch.row0 + tr);
+    float4 v = *reinterpret_cast<const float4*>(p.dh_partial + row * 16 + q);
+    for (int g = 1; g < p.groups; ++g) {
+        const float4 a = *reinterpret_cast<const float4*>(p.dh_partial + ((size_t)g * p.T + row) * 16 + q);
+        v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+    }
+    v.x *= sd.scale; v.y *= sd.scale; v.z *= sd.scale; v.w *= sd.scale;
+    const unsigned h01 = pack2_bf16(v.x, v.y), h23 = pack2_bf16(v.z, v.w);
+    uint2 hi2, lo2;
+    hi2.x = h01;
+    hi2.y = h23;
+    lo2.x = pack2_bf16(v.x - bf16_bits_to_f32((unsigned short)(h01 & 0xffffu)), v.y - bf16_bits_to_f32((unsigned short)(h01 >> 16)));
+    lo2.y = pack2_bf16(v.z - bf16_bits_to_f32((unsigned short)(h23 & 0xffffu)), v.w - bf16_bits_to_f32((unsigned short)(h23 >> 16)));
+    bf16* o = p.out + row * p.out_pitch;
+    *reinterpret_cast<uint2*>(o + q) = hi2;
+    *reinterpret_cast<uint2*>(o + sd.rpad + q) = lo2;
 }
 
 // Sums the runs of the split segments (see GradItem) into their dA / dB: element by element,

@@ -275,6 +275,15 @@ SplitPlan gemm_split_plan(int M, int N, int K) {
     return s;
 }
 
+// One-pass dH + dB kernel: column blocks of 256 columns per workgroup (0: the layer is too narrow for it:
+// with few column blocks the launch has too few workgroups, each walking its tokens alone, and the two
+// separate passes are faster), and the number of workgroups along d_out.
+int dhdb_blocks_per_group(int d_out) { return (d_out + 255) / 256 >= 64 ? 2 : 0; }
+int dhdb_groups(int d_out) {
+    const int g = dhdb_blocks_per_group(d_out);
+    return g ? ((d_out + 255) / 256 + g - 1) / g : 0;
+}
+
 // LoRA gradients of long segments: a segment of more than GRAD_SPLIT_MIN tokens is walked in runs of
 // GRAD_SPLIT tokens, each by workgroups of its own, which leave fp32 sums of the result's size in the
 // workspace; a second kernel adds the runs up in order.  Number of runs of a segment of n tokens:
@@ -303,6 +312,7 @@ struct WsLayout {
     size_t pa_off = 0, pa_bytes = 0;      // packed A^T (input-major weight, input gradient only)
     size_t so_off = 0, so_bytes = 0;      // flat output [T][width] bf16 of a per-segment call whose outputs overlap its inputs
     size_t gr_off = 0, gr_bytes = 0;      // fp32 runs of the LoRA gradients of split segments (see grad_split)
+    size_t dp_off = 0, dp_bytes = 0;      // fp32 partial sums of dH per group of column blocks (one-pass dH + dB, ranks up to 16)
     // optional regions (a workspace that ends before them makes the call take the tiled kernel, unsplit):
     size_t sg_off = 0, sg_bytes = 0;      // calls of at most 16 rows: flat copy of the activation rows [T][K] (gathered / scaled)
     size_t sp_off = 0, sp_bytes = 0;      // calls of at most 16 rows, weight read N-contiguous: fp32 partial sums per K range
@@ -357,6 +367,7 @@ WsLayout ws_layout(const symb_batch* b, const BatchInfo& bi, int op, bool full_b
             take(w.pk_off, w.pk_bytes, bi.packed_elems * 2);
             const size_t gr = std::max(grad_split_floats(b, true), grad_split_floats(b, false)) * 4;   // dB's runs, then dA's, in the same place
             if (gr) take(w.gr_off, w.gr_bytes, gr);
+            if (bi.max_rpad == 16 && dhdb_groups(b->d_out)) take(w.dp_off, w.dp_bytes, (size_t)dhdb_groups(b->d_out) * bi.T * 16 * 4);
         }
     }
     if (staged_out && op != SYMB_OP_ADAPTER_GRAD)
@@ -1140,20 +1151,23 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     if (st != SYMB_OK) return st;
     CallGuard guard(h);
     if ((st = validate(h, b)) != SYMB_OK) return st;
-    if (flags != SYMB_BWD_FULL && flags != SYMB_BWD_BASE_ONLY) return fail(h, SYMB_ERR_INVALID_ARG, "unknown backward flag %u", flags);
+    if (flags & ~(uint32_t)(SYMB_BWD_BASE_ONLY | SYMB_BWD_REUSE_DH)) return fail(h, SYMB_ERR_INVALID_ARG, "unknown backward flag %u", flags);
+    if ((flags & SYMB_BWD_BASE_ONLY) && (flags & SYMB_BWD_REUSE_DH))
+        return fail(h, SYMB_ERR_INVALID_ARG, "SYMB_BWD_REUSE_DH makes no sense with SYMB_BWD_BASE_ONLY");
+    const bool take_dh = (flags & SYMB_BWD_REUSE_DH) != 0;      // dH is in the workspace already (a gradient call on this batch left it)
     const BatchInfo bi = inspect(b);
     if (bi.T == 0) return SYMB_OK;
     const bool seg_io = dY_seg != nullptr;
     const void* g_base = nullptr;
     if (seg_io) {
         if (!W) return fail(h, SYMB_ERR_INVALID_ARG, "W is required");
-        const bool copy_first = flags == SYMB_BWD_FULL && bi.n_ia3 > 0;     // then the GEMM reads the scaled copy, not the buffers
+        const bool copy_first = !(flags & SYMB_BWD_BASE_ONLY) && bi.n_ia3 > 0;     // then the GEMM reads the scaled copy, not the buffers
         if ((st = check_seg_ptrs(h, b, dY_seg, (size_t)b->d_out * 2, "dY", !copy_first, &g_base)) != SYMB_OK) return st;
         if ((st = check_seg_ptrs(h, b, (const void* const*)dX_seg, (size_t)b->d_in * 2, "dX", false, nullptr)) != SYMB_OK) return st;
     } else if (!dY || !W || !dX) return fail(h, SYMB_ERR_INVALID_ARG, "dY, W and dX are required");
     if (misaligned16(dY) || misaligned16(W) || misaligned16(dX) || misaligned16(dXbase) || misaligned16(ws))
         return fail(h, SYMB_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
-    const bool full = flags == SYMB_BWD_FULL;
+    const bool full = !(flags & SYMB_BWD_BASE_ONLY);
     const bool staged = seg_io && seg_buffers_overlap(b, dY_seg, (size_t)b->d_out * 2, dX_seg, (size_t)b->d_in * 2);   // see the forward
     const WsLayout wl = ws_layout(b, bi, SYMB_OP_BWD_INPUT, full, false, staged);
     const size_t ws_need = wl.mandatory;     // the regions after it are optional
@@ -1251,8 +1265,8 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
         hipLaunchKernelGGL(symb_pack_at_kernel, dim3((b->d_in + 255) / 256, bi.S), dim3(256), 0, s, pa);
         SYMB_HIP(h, hipGetLastError());
     }
-    if (lora) {
-        dH = (bf16*)(wsb + wl.dh_off);
+    if (lora) dH = (bf16*)(wsb + wl.dh_off);
+    if (lora && !take_dh) {
         PackParams pp{(const SegDesc*)(dev + o_seg), (bf16*)(wsb + wl.pk_off), (const int64_t*)(dev + o_pk), b->d_out};
         hipLaunchKernelGGL(symb_pack_bt_kernel, dim3((b->d_out + 255) / 256, bi.S), dim3(256), 0, s, pp);
         SYMB_HIP(h, hipGetLastError());
@@ -1503,22 +1517,51 @@ static symb_status adapter_grad_impl(symb_handle h, const symb_batch* b, const v
     const SegDesc* dseg = (const SegDesc*)(dev + o_seg);
     const int32_t* doff = (const int32_t*)(dev + o_off);
 
-    if (!want_b.empty()) {       // dB_i = s_i * dY_i^T H_i  ==  dY_i^T Hs_i
-        if (!reuse_hs) {
-            SkinnyParams sp{};
-            sp.L = (const bf16*)X;
-            sp.out = (bf16*)(wsb + wl.h_off);
-            sp.K = b->d_in;
-            sp.out_pitch = 2 * bi.max_rpad;
-            sp.chunks = (const RowChunk*)(dev + o_chh);
-            sp.seg = dseg;
-            sp.use_packed = 0;
-            if (seg_io) {
-                sp.L_seg = (const bf16* const*)(dev + o_xs);
-                sp.off = doff;
-            }
-            if ((st = launch_skinny(h, sp, (int)ch_h.size(), grad_max_rpad, s)) != SYMB_OK) return st;
+    auto run_skinny_h = [&]() -> symb_status {          // Hs = s X A^T of the segments that want dB
+        SkinnyParams sp{};
+        sp.L = (const bf16*)X;
+        sp.out = (bf16*)(wsb + wl.h_off);
+        sp.K = b->d_in;
+        sp.out_pitch = 2 * bi.max_rpad;
+        sp.chunks = (const RowChunk*)(dev + o_chh);
+        sp.seg = dseg;
+        sp.use_packed = 0;
+        if (seg_io) {
+            sp.L_seg = (const bf16* const*)(dev + o_xs);
+            sp.off = doff;
         }
+        return launch_skinny(h, sp, (int)ch_h.size(), grad_max_rpad, s);
+    };
+    auto run_pack = [&]() -> symb_status {
+        PackParams pp{dseg, (bf16*)(wsb + wl.pk_off), (const int64_t*)(dev + o_pk), b->d_out};
+        hipLaunchKernelGGL(symb_pack_bt_kernel, dim3((b->d_out + 255) / 256, bi.S), dim3(256), 0, s, pp);
+        SYMB_HIP(h, hipGetLastError());
+        return SYMB_OK;
+    };
+    // One pass over dY for dB and dH: when both gradients are wanted of the same segments, dH has to be
+    // computed here anyway, and the ranks fit one rank block.  The pass leaves dH in the workspace where an
+    // input-gradient call with SYMB_BWD_REUSE_DH (same batch, same dY, same workspace) takes it.
+    const bool one_pass = !reuse_dh && want_a == want_b && !want_b.empty() && bi.max_rpad == 16 && wl.dp_bytes;
+    bool have_dh = reuse_dh;
+    if (one_pass) {
+        if (!reuse_hs && (st = run_skinny_h()) != SYMB_OK) return st;
+        if ((st = run_pack()) != SYMB_OK) return st;
+        DhDbParams dp{(const bf16*)dY, (const bf16*)(wsb + wl.h_off), (const bf16*)(wsb + wl.pk_off), (const int64_t*)(dev + o_pk),
+                      b->d_out, 2 * bi.max_rpad, doff, dseg, (const GradItem*)(dev + o_itb), acc ? 1 : 0,
+                      seg_io ? (const bf16* const*)(dev + o_gs) : nullptr, (float*)(wsb + wl.gr_off), (float*)(wsb + wl.dp_off), bi.T};
+        const int groups = dhdb_groups(b->d_out);
+        if (dhdb_blocks_per_group(b->d_out) == 2) hipLaunchKernelGGL(symb_lora_dhdb_kernel<2>, dim3(groups, (unsigned)it_b.size()), dim3(256), 0, s, dp);
+        else hipLaunchKernelGGL(symb_lora_dhdb_kernel<4>, dim3(groups, (unsigned)it_b.size()), dim3(256), 0, s, dp);
+        SYMB_HIP(h, hipGetLastError());
+        if ((st = launch_grad_reduce(h, GradReduceParams{dseg, (const GradReduceItem*)(dev + o_rdb), (const float*)(wsb + wl.gr_off), b->d_out, 1, acc ? 1 : 0},
+                                     (int)red_b.size(), s)) != SYMB_OK) return st;
+        DhFinishParams fp{(const float*)(wsb + wl.dp_off), groups, bi.T, (bf16*)(wsb + wl.dh_off), 2 * bi.max_rpad,
+                          (const RowChunk*)(dev + o_chd), dseg};
+        hipLaunchKernelGGL(symb_dh_finish_kernel, dim3((unsigned)ch_dh.size()), dim3(128), 0, s, fp);
+        SYMB_HIP(h, hipGetLastError());
+        have_dh = true;
+    } else if (!want_b.empty()) {       // dB_i = s_i * dY_i^T H_i  ==  dY_i^T Hs_i
+        if (!reuse_hs && (st = run_skinny_h()) != SYMB_OK) return st;
         GradParams gp{(const bf16*)dY, (const bf16*)(wsb + wl.h_off), b->d_out, 2 * bi.max_rpad, doff, dseg,
                       (const GradItem*)(dev + o_itb), acc ? 1 : 0, seg_io ? (const bf16* const*)(dev + o_gs) : nullptr,
                       (float*)(wsb + wl.gr_off)};
@@ -1527,10 +1570,8 @@ static symb_status adapter_grad_impl(symb_handle h, const symb_batch* b, const v
                                      (int)red_b.size(), s)) != SYMB_OK) return st;
     }
     if (!want_a.empty()) {       // dA_i = dH_i^T X_i
-        if (!reuse_dh) {
-            PackParams pp{dseg, (bf16*)(wsb + wl.pk_off), (const int64_t*)(dev + o_pk), b->d_out};
-            hipLaunchKernelGGL(symb_pack_bt_kernel, dim3((b->d_out + 255) / 256, bi.S), dim3(256), 0, s, pp);
-            SYMB_HIP(h, hipGetLastError());
+        if (!have_dh) {
+            if ((st = run_pack()) != SYMB_OK) return st;
             SkinnyParams sp{};
             sp.L = (const bf16*)dY;
             sp.out = (bf16*)(wsb + wl.dh_off);

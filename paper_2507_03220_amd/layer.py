@@ -103,6 +103,7 @@ class ProjectionRun:
     def fwd(self, stream: int = 0) -> None:
         sb.symb_base_linear_fwd(self.h, self.fwd_batch, self.X, self.W, self.bias, self.Y, self.Ybase, self.ws, stream)
         self._dh_in_ws = False
+        self._dh_from_grad = False
         self._hs_in_ws = self._gather is None      # backward batch == forward batch: Hs stays valid for it
 
     def sync_saved_output(self) -> None:
@@ -110,9 +111,13 @@ class ProjectionRun:
         if self._gather is not None and self.want_ybase and self.Tb:
             torch.index_select(self.Ybase, 0, self._gather, out=self.Ybase_b)
 
-    def bwd_input(self, stream: int = 0, flags: int = sb.SYMB_BWD_FULL) -> None:
+    def bwd_input(self, stream: int = 0, flags: int = sb.SYMB_BWD_FULL, reuse_dh: bool = False) -> None:
+        """reuse_dh: the workspace still holds dH from the adapter_grad call just before (same batch, same dY)."""
+        if reuse_dh and flags == sb.SYMB_BWD_FULL and getattr(self, "_dh_from_grad", False):
+            flags |= sb.SYMB_BWD_REUSE_DH
         sb.symb_base_linear_bwd_input(self.h, self.bwd_batch, self.dY, self.W, self.dX, flags, self.ws, stream)
-        self._dh_in_ws = flags == sb.SYMB_BWD_FULL
+        self._dh_in_ws = not (flags & sb.SYMB_BWD_BASE_ONLY)
+        self._dh_from_grad = False
 
     def adapter_grad(self, stream: int = 0, flags: int = sb.SYMB_GRAD_OVERWRITE, reuse_dh: bool = False,
                      reuse_hs: bool = False) -> None:
@@ -124,6 +129,8 @@ class ProjectionRun:
             flags |= sb.SYMB_GRAD_REUSE_HS
         sb.symb_adapter_grad(self.h, self.bwd_batch, self.Xb, self.dY, self.Ybase_b, flags, self.ws, stream)
         self._dh_in_ws = False
+        # a gradient call computes dH of every LoRA segment that wants dA (all of them here) into the workspace
+        self._dh_from_grad = any(s.kind == sb.SYMB_ADAPTER_LORA for s in self.segs)
 
     # -- algorithmic work (flops) ----------------------------------------------------------------
     def flops(self) -> dict:

@@ -4,9 +4,10 @@ buffers, workspace and call sequence the bench times.
 Per projection: (1) a forward that also emits the pre-adapter output (the full-epilogue
 instantiation of the GEMM); (2) the forward exactly as the bench launches it -- no bias, no
 pre-adapter output, the whole workspace, so the plain-epilogue instantiation with its last
-round of tiles split over K ranges where the planner splits it; (3) the input gradient;
-(4) the adapter gradients taking Hs and dH from the workspace as in a bench step, and once
-more recomputing them, which must give the same bits.
+round of tiles split over K ranges where the planner splits it; (3) the adapter
+gradients as in a bench step (Hs from the workspace, dB and dH in one pass over dY); (4) the input
+gradient taking that dH; (5) the other order (input gradient first, the gradient call taking its
+dH), whose dB must have the same bits; (6) a gradient call on its own.
 
 The fp64 oracle cannot compute whole tensors at these sizes, so rows of Y, Ybase and dX are
 sampled: per segment its first two and last two rows and 28 seeded random rows, plus one
@@ -86,19 +87,12 @@ def run_projection(wl, pr):
     run.Ybase = ybase
     assert_close(_f64(run.Y.index_select(0, ridx)), Yr, f"{tag} Y (as timed)", out_bf16=True)
 
-    # ---- (3) input gradient of the fine-tuning clients only (a batch of its own)
+    # ---- (3) adapter gradients of every fine-tuning segment (a backward batch of its own), as in a bench step:
+    # Hs taken from the workspace where the backward batch is the forward batch; dB and dH in one pass
+    # over dY where the ranks allow.  The saved base output fed back for the IA3 gradients is the
+    # oracle's, rounded to bf16.
     boads = [oads[i] for i in ft]
     Xb = np.ascontiguousarray(X[np.concatenate([np.arange(off[i], off[i + 1]) for i in ft])]) if len(ft) != len(clients) else X
-    run.dX.fill_(float("nan"))
-    run.bwd_input(s)
-    torch.cuda.synchronize()
-    brows = synth.sample_rows(boff, ROWS_PER_SEGMENT, tag + "/bwd", block=ROW_BLOCK)
-    dXr = oracle.backward_input(boff, boads, dY, W, rows=brows)
-    bidx = torch.from_numpy(brows.astype(np.int64)).cuda()
-    assert_close(_f64(run.dX.index_select(0, bidx)), dXr, f"{tag} dX", out_bf16=True)
-
-    # ---- (4) adapter gradients of every fine-tuning segment; the saved base output fed back for
-    # the IA3 gradients is the oracle's, rounded to bf16
     ia3_rows = [np.arange(boff[q], boff[q + 1]) for q in range(len(ft)) if boads[q].kind == oracle.IA3]
     Y0_saved = None
     if ia3_rows:
@@ -107,30 +101,64 @@ def run_projection(wl, pr):
         Y0_saved = np.zeros((int(boff[-1]), pr.d_out), dtype=np.uint16)
         Y0_saved[need] = synth.f32_to_bf16_bits(Y0n.astype(np.float32))
         run.Ybase_b = layer.bits_to_dev(Y0_saved)
-    run.adapter_grad(s, reuse_dh=True, reuse_hs=True)        # as in a bench step
-    torch.cuda.synchronize()
-    first = [(d.dA.clone() if d.dA is not None else None, d.dB.clone() if d.dB is not None else None) for d in run.bwd_ad]
-    n_grads = 0
+    ref_grads = {}
     for q in range(len(ft)):
         a = boads[q]
-        d = run.bwd_ad[q]
         if a.kind == oracle.LORA:
-            dAr, dBr = oracle.lora_grad(boff, boads, Xb, dY, q)
-            assert_close(d.dA.cpu().numpy(), dAr, f"{tag} dA[{q}]")
-            assert_close(d.dB.cpu().numpy(), dBr, f"{tag} dB[{q}]")
-            n_grads += 1
+            ref_grads[q] = oracle.lora_grad(boff, boads, Xb, dY, q)
         elif a.kind == oracle.IA3:
             cols = np.unique(np.concatenate([[0, 1, pr.d_out - 1], np.random.default_rng(q).integers(0, pr.d_out, 61)])).astype(np.int32)
-            dlr = oracle.ia3_grad(boff, boads, Xb, dY, W, None, q, cols=cols, Y0_saved=Y0_saved)
-            assert_close(d.dA.cpu().numpy()[cols], dlr, f"{tag} dl[{q}]")
-            n_grads += 1
-    run.adapter_grad(s)                                       # stand-alone: recomputes Hs and dH
+            ref_grads[q] = (cols, oracle.ia3_grad(boff, boads, Xb, dY, W, None, q, cols=cols, Y0_saved=Y0_saved))
+
+    def check_grads(route):
+        for q, ref in ref_grads.items():
+            d = run.bwd_ad[q]
+            if boads[q].kind == oracle.LORA:
+                assert_close(d.dA.cpu().numpy(), ref[0], f"{tag} dA[{q}] ({route})")
+                assert_close(d.dB.cpu().numpy(), ref[1], f"{tag} dB[{q}] ({route})")
+            else:
+                assert_close(d.dA.cpu().numpy()[ref[0]], ref[1], f"{tag} dl[{q}] ({route})")
+
+    def nan_grads():
+        for d in run.bwd_ad:
+            for g in (d.dA, d.dB):
+                if g is not None:
+                    g.fill_(float("nan"))
+
+    nan_grads()
+    run.adapter_grad(s, reuse_hs=True)
     torch.cuda.synchronize()
-    for (a1, b1), d in zip(first, run.bwd_ad):
-        if a1 is not None:
-            assert torch.equal(a1, d.dA), f"{tag}: dA differs between the reuse and the recompute route"
+    check_grads("gradients first")
+    first_dB = [d.dB.clone() if d.dB is not None else None for d in run.bwd_ad]
+    n_grads = len(ref_grads)
+
+    # ---- (4) input gradient taking dH from that gradient call
+    brows = synth.sample_rows(boff, ROWS_PER_SEGMENT, tag + "/bwd", block=ROW_BLOCK)
+    dXr = oracle.backward_input(boff, boads, dY, W, rows=brows)
+    bidx = torch.from_numpy(brows.astype(np.int64)).cuda()
+    run.dX.fill_(float("nan"))
+    run.bwd_input(s, reuse_dh=True)
+    torch.cuda.synchronize()
+    assert_close(_f64(run.dX.index_select(0, bidx)), dXr, f"{tag} dX (as timed)", out_bf16=True)
+
+    # ---- (5) the other order: the input gradient computes dH itself, the gradient call takes it over
+    run.dX.fill_(float("nan"))
+    run.bwd_input(s)
+    torch.cuda.synchronize()
+    assert_close(_f64(run.dX.index_select(0, bidx)), dXr, f"{tag} dX", out_bf16=True)
+    nan_grads()
+    run.adapter_grad(s, reuse_dh=True, reuse_hs=True)
+    torch.cuda.synchronize()
+    check_grads("input gradient first")
+    for b1, d in zip(first_dB, run.bwd_ad):
         if b1 is not None:
-            assert torch.equal(b1, d.dB), f"{tag}: dB differs between the reuse and the recompute route"
+            assert torch.equal(b1, d.dB), f"{tag}: dB differs between the one-pass and the two-pass route"
+    # ---- (6) a gradient call on its own recomputes Hs and dH
+    nan_grads()
+    run._hs_in_ws = False
+    run.adapter_grad(s)
+    torch.cuda.synchronize()
+    check_grads("stand-alone")
     print(f"[{tag}] compared {len(rows)} rows of Y/Ybase, {len(brows)} rows of dX, gradients of {n_grads}/{len(ft)} "
           f"fine-tuning segments in {time.time() - t_start:.1f}s", flush=True)
     del run

@@ -360,7 +360,7 @@ def test_errors_enqueue_nothing_and_leave_handle_usable():
 
 
 def test_adapter_grad_can_reuse_dh_from_the_input_gradient_call():
-    """SYMB_GRAD_REUSE_DH / SYMB_GRAD_REUSE_HS: same batch, same X and dY, same workspace -> bit-identical gradients."""
+    """SYMB_GRAD_REUSE_DH / SYMB_GRAD_REUSE_HS: same batch, same X and dY, same workspace -> the same gradients."""
     p = make_problem(16, 264, 392, [150, 1, 70, 33], [L, I, L, L], [8, 24, 5])
     d_in, d_out, off = p["d_in"], p["d_out"], p["off"]
     Xd, dYd, Wd = gh.to_dev(p["X"]), gh.to_dev(p["dY"]), gh.to_dev(p["W"])
@@ -380,11 +380,18 @@ def test_adapter_grad_can_reuse_dh_from_the_input_gradient_call():
     torch.cuda.synchronize()
 
     def same(x, y):
-        for d1, d2 in zip(x.descs, y.descs):
-            if d1.dA is not None:
-                assert torch.equal(d1.dA, d2.dA)
+        # dB does not depend on where dH came from: same bits.  dA does: a stand-alone gradient call of ranks up
+        # to 16 forms dH in its one pass over dY (column blocks summed in groups), the input gradient call forms
+        # it with the shrink kernel; the two dH agree to rounding, so dA is held to the oracle's bar instead.
+        for i, (d1, d2) in enumerate(zip(x.descs, y.descs)):
             if d1.dB is not None:
                 assert torch.equal(d1.dB, d2.dB)
+            if d1.dA is not None and p["ads"][i].kind == L:
+                dAr, _ = oracle.lora_grad(off, oracle_ads(p["ads"]), p["X"], p["dY"], i, want_dB=False)
+                assert_close(d1.dA.cpu().numpy(), dAr, f"dA[{i}] stand-alone")
+                assert_close(d2.dA.cpu().numpy(), dAr, f"dA[{i}] reusing dH")
+            elif d1.dA is not None:
+                assert torch.equal(d1.dA, d2.dA)
     same(plain, reuse)
     # forward, input gradient, then gradients taking both Hs and dH from the workspace
     both = gh.upload_adapters(p["ads"], d_in, d_out, grads=True)
@@ -862,3 +869,61 @@ def test_a_handful_of_rows_in_every_call_form(lens, dims):
                                       sb.SYMB_BWD_FULL, gh.workspace(qb, sb.SYMB_OP_BWD_INPUT_INPLACE))
     torch.cuda.synchronize()
     assert_close(gather(d_in), qdXr, "small in-place dX", out_bf16=True)
+
+
+@pytest.mark.parametrize("case", [
+    dict(seed=91, d_in=264, d_out=392, lens=[150, 1, 70, 0, 33], kinds=[L, I, L, L, N], ranks=[8, 16, 5, 3]),
+    # segments summed in runs of 1024 tokens, 1100 columns (five column blocks: a full group and a group of one)
+    dict(seed=92, d_in=136, d_out=1096, lens=[1700, 3, 2100], kinds=[L, L, L], ranks=[16, 1, 12]),
+    # 256x256 tiles in the input gradient
+    dict(seed=93, d_in=6208, d_out=136, lens=[700, 5, 795], kinds=[L, N, L], ranks=[16, 8]),
+])
+def test_gradient_call_first_then_the_input_gradient_takes_its_dh(case):
+    """Ranks up to 16: symb_adapter_grad forms dB and dH in one pass over dY and leaves dH in the
+    workspace; symb_base_linear_bwd_input with SYMB_BWD_REUSE_DH takes it from there.  Gradients and dX
+    against the oracle; dB bit-identical to the two-pass route; accumulation adds."""
+    c = dict(case)
+    p = make_problem(c.pop("seed"), c.pop("d_in"), c.pop("d_out"), c.pop("lens"), c.pop("kinds"), c.pop("ranks"))
+    off, d_in, d_out, T = p["off"], p["d_in"], p["d_out"], p["T"]
+    oads = oracle_ads(p["ads"])
+    h = gh.handle()
+    Xd, dYd, Wd = gh.to_dev(p["X"]), gh.to_dev(p["dY"]), gh.to_dev(p["W"])
+    Y0r, _ = oracle.forward(off, oads, p["X"], p["W"], p["bias"])
+    Yb = gh.to_dev(synth.f32_to_bf16_bits(Y0r.astype(np.float32)))
+    dev = gh.upload_adapters(p["ads"], d_in, d_out, grads=True)
+    b = sb.Batch(d_in, d_out, off, dev.descs)
+    ws = torch.empty(max(sb.symb_workspace_bytes(b, op) for op in (sb.SYMB_OP_FWD, sb.SYMB_OP_BWD_INPUT, sb.SYMB_OP_ADAPTER_GRAD)),
+                     device="cuda", dtype=torch.uint8)
+    ws.fill_(0x7f)
+    dX = torch.full((T, d_in), float("nan"), device="cuda", dtype=torch.bfloat16)
+    sb.symb_adapter_grad(h, b, Xd, dYd, Yb, sb.SYMB_GRAD_OVERWRITE, ws)
+    sb.symb_base_linear_bwd_input(h, b, dYd, Wd, dX, sb.SYMB_BWD_FULL | sb.SYMB_BWD_REUSE_DH, ws)
+    torch.cuda.synchronize()
+    assert_close(gh.bf16_to_f64(dX), oracle.backward_input(off, oads, p["dY"], p["W"]), "dX from the gradient call's dH", out_bf16=True)
+    for i, a in enumerate(p["ads"]):
+        if a.kind == L and off[i + 1] > off[i]:
+            dAr, dBr = oracle.lora_grad(off, oads, p["X"], p["dY"], i)
+            assert_close(dev.descs[i].dA.cpu().numpy(), dAr, f"one-pass dA[{i}]")
+            assert_close(dev.descs[i].dB.cpu().numpy(), dBr, f"one-pass dB[{i}]")
+    # two-pass route: the input gradient first, the gradient call takes its dH
+    two = gh.upload_adapters(p["ads"], d_in, d_out, grads=True)
+    b2 = sb.Batch(d_in, d_out, off, two.descs)
+    sb.symb_base_linear_bwd_input(h, b2, dYd, Wd, dX, sb.SYMB_BWD_FULL, ws)
+    sb.symb_adapter_grad(h, b2, Xd, dYd, Yb, sb.SYMB_GRAD_OVERWRITE | sb.SYMB_GRAD_REUSE_DH, ws)
+    torch.cuda.synchronize()
+    for d1, d2 in zip(dev.descs, two.descs):
+        if d1.dB is not None:
+            assert torch.equal(d1.dB, d2.dB), "dB must not depend on the route"
+    # accumulate on top of the first result
+    once = [(d.dA.clone() if d.dA is not None else None, d.dB.clone() if d.dB is not None else None) for d in dev.descs]
+    sb.symb_adapter_grad(h, b, Xd, dYd, Yb, sb.SYMB_GRAD_ACCUMULATE, ws)
+    torch.cuda.synchronize()
+    for (a1, b1), d in zip(once, dev.descs):
+        if a1 is not None:
+            assert torch.equal(d.dA, a1 + a1)
+        if b1 is not None:
+            assert torch.equal(d.dB, b1 + b1)
+    # the flag is refused where it makes no sense
+    with pytest.raises(sb.SymbError) as e:
+        sb.symb_base_linear_bwd_input(h, b, dYd, Wd, dX, sb.SYMB_BWD_BASE_ONLY | sb.SYMB_BWD_REUSE_DH, ws)
+    assert e.value.status == sb.SYMB_ERR_INVALID_ARG
