@@ -219,6 +219,25 @@ int gemm_variant(int M, int N) {
 }
 int gemm_tile_m(int M, int N) { return gemm_variant(M, N) == 3 ? 256 : 128; }
 
+// Row tiles per group of the tile walk (a group is walked column by column, so the 32 tiles an XCD runs
+// at once are g row tiles x 32 / g column tiles).  Measured on the Gemma2-27B-shaped launches (80 row
+// tiles), GEMM calls of a step summed: g = 5 32.7 ms, 4 32.9, 6 33.1, 8 33.3, 10 33.1, 7 33.6, 16 34+:
+// small groups win (most on the long-K shapes, 2-3 %), and a g that does not divide the row tiles loses
+// (ragged last group, groups straddling the XCDs' runs).  That holds for launches of many rounds whose
+// tiles cost the same.  Where row tiles differ (a mixed batch: a row tile of dozens of one-token LoRA
+// segments takes far longer than one inside a long segment) small groups put more column tiles of the
+// slowest row tile side by side and lose (+6 % on the mixed workload's step), and launches of two or
+// three rounds do not care.  So: 8 unless the launch has at least five rounds per XCD and at most two
+// segments per row tile; then the divisor of the row-tile count nearest 5 among 3..8, else 4.
+int gemm_group_m(int num_m_tiles, int num_n_tiles, const std::vector<int32_t>& seg_lo, const std::vector<int32_t>& seg_hi) {
+    int most = 0;
+    for (size_t u = 0; u < seg_lo.size(); ++u) most = std::max(most, seg_hi[u] - seg_lo[u] + 1);
+    if (most > 2 || ((long)num_m_tiles * num_n_tiles + 7) / 8 < 160) return 8;
+    for (int g : {5, 4, 6, 3, 8, 7})
+        if (num_m_tiles % g == 0) return g;
+    return 4;
+}
+
 // K-split.  Every XCD walks a contiguous run of per_xcd = ceil(tiles / 8) tiles; the tiles of that run
 // from number `whole` on are computed by `parts` workgroups each, one per K range, which leave fp32
 // partial tiles in the workspace; the last one to arrive adds them up in part order and writes the
@@ -503,7 +522,8 @@ symb_status launch_gemm_fn(symb_handle h, GemmParams gp, hipStream_t st, KFN kfn
     }
     gp.num_m_tiles = (gp.M + BM - 1) / BM;
     gp.num_n_tiles = (gp.N + BN - 1) / BN;
-    gp.group_m = 8;
+    if (h->opt_experiment >> 8) gp.group_m = h->opt_experiment >> 8;
+    if (gp.group_m <= 0) gp.group_m = 8;
     const int total = gp.num_m_tiles * gp.num_n_tiles;
     const int per_xcd = (total + 7) / 8;
     int grid = per_xcd * 8;
@@ -1038,6 +1058,7 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     gp.tile_epi = (const int32_t*)(dev + o_te);
     gp.neff = nd.empty() ? nullptr : (const NoiseDesc*)(dev + o_nd);
     gp.timing_flops = gemm_flops(b, b->d_out, b->d_in, bi.n_lora > 0);
+    gp.group_m = gemm_group_m((bi.T + bm - 1) / bm, (b->d_out + bm - 1) / bm, lo, hi);
     if (k_split) {
         gp.k_parts = ksp.parts;
         gp.k_whole = ksp.whole;
@@ -1338,6 +1359,7 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
     gp.epi_ia3 = (full && bi.n_ia3in > 0) ? KIND_IA3_IN : 0;      // dX rows of IA3_IN segments: l_i * (dY W)
     gp.tile_epi = (const int32_t*)(dev + o_te);
     gp.timing_flops = gemm_flops(b, b->d_in, b->d_out, lora);
+    gp.group_m = gemm_group_m((bi.T + bm - 1) / bm, (b->d_in + bm - 1) / bm, lo, hi);
     if (k_split) {
         gp.k_parts = ksp.parts;
         gp.k_whole = ksp.whole;
