@@ -67,7 +67,6 @@ struct symb_context {
     std::string error;
     // measurement switches (symb_debug_set_option); all on by default
     bool opt_desc_reuse = true, opt_k_split = true, opt_small_rows = true, opt_skinny_deep = true;
-    int opt_experiment = 0;
     // Whether workgroup id mod 8 names the XCD a workgroup runs on, measured at creation: the K-split of
     // the GEMM keeps all parts of a tile on one XCD (behind one L2) and is used only if this holds.
     bool xcd_rule = false;
@@ -522,7 +521,6 @@ symb_status launch_gemm_fn(symb_handle h, GemmParams gp, hipStream_t st, KFN kfn
     }
     gp.num_m_tiles = (gp.M + BM - 1) / BM;
     gp.num_n_tiles = (gp.N + BN - 1) / BN;
-    if (h->opt_experiment >> 8) gp.group_m = h->opt_experiment >> 8;
     if (gp.group_m <= 0) gp.group_m = 8;
     const int total = gp.num_m_tiles * gp.num_n_tiles;
     const int per_xcd = (total + 7) / 8;
@@ -727,7 +725,6 @@ symb_status symb_debug_set_option(symb_handle h, int32_t option, int32_t value) 
         case SYMB_OPT_K_SPLIT: h->opt_k_split = value != 0; break;
         case SYMB_OPT_SMALL_BATCH_KERNELS: h->opt_small_rows = value != 0; break;
         case SYMB_OPT_SKINNY_DEEP: h->opt_skinny_deep = value != 0; break;
-        case 100: h->opt_experiment = value; break;
         default: return fail(h, SYMB_ERR_INVALID_ARG, "unknown option %d", option);
     }
     return SYMB_OK;
