@@ -157,15 +157,19 @@ symb_status symb_plan_row_tiles(const symb_batch* b, int32_t tile_m, int32_t* se
  * fp32 partial tiles: such a call computes output tiles in several workgroups, one per
  * range of the inner dimension -- every tile of a batch of a few hundred rows (which alone
  * would leave most of the chip idle), or the tiles of a last round of workgroups that
- * would be partly empty (up to 160 MiB).  That region is optional: a workspace that
- * covers everything before it (in particular none at all for a batch without adapters)
- * makes the call run without the split, only slower; anything smaller fails with
- * SYMB_ERR_WORKSPACE_TOO_SMALL.  Every call is deterministic (the same arguments give the
+ * would be partly empty (up to 160 MiB).  Before it, for a batch of at most 16 rows, come
+ * the regions of the weight-streaming kernels such calls take (a flat copy of the rows and,
+ * where the weight is read N-contiguous, up to 8 MiB of fp32 partial sums per K range).  These
+ * trailing regions are optional: a workspace that covers everything before them (in
+ * particular none at all for a batch without adapters) makes the call take the tiled kernel
+ * without the split, only slower; anything smaller fails with SYMB_ERR_WORKSPACE_TOO_SMALL.
+ * The figure depends on the batch and the operation alone (not on the handle or its options).  Every call is deterministic (the same arguments give the
  * same bits, whatever order the workgroups finish in); a split call sums the inner dimension
  * in a different order than an unsplit one, so the two can differ in the last rounding.  For
  * SYMB_OP_ADAPTER_GRAD the figure includes room for the partial sums of LoRA gradients of
  * segments longer than 1536 tokens (summed in runs of 1024 tokens, the runs added in order: a
- * segment's gradient does not depend on what else is in the batch). */
+ * segment's gradient does not depend on what else is in the batch) and, for ranks up to 16 on
+ * layers at least 16384 wide, for the partial sums of dH of the pass that forms dB and dH together. */
 symb_status symb_workspace_bytes(const symb_batch* b, int32_t op, size_t* out);
 
 /*
