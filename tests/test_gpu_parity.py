@@ -877,11 +877,16 @@ def test_a_handful_of_rows_in_every_call_form(lens, dims):
     dict(seed=92, d_in=136, d_out=1096, lens=[1700, 3, 2100], kinds=[L, L, L], ranks=[16, 1, 12]),
     # 256x256 tiles in the input gradient
     dict(seed=93, d_in=6208, d_out=136, lens=[700, 5, 795], kinds=[L, N, L], ranks=[16, 8]),
+    # layers wide enough for the one-pass dB + dH kernel (at least 64 column blocks of 256): ragged token counts,
+    # one-token and empty segments, a last group of one column block with 8 columns, ranks 1..16
+    dict(seed=94, d_in=72, d_out=16648, lens=[150, 1, 70, 0, 33], kinds=[L, L, L, L, N], ranks=[8, 16, 5, 3]),
+    # ... and segments summed in runs of 1024 tokens
+    dict(seed=95, d_in=40, d_out=16384, lens=[1700, 40, 1537], kinds=[L, L, L], ranks=[16, 1, 12]),
 ])
 def test_gradient_call_first_then_the_input_gradient_takes_its_dh(case):
-    """Ranks up to 16: symb_adapter_grad forms dB and dH in one pass over dY and leaves dH in the
-    workspace; symb_base_linear_bwd_input with SYMB_BWD_REUSE_DH takes it from there.  Gradients and dX
-    against the oracle; dB bit-identical to the two-pass route; accumulation adds."""
+    """symb_adapter_grad leaves dH in the workspace and symb_base_linear_bwd_input with SYMB_BWD_REUSE_DH
+    takes it from there; on wide layers with ranks up to 16 the gradient call forms dB and dH in one pass
+    over dY.  Gradients and dX against the oracle; dB bit-identical to the two-pass route; accumulation adds."""
     c = dict(case)
     p = make_problem(c.pop("seed"), c.pop("d_in"), c.pop("d_out"), c.pop("lens"), c.pop("kinds"), c.pop("ranks"))
     off, d_in, d_out, T = p["off"], p["d_in"], p["d_out"], p["T"]
