@@ -3,6 +3,8 @@ callers that cannot allocate) against symb_base_linear_fwd on the same inputs, t
 two calls in a row on one handle, the second with a smaller batch, so that whatever the first call
 left in the shared array is there when the second runs.  The two entry points launch the same
 kernels, so the outputs must agree bit for bit; the first call is also held to the oracle's bar."""
+import gc
+
 import numpy as np
 import pytest
 import torch
@@ -49,11 +51,15 @@ def _both(h, p, want_base):
     ws = torch.empty(sb.SYMB_STATIC_SCRATCH_BYTES, device="cuda", dtype=torch.uint8)
     sb.symb_base_linear_fwd(h, batch, Xd, Wd, bd, Y1, B1, ws, gh.stream_ptr())
     torch.cuda.synchronize()
-    free_before, held_before = torch.cuda.mem_get_info()[0], torch.cuda.memory_allocated()
+    # Allocation events are counted, not bytes held: after other tests the collector may free their tensors
+    # at any moment, which lowers the bytes held (and can only raise the device's free memory).
+    events = lambda: torch.cuda.memory_stats().get("allocation.all.allocated", 0)
+    gc.collect()
+    free_before, events_before = torch.cuda.mem_get_info()[0], events()
     sb.symb_base_linear_fwd_static(h, batch, Xd, Wd, bd, Y2, B2, gh.stream_ptr())
     torch.cuda.synchronize()
     # nothing was allocated on the device, by torch or behind its back
-    assert torch.cuda.memory_allocated() == held_before and torch.cuda.mem_get_info()[0] >= free_before
+    assert events() == events_before and torch.cuda.mem_get_info()[0] >= free_before
     return Y1, Y2, B1, B2
 
 
