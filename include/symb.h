@@ -134,7 +134,9 @@ typedef struct symb_context* symb_handle;
  * device ring, 32 slots of 2 MiB each).  The only call that allocates.  A later call
  * whose offsets, adapters and buffers give the same descriptor bytes as an earlier call
  * on the same stream reads the copy already on the device instead of sending it again.
- * SYMB_ERR_DEVICE if HIP fails. */
+ * A call's descriptors (about 170 bytes per segment plus 16 per row tile and row chunk) must fit
+ * one slot: batches beyond roughly 12 000 segments are refused with SYMB_ERR_UNSUPPORTED before
+ * anything is launched.  SYMB_ERR_DEVICE if HIP fails. */
 symb_status symb_create(symb_handle* out, int device);
 symb_status symb_destroy(symb_handle h);
 

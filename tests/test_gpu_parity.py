@@ -932,3 +932,41 @@ def test_gradient_call_first_then_the_input_gradient_takes_its_dh(case):
     with pytest.raises(sb.SymbError) as e:
         sb.symb_base_linear_bwd_input(h, b, dYd, Wd, dX, sb.SYMB_BWD_BASE_ONLY | sb.SYMB_BWD_REUSE_DH, ws)
     assert e.value.status == sb.SYMB_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("case", [
+    # the 128x128 tile: about 60 segments per row tile
+    dict(seed=101, S=2000, d_in=264, d_out=392),
+    # the 256x256 tile in the forward (one LoRA step fetched while another multiplies), about 110 segments per row tile
+    dict(seed=102, S=1000, d_in=136, d_out=6208),
+])
+def test_thousands_of_clients_of_a_few_tokens_each(case):
+    """A decode-heavy batch (Sec. 3.7: many inference clients, a token or a few each, batched per layer):
+    thousands of segments of 0..9 rows with every adapter kind and ranks 3..16, each with buffers of its
+    own, so that every row tile holds dozens of segments.  Everything against the oracle in full."""
+    rng = np.random.default_rng(case["seed"])
+    lens = [int(x) for x in rng.choice([0, 1, 1, 1, 1, 2, 3, 9], case["S"])]
+    p = make_problem(case["seed"], case["d_in"], case["d_out"], lens, [L, L, I, N, L], [4, 8, 16, 3])
+    print(f"[many clients] S={case['S']} T={p['T']} {case['d_in']}->{case['d_out']}", flush=True)
+    check_all(p, f"{case['S']} clients")
+
+
+def test_more_segments_than_the_descriptor_slot_holds_are_refused():
+    """The per-call descriptors of a batch must fit one 2 MiB slot of the descriptor ring: a batch of
+    40000 segments is refused with SYMB_ERR_UNSUPPORTED before anything is launched, and the handle
+    keeps working."""
+    h = gh.handle()
+    S = 40000
+    off = np.arange(S + 1, dtype=np.int32)
+    b = sb.Batch(64, 64, off, [sb.Adapter() for _ in range(S)])
+    X = torch.zeros((S, 64), device="cuda", dtype=torch.bfloat16)
+    W = torch.zeros((64, 64), device="cuda", dtype=torch.bfloat16)
+    Y = torch.full((S, 64), float("nan"), device="cuda", dtype=torch.bfloat16)
+    ws = torch.empty(max(1, sb.symb_workspace_bytes(b, sb.SYMB_OP_FWD)), device="cuda", dtype=torch.uint8)
+    with pytest.raises(sb.SymbError) as e:
+        sb.symb_base_linear_fwd(h, b, X, W, None, Y, None, ws)
+    assert e.value.status == sb.SYMB_ERR_UNSUPPORTED and "capacity" in str(e.value)
+    torch.cuda.synchronize()
+    assert torch.isnan(Y.float()).all(), "a refused call must leave its output untouched"
+    p = make_problem(7, 64, 72, [5, 3], [L, N], [8])
+    check_all(p, "after a refused call")
