@@ -36,10 +36,7 @@ struct SkinnyParams {
     const int32_t* off;       // device [S+1] (read only with L_seg)
 };
 
-#ifndef SYMB_SKINNY_BLKS
-#define SYMB_SKINNY_BLKS 2
-#endif
-constexpr int SKINNY_BLKS = SYMB_SKINNY_BLKS;          // 16-row MFMA blocks per wavefront
+constexpr int SKINNY_BLKS = 2;                         // 16-row MFMA blocks per wavefront
 constexpr int SKINNY_ROWS = 16 * SKINNY_BLKS;          // rows per workgroup
 
 // The skinny kernel's row stream.  A lane of an MFMA operand holds 16 bytes of one row, so fragment
