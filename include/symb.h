@@ -239,8 +239,11 @@ symb_status symb_base_linear_bwd_input_ex(symb_handle h, const symb_batch* b, co
  * the call, no split after it.  The arrays are HOST arrays of num_segments DEVICE pointers (dense
  * bf16 rows, 16-byte aligned; an empty segment's entry is ignored).  The input buffers of one call
  * must lie within one 4 GiB window (SYMB_ERR_UNSUPPORTED otherwise): carve them from one arena.
- * No Ybase / dXbase output and no IA3 input scaling in this form (a client that needs Ybase for an
- * IA3 gradient keeps its own output of an all-NONE call, which is the paper's flow).
+ * With an IA3_IN segment in the batch the forward multiplies a flat, scaled copy of all rows (in the
+ * workspace, as the flat call does) and the window rule does not apply.  No Ybase / dXbase output in
+ * this form: a client that needs the pre-adapter output for an IA3 gradient keeps its own output of
+ * an all-NONE call, one that needs the input gradient before the input scale for an IA3_IN gradient
+ * keeps the rows a SYMB_BWD_BASE_ONLY call wrote for it, which is the paper's flow (Sec. 3.6).
  *
  * One buffer per client for both directions (Sec. 3.5: each client pre-allocates a single tensor of
  * batch x sequence x max(d_in, d_out) elements and every layer's input and output travel through
@@ -259,8 +262,11 @@ symb_status symb_base_linear_fwd_seg(symb_handle h, const symb_batch* b, const v
 symb_status symb_base_linear_bwd_input_seg(symb_handle h, const symb_batch* b, const void* const* dY_seg,
                                            const void* W, void* const* dX_seg, uint32_t flags, void* ws,
                                            size_t ws_bytes, void* stream);
-/* Adapter gradients from per-client buffers (Ybase_seg may be NULL if no IA3 segment wants dl; no
- * window restriction here; the SYMB_GRAD_REUSE_* flags work as in the flat call). */
+/* Adapter gradients from per-client buffers.  Ybase_seg[i] is what client i kept for its dl: the
+ * pre-adapter output rows [n_i][d_out] of an IA3 segment, the rows [n_i][d_in] of the input gradient
+ * before the input scale (dY W) of an IA3_IN segment; ignored for other segments; the array may be
+ * NULL if no such segment wants dl.  No window restriction here; the SYMB_GRAD_REUSE_* flags work as
+ * in the flat call. */
 symb_status symb_adapter_grad_seg(symb_handle h, const symb_batch* b, const void* const* X_seg,
                                   const void* const* dY_seg, const void* const* Ybase_seg, uint32_t flags,
                                   void* ws, size_t ws_bytes, void* stream);

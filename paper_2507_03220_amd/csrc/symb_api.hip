@@ -911,8 +911,8 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     const void* x_base = nullptr;
     if (seg_io) {
         if (!Y_seg || !W) return fail(h, SYMB_ERR_INVALID_ARG, "X_seg, Y_seg and W are required");
-        if (bi.n_ia3in) return fail(h, SYMB_ERR_UNSUPPORTED, "IA3 input scaling is not available with per-segment buffers");
-        if ((st = check_seg_ptrs(h, b, X_seg, (size_t)b->d_in * 2, "X", true, &x_base)) != SYMB_OK) return st;
+        // with an IA3_IN segment the GEMM reads a flat, scaled copy of the rows: no window needed then
+        if ((st = check_seg_ptrs(h, b, X_seg, (size_t)b->d_in * 2, "X", bi.n_ia3in == 0, &x_base)) != SYMB_OK) return st;
         if ((st = check_seg_ptrs(h, b, (const void* const*)Y_seg, (size_t)b->d_out * 2, "Y", false, nullptr)) != SYMB_OK) return st;
     } else if (!X || !W || !Y) return fail(h, SYMB_ERR_INVALID_ARG, "X, W and Y are required");
     std::vector<NoiseDesc> nd;
@@ -1033,9 +1033,11 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
     GemmParams gp{};
     gp.Aop = x_op;
     if (seg_io) {
-        gp.Aop = nullptr;
-        gp.a_seg = (const bf16* const*)(dev + o_xs);
-        gp.a_base = (const bf16*)x_base;
+        if (!copy_rows) {          // (a flat copy of the rows, scaled for IA3_IN, is read as one tensor)
+            gp.Aop = nullptr;
+            gp.a_seg = (const bf16* const*)(dev + o_xs);
+            gp.a_base = (const bf16*)x_base;
+        }
         if (!staged) gp.c_seg = (bf16* const*)(dev + o_ys);
     }
     gp.Bop = (const bf16*)W;
@@ -1411,14 +1413,16 @@ static symb_status adapter_grad_impl(symb_handle h, const symb_batch* b, const v
     const BatchInfo bi = inspect(b);
     const bool seg_io = X_seg != nullptr;
     if (seg_io) {
-        if (bi.n_ia3in) return fail(h, SYMB_ERR_UNSUPPORTED, "IA3 input scaling is not available with per-segment buffers");
         if ((st = check_seg_ptrs(h, b, X_seg, (size_t)b->d_in * 2, "X", false, nullptr)) != SYMB_OK) return st;
         if ((st = check_seg_ptrs(h, b, dY_seg, (size_t)b->d_out * 2, "dY", false, nullptr)) != SYMB_OK) return st;
         if (Ybase_seg) {
-            for (int i = 0; i < bi.S; ++i)
-                if (b->adapters[i].kind == SYMB_ADAPTER_IA3 && b->adapters[i].dA && b->seg_offsets[i + 1] > b->seg_offsets[i] &&
+            // what the client kept for dl: the pre-adapter output rows (IA3), the input gradient before the input scale (IA3_IN)
+            for (int i = 0; i < bi.S; ++i) {
+                const int k = b->adapters[i].kind;
+                if ((k == SYMB_ADAPTER_IA3 || k == SYMB_ADAPTER_IA3_IN) && b->adapters[i].dA && b->seg_offsets[i + 1] > b->seg_offsets[i] &&
                     (!Ybase_seg[i] || misaligned16(Ybase_seg[i])))
-                    return fail(h, SYMB_ERR_INVALID_ARG, "Ybase of IA3 segment %d is null or misaligned", i);
+                    return fail(h, SYMB_ERR_INVALID_ARG, "the saved rows of IA3 segment %d are null or misaligned", i);
+            }
         }
     } else if (!X || !dY) {
         if (bi.T > 0) return fail(h, SYMB_ERR_INVALID_ARG, "X and dY are required");
@@ -1458,7 +1462,7 @@ static symb_status adapter_grad_impl(symb_handle h, const symb_batch* b, const v
             want_lin.push_back(i);
         }
     }
-    if (!want_lin.empty() && !dXbase)
+    if (!want_lin.empty() && !(seg_io ? (const void*)Ybase_seg : dXbase))
         return fail(h, SYMB_ERR_INVALID_ARG, "an IA3_IN segment wants dl but dXbase (the input gradient before the input scale) is null");
     if (!want_l.empty() && !(seg_io ? (const void*)Ybase_seg : Ybase))
         return fail(h, SYMB_ERR_INVALID_ARG, "an IA3 segment wants dl but Ybase (the pre-adapter output) is null");
@@ -1622,7 +1626,7 @@ static symb_status adapter_grad_impl(symb_handle h, const symb_batch* b, const v
     }
     if (!want_lin.empty()) {     // dl_i[k] = sum_t X[t][k] * (dY W)[t][k]: the same reduction over the input width
         Ia3GradParams ip{(const bf16*)X, (const bf16*)dXbase, b->d_in, doff, dseg, (const int32_t*)(dev + o_wli), acc ? 1 : 0,
-                         nullptr, nullptr};
+                         seg_io ? (const bf16* const*)(dev + o_xs) : nullptr, seg_io ? (const bf16* const*)(dev + o_ys) : nullptr};
         hipLaunchKernelGGL(symb_ia3_grad_kernel, dim3((b->d_in + IA3_GRAD_COLS - 1) / IA3_GRAD_COLS, (unsigned)want_lin.size()), dim3(256), 0, s, ip);
         SYMB_HIP(h, hipGetLastError());
     }

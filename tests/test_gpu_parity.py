@@ -545,6 +545,10 @@ def test_ia3_input_scaling(case):
     # 266 tiles of 256x256 with the last round split over K ranges, rows from and to per-client buffers
     dict(seed=64, d_in=2056, d_out=33800, lens=[120, 1, 99, 80], kinds=[L, I, L, N], ranks=[16, 8, 40]),
     dict(seed=65, d_in=33800, d_out=2056, lens=[120, 1, 99, 80], kinds=[L, N, L, L], ranks=[16, 8, 40, 24]),
+    # IA3 on the input (kind 3) among the clients: the forward multiplies a flat scaled copy of the rows
+    dict(seed=66, d_in=320, d_out=264, lens=[130, 1, 0, 77, 1, 300, 64], kinds=[L, 3, L, N, 3, I, 3], ranks=[8, 16, 5]),
+    dict(seed=67, d_in=136, d_out=6208, lens=[700, 5, 795], kinds=[3, L, 3], ranks=[16]),
+    dict(seed=68, d_in=6208, d_out=136, lens=[700, 5, 795], kinds=[L, 3, 3], ranks=[12]),
 ])
 def test_per_segment_buffers(case):
     """Rows read from and written to one buffer per client, carved in shuffled order and with gaps
@@ -604,7 +608,11 @@ def test_per_segment_buffers(case):
     Y0_saved = synth.f32_to_bf16_bits(Y0r.astype(np.float32))
     _, Gv = carve(d_out, p["dY"])
     _, Y0v = carve(d_out, Y0_saved)
-    sb.symb_adapter_grad_seg(h, bg, Xv, Gv, Y0v, sb.SYMB_GRAD_OVERWRITE, gh.workspace(bg, sb.SYMB_OP_ADAPTER_GRAD))
+    # a client with IA3 on the input kept its rows of the input gradient before the scale instead (oracle's, in bf16)
+    G_saved = synth.f32_to_bf16_bits(oracle.backward_input(off, oads, p["dY"], p["W"], base_only=True).astype(np.float32))
+    _, G0v = carve(d_in, G_saved)
+    saved = [G0v[i] if a.kind == 3 else Y0v[i] for i, a in enumerate(p["ads"])]
+    sb.symb_adapter_grad_seg(h, bg, Xv, Gv, saved, sb.SYMB_GRAD_OVERWRITE, gh.workspace(bg, sb.SYMB_OP_ADAPTER_GRAD))
     torch.cuda.synchronize()
     for i, a in enumerate(p["ads"]):
         if off[i + 1] == off[i]:
@@ -616,6 +624,11 @@ def test_per_segment_buffers(case):
         elif a.kind == I:
             dlr = oracle.ia3_grad(off, oads, p["X"], p["dY"], p["W"], p["bias"], i, Y0_saved=Y0_saved)
             assert_close(grads.descs[i].dA.cpu().numpy(), dlr, f"per-segment dl[{i}]")
+        elif a.kind == 3:
+            dlr = oracle.ia3_grad(off, oads, p["X"], p["dY"], p["W"], p["bias"], i, G_saved=G_saved)
+            assert_close(grads.descs[i].dA.cpu().numpy(), dlr, f"per-segment dl (input scaling) [{i}]")
+    if any(a.kind == 3 for a in p["ads"]):
+        return                                      # (no window rule for the forward's inputs then)
     # buffers more than 4 GiB apart are refused before any launch (fake addresses: nothing is dereferenced)
     far = [int(Xv[i].data_ptr()) if Xv[i] is not None else 0 for i in range(S)]
     first = next(i for i in range(S) if Xv[i] is not None)
