@@ -665,8 +665,8 @@ symb_lora_grad_kernel(const GradParams p) {
         for (int j = 0; j < RB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     // R tile: 32 rows x CT/8 chunks of 8 columns, NRC per thread.  L tile: 32 x (rpad/4) chunks,
-    // at most NLC per thread.  Three register sets: the chunks of tokens t0 + 64 are requested while the
-    // step at t0 multiplies, so a request has two steps to arrive (a step is far shorter than the memory
+    // at most NLC per thread.  Two register sets: the chunks of tokens t0 + 64 are requested as soon as those
+    // of t0 are in LDS (their set is free then), so a request has two steps to arrive (a step is far shorter than the memory
     // latency, and a launch over a few segments has too few workgroups per CU to hide it otherwise).
     // Every load is unconditional: out-of-range chunks read a valid address and count as zero when they go
     // to LDS, two steps later.  (With the zeroing next to the load the compiler puts the load under the
@@ -723,21 +723,22 @@ symb_lora_grad_kernel(const GradParams p) {
         }
     };
     if (t_lo < t_hi) {
-        Stage sg0, sg1, sg2;
+        Stage sg0, sg1;
         fetch(sg0, t_lo);
         fetch(sg1, t_lo + GRAD_TT);
-        // cur was requested two fetches ago: the compiler's wait for it leaves the newest fetch in flight
-        auto step = [&](Stage& cur, Stage& nxt, int t0) __attribute__((always_inline)) {
+        // Two register sets, two tiles in flight: a set is free again as soon as its tile is in LDS, so the
+        // tile two steps ahead is requested into it; cur was requested two fetches ago, and the wait for it
+        // leaves the newest fetch in flight.
+        auto step = [&](Stage& cur, int t0) __attribute__((always_inline)) {
             __syncthreads();     // previous step's LDS reads are done
             put(cur, t0);
             __syncthreads();
-            fetch(nxt, t0 + 2 * GRAD_TT);
+            fetch(cur, t0 + 2 * GRAD_TT);
             multiply();
         };
-        for (int t0 = t_lo; t0 < t_hi; t0 += 3 * GRAD_TT) {
-            step(sg0, sg2, t0);
-            if (t0 + GRAD_TT < t_hi) step(sg1, sg0, t0 + GRAD_TT);
-            if (t0 + 2 * GRAD_TT < t_hi) step(sg2, sg1, t0 + 2 * GRAD_TT);
+        for (int t0 = t_lo; t0 < t_hi; t0 += 2 * GRAD_TT) {
+            step(sg0, t0);
+            if (t0 + GRAD_TT < t_hi) step(sg1, t0 + GRAD_TT);
         }
     }
     float* out = it.direct ? (CMAJOR ? sd.dB : sd.dA) : p.partial + it.partial_off;
@@ -900,23 +901,23 @@ symb_lora_dhdb_kernel(const DhDbParams p) {
                 dh[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, btf[g][ks]), __builtin_bit_cast(bf16x8, yv), dh[tb], 0, 0, 0);
             }
     };
-    // One tile = (token step, column block), blocks fastest.  Three register sets: the tile two ahead is
-    // requested while the current one multiplies.
+    // One tile = (token step, column block), blocks fastest.  Two register sets, the tile two ahead is
+    // requested as soon as the current one is in LDS.
     auto advance = [&](int& t0, int& g) __attribute__((always_inline)) {
         if (++g == ncb) { g = 0; t0 += GRAD_TT; }
     };
     if (t_lo < t_hi) {
-        Stage sg0, sg1, sg2;
+        Stage sg0, sg1;
         int ft = t_lo, fg = 0;                           // the next tile to request
         fetch(sg0, ft, fg); advance(ft, fg);
         fetch(sg1, ft, fg); advance(ft, fg);
         int t0 = t_lo, g = 0;                            // the tile being computed
-        auto step = [&](Stage& cur, Stage& nxt) __attribute__((always_inline)) {
+        auto step = [&](Stage& cur) __attribute__((always_inline)) {
             if (g == 0) dh[0] = dh[1] = floatx4{0.f, 0.f, 0.f, 0.f};
             __syncthreads();                             // the previous tile's LDS reads are done
             put(cur, t0, g);
             __syncthreads();
-            fetch(nxt, ft, fg); advance(ft, fg);
+            fetch(cur, ft, fg); advance(ft, fg);         // the set is free again: the tile two steps ahead goes into it
             // the block index selects registers: dispatch on it (uniform)
             grad_static_for<0, G>([&](auto GC) __attribute__((always_inline)) {
                 if (g == decltype(GC)::value) multiply(GC);
@@ -943,9 +944,8 @@ symb_lora_dhdb_kernel(const DhDbParams p) {
             advance(t0, g);
         };
         while (t0 < t_hi) {
-            step(sg0, sg2);
-            if (t0 < t_hi) step(sg1, sg0);
-            if (t0 < t_hi) step(sg2, sg1);
+            step(sg0);
+            if (t0 < t_hi) step(sg1);
         }
     }
     // ---- dB of every block, as symb_lora_grad_kernel<1, true> writes it
