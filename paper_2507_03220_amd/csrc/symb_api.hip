@@ -983,8 +983,10 @@ static symb_status forward_impl(symb_handle h, const symb_batch* b, const void* 
         ScaleParams sc{(const bf16*)X, copy, b->d_in, (const RowChunk*)(dev + o_all),
                        (const SegDesc*)(dev + o_seg), KIND_IA3_IN, seg_io ? (const bf16* const*)(dev + o_xs) : nullptr,
                        (const int32_t*)(dev + o_off)};
-        hipLaunchKernelGGL(symb_ia3_scale_rows_kernel, dim3((unsigned)all_chunks.size()), dim3(256), 0, s, sc);
-        SYMB_HIP(h, hipGetLastError());
+        if (!all_chunks.empty()) {
+            hipLaunchKernelGGL(symb_ia3_scale_rows_kernel, dim3((unsigned)all_chunks.size()), dim3(256), 0, s, sc);
+            SYMB_HIP(h, hipGetLastError());
+        }
         x_op = copy;
     }
     bf16* Hs = bi.n_lora ? (bf16*)(wsb + wl.h_off) : nullptr;
@@ -1312,8 +1314,10 @@ static symb_status backward_input_impl(symb_handle h, const symb_batch* b, const
         bf16* const copy = (bf16*)(wsb + (small_copy ? wl.sg_off : wl.sc_off));
         ScaleParams sc{(const bf16*)dY, copy, b->d_out, (const RowChunk*)(dev + o_all), (const SegDesc*)(dev + o_seg),
                        ia3 ? (int)KIND_IA3 : -1, seg_io ? (const bf16* const*)(dev + o_gs) : nullptr, (const int32_t*)(dev + o_off)};
-        hipLaunchKernelGGL(symb_ia3_scale_rows_kernel, dim3((unsigned)all_chunks.size()), dim3(256), 0, s, sc);
-        SYMB_HIP(h, hipGetLastError());
+        if (!all_chunks.empty()) {          // (every IA3 segment of the batch may be empty: nothing to scale then)
+            hipLaunchKernelGGL(symb_ia3_scale_rows_kernel, dim3((unsigned)all_chunks.size()), dim3(256), 0, s, sc);
+            SYMB_HIP(h, hipGetLastError());
+        }
         a_op = copy;
     }
     if (small) {
