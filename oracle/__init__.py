@@ -100,8 +100,14 @@ def row_segment_map(off) -> np.ndarray:
 
 
 def forward(off, adapters: Sequence[Adapter], X: np.ndarray, W: np.ndarray,
-            bias: Optional[np.ndarray] = None, rows=None):
-    """Returns (Y0, Y) as fp64 [nrows, d_out] for the listed rows (default: all)."""
+            bias: Optional[np.ndarray] = None, rows=None, client_bf16: bool = False):
+    """Returns (Y0, Y) as fp64 [nrows, d_out] for the listed rows (default: all).  client_bf16: the
+    product x * l_i of IA3_IN segments is the bf16 tensor the paper's client would send (client_scale);
+    Y0 stays the base output of the unscaled input."""
+    if client_bf16 and any(a.kind == IA3_IN for a in adapters):
+        Y0, _ = forward(off, adapters, X, W, bias, rows=rows)
+        _, Y = forward(off, _without(adapters, IA3_IN), client_scale(off, adapters, X, IA3_IN), W, bias, rows=rows)
+        return Y0, Y
     off = _i32(off)
     S = len(off) - 1
     d_out, d_in = W.shape
@@ -168,9 +174,12 @@ def forward_private(off, adapters: Sequence[Adapter], Xn: np.ndarray, W: np.ndar
 
 
 def forward_denoise(off, adapters: Sequence[Adapter], Xn: np.ndarray, W: np.ndarray, bias: Optional[np.ndarray],
-                    neff: Sequence[Optional[np.ndarray]], rows=None) -> np.ndarray:
+                    neff: Sequence[Optional[np.ndarray]], rows=None, client_bf16: bool = False) -> np.ndarray:
     """y = (layer(xn) + b) - neff with the noise effect given as the bf16 tensor the client kept
-    (steps (2) and (3) of Sec. 3.8); neff[i]: None or bf16 bits [rows][d_out]; fp64 [nrows, d_out]."""
+    (steps (2) and (3) of Sec. 3.8); neff[i]: None or bf16 bits [rows][d_out]; fp64 [nrows, d_out].
+    client_bf16: as in forward()."""
+    if client_bf16 and any(a.kind == IA3_IN for a in adapters):
+        return forward_denoise(off, _without(adapters, IA3_IN), client_scale(off, adapters, Xn, IA3_IN), W, bias, neff, rows=rows)
     off = _i32(off)
     S = len(off) - 1
     d_out, d_in = W.shape
@@ -190,8 +199,37 @@ def forward_denoise(off, adapters: Sequence[Adapter], Xn: np.ndarray, W: np.ndar
     return Y
 
 
+def client_scale(off, adapters: Sequence[Adapter], V: np.ndarray, kind: int) -> np.ndarray:
+    """bf16 bits of V * l_i on the rows of every segment of `kind` (IA3: V = dY; IA3_IN: V = X), other rows
+    copied: the product an IA3 client forms in 16 bits before the tensor goes to the executor (Sec. 3.2, 4)."""
+    off = _i32(off)
+    S = len(off) - 1
+    width = V.shape[1]
+    Vc = np.ascontiguousarray(V, dtype=np.uint16)
+    out = np.empty_like(Vc)
+    arr = (_Adapter * max(1, len(adapters)))()
+    for i, a in enumerate(adapters):
+        arr[i].kind = int(a.kind)
+        if a.kind == kind:
+            assert a.A.shape == (width,)
+            arr[i].A = _u16(a.A).value
+    rc = lib().orc_client_scale(C.c_int32(width), C.c_int32(S), off.ctypes.data_as(C.c_void_p), arr, C.c_int32(kind),
+                                _u16(Vc), out.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise ValueError("oracle client_scale: bad offsets or kind")
+    return out
+
+
+def _without(adapters: Sequence[Adapter], kind: int):
+    return [Adapter() if a.kind == kind else a for a in adapters]
+
+
 def backward_input(off, adapters: Sequence[Adapter], dY: np.ndarray, W: np.ndarray,
-                   rows=None, base_only: bool = False) -> np.ndarray:
+                   rows=None, base_only: bool = False, client_bf16: bool = False) -> np.ndarray:
+    """dX in fp64 [nrows, d_in].  client_bf16: the IA3 product dY * l_i is the bf16 tensor the paper's
+    client would send (client_scale), not the exact product."""
+    if client_bf16 and not base_only and any(a.kind == IA3 for a in adapters):
+        return backward_input(off, _without(adapters, IA3), client_scale(off, adapters, dY, IA3), W, rows=rows)
     off = _i32(off)
     S = len(off) - 1
     d_out, d_in = W.shape

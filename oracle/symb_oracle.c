@@ -33,7 +33,9 @@
  * Parity pins (tests/test_oracle_*.py): brute-force Python loops on tiny shapes,
  * merged-weight closed forms via a library fp64 matmul, B=0 / l=1 reductions,
  * segment-permutation and batched-vs-alone invariance, exact central finite
- * differences of <dY,Y>, noise linearity, and an exact integer-valued index probe.
+ * differences of <dY,Y>, noise linearity, and an exact integer-valued index probe; the two roundings
+ * the paper's flow fixes (the client's x + n and its IA3 product, orc_noise_add and orc_client_scale)
+ * against exact rational arithmetic rounded by the definition of round-to-nearest-even.
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -183,6 +185,35 @@ int orc_noise_add(int32_t width, int32_t S, const int32_t* off, const uint16_t* 
                 out[(size_t)t * width + k] = x;
             }
     }
+    return 0;
+}
+
+/*
+ * orc_client_scale: the elementwise product an IA3 client forms itself, in 16 bits, before the tensor
+ * crosses to the executor (Sec. 3.2: the adapters run at the client; Sec. 4: 16-bit precision):
+ * out[t][c] = bf16(in[t][c] * l_i[c]) for the rows of every segment of kind `kind` (ORC_IA3: in = dY,
+ * the gradient entering the frozen layer's backward; ORC_IA3_IN: in = x, the layer's input), rows of
+ * other segments copied.  The product of two bf16 values is exact in fp32, so this is one rounding,
+ * nearest-even.  Feeding the result to orc_backward_input_rows / orc_forward_rows with those segments'
+ * adapters set to NONE gives the layer's result as the paper's unfused flow computes it.
+ */
+int orc_client_scale(int32_t width, int32_t S, const int32_t* off, const orc_adapter* ad, int32_t kind,
+                     const uint16_t* in, uint16_t* out) {
+    if (orc_check_offsets(S, off)) return 1;
+    if (kind != ORC_IA3 && kind != ORC_IA3_IN) return 1;
+    for (int32_t i = 0; i < S; ++i)
+        for (int32_t t = off[i]; t < off[i + 1]; ++t)
+            for (int32_t c = 0; c < width; ++c) {
+                uint16_t v = in[(size_t)t * width + c];
+                if (ad[i].kind == kind) {
+                    uint32_t vu = (uint32_t)v << 16, lu = (uint32_t)ad[i].A[c] << 16;
+                    float vf, lf;
+                    memcpy(&vf, &vu, 4);
+                    memcpy(&lf, &lu, 4);
+                    v = to_bf16_rne(vf * lf);
+                }
+                out[(size_t)t * width + c] = v;
+            }
     return 0;
 }
 

@@ -116,3 +116,36 @@ def assert_close(got, ref, what="", out_bf16=False):
                           f"({MAX_ABS_TOL} * RMS" + (f", or half a bf16 ulp beyond {TAIL_RMS:g} RMS: {n_tail} such elements, "
                                                      f"{n_used} of them outside the bare bound)" if out_bf16 else ")"))
     return rf, bare
+
+
+def assert_close_client(got, ref_exact, ref_client, what=""):
+    """The bar for the two outputs that contract a tensor the paper's IA3 client forms in 16 bits before
+    it reaches the executor (Sec. 3.2: adapters run at the client; Sec. 4: 16-bit precision): the input
+    gradient through an IA3 segment (dY * l) and the forward through an IA3_IN segment (x * l).  The fused
+    path forms that same bf16 tensor in its workspace.  Full bar against the oracle evaluated on that bf16
+    tensor (its client_bf16 route); against the exact definition the relative Frobenius bound (that one
+    extra operand rounding moves single elements of multi-million-element tensors by up to 1.2e-2 RMS,
+    which together with the rounding of the bf16 output can pass 2e-2 RMS)."""
+    rf = rel_fro(got, ref_exact)
+    assert rf <= REL_FRO_TOL, f"{what}: relative Frobenius error {rf:.3e} > {REL_FRO_TOL} against the exact definition"
+    return assert_close(got, ref_client, what, out_bf16=True)
+
+
+def check_dx(got, off, oads, dY, W, what="", rows=None, base_only=False):
+    """Input gradient rows `got` (bf16 output) against the oracle; returns the exact reference."""
+    exact = oracle.backward_input(off, oads, dY, W, rows=rows, base_only=base_only)
+    if not base_only and any(a.kind == oracle.IA3 for a in oads):
+        assert_close_client(got, exact, oracle.backward_input(off, oads, dY, W, rows=rows, client_bf16=True), what)
+    else:
+        assert_close(got, exact, what, out_bf16=True)
+    return exact
+
+
+def check_y(got, off, oads, X, W, bias, what="", rows=None):
+    """Forward output rows `got` (bf16) against the oracle; returns the exact (Y0, Y)."""
+    Y0, exact = oracle.forward(off, oads, X, W, bias, rows=rows)
+    if any(a.kind == oracle.IA3_IN for a in oads):
+        assert_close_client(got, exact, oracle.forward(off, oads, X, W, bias, rows=rows, client_bf16=True)[1], what)
+    else:
+        assert_close(got, exact, what, out_bf16=True)
+    return Y0, exact

@@ -11,7 +11,7 @@ import torch
 
 import oracle
 import synth
-from helpers import assert_close
+from helpers import check_dx, check_y
 
 pytestmark = pytest.mark.gpu
 
@@ -96,8 +96,7 @@ def test_queue_formed_batches_give_each_request_its_own_result():
     assert any(n > 1 and 16 < tok for n, tok in sizes) and any(tok <= 16 for _, tok in sizes)
     for r in reqs:
         alone = np.array([0, r["n"]], dtype=np.int32)
-        _, Yr = oracle.forward(alone, [oads[r["client"]]], r["X"], W, bias)
-        assert_close(r["Y"], Yr, f"request {r['rid']} (client {r['client']}, {r['n']} tokens) Y", out_bf16=True)
+        check_y(r["Y"], alone, [oads[r["client"]]], r["X"], W, bias, f"request {r['rid']} (client {r['client']}, {r['n']} tokens) Y")
 
     # backward: fine-tuning requests only, arriving in another order -> other groups than in the forward
     ft = [r for r in reqs if not r["decode"]]
@@ -124,5 +123,4 @@ def test_queue_formed_batches_give_each_request_its_own_result():
     assert sorted(x for g in groups for x in g) == sorted(r["rid"] for r in ft)
     for r in ft:
         alone = np.array([0, r["n"]], dtype=np.int32)
-        dXr = oracle.backward_input(alone, [oads[r["client"]]], r["dY"], W)
-        assert_close(r["dX"], dXr, f"request {r['rid']} dX", out_bf16=True)
+        check_dx(r["dX"], alone, [oads[r["client"]]], r["dY"], W, f"request {r['rid']} dX")

@@ -23,7 +23,7 @@ import torch
 
 import oracle
 import synth
-from helpers import assert_close
+from helpers import assert_close, assert_close_client
 
 pytestmark = pytest.mark.gpu
 
@@ -135,17 +135,20 @@ def run_projection(wl, pr):
     # ---- (4) input gradient taking dH from that gradient call
     brows = synth.sample_rows(boff, ROWS_PER_SEGMENT, tag + "/bwd", block=ROW_BLOCK)
     dXr = oracle.backward_input(boff, boads, dY, W, rows=brows)
+    # with IA3 segments in the backward batch: dY * l as the bf16 tensor the paper's client would send (helpers.py)
+    dXc = oracle.backward_input(boff, boads, dY, W, rows=brows, client_bf16=True) if any(a.kind == oracle.IA3 for a in boads) else None
+    close_dx = lambda got, what: assert_close(got, dXr, what, out_bf16=True) if dXc is None else assert_close_client(got, dXr, dXc, what)
     bidx = torch.from_numpy(brows.astype(np.int64)).cuda()
     run.dX.fill_(float("nan"))
     run.bwd_input(s, reuse_dh=True)
     torch.cuda.synchronize()
-    assert_close(_f64(run.dX.index_select(0, bidx)), dXr, f"{tag} dX (as timed)", out_bf16=True)
+    close_dx(_f64(run.dX.index_select(0, bidx)), f"{tag} dX (as timed)")
 
     # ---- (5) the other order: the input gradient computes dH itself, the gradient call takes it over
     run.dX.fill_(float("nan"))
     run.bwd_input(s)
     torch.cuda.synchronize()
-    assert_close(_f64(run.dX.index_select(0, bidx)), dXr, f"{tag} dX", out_bf16=True)
+    close_dx(_f64(run.dX.index_select(0, bidx)), f"{tag} dX")
     nan_grads()
     run.adapter_grad(s, reuse_dh=True, reuse_hs=True)
     torch.cuda.synchronize()

@@ -15,7 +15,7 @@ import torch
 
 import oracle
 import synth
-from helpers import assert_close, bits_of
+from helpers import assert_close, assert_close_client, check_dx, check_y, bits_of
 
 pytestmark = pytest.mark.gpu
 
@@ -79,9 +79,8 @@ def check_all(p, tag):
     # backward, both flavours
     for base_only in (False, True):
         dX = gh.backward_input(off, p["ads"], p["dY"], p["W"], base_only=base_only)
-        dXr = oracle.backward_input(off, oads, p["dY"], p["W"], base_only=base_only)
         if p["T"]:
-            assert_close(gh.bf16_to_f64(dX), dXr, f"{tag} dX base_only={base_only}", out_bf16=True)
+            check_dx(gh.bf16_to_f64(dX), off, oads, p["dY"], p["W"], f"{tag} dX base_only={base_only}", base_only=base_only)
     # adapter gradients.  The saved base output a client feeds back is a bf16 tensor: both sides
     # get the same one, the oracle's Y0 rounded to bf16 here (never the GPU's own output).
     Y0_saved = synth.f32_to_bf16_bits(Y0r.astype(np.float32))
@@ -162,6 +161,10 @@ def test_cfg1_tiny_full():
     # single segment, single token
     dict(seed=6, d_in=64, d_out=64, lens=[1], kinds=[L], ranks=[8]),
     dict(seed=7, d_in=72, d_out=40, lens=[1], kinds=[I], ranks=[1]),
+    # the only IA3 (IA3 on the input) segment of the batch is empty: nothing to scale, on either side of the layer
+    dict(seed=26, d_in=328, d_out=10976, lens=[33, 256, 16, 257, 0], kinds=[L, L, L, N, I], ranks=[32, 1, 100]),
+    dict(seed=27, d_in=328, d_out=392, lens=[0, 33, 256], kinds=[3, L, N], ranks=[8]),
+    dict(seed=28, d_in=72, d_out=200, lens=[0, 9], kinds=[I, N], ranks=[1]),
     # many decode rows interleaved with long segments
     dict(seed=8, d_in=512, d_out=384, lens=[1, 1, 200, 1, 1, 1, 90, 1, 257, 1, 1], kinds=[L, I, L, L, I, N, I, L, L, I, L], ranks=[4, 64, 16, 8, 32, 128]),
 ])
@@ -487,8 +490,7 @@ def test_input_major_weight_layout(case):
     assert_close(gh.bf16_to_f64(Yb), Y0r, "conv1d Ybase", out_bf16=True)
     for base_only in (False, True):
         dX = gh.backward_input(off, p["ads"], p["dY"], p["W"], base_only=base_only, conv1d=True)
-        dXr = oracle.backward_input(off, oads, p["dY"], p["W"], base_only=base_only)
-        assert_close(gh.bf16_to_f64(dX), dXr, f"conv1d dX base_only={base_only}", out_bf16=True)
+        check_dx(gh.bf16_to_f64(dX), off, oads, p["dY"], p["W"], f"conv1d dX base_only={base_only}", base_only=base_only)
 
 
 @pytest.mark.parametrize("case", [
@@ -504,8 +506,7 @@ def test_ia3_input_scaling(case):
     p = make_problem(c.pop("seed"), c.pop("d_in"), c.pop("d_out"), c.pop("lens"), c.pop("kinds"), c.pop("ranks"))
     oads, off, d_in, d_out, T = oracle_ads(p["ads"]), p["off"], p["d_in"], p["d_out"], p["T"]
     Y, _ = gh.forward(off, p["ads"], p["X"], p["W"], p["bias"], want_base=False, conv1d=conv1d)
-    _, Yr = oracle.forward(off, oads, p["X"], p["W"], p["bias"])
-    assert_close(gh.bf16_to_f64(Y), Yr, "IA3_IN Y", out_bf16=True)
+    check_y(gh.bf16_to_f64(Y), off, oads, p["X"], p["W"], p["bias"], "IA3_IN Y")
     # input gradient with the pre-scale output
     dev = gh.upload_adapters(p["ads"], d_in, d_out, grads=True)
     b = sb.Batch(d_in, d_out, off, dev.descs, sb.SYMB_WEIGHT_CONV1D if conv1d else sb.SYMB_WEIGHT_LINEAR)
@@ -515,7 +516,7 @@ def test_ia3_input_scaling(case):
     G = torch.full((T, d_in), float("nan"), device="cuda", dtype=torch.bfloat16)
     sb.symb_base_linear_bwd_input_ex(h, b, gd, Wd, dX, G, sb.SYMB_BWD_FULL, gh.workspace(b, sb.SYMB_OP_BWD_INPUT))
     torch.cuda.synchronize()
-    assert_close(gh.bf16_to_f64(dX), oracle.backward_input(off, oads, p["dY"], p["W"]), "IA3_IN dX", out_bf16=True)
+    check_dx(gh.bf16_to_f64(dX), off, oads, p["dY"], p["W"], "IA3_IN dX")
     Gr = oracle.backward_input(off, oads, p["dY"], p["W"], base_only=True)
     ia3_rows = np.concatenate([np.arange(off[i], off[i + 1]) for i, a in enumerate(p["ads"]) if a.kind == I] or [np.zeros(0, int)]).astype(int)
     keep = np.setdiff1d(np.arange(T), ia3_rows)          # rows of output-scaling segments hold the scaled product there
@@ -591,16 +592,14 @@ def test_per_segment_buffers(case):
     _, Yv = carve(d_out)
     sb.symb_base_linear_fwd_seg(h, b, Xv, Wd, bd, Yv, gh.workspace(b, sb.SYMB_OP_FWD))
     torch.cuda.synchronize()
-    _, Yr = oracle.forward(off, oads, p["X"], p["W"], p["bias"])
-    assert_close(gather(Yv, d_out), Yr, "per-segment Y", out_bf16=True)
+    check_y(gather(Yv, d_out), off, oads, p["X"], p["W"], p["bias"], "per-segment Y")
     for base_only in (False, True):
         _, Gv = carve(d_out, p["dY"])
         _, DXv = carve(d_in)
         sb.symb_base_linear_bwd_input_seg(h, b, Gv, Wd, DXv, sb.SYMB_BWD_BASE_ONLY if base_only else sb.SYMB_BWD_FULL,
                                           gh.workspace(b, sb.SYMB_OP_BWD_INPUT))
         torch.cuda.synchronize()
-        assert_close(gather(DXv, d_in), oracle.backward_input(off, oads, p["dY"], p["W"], base_only=base_only),
-                     f"per-segment dX base_only={base_only}", out_bf16=True)
+        check_dx(gather(DXv, d_in), off, oads, p["dY"], p["W"], f"per-segment dX base_only={base_only}", base_only=base_only)
     # adapter gradients from the same kind of buffers (the IA3 gradient takes the oracle's Y0 rounded to bf16)
     grads = gh.upload_adapters(p["ads"], d_in, d_out, grads=True)
     bg = sb.Batch(d_in, d_out, off, grads.descs)
@@ -652,8 +651,7 @@ def test_large_tile_kernel_with_one_to_five_k_stages(d_in):
     # the same K extents in the input gradient: d_out takes the role of K there
     q = make_problem(170 + d_in, 6208, d_in, [700, 5, 795], [L, N, I], [16])
     dX = gh.backward_input(q["off"], q["ads"], q["dY"], q["W"])
-    assert_close(gh.bf16_to_f64(dX), oracle.backward_input(q["off"], oracle_ads(q["ads"]), q["dY"], q["W"]),
-                 f"dX d_out={d_in}", out_bf16=True)
+    check_dx(gh.bf16_to_f64(dX), q["off"], oracle_ads(q["ads"]), q["dY"], q["W"], f"dX d_out={d_in}")
 
 
 @pytest.mark.parametrize("lens", [[1], [16], [9, 0, 8], [1, 1, 20, 1, 1, 24], [30, 1, 40, 29], [1] * 48, [50, 78]])
@@ -690,6 +688,7 @@ def test_k_split_rests_on_a_measured_xcd_rule():
         oads = oracle_ads(p["ads"])
         _, Yr = oracle.forward(p["off"], oads, p["X"], p["W"], p["bias"])
         dXr = oracle.backward_input(p["off"], oads, p["dY"], p["W"])
+        dXc = oracle.backward_input(p["off"], oads, p["dY"], p["W"], client_bf16=True)   # (an IA3 segment is in the batch)
         got = {}
         try:
             for split in (1, 0):
@@ -697,7 +696,7 @@ def test_k_split_rests_on_a_measured_xcd_rule():
                 Y, _ = gh.forward(p["off"], p["ads"], p["X"], p["W"], p["bias"], want_base=False)
                 dX = gh.backward_input(p["off"], p["ads"], p["dY"], p["W"])
                 assert_close(gh.bf16_to_f64(Y), Yr, f"Y split={split}", out_bf16=True)
-                assert_close(gh.bf16_to_f64(dX), dXr, f"dX split={split}", out_bf16=True)
+                assert_close_client(gh.bf16_to_f64(dX), dXr, dXc, f"dX split={split}")
                 got[split] = (gh.bf16_bits(Y), gh.bf16_bits(dX))
         finally:
             sb.symb_debug_set_option(h, sb.SYMB_OPT_K_SPLIT, 1)
@@ -776,7 +775,7 @@ def test_one_buffer_per_client_for_input_and_output(case):
     xout = [view(i, d_in) for i in range(S)]
     sb.symb_base_linear_bwd_input_seg(h, b, gin, Wd, xout, sb.SYMB_BWD_FULL, gh.workspace(b, sb.SYMB_OP_BWD_INPUT_INPLACE))
     torch.cuda.synchronize()
-    assert_close(gather(d_in), oracle.backward_input(off, oads, p["dY"], p["W"]), "in-place dX", out_bf16=True)
+    check_dx(gather(d_in), off, oads, p["dY"], p["W"], "in-place dX")
 
 
 @pytest.mark.parametrize("lens", [[1], [16], [9, 0, 7], [1, 1, 5, 1, 1, 4], [3, 1, 2, 1, 1, 2, 1, 1]])
@@ -798,17 +797,18 @@ def test_a_handful_of_rows_in_every_call_form(lens, dims):
     oads = oracle_ads(p["ads"])
     h = gh.handle()
     Y0r, Yr = oracle.forward(off, oads, p["X"], p["W"], p["bias"])
+    _, Yc = oracle.forward(off, oads, p["X"], p["W"], p["bias"], client_bf16=True)   # IA3 on the input: x * l as the client's bf16 tensor
     kind_of_row = np.array([p["ads"][int(np.searchsorted(off, t, side="right") - 1)].kind for t in range(T)])
     plain_in = np.flatnonzero(kind_of_row != 3)       # rows of input-scaling segments hold the product of the scaled input in Ybase
     for conv1d in (False, True):
         Y, Yb = gh.forward(off, p["ads"], p["X"], p["W"], p["bias"], want_base=True, conv1d=conv1d)
-        assert_close(gh.bf16_to_f64(Y), Yr, f"small Y conv1d={conv1d}", out_bf16=True)
+        assert_close_client(gh.bf16_to_f64(Y), Yr, Yc, f"small Y conv1d={conv1d}")
         assert_close(gh.bf16_to_f64(Yb)[plain_in], Y0r[plain_in], f"small Ybase conv1d={conv1d}", out_bf16=True)
-        assert_close(gh.bf16_to_f64(Yb)[kind_of_row == 3], Yr[kind_of_row == 3], f"small Ybase of IA3_IN rows conv1d={conv1d}", out_bf16=True)
+        if (kind_of_row == 3).any():
+            assert_close_client(gh.bf16_to_f64(Yb)[kind_of_row == 3], Yr[kind_of_row == 3], Yc[kind_of_row == 3], f"small Ybase of IA3_IN rows conv1d={conv1d}")
         for base_only in (False, True):
-            dXr = oracle.backward_input(off, oads, p["dY"], p["W"], base_only=base_only)
             dX = gh.backward_input(off, p["ads"], p["dY"], p["W"], base_only=base_only, conv1d=conv1d)
-            assert_close(gh.bf16_to_f64(dX), dXr, f"small dX conv1d={conv1d} base_only={base_only}", out_bf16=True)
+            check_dx(gh.bf16_to_f64(dX), off, oads, p["dY"], p["W"], f"small dX conv1d={conv1d} base_only={base_only}", base_only=base_only)
     # the pre-adapter input gradient next to the full one
     dev = gh.upload_adapters(p["ads"], d_in, d_out, grads=False)
     b = sb.Batch(d_in, d_out, off, dev.descs)
@@ -817,7 +817,7 @@ def test_a_handful_of_rows_in_every_call_form(lens, dims):
     G = torch.full((T, d_in), float("nan"), device="cuda", dtype=torch.bfloat16)
     sb.symb_base_linear_bwd_input_ex(h, b, gd, Wd, dX, G, sb.SYMB_BWD_FULL, gh.workspace(b, sb.SYMB_OP_BWD_INPUT))
     torch.cuda.synchronize()
-    assert_close(gh.bf16_to_f64(dX), oracle.backward_input(off, oads, p["dY"], p["W"]), "small dX (with dXbase)", out_bf16=True)
+    check_dx(gh.bf16_to_f64(dX), off, oads, p["dY"], p["W"], "small dX (with dXbase)")
     Gr = oracle.backward_input(off, oads, p["dY"], p["W"], base_only=True)
     keep = np.flatnonzero(kind_of_row != I)
     if len(keep):
@@ -830,7 +830,8 @@ def test_a_handful_of_rows_in_every_call_form(lens, dims):
     Yd = torch.full((T, d_out), float("nan"), device="cuda", dtype=torch.bfloat16)
     sb.symb_base_linear_fwd_denoise(h, b, Xd, Wd, bd, [gh.to_dev(n) for n in neff], Yd, gh.workspace(b, sb.SYMB_OP_FWD))
     torch.cuda.synchronize()
-    assert_close(gh.bf16_to_f64(Yd), oracle.forward_denoise(off, oads, p["X"], p["W"], p["bias"], neff), "small denoised Y", out_bf16=True)
+    assert_close_client(gh.bf16_to_f64(Yd), oracle.forward_denoise(off, oads, p["X"], p["W"], p["bias"], neff),
+                        oracle.forward_denoise(off, oads, p["X"], p["W"], p["bias"], neff, client_bf16=True), "small denoised Y")
     # per-client buffers (no IA3 on the input in that form): separate output buffers, then one buffer for both
     q = make_problem(500 + len(lens) + d_in, d_in, d_out, lens, [L, I, N, L, I, L, N, L], [1, 128, 24, 8, 100] if not big else [16, 8, 64])
     qads = oracle_ads(q["ads"])
@@ -858,7 +859,6 @@ def test_a_handful_of_rows_in_every_call_form(lens, dims):
         return out
 
     _, qYr = oracle.forward(off, qads, q["X"], q["W"], q["bias"])
-    qdXr = oracle.backward_input(off, qads, q["dY"], q["W"])
     for i in range(S):
         if views[i] is not None:
             view(i, d_in).copy_(gh.to_dev(np.ascontiguousarray(q["X"][off[i]:off[i + 1]])))
@@ -881,7 +881,7 @@ def test_a_handful_of_rows_in_every_call_form(lens, dims):
     sb.symb_base_linear_bwd_input_seg(h, qb, [view(i, d_out) for i in range(S)], qW, [view(i, d_in) for i in range(S)],
                                       sb.SYMB_BWD_FULL, gh.workspace(qb, sb.SYMB_OP_BWD_INPUT_INPLACE))
     torch.cuda.synchronize()
-    assert_close(gather(d_in), qdXr, "small in-place dX", out_bf16=True)
+    check_dx(gather(d_in), off, qads, q["dY"], q["W"], "small in-place dX")
 
 
 @pytest.mark.parametrize("case", [
@@ -917,7 +917,7 @@ def test_gradient_call_first_then_the_input_gradient_takes_its_dh(case):
     sb.symb_adapter_grad(h, b, Xd, dYd, Yb, sb.SYMB_GRAD_OVERWRITE, ws)
     sb.symb_base_linear_bwd_input(h, b, dYd, Wd, dX, sb.SYMB_BWD_FULL | sb.SYMB_BWD_REUSE_DH, ws)
     torch.cuda.synchronize()
-    assert_close(gh.bf16_to_f64(dX), oracle.backward_input(off, oads, p["dY"], p["W"]), "dX from the gradient call's dH", out_bf16=True)
+    check_dx(gh.bf16_to_f64(dX), off, oads, p["dY"], p["W"], "dX from the gradient call's dH")
     for i, a in enumerate(p["ads"]):
         if a.kind == L and off[i + 1] > off[i]:
             dAr, dBr = oracle.lora_grad(off, oads, p["X"], p["dY"], i)

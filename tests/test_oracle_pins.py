@@ -452,6 +452,84 @@ def test_denoise_with_a_stored_noise_effect():
 # ---------------------------------------------------------------------------
 # P9: adapter-index probe with exactly representable values
 # ---------------------------------------------------------------------------
+def test_client_scaled_tensor_is_the_exact_product_rounded_once():
+    """The product an IA3 client forms in 16 bits before the tensor goes to the executor (Sec. 3.2, Sec. 4):
+    each element against the exact rational product rounded by the definition of round-to-nearest-even;
+    rows of other segments untouched; both kinds."""
+    rng = np.random.default_rng(44)
+    width = 9
+    off = np.array([0, 3, 3, 8, 10], dtype=np.int32)
+    V = synth.f32_to_bf16_bits(rng.standard_normal((10, width)).astype(np.float32))
+    lvec = lambda: synth.f32_to_bf16_bits((1.0 + 0.3 * rng.standard_normal(width)).astype(np.float32))
+    for kind, other in ((oracle.IA3, oracle.IA3_IN), (oracle.IA3_IN, oracle.IA3)):
+        ads = [oracle.Adapter(kind, 0, 0.0, lvec()), oracle.Adapter(kind, 0, 0.0, lvec()),
+               oracle.Adapter(other, 0, 0.0, lvec()), oracle.Adapter(kind, 0, 0.0, lvec())]
+        out = oracle.client_scale(off, ads, V, kind)
+        vf, of = f64(V), f64(out)
+        n_rounded = 0
+        for t in range(10):
+            seg = int(np.searchsorted(off, t, side="right") - 1)
+            for c in range(width):
+                if ads[seg].kind != kind:
+                    assert out[t, c] == V[t, c]
+                    continue
+                exact = Fraction(float(vf[t, c])) * Fraction(float(f64(ads[seg].A)[c]))
+                want = _round_to_bf16_by_definition(exact)
+                assert Fraction(float(of[t, c])) == want, (kind, t, c)
+                n_rounded += want != exact
+        assert n_rounded > 20          # the case does exercise the rounding
+    with pytest.raises(ValueError):
+        oracle.client_scale(off, ads, V, oracle.LORA)
+
+
+def test_client_route_is_the_plain_layer_on_the_client_scaled_tensor():
+    """backward_input / forward with client_bf16: (a) with scale vectors that are powers of two no product
+    needs rounding, and the route gives the exact definition bit for bit; (b) in general it is the exact
+    definition evaluated on the rounded product, so it differs from the exact result by at most the
+    rounding bound 2^-8 sum |term| per element (half a spacing of 8-bit significands is at most 2^-8 of the value), and does differ; (c) base-only calls and batches without
+    such segments are untouched."""
+    p = tiny_problem(seed=8, d_in=6, d_out=5, lens=(3, 0, 2, 2, 4))       # kinds: LoRA, LoRA, IA3, NONE, IA3_IN
+    rng = np.random.default_rng(8)
+    off, ads = p["off"], list(p["ads"])
+    X = synth.f32_to_bf16_bits(rng.standard_normal((p["T"], 6)).astype(np.float32))
+    dY = synth.f32_to_bf16_bits(rng.standard_normal((p["T"], 5)).astype(np.float32))
+    W = synth.f32_to_bf16_bits(rng.standard_normal((5, 6)).astype(np.float32))
+    b = synth.f32_to_bf16_bits(rng.standard_normal(5).astype(np.float32))
+    pow2 = lambda n: bits_of(np.float32(2.0) ** rng.integers(-3, 4, n).astype(np.float32) * rng.choice([-1.0, 1.0], n).astype(np.float32))
+    ads_p2 = list(ads)
+    ads_p2[2] = oracle.Adapter(oracle.IA3, 0, 0.0, pow2(5))
+    ads_p2[4] = oracle.Adapter(oracle.IA3_IN, 0, 0.0, pow2(6))
+    np.testing.assert_array_equal(oracle.backward_input(off, ads_p2, dY, W, client_bf16=True), oracle.backward_input(off, ads_p2, dY, W))
+    for got, want in zip(oracle.forward(off, ads_p2, X, W, b, client_bf16=True), oracle.forward(off, ads_p2, X, W, b)):
+        np.testing.assert_array_equal(got, want)
+    # general vectors: within the rounding bound of the exact result, and not equal to it
+    ads_g = list(ads)
+    ads_g[2] = oracle.Adapter(oracle.IA3, 0, 0.0, synth.f32_to_bf16_bits((1 + 0.3 * rng.standard_normal(5)).astype(np.float32)))
+    ads_g[4] = oracle.Adapter(oracle.IA3_IN, 0, 0.0, synth.f32_to_bf16_bits((1 + 0.3 * rng.standard_normal(6)).astype(np.float32)))
+    dXe, dXc = oracle.backward_input(off, ads_g, dY, W), oracle.backward_input(off, ads_g, dY, W, client_bf16=True)
+    rows3 = slice(off[2], off[3])
+    bound = 2.0 ** -8 * (np.abs(f64(dY)[rows3] * f64(ads_g[2].A)) @ np.abs(f64(W)))
+    assert (np.abs(dXc - dXe)[rows3] <= bound + 1e-15).all() and np.abs(dXc - dXe)[rows3].max() > 0
+    keep = np.ones(p["T"], bool); keep[rows3] = False
+    np.testing.assert_array_equal(dXc[keep], dXe[keep])
+    (Y0e, Ye), (Y0c, Yc) = oracle.forward(off, ads_g, X, W, b), oracle.forward(off, ads_g, X, W, b, client_bf16=True)
+    rows5 = slice(off[4], off[5])
+    bound = 2.0 ** -8 * (np.abs(f64(X)[rows5] * f64(ads_g[4].A)) @ np.abs(f64(W)).T)
+    assert (np.abs(Yc - Ye)[rows5] <= bound + 1e-15).all() and np.abs(Yc - Ye)[rows5].max() > 0
+    keep = np.ones(p["T"], bool); keep[rows5] = False
+    np.testing.assert_array_equal(Yc[keep], Ye[keep])
+    np.testing.assert_array_equal(Y0c, Y0e)
+    # row subsets go through the same route
+    rows = np.array([off[3] - 1, 0, off[5] - 1], dtype=np.int32)
+    np.testing.assert_array_equal(oracle.backward_input(off, ads_g, dY, W, rows=rows, client_bf16=True), dXc[rows])
+    np.testing.assert_array_equal(oracle.forward(off, ads_g, X, W, b, rows=rows, client_bf16=True)[1], Yc[rows])
+    # untouched: base-only, and a batch with no such segment
+    np.testing.assert_array_equal(oracle.backward_input(off, ads_g, dY, W, base_only=True, client_bf16=True),
+                                  oracle.backward_input(off, ads_g, dY, W, base_only=True))
+    plain = [a if a.kind == oracle.LORA else oracle.Adapter() for a in ads_g]
+    np.testing.assert_array_equal(oracle.backward_input(off, plain, dY, W, client_bf16=True), oracle.backward_input(off, plain, dY, W))
+
+
 def test_index_probe_recovers_row_to_adapter_map():
     lens = [3, 0, 1, 5, 1, 1, 0, 7, 2]
     S = len(lens)
