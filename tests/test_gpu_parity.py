@@ -628,13 +628,24 @@ def test_per_segment_buffers(case):
             assert_close(grads.descs[i].dA.cpu().numpy(), dlr, f"per-segment dl (input scaling) [{i}]")
     if any(a.kind == 3 for a in p["ads"]):
         return                                      # (no window rule for the forward's inputs then)
-    # buffers more than 4 GiB apart are refused before any launch (fake addresses: nothing is dereferenced)
-    far = [int(Xv[i].data_ptr()) if Xv[i] is not None else 0 for i in range(S)]
-    first = next(i for i in range(S) if Xv[i] is not None)
-    far[first] += 5 << 30
-    with pytest.raises(sb.SymbError) as e:
-        sb.symb_base_linear_fwd_seg(h, b, far, Wd, bd, Yv, gh.workspace(b, sb.SYMB_OP_FWD))
-    assert e.value.status == sb.SYMB_ERR_UNSUPPORTED
+    # input buffers more than 4 GiB apart are refused before any launch.  Every address handed over is real
+    # memory: one segment's rows are copied to the far end of a 4.6 GB allocation, the others to its start.
+    nonempty = [i for i in range(S) if Xv[i] is not None]
+    if len(nonempty) >= 2:
+        span = torch.empty(((1 << 32) + (64 << 20) + 2 * T * d_in) // 2, device="cuda", dtype=torch.bfloat16)
+        far, cur = list(Xv), 0
+        for i in nonempty[1:]:
+            far[i] = span[cur:cur + Xv[i].numel()].view_as(Xv[i])
+            far[i].copy_(Xv[i])
+            cur += Xv[i].numel() + 8
+        first = nonempty[0]
+        far[first] = span[span.numel() - Xv[first].numel():].view_as(Xv[first])
+        far[first].copy_(Xv[first])
+        assert far[first].data_ptr() - far[nonempty[1]].data_ptr() > (1 << 32)
+        with pytest.raises(sb.SymbError) as e:
+            sb.symb_base_linear_fwd_seg(h, b, far, Wd, bd, Yv, gh.workspace(b, sb.SYMB_OP_FWD))
+        assert e.value.status == sb.SYMB_ERR_UNSUPPORTED
+        del span, far
 
 
 @pytest.mark.parametrize("d_in", [40, 64, 72, 128, 192, 200, 320])
@@ -764,7 +775,8 @@ def test_one_buffer_per_client_for_input_and_output(case):
             sb.symb_base_linear_fwd_seg(h, b, xin, Wd, bd, yout, gh.workspace(b, sb.SYMB_OP_FWD))
         assert e.value.status == sb.SYMB_ERR_WORKSPACE_TOO_SMALL
         torch.cuda.synchronize()
-        assert np.array_equal(gh.bf16_bits(view(0, d_in)), p["X"][off[0]:off[1]]), "a refused call must leave the buffers alone"
+        k = next(i for i in range(S) if off[i + 1] > off[i])
+        assert np.array_equal(gh.bf16_bits(view(k, d_in)), p["X"][off[k]:off[k + 1]]), "a refused call must leave the buffers alone"
     sb.symb_base_linear_fwd_seg(h, b, xin, Wd, bd, yout, gh.workspace(b, sb.SYMB_OP_FWD_INPLACE))
     torch.cuda.synchronize()
     _, Yr = oracle.forward(off, oads, p["X"], p["W"], p["bias"])
