@@ -995,3 +995,51 @@ def test_more_segments_than_the_descriptor_slot_holds_are_refused():
     assert torch.isnan(Y.float()).all(), "a refused call must leave its output untouched"
     p = make_problem(7, 64, 72, [5, 3], [L, N], [8])
     check_all(p, "after a refused call")
+
+
+def test_descriptor_ring_wraps_under_a_changing_mix_of_batches():
+    """Batches differ from call to call (Sec. 3.7: whoever is queued when a layer runs); the 32-slot
+    descriptor ring serves more distinct batches than it has slots.  48 batches (every tile split over K
+    ranges: their arrival counters live with the descriptors), 400 calls in random order: each call gives
+    the bits of that batch's first call, whether its descriptors were still in place, had been evicted
+    and were sent again, or were never seen; a sample of the batches is held to the oracle."""
+    h = sb.symb_create(0)
+    try:
+        rng = np.random.default_rng(11)
+        d_in, d_out = 1032, 264
+        probs = []
+        for k in range(48):
+            S = int(rng.integers(1, 5))
+            lens = [int(x) for x in rng.choice([1, 3, 17, 40, 64], size=S)]
+            kinds = [int(x) for x in rng.choice([L, L, I, N], size=S)]
+            p = make_problem(600 + k, d_in, d_out, lens, kinds, [int(x) for x in rng.choice([4, 8, 16, 40], size=S)])
+            dev = gh.upload_adapters(p["ads"], d_in, d_out, grads=False)
+            p["dev"], p["batch"] = dev, sb.Batch(d_in, d_out, p["off"], dev.descs)
+            p["Xd"], p["Wd"], p["bd"] = gh.to_dev(p["X"]), gh.to_dev(p["W"]), gh.to_dev(p["bias"])
+            p["Y"] = torch.empty((p["T"], d_out), device="cuda", dtype=torch.bfloat16)
+            p["ws"] = gh.workspace(p["batch"], sb.SYMB_OP_FWD)
+            p["first"] = None
+            probs.append(p)
+        order = [int(x) for x in rng.integers(0, len(probs), 400)]
+        order[:8] = [0, 1, 0, 1, 2, 0, 1, 2]                   # immediate repeats: descriptors in place
+        for n, k in enumerate(order):
+            p = probs[k]
+            p["Y"].fill_(float("nan"))
+            sb.symb_base_linear_fwd(h, p["batch"], p["Xd"], p["Wd"], p["bd"], p["Y"], None, p["ws"], gh.stream_ptr())
+            if n % 7 == 0:
+                torch.cuda.synchronize()                       # some calls overlap the next one's host work, some do not
+            bits = p["Y"].view(torch.int16).clone()
+            if p["first"] is None:
+                p["first"] = bits
+            else:
+                assert torch.equal(bits, p["first"]), f"call {n} (batch {k}) differs from that batch's first call"
+        torch.cuda.synchronize()
+        sent, in_place = sb.symb_debug_descriptor_stats(h)
+        assert sent + in_place == len(order) and in_place > 0 and sent > len(probs), (sent, in_place)
+        for k in (0, 5, 23, 47):
+            p = probs[k]
+            _, Yr = oracle.forward(p["off"], oracle_ads(p["ads"]), p["X"], p["W"], p["bias"])
+            assert_close(gh.bf16_to_f64(p["first"].view(torch.bfloat16)), Yr, f"ring batch {k} Y", out_bf16=True)
+    finally:
+        torch.cuda.synchronize()
+        sb.symb_destroy(h)
