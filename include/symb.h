@@ -43,7 +43,9 @@
  *
  * Ordering.  All GPU work is enqueued on the given stream (a hipStream_t passed as
  * void*; NULL = the default stream); calls return without synchronising.  Calls on
- * one handle from several host threads must be serialised by the caller.
+ * different streams may be in flight together as long as their output buffers and
+ * workspaces are distinct.  Calls on one handle from several host threads must be
+ * serialised by the caller.
  *
  * Errors.  Every entry point returns a symb_status; nothing throws or aborts.  All
  * argument checks happen before the first launch: a failing call enqueues nothing,

@@ -1043,3 +1043,61 @@ def test_descriptor_ring_wraps_under_a_changing_mix_of_batches():
     finally:
         torch.cuda.synchronize()
         sb.symb_destroy(h)
+
+
+def test_two_streams_share_one_handle():
+    """Calls of one host thread on two streams (both at the default priority) through one handle: each
+    stream has its own buffers and workspace, the descriptor ring is shared (a slot is found in place only
+    by the stream that filled it, and a slot another stream still reads is waited for before it is
+    overwritten).  Forward and input gradient of three batches, interleaved over the streams for 40 rounds
+    with more distinct descriptor blobs than half the ring: every result has the bits of the same call made
+    alone on the default stream."""
+    h = sb.symb_create(0)
+    try:
+        d_in, d_out = 1032, 520
+        probs = []
+        for k, lens in enumerate([[700, 5, 60], [33, 1, 200, 90], [130]]):
+            p = make_problem(700 + k, d_in, d_out, lens, [L, I, N, L], [16, 8, 40])
+            dev = gh.upload_adapters(p["ads"], d_in, d_out, grads=False)
+            p["dev"], p["batch"] = dev, sb.Batch(d_in, d_out, p["off"], dev.descs)
+            p["Xd"], p["Wd"], p["bd"], p["gd"] = gh.to_dev(p["X"]), gh.to_dev(p["W"]), gh.to_dev(p["bias"]), gh.to_dev(p["dY"])
+            nws = max(sb.symb_workspace_bytes(p["batch"], op) for op in (sb.SYMB_OP_FWD, sb.SYMB_OP_BWD_INPUT))
+            p["buf"] = {}
+            for tag in ("alone", "s1", "s2"):
+                p["buf"][tag] = (torch.full((p["T"], d_out), float("nan"), device="cuda", dtype=torch.bfloat16),
+                                 torch.full((p["T"], d_in), float("nan"), device="cuda", dtype=torch.bfloat16),
+                                 torch.empty(nws, device="cuda", dtype=torch.uint8))
+            probs.append(p)
+
+        def call(p, tag, stream_ptr):
+            Y, dX, ws = p["buf"][tag]
+            sb.symb_base_linear_fwd(h, p["batch"], p["Xd"], p["Wd"], p["bd"], Y, None, ws, stream_ptr)
+            sb.symb_base_linear_bwd_input(h, p["batch"], p["gd"], p["Wd"], dX, sb.SYMB_BWD_FULL, ws, stream_ptr)
+
+        for p in probs:
+            call(p, "alone", gh.stream_ptr())
+        torch.cuda.synchronize()
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        rng = np.random.default_rng(3)
+        for rnd in range(40):
+            a, b = (int(x) for x in rng.integers(0, 3, 2))
+            call(probs[a], "s1", s1.cuda_stream)
+            call(probs[b], "s2", s2.cuda_stream)
+            if rnd % 5 == 4:
+                torch.cuda.synchronize()
+                for p in probs:
+                    for tag in ("s1", "s2"):
+                        Y, dX, _ = p["buf"][tag]
+                        if not torch.isnan(Y[0, 0].float()):
+                            assert torch.equal(Y.view(torch.int16), p["buf"]["alone"][0].view(torch.int16)), (rnd, tag)
+                            assert torch.equal(dX.view(torch.int16), p["buf"]["alone"][1].view(torch.int16)), (rnd, tag)
+                            Y.fill_(float("nan")); dX.fill_(float("nan"))
+                torch.cuda.synchronize()
+        p = probs[0]
+        oads = oracle_ads(p["ads"])
+        _, Yr = oracle.forward(p["off"], oads, p["X"], p["W"], p["bias"])
+        assert_close(gh.bf16_to_f64(p["buf"]["alone"][0]), Yr, "two streams: Y", out_bf16=True)
+        check_dx(gh.bf16_to_f64(p["buf"]["alone"][1]), p["off"], oads, p["dY"], p["W"], "two streams: dX")
+    finally:
+        torch.cuda.synchronize()
+        sb.symb_destroy(h)
