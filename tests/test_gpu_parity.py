@@ -466,11 +466,12 @@ def test_privacy_flow_noise_add_and_denoised_forward(shape):
     assert rel_fro(gh.bf16_to_f64(Y), Yplain) < 1e-2
     assert rel_fro(gh.bf16_to_f64(Y), oracle.forward_private(off, oads, Xn_ref, p["W"], p["bias"], noise)) < 1e-2
     # a noise tensor with the wrong number of rows is refused before anything is launched
-    bad = list(nd)
-    bad[0] = nd[0][:2]
-    with pytest.raises(sb.SymbError) as e:
-        sb.symb_noise_add(h, b, Xd, bad, Xn)
-    assert e.value.status == sb.SYMB_ERR_INVALID_ARG
+    if lens[0] >= 3:                     # (2 rows are neither one broadcast row nor one per token then)
+        bad = list(nd)
+        bad[0] = nd[0][:2]
+        with pytest.raises(sb.SymbError) as e:
+            sb.symb_noise_add(h, b, Xd, bad, Xn)
+        assert e.value.status == sb.SYMB_ERR_INVALID_ARG
 
 
 @pytest.mark.parametrize("case", [
